@@ -1,0 +1,175 @@
+"""Seeded synthetic inputs for the LBA matrix product (shapes and value distributions only).
+
+This module holds NO arithmetic of the method itself (no quantizer Q, no FMAq, no accumulation):
+it only draws random tensors, scales them per tensor, and casts them to FP8 E4M3 codes.  It is the
+one module that both the test oracle's callers and the HIP path's callers use, so that the two
+sides see the same bytes.
+
+Random numbers: a counter-based generator (the published splitmix64 finaliser applied to
+seed/stream/index) followed by the Box-Muller transform, written with torch integer/float64 ops so
+that it runs on the CPU or on the GPU.  Element i of stream s under seed z is a pure function of
+(z, s, i): tensors can be generated in chunks and in any order.
+
+Workload stand-ins.  The paper fine-tunes torchvision ResNets on ImageNet and BERT models on SQuAD
+(Sec. 3.1-3.2, App. C); neither the datasets nor the weights exist here, so only layer SHAPES and
+plausible value distributions are kept: ReLU(N(0,1)) activations with Kaiming-normal weights for
+convolutions (as im2col GEMMs), N(0,1) activations with N(0, 0.02^2) weights for BERT linears.
+"""
+import math
+
+import torch
+
+_MASK64 = (1 << 64) - 1
+_GOLDEN = 0x9E3779B97F4A7C15
+_MUL1 = 0xBF58476D1CE4E5B9
+_MUL2 = 0x94D049BB133111EB
+
+
+def _s64(x):
+    """Python int (mod 2^64) -> the same bits as a signed 64-bit value."""
+    x &= _MASK64
+    return x - (1 << 64) if x >= (1 << 63) else x
+
+
+def _lsr(x, s):
+    """Logical right shift of an int64 tensor."""
+    return (x >> s) & ((1 << (64 - s)) - 1)
+
+
+def _mix(z):
+    z = (z ^ _lsr(z, 30)) * _s64(_MUL1)
+    z = (z ^ _lsr(z, 27)) * _s64(_MUL2)
+    return z ^ _lsr(z, 31)
+
+
+def _mix_py(z):
+    z &= _MASK64
+    z = ((z ^ (z >> 30)) * _MUL1) & _MASK64
+    z = ((z ^ (z >> 27)) * _MUL2) & _MASK64
+    return z ^ (z >> 31)
+
+
+def _stream_base(seed, stream):
+    return _mix_py(_mix_py(seed * 2 + 1) ^ ((stream * 2 + 1) * _GOLDEN))
+
+
+def uniform_bits(seed, stream, start, count, device="cpu"):
+    """53-bit uniform integers (as int64) for counters start .. start+count-1."""
+    base = _stream_base(seed, stream)
+    i = torch.arange(start, start + count, dtype=torch.int64, device=device)
+    z = i * _s64(_GOLDEN) + _s64(base)
+    return _lsr(_mix(z), 11)
+
+
+def normal(seed, stream, n, device="cpu", chunk=1 << 24):
+    """n independent N(0,1) draws (float64), Box-Muller on two counters per draw."""
+    out = torch.empty(n, dtype=torch.float64, device=device)
+    for lo in range(0, n, chunk):
+        c = min(chunk, n - lo)
+        b = uniform_bits(seed, stream, 2 * lo, 2 * c, device)
+        u1 = (b[0::2] + 1).to(torch.float64) * (2.0 ** -53)     # (0, 1]
+        u2 = b[1::2].to(torch.float64) * (2.0 ** -53)           # [0, 1)
+        out[lo:lo + c] = torch.sqrt(-2.0 * torch.log(u1)) * torch.cos((2.0 * math.pi) * u2)
+    return out
+
+
+def to_e4m3(x):
+    """float64 tensor -> uint8 OCP E4M3 codes: round-to-nearest-even, saturating at +-448."""
+    ax = x.abs().clamp(max=448.0)
+    _, ex = torch.frexp(ax)                       # ax = f * 2^ex, f in [0.5, 1)
+    e = (ex - 1).clamp(min=-6)                    # binade; below 2^-6 the grid is the subnormal one
+    quantum = torch.ldexp(torch.ones_like(ax), e - 3)
+    q = torch.round(ax / quantum)                 # half-to-even; exact division by a power of two
+    v = q * quantum
+    _, ex2 = torch.frexp(v)
+    e2 = (ex2 - 1).clamp(min=-6)
+    m = torch.round(v / torch.ldexp(torch.ones_like(v), e2 - 3)).to(torch.int64)   # 0..15
+    normal_code = ((e2 + 7).to(torch.int64) << 3) + (m - 8)
+    code = torch.where(m >= 8, normal_code, m)    # m < 8 only on the subnormal grid (e2 == -6)
+    code = code + (torch.signbit(x).to(torch.int64) << 7)
+    return code.to(torch.uint8)
+
+
+def pow2_scale_exp(x):
+    """Largest integer t with max|x| * 2^t <= 448 (the per-tensor power-of-two scale)."""
+    mx = float(x.abs().max())
+    if mx == 0.0 or not math.isfinite(mx):
+        return 0
+    t = math.floor(math.log2(448.0 / mx))
+    while mx * 2.0 ** (t + 1) <= 448.0:
+        t += 1
+    while mx * 2.0 ** t > 448.0:
+        t -= 1
+    return t
+
+
+def quantize_tensor(x, scale_mode="pow2"):
+    """Per-tensor scale then cast.  Returns (uint8 codes, t) with codes ~ x * 2^t ('pow2') or
+    x * 448/max|x| ('exact448', t = round(log2 of that scale))."""
+    if scale_mode == "pow2":
+        t = pow2_scale_exp(x)
+        return to_e4m3(torch.ldexp(x, torch.tensor(t, device=x.device))), t
+    if scale_mode == "exact448":
+        mx = float(x.abs().max())
+        s = 448.0 / mx if mx > 0 else 1.0
+        return to_e4m3(x * s), int(round(math.log2(s)))
+    raise ValueError(scale_mode)
+
+
+def make_operand(kind, rows, cols, seed, stream, device="cpu", scale_mode="pow2", std=1.0,
+                 row_chunk=None):
+    """One operand matrix [rows, cols] of E4M3 codes.  kind: 'normal' N(0,std^2) or 'relu'
+    ReLU(N(0,1)).  Returns (codes uint8 [rows, cols], t)."""
+    n = rows * cols
+    x = normal(seed, stream, n, device=device)
+    if kind == "relu":
+        x = torch.clamp(x, min=0.0)
+    elif kind == "normal":
+        if std != 1.0:
+            x = x * std
+    else:
+        raise ValueError(kind)
+    codes, t = quantize_tensor(x, scale_mode)
+    return codes.reshape(rows, cols), t
+
+
+# ---------------------------------------------------------------------------------------------
+# Layer shapes (M, N, K) as im2col / linear GEMMs
+# ---------------------------------------------------------------------------------------------
+
+def resnet50_gemms(batch=64, image=224):
+    """(name, M, N, K) for every conv and the FC of a torchvision-style ResNet-50 forward pass
+    (stride on the 3x3 conv of each bottleneck), each written as C[M,N] = A[M,K] . B[N,K]^T."""
+    layers = []
+    h = image // 2                                # conv1: 7x7 / 2
+    layers.append(("conv1", batch * h * h, 64, 3 * 49))
+    h = h // 2                                    # maxpool / 2
+    inplanes = 64
+    for si, (planes, blocks, stride) in enumerate(((64, 3, 1), (128, 4, 2), (256, 6, 2), (512, 3, 2))):
+        for bi in range(blocks):
+            s = stride if bi == 0 else 1
+            name = "layer%d.%d" % (si + 1, bi)
+            layers.append((name + ".conv1", batch * h * h, planes, inplanes))            # 1x1
+            ho = h // s
+            layers.append((name + ".conv2", batch * ho * ho, planes, planes * 9))        # 3x3 / s
+            layers.append((name + ".conv3", batch * ho * ho, planes * 4, planes))        # 1x1
+            if bi == 0:
+                layers.append((name + ".downsample", batch * ho * ho, planes * 4, inplanes))
+            inplanes = planes * 4
+            h = ho
+    layers.append(("fc", batch, 1000, 2048))
+    return layers
+
+
+def bert_base_gemms(batch=32, seq=128):
+    m = batch * seq
+    return [("qkv", m, 2304, 768), ("attn_out", m, 768, 768),
+            ("ffn_in", m, 3072, 768), ("ffn_out", m, 768, 3072)]
+
+
+def folded_formats(t_a, t_b, prod=(5, 7, 15), acc=(4, 7, 7), rnd=0):
+    """Biases of (E, M, b) formats given in real units, moved into code units:
+    codes = real * 2^(t_a+t_b) for a product, and Q_{M,E,b}(2^-T y) = 2^-T Q_{M,E,b-T}(y),
+    so the library is called with b - T.  Returns ((E,M,b',round), (E,M,b',round), T)."""
+    T = t_a + t_b
+    return (prod[0], prod[1], prod[2] - T, rnd), (acc[0], acc[1], acc[2] - T, rnd), T

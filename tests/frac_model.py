@@ -1,0 +1,76 @@
+"""A second, independently written evaluation of the paper's definitions with Python Fractions.
+
+Used only to cross-check the C++ oracle by brute force on tiny cases.  It follows the paper's
+equations (Sec. 2.3 quantizer, Sec. 3 FMAq, App. D recursion) on exact rationals; it is NOT how
+the oracle computes (that one uses integer magnitudes in a common unit) and it is far too slow
+for anything but a handful of steps.
+"""
+from fractions import Fraction as F
+
+
+def e4m3_value(code):
+    s = -1 if code & 0x80 else 1
+    e = (code >> 3) & 15
+    m = code & 7
+    if e == 0:
+        return s * F(m, 8) * F(1, 64)
+    return s * (1 + F(m, 8)) * F(2) ** (e - 7)
+
+
+def floor_log2(x):
+    """floor(log2 x) for a positive Fraction."""
+    e = x.numerator.bit_length() - x.denominator.bit_length()
+    if F(2) ** e > x:
+        e -= 1
+    assert F(2) ** e <= x < F(2) ** (e + 1)
+    return e
+
+
+def rne_int(x):
+    fl = x.numerator // x.denominator
+    r = x - fl
+    if r > F(1, 2) or (r == F(1, 2) and fl % 2 == 1):
+        return fl + 1
+    return fl
+
+
+def quant(x, E, M, b, rnd):
+    r_of = F(2) ** (2 ** E - b - 1) * (2 - F(1, 2 ** M))
+    r_uf = F(2) ** (-b)
+    sgn = -1 if x < 0 else 1
+    ax = abs(x)
+    if ax >= r_of:
+        return sgn * r_of, "OF"
+    if ax < r_uf:
+        return F(0), ("UF" if ax != 0 else "")
+    e = floor_log2(ax)
+    frac = (ax / F(2) ** e - 1) * 2 ** M
+    m = rne_int(frac) if rnd == 1 else frac.numerator // frac.denominator
+    return sgn * F(2) ** e * (1 + F(m, 2 ** M)), ""
+
+
+def fmaq(a_code, b_code, s, qp, qa):
+    xw = e4m3_value(a_code) * e4m3_value(b_code)
+    p, _ = quant(xw, *qp)
+    t = p + s
+    z, ev = quant(t, *qa)
+    of = ev == "OF"
+    uf = (xw != 0 and p == 0) or ev == "UF"
+    return z, of, uf
+
+
+def chain(a_codes, b_codes, qp, qa):
+    s = F(0)
+    evs = []
+    for a, b in zip(a_codes, b_codes):
+        s, of, uf = fmaq(a, b, s, qp, qa)
+        evs.append((of, uf))
+    return s, evs
+
+
+def chain_chunk16(a_codes, b_codes, qp, qa):
+    t = F(0)
+    for k0 in range(0, len(a_codes), 16):
+        c, _ = chain(a_codes[k0:k0 + 16], b_codes[k0:k0 + 16], qp, qa)
+        t, _ = quant(t + c, *qa)
+    return t
