@@ -1,0 +1,207 @@
+#!/usr/bin/env python3
+"""Benchmark of the simulated low-bit-width-accumulator GEMM on one MI355X.
+
+A "step" is one pass of the hot path over the default workload: every convolution (as an im2col
+GEMM) and the FC layer of a ResNet-50 forward pass at batch 64, 224x224 (54 GEMMs,
+2.617e11 LBA-MACs), with FP8 E4M3 operands, Q_prod = M7E5 (b=15) and the 12-bit accumulator
+Q_acc = M7E4 (b=7), biases folded by the per-tensor power-of-two scales, sequential order,
+floor rounding (the paper's LBA rounding, Sec. 3).  Inputs are synthetic and resident in HBM
+before the timed region.  Prints ONE JSON line.
+
+Other workloads (for profiling, not the headline): --workload conv (ResNet-18 3x3 conv 64->64 at
+batch 32), bert (BERT-base linears at 4096 tokens), gemm4096 (4096^3).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_LANE_OPS = 256 * 64 * 2.4e9          # CUs x lanes issued per clock per CU x clock = 39.3e12 /s
+PROD_FMT = (5, 7, 15)
+ACC_FMT = (4, 7, 7)
+
+
+def build_workload(name, device):
+    import torch
+    from paper_2401_14110_amd import inputs
+    if name == "resnet50":
+        layers = inputs.resnet50_gemms(batch=64, image=224)
+        seed = 2
+    elif name == "conv":
+        layers = [("resnet18.layer1.conv", 32 * 56 * 56, 64, 576)]
+        seed = 1
+    elif name == "bert":
+        layers = inputs.bert_base_gemms(32, 128)
+        seed = 3
+    elif name == "gemm4096":
+        layers = [("gemm4096", 4096, 4096, 4096)]
+        seed = 4
+    else:
+        raise SystemExit("unknown workload %r" % name)
+    # one operand tensor per distinct (rows, K) and role: layers of equal shape share data
+    cache_a, cache_b, out = {}, {}, []
+    for idx, (lname, M, N, K) in enumerate(layers):
+        if (M, K) not in cache_a:
+            if name == "resnet50":
+                kind = "normal" if lname == "conv1" else "relu"
+            elif name == "conv":
+                kind = "relu"
+            else:
+                kind = "normal"
+            cache_a[(M, K)] = inputs.make_operand(kind, M, K, seed, 2 * len(cache_a), device=device)
+        if (N, K) not in cache_b:
+            if name in ("resnet50", "conv"):
+                std = (2.0 / K) ** 0.5
+            elif name == "bert":
+                std = 0.02
+            else:
+                std = 1.0
+            cache_b[(N, K)] = inputs.make_operand("normal", N, K, seed, 2 * len(cache_b) + 1,
+                                                  device=device, std=std)
+        A, ta = cache_a[(M, K)]
+        B, tb = cache_b[(N, K)]
+        out.append(dict(name=lname, M=M, N=N, K=K, A=A, B=B, ta=ta, tb=tb))
+    torch.cuda.synchronize()
+    return out
+
+
+def cpu_baseline(layer, qp, qa, C_gpu, budget_macs=2.0e9):
+    """The oracle, as it stands, on a bounded slab of one layer; also a parity check of the slab."""
+    import numpy as np
+    from oracle import lba_ref
+    rows = int(min(layer["M"], max(1, budget_macs // (layer["N"] * layer["K"]))))
+    A = layer["A"][:rows].cpu().numpy()
+    B = layer["B"].cpu().numpy()
+    threads = min(16, os.cpu_count() or 1)
+    t0 = time.perf_counter()
+    want = lba_ref.gemm(A, B, lba_ref.QFmt(*qp), lba_ref.QFmt(*qa), nthreads=threads)
+    dt = time.perf_counter() - t0
+    got = C_gpu[:rows].cpu().numpy()
+    parity = bool(np.array_equal(got.view(np.uint32), want.view(np.uint32)))
+    macs = rows * layer["N"] * layer["K"]
+    return {"value": macs / dt, "unit": "LBA-MAC/s", "cores": threads, "kind": "oracle",
+            "sample": "first %d rows of %s (M=%d,N=%d,K=%d), %.3g MACs, %.1f s" %
+                      (rows, layer["name"], layer["M"], layer["N"], layer["K"], macs, dt),
+            "bit_exact_vs_gpu": parity}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="resnet50")
+    ap.add_argument("--round", default="floor", choices=["floor", "rne"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs on ONE GPU (every output chain is independent; "
+                         "see DESIGN.md for how it would shard). Use --gpus 1.")
+    import torch
+    from paper_2401_14110_amd import binding as lb
+    from paper_2401_14110_amd import inputs
+    lb.lib()
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    rnd = 0 if args.round == "floor" else 1
+
+    layers = build_workload(args.workload, dev)
+    cmax = max(l["M"] * l["N"] for l in layers)
+    Cbuf = torch.empty(cmax, dtype=torch.float32, device=dev)
+    for l in layers:
+        l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], PROD_FMT, ACC_FMT, rnd)
+        l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"])
+        l["C"] = Cbuf[: l["M"] * l["N"]].view(l["M"], l["N"])
+        l["macs"] = l["M"] * l["N"] * l["K"]
+    total_macs = sum(l["macs"] for l in layers)
+
+    def one_step(events=None):
+        for i, l in enumerate(layers):
+            if events is not None:
+                events[i][0].record()
+            lb.gemm(l["A"], l["B"], l["qp"], l["qa"], out=l["C"])
+            if events is not None:
+                events[i][1].record()
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in layers]
+          for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        one_step(ev[s])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    value = total_macs * args.steps / wall
+
+    # per-launch durations (HIP events on the launch stream), grouped by kernel variant
+    groups = {}
+    per_layer_ms = [0.0] * len(layers)
+    for s in range(args.steps):
+        for i, l in enumerate(layers):
+            ms = ev[s][i][0].elapsed_time(ev[s][i][1])
+            per_layer_ms[i] += ms / args.steps
+            p = l["plan"]
+            key = (p["kernel"], p["prod_mode"], p["round"], p["thread_m"], p["thread_n"], p["tile_k"])
+            g = groups.setdefault(key, dict(ms=0.0, macs=0, launches=0, ops=p["valu_per_mac_x100"] / 100.0))
+            g["ms"] += ms
+            g["macs"] += l["macs"]
+            g["launches"] += 1
+    dom_key = max(groups, key=lambda k: groups[k]["ms"])
+    dom = groups[dom_key]
+    achieved = dom["macs"] * dom["ops"] / (dom["ms"] * 1e-3)
+    roofline = {
+        "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
+        "frac": achieved / PEAK_LANE_OPS, "traffic": None,
+        "kernel": "lba_%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (
+            "fast" if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
+            "rne" if dom_key[2] else "floor"),
+        "valu_ops_per_mac": dom["ops"], "avg_launch_ms": dom["ms"] / dom["launches"],
+        "launches": dom["launches"], "mac_per_s": dom["macs"] / (dom["ms"] * 1e-3),
+        "time_share": dom["ms"] / sum(g["ms"] for g in groups.values()),
+    }
+
+    if args.per_layer:
+        for i, l in enumerate(layers):
+            p = l["plan"]
+            sys.stderr.write("%-24s M=%-7d N=%-5d K=%-5d %8.3f ms %7.3f TMAC/s  tile %dx%dx%d pm=%d grid=%dx%d\n" % (
+                l["name"], l["M"], l["N"], l["K"], per_layer_ms[i], l["macs"] / per_layer_ms[i] / 1e9,
+                p["tile_m"], p["tile_n"], p["tile_k"], p["prod_mode"], p["grid_x"], p["grid_y"]))
+
+    out = {
+        "metric": "simulated LBA-MACs/sec on one MI355X", "value": value, "unit": "LBA-MAC/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32-carrier/fp8-in",
+        "data": "synthetic",
+        "config": {"workload": {"resnet50": "ResNet-50 forward, batch 64, 224x224: 53 convs (im2col) + FC as 54 LBA GEMMs",
+                                "conv": "ResNet-18 3x3 conv 64->64, batch 32, 56x56 (M=100352,N=64,K=576)",
+                                "bert": "BERT-base linears, 4096 tokens", "gemm4096": "4096^3 GEMM"}[args.workload],
+                   "macs_per_step": total_macs, "qprod": "M7E5 b=15", "qacc": "M7E4 b=7 (12-bit)",
+                   "round": args.round, "order": "sequential", "scale": "per-tensor power of two, folded into b"},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        # a mid-sized layer whose output is still in the shared buffer: recompute it last
+        pick = max(range(len(layers)), key=lambda i: (layers[i]["K"] == 576, layers[i]["M"]))
+        l = layers[pick]
+        lb.gemm(l["A"], l["B"], l["qp"], l["qa"], out=l["C"])
+        torch.cuda.synchronize()
+        out["cpu_baseline"] = cpu_baseline(l, l["qp"], l["qa"], l["C"])
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

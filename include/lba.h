@@ -1,0 +1,111 @@
+/* lba.h -- C ABI of the MI355X (gfx950) simulated low-bit-width-accumulator matrix product.
+ *
+ * The library computes, for FP8 (OCP E4M3) operand matrices, the matrix product in which every
+ * fused multiply-add is replaced by the quantized one of arXiv 2401.14110, Sec. 3:
+ *
+ *      FMAq(x, w, s) = Q_acc( Q_prod(x * w) + s )
+ *
+ * where x*w and the sum are exact and Q_prod / Q_acc are the floating-point quantizer of Sec. 2.3
+ * (M mantissa bits, E exponent bits, exponent bias b):
+ *
+ *      R_OF = 2^(2^E - b - 1) * (2 - 2^-M),    R_UF = 2^-b
+ *      |v| >= R_OF  ->  sign(v) * R_OF           (saturation)
+ *      |v| <  R_UF  ->  0                        (flush to zero, decided before rounding)
+ *      otherwise       sign(v) * 2^e * (1 + m),  e = floor(log2 |v|), m rounded to M bits
+ *
+ * with the mantissa rounded by truncation of the magnitude ("floor ... via bit-mask", Sec. 3) or
+ * to nearest, ties to even.  The format has 2^E exponent values, no subnormals, no inf, no NaN.
+ *
+ * Layout follows App. A (Y = X W^T): A is [M, K] and B is [N, K], both row-major with the
+ * reduction index contiguous; C is [M, N] row-major float32:  C[m, n] = S_K of the recursion
+ * S_0 = 0, S_{k+1} = FMAq(A[m, k], B[n, k], S_k)  (App. D), k = 0 .. K-1 in that order.
+ *
+ * All pointers are DEVICE pointers owned by the caller.  Calls enqueue work on `hip_stream`
+ * (a hipStream_t passed as void*; NULL = the default stream) and return without synchronising.
+ * A and B are only read; C and the masks are fully overwritten.  The library keeps no state
+ * between calls and allocates no device memory.  On any error nothing is enqueued.
+ */
+#ifndef LBA_H_
+#define LBA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* One quantizer Q_{M,E,b} (Sec. 2.3).  bias is the paper's b (signed): R_UF = 2^-bias and the
+ * top exponent is 2^exp_bits - bias - 1.  A per-tensor power-of-two scale of the operands is
+ * folded by the caller into bias:  Q_{M,E,b}(2^-T y) = 2^-T Q_{M,E,b-T}(y).
+ * Limits (else LBA_ERR_FORMAT): 1 <= man_bits <= 23, 2 <= exp_bits <= 7, round in {0, 1},
+ * bias <= 126 and 2^exp_bits - bias - 1 <= 127, i.e. every value of the format is an FP32 normal. */
+typedef struct {
+    int32_t exp_bits;   /* E */
+    int32_t man_bits;   /* M */
+    int32_t bias;       /* b */
+    int32_t round;      /* LBA_ROUND_FLOOR or LBA_ROUND_RNE */
+} lba_qfmt;
+
+enum { LBA_ROUND_FLOOR = 0,   /* truncate the magnitude's mantissa (the paper's LBA rounding) */
+       LBA_ROUND_RNE = 1 };   /* nearest, ties to even (the generic Round of the quantizer)   */
+
+enum { LBA_ORDER_SEQ = 0,       /* k = 0 .. K-1 in one chain (App. D)                           */
+       LBA_ORDER_CHUNK16 = 1 }; /* chunks of 16, then a chain over the chunk sums (Sec. 3, Fig. 1) */
+
+enum { LBA_OK = 0,
+       LBA_ERR_NULL = 1,         /* a required pointer is NULL                                  */
+       LBA_ERR_SHAPE = 2,        /* negative or too large M, N, K                               */
+       LBA_ERR_FORMAT = 3,       /* a quantizer format outside the limits above                 */
+       LBA_ERR_UNSUPPORTED = 4,  /* unknown order, or an order this build does not implement    */
+       LBA_ERR_ALIGN = 5,        /* reserved: no entry point requires alignment                 */
+       LBA_ERR_LAUNCH = 6 };     /* the HIP runtime refused the launch                          */
+
+/* Forward product (Sec. 3, App. A, App. D).
+ *   A   [M, K] uint8 E4M3 codes (device), B [N, K] uint8 E4M3 codes (device), C [M, N] float32 (device).
+ *   E4M3: 1 sign, 4 exponent (bias 7), 3 mantissa bits; e = 0 is subnormal, m * 2^-9; no inf.
+ *   The two NaN codes 0x7f / 0xff are outside the contract; they are read as +-480.
+ *   Zero results are stored as +0.0f.  K == 0 stores +0.0f everywhere; M*N == 0 does nothing.
+ *   No alignment is required of A, B, C or of K.  Shape limits: M, N, K < 2^31, N <= 2^21. */
+int lba_gemm(const uint8_t* A, const uint8_t* B, float* C,
+             int64_t M, int64_t N, int64_t K,
+             lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream);
+
+/* Forward product re-run for the fine-grained gradient estimators (Sec. 4, App. C.3, App. D): the
+ * same deterministic chain, additionally writing one bit per FMAq step and event:
+ *   OF_k = [ |Q_prod(x_k w_k) + S_k| >= R_OF of Q_acc ]         (1 - STE^OF of App. D)
+ *   UF_k = [ x_k w_k != 0 and Q_prod(x_k w_k) == 0 ]  or  [ t_k != 0 and |t_k| < R_UF of Q_acc ]
+ * Each plane holds lba_mask_words(M, N, K) uint32 words: word index ((k / 32) * M + m) * N + n,
+ * bit k % 32; bits for k >= K are zero.  C may be NULL (then only the planes are written); either
+ * plane may be NULL but not both.  C, when given, equals lba_gemm's bit for bit.
+ * LBA_ORDER_SEQ only. */
+int lba_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C,
+                 uint32_t* of_mask, uint32_t* uf_mask,
+                 int64_t M, int64_t N, int64_t K,
+                 lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream);
+
+/* Number of uint32 words in one event plane: ceil(K / 32) * M * N (0 if any size is <= 0). */
+size_t lba_mask_words(int64_t M, int64_t N, int64_t K);
+
+/* Static, human-readable text for a status code (never NULL). */
+const char* lba_strerror(int code);
+
+/* Which kernel a call would run, without running it (host only; needs no GPU).
+ * The numeric result never depends on this choice; it is exposed for benchmarking reports. */
+typedef struct {
+    int32_t kernel;        /* 0: scaled-domain FP32-carrier kernel, 1: general kernel            */
+    int32_t prod_mode;     /* kernel 0: 0 Q_prod is the identity, 1 flush only, 2 flush + clamp   */
+    int32_t round;         /* rounding of Q_acc as executed                                       */
+    int32_t tile_m, tile_n, tile_k;   /* workgroup tile                                           */
+    int32_t thread_m, thread_n;       /* outputs per lane                                         */
+    int32_t grid_x, grid_y;           /* workgroups launched                                      */
+    int32_t valu_per_mac_x100;        /* VALU instructions per MAC in the inner loop, times 100   */
+} lba_plan_info;
+
+int lba_plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc,
+                   int32_t order, int32_t with_masks, lba_plan_info* out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LBA_H_ */

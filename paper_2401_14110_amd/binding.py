@@ -1,0 +1,145 @@
+"""Thin ctypes binding over the C ABI in include/lba.h (argument marshalling only).
+
+Every step of the computation runs in the HIP library; there is no CPU fallback: if the library
+has not been built, loading raises.  torch is used for device memory and for the current stream.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIBPATH = os.path.join(_HERE, "liblba_hip.so")
+
+ROUND_FLOOR, ROUND_RNE = 0, 1
+ORDER_SEQ, ORDER_CHUNK16 = 0, 1
+OK, ERR_NULL, ERR_SHAPE, ERR_FORMAT, ERR_UNSUPPORTED, ERR_ALIGN, ERR_LAUNCH = range(7)
+
+
+class lba_qfmt(ctypes.Structure):
+    _fields_ = [("exp_bits", ctypes.c_int32), ("man_bits", ctypes.c_int32),
+                ("bias", ctypes.c_int32), ("round", ctypes.c_int32)]
+
+
+class lba_plan_info(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in (
+        "kernel", "prod_mode", "round", "tile_m", "tile_n", "tile_k", "thread_m", "thread_n",
+        "grid_x", "grid_y", "valu_per_mac_x100")]
+
+
+class LbaError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__("lba error %d: %s" % (code, text))
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load paper_2401_14110_amd/liblba_hip.so (built by __graft_entry__.build())."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIBPATH):
+            raise RuntimeError("HIP library %s is missing: run `python __graft_entry__.py` "
+                               "(there is no fallback path)" % _LIBPATH)
+        L = ctypes.CDLL(_LIBPATH)
+        vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
+        L.lba_gemm.restype = ctypes.c_int
+        L.lba_gemm.argtypes = [vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, i32, vp]
+        L.lba_gemm_bwd.restype = ctypes.c_int
+        L.lba_gemm_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, i32, vp]
+        L.lba_mask_words.restype = ctypes.c_size_t
+        L.lba_mask_words.argtypes = [i64, i64, i64]
+        L.lba_strerror.restype = ctypes.c_char_p
+        L.lba_strerror.argtypes = [ctypes.c_int]
+        L.lba_plan_query.restype = ctypes.c_int
+        L.lba_plan_query.argtypes = [i64, i64, i64, lba_qfmt, lba_qfmt, i32, i32,
+                                     ctypes.POINTER(lba_plan_info)]
+        _lib = L
+    return _lib
+
+
+def qfmt(f):
+    """(E, M, b, round) tuple or lba_qfmt -> lba_qfmt."""
+    return f if isinstance(f, lba_qfmt) else lba_qfmt(*[int(v) for v in f])
+
+
+def lba_strerror(code):
+    return lib().lba_strerror(int(code)).decode()
+
+
+strerror = lba_strerror
+
+
+def _check(rc):
+    if rc != OK:
+        raise LbaError(rc, strerror(rc))
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+# ---- raw calls: same names and argument order as include/lba.h ------------------------------
+
+def lba_gemm(A, B, C, M, N, K, qprod, qacc, order=ORDER_SEQ, hip_stream=None):
+    """Raw call: A, B, C are device addresses (ints) or None; returns the status code."""
+    return lib().lba_gemm(A, B, C, M, N, K, qfmt(qprod), qfmt(qacc), order,
+                          ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_gemm_bwd(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, order=ORDER_SEQ, hip_stream=None):
+    return lib().lba_gemm_bwd(A, B, C, of_mask, uf_mask, M, N, K, qfmt(qprod), qfmt(qacc), order,
+                              ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_mask_words(M, N, K):
+    return int(lib().lba_mask_words(M, N, K))
+
+
+def lba_plan_query(M, N, K, qprod, qacc, order=ORDER_SEQ, with_masks=0):
+    info = lba_plan_info()
+    _check(lib().lba_plan_query(M, N, K, qfmt(qprod), qfmt(qacc), order, with_masks, ctypes.byref(info)))
+    return {n: getattr(info, n) for n, _ in lba_plan_info._fields_}
+
+
+# ---- tensor conveniences --------------------------------------------------------------------
+
+def _ops(A, B):
+    if A.dtype != torch.uint8 or B.dtype != torch.uint8:
+        raise TypeError("A and B must be uint8 E4M3 codes")
+    if not (A.is_cuda and B.is_cuda):
+        raise ValueError("A and B must be device tensors")
+    if A.dim() != 2 or B.dim() != 2 or A.shape[1] != B.shape[1]:
+        raise ValueError("A must be [M, K] and B [N, K]")
+    return A.contiguous(), B.contiguous()
+
+
+def gemm(A, B, qprod, qacc, order=ORDER_SEQ, out=None, stream=None):
+    """C[M,N] (float32, device) = LBA product of A [M,K] and B [N,K] uint8 E4M3 device tensors."""
+    A, B = _ops(A, B)
+    M, K = A.shape
+    N = B.shape[0]
+    C = out if out is not None else torch.empty((M, N), dtype=torch.float32, device=A.device)
+    _check(lib().lba_gemm(A.data_ptr() or None, B.data_ptr() or None, C.data_ptr() or None,
+                          M, N, K, qfmt(qprod), qfmt(qacc), order, _stream(stream)))
+    return C
+
+
+def gemm_bwd(A, B, qprod, qacc, order=ORDER_SEQ, want_c=True, stream=None):
+    """Returns (C or None, OF plane, UF plane); planes are int32 tensors [ceil(K/32), M, N]."""
+    A, B = _ops(A, B)
+    M, K = A.shape
+    N = B.shape[0]
+    W = (K + 31) // 32
+    C = torch.empty((M, N), dtype=torch.float32, device=A.device) if want_c else None
+    of = torch.empty((W, M, N), dtype=torch.int32, device=A.device)
+    uf = torch.empty((W, M, N), dtype=torch.int32, device=A.device)
+    _check(lib().lba_gemm_bwd(A.data_ptr() or None, B.data_ptr() or None,
+                              (C.data_ptr() or None) if want_c else None,
+                              of.data_ptr() or None, uf.data_ptr() or None,
+                              M, N, K, qfmt(qprod), qfmt(qacc), order, _stream(stream)))
+    return C, of, uf

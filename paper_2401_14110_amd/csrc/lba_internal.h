@@ -1,0 +1,57 @@
+// lba_internal.h -- host-side plan of one LBA GEMM call and the parameter block its kernel reads.
+// Shared by the planner (plain C++, testable without a GPU) and the HIP translation unit.
+#ifndef LBA_INTERNAL_H_
+#define LBA_INTERNAL_H_
+
+#include <stdint.h>
+
+#include "lba.h"
+
+namespace lba {
+
+enum { KERNEL_FAST = 0, KERNEL_GEN = 1 };
+enum { PM_IDENT = 0, PM_FLUSH = 1, PM_FLUSH_CLAMP = 2 };
+
+// Uniform (scalar-register) parameters of a launch.  All thresholds are exact FP32 values.
+struct KParams {
+    const uint8_t* A;
+    const uint8_t* B;
+    float* C;
+    uint32_t* of_mask;
+    uint32_t* uf_mask;
+    int32_t M, N, K;
+    int32_t ld_align;        // 16: every row start of A and B is 16-byte aligned; 1: any alignment
+    int32_t c_vec;           // 1 if rows of C (and of the planes) can take 16-byte stores
+    // operand decode: value(code) * 2^exp_a / 2^exp_b, folded into the lookup tables
+    int32_t exp_a, exp_b;
+    int32_t out_exp;         // C = S * 2^out_exp
+    float kc;                // FAST with an explicit product: t = p * kc + S
+    // accumulator quantizer, in the kernel's (possibly scaled) domain
+    uint32_t mask_a; uint32_t half_a; int32_t sh_a; float rof_a; float ruf_a;
+    // product quantizer
+    uint32_t mask_p; uint32_t half_p; int32_t sh_p; float rof_p; float ruf_p;
+    int32_t prod_round;      // GEN: product mantissa narrower than an E4M3 product (M_prod < 7)
+    int32_t prod_rne;        // GEN: its rounding
+};
+
+struct Plan {
+    int kernel;              // KERNEL_FAST / KERNEL_GEN
+    int prod_mode;           // PM_*
+    int round;               // LBA_ROUND_*
+    int events;              // also write the event planes
+    int tm, tn, bk;          // outputs per lane (tm x tn), k-depth of a tile; tile = 16tm x 16tn
+    int grid_x, grid_y;
+    int valu_per_mac_x100;
+    KParams kp;
+};
+
+// Validation shared by every entry point; returns an lba status code.
+int validate_shapes(int64_t M, int64_t N, int64_t K);
+int validate_fmt(const lba_qfmt& q);
+
+// Builds the plan (pointers in kp are left null).  Returns an lba status code.
+int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qprod, const lba_qfmt& qacc,
+              int order, int events, Plan* out);
+
+}  // namespace lba
+#endif

@@ -1,0 +1,596 @@
+// lba_kernels.hip -- gfx950 kernels and C ABI of the simulated low-bit-width-accumulator GEMM.
+//
+// One FMAq step is  S <- Q_acc(Q_prod(a*b) + S)  (arXiv 2401.14110, Sec. 3) with the quantizer of
+// Sec. 2.3; each output element C[m,n] is the K-long sequential chain of App. D.  The chain is a
+// strict dependency in k, so parallelism is over outputs only: every lane owns a TM x TN block of
+// independent chains held in registers, a 256-lane workgroup owns a (16 TM) x (16 TN) tile of C,
+// and k advances in lock-step through tiles of A and B staged in LDS.
+//
+// Data path per k-tile (depth BK):
+//   global: each lane fetches 16 contiguous bytes (one row, 16 k) of A and/or B   [coalescing is
+//           irrelevant here: < 0.1 byte per MAC]
+//   decode: byte -> FP32 through a 256-entry LDS table built once per workgroup; the table holds
+//           value(code) * 2^exp, so operands arrive pre-scaled into the kernel's domain
+//   LDS:    tiles are stored k-major ([k][row], row contiguous) so that a lane reads its 4 / 8
+//           operand values of one k with one / two 16-byte reads, without bank conflicts
+//   VALU:   TM*TN chains advance by one step; all FP32 ops are exact or a single rounding
+//           (see lba_plan.cpp for the argument)
+// Two LDS stages; the next tile's global loads are in flight while the current one is consumed.
+//
+// The wave's FP mode is changed with s_setreg (rounding mode) and the translation unit is built
+// with FP32 denormals flushed; no runtime integer division is used inside the kernels.
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lba_internal.h"
+
+namespace lba {
+
+// ---------------------------------------------------------------------------------------------
+// wave FP mode
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void set_round_nearest() { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 0\n\ts_nop 1" ::: "memory"); }
+__device__ __forceinline__ void set_round_pinf()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 1\n\ts_nop 1" ::: "memory"); }
+__device__ __forceinline__ void set_round_ninf()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 2\n\ts_nop 1" ::: "memory"); }
+__device__ __forceinline__ void set_round_zero()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 3\n\ts_nop 1" ::: "memory"); }
+__device__ __forceinline__ void set_flush_f32()     { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 4, 2), 0\n\ts_nop 1" ::: "memory"); }
+
+__device__ __forceinline__ float med3(float x, float lo, float hi) { return __builtin_amdgcn_fmed3f(x, lo, hi); }
+
+// ---------------------------------------------------------------------------------------------
+// operand decode table: E4M3 code -> value * 2^e as an exact FP32 (Sec. "inputs" of lba.h)
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ float decode_entry(int code, int e) {
+    const int ex = (code >> 3) & 15, m = code & 7;
+    const int sig = ex ? (8 + m) : m;
+    const int lsb = ex ? (ex - 10) : -9;
+    const float v = __builtin_ldexpf((float)sig, lsb + e);
+    return (code & 0x80) ? -v : v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// FMAq step policies
+// ---------------------------------------------------------------------------------------------
+// Mantissa rounding of an FP32 word to the top (23 - sh) mantissa bits, nearest-even, for a word
+// that is already the exact value or a harmless first rounding of it.
+__device__ __forceinline__ uint32_t rne_bits(uint32_t u, uint32_t half, int sh, uint32_t mask) {
+    return (u + half + ((u >> sh) & 1u)) & mask;
+}
+
+template <int PM, int RND>
+struct FastStep {
+    static constexpr bool kEvents = false;
+    static constexpr bool kRtz = (RND == LBA_ROUND_FLOOR);
+    __device__ static __forceinline__ void begin() { if (kRtz) set_round_zero(); }
+    __device__ static __forceinline__ void end() { if (kRtz) set_round_nearest(); }
+    __device__ static __forceinline__ float run(float S, float a, float b, const KParams& p) {
+        float t;
+        if (PM == PM_IDENT) {
+            t = __builtin_fmaf(a, b, S);
+        } else {
+            float q = a * b;                                   // exact; flushed below Q_prod's R_UF
+            if (PM == PM_FLUSH_CLAMP) q = med3(q, -p.rof_p, p.rof_p);
+            t = __builtin_fmaf(q, p.kc, S);                    // one rounding of the exact sum
+        }
+        uint32_t u = __float_as_uint(t);
+        if (RND == LBA_ROUND_RNE) u = rne_bits(u, p.half_a, p.sh_a, p.mask_a);
+        else u &= p.mask_a;
+        return med3(__uint_as_float(u), -p.rof_a, p.rof_a);
+    }
+};
+
+// General step: plain domain, every sub-step explicit.  EVENTS adds the two event bits.
+struct GenOut { float S; uint32_t of; uint32_t uf; };
+
+template <int RND>
+__device__ __forceinline__ float gen_product(float a, float b, const KParams& p, uint32_t* uf1) {
+    float pr = a * b;                                          // exact
+    uint32_t u = __float_as_uint(pr);
+    if (p.prod_round) {
+        if (p.prod_rne) u = rne_bits(u, p.half_p, p.sh_p, p.mask_p);   // input exact: one rounding
+        else u &= p.mask_p;
+    }
+    float q = __uint_as_float(u);
+    const bool fl = __builtin_fabsf(pr) < p.ruf_p;             // decided on the un-rounded product
+    *uf1 = (fl && pr != 0.0f) ? 1u : 0u;
+    q = fl ? 0.0f : q;
+    return med3(q, -p.rof_p, p.rof_p);
+}
+
+// Accumulator quantizer from the truncated sum's word uz (sign-magnitude, exact decisions) and
+// the sticky bit.
+__device__ __forceinline__ float gen_acc_rne(uint32_t uz, uint32_t sticky, const KParams& p,
+                                             uint32_t* of, bool* small) {
+    const uint32_t mag = uz & 0x7FFFFFFFu;
+    const uint32_t sign = uz & 0x80000000u;
+    const uint32_t rofb = __float_as_uint(p.rof_a), rufb = __float_as_uint(p.ruf_a);
+    *of = mag >= rofb ? 1u : 0u;
+    *small = mag < rufb;
+    const int s1 = p.sh_a + 1;
+    uint32_t w = (mag << 1) | sticky;                          // one more bit of precision
+    const uint32_t lowmask = (1u << s1) - 1u;
+    w = (w + (lowmask >> 1) + ((w >> s1) & 1u)) & ~lowmask;
+    uint32_t r = sign | (w >> 1);
+    r = *of ? (sign | rofb) : r;
+    r = *small ? 0u : r;
+    return __uint_as_float(r);
+}
+
+// ---------------------------------------------------------------------------------------------
+// tile kernel
+// ---------------------------------------------------------------------------------------------
+template <int ROWS, int BK>
+struct Stage {
+    static constexpr int kChunks = ROWS * BK / 16;                         // 16-byte pieces per tile
+    static constexpr int kPerLane = (kChunks + 255) / 256;
+};
+
+// Fetch this lane's 16-byte pieces of one operand tile into registers (zero outside the matrix).
+// ld_align == 16: every piece is 16-byte aligned and wholly inside its row (K % 16 == 0).
+// Otherwise: five 4-byte-aligned loads cover the piece at any byte offset and are funnel-shifted
+// into place.  Each load address is clamped to the aligned word holding the last valid byte, so
+// every word read contains at least one byte of the matrix (it cannot cross into another page).
+template <int ROWS, int BK>
+__device__ __forceinline__ void fetch_tile(const uint8_t* __restrict__ G, int rows, int K, int r0, int k0,
+                                           int ld_align, int tid, uint4 (&regs)[Stage<ROWS, BK>::kPerLane]) {
+#pragma unroll
+    for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
+        const int c = tid + i * 256;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (c < Stage<ROWS, BK>::kChunks) {
+            const int row = c & (ROWS - 1);
+            const int kq = c / ROWS;                                        // ROWS is a power of two
+            const int r = r0 + row, k = k0 + kq * 16;
+            if (r < rows && k < K) {
+                const uint8_t* src = G + (int64_t)r * K + k;
+                if (ld_align == 16) {
+                    v = *reinterpret_cast<const uint4*>(src);
+                } else {
+                    const int nvalid = (K - k) < 16 ? (K - k) : 16;         // bytes of this piece inside the row
+                    const uintptr_t a0 = reinterpret_cast<uintptr_t>(src);
+                    const uintptr_t first = a0 & ~(uintptr_t)3;
+                    const uintptr_t last = (a0 + (uintptr_t)(nvalid - 1)) & ~(uintptr_t)3;
+                    uint32_t d[5];
+#pragma unroll
+                    for (int j = 0; j < 5; ++j) {
+                        uintptr_t a = first + 4u * j;
+                        a = a < last ? a : last;
+                        d[j] = *reinterpret_cast<const uint32_t*>(a);
+                    }
+                    const uint32_t sh = (uint32_t)(a0 & 3u) * 8u;
+                    uint32_t w[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        w[j] = __builtin_amdgcn_alignbit(d[j + 1], d[j], sh);   // ({d[j+1], d[j]} >> sh)[31:0]
+                        const int nb = nvalid - 4 * j;                      // valid bytes in this word
+                        const uint32_t keep = nb >= 4 ? 0xFFFFFFFFu : (nb <= 0 ? 0u : ((1u << (8 * nb)) - 1u));
+                        w[j] &= keep;
+                    }
+                    v = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+        }
+        regs[i] = v;
+    }
+}
+
+// Decode the fetched pieces through the table and store them k-major into one LDS stage.
+template <int ROWS, int BK>
+__device__ __forceinline__ void store_tile(float* __restrict__ dst /* [BK][ROWS] */, const float* __restrict__ lut,
+                                           int tid, const uint4 (&regs)[Stage<ROWS, BK>::kPerLane]) {
+#pragma unroll
+    for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
+        const int c = tid + i * 256;
+        if (c < Stage<ROWS, BK>::kChunks) {
+            const int row = c & (ROWS - 1);
+            const int kq = c / ROWS;
+            const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const uint32_t code = (w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+                dst[(kq * 16 + j) * ROWS + row] = lut[code];
+            }
+        }
+    }
+}
+
+template <int TM, int TN, int BK, class Step>
+__global__ void __launch_bounds__(256) lba_fast_kernel(const KParams p) {
+    constexpr int BM = 16 * TM, BN = 16 * TN;
+    constexpr int STAGE = BK * (BM + BN);
+    constexpr int kUnroll = (TM * TN >= 64) ? 2 : 8;
+    __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
+    __shared__ float lut_a[256];
+    __shared__ float lut_b[256];
+
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+
+    lut_a[tid] = decode_entry(tid, p.exp_a);
+    lut_b[tid] = decode_entry(tid, p.exp_b);
+    set_flush_f32();
+    Step::begin();
+
+    float acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) acc[i][j] = 0.0f;
+
+    uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
+    const int ntiles = (p.K + BK - 1) / BK;                    // K > 0 here; division by a constant
+
+    fetch_tile<BM, BK>(p.A, p.M, p.K, m0, 0, p.ld_align, tid, ra);
+    fetch_tile<BN, BK>(p.B, p.N, p.K, n0, 0, p.ld_align, tid, rb);
+    __syncthreads();                                           // tables ready
+    store_tile<BM, BK>(smem, lut_a, tid, ra);
+    store_tile<BN, BK>(smem + BK * BM, lut_b, tid, rb);
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        const float* As = smem + (t & 1) * STAGE;
+        const float* Bs = As + BK * BM;
+        const bool more = (t + 1) < ntiles;
+        if (more) {
+            fetch_tile<BM, BK>(p.A, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
+            fetch_tile<BN, BK>(p.B, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tid, rb);
+        }
+#pragma unroll kUnroll
+        for (int k = 0; k < BK; ++k) {
+            float a[TM], b[TN];
+#pragma unroll
+            for (int g = 0; g < TM / 4; ++g) {
+                const float4 v = *reinterpret_cast<const float4*>(As + k * BM + g * (BM / 2) + ty * 4);
+                a[4 * g + 0] = v.x; a[4 * g + 1] = v.y; a[4 * g + 2] = v.z; a[4 * g + 3] = v.w;
+            }
+#pragma unroll
+            for (int g = 0; g < TN / 4; ++g) {
+                const float4 v = *reinterpret_cast<const float4*>(Bs + k * BN + g * (BN / 2) + tx * 4);
+                b[4 * g + 0] = v.x; b[4 * g + 1] = v.y; b[4 * g + 2] = v.z; b[4 * g + 3] = v.w;
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = Step::run(acc[i][j], a[i], b[j], p);
+        }
+        if (more) {
+            float* Ad = smem + ((t + 1) & 1) * STAGE;
+            store_tile<BM, BK>(Ad, lut_a, tid, ra);
+            store_tile<BN, BK>(Ad + BK * BM, lut_b, tid, rb);
+        }
+        __syncthreads();
+    }
+    Step::end();
+
+    // C = S * 2^out_exp, zero written as +0
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + (i >> 2) * (BM / 2) + ty * 4 + (i & 3);
+        if (m >= p.M) continue;
+#pragma unroll
+        for (int g = 0; g < TN / 4; ++g) {
+            const int n = n0 + g * (BN / 2) + tx * 4;
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float s = acc[i][4 * g + j];
+                v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);
+            }
+            float* dst = p.C + (int64_t)m * p.N + n;
+            if (p.c_vec && n + 3 < p.N) {
+                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (n + j < p.N) dst[j] = v[j];
+            }
+        }
+    }
+}
+
+// General kernel: 4 x 4 outputs per lane, 64 x 64 tile, BK = 32 (one event word per tile).
+template <int RND, bool EVENTS>
+__global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
+    constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
+    constexpr int STAGE = BK * (BM + BN);
+    __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
+    __shared__ float lut_a[256];
+    __shared__ float lut_b[256];
+
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+
+    lut_a[tid] = decode_entry(tid, p.exp_a);
+    lut_b[tid] = decode_entry(tid, p.exp_b);
+    set_flush_f32();
+    if (RND == LBA_ROUND_FLOOR) set_round_zero();
+
+    float acc[TM][TN];
+    uint32_t wof[TM][TN], wuf[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) { acc[i][j] = 0.0f; wof[i][j] = 0u; wuf[i][j] = 0u; }
+
+    uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
+    const int ntiles = (p.K + BK - 1) / BK;
+    const uint32_t rofb = __float_as_uint(p.rof_a), rufb = __float_as_uint(p.ruf_a);
+
+    fetch_tile<BM, BK>(p.A, p.M, p.K, m0, 0, p.ld_align, tid, ra);
+    fetch_tile<BN, BK>(p.B, p.N, p.K, n0, 0, p.ld_align, tid, rb);
+    __syncthreads();
+    store_tile<BM, BK>(smem, lut_a, tid, ra);
+    store_tile<BN, BK>(smem + BK * BM, lut_b, tid, rb);
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        const float* As = smem + (t & 1) * STAGE;
+        const float* Bs = As + BK * BM;
+        const bool more = (t + 1) < ntiles;
+        if (more) {
+            fetch_tile<BM, BK>(p.A, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
+            fetch_tile<BN, BK>(p.B, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tid, rb);
+        }
+#pragma unroll 2
+        for (int k = 0; k < BK; ++k) {
+            const float4 av = *reinterpret_cast<const float4*>(As + k * BM + ty * 4);
+            const float4 bv = *reinterpret_cast<const float4*>(Bs + k * BN + tx * 4);
+            const float a[4] = {av.x, av.y, av.z, av.w};
+            const float b[4] = {bv.x, bv.y, bv.z, bv.w};
+            float pq[TM][TN];
+            uint32_t uf1[TM][TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) pq[i][j] = gen_product<RND>(a[i], b[j], p, &uf1[i][j]);
+
+            if (RND == LBA_ROUND_FLOOR) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const float S = acc[i][j];
+                        const float tz = pq[i][j] + S;                      // toward zero: truncated exact sum
+                        const uint32_t uz = __float_as_uint(tz);
+                        const uint32_t mag = uz & 0x7FFFFFFFu;
+                        const bool of = mag >= rofb, small = mag < rufb;
+                        uint32_t r = uz & p.mask_a;
+                        r = of ? ((uz & 0x80000000u) | rofb) : r;
+                        r = small ? 0u : r;
+                        acc[i][j] = __uint_as_float(r);
+                        if (EVENTS) {
+                            const bool nz = pq[i][j] != -S;                 // exact sum is not zero
+                            wof[i][j] = (wof[i][j] << 1) | (of ? 1u : 0u);
+                            wuf[i][j] = (wuf[i][j] << 1) | ((uf1[i][j] || (small && nz)) ? 1u : 0u);
+                        }
+                    }
+            } else {
+                float tp[TM][TN], tn[TM][TN];
+                set_round_pinf();
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        asm volatile("v_add_f32 %0, %1, %2" : "=v"(tp[i][j]) : "v"(pq[i][j]), "v"(acc[i][j]));
+                set_round_ninf();
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        asm volatile("v_add_f32 %0, %1, %2" : "=v"(tn[i][j]) : "v"(pq[i][j]), "v"(acc[i][j]));
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const float S = acc[i][j];
+                        const uint32_t up = __float_as_uint(tp[i][j]), un = __float_as_uint(tn[i][j]);
+                        const uint32_t sticky = (up ^ un) & 1u;             // the two differ iff inexact
+                        const uint32_t uz = up < un ? up : un;              // smaller magnitude (same sign)
+                        uint32_t of; bool small;
+                        acc[i][j] = gen_acc_rne(uz, sticky, p, &of, &small);
+                        if (EVENTS) {
+                            const bool nz = pq[i][j] != -S;
+                            wof[i][j] = (wof[i][j] << 1) | of;
+                            wuf[i][j] = (wuf[i][j] << 1) | ((uf1[i][j] || (small && nz)) ? 1u : 0u);
+                        }
+                    }
+            }
+        }
+        if (EVENTS) {
+            // bits were shifted in first-k-highest; reverse, drop padded steps, store word t
+            const int valid = p.K - t * BK;
+            const uint32_t vmask = valid >= 32 ? 0xFFFFFFFFu : ((1u << valid) - 1u);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int m = m0 + ty * 4 + i;
+                if (m < p.M) {
+                    const int n = n0 + tx * 4;
+                    const int64_t off = ((int64_t)t * p.M + m) * p.N + n;
+                    uint32_t o[4], u[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) { o[j] = __builtin_bitreverse32(wof[i][j]) & vmask; u[j] = __builtin_bitreverse32(wuf[i][j]) & vmask; }
+                    if (p.c_vec && n + 3 < p.N) {
+                        if (p.of_mask) *reinterpret_cast<uint4*>(p.of_mask + off) = make_uint4(o[0], o[1], o[2], o[3]);
+                        if (p.uf_mask) *reinterpret_cast<uint4*>(p.uf_mask + off) = make_uint4(u[0], u[1], u[2], u[3]);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (n + j < p.N) {
+                                if (p.of_mask) p.of_mask[off + j] = o[j];
+                                if (p.uf_mask) p.uf_mask[off + j] = u[j];
+                            }
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { wof[i][j] = 0u; wuf[i][j] = 0u; }
+            }
+        }
+        if (more) {
+            float* Ad = smem + ((t + 1) & 1) * STAGE;
+            store_tile<BM, BK>(Ad, lut_a, tid, ra);
+            store_tile<BN, BK>(Ad + BK * BM, lut_b, tid, rb);
+        }
+        __syncthreads();
+    }
+    set_round_nearest();
+
+    if (p.C) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = m0 + ty * 4 + i;
+            if (m >= p.M) continue;
+            const int n = n0 + tx * 4;
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (acc[i][j] == 0.0f) ? 0.0f : acc[i][j];
+            float* dst = p.C + (int64_t)m * p.N + n;
+            if (p.c_vec && n + 3 < p.N) {
+                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (n + j < p.N) dst[j] = v[j];
+            }
+        }
+    }
+}
+
+__global__ void lba_fill_zero_kernel(float* C, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) C[i] = 0.0f;
+}
+
+// ---------------------------------------------------------------------------------------------
+// launchers
+// ---------------------------------------------------------------------------------------------
+template <int TM, int TN, int BK>
+static hipError_t launch_fast_tile(const Plan& pl, hipStream_t st) {
+    const dim3 grid(pl.grid_x, pl.grid_y), block(256);
+    const KParams& kp = pl.kp;
+#define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<TM, TN, BK, FastStep<PM, RND>>), grid, block, 0, st, kp)
+    if (pl.round == LBA_ROUND_FLOOR) {
+        switch (pl.prod_mode) {
+            case PM_IDENT: LBA_LAUNCH(PM_IDENT, LBA_ROUND_FLOOR); break;
+            case PM_FLUSH: LBA_LAUNCH(PM_FLUSH, LBA_ROUND_FLOOR); break;
+            default:       LBA_LAUNCH(PM_FLUSH_CLAMP, LBA_ROUND_FLOOR); break;
+        }
+    } else {
+        switch (pl.prod_mode) {
+            case PM_IDENT: LBA_LAUNCH(PM_IDENT, LBA_ROUND_RNE); break;
+            case PM_FLUSH: LBA_LAUNCH(PM_FLUSH, LBA_ROUND_RNE); break;
+            default:       LBA_LAUNCH(PM_FLUSH_CLAMP, LBA_ROUND_RNE); break;
+        }
+    }
+#undef LBA_LAUNCH
+    return hipGetLastError();
+}
+
+static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
+    if (pl.kernel == KERNEL_FAST) {
+        if (pl.tm == 8 && pl.tn == 8) return launch_fast_tile<8, 8, 16>(pl, st);
+        if (pl.tm == 8 && pl.tn == 4) return launch_fast_tile<8, 4, 32>(pl, st);
+        if (pl.tm == 4 && pl.tn == 8) return launch_fast_tile<4, 8, 32>(pl, st);
+        return launch_fast_tile<4, 4, 32>(pl, st);
+    }
+    const dim3 grid(pl.grid_x, pl.grid_y), block(256);
+    const KParams& kp = pl.kp;
+    if (pl.round == LBA_ROUND_FLOOR) {
+        if (pl.events) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, true>), grid, block, 0, st, kp);
+        else           hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, false>), grid, block, 0, st, kp);
+    } else {
+        if (pl.events) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, true>), grid, block, 0, st, kp);
+        else           hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, false>), grid, block, 0, st, kp);
+    }
+    return hipGetLastError();
+}
+
+static int gcd_align(const void* ptr, int64_t K) {
+    const uintptr_t a = (uintptr_t)ptr;
+    if ((a % 16) == 0 && (K % 16) == 0) return 16;
+    return 1;
+}
+
+static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
+               int64_t M, int64_t N, int64_t K, const lba_qfmt& qprod, const lba_qfmt& qacc,
+               int order, int events, void* stream) {
+    Plan pl;
+    int rc = make_plan(M, N, K, qprod, qacc, order, events, &pl);
+    if (rc != LBA_OK) return rc;
+    if (M == 0 || N == 0) return LBA_OK;
+    if (!events && !C) return LBA_ERR_NULL;
+    if (events && !of_mask && !uf_mask) return LBA_ERR_NULL;
+    hipStream_t st = (hipStream_t)stream;
+    if (K == 0) {                                              // empty chains: S_0 = 0; no mask words
+        if (C) {
+            const int64_t n = M * N;
+            hipLaunchKernelGGL(lba_fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, C, n);
+            if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
+        }
+        return LBA_OK;
+    }
+    if (!A || !B) return LBA_ERR_NULL;
+    KParams& kp = pl.kp;
+    kp.A = A; kp.B = B; kp.C = C; kp.of_mask = of_mask; kp.uf_mask = uf_mask;
+    const int la = gcd_align(A, K), lb = gcd_align(B, K);
+    kp.ld_align = la < lb ? la : lb;
+    const bool c_ok = !C || ((uintptr_t)C % 16) == 0;
+    const bool o_ok = !of_mask || ((uintptr_t)of_mask % 16) == 0;
+    const bool u_ok = !uf_mask || ((uintptr_t)uf_mask % 16) == 0;
+    kp.c_vec = ((N % 4) == 0 && c_ok && o_ok && u_ok) ? 1 : 0;
+    return launch_plan(pl, st) == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
+}
+
+}  // namespace lba
+
+// ---------------------------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------------------------
+extern "C" {
+
+int lba_gemm(const uint8_t* A, const uint8_t* B, float* C, int64_t M, int64_t N, int64_t K,
+             lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream) {
+    return lba::run(A, B, C, nullptr, nullptr, M, N, K, qprod, qacc, order, 0, hip_stream);
+}
+
+int lba_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
+                 int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
+                 void* hip_stream) {
+    return lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, order, 1, hip_stream);
+}
+
+size_t lba_mask_words(int64_t M, int64_t N, int64_t K) {
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    return (size_t)((K + 31) / 32) * (size_t)M * (size_t)N;
+}
+
+const char* lba_strerror(int code) {
+    switch (code) {
+        case LBA_OK: return "ok";
+        case LBA_ERR_NULL: return "a required pointer is NULL";
+        case LBA_ERR_SHAPE: return "invalid shape (negative, or M/K >= 2^31, or N > 2^21)";
+        case LBA_ERR_FORMAT: return "quantizer format outside the supported limits";
+        case LBA_ERR_UNSUPPORTED: return "unknown or unimplemented accumulation order";
+        case LBA_ERR_ALIGN: return "alignment (reserved)";
+        case LBA_ERR_LAUNCH: return "HIP kernel launch failed";
+        default: return "unknown status code";
+    }
+}
+
+int lba_plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
+                   int32_t with_masks, lba_plan_info* out) {
+    if (!out) return LBA_ERR_NULL;
+    lba::Plan pl;
+    int rc = lba::make_plan(M, N, K, qprod, qacc, order, with_masks, &pl);
+    if (rc != LBA_OK) return rc;
+    out->kernel = pl.kernel; out->prod_mode = pl.prod_mode; out->round = pl.round;
+    out->tile_m = 16 * pl.tm; out->tile_n = 16 * pl.tn; out->tile_k = pl.bk;
+    out->thread_m = pl.tm; out->thread_n = pl.tn;
+    out->grid_x = pl.grid_x; out->grid_y = pl.grid_y;
+    out->valu_per_mac_x100 = pl.valu_per_mac_x100;
+    return LBA_OK;
+}
+
+}  // extern "C"

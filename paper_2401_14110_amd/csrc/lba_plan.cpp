@@ -1,0 +1,175 @@
+// lba_plan.cpp -- argument validation and kernel selection for the LBA GEMM (host only, no HIP).
+//
+// The quantizer Q_{M,E,b} is the one of arXiv 2401.14110 Sec. 2.3; FMAq = Q_acc(Q_prod(x w) + s)
+// is Sec. 3.  Two kernels implement one FMAq step, both on an FP32 carrier:
+//
+// FAST  works in a scaled domain where the accumulator's R_UF sits at 2^-126, the smallest FP32
+//       normal, with FP32 denormals flushed: the hardware flush of the add IS Q_acc's underflow.
+//       Operands are decoded as a * 2^exp_a, b * 2^exp_b.
+//         PM_IDENT        t = fma(a', b', S)                 (Q_prod cannot change any product)
+//         PM_FLUSH        p = a' * b'  in the domain where Q_prod's R_UF is 2^-126, so the
+//                         multiply's flush is Q_prod's underflow; t = fma(p, kc, S) moves p into
+//                         the accumulator's domain exactly (kc is a power of two)
+//         PM_FLUSH_CLAMP  same, p clamped to +-R_OF of Q_prod in between
+//       then mantissa rounding by bit manipulation and a clamp to +-R_OF of Q_acc.
+//       Exactness: an E4M3 product has at most 8 significant bits, so a'*b' is exact; the fma
+//       rounds the exact sum once to 24 bits.
+//         floor:   the kernel runs with the FP32 rounding mode "toward zero"; truncating to 24
+//                  bits and then to M+1 bits equals truncating the exact sum to M+1 bits.  Always
+//                  exact, any M.
+//         nearest: the fma rounds to nearest-even at 24 bits, then the bit trick rounds to M+1
+//                  bits.  The double rounding is harmless iff the first rounding can never land
+//                  exactly on a midpoint of the M+1-bit grid.  The first rounding is inexact only
+//                  when the smaller operand's lowest bit is more than 23 places below the sum's
+//                  leading bit; the larger operand then decides the neighbourhood, and if it lies
+//                  ON the M+1-bit grid the sum stays within 2^(e-M-2) of a grid point provided
+//                  the smaller operand has at most 22-M significant bits.  Hence the conditions
+//                  checked in rne_fast_ok(): M <= 10; products on the accumulator grid (8 <= M+1);
+//                  a saturated product (M_prod+1 bits) on it too or impossible; and the flush
+//                  decision near 2^-126 unaffected (no sum can sit within 2^-150 below 2^-126).
+//       Everything else falls to GEN.
+//
+// GEN   works in the plain domain with every step explicit (product rounding, flush, clamp, add,
+//       rounding, flush, clamp).  For nearest-even it adds twice, once rounding toward +inf and
+//       once toward -inf: the smaller magnitude is the truncated sum and the two differ iff the
+//       sum was inexact, which gives the sticky bit for a correct single rounding at any M.
+//       It also produces the per-step event bits for lba_gemm_bwd.
+
+#include <cmath>
+#include <cstring>
+
+#include "lba_internal.h"
+
+namespace lba {
+
+static const int64_t kMaxDim = 2147483647LL;
+static const int64_t kMaxN = 1LL << 21;
+static const int kMaxProdExp = 17;     // 480 * 480 = 230400 < 2^18
+static const double kMaxProd = 230400.0;
+
+int validate_shapes(int64_t M, int64_t N, int64_t K) {
+    if (M < 0 || N < 0 || K < 0) return LBA_ERR_SHAPE;
+    if (M > kMaxDim || K > kMaxDim || N > kMaxN) return LBA_ERR_SHAPE;
+    return LBA_OK;
+}
+
+int validate_fmt(const lba_qfmt& q) {
+    if (q.man_bits < 1 || q.man_bits > 23) return LBA_ERR_FORMAT;
+    if (q.exp_bits < 2 || q.exp_bits > 7) return LBA_ERR_FORMAT;
+    if (q.round != LBA_ROUND_FLOOR && q.round != LBA_ROUND_RNE) return LBA_ERR_FORMAT;
+    if (q.bias > 126) return LBA_ERR_FORMAT;
+    if ((1 << q.exp_bits) - q.bias - 1 > 127) return LBA_ERR_FORMAT;
+    return LBA_OK;
+}
+
+static inline int top_exp(const lba_qfmt& q) { return (1 << q.exp_bits) - q.bias - 1; }
+
+static inline float rof_value(const lba_qfmt& q, int shift) {
+    return (float)std::ldexp(2.0 - std::ldexp(1.0, -q.man_bits), top_exp(q) + shift);
+}
+
+static void fill_quant(const lba_qfmt& q, int shift, uint32_t* mask, uint32_t* half, int32_t* sh,
+                       float* rof, float* ruf) {
+    *sh = 23 - q.man_bits;
+    *mask = (*sh == 0) ? 0xFFFFFFFFu : (0xFFFFFFFFu << *sh);
+    *half = (*sh == 0) ? 0u : ((1u << (*sh - 1)) - 1u);
+    *rof = rof_value(q, shift);
+    *ruf = (float)std::ldexp(1.0, -q.bias + shift);
+}
+
+// Can Q_prod's underflow / overflow ever fire on a product of two E4M3 values?
+static bool prod_flush_possible(const lba_qfmt& qp) { return qp.bias < 18; }          // R_UF > 2^-18
+static bool prod_clamp_possible(const lba_qfmt& qp) {
+    return std::ldexp(2.0 - std::ldexp(1.0, -qp.man_bits), top_exp(qp)) <= kMaxProd;
+}
+
+static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp) {
+    if (qa.man_bits > 10) return false;
+    if (qa.man_bits < 7) return false;                     // an 8-bit product would leave the grid
+    if (clamp && qp.man_bits > qa.man_bits) return false;  // a saturated product would
+    int bpe = prod_flush_possible(qp) ? qp.bias : 18;      // nonzero |p| >= 2^-bpe
+    if (bpe - qa.bias >= 24) return false;                 // a product could hide below 2^-150
+    return true;
+}
+
+static void pick_tile(int64_t M, int64_t N, int kernel, int* tm, int* tn, int* bk) {
+    if (kernel == KERNEL_GEN) { *tm = 4; *tn = 4; *bk = 32; return; }
+    // Candidates, largest first.  A candidate's cost is the number of workgroup slots it occupies
+    // (rounded up to whole machine fills) times the tile area: padding and partial fills both count.
+    static const int cand[4][2] = {{8, 8}, {8, 4}, {4, 8}, {4, 4}};
+    const double slots = 256.0 * 4.0;
+    double best = 0.0; int bi = 3;
+    for (int i = 0; i < 4; ++i) {
+        int64_t bm = 16 * cand[i][0], bn = 16 * cand[i][1];
+        double blocks = (double)((M + bm - 1) / bm) * (double)((N + bn - 1) / bn);
+        double fills = std::ceil(blocks / slots);
+        double eff = ((double)M * (double)N) / (fills * slots * (double)(bm * bn));
+        // mild preference for larger tiles (fewer LDS bytes per MAC)
+        double score = eff * (1.0 + 0.02 * (cand[i][0] * cand[i][1]) / 64.0);
+        if (score > best) { best = score; bi = i; }
+    }
+    *tm = cand[bi][0]; *tn = cand[bi][1];
+    *bk = (*tm * *tn >= 64) ? 16 : 32;
+}
+
+int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfmt& qa,
+              int order, int events, Plan* out) {
+    int rc = validate_shapes(M, N, K);
+    if (rc != LBA_OK) return rc;
+    if ((rc = validate_fmt(qp)) != LBA_OK) return rc;
+    if ((rc = validate_fmt(qa)) != LBA_OK) return rc;
+    if (order != LBA_ORDER_SEQ && order != LBA_ORDER_CHUNK16) return LBA_ERR_UNSUPPORTED;
+    if (order == LBA_ORDER_CHUNK16) return LBA_ERR_UNSUPPORTED;
+
+    Plan p;
+    std::memset(&p, 0, sizeof(p));
+    p.events = events ? 1 : 0;
+    p.round = qa.round;
+    KParams& kp = p.kp;
+    kp.M = (int32_t)M; kp.N = (int32_t)N; kp.K = (int32_t)K;
+
+    const bool flush = prod_flush_possible(qp);
+    const bool clamp = prod_clamp_possible(qp);
+    const bool prod_round = qp.man_bits < 7;
+
+    // effective biases: below -20 every product / every sum underflows anyway
+    const int bpe = qp.bias < -20 ? -20 : qp.bias;
+    const int bae = qa.bias < -20 ? -20 : qa.bias;
+
+    bool fast = !events && !prod_round;
+    if (fast && qa.round == LBA_ROUND_RNE && !rne_fast_ok(qp, qa, clamp)) fast = false;
+    if (fast && (flush || clamp) && std::abs(bae - bpe) > 120) fast = false;   // kc must be an FP32 normal
+
+    if (fast) {
+        p.kernel = KERNEL_FAST;
+        p.prod_mode = clamp ? PM_FLUSH_CLAMP : (flush ? PM_FLUSH : PM_IDENT);
+        const int c_a = bae - 126;                         // accumulator domain: R_UF -> 2^-126
+        const int c_p = (p.prod_mode == PM_IDENT) ? c_a : (bpe - 126);
+        kp.exp_a = c_p / 2;                                // split the product's scale over a and b
+        kp.exp_b = c_p - kp.exp_a;
+        kp.kc = (float)std::ldexp(1.0, c_a - c_p);
+        kp.out_exp = -c_a;
+        fill_quant(qa, c_a, &kp.mask_a, &kp.half_a, &kp.sh_a, &kp.rof_a, &kp.ruf_a);
+        fill_quant(qp, c_p, &kp.mask_p, &kp.half_p, &kp.sh_p, &kp.rof_p, &kp.ruf_p);
+        int ops = (p.prod_mode == PM_IDENT) ? 3 : (p.prod_mode == PM_FLUSH ? 4 : 5);
+        if (qa.round == LBA_ROUND_RNE) ops += 2;
+        p.valu_per_mac_x100 = ops * 100;
+    } else {
+        p.kernel = KERNEL_GEN;
+        p.prod_mode = PM_FLUSH_CLAMP;
+        kp.exp_a = 0; kp.exp_b = 0; kp.out_exp = 0; kp.kc = 1.0f;
+        fill_quant(qa, 0, &kp.mask_a, &kp.half_a, &kp.sh_a, &kp.rof_a, &kp.ruf_a);
+        fill_quant(qp, 0, &kp.mask_p, &kp.half_p, &kp.sh_p, &kp.rof_p, &kp.ruf_p);
+        kp.prod_round = prod_round ? 1 : 0;
+        kp.prod_rne = (qp.round == LBA_ROUND_RNE) ? 1 : 0;
+        p.valu_per_mac_x100 = 0;                           // filled by the launcher's table
+    }
+    pick_tile(M, N, p.kernel, &p.tm, &p.tn, &p.bk);
+    const int64_t bm = 16 * p.tm, bn = 16 * p.tn;
+    p.grid_x = (int)((M + bm - 1) / bm);
+    p.grid_y = (int)((N + bn - 1) / bn);
+    *out = p;
+    return LBA_OK;
+}
+
+}  // namespace lba

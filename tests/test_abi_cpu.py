@@ -1,0 +1,113 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol the
+header declares, validates arguments before touching the device, and plans kernels sensibly."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2401_14110_amd import binding as lb
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+GOOD_P = (5, 7, 15, 0)
+GOOD_A = (4, 7, 7, 0)
+
+
+def declared_functions():
+    names = set()
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(lba_\w+)\s*\(", text))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    L = lb.lib()
+    names = declared_functions()
+    assert {"lba_gemm", "lba_gemm_bwd", "lba_mask_words", "lba_strerror", "lba_plan_query"} <= names
+    for n in names:
+        assert hasattr(L, n), n
+        # the Python binding carries the same names
+        assert hasattr(lb, n), n
+
+
+def test_status_texts():
+    for code in range(0, 7):
+        assert lb.strerror(code)
+    assert lb.strerror(0) == "ok"
+    assert "unknown" in lb.strerror(99)
+
+
+def test_mask_words():
+    assert lb.lba_mask_words(4, 5, 1) == 20
+    assert lb.lba_mask_words(4, 5, 32) == 20
+    assert lb.lba_mask_words(4, 5, 33) == 40
+    assert lb.lba_mask_words(4096, 4096, 4096) == 128 * 4096 * 4096
+    assert lb.lba_mask_words(0, 5, 33) == 0 and lb.lba_mask_words(4, 5, 0) == 0 and lb.lba_mask_words(-1, 5, 3) == 0
+
+
+BAD_FMTS = [(4, 0, 7, 0), (4, 24, 7, 0), (1, 7, 0, 0), (8, 7, 7, 0), (4, 7, 127, 0), (4, 7, 7, 2), (4, 7, 7, -1),
+            (7, 7, -1, 0), (4, 7, -113, 0)]
+
+
+@pytest.mark.parametrize("bad", BAD_FMTS)
+def test_format_limits_are_rejected_before_any_device_work(bad):
+    # bogus non-null addresses: a call that got as far as the device would fault, so a clean
+    # status proves validation comes first
+    A = B = C = ctypes.c_void_p(0x1000)
+    assert lb.lba_gemm(A, B, C, 8, 8, 8, bad, GOOD_A) == lb.ERR_FORMAT
+    assert lb.lba_gemm(A, B, C, 8, 8, 8, GOOD_P, bad) == lb.ERR_FORMAT
+    assert lb.lba_gemm_bwd(A, B, C, C, C, 8, 8, 8, bad, GOOD_A) == lb.ERR_FORMAT
+    with pytest.raises(lb.LbaError):
+        lb.lba_plan_query(8, 8, 8, bad, GOOD_A)
+
+
+def test_edge_formats_are_accepted():
+    for ok in [(4, 7, 126, 0), (7, 23, 0, 1), (2, 1, -124, 0), (7, 7, 64, 1), (4, 7, -112, 0)]:
+        lb.lba_plan_query(8, 8, 8, ok, ok)
+
+
+def test_shape_order_and_null_errors():
+    A = B = C = ctypes.c_void_p(0x1000)
+    assert lb.lba_gemm(A, B, C, -1, 8, 8, GOOD_P, GOOD_A) == lb.ERR_SHAPE
+    assert lb.lba_gemm(A, B, C, 8, -1, 8, GOOD_P, GOOD_A) == lb.ERR_SHAPE
+    assert lb.lba_gemm(A, B, C, 8, 8, -1, GOOD_P, GOOD_A) == lb.ERR_SHAPE
+    assert lb.lba_gemm(A, B, C, 1 << 31, 8, 8, GOOD_P, GOOD_A) == lb.ERR_SHAPE
+    assert lb.lba_gemm(A, B, C, 8, (1 << 21) + 1, 8, GOOD_P, GOOD_A) == lb.ERR_SHAPE
+    assert lb.lba_gemm(A, B, C, 8, 8, 8, GOOD_P, GOOD_A, order=5) == lb.ERR_UNSUPPORTED
+    assert lb.lba_gemm(A, B, None, 8, 8, 8, GOOD_P, GOOD_A) == lb.ERR_NULL
+    assert lb.lba_gemm(None, B, C, 8, 8, 8, GOOD_P, GOOD_A) == lb.ERR_NULL
+    assert lb.lba_gemm(A, None, C, 8, 8, 8, GOOD_P, GOOD_A) == lb.ERR_NULL
+    assert lb.lba_gemm_bwd(A, B, C, None, None, 8, 8, 8, GOOD_P, GOOD_A) == lb.ERR_NULL
+    # empty outputs: nothing to do, pointers are not looked at
+    assert lb.lba_gemm(None, None, None, 0, 8, 8, GOOD_P, GOOD_A) == lb.OK
+    assert lb.lba_gemm(None, None, None, 8, 0, 8, GOOD_P, GOOD_A) == lb.OK
+
+
+def test_plan_picks_the_scaled_kernel_for_the_paper_formats():
+    # 12-bit accumulator M7E4 with an M7E5 product format (Sec. 3.1), floor and nearest-even
+    for rnd in (0, 1):
+        for bp, ba in ((15, 7), (-1, -9), (12, 10), (9, 7)):
+            p = lb.lba_plan_query(100352, 64, 576, (5, 7, bp, rnd), (4, 7, ba, rnd))
+            assert p["kernel"] == 0 and p["round"] == rnd
+            assert p["tile_m"] * p["grid_x"] >= 100352 and p["tile_n"] * p["grid_y"] >= 64
+    # a product format that cannot alter any E4M3 product: fused multiply-add path
+    assert lb.lba_plan_query(64, 64, 64, (6, 7, 20, 0), (4, 7, 7, 0))["prod_mode"] == 0
+    assert lb.lba_plan_query(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["prod_mode"] == 2   # can saturate
+    assert lb.lba_plan_query(64, 64, 64, (5, 7, -1, 0), (4, 7, -9, 0))["prod_mode"] == 1  # can only flush
+
+
+def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
+    q = lb.lba_plan_query
+    assert q(64, 64, 64, (5, 7, 15, 1), (4, 3, 7, 1))["kernel"] == 1      # nearest-even, M_acc < 7
+    assert q(64, 64, 64, (5, 7, 15, 1), (4, 11, 7, 1))["kernel"] == 1     # nearest-even, M_acc > 10
+    assert q(64, 64, 64, (5, 9, 15, 1), (4, 8, 7, 1))["kernel"] == 1      # saturated product off the grid
+    assert q(64, 64, 64, (5, 7, 40, 1), (4, 7, -9, 1))["kernel"] == 1     # products far below R_UF of Q_acc
+    assert q(64, 64, 64, (5, 4, 15, 0), (4, 7, 7, 0))["kernel"] == 1      # product mantissa is rounded
+    assert q(64, 64, 64, (5, 7, 15, 0), (4, 3, 7, 0))["kernel"] == 0      # floor is exact at any M
+    assert q(64, 64, 64, (5, 7, 15, 0), (7, 23, 64, 0))["kernel"] == 0
+    assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 1
+    with pytest.raises(lb.LbaError):
+        q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=1)

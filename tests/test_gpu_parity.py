@@ -1,0 +1,221 @@
+"""GPU parity: the HIP library (called through the C ABI binding) against the CPU oracle, element
+by element and bit for bit, on the same seeded inputs.  Run with -m gpu on an MI355X."""
+import itertools
+import os
+import random
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2401_14110_amd import binding as lb
+from paper_2401_14110_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def fm(ref, f):
+    return ref.QFmt(*f)
+
+
+def rand_codes(rng, shape, lo_e=0, hi_e=15, nan_free=True):
+    e = rng.integers(lo_e, hi_e + 1, shape)
+    m = rng.integers(0, 8, shape)
+    s = rng.integers(0, 2, shape)
+    c = (s << 7) | (e << 3) | m
+    if nan_free:
+        c = np.where((c & 0x7F) == 0x7F, c & 0xFE, c)
+    return c.astype(np.uint8)
+
+
+def bits(x):
+    return np.ascontiguousarray(x).view(np.uint32)
+
+
+def run_gpu(A, B, qp, qa):
+    C = lb.gemm(torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV), qp, qa)
+    torch.cuda.synchronize()
+    return C.cpu().numpy()
+
+
+def check(ref, A, B, qp, qa, what=""):
+    got = run_gpu(A, B, qp, qa)
+    want = ref.gemm(A, B, fm(ref, qp), fm(ref, qa))
+    bad = bits(got) != bits(want)
+    if bad.any():
+        i, j = np.argwhere(bad)[0]
+        raise AssertionError("%s qp=%s qa=%s shape=%s: %d mismatches, first at [%d,%d]: gpu %r oracle %r (plan %s)"
+                             % (what, qp, qa, (A.shape, B.shape), int(bad.sum()), i, j, got[i, j], want[i, j],
+                                lb.lba_plan_query(A.shape[0], B.shape[0], A.shape[1], qp, qa)))
+    return got
+
+
+# formats: (qprod, qacc) as (E, M, b); rounding appended per test
+FMT_PAPER = [((5, 7, 15), (4, 7, 7)),        # default biases in real units
+             ((5, 7, -1), (4, 7, -9)),       # the same moved into code units of scaled operands
+             ((4, 7, 12), (4, 7, 10)),       # b_acc, b_prod = 10, 12 (Sec. 3.1)
+             ((4, 7, 9), (4, 7, 7)),         # 7, 9 (Table 4)
+             ((6, 7, 20), (4, 7, 7))]        # Q_prod cannot change a product: fused path
+FMT_SWEEP = [((5, 7, 15), (E, M, (1 << (E - 1)) - 1)) for M in (3, 5, 8, 10) for E in (4, 5, 6)]
+FMT_ODD = [((5, 4, 15), (4, 7, 7)),          # product mantissa is rounded
+           ((3, 4, 6), (3, 4, 6)),           # 8-bit accumulator M4E3 (Sec. 4), b = 6 (App. C.4)
+           ((3, 4, 5), (3, 4, 5)),           # b = 5 (App. C.3)
+           ((5, 9, 15), (4, 8, 7)),          # wider product mantissa than accumulator
+           ((5, 7, 40), (4, 7, -9)),         # products far below the accumulator's range
+           ((7, 23, 64), (7, 23, 64)),       # widest formats
+           ((5, 7, 15), (4, 22, 7)), ((5, 7, 15), (4, 23, 7)), ((5, 7, 15), (5, 11, 15)),
+           ((2, 1, 0), (2, 1, 0)), ((7, 7, 126), (7, 7, 126)), ((4, 7, -112), (4, 7, -112)),
+           ((5, 7, -30), (4, 7, 7)), ((5, 7, 15), (4, 7, -30))]
+
+
+def test_k1_every_code_pair(ref):
+    # C[a, b] = Q_acc(Q_prod(a * b)) for all 256 x 256 codes (NaN codes included: read as +-480)
+    codes = np.arange(256, dtype=np.uint8).reshape(256, 1)
+    for (qp, qa), rnd in itertools.product(FMT_PAPER + FMT_SWEEP[::3] + FMT_ODD, (0, 1)):
+        check(ref, codes, codes, qp + (rnd,), qa + (rnd,), "K=1")
+
+
+def test_hand_worked_chain_and_exact_sum(ref):
+    tab = [l.split("#")[0].split() for l in open(os.path.join(GOLD, "chain_p1b.txt"))]
+    tab = [r for r in tab if r]
+    a = np.array([[int(r[1], 16) for r in tab]], dtype=np.uint8)
+    b = np.array([[int(r[2], 16) for r in tab]], dtype=np.uint8)
+    for rnd, col in ((0, 3), (1, 6)):
+        for k in range(1, 5):
+            got = run_gpu(a[:, :k], b[:, :k], (5, 7, 16, rnd), (4, 7, 7, rnd))
+            assert got[0, 0] == float(tab[k - 1][col])
+    # 256 - 2^-18: floor must give 255 (sum exact before rounding), nearest-even 256
+    a = np.array([[0x58, 0x81]], dtype=np.uint8)
+    b = np.array([[0x58, 0x01]], dtype=np.uint8)
+    assert run_gpu(a, b, (5, 7, 18, 0), (4, 7, 7, 0))[0, 0] == 255.0
+    assert run_gpu(a, b, (5, 7, 18, 1), (4, 7, 7, 1))[0, 0] == 256.0
+
+
+def test_config1_single_gemm(ref):
+    # M = N = 64, K = 256, N(0,1) operands scaled to max|x| = 448, seed 0; Q_prod 1-5-7, Q_acc 1-4-7
+    A = inputs.normal(0, 0, 64 * 256)
+    B = inputs.normal(0, 1, 64 * 256)
+    Ac, ta = inputs.quantize_tensor(A, "exact448")
+    Bc, tb = inputs.quantize_tensor(B, "exact448")
+    Ac = Ac.reshape(64, 256).numpy(); Bc = Bc.reshape(64, 256).numpy()
+    for rnd in (1, 0):
+        # biases as written (code units: saturates nearly everywhere) and folded to real units
+        check(ref, Ac, Bc, (5, 7, 15, rnd), (4, 7, 7, rnd), "config1 literal")
+        qp, qa, _ = inputs.folded_formats(ta, tb, rnd=rnd)
+        got = check(ref, Ac, Bc, qp, qa, "config1 folded")
+        assert np.count_nonzero(got) > 3000
+
+
+SHAPES = [(1, 1, 1), (3, 5, 7), (17, 9, 31), (65, 67, 33), (130, 70, 147), (257, 129, 100), (64, 1000, 64),
+          (200, 64, 576), (128, 128, 16), (129, 257, 48), (64, 64, 1025)]
+
+
+@pytest.mark.parametrize("rnd", [0, 1])
+def test_ragged_shapes_paper_formats(ref, rnd):
+    rng = np.random.default_rng(20 + rnd)
+    for (M, N, K) in SHAPES:
+        A = rand_codes(rng, (M, K), 3, 12)
+        B = rand_codes(rng, (N, K), 3, 12)
+        for qp, qa in FMT_PAPER:
+            check(ref, A, B, qp + (rnd,), qa + (rnd,), "ragged")
+
+
+@pytest.mark.parametrize("rnd", [0, 1])
+def test_accumulator_width_sweep_and_odd_formats(ref, rnd):
+    rng = np.random.default_rng(30 + rnd)
+    A = rand_codes(rng, (150, 200)); B = rand_codes(rng, (70, 200))
+    A2 = rand_codes(rng, (70, 96), 5, 10); B2 = rand_codes(rng, (66, 96), 5, 10)
+    for qp, qa in FMT_SWEEP + FMT_ODD:
+        check(ref, A, B, qp + (rnd,), qa + (rnd,), "sweep full-range operands")
+        check(ref, A2, B2, qp + (rnd,), qa + (rnd,), "sweep mid-range operands")
+
+
+def test_synthetic_workload_distributions(ref):
+    # ReLU activations x Kaiming weights (conv as im2col) and N(0,1) x N(0,0.02) (BERT linear),
+    # power-of-two per-tensor scaling, biases folded; sizes span several tiles with ragged tails
+    for kind_a, std_b, (M, N, K), seed in (("relu", None, (300, 64, 576), 2), ("relu", None, (200, 130, 147), 3),
+                                           ("normal", 0.02, (260, 200, 768), 4)):
+        std = (2.0 / K) ** 0.5 if std_b is None else std_b
+        A, ta = inputs.make_operand(kind_a, M, K, seed, 0)
+        B, tb = inputs.make_operand("normal", N, K, seed, 1, std=std)
+        for rnd in (0, 1):
+            qp, qa, _ = inputs.folded_formats(ta, tb, rnd=rnd)
+            got = check(ref, A.numpy(), B.numpy(), qp, qa, "workload")
+            assert np.count_nonzero(got) > got.size // 2
+
+
+TINY = [0x00, 0x80, 0x01, 0x81, 0x08, 0x38, 0xB8, 0x39, 0x3F, 0x47, 0x58, 0xDA, 0x7E, 0xFE, 0x77, 0x0F]
+
+
+def test_brute_force_short_sequences(ref):
+    # every pair of the 16-code subset at K = 2 against every other pair (65536 chains), and random
+    # K = 3, 4 sequences: all outputs of the cross product are compared
+    pairs = np.array(list(itertools.product(TINY, TINY)), dtype=np.uint8)          # [256, 2]
+    rnd_gen = random.Random(5)
+    seq3 = np.array([[rnd_gen.choice(TINY) for _ in range(3)] for _ in range(300)], dtype=np.uint8)
+    seq4 = np.array([[rnd_gen.choice(TINY) for _ in range(4)] for _ in range(300)], dtype=np.uint8)
+    for (qp, qa), rnd in itertools.product([FMT_PAPER[0], FMT_PAPER[1], FMT_ODD[1], FMT_ODD[3], FMT_SWEEP[0]], (0, 1)):
+        for S in (pairs, seq3, seq4):
+            check(ref, S, S, qp + (rnd,), qa + (rnd,), "brute")
+
+
+def test_unaligned_pointers_and_views(ref):
+    rng = np.random.default_rng(40)
+    for K in (16, 64, 147, 50):
+        base_a = torch.from_numpy(rand_codes(rng, (40 * K + 13,), 4, 11)).to(DEV)
+        base_b = torch.from_numpy(rand_codes(rng, (33 * K + 7,), 4, 11)).to(DEV)
+        for oa, ob in ((0, 0), (1, 3), (5, 2), (13, 7)):
+            A = base_a[oa:oa + 40 * K].view(40, K)
+            B = base_b[ob:ob + 33 * K].view(33, K)
+            Cbuf = torch.empty(40 * 33 + 3, dtype=torch.float32, device=DEV)
+            C = Cbuf[1:1 + 40 * 33].view(40, 33)               # 4-byte aligned only
+            lb.gemm(A, B, (5, 7, 15, 0), (4, 7, 7, 0), out=C)
+            torch.cuda.synchronize()
+            want = ref.gemm(A.cpu().numpy(), B.cpu().numpy(), ref.QFmt(5, 7, 15, 0), ref.QFmt(4, 7, 7, 0))
+            assert np.array_equal(bits(C.cpu().numpy()), bits(want)), (K, oa, ob)
+
+
+def test_degenerate_sizes(ref):
+    A = torch.zeros((5, 0), dtype=torch.uint8, device=DEV)
+    B = torch.zeros((7, 0), dtype=torch.uint8, device=DEV)
+    C = torch.full((5, 7), 3.0, device=DEV)
+    lb.gemm(A, B, (5, 7, 15, 0), (4, 7, 7, 0), out=C)
+    torch.cuda.synchronize()
+    assert (C.cpu().numpy().view(np.uint32) == 0).all()                 # K = 0: +0 everywhere
+    E = torch.zeros((0, 9), dtype=torch.uint8, device=DEV)
+    assert lb.gemm(E, torch.zeros((4, 9), dtype=torch.uint8, device=DEV), (5, 7, 15, 0), (4, 7, 7, 0)).shape == (0, 4)
+    # all-zero operands, negative zeros
+    Z = np.full((70, 40), 0x80, dtype=np.uint8)
+    got = check(ref, Z, Z, (5, 7, 15, 0), (4, 7, 7, 0), "zeros")
+    assert (bits(got) == 0).all()
+    # maximum-magnitude operands: saturates at once
+    X = np.full((66, 40), 0x7E, dtype=np.uint8)
+    got = check(ref, X, X, (5, 7, 15, 1), (4, 7, 7, 1), "max")
+    assert (got == 510.0).all()
+
+
+def test_event_planes_and_c_of_the_recompute_call(ref):
+    rng = np.random.default_rng(50)
+    cases = [((70, 66, 100), 0, 15), ((33, 130, 64), 3, 12), ((5, 3, 31), 0, 15), ((64, 64, 33), 5, 10)]
+    for (M, N, K), lo, hi in cases:
+        A = rand_codes(rng, (M, K), lo, hi); B = rand_codes(rng, (N, K), lo, hi)
+        for (qp, qa), rnd in itertools.product([FMT_PAPER[0], FMT_PAPER[1], FMT_ODD[1], FMT_ODD[0], FMT_SWEEP[1]], (0, 1)):
+            qpf, qaf = qp + (rnd,), qa + (rnd,)
+            C, of, uf = lb.gemm_bwd(torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV), qpf, qaf)
+            torch.cuda.synchronize()
+            wc, wof, wuf = ref.gemm_bwd(A, B, fm(ref, qpf), fm(ref, qaf))
+            assert np.array_equal(bits(C.cpu().numpy()), bits(wc)), (M, N, K, qpf, qaf)
+            assert np.array_equal(of.cpu().numpy().view(np.uint32), wof), (M, N, K, qpf, qaf, "OF")
+            assert np.array_equal(uf.cpu().numpy().view(np.uint32), wuf), (M, N, K, qpf, qaf, "UF")
+            fwd = run_gpu(A, B, qpf, qaf)                                  # same C as the forward call
+            assert np.array_equal(bits(fwd), bits(wc))
+    # planes alone, one plane alone
+    A = torch.from_numpy(rand_codes(rng, (20, 40))).to(DEV); B = torch.from_numpy(rand_codes(rng, (24, 40))).to(DEV)
+    C, of, uf = lb.gemm_bwd(A, B, (5, 7, 15, 0), (4, 7, 7, 0), want_c=False)
+    torch.cuda.synchronize()
+    _, wof, wuf = ref.gemm_bwd(A.cpu().numpy(), B.cpu().numpy(), ref.QFmt(5, 7, 15, 0), ref.QFmt(4, 7, 7, 0))
+    assert C is None and np.array_equal(of.cpu().numpy().view(np.uint32), wof)
+    assert np.array_equal(uf.cpu().numpy().view(np.uint32), wuf)
