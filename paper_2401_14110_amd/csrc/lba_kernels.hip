@@ -58,27 +58,73 @@ __device__ __forceinline__ uint32_t rne_bits(uint32_t u, uint32_t half, int sh, 
     return (u + half + ((u >> sh) & 1u)) & mask;
 }
 
-template <int PM, int RND>
-struct FastStep {
-    static constexpr bool kEvents = false;
-    static constexpr bool kRtz = (RND == LBA_ROUND_FLOOR);
-    __device__ static __forceinline__ void begin() { if (kRtz) set_round_zero(); }
-    __device__ static __forceinline__ void end() { if (kRtz) set_round_nearest(); }
-    __device__ static __forceinline__ float run(float S, float a, float b, const KParams& p) {
-        float t;
-        if (PM == PM_IDENT) {
-            t = __builtin_fmaf(a, b, S);
-        } else {
-            float q = a * b;                                   // exact; flushed below Q_prod's R_UF
-            if (PM == PM_FLUSH_CLAMP) q = med3(q, -p.rof_p, p.rof_p);
-            t = __builtin_fmaf(q, p.kc, S);                    // one rounding of the exact sum
-        }
-        uint32_t u = __float_as_uint(t);
-        if (RND == LBA_ROUND_RNE) u = rne_bits(u, p.half_a, p.sh_a, p.mask_a);
-        else u &= p.mask_a;
-        return med3(__uint_as_float(u), -p.rof_a, p.rof_a);
-    }
+// Per-wave constants of the fast kernel, forced into vector registers: on gfx950 the simple
+// FP32 / bitwise VALU ops issue at twice the rate when all their operands are VGPRs.
+struct FastConst {
+    float kc, rof, rofp;
+    uint32_t mask, half;
+    int sh;
 };
+
+// One k-step for a GROUP of NCH independent chains, written phase by phase (all products, then
+// all adds, then all roundings) so that consecutive instructions never depend on each other.
+// CLAMP = false is used for k-tiles in which no chain can reach R_OF (see lba_fast_kernel).
+template <int PM, int RND, bool CLAMP, int I0, int NI, int TM, int NJ>
+__device__ __forceinline__ void fast_group(float (&accf)[TM][NJ], const float (&af)[TM], const float (&b)[NJ],
+                                           const FastConst& c) {
+    float (*acc)[NJ] = &accf[I0];
+    const float* a = &af[I0];
+    if (PM == PM_IDENT) {
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
+    } else {
+        float q[NI][NJ];
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) q[i][j] = a[i] * b[j];        // exact; flushed below Q_prod's R_UF
+        __builtin_amdgcn_sched_barrier(0);
+        if (PM == PM_FLUSH_CLAMP) {
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) q[i][j] = med3(q[i][j], -c.rofp, c.rofp);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_fmaf(q[i][j], c.kc, acc[i][j]);   // one rounding of the exact sum
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    if (RND == LBA_ROUND_RNE) {
+        uint32_t l[NI][NJ];
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) l[i][j] = (__float_as_uint(acc[i][j]) >> c.sh) & 1u;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) acc[i][j] = __uint_as_float(__float_as_uint(acc[i][j]) + c.half + l[i][j]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[i][j] = __uint_as_float(__float_as_uint(acc[i][j]) & c.mask);
+    if (CLAMP) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) acc[i][j] = med3(acc[i][j], -c.rof, c.rof);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
 
 // General step: plain domain, every sub-step explicit.  EVENTS adds the two event bits.
 struct GenOut { float S; uint32_t of; uint32_t uf; };
@@ -195,11 +241,49 @@ __device__ __forceinline__ void store_tile(float* __restrict__ dst /* [BK][ROWS]
     }
 }
 
-template <int TM, int TN, int BK, class Step>
+// Reads the TM + TN operand values of one k from an LDS stage.
+template <int TM, int TN, int BM, int BN>
+__device__ __forceinline__ void read_operands(const float* As, const float* Bs, int k, int tx, int ty,
+                                              float (&a)[TM], float (&b)[TN]) {
+#pragma unroll
+    for (int g = 0; g < TM / 4; ++g) {
+        const float4 v = *reinterpret_cast<const float4*>(As + k * BM + g * (BM / 2) + ty * 4);
+        a[4 * g + 0] = v.x; a[4 * g + 1] = v.y; a[4 * g + 2] = v.z; a[4 * g + 3] = v.w;
+    }
+#pragma unroll
+    for (int g = 0; g < TN / 4; ++g) {
+        const float4 v = *reinterpret_cast<const float4*>(Bs + k * BN + g * (BN / 2) + tx * 4);
+        b[4 * g + 0] = v.x; b[4 * g + 1] = v.y; b[4 * g + 2] = v.z; b[4 * g + 3] = v.w;
+    }
+}
+
+// All chains of the lane advance by one k: groups of 4 rows x TN columns.
+template <int PM, int RND, bool CLAMP, int TM, int TN>
+__device__ __forceinline__ void fast_kstep(float (&acc)[TM][TN], const float (&a)[TM], const float (&b)[TN],
+                                           const FastConst& c) {
+    fast_group<PM, RND, CLAMP, 0, 4, TM, TN>(acc, a, b, c);
+    if (TM > 4) fast_group<PM, RND, CLAMP, (TM > 4 ? 4 : 0), 4, TM, TN>(acc, a, b, c);
+}
+
+// One k-tile from LDS, operands double-buffered in registers one k ahead.
+template <int PM, int RND, bool CLAMP, int TM, int TN, int BK, int BM, int BN>
+__device__ __forceinline__ void fast_tile(float (&acc)[TM][TN], const float* As, const float* Bs, int tx, int ty,
+                                          const FastConst& c) {
+    float a0[TM], b0[TN], a1[TM], b1[TN];
+    read_operands<TM, TN, BM, BN>(As, Bs, 0, tx, ty, a0, b0);
+#pragma unroll 1
+    for (int k = 0; k < BK; k += 2) {
+        read_operands<TM, TN, BM, BN>(As, Bs, k + 1, tx, ty, a1, b1);
+        fast_kstep<PM, RND, CLAMP, TM, TN>(acc, a0, b0, c);
+        if (k + 2 < BK) read_operands<TM, TN, BM, BN>(As, Bs, k + 2, tx, ty, a0, b0);
+        fast_kstep<PM, RND, CLAMP, TM, TN>(acc, a1, b1, c);
+    }
+}
+
+template <int TM, int TN, int BK, int PM, int RND>
 __global__ void __launch_bounds__(256) lba_fast_kernel(const KParams p) {
     constexpr int BM = 16 * TM, BN = 16 * TN;
     constexpr int STAGE = BK * (BM + BN);
-    constexpr int kUnroll = (TM * TN >= 64) ? 2 : 8;
     __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
     __shared__ float lut_a[256];
     __shared__ float lut_b[256];
@@ -211,7 +295,12 @@ __global__ void __launch_bounds__(256) lba_fast_kernel(const KParams p) {
     lut_a[tid] = decode_entry(tid, p.exp_a);
     lut_b[tid] = decode_entry(tid, p.exp_b);
     set_flush_f32();
-    Step::begin();
+    if (RND == LBA_ROUND_FLOOR) set_round_zero();
+
+    FastConst c;
+    c.kc = p.kc; c.rof = p.rof_a; c.rofp = p.rof_p; c.mask = p.mask_a; c.half = p.half_a; c.sh = p.sh_a;
+    float thresh = p.fast_thresh;
+    asm volatile("" : "+v"(c.kc), "+v"(c.rof), "+v"(c.rofp), "+v"(c.mask), "+v"(c.half), "+v"(thresh));
 
     float acc[TM][TN];
 #pragma unroll
@@ -237,24 +326,16 @@ __global__ void __launch_bounds__(256) lba_fast_kernel(const KParams p) {
             fetch_tile<BM, BK>(p.A, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
             fetch_tile<BN, BK>(p.B, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tid, rb);
         }
-#pragma unroll kUnroll
-        for (int k = 0; k < BK; ++k) {
-            float a[TM], b[TN];
+        // If every chain of the wave starts this tile below fast_thresh = R_OF - BK * max|p| (scaled
+        // down further for nearest-even), no sum inside the tile can reach R_OF: the clamp is a no-op
+        // and is skipped.  The test is per wave, so the branch is uniform.
+        float mx = 0.0f;
 #pragma unroll
-            for (int g = 0; g < TM / 4; ++g) {
-                const float4 v = *reinterpret_cast<const float4*>(As + k * BM + g * (BM / 2) + ty * 4);
-                a[4 * g + 0] = v.x; a[4 * g + 1] = v.y; a[4 * g + 2] = v.z; a[4 * g + 3] = v.w;
-            }
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int g = 0; g < TN / 4; ++g) {
-                const float4 v = *reinterpret_cast<const float4*>(Bs + k * BN + g * (BN / 2) + tx * 4);
-                b[4 * g + 0] = v.x; b[4 * g + 1] = v.y; b[4 * g + 2] = v.z; b[4 * g + 3] = v.w;
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) acc[i][j] = Step::run(acc[i][j], a[i], b[j], p);
-        }
+            for (int j = 0; j < TN; ++j) mx = __builtin_fmaxf(mx, __builtin_fabsf(acc[i][j]));
+        if (__all(mx < thresh)) fast_tile<PM, RND, false, TM, TN, BK, BM, BN>(acc, As, Bs, tx, ty, c);
+        else                    fast_tile<PM, RND, true, TM, TN, BK, BM, BN>(acc, As, Bs, tx, ty, c);
         if (more) {
             float* Ad = smem + ((t + 1) & 1) * STAGE;
             store_tile<BM, BK>(Ad, lut_a, tid, ra);
@@ -262,7 +343,7 @@ __global__ void __launch_bounds__(256) lba_fast_kernel(const KParams p) {
         }
         __syncthreads();
     }
-    Step::end();
+    if (RND == LBA_ROUND_FLOOR) set_round_nearest();
 
     // C = S * 2^out_exp, zero written as +0
 #pragma unroll
@@ -368,7 +449,17 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
                         }
                     }
             } else {
-                float tp[TM][TN], tn[TM][TN];
+                float tp[TM][TN], tn[TM][TN], tr[TM][TN];
+                if (p.sh_a == 0) {
+                    // M = 23: the 24-bit nearest-even sum is the mantissa rounding itself; the two
+                    // directed sums below still give the exact over/underflow decisions
+                    set_round_nearest();
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            asm volatile("v_add_f32 %0, %1, %2" : "=v"(tr[i][j]) : "v"(pq[i][j]), "v"(acc[i][j]));
+                }
                 set_round_pinf();
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
@@ -390,7 +481,15 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
                         const uint32_t sticky = (up ^ un) & 1u;             // the two differ iff inexact
                         const uint32_t uz = up < un ? up : un;              // smaller magnitude (same sign)
                         uint32_t of; bool small;
-                        acc[i][j] = gen_acc_rne(uz, sticky, p, &of, &small);
+                        float r = gen_acc_rne(uz, sticky, p, &of, &small);
+                        if (p.sh_a == 0) {
+                            const uint32_t sign = uz & 0x80000000u;
+                            uint32_t w = __float_as_uint(tr[i][j]);
+                            w = of ? (sign | rofb) : w;
+                            w = small ? 0u : w;
+                            r = __uint_as_float(w);
+                        }
+                        acc[i][j] = r;
                         if (EVENTS) {
                             const bool nz = pq[i][j] != -S;
                             wof[i][j] = (wof[i][j] << 1) | of;
@@ -470,7 +569,7 @@ template <int TM, int TN, int BK>
 static hipError_t launch_fast_tile(const Plan& pl, hipStream_t st) {
     const dim3 grid(pl.grid_x, pl.grid_y), block(256);
     const KParams& kp = pl.kp;
-#define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<TM, TN, BK, FastStep<PM, RND>>), grid, block, 0, st, kp)
+#define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<TM, TN, BK, PM, RND>), grid, block, 0, st, kp)
     if (pl.round == LBA_ROUND_FLOOR) {
         switch (pl.prod_mode) {
             case PM_IDENT: LBA_LAUNCH(PM_IDENT, LBA_ROUND_FLOOR); break;
@@ -491,9 +590,9 @@ static hipError_t launch_fast_tile(const Plan& pl, hipStream_t st) {
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
     if (pl.kernel == KERNEL_FAST) {
         if (pl.tm == 8 && pl.tn == 8) return launch_fast_tile<8, 8, 16>(pl, st);
-        if (pl.tm == 8 && pl.tn == 4) return launch_fast_tile<8, 4, 32>(pl, st);
-        if (pl.tm == 4 && pl.tn == 8) return launch_fast_tile<4, 8, 32>(pl, st);
-        return launch_fast_tile<4, 4, 32>(pl, st);
+        if (pl.tm == 8 && pl.tn == 4) return launch_fast_tile<8, 4, 16>(pl, st);
+        if (pl.tm == 4 && pl.tn == 8) return launch_fast_tile<4, 8, 16>(pl, st);
+        return launch_fast_tile<4, 4, 16>(pl, st);
     }
     const dim3 grid(pl.grid_x, pl.grid_y), block(256);
     const KParams& kp = pl.kp;

@@ -36,6 +36,7 @@
 //       It also produces the per-step event bits for lba_gemm_bwd.
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 
 #include "lba_internal.h"
@@ -109,7 +110,13 @@ static void pick_tile(int64_t M, int64_t N, int kernel, int* tm, int* tn, int* b
         if (score > best) { best = score; bi = i; }
     }
     *tm = cand[bi][0]; *tn = cand[bi][1];
-    *bk = (*tm * *tn >= 64) ? 16 : 32;
+    *bk = 16;
+    // tuning aid: LBA_TILE=8x8|8x4|4x8|4x4 forces the lane block (never changes any result)
+    if (const char* f = std::getenv("LBA_TILE")) {
+        if (f[0] && f[1] == 'x' && f[2] && (f[0] == '4' || f[0] == '8') && (f[2] == '4' || f[2] == '8')) {
+            *tm = f[0] - '0'; *tn = f[2] - '0';
+        }
+    }
 }
 
 int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfmt& qa,
@@ -165,6 +172,22 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
         p.valu_per_mac_x100 = 0;                           // filled by the launcher's table
     }
     pick_tile(M, N, p.kernel, &p.tm, &p.tn, &p.bk);
+    kp.fast_thresh = -1.0f;
+    if (p.kernel == KERNEL_FAST) {
+        // |S| can grow by at most max|p| per step (and by the rounding, for nearest-even): below
+        // this bound at the start of a k-tile, no sum inside the tile reaches R_OF of Q_acc.
+        const int c_a = -kp.out_exp;
+        double pmax = kMaxProd;
+        if (clamp) pmax = std::ldexp(2.0 - std::ldexp(1.0, -qp.man_bits), top_exp(qp));
+        pmax = std::ldexp(pmax, c_a);
+        double th = (double)kp.rof_a;
+        if (qa.round == LBA_ROUND_RNE)
+            th /= std::pow((1.0 + std::ldexp(1.0, -qa.man_bits - 1)) * (1.0 + std::ldexp(1.0, -24)), p.bk);
+        th -= (double)p.bk * pmax;
+        float thf = (float)th;
+        if ((double)thf > th) thf = std::nextafterf(thf, -INFINITY);
+        if (th > 0.0 && thf > 0.0f) kp.fast_thresh = thf;
+    }
     const int64_t bm = 16 * p.tm, bn = 16 * p.tn;
     p.grid_x = (int)((M + bm - 1) / bm);
     p.grid_y = (int)((N + bn - 1) / bn);
