@@ -170,6 +170,10 @@ template <int ROWS, int BK>
 struct Stage {
     static constexpr int kChunks = ROWS * BK / 16;                         // 16-byte pieces per tile
     static constexpr int kPerLane = (kChunks + 255) / 256;
+    static constexpr int kRowShift = ROWS == 16 ? 4 : ROWS == 32 ? 5 : ROWS == 64 ? 6 : ROWS == 128 ? 7 : 8;
+    static_assert((1 << kRowShift) == ROWS, "tile rows must be a power of two");
+    // lanes that take B's pieces: the highest-numbered ones, so that A and B share the work
+    static constexpr int kTailShift = kChunks < 256 ? 256 - kChunks : 0;
 };
 
 // Fetch this lane's 16-byte pieces of one operand tile into registers (zero outside the matrix).
@@ -184,9 +188,9 @@ __device__ __forceinline__ void fetch_tile(const uint8_t* __restrict__ G, int ro
     for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
         const int c = tid + i * 256;
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (c < Stage<ROWS, BK>::kChunks) {
+        if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
             const int row = c & (ROWS - 1);
-            const int kq = c / ROWS;                                        // ROWS is a power of two
+            const int kq = c >> Stage<ROWS, BK>::kRowShift;                 // ROWS is a power of two
             const int r = r0 + row, k = k0 + kq * 16;
             if (r < rows && k < K) {
                 const uint8_t* src = G + (int64_t)r * K + k;
@@ -228,9 +232,9 @@ __device__ __forceinline__ void store_tile(float* __restrict__ dst /* [BK][ROWS]
 #pragma unroll
     for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
         const int c = tid + i * 256;
-        if (c < Stage<ROWS, BK>::kChunks) {
+        if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
             const int row = c & (ROWS - 1);
-            const int kq = c / ROWS;
+            const int kq = c >> Stage<ROWS, BK>::kRowShift;
             const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
@@ -265,13 +269,13 @@ __device__ __forceinline__ void fast_kstep(float (&acc)[TM][TN], const float (&a
     if (TM > 4) fast_group<PM, RND, CLAMP, (TM > 4 ? 4 : 0), 4, TM, TN>(acc, a, b, c);
 }
 
-// One k-tile from LDS, operands double-buffered in registers one k ahead.
+// One k-tile from LDS, fully unrolled; operands are read one k ahead of their use.
 template <int PM, int RND, bool CLAMP, int TM, int TN, int BK, int BM, int BN>
 __device__ __forceinline__ void fast_tile(float (&acc)[TM][TN], const float* As, const float* Bs, int tx, int ty,
                                           const FastConst& c) {
     float a0[TM], b0[TN], a1[TM], b1[TN];
     read_operands<TM, TN, BM, BN>(As, Bs, 0, tx, ty, a0, b0);
-#pragma unroll 1
+#pragma unroll
     for (int k = 0; k < BK; k += 2) {
         read_operands<TM, TN, BM, BN>(As, Bs, k + 1, tx, ty, a1, b1);
         fast_kstep<PM, RND, CLAMP, TM, TN>(acc, a0, b0, c);
@@ -290,6 +294,7 @@ __global__ void __launch_bounds__(256) lba_fast_kernel(const KParams p) {
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
+    const int tidb = tid - Stage<BN, BK>::kTailShift;       // B's pieces go to the last lanes
     const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
 
     lut_a[tid] = decode_entry(tid, p.exp_a);
@@ -312,10 +317,10 @@ __global__ void __launch_bounds__(256) lba_fast_kernel(const KParams p) {
     const int ntiles = (p.K + BK - 1) / BK;                    // K > 0 here; division by a constant
 
     fetch_tile<BM, BK>(p.A, p.M, p.K, m0, 0, p.ld_align, tid, ra);
-    fetch_tile<BN, BK>(p.B, p.N, p.K, n0, 0, p.ld_align, tid, rb);
+    fetch_tile<BN, BK>(p.B, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
     __syncthreads();                                           // tables ready
     store_tile<BM, BK>(smem, lut_a, tid, ra);
-    store_tile<BN, BK>(smem + BK * BM, lut_b, tid, rb);
+    store_tile<BN, BK>(smem + BK * BM, lut_b, tidb, rb);
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
@@ -324,7 +329,7 @@ __global__ void __launch_bounds__(256) lba_fast_kernel(const KParams p) {
         const bool more = (t + 1) < ntiles;
         if (more) {
             fetch_tile<BM, BK>(p.A, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
-            fetch_tile<BN, BK>(p.B, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tid, rb);
+            fetch_tile<BN, BK>(p.B, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
         // If every chain of the wave starts this tile below fast_thresh = R_OF - BK * max|p| (scaled
         // down further for nearest-even), no sum inside the tile can reach R_OF: the clamp is a no-op
@@ -339,7 +344,7 @@ __global__ void __launch_bounds__(256) lba_fast_kernel(const KParams p) {
         if (more) {
             float* Ad = smem + ((t + 1) & 1) * STAGE;
             store_tile<BM, BK>(Ad, lut_a, tid, ra);
-            store_tile<BN, BK>(Ad + BK * BM, lut_b, tid, rb);
+            store_tile<BN, BK>(Ad + BK * BM, lut_b, tidb, rb);
         }
         __syncthreads();
     }
@@ -592,7 +597,7 @@ static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
         if (pl.tm == 8 && pl.tn == 8) return launch_fast_tile<8, 8, 16>(pl, st);
         if (pl.tm == 8 && pl.tn == 4) return launch_fast_tile<8, 4, 16>(pl, st);
         if (pl.tm == 4 && pl.tn == 8) return launch_fast_tile<4, 8, 16>(pl, st);
-        return launch_fast_tile<4, 4, 16>(pl, st);
+        return launch_fast_tile<4, 4, 32>(pl, st);
     }
     const dim3 grid(pl.grid_x, pl.grid_y), block(256);
     const KParams& kp = pl.kp;
