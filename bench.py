@@ -21,53 +21,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_LANE_OPS = 256 * 64 * 2.4e9          # CUs x lanes issued per clock per CU x clock = 39.3e12 /s
+# 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz = 78.6e12 full-rate VALU lane-ops per second: the
+# rate behind the published 157.3 TFLOP/s FP32 vector peak (an FMA counts two flops).
+PEAK_LANE_OPS = 256 * 4 * 32 * 2.4e9
+# HBM bytes per launch of the default workload, from the calibrated rocprofv3 FETCH_SIZE / WRITE_SIZE
+# runs summarised in profiles/lba_fast_kernel_resnet50_sweep.md: (2905 + 2714) MiB over 54 launches.
+RESNET50_TRAFFIC_BYTES_PER_LAUNCH = (2905 + 2714) * 2 ** 20 / 54
 PROD_FMT = (5, 7, 15)
 ACC_FMT = (4, 7, 7)
-
-
-def build_workload(name, device):
-    import torch
-    from paper_2401_14110_amd import inputs
-    if name == "resnet50":
-        layers = inputs.resnet50_gemms(batch=64, image=224)
-        seed = 2
-    elif name == "conv":
-        layers = [("resnet18.layer1.conv", 32 * 56 * 56, 64, 576)]
-        seed = 1
-    elif name == "bert":
-        layers = inputs.bert_base_gemms(32, 128)
-        seed = 3
-    elif name == "gemm4096":
-        layers = [("gemm4096", 4096, 4096, 4096)]
-        seed = 4
-    else:
-        raise SystemExit("unknown workload %r" % name)
-    # one operand tensor per distinct (rows, K) and role: layers of equal shape share data
-    cache_a, cache_b, out = {}, {}, []
-    for idx, (lname, M, N, K) in enumerate(layers):
-        if (M, K) not in cache_a:
-            if name == "resnet50":
-                kind = "normal" if lname == "conv1" else "relu"
-            elif name == "conv":
-                kind = "relu"
-            else:
-                kind = "normal"
-            cache_a[(M, K)] = inputs.make_operand(kind, M, K, seed, 2 * len(cache_a), device=device)
-        if (N, K) not in cache_b:
-            if name in ("resnet50", "conv"):
-                std = (2.0 / K) ** 0.5
-            elif name == "bert":
-                std = 0.02
-            else:
-                std = 1.0
-            cache_b[(N, K)] = inputs.make_operand("normal", N, K, seed, 2 * len(cache_b) + 1,
-                                                  device=device, std=std)
-        A, ta = cache_a[(M, K)]
-        B, tb = cache_b[(N, K)]
-        out.append(dict(name=lname, M=M, N=N, K=K, A=A, B=B, ta=ta, tb=tb))
-    torch.cuda.synchronize()
-    return out
 
 
 def cpu_baseline(layer, qp, qa, C_gpu, budget_macs=2.0e9):
@@ -99,6 +60,8 @@ def main():
     ap.add_argument("--round", default="floor", choices=["floor", "rne"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="after the steps, run a 1 GiB fill and a 1 GiB add (references for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU (every output chain is independent; "
@@ -113,7 +76,7 @@ def main():
     torch.cuda.set_device(dev)
     rnd = 0 if args.round == "floor" else 1
 
-    layers = build_workload(args.workload, dev)
+    layers = inputs.make_workload(args.workload, dev)
     cmax = max(l["M"] * l["N"] for l in layers)
     Cbuf = torch.empty(cmax, dtype=torch.float32, device=dev)
     for l in layers:
@@ -144,6 +107,13 @@ def main():
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
 
+    if args.copy_calibration:
+        # two kernels of known traffic: a fill (writes 1 GiB) and an add (reads 1 GiB, writes 1 GiB)
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+
     ms_per_step = wall * 1e3 / args.steps
     value = total_macs * args.steps / wall
 
@@ -165,11 +135,12 @@ def main():
     achieved = dom["macs"] * dom["ops"] / (dom["ms"] * 1e-3)
     roofline = {
         "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
-        "frac": achieved / PEAK_LANE_OPS, "traffic": None,
+        "frac": achieved / PEAK_LANE_OPS,
+        "traffic": RESNET50_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "resnet50" and rnd == 0) else None,
         "kernel": "lba_%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (
             "fast" if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
             "rne" if dom_key[2] else "floor"),
-        "valu_ops_per_mac": dom["ops"], "avg_launch_ms": dom["ms"] / dom["launches"],
+        "valu_slots_per_mac": dom["ops"], "avg_launch_ms": dom["ms"] / dom["launches"],
         "launches": dom["launches"], "mac_per_s": dom["macs"] / (dom["ms"] * 1e-3),
         "time_share": dom["ms"] / sum(g["ms"] for g in groups.values()),
     }

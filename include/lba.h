@@ -99,7 +99,9 @@ typedef struct {
     int32_t tile_m, tile_n, tile_k;   /* workgroup tile                                           */
     int32_t thread_m, thread_n;       /* outputs per lane                                         */
     int32_t grid_x, grid_y;           /* workgroups launched                                      */
-    int32_t valu_per_mac_x100;        /* VALU instructions per MAC in the inner loop, times 100   */
+    int32_t valu_per_mac_x100;        /* kernel 0: full-rate VALU issue slots per MAC of the inner
+                                         loop without the accumulator clamp, times 100 (a half-rate
+                                         instruction counts as 2 slots); kernel 1: 0 (not modelled) */
 } lba_plan_info;
 
 int lba_plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc,

@@ -145,9 +145,13 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
         kp.out_exp = -c_a;
         fill_quant(qa, c_a, &kp.mask_a, &kp.half_a, &kp.sh_a, &kp.rof_a, &kp.ruf_a);
         fill_quant(qp, c_p, &kp.mask_p, &kp.half_p, &kp.sh_p, &kp.rof_p, &kp.ruf_p);
-        int ops = (p.prod_mode == PM_IDENT) ? 3 : (p.prod_mode == PM_FLUSH ? 4 : 5);
-        if (qa.round == LBA_ROUND_RNE) ops += 2;
-        p.valu_per_mac_x100 = ops * 100;
+        // Issue slots per MAC of the clamp-free inner loop, in units of one full-rate VALU op
+        // (v_mul_f32 / v_fma_f32 / v_and_b32 with register operands: 32 lanes per clock per SIMD).
+        // v_med3_f32, v_bfe_u32 and v_add3_u32 issue at half that rate and count 2.
+        int slots = (p.prod_mode == PM_IDENT) ? 2 : 3;           // [mul,] fma, and
+        if (p.prod_mode == PM_FLUSH_CLAMP) slots += 2;           // med3 on the product
+        if (qa.round == LBA_ROUND_RNE) slots += 4;               // bfe, add3
+        p.valu_per_mac_x100 = slots * 100;
     } else {
         p.kernel = KERNEL_GEN;
         p.prod_mode = PM_FLUSH_CLAMP;

@@ -167,6 +167,52 @@ def bert_base_gemms(batch=32, seq=128):
             ("ffn_in", m, 3072, 768), ("ffn_out", m, 768, 3072)]
 
 
+def make_workload(name, device="cpu"):
+    """Operands of a named workload as a list of dicts (name, M, N, K, A, B, ta, tb): A [M,K] and
+    B [N,K] uint8 codes on `device`, ta / tb the power-of-two scale exponents.  Layers of equal
+    operand shape share data.  Workloads: 'resnet50' (ResNet-50 forward, batch 64, 224x224: 54 GEMMs),
+    'conv' (ResNet-18 3x3 conv 64->64 at batch 32), 'bert' (BERT-base linears, 4096 tokens),
+    'gemm4096' (4096^3, N(0,1) operands)."""
+    if name == "resnet50":
+        layers = resnet50_gemms(batch=64, image=224)
+        seed = 2
+    elif name == "conv":
+        layers = [("resnet18.layer1.conv", 32 * 56 * 56, 64, 576)]
+        seed = 1
+    elif name == "bert":
+        layers = bert_base_gemms(32, 128)
+        seed = 3
+    elif name == "gemm4096":
+        layers = [("gemm4096", 4096, 4096, 4096)]
+        seed = 4
+    else:
+        raise ValueError("unknown workload %r" % name)
+    # one operand tensor per distinct (rows, K) and role: layers of equal shape share data
+    cache_a, cache_b, out = {}, {}, []
+    for idx, (lname, M, N, K) in enumerate(layers):
+        if (M, K) not in cache_a:
+            if name == "resnet50":
+                kind = "normal" if lname == "conv1" else "relu"
+            elif name == "conv":
+                kind = "relu"
+            else:
+                kind = "normal"
+            cache_a[(M, K)] = make_operand(kind, M, K, seed, 2 * len(cache_a), device=device)
+        if (N, K) not in cache_b:
+            if name in ("resnet50", "conv"):
+                std = (2.0 / K) ** 0.5
+            elif name == "bert":
+                std = 0.02
+            else:
+                std = 1.0
+            cache_b[(N, K)] = make_operand("normal", N, K, seed, 2 * len(cache_b) + 1,
+                                                  device=device, std=std)
+        A, ta = cache_a[(M, K)]
+        B, tb = cache_b[(N, K)]
+        out.append(dict(name=lname, M=M, N=N, K=K, A=A, B=B, ta=ta, tb=tb))
+    return out
+
+
 def folded_formats(t_a, t_b, prod=(5, 7, 15), acc=(4, 7, 7), rnd=0):
     """Biases of (E, M, b) formats given in real units, moved into code units:
     codes = real * 2^(t_a+t_b) for a product, and Q_{M,E,b}(2^-T y) = 2^-T Q_{M,E,b-T}(y),

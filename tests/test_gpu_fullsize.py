@@ -1,0 +1,144 @@
+"""GPU parity at the benchmark's full sizes and launch configuration: sampled rows (all N columns)
+against the oracle, plus properties that hold at any size.  Inputs are generated on the GPU by the
+same seeded recipe the benchmark uses; the sampled rows are copied to the host for the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2401_14110_amd import binding as lb
+from paper_2401_14110_amd import inputs
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+PROD = (5, 7, 15)
+ACC = (4, 7, 7)
+
+
+def sample_rows(M, n_random=24, seed=0):
+    """First and last tile rows, tile-boundary rows, and pseudo-random rows."""
+    rows = {0, 1, 2, 3, 63, 64, 65, M - 1, M - 2, M - 64, M // 2}
+    rng = np.random.default_rng(seed + M)
+    rows |= set(int(r) for r in rng.integers(0, M, n_random))
+    return np.array(sorted(r for r in rows if 0 <= r < M))
+
+
+def check_rows(ref, layer, C, qp, qa, rows, what):
+    idx = torch.from_numpy(rows).to(DEV)
+    A = layer["A"].index_select(0, idx).cpu().numpy()
+    B = layer["B"].cpu().numpy()
+    want = ref.gemm(A, B, ref.QFmt(*qp), ref.QFmt(*qa))
+    got = C.index_select(0, idx).cpu().numpy()
+    bad = got.view(np.uint32) != want.view(np.uint32)
+    assert not bad.any(), "%s: %d mismatches in %d sampled rows, first %s: gpu %r oracle %r" % (
+        what, int(bad.sum()), len(rows), np.argwhere(bad)[0], got[bad][0], want[bad][0])
+
+
+def check_grid_property(C, qa):
+    """Every output is a value of Q_acc: low mantissa bits clear, magnitude <= R_OF, zero is +0."""
+    E, M, b, _ = qa
+    w = C.view(torch.int32)
+    low = (1 << (23 - M)) - 1
+    assert int((w & low).ne(0).sum()) == 0
+    rof = (2.0 - 2.0 ** -M) * 2.0 ** ((1 << E) - b - 1)
+    assert float(C.abs().max()) <= rof
+    nz = C[C != 0]
+    if nz.numel():
+        assert float(nz.abs().min()) >= 2.0 ** -b
+    assert int((w == -2 ** 31).sum()) == 0                         # no negative zero
+
+
+@pytest.fixture(scope="module")
+def resnet50():
+    return inputs.make_workload("resnet50", DEV)
+
+
+@pytest.mark.parametrize("rnd", [0, 1])
+def test_resnet50_layers_sampled_rows(ref, resnet50, rnd):
+    seen = set()
+    for l in resnet50:
+        key = (l["M"], l["N"], l["K"])
+        if key in seen:
+            continue
+        seen.add(key)
+        qp, qa, _ = inputs.folded_formats(l["ta"], l["tb"], PROD, ACC, rnd)
+        C = lb.gemm(l["A"], l["B"], qp, qa)
+        C2 = lb.gemm(l["A"], l["B"], qp, qa)
+        torch.cuda.synchronize()
+        check_rows(ref, l, C, qp, qa, sample_rows(l["M"]), "resnet50 %s %s" % (l["name"], key))
+        check_grid_property(C, qa)
+        assert torch.equal(C.view(torch.int32), C2.view(torch.int32))              # deterministic
+        assert int(C.ne(0).sum()) > C.numel() // 4
+        del C, C2
+    assert len(seen) == 21
+
+
+def test_resnet18_conv_config(ref):
+    (l,) = inputs.make_workload("conv", DEV)
+    assert (l["M"], l["N"], l["K"]) == (100352, 64, 576)
+    for rnd in (0, 1):
+        qp, qa, _ = inputs.folded_formats(l["ta"], l["tb"], PROD, ACC, rnd)
+        C = lb.gemm(l["A"], l["B"], qp, qa)
+        torch.cuda.synchronize()
+        check_rows(ref, l, C, qp, qa, sample_rows(l["M"], 200), "conv")
+        check_grid_property(C, qa)
+        # a row permutation of A permutes the rows of C (chains are independent)
+        perm = torch.randperm(l["M"], device=DEV, generator=torch.Generator(DEV).manual_seed(1))
+        Cp = lb.gemm(l["A"].index_select(0, perm), l["B"], qp, qa)
+        torch.cuda.synchronize()
+        assert torch.equal(Cp.view(torch.int32), C.index_select(0, perm).view(torch.int32))
+
+
+def test_bert_base_linears(ref):
+    for l in inputs.make_workload("bert", DEV):
+        for rnd in (0, 1):
+            qp, qa, _ = inputs.folded_formats(l["ta"], l["tb"], PROD, ACC, rnd)
+            C = lb.gemm(l["A"], l["B"], qp, qa)
+            torch.cuda.synchronize()
+            if l["name"] == "attn_out" and rnd == 0:               # one layer in full
+                rows = np.arange(l["M"])
+            else:
+                rows = sample_rows(l["M"], 40)
+            check_rows(ref, l, C, qp, qa, rows, "bert %s" % l["name"])
+            check_grid_property(C, qa)
+
+
+def test_accumulator_width_sweep_4096(ref):
+    (l,) = inputs.make_workload("gemm4096", DEV)
+    rows = sample_rows(4096, 8)
+    for M in range(3, 11):
+        for E in (4, 5, 6):
+            acc = (E, M, (1 << (E - 1)) - 1)
+            for rnd in ((0, 1) if (M in (3, 7, 10)) else (0,)):
+                qp, qa, _ = inputs.folded_formats(l["ta"], l["tb"], PROD, acc, rnd)
+                C = lb.gemm(l["A"], l["B"], qp, qa)
+                torch.cuda.synchronize()
+                check_rows(ref, l, C, qp, qa, rows, "sweep M%dE%d rnd%d" % (M, E, rnd))
+                check_grid_property(C, qa)
+
+
+def test_event_planes_full_512_and_slab_of_4096(ref):
+    (l,) = inputs.make_workload("gemm4096", DEV)
+    # a full 512^3 problem
+    A = l["A"][:512, :512].contiguous(); B = l["B"][:512, :512].contiguous()
+    for acc, rnd in (((4, 3, 7), 0), ((4, 7, 7), 0), ((6, 10, 31), 1)):
+        qp, qa, _ = inputs.folded_formats(l["ta"], l["tb"], PROD, acc, rnd)
+        C, of, uf = lb.gemm_bwd(A, B, qp, qa)
+        torch.cuda.synchronize()
+        wc, wof, wuf = ref.gemm_bwd(A.cpu().numpy(), B.cpu().numpy(), ref.QFmt(*qp), ref.QFmt(*qa))
+        assert np.array_equal(C.cpu().numpy().view(np.uint32), wc.view(np.uint32))
+        assert np.array_equal(of.cpu().numpy().view(np.uint32), wof)
+        assert np.array_equal(uf.cpu().numpy().view(np.uint32), wuf)
+        assert torch.equal(lb.gemm(A, B, qp, qa).view(torch.int32), C.view(torch.int32))
+    # the 4096^3 problem: both planes (17 GB), a 48-row slab against the oracle
+    qp, qa, _ = inputs.folded_formats(l["ta"], l["tb"], PROD, (4, 7, 7), 0)
+    C, of, uf = lb.gemm_bwd(l["A"], l["B"], qp, qa)
+    torch.cuda.synchronize()
+    rows = np.concatenate([np.arange(0, 16), np.arange(2040, 2056), np.arange(4080, 4096)])
+    idx = torch.from_numpy(rows).to(DEV)
+    wc, wof, wuf = ref.gemm_bwd(l["A"].index_select(0, idx).cpu().numpy(), l["B"].cpu().numpy(),
+                                ref.QFmt(*qp), ref.QFmt(*qa))
+    assert np.array_equal(C.index_select(0, idx).cpu().numpy().view(np.uint32), wc.view(np.uint32))
+    assert np.array_equal(of.index_select(1, idx).cpu().numpy().view(np.uint32), wof)
+    assert np.array_equal(uf.index_select(1, idx).cpu().numpy().view(np.uint32), wuf)
+    assert torch.equal(lb.gemm(l["A"], l["B"], qp, qa).view(torch.int32), C.view(torch.int32))
