@@ -27,6 +27,7 @@ struct KParams {
     int32_t out_exp;         // C = S * 2^out_exp
     float kc;                // FAST with an explicit product: t = p * kc + S
     float fast_thresh;       // FAST: a k-tile needs no clamp if every |S| is below this at its start
+    float fast_thresh4;      // FAST: same for four consecutive k-tiles
     // accumulator quantizer, in the kernel's (possibly scaled) domain
     uint32_t mask_a; uint32_t half_a; int32_t sh_a; float rof_a; float ruf_a;
     // product quantizer

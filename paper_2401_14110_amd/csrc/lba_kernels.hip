@@ -245,6 +245,43 @@ __device__ __forceinline__ void store_tile(float* __restrict__ dst /* [BK][ROWS]
     }
 }
 
+// Same, decoding with the hardware FP8 conversion (gfx950 decodes OCP E4M3) and one exact
+// multiply by the power-of-two scale.  The two NaN codes, which the conversion would turn into NaN,
+// are patched to +-480 * scale on a rarely taken path so that every code has a defined value.
+template <int ROWS, int BK>
+__device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][ROWS] */, float scale,
+                                               int tid, const uint4 (&regs)[Stage<ROWS, BK>::kPerLane]) {
+    typedef float v2f __attribute__((ext_vector_type(2)));
+#pragma unroll
+    for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
+        const int c = tid + i * 256;
+        if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
+            const int row = c & (ROWS - 1);
+            const int kq = c >> Stage<ROWS, BK>::kRowShift;
+            const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+            float f[16];
+            uint32_t nan_any = 0u;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[d], false);
+                const v2f hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[d], true);
+                f[4 * d + 0] = lo.x * scale; f[4 * d + 1] = lo.y * scale;
+                f[4 * d + 2] = hi.x * scale; f[4 * d + 3] = hi.y * scale;
+                nan_any |= ((w[d] & 0x7F7F7F7Fu) + 0x01010101u) & 0x80808080u;   // a byte with low 7 bits all set
+            }
+            if (nan_any) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const uint32_t code = (w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+                    if ((code & 0x7Fu) == 0x7Fu) f[j] = (code & 0x80u) ? -480.0f * scale : 480.0f * scale;
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < 16; ++j) dst[(kq * 16 + j) * ROWS + row] = f[j];
+        }
+    }
+}
+
 // Reads the TM + TN operand values of one k from an LDS stage.
 template <int TM, int TN, int BM, int BN>
 __device__ __forceinline__ void read_operands(const float* As, const float* Bs, int k, int tx, int ty,
@@ -284,28 +321,30 @@ __device__ __forceinline__ void fast_tile(float (&acc)[TM][TN], const float* As,
     }
 }
 
+#ifndef LBA_FAST_MIN_WAVES
+#define LBA_FAST_MIN_WAVES 4        // waves per SIMD the register allocation must allow
+#endif
+
 template <int TM, int TN, int BK, int PM, int RND>
-__global__ void __launch_bounds__(256) lba_fast_kernel(const KParams p) {
+__global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const KParams p) {
     constexpr int BM = 16 * TM, BN = 16 * TN;
     constexpr int STAGE = BK * (BM + BN);
     __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
-    __shared__ float lut_a[256];
-    __shared__ float lut_b[256];
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int tidb = tid - Stage<BN, BK>::kTailShift;       // B's pieces go to the last lanes
     const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
 
-    lut_a[tid] = decode_entry(tid, p.exp_a);
-    lut_b[tid] = decode_entry(tid, p.exp_b);
+    const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
     set_flush_f32();
     if (RND == LBA_ROUND_FLOOR) set_round_zero();
 
     FastConst c;
     c.kc = p.kc; c.rof = p.rof_a; c.rofp = p.rof_p; c.mask = p.mask_a; c.half = p.half_a; c.sh = p.sh_a;
-    float thresh = p.fast_thresh;
-    asm volatile("" : "+v"(c.kc), "+v"(c.rof), "+v"(c.rofp), "+v"(c.mask), "+v"(c.half), "+v"(thresh));
+    float thresh = p.fast_thresh, thresh4 = p.fast_thresh4;
+    int safe_tiles = 0;
+    asm volatile("" : "+v"(c.kc), "+v"(c.rof), "+v"(c.rofp), "+v"(c.mask), "+v"(c.half), "+v"(thresh), "+v"(thresh4));
 
     float acc[TM][TN];
 #pragma unroll
@@ -318,9 +357,8 @@ __global__ void __launch_bounds__(256) lba_fast_kernel(const KParams p) {
 
     fetch_tile<BM, BK>(p.A, p.M, p.K, m0, 0, p.ld_align, tid, ra);
     fetch_tile<BN, BK>(p.B, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
-    __syncthreads();                                           // tables ready
-    store_tile<BM, BK>(smem, lut_a, tid, ra);
-    store_tile<BN, BK>(smem + BK * BM, lut_b, tidb, rb);
+    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra);
+    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb);
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
@@ -331,20 +369,29 @@ __global__ void __launch_bounds__(256) lba_fast_kernel(const KParams p) {
             fetch_tile<BM, BK>(p.A, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
             fetch_tile<BN, BK>(p.B, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
-        // If every chain of the wave starts this tile below fast_thresh = R_OF - BK * max|p| (scaled
-        // down further for nearest-even), no sum inside the tile can reach R_OF: the clamp is a no-op
-        // and is skipped.  The test is per wave, so the branch is uniform.
-        float mx = 0.0f;
+        // If every chain of the wave starts a tile below R_OF - n * BK * max|p| (scaled down further
+        // for nearest-even), no sum inside the next n tiles can reach R_OF: the clamp is a no-op there
+        // and a clamp-free copy of the loop runs.  The test is per wave (uniform branch) and is made
+        // for n = 4 and n = 1; after a successful n = 4 test the next three tiles are not tested.
+        if (safe_tiles == 0) {
+            float mx = 0.0f;
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) mx = __builtin_fmaxf(mx, __builtin_fabsf(acc[i][j]));
-        if (__all(mx < thresh)) fast_tile<PM, RND, false, TM, TN, BK, BM, BN>(acc, As, Bs, tx, ty, c);
-        else                    fast_tile<PM, RND, true, TM, TN, BK, BM, BN>(acc, As, Bs, tx, ty, c);
+                for (int j = 0; j < TN; j += 2)
+                    mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(acc[i][j]), __builtin_fabsf(acc[i][j + 1])));
+            safe_tiles = __all(mx < thresh4) ? 4 : (__all(mx < thresh) ? 1 : 0);
+        }
+        if (safe_tiles > 0) {
+            --safe_tiles;
+            fast_tile<PM, RND, false, TM, TN, BK, BM, BN>(acc, As, Bs, tx, ty, c);
+        } else {
+            fast_tile<PM, RND, true, TM, TN, BK, BM, BN>(acc, As, Bs, tx, ty, c);
+        }
         if (more) {
             float* Ad = smem + ((t + 1) & 1) * STAGE;
-            store_tile<BM, BK>(Ad, lut_a, tid, ra);
-            store_tile<BN, BK>(Ad + BK * BM, lut_b, tidb, rb);
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra);
+            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb);
         }
         __syncthreads();
     }
@@ -592,12 +639,16 @@ static hipError_t launch_fast_tile(const Plan& pl, hipStream_t st) {
     return hipGetLastError();
 }
 
+#ifndef LBA_FAST_BK
+#define LBA_FAST_BK 32
+#endif
+
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
     if (pl.kernel == KERNEL_FAST) {
         if (pl.tm == 8 && pl.tn == 8) return launch_fast_tile<8, 8, 16>(pl, st);
         if (pl.tm == 8 && pl.tn == 4) return launch_fast_tile<8, 4, 16>(pl, st);
         if (pl.tm == 4 && pl.tn == 8) return launch_fast_tile<4, 8, 16>(pl, st);
-        return launch_fast_tile<4, 4, 32>(pl, st);
+        return launch_fast_tile<4, 4, LBA_FAST_BK>(pl, st);
     }
     const dim3 grid(pl.grid_x, pl.grid_y), block(256);
     const KParams& kp = pl.kp;

@@ -103,7 +103,10 @@ static void pick_tile(int64_t M, int64_t N, int kernel, int* tm, int* tn, int* b
             *tm = f[0] - '0'; *tn = f[2] - '0';
         }
     }
-    *bk = (*tm * *tn <= 16) ? 32 : 16;
+#ifndef LBA_FAST_BK
+#define LBA_FAST_BK 32
+#endif
+    *bk = (*tm * *tn <= 16) ? LBA_FAST_BK : 16;
 }
 
 int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfmt& qa,
@@ -164,20 +167,24 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
     }
     pick_tile(M, N, p.kernel, &p.tm, &p.tn, &p.bk);
     kp.fast_thresh = -1.0f;
+    kp.fast_thresh4 = -1.0f;
     if (p.kernel == KERNEL_FAST) {
         // |S| can grow by at most max|p| per step (and by the rounding, for nearest-even): below
-        // this bound at the start of a k-tile, no sum inside the tile reaches R_OF of Q_acc.
+        // this bound at the start of n k-tiles, no sum inside them reaches R_OF of Q_acc.
         const int c_a = -kp.out_exp;
         double pmax = kMaxProd;
         if (clamp) pmax = std::ldexp(2.0 - std::ldexp(1.0, -qp.man_bits), top_exp(qp));
         pmax = std::ldexp(pmax, c_a);
-        double th = (double)kp.rof_a;
-        if (qa.round == LBA_ROUND_RNE)
-            th /= std::pow((1.0 + std::ldexp(1.0, -qa.man_bits - 1)) * (1.0 + std::ldexp(1.0, -24)), p.bk);
-        th -= (double)p.bk * pmax;
-        float thf = (float)th;
-        if ((double)thf > th) thf = std::nextafterf(thf, -INFINITY);
-        if (th > 0.0 && thf > 0.0f) kp.fast_thresh = thf;
+        for (int n = 1; n <= 4; n += 3) {
+            const int steps = n * p.bk;
+            double th = (double)kp.rof_a;
+            if (qa.round == LBA_ROUND_RNE)
+                th /= std::pow((1.0 + std::ldexp(1.0, -qa.man_bits - 1)) * (1.0 + std::ldexp(1.0, -24)), steps);
+            th -= (double)steps * pmax;
+            float thf = (float)th;
+            if ((double)thf > th) thf = std::nextafterf(thf, -INFINITY);
+            if (th > 0.0 && thf > 0.0f) (n == 1 ? kp.fast_thresh : kp.fast_thresh4) = thf;
+        }
     }
     const int64_t bm = 16 * p.tm, bn = 16 * p.tn;
     p.grid_x = (int)((M + bm - 1) / bm);
