@@ -31,7 +31,7 @@ PROD_FMT = (5, 7, 15)
 ACC_FMT = (4, 7, 7)
 
 
-def cpu_baseline(layer, qp, qa, C_gpu, budget_macs=2.0e9):
+def cpu_baseline(layer, qp, qa, C_gpu, order=0, budget_macs=2.0e9):
     """The oracle, as it stands, on a bounded slab of one layer; also a parity check of the slab."""
     import numpy as np
     from oracle import lba_ref
@@ -40,7 +40,7 @@ def cpu_baseline(layer, qp, qa, C_gpu, budget_macs=2.0e9):
     B = layer["B"].cpu().numpy()
     threads = min(16, os.cpu_count() or 1)
     t0 = time.perf_counter()
-    want = lba_ref.gemm(A, B, lba_ref.QFmt(*qp), lba_ref.QFmt(*qa), nthreads=threads)
+    want = lba_ref.gemm(A, B, lba_ref.QFmt(*qp), lba_ref.QFmt(*qa), order=order, nthreads=threads)
     dt = time.perf_counter() - t0
     got = C_gpu[:rows].cpu().numpy()
     parity = bool(np.array_equal(got.view(np.uint32), want.view(np.uint32)))
@@ -58,6 +58,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="resnet50")
     ap.add_argument("--round", default="floor", choices=["floor", "rne"])
+    ap.add_argument("--order", default="seq", choices=["seq", "chunk16"],
+                    help="accumulation order: one sequential chain (default) or the paper's chunks of 16")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -75,13 +77,14 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     rnd = 0 if args.round == "floor" else 1
+    order = 0 if args.order == "seq" else 1
 
     layers = inputs.make_workload(args.workload, dev)
     cmax = max(l["M"] * l["N"] for l in layers)
     Cbuf = torch.empty(cmax, dtype=torch.float32, device=dev)
     for l in layers:
         l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], PROD_FMT, ACC_FMT, rnd)
-        l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"])
+        l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order)
         l["C"] = Cbuf[: l["M"] * l["N"]].view(l["M"], l["N"])
         l["macs"] = l["M"] * l["N"] * l["K"]
     total_macs = sum(l["macs"] for l in layers)
@@ -90,7 +93,7 @@ def main():
         for i, l in enumerate(layers):
             if events is not None:
                 events[i][0].record()
-            lb.gemm(l["A"], l["B"], l["qp"], l["qa"], out=l["C"])
+            lb.gemm(l["A"], l["B"], l["qp"], l["qa"], order=order, out=l["C"])
             if events is not None:
                 events[i][1].record()
 
@@ -136,7 +139,7 @@ def main():
     roofline = {
         "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
         "frac": achieved / PEAK_LANE_OPS,
-        "traffic": RESNET50_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "resnet50" and rnd == 0) else None,
+        "traffic": RESNET50_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "resnet50" and rnd == 0 and order == 0) else None,
         "kernel": "lba_%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (
             "fast" if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
             "rne" if dom_key[2] else "floor"),
@@ -161,16 +164,16 @@ def main():
                                 "conv": "ResNet-18 3x3 conv 64->64, batch 32, 56x56 (M=100352,N=64,K=576)",
                                 "bert": "BERT-base linears, 4096 tokens", "gemm4096": "4096^3 GEMM"}[args.workload],
                    "macs_per_step": total_macs, "qprod": "M7E5 b=15", "qacc": "M7E4 b=7 (12-bit)",
-                   "round": args.round, "order": "sequential", "scale": "per-tensor power of two, folded into b"},
+                   "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b"},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
         # a mid-sized layer whose output is still in the shared buffer: recompute it last
         pick = max(range(len(layers)), key=lambda i: (layers[i]["K"] == 576, layers[i]["M"]))
         l = layers[pick]
-        lb.gemm(l["A"], l["B"], l["qp"], l["qa"], out=l["C"])
+        lb.gemm(l["A"], l["B"], l["qp"], l["qa"], order=order, out=l["C"])
         torch.cuda.synchronize()
-        out["cpu_baseline"] = cpu_baseline(l, l["qp"], l["qa"], l["C"])
+        out["cpu_baseline"] = cpu_baseline(l, l["qp"], l["qa"], l["C"], order)
     print(json.dumps(out))
 
 

@@ -57,7 +57,7 @@ enum { LBA_OK = 0,
        LBA_ERR_NULL = 1,         /* a required pointer is NULL                                  */
        LBA_ERR_SHAPE = 2,        /* negative or too large M, N, K                               */
        LBA_ERR_FORMAT = 3,       /* a quantizer format outside the limits above                 */
-       LBA_ERR_UNSUPPORTED = 4,  /* unknown order, or an order this build does not implement    */
+       LBA_ERR_UNSUPPORTED = 4,  /* unknown order, or lba_gemm_bwd with the chunked order        */
        LBA_ERR_ALIGN = 5,        /* reserved: no entry point requires alignment                 */
        LBA_ERR_LAUNCH = 6 };     /* the HIP runtime refused the launch                          */
 
@@ -66,7 +66,10 @@ enum { LBA_OK = 0,
  *   E4M3: 1 sign, 4 exponent (bias 7), 3 mantissa bits; e = 0 is subnormal, m * 2^-9; no inf.
  *   The two NaN codes 0x7f / 0xff are outside the contract; they are read as +-480.
  *   Zero results are stored as +0.0f.  K == 0 stores +0.0f everywhere; M*N == 0 does nothing.
- *   No alignment is required of A, B, C or of K.  Shape limits: M, N, K < 2^31, N <= 2^21. */
+ *   No alignment is required of A, B, C or of K.  Shape limits: M, N, K < 2^31, N <= 2^21.
+ *   order: LBA_ORDER_SEQ, or LBA_ORDER_CHUNK16 = chunks of 16 consecutive k, each summed by its own
+ *   chain from 0, then T_0 = 0, T_{j+1} = Q_acc(T_j + chunk_j) over the chunks in order (a short last
+ *   chunk when 16 does not divide K; no Q_prod at the second level). */
 int lba_gemm(const uint8_t* A, const uint8_t* B, float* C,
              int64_t M, int64_t N, int64_t K,
              lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream);

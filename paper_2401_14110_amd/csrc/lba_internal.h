@@ -41,6 +41,7 @@ struct Plan {
     int prod_mode;           // PM_*
     int round;               // LBA_ROUND_*
     int events;              // also write the event planes
+    int order;               // LBA_ORDER_*
     int tm, tn, bk;          // outputs per lane (tm x tn), k-depth of a tile; tile = 16tm x 16tn
     int grid_x, grid_y;
     int valu_per_mac_x100;

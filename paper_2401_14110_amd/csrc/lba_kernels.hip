@@ -298,6 +298,46 @@ __device__ __forceinline__ void read_operands(const float* As, const float* Bs, 
     }
 }
 
+// Second level of the chunked order (Sec. 3, Fig. 1 right): T <- Q_acc(T + S), then S <- 0,
+// for all chains of the lane, phase by phase.  T and S are both values of Q_acc's grid, so the
+// same one-rounding argument as for a product step applies.
+template <int RND, bool CLAMP, int TM, int TN>
+__device__ __forceinline__ void fast_level2(float (&top)[TM][TN], float (&acc)[TM][TN], const FastConst& c) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) top[i][j] = top[i][j] + acc[i][j];
+    __builtin_amdgcn_sched_barrier(0);
+    if (RND == LBA_ROUND_RNE) {
+        uint32_t l[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) l[i][j] = (__float_as_uint(top[i][j]) >> c.sh) & 1u;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) top[i][j] = __uint_as_float(__float_as_uint(top[i][j]) + c.half + l[i][j]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            top[i][j] = __uint_as_float(__float_as_uint(top[i][j]) & c.mask);
+            acc[i][j] = 0.0f;
+        }
+    if (CLAMP) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) top[i][j] = med3(top[i][j], -c.rof, c.rof);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 // All chains of the lane advance by one k: groups of 4 rows x TN columns.
 template <int PM, int RND, bool CLAMP, int TM, int TN>
 __device__ __forceinline__ void fast_kstep(float (&acc)[TM][TN], const float (&a)[TM], const float (&b)[TN],
@@ -306,10 +346,12 @@ __device__ __forceinline__ void fast_kstep(float (&acc)[TM][TN], const float (&a
     if (TM > 4) fast_group<PM, RND, CLAMP, (TM > 4 ? 4 : 0), 4, TM, TN>(acc, a, b, c);
 }
 
-// One k-tile from LDS, fully unrolled; operands are read one k ahead of their use.
-template <int PM, int RND, bool CLAMP, int TM, int TN, int BK, int BM, int BN>
-__device__ __forceinline__ void fast_tile(float (&acc)[TM][TN], const float* As, const float* Bs, int tx, int ty,
-                                          const FastConst& c) {
+// One k-tile from LDS, fully unrolled; operands are read one k ahead of their use.  With the
+// chunked order every 16th step is followed by the second-level step (tiles start at multiples
+// of 16, so chunk boundaries are compile-time positions).
+template <int PM, int RND, int ORDER, bool CLAMP, int TM, int TN, int BK, int BM, int BN>
+__device__ __forceinline__ void fast_tile(float (&acc)[TM][TN], float (&top)[TM][TN], const float* As, const float* Bs,
+                                          int tx, int ty, const FastConst& c) {
     float a0[TM], b0[TN], a1[TM], b1[TN];
     read_operands<TM, TN, BM, BN>(As, Bs, 0, tx, ty, a0, b0);
 #pragma unroll
@@ -318,6 +360,7 @@ __device__ __forceinline__ void fast_tile(float (&acc)[TM][TN], const float* As,
         fast_kstep<PM, RND, CLAMP, TM, TN>(acc, a0, b0, c);
         if (k + 2 < BK) read_operands<TM, TN, BM, BN>(As, Bs, k + 2, tx, ty, a0, b0);
         fast_kstep<PM, RND, CLAMP, TM, TN>(acc, a1, b1, c);
+        if (ORDER == LBA_ORDER_CHUNK16 && ((k + 2) & 15) == 0) fast_level2<RND, CLAMP, TM, TN>(top, acc, c);
     }
 }
 
@@ -325,8 +368,9 @@ __device__ __forceinline__ void fast_tile(float (&acc)[TM][TN], const float* As,
 #define LBA_FAST_MIN_WAVES 4        // waves per SIMD the register allocation must allow
 #endif
 
-template <int TM, int TN, int BK, int PM, int RND>
+template <int TM, int TN, int BK, int PM, int RND, int ORDER>
 __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const KParams p) {
+    static_assert(BK % 16 == 0, "chunk boundaries must fall on fixed positions of a k-tile");
     constexpr int BM = 16 * TM, BN = 16 * TN;
     constexpr int STAGE = BK * (BM + BN);
     __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
@@ -346,11 +390,11 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
     int safe_tiles = 0;
     asm volatile("" : "+v"(c.kc), "+v"(c.rof), "+v"(c.rofp), "+v"(c.mask), "+v"(c.half), "+v"(thresh), "+v"(thresh4));
 
-    float acc[TM][TN];
+    float acc[TM][TN], top[TM][TN];                            // top: second-level sums (chunked order only)
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) acc[i][j] = 0.0f;
+        for (int j = 0; j < TN; ++j) { acc[i][j] = 0.0f; top[i][j] = 0.0f; }
 
     uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
     const int ntiles = (p.K + BK - 1) / BK;                    // K > 0 here; division by a constant
@@ -369,6 +413,8 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
             fetch_tile<BM, BK>(p.A, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
             fetch_tile<BN, BK>(p.B, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
+        // (Chunked order: the test is on the second-level sums; a first-level sum starts from 0 and
+        // is covered by the same bound.)
         // If every chain of the wave starts a tile below R_OF - n * BK * max|p| (scaled down further
         // for nearest-even), no sum inside the next n tiles can reach R_OF: the clamp is a no-op there
         // and a clamp-free copy of the loop runs.  The test is per wave (uniform branch) and is made
@@ -379,14 +425,16 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; j += 2)
-                    mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(acc[i][j]), __builtin_fabsf(acc[i][j + 1])));
+                    mx = (ORDER == LBA_ORDER_CHUNK16)
+                             ? __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(top[i][j]), __builtin_fabsf(top[i][j + 1])))
+                             : __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(acc[i][j]), __builtin_fabsf(acc[i][j + 1])));
             safe_tiles = __all(mx < thresh4) ? 4 : (__all(mx < thresh) ? 1 : 0);
         }
         if (safe_tiles > 0) {
             --safe_tiles;
-            fast_tile<PM, RND, false, TM, TN, BK, BM, BN>(acc, As, Bs, tx, ty, c);
+            fast_tile<PM, RND, ORDER, false, TM, TN, BK, BM, BN>(acc, top, As, Bs, tx, ty, c);
         } else {
-            fast_tile<PM, RND, true, TM, TN, BK, BM, BN>(acc, As, Bs, tx, ty, c);
+            fast_tile<PM, RND, ORDER, true, TM, TN, BK, BM, BN>(acc, top, As, Bs, tx, ty, c);
         }
         if (more) {
             float* Ad = smem + ((t + 1) & 1) * STAGE;
@@ -408,7 +456,7 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
             float v[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const float s = acc[i][4 * g + j];
+                const float s = (ORDER == LBA_ORDER_CHUNK16) ? top[i][4 * g + j] : acc[i][4 * g + j];
                 v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);
             }
             float* dst = p.C + (int64_t)m * p.N + n;
@@ -423,8 +471,89 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
     }
 }
 
-// General kernel: 4 x 4 outputs per lane, 64 x 64 tile, BK = 32 (one event word per tile).
+// dst <- Q_acc(add + dst) for the 16 chains of a lane, with exact decisions.
+// Floor: one toward-zero add (the kernel runs in that mode).  Nearest-even: the add is done twice,
+// toward +inf and toward -inf; the smaller magnitude is the truncated sum and the two differ iff the
+// sum was inexact (the sticky bit).  With EVENTS, one OF and one UF bit per chain are shifted into
+// wof / wuf (uf1 = product-underflow flags of this step).
 template <int RND, bool EVENTS>
+__device__ __forceinline__ void gen_qadd_all(float (&dst)[4][4], const float (&add)[4][4], const KParams& p,
+                                             uint32_t rofb, uint32_t rufb, const uint32_t (&uf1)[4][4],
+                                             uint32_t (&wof)[4][4], uint32_t (&wuf)[4][4]) {
+    constexpr int TM = 4, TN = 4;
+    if (RND == LBA_ROUND_FLOOR) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const float S = dst[i][j];
+                const float tz = add[i][j] + S;                             // toward zero: truncated exact sum
+                const uint32_t uz = __float_as_uint(tz);
+                const uint32_t mag = uz & 0x7FFFFFFFu;
+                const bool of = mag >= rofb, small = mag < rufb;
+                uint32_t r = uz & p.mask_a;
+                r = of ? ((uz & 0x80000000u) | rofb) : r;
+                r = small ? 0u : r;
+                dst[i][j] = __uint_as_float(r);
+                if (EVENTS) {
+                    const bool nz = add[i][j] != -S;                        // exact sum is not zero
+                    wof[i][j] = (wof[i][j] << 1) | (of ? 1u : 0u);
+                    wuf[i][j] = (wuf[i][j] << 1) | ((uf1[i][j] || (small && nz)) ? 1u : 0u);
+                }
+            }
+    } else {
+        float tp[TM][TN], tn[TM][TN], tr[TM][TN];
+        if (p.sh_a == 0) {
+            // M = 23: the 24-bit nearest-even sum is the mantissa rounding itself; the two
+            // directed sums below still give the exact over/underflow decisions
+            set_round_nearest();
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    asm volatile("v_add_f32 %0, %1, %2" : "=v"(tr[i][j]) : "v"(add[i][j]), "v"(dst[i][j]));
+        }
+        set_round_pinf();
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                asm volatile("v_add_f32 %0, %1, %2" : "=v"(tp[i][j]) : "v"(add[i][j]), "v"(dst[i][j]));
+        set_round_ninf();
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                asm volatile("v_add_f32 %0, %1, %2" : "=v"(tn[i][j]) : "v"(add[i][j]), "v"(dst[i][j]));
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const float S = dst[i][j];
+                const uint32_t up = __float_as_uint(tp[i][j]), un = __float_as_uint(tn[i][j]);
+                const uint32_t sticky = (up ^ un) & 1u;                     // the two differ iff inexact
+                const uint32_t uz = up < un ? up : un;                      // smaller magnitude (same sign)
+                uint32_t of; bool small;
+                float r = gen_acc_rne(uz, sticky, p, &of, &small);
+                if (p.sh_a == 0) {
+                    const uint32_t sign = uz & 0x80000000u;
+                    uint32_t w = __float_as_uint(tr[i][j]);
+                    w = of ? (sign | rofb) : w;
+                    w = small ? 0u : w;
+                    r = __uint_as_float(w);
+                }
+                dst[i][j] = r;
+                if (EVENTS) {
+                    const bool nz = add[i][j] != -S;
+                    wof[i][j] = (wof[i][j] << 1) | of;
+                    wuf[i][j] = (wuf[i][j] << 1) | ((uf1[i][j] || (small && nz)) ? 1u : 0u);
+                }
+            }
+    }
+}
+
+// General kernel: 4 x 4 outputs per lane, 64 x 64 tile, BK = 32 (one event word per tile).
+template <int RND, bool EVENTS, int ORDER>
 __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
     constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
     constexpr int STAGE = BK * (BM + BN);
@@ -441,12 +570,12 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
     set_flush_f32();
     if (RND == LBA_ROUND_FLOOR) set_round_zero();
 
-    float acc[TM][TN];
+    float acc[TM][TN], top[TM][TN];                            // top: second-level sums (chunked order only)
     uint32_t wof[TM][TN], wuf[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) { acc[i][j] = 0.0f; wof[i][j] = 0u; wuf[i][j] = 0u; }
+        for (int j = 0; j < TN; ++j) { acc[i][j] = 0.0f; top[i][j] = 0.0f; wof[i][j] = 0u; wuf[i][j] = 0u; }
 
     uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
     const int ntiles = (p.K + BK - 1) / BK;
@@ -480,74 +609,14 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j) pq[i][j] = gen_product<RND>(a[i], b[j], p, &uf1[i][j]);
 
-            if (RND == LBA_ROUND_FLOOR) {
+            gen_qadd_all<RND, EVENTS>(acc, pq, p, rofb, rufb, uf1, wof, wuf);
+            if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
+                // second level (Sec. 3, Fig. 1 right): T <- Q_acc(T + S), S <- 0
+                gen_qadd_all<RND, false>(top, acc, p, rofb, rufb, uf1, wof, wuf);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        const float S = acc[i][j];
-                        const float tz = pq[i][j] + S;                      // toward zero: truncated exact sum
-                        const uint32_t uz = __float_as_uint(tz);
-                        const uint32_t mag = uz & 0x7FFFFFFFu;
-                        const bool of = mag >= rofb, small = mag < rufb;
-                        uint32_t r = uz & p.mask_a;
-                        r = of ? ((uz & 0x80000000u) | rofb) : r;
-                        r = small ? 0u : r;
-                        acc[i][j] = __uint_as_float(r);
-                        if (EVENTS) {
-                            const bool nz = pq[i][j] != -S;                 // exact sum is not zero
-                            wof[i][j] = (wof[i][j] << 1) | (of ? 1u : 0u);
-                            wuf[i][j] = (wuf[i][j] << 1) | ((uf1[i][j] || (small && nz)) ? 1u : 0u);
-                        }
-                    }
-            } else {
-                float tp[TM][TN], tn[TM][TN], tr[TM][TN];
-                if (p.sh_a == 0) {
-                    // M = 23: the 24-bit nearest-even sum is the mantissa rounding itself; the two
-                    // directed sums below still give the exact over/underflow decisions
-                    set_round_nearest();
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j)
-                            asm volatile("v_add_f32 %0, %1, %2" : "=v"(tr[i][j]) : "v"(pq[i][j]), "v"(acc[i][j]));
-                }
-                set_round_pinf();
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        asm volatile("v_add_f32 %0, %1, %2" : "=v"(tp[i][j]) : "v"(pq[i][j]), "v"(acc[i][j]));
-                set_round_ninf();
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        asm volatile("v_add_f32 %0, %1, %2" : "=v"(tn[i][j]) : "v"(pq[i][j]), "v"(acc[i][j]));
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        const float S = acc[i][j];
-                        const uint32_t up = __float_as_uint(tp[i][j]), un = __float_as_uint(tn[i][j]);
-                        const uint32_t sticky = (up ^ un) & 1u;             // the two differ iff inexact
-                        const uint32_t uz = up < un ? up : un;              // smaller magnitude (same sign)
-                        uint32_t of; bool small;
-                        float r = gen_acc_rne(uz, sticky, p, &of, &small);
-                        if (p.sh_a == 0) {
-                            const uint32_t sign = uz & 0x80000000u;
-                            uint32_t w = __float_as_uint(tr[i][j]);
-                            w = of ? (sign | rofb) : w;
-                            w = small ? 0u : w;
-                            r = __uint_as_float(w);
-                        }
-                        acc[i][j] = r;
-                        if (EVENTS) {
-                            const bool nz = pq[i][j] != -S;
-                            wof[i][j] = (wof[i][j] << 1) | of;
-                            wuf[i][j] = (wuf[i][j] << 1) | ((uf1[i][j] || (small && nz)) ? 1u : 0u);
-                        }
-                    }
+                    for (int j = 0; j < TN; ++j) acc[i][j] = 0.0f;
             }
         }
         if (EVENTS) {
@@ -596,7 +665,10 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
             const int n = n0 + tx * 4;
             float v[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = (acc[i][j] == 0.0f) ? 0.0f : acc[i][j];
+            for (int j = 0; j < 4; ++j) {
+                const float r = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
+                v[j] = (r == 0.0f) ? 0.0f : r;
+            }
             float* dst = p.C + (int64_t)m * p.N + n;
             if (p.c_vec && n + 3 < p.N) {
                 *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
@@ -617,11 +689,15 @@ __global__ void lba_fill_zero_kernel(float* C, int64_t n) {
 // ---------------------------------------------------------------------------------------------
 // launchers
 // ---------------------------------------------------------------------------------------------
-template <int TM, int TN, int BK>
-static hipError_t launch_fast_tile(const Plan& pl, hipStream_t st) {
+#ifndef LBA_FAST_BK
+#define LBA_FAST_BK 32              // k-depth of a tile of the fast kernel (a multiple of 16)
+#endif
+
+template <int ORDER>
+static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
     const dim3 grid(pl.grid_x, pl.grid_y), block(256);
     const KParams& kp = pl.kp;
-#define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<TM, TN, BK, PM, RND>), grid, block, 0, st, kp)
+#define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<4, 4, LBA_FAST_BK, PM, RND, ORDER>), grid, block, 0, st, kp)
     if (pl.round == LBA_ROUND_FLOOR) {
         switch (pl.prod_mode) {
             case PM_IDENT: LBA_LAUNCH(PM_IDENT, LBA_ROUND_FLOOR); break;
@@ -639,25 +715,20 @@ static hipError_t launch_fast_tile(const Plan& pl, hipStream_t st) {
     return hipGetLastError();
 }
 
-#ifndef LBA_FAST_BK
-#define LBA_FAST_BK 32
-#endif
-
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
-    if (pl.kernel == KERNEL_FAST) {
-        if (pl.tm == 8 && pl.tn == 8) return launch_fast_tile<8, 8, 16>(pl, st);
-        if (pl.tm == 8 && pl.tn == 4) return launch_fast_tile<8, 4, 16>(pl, st);
-        if (pl.tm == 4 && pl.tn == 8) return launch_fast_tile<4, 8, 16>(pl, st);
-        return launch_fast_tile<4, 4, LBA_FAST_BK>(pl, st);
-    }
+    if (pl.kernel == KERNEL_FAST)
+        return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<LBA_ORDER_CHUNK16>(pl, st) : launch_fast<LBA_ORDER_SEQ>(pl, st);
     const dim3 grid(pl.grid_x, pl.grid_y), block(256);
     const KParams& kp = pl.kp;
-    if (pl.round == LBA_ROUND_FLOOR) {
-        if (pl.events) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, true>), grid, block, 0, st, kp);
-        else           hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, false>), grid, block, 0, st, kp);
+    if (pl.order == LBA_ORDER_CHUNK16) {
+        if (pl.round == LBA_ROUND_FLOOR) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, false, LBA_ORDER_CHUNK16>), grid, block, 0, st, kp);
+        else                             hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, false, LBA_ORDER_CHUNK16>), grid, block, 0, st, kp);
+    } else if (pl.round == LBA_ROUND_FLOOR) {
+        if (pl.events) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, true, LBA_ORDER_SEQ>), grid, block, 0, st, kp);
+        else           hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, false, LBA_ORDER_SEQ>), grid, block, 0, st, kp);
     } else {
-        if (pl.events) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, true>), grid, block, 0, st, kp);
-        else           hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, false>), grid, block, 0, st, kp);
+        if (pl.events) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, true, LBA_ORDER_SEQ>), grid, block, 0, st, kp);
+        else           hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, false, LBA_ORDER_SEQ>), grid, block, 0, st, kp);
     }
     return hipGetLastError();
 }

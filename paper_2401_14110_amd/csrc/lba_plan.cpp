@@ -36,7 +36,6 @@
 //       It also produces the per-step event bits for lba_gemm_bwd.
 
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 
 #include "lba_internal.h"
@@ -93,20 +92,15 @@ static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp) {
     return true;
 }
 
-static void pick_tile(int64_t M, int64_t N, int kernel, int* tm, int* tn, int* bk) {
-    if (kernel == KERNEL_GEN) { *tm = 4; *tn = 4; *bk = 32; return; }
-    (void)M; (void)N;
-    *tm = 4; *tn = 4;          // measured best on every ResNet-50 / BERT shape; others via LBA_TILE
-    // tuning aid: LBA_TILE=8x8|8x4|4x8|4x4 forces the lane block (never changes any result)
-    if (const char* f = std::getenv("LBA_TILE")) {
-        if (f[0] && f[1] == 'x' && f[2] && (f[0] == '4' || f[0] == '8') && (f[2] == '4' || f[2] == '8')) {
-            *tm = f[0] - '0'; *tn = f[2] - '0';
-        }
-    }
 #ifndef LBA_FAST_BK
 #define LBA_FAST_BK 32
 #endif
-    *bk = (*tm * *tn <= 16) ? LBA_FAST_BK : 16;
+
+// 4 x 4 outputs per lane (64 x 64 per workgroup) was the fastest lane block on every ResNet-50 and
+// BERT shape measured; 8 x 8, 8 x 4 and 4 x 8 lost to it through lower occupancy and coarser grids.
+static void pick_tile(int kernel, int* tm, int* tn, int* bk) {
+    *tm = 4; *tn = 4;
+    *bk = (kernel == KERNEL_GEN) ? 32 : LBA_FAST_BK;
 }
 
 int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfmt& qa,
@@ -116,11 +110,12 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
     if ((rc = validate_fmt(qp)) != LBA_OK) return rc;
     if ((rc = validate_fmt(qa)) != LBA_OK) return rc;
     if (order != LBA_ORDER_SEQ && order != LBA_ORDER_CHUNK16) return LBA_ERR_UNSUPPORTED;
-    if (order == LBA_ORDER_CHUNK16) return LBA_ERR_UNSUPPORTED;
+    if (order == LBA_ORDER_CHUNK16 && events) return LBA_ERR_UNSUPPORTED;   // planes of the chunked order: not built
 
     Plan p;
     std::memset(&p, 0, sizeof(p));
     p.events = events ? 1 : 0;
+    p.order = order;
     p.round = qa.round;
     KParams& kp = p.kp;
     kp.M = (int32_t)M; kp.N = (int32_t)N; kp.K = (int32_t)K;
@@ -155,6 +150,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
         if (p.prod_mode == PM_FLUSH_CLAMP) slots += 2;           // med3 on the product
         if (qa.round == LBA_ROUND_RNE) slots += 4;               // bfe, add3
         p.valu_per_mac_x100 = slots * 100;
+        if (order == LBA_ORDER_CHUNK16)                          // add, and [, bfe, add3], zero per 16 steps
+            p.valu_per_mac_x100 += (qa.round == LBA_ROUND_RNE ? 700 : 300) / 16;
     } else {
         p.kernel = KERNEL_GEN;
         p.prod_mode = PM_FLUSH_CLAMP;
@@ -165,7 +162,7 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
         kp.prod_rne = (qp.round == LBA_ROUND_RNE) ? 1 : 0;
         p.valu_per_mac_x100 = 0;                           // filled by the launcher's table
     }
-    pick_tile(M, N, p.kernel, &p.tm, &p.tn, &p.bk);
+    pick_tile(p.kernel, &p.tm, &p.tn, &p.bk);
     kp.fast_thresh = -1.0f;
     kp.fast_thresh4 = -1.0f;
     if (p.kernel == KERNEL_FAST) {

@@ -23,11 +23,11 @@ def sample_rows(M, n_random=24, seed=0):
     return np.array(sorted(r for r in rows if 0 <= r < M))
 
 
-def check_rows(ref, layer, C, qp, qa, rows, what):
+def check_rows(ref, layer, C, qp, qa, rows, what, order=0):
     idx = torch.from_numpy(rows).to(DEV)
     A = layer["A"].index_select(0, idx).cpu().numpy()
     B = layer["B"].cpu().numpy()
-    want = ref.gemm(A, B, ref.QFmt(*qp), ref.QFmt(*qa))
+    want = ref.gemm(A, B, ref.QFmt(*qp), ref.QFmt(*qa), order=order)
     got = C.index_select(0, idx).cpu().numpy()
     bad = got.view(np.uint32) != want.view(np.uint32)
     assert not bad.any(), "%s: %d mismatches in %d sampled rows, first %s: gpu %r oracle %r" % (
@@ -71,6 +71,22 @@ def test_resnet50_layers_sampled_rows(ref, resnet50, rnd):
         assert int(C.ne(0).sum()) > C.numel() // 4
         del C, C2
     assert len(seen) == 21
+
+
+def test_resnet50_layers_chunked_order(ref, resnet50):
+    # the paper's own accumulation order (chunks of 16) and bias pair b_acc, b_prod = 10, 12 (Sec. 3.1)
+    seen = set()
+    for l in resnet50:
+        key = (l["M"], l["N"], l["K"])
+        if key in seen:
+            continue
+        seen.add(key)
+        qp, qa, _ = inputs.folded_formats(l["ta"], l["tb"], (4, 7, 12), (4, 7, 10), 0)
+        C = lb.gemm(l["A"], l["B"], qp, qa, order=1)
+        torch.cuda.synchronize()
+        check_rows(ref, l, C, qp, qa, sample_rows(l["M"], 12), "resnet50 chunk16 %s" % (key,), order=1)
+        check_grid_property(C, qa)
+        del C
 
 
 def test_resnet18_conv_config(ref):

@@ -35,15 +35,15 @@ def bits(x):
     return np.ascontiguousarray(x).view(np.uint32)
 
 
-def run_gpu(A, B, qp, qa):
-    C = lb.gemm(torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV), qp, qa)
+def run_gpu(A, B, qp, qa, order=0):
+    C = lb.gemm(torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV), qp, qa, order=order)
     torch.cuda.synchronize()
     return C.cpu().numpy()
 
 
-def check(ref, A, B, qp, qa, what=""):
-    got = run_gpu(A, B, qp, qa)
-    want = ref.gemm(A, B, fm(ref, qp), fm(ref, qa))
+def check(ref, A, B, qp, qa, what="", order=0):
+    got = run_gpu(A, B, qp, qa, order)
+    want = ref.gemm(A, B, fm(ref, qp), fm(ref, qa), order=order)
     bad = bits(got) != bits(want)
     if bad.any():
         i, j = np.argwhere(bad)[0]
@@ -145,6 +145,26 @@ def test_synthetic_workload_distributions(ref):
             qp, qa, _ = inputs.folded_formats(ta, tb, rnd=rnd)
             got = check(ref, A.numpy(), B.numpy(), qp, qa, "workload")
             assert np.count_nonzero(got) > got.size // 2
+
+
+@pytest.mark.parametrize("rnd", [0, 1])
+def test_chunked_order(ref, rnd):
+    # chunks of 16 then a second-level chain (Sec. 3): K below, at and across chunk and tile
+    # boundaries, fast and general kernels, saturating and non-saturating formats
+    rng = np.random.default_rng(60 + rnd)
+    for (M, N, K) in [(5, 7, 1), (9, 3, 15), (17, 9, 16), (33, 20, 17), (65, 67, 31), (70, 64, 32), (64, 70, 33),
+                      (130, 66, 48), (40, 40, 147), (66, 130, 576)]:
+        A = rand_codes(rng, (M, K), 3, 12)
+        B = rand_codes(rng, (N, K), 3, 12)
+        for qp, qa in FMT_PAPER + [FMT_ODD[0], FMT_ODD[1], FMT_ODD[3], FMT_SWEEP[0], FMT_SWEEP[5], FMT_ODD[5]]:
+            check(ref, A, B, qp + (rnd,), qa + (rnd,), "chunk16", order=1)
+    A, ta = inputs.make_operand("relu", 200, 576, 5, 0)
+    B, tb = inputs.make_operand("normal", 64, 576, 5, 1, std=(2.0 / 576) ** 0.5)
+    # the paper's bias pairs (b_acc, b_prod) = (10, 12), (7, 9), (8, 10) in real units, folded
+    for ba, bp in ((10, 12), (7, 9), (8, 10)):
+        qp, qa, _ = inputs.folded_formats(ta, tb, (4, 7, bp), (4, 7, ba), rnd)
+        got = check(ref, A.numpy(), B.numpy(), qp, qa, "chunk16 paper biases", order=1)
+        assert np.count_nonzero(got) > got.size // 2
 
 
 TINY = [0x00, 0x80, 0x01, 0x81, 0x08, 0x38, 0xB8, 0x39, 0x3F, 0x47, 0x58, 0xDA, 0x7E, 0xFE, 0x77, 0x0F]
