@@ -282,19 +282,25 @@ __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][R
     }
 }
 
-// Reads the TM + TN operand values of one k from an LDS stage.
+// Reads the TM + TN operand values of one k from an LDS stage (TM, TN in {2, 4}): the lane's
+// rows ty*TM .. and columns tx*TN .. are contiguous in the k-major tiles.
 template <int TM, int TN, int BM, int BN>
 __device__ __forceinline__ void read_operands(const float* As, const float* Bs, int k, int tx, int ty,
                                               float (&a)[TM], float (&b)[TN]) {
-#pragma unroll
-    for (int g = 0; g < TM / 4; ++g) {
-        const float4 v = *reinterpret_cast<const float4*>(As + k * BM + g * (BM / 2) + ty * 4);
-        a[4 * g + 0] = v.x; a[4 * g + 1] = v.y; a[4 * g + 2] = v.z; a[4 * g + 3] = v.w;
+    static_assert((TM == 2 || TM == 4) && (TN == 2 || TN == 4), "lane block");
+    if (TM == 4) {
+        const float4 v = *reinterpret_cast<const float4*>(As + k * BM + ty * 4);
+        a[0] = v.x; a[1] = v.y; a[TM - 2] = v.z; a[TM - 1] = v.w;
+    } else {
+        const float2 v = *reinterpret_cast<const float2*>(As + k * BM + ty * 2);
+        a[0] = v.x; a[1] = v.y;
     }
-#pragma unroll
-    for (int g = 0; g < TN / 4; ++g) {
-        const float4 v = *reinterpret_cast<const float4*>(Bs + k * BN + g * (BN / 2) + tx * 4);
-        b[4 * g + 0] = v.x; b[4 * g + 1] = v.y; b[4 * g + 2] = v.z; b[4 * g + 3] = v.w;
+    if (TN == 4) {
+        const float4 w = *reinterpret_cast<const float4*>(Bs + k * BN + tx * 4);
+        b[0] = w.x; b[1] = w.y; b[TN - 2] = w.z; b[TN - 1] = w.w;
+    } else {
+        const float2 w = *reinterpret_cast<const float2*>(Bs + k * BN + tx * 2);
+        b[0] = w.x; b[1] = w.y;
     }
 }
 
@@ -338,12 +344,11 @@ __device__ __forceinline__ void fast_level2(float (&top)[TM][TN], float (&acc)[T
     __builtin_amdgcn_sched_barrier(0);
 }
 
-// All chains of the lane advance by one k: groups of 4 rows x TN columns.
+// All chains of the lane advance by one k.
 template <int PM, int RND, bool CLAMP, int TM, int TN>
 __device__ __forceinline__ void fast_kstep(float (&acc)[TM][TN], const float (&a)[TM], const float (&b)[TN],
                                            const FastConst& c) {
-    fast_group<PM, RND, CLAMP, 0, 4, TM, TN>(acc, a, b, c);
-    if (TM > 4) fast_group<PM, RND, CLAMP, (TM > 4 ? 4 : 0), 4, TM, TN>(acc, a, b, c);
+    fast_group<PM, RND, CLAMP, 0, TM, TM, TN>(acc, a, b, c);
 }
 
 // One k-tile from LDS, fully unrolled; operands are read one k ahead of their use.  With the
@@ -448,25 +453,24 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
     // C = S * 2^out_exp, zero written as +0
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
-        const int m = m0 + (i >> 2) * (BM / 2) + ty * 4 + (i & 3);
+        const int m = m0 + ty * TM + i;
         if (m >= p.M) continue;
+        const int n = n0 + tx * TN;
+        float v[TN];
 #pragma unroll
-        for (int g = 0; g < TN / 4; ++g) {
-            const int n = n0 + g * (BN / 2) + tx * 4;
-            float v[4];
+        for (int j = 0; j < TN; ++j) {
+            const float s = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
+            v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);
+        }
+        float* dst = p.C + (int64_t)m * p.N + n;
+        if (TN == 4 && p.c_vec && n + 3 < p.N) {
+            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[TN - 2], v[TN - 1]);
+        } else if (TN == 2 && p.c_vec && n + 1 < p.N) {
+            *reinterpret_cast<float2*>(dst) = make_float2(v[0], v[1]);
+        } else {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float s = (ORDER == LBA_ORDER_CHUNK16) ? top[i][4 * g + j] : acc[i][4 * g + j];
-                v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);
-            }
-            float* dst = p.C + (int64_t)m * p.N + n;
-            if (p.c_vec && n + 3 < p.N) {
-                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (n + j < p.N) dst[j] = v[j];
-            }
+            for (int j = 0; j < TN; ++j)
+                if (n + j < p.N) dst[j] = v[j];
         }
     }
 }
@@ -693,11 +697,11 @@ __global__ void lba_fill_zero_kernel(float* C, int64_t n) {
 #define LBA_FAST_BK 32              // k-depth of a tile of the fast kernel (a multiple of 16)
 #endif
 
-template <int ORDER>
+template <int TM, int TN, int ORDER>
 static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
     const dim3 grid(pl.grid_x, pl.grid_y), block(256);
     const KParams& kp = pl.kp;
-#define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<4, 4, LBA_FAST_BK, PM, RND, ORDER>), grid, block, 0, st, kp)
+#define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<TM, TN, LBA_FAST_BK, PM, RND, ORDER>), grid, block, 0, st, kp)
     if (pl.round == LBA_ROUND_FLOOR) {
         switch (pl.prod_mode) {
             case PM_IDENT: LBA_LAUNCH(PM_IDENT, LBA_ROUND_FLOOR); break;
@@ -716,8 +720,13 @@ static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
 }
 
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
-    if (pl.kernel == KERNEL_FAST)
-        return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<LBA_ORDER_CHUNK16>(pl, st) : launch_fast<LBA_ORDER_SEQ>(pl, st);
+    if (pl.kernel == KERNEL_FAST) {
+        if (pl.tm == 2 && pl.tn == 2)
+            return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<2, 2, LBA_ORDER_CHUNK16>(pl, st) : launch_fast<2, 2, LBA_ORDER_SEQ>(pl, st);
+        if (pl.tm == 2)
+            return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<2, 4, LBA_ORDER_CHUNK16>(pl, st) : launch_fast<2, 4, LBA_ORDER_SEQ>(pl, st);
+        return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<4, 4, LBA_ORDER_CHUNK16>(pl, st) : launch_fast<4, 4, LBA_ORDER_SEQ>(pl, st);
+    }
     const dim3 grid(pl.grid_x, pl.grid_y), block(256);
     const KParams& kp = pl.kp;
     if (pl.order == LBA_ORDER_CHUNK16) {

@@ -96,11 +96,19 @@ static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp) {
 #define LBA_FAST_BK 32
 #endif
 
-// 4 x 4 outputs per lane (64 x 64 per workgroup) was the fastest lane block on every ResNet-50 and
-// BERT shape measured; 8 x 8, 8 x 4 and 4 x 8 lost to it through lower occupancy and coarser grids.
-static void pick_tile(int kernel, int* tm, int* tn, int* bk) {
+// Lane block (outputs per lane).  4 x 4 (64 x 64 per workgroup) was the fastest on every large GEMM
+// measured (8 x 8, 8 x 4 and 4 x 8 lost to it through lower occupancy and coarser grids).  GEMMs
+// with few outputs cannot keep two waves on every SIMD with 16 chains per lane: between 512 and 1024
+// workgroups 2 x 4 measured 3-6 % faster, and up to 64 workgroups (a latency-bound launch) 2 x 2 is
+// about twice as fast.  The choice never changes a result.
+static void pick_tile(int64_t M, int64_t N, int kernel, int* tm, int* tn, int* bk) {
     *tm = 4; *tn = 4;
     *bk = (kernel == KERNEL_GEN) ? 32 : LBA_FAST_BK;
+    if (kernel == KERNEL_FAST) {
+        const int64_t blocks = ((M + 63) / 64) * ((N + 63) / 64);
+        if (blocks <= 64) { *tm = 2; *tn = 2; }
+        else if (blocks > 512 && blocks <= 1024) *tm = 2;
+    }
 }
 
 int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfmt& qa,
@@ -162,7 +170,7 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
         kp.prod_rne = (qp.round == LBA_ROUND_RNE) ? 1 : 0;
         p.valu_per_mac_x100 = 0;                           // filled by the launcher's table
     }
-    pick_tile(p.kernel, &p.tm, &p.tn, &p.bk);
+    pick_tile(M, N, p.kernel, &p.tm, &p.tn, &p.bk);
     kp.fast_thresh = -1.0f;
     kp.fast_thresh4 = -1.0f;
     if (p.kernel == KERNEL_FAST) {

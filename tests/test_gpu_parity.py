@@ -167,6 +167,19 @@ def test_chunked_order(ref, rnd):
         assert np.count_nonzero(got) > got.size // 2
 
 
+def test_every_lane_block(ref):
+    # output counts that select each lane block of the fast kernel (2x2, 2x4, 4x4), ragged on both
+    # sides, both roundings and both orders; all outputs compared
+    rng = np.random.default_rng(70)
+    for (M, N, K), want_tile in (((130, 70, 70), (32, 32)), ((1500, 1530, 70), (32, 64)), ((2100, 2110, 70), (64, 64))):
+        A = rand_codes(rng, (M, K), 3, 12)
+        B = rand_codes(rng, (N, K), 3, 12)
+        for (qp, qa), rnd, order in itertools.product([FMT_PAPER[1], FMT_PAPER[3], FMT_PAPER[4]], (0, 1), (0, 1)):
+            plan = lb.lba_plan_query(M, N, K, qp + (rnd,), qa + (rnd,), order)
+            assert plan["kernel"] == 0 and (plan["tile_m"], plan["tile_n"]) == want_tile
+            check(ref, A, B, qp + (rnd,), qa + (rnd,), "lane block %s" % (want_tile,), order=order)
+
+
 TINY = [0x00, 0x80, 0x01, 0x81, 0x08, 0x38, 0xB8, 0x39, 0x3F, 0x47, 0x58, 0xDA, 0x7E, 0xFE, 0x77, 0x0F]
 
 
