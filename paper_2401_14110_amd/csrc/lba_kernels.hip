@@ -58,6 +58,18 @@ __device__ __forceinline__ uint32_t rne_bits(uint32_t u, uint32_t half, int sh, 
     return (u + half + ((u >> sh) & 1u)) & mask;
 }
 
+// Internal rounding code of the fast kernel: nearest-even to 8 significant bits (M = 7) done by
+// the hardware float -> bfloat16 conversion, whose packed result with a zero low half is the FP32
+// word of the rounded value.  Same function as the bfe/add3/and sequence, in one instruction.
+enum { RND_RNE_BF16 = 2 };
+
+__device__ __forceinline__ float rne_to_8_bits(float t) {
+    typedef float v2f __attribute__((ext_vector_type(2)));
+    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+    const v2f v = {0.0f, t};
+    return __uint_as_float(__builtin_bit_cast(uint32_t, __builtin_convertvector(v, v2bf)));
+}
+
 // Per-wave constants of the fast kernel, forced into vector registers: on gfx950 the simple
 // FP32 / bitwise VALU ops issue at twice the rate when all their operands are VGPRs.
 struct FastConst {
@@ -99,23 +111,30 @@ __device__ __forceinline__ void fast_group(float (&accf)[TM][NJ], const float (&
             for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_fmaf(q[i][j], c.kc, acc[i][j]);   // one rounding of the exact sum
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (RND == LBA_ROUND_RNE) {
-        uint32_t l[NI][NJ];
+    if (RND == RND_RNE_BF16) {
 #pragma unroll
         for (int i = 0; i < NI; ++i)
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) l[i][j] = (__float_as_uint(acc[i][j]) >> c.sh) & 1u;
-        __builtin_amdgcn_sched_barrier(0);
+            for (int j = 0; j < NJ; ++j) acc[i][j] = rne_to_8_bits(acc[i][j]);
+    } else {
+        if (RND == LBA_ROUND_RNE) {
+            uint32_t l[NI][NJ];
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) l[i][j] = (__float_as_uint(acc[i][j]) >> c.sh) & 1u;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) acc[i][j] = __uint_as_float(__float_as_uint(acc[i][j]) + c.half + l[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
+        }
 #pragma unroll
         for (int i = 0; i < NI; ++i)
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) acc[i][j] = __uint_as_float(__float_as_uint(acc[i][j]) + c.half + l[i][j]);
-        __builtin_amdgcn_sched_barrier(0);
+            for (int j = 0; j < NJ; ++j) acc[i][j] = __uint_as_float(__float_as_uint(acc[i][j]) & c.mask);
     }
-#pragma unroll
-    for (int i = 0; i < NI; ++i)
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[i][j] = __uint_as_float(__float_as_uint(acc[i][j]) & c.mask);
     if (CLAMP) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -314,26 +333,33 @@ __device__ __forceinline__ void fast_level2(float (&top)[TM][TN], float (&acc)[T
 #pragma unroll
         for (int j = 0; j < TN; ++j) top[i][j] = top[i][j] + acc[i][j];
     __builtin_amdgcn_sched_barrier(0);
-    if (RND == LBA_ROUND_RNE) {
-        uint32_t l[TM][TN];
+    if (RND == RND_RNE_BF16) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) l[i][j] = (__float_as_uint(top[i][j]) >> c.sh) & 1u;
-        __builtin_amdgcn_sched_barrier(0);
+            for (int j = 0; j < TN; ++j) { top[i][j] = rne_to_8_bits(top[i][j]); acc[i][j] = 0.0f; }
+    } else {
+        if (RND == LBA_ROUND_RNE) {
+            uint32_t l[TM][TN];
 #pragma unroll
-        for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < TN; ++j) top[i][j] = __uint_as_float(__float_as_uint(top[i][j]) + c.half + l[i][j]);
-        __builtin_amdgcn_sched_barrier(0);
-    }
+                for (int j = 0; j < TN; ++j) l[i][j] = (__float_as_uint(top[i][j]) >> c.sh) & 1u;
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            top[i][j] = __uint_as_float(__float_as_uint(top[i][j]) & c.mask);
-            acc[i][j] = 0.0f;
+                for (int j = 0; j < TN; ++j) top[i][j] = __uint_as_float(__float_as_uint(top[i][j]) + c.half + l[i][j]);
+            __builtin_amdgcn_sched_barrier(0);
         }
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                top[i][j] = __uint_as_float(__float_as_uint(top[i][j]) & c.mask);
+                acc[i][j] = 0.0f;
+            }
+    }
     if (CLAMP) {
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -707,6 +733,12 @@ static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
             case PM_IDENT: LBA_LAUNCH(PM_IDENT, LBA_ROUND_FLOOR); break;
             case PM_FLUSH: LBA_LAUNCH(PM_FLUSH, LBA_ROUND_FLOOR); break;
             default:       LBA_LAUNCH(PM_FLUSH_CLAMP, LBA_ROUND_FLOOR); break;
+        }
+    } else if (pl.kp.sh_a == 16) {                           // M = 7: rounding by the bfloat16 conversion
+        switch (pl.prod_mode) {
+            case PM_IDENT: LBA_LAUNCH(PM_IDENT, RND_RNE_BF16); break;
+            case PM_FLUSH: LBA_LAUNCH(PM_FLUSH, RND_RNE_BF16); break;
+            default:       LBA_LAUNCH(PM_FLUSH_CLAMP, RND_RNE_BF16); break;
         }
     } else {
         switch (pl.prod_mode) {

@@ -156,7 +156,7 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
         // v_med3_f32, v_bfe_u32 and v_add3_u32 issue at half that rate and count 2.
         int slots = (p.prod_mode == PM_IDENT) ? 2 : 3;           // [mul,] fma, and
         if (p.prod_mode == PM_FLUSH_CLAMP) slots += 2;           // med3 on the product
-        if (qa.round == LBA_ROUND_RNE) slots += 4;               // bfe, add3
+        if (qa.round == LBA_ROUND_RNE) slots += (qa.man_bits == 7) ? 1 : 4;   // M = 7: cvt to bfloat16 replaces and; else bfe, add3
         p.valu_per_mac_x100 = slots * 100;
         if (order == LBA_ORDER_CHUNK16)                          // add, and [, bfe, add3], zero per 16 steps
             p.valu_per_mac_x100 += (qa.round == LBA_ROUND_RNE ? 700 : 300) / 16;
