@@ -60,6 +60,8 @@ def main():
     ap.add_argument("--round", default="floor", choices=["floor", "rne"])
     ap.add_argument("--order", default="seq", choices=["seq", "chunk16"],
                     help="accumulation order: one sequential chain (default) or the paper's chunks of 16")
+    ap.add_argument("--bwd", action="store_true",
+                    help="time lba_gemm_bwd (forward chain + both event planes) instead of lba_gemm")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -84,16 +86,30 @@ def main():
     Cbuf = torch.empty(cmax, dtype=torch.float32, device=dev)
     for l in layers:
         l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], PROD_FMT, ACC_FMT, rnd)
-        l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order)
+        l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, 1 if args.bwd else 0)
         l["C"] = Cbuf[: l["M"] * l["N"]].view(l["M"], l["N"])
         l["macs"] = l["M"] * l["N"] * l["K"]
     total_macs = sum(l["macs"] for l in layers)
+    if args.bwd:
+        wmax = max(lb.lba_mask_words(l["M"], l["N"], l["K"]) for l in layers)
+        of_buf = torch.empty(wmax, dtype=torch.int32, device=dev)
+        uf_buf = torch.empty(wmax, dtype=torch.int32, device=dev)
+        stream = torch.cuda.current_stream().cuda_stream
+
+        def launch(l):
+            rc = lb.lba_gemm_bwd(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
+                                 uf_buf.data_ptr(), l["M"], l["N"], l["K"], l["qp"], l["qa"], order, stream)
+            if rc != 0:
+                raise RuntimeError(lb.lba_strerror(rc))
+    else:
+        def launch(l):
+            lb.gemm(l["A"], l["B"], l["qp"], l["qa"], order=order, out=l["C"])
 
     def one_step(events=None):
         for i, l in enumerate(layers):
             if events is not None:
                 events[i][0].record()
-            lb.gemm(l["A"], l["B"], l["qp"], l["qa"], order=order, out=l["C"])
+            launch(l)
             if events is not None:
                 events[i][1].record()
 
@@ -139,9 +155,9 @@ def main():
     roofline = {
         "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
         "frac": achieved / PEAK_LANE_OPS,
-        "traffic": RESNET50_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "resnet50" and rnd == 0 and order == 0) else None,
+        "traffic": RESNET50_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "resnet50" and rnd == 0 and order == 0 and not args.bwd) else None,
         "kernel": "lba_%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (
-            "fast" if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
+            ("fast_bwd" if args.bwd else "fast") if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
             "rne" if dom_key[2] else "floor"),
         "valu_slots_per_mac": dom["ops"], "avg_launch_ms": dom["ms"] / dom["launches"],
         "launches": dom["launches"], "mac_per_s": dom["macs"] / (dom["ms"] * 1e-3),
@@ -164,14 +180,14 @@ def main():
                                 "conv": "ResNet-18 3x3 conv 64->64, batch 32, 56x56 (M=100352,N=64,K=576)",
                                 "bert": "BERT-base linears, 4096 tokens", "gemm4096": "4096^3 GEMM"}[args.workload],
                    "macs_per_step": total_macs, "qprod": "M7E5 b=15", "qacc": "M7E4 b=7 (12-bit)",
-                   "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b"},
+                   "call": "lba_gemm_bwd (C + OF and UF planes)" if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b"},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
         # a mid-sized layer whose output is still in the shared buffer: recompute it last
         pick = max(range(len(layers)), key=lambda i: (layers[i]["K"] == 576, layers[i]["M"]))
         l = layers[pick]
-        lb.gemm(l["A"], l["B"], l["qp"], l["qa"], order=order, out=l["C"])
+        launch(l)
         torch.cuda.synchronize()
         out["cpu_baseline"] = cpu_baseline(l, l["qp"], l["qa"], l["C"], order)
     print(json.dumps(out))

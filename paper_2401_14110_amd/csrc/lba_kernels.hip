@@ -501,6 +501,162 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// fast recompute kernel: forward chain + event planes (floor, sequential order, Q_prod can flush)
+// ---------------------------------------------------------------------------------------------
+// Same scaled domain as lba_fast_kernel, so both underflows are hardware flushes, and every decision
+// is exact under the toward-zero mode:
+//   OF_k  <=>  |t| >= R_OF  <=>  the clamped, truncated sum has magnitude exactly R_OF
+//   product underflow  <=>  the flushed product is 0 although both operands are non-zero
+//   accumulator underflow  <=>  the flushed sum is 0, the product is not, and the exact sum is not
+//       zero; the exact sum is zero only if p*kc == -S with S != 0, and then p*kc is a normal number
+//       that a plain multiply reproduces exactly
+// One 32-bit word per chain and k-tile: bits are shifted in (first k highest) and reversed at the end.
+template <int PM>
+__global__ void __launch_bounds__(256, 4) lba_fast_bwd_kernel(const KParams p) {
+    constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
+    constexpr int STAGE = BK * (BM + BN);
+    __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
+
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int tidb = tid - Stage<BN, BK>::kTailShift;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+
+    const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
+    set_flush_f32();
+    set_round_zero();
+
+    // kc_up / up: the same product and accumulator moved up by 2^60, where neither can flush
+    float kc = p.kc, rof = p.rof_a, rofp = p.rof_p, kc_up = p.kc * 0x1p60f, up = 0x1p60f;
+    uint32_t mask = p.mask_a;
+    asm volatile("" : "+v"(kc), "+v"(rof), "+v"(rofp), "+v"(mask), "+v"(kc_up), "+v"(up));
+
+    float acc[TM][TN];
+    uint32_t wof[TM][TN], wuf[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) { acc[i][j] = 0.0f; wof[i][j] = 0u; wuf[i][j] = 0u; }
+
+    uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
+    const int ntiles = (p.K + BK - 1) / BK;
+
+    fetch_tile<BM, BK>(p.A, p.M, p.K, m0, 0, p.ld_align, tid, ra);
+    fetch_tile<BN, BK>(p.B, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
+    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra);
+    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb);
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        const float* As = smem + (t & 1) * STAGE;
+        const float* Bs = As + BK * BM;
+        const bool more = (t + 1) < ntiles;
+        if (more) {
+            fetch_tile<BM, BK>(p.A, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
+            fetch_tile<BN, BK>(p.B, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
+        }
+#pragma unroll 4
+        for (int k = 0; k < BK; ++k) {
+            float a[TM], b[TN];
+            read_operands<TM, TN, BM, BN>(As, Bs, k, tx, ty, a, b);
+            // all tests produce 64-bit lane masks; the event logic runs on the scalar unit
+            uint64_t nza[TM], nzb[TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) nza[i] = __builtin_amdgcn_ballot_w64(a[i] != 0.0f);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) nzb[j] = __builtin_amdgcn_ballot_w64(b[j] != 0.0f);
+            float q[TM][TN], w[TM][TN], su[TM][TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) q[i][j] = a[i] * b[j];            // flushed below Q_prod's R_UF
+            if (PM == PM_FLUSH_CLAMP) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) q[i][j] = med3(q[i][j], -rofp, rofp);
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) { w[i][j] = q[i][j] * kc_up; su[i][j] = acc[i][j] * up; }   // exact, never flushed
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const uint64_t cancel = __builtin_amdgcn_ballot_w64(w[i][j] == -su[i][j]);   // exact sum is zero (or p = S = 0)
+                    float tsum = __builtin_fmaf(q[i][j], kc, acc[i][j]);       // truncated, flushed exact sum
+                    tsum = __uint_as_float(__float_as_uint(tsum) & mask);
+                    tsum = med3(tsum, -rof, rof);
+                    const uint64_t zq = __builtin_amdgcn_ballot_w64(q[i][j] == 0.0f);
+                    const uint64_t zt = __builtin_amdgcn_ballot_w64(tsum == 0.0f);
+                    const uint64_t of = __builtin_amdgcn_ballot_w64(__builtin_fabsf(tsum) == rof);
+                    const uint64_t uf = (zq & nza[i] & nzb[j]) | (zt & ~zq & ~cancel);
+                    acc[i][j] = tsum;
+                    // word <- 2 * word + (this lane's bit of the mask): add with the mask as carry-in
+                    asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof[i][j]) : "s"(of) : "vcc");
+                    asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wuf[i][j]) : "s"(uf) : "vcc");
+                }
+        }
+        {
+            const int valid = p.K - t * BK;
+            const uint32_t vmask = valid >= 32 ? 0xFFFFFFFFu : ((1u << valid) - 1u);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                const int m = m0 + ty * 4 + i;
+                if (m < p.M) {
+                    const int n = n0 + tx * 4;
+                    const int64_t off = ((int64_t)t * p.M + m) * p.N + n;
+                    uint32_t o[4], u[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) { o[j] = __builtin_bitreverse32(wof[i][j]) & vmask; u[j] = __builtin_bitreverse32(wuf[i][j]) & vmask; }
+                    if (p.c_vec && n + 3 < p.N) {
+                        if (p.of_mask) *reinterpret_cast<uint4*>(p.of_mask + off) = make_uint4(o[0], o[1], o[2], o[3]);
+                        if (p.uf_mask) *reinterpret_cast<uint4*>(p.uf_mask + off) = make_uint4(u[0], u[1], u[2], u[3]);
+                    } else {
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            if (n + j < p.N) {
+                                if (p.of_mask) p.of_mask[off + j] = o[j];
+                                if (p.uf_mask) p.uf_mask[off + j] = u[j];
+                            }
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < 4; ++j) { wof[i][j] = 0u; wuf[i][j] = 0u; }
+            }
+        }
+        if (more) {
+            float* Ad = smem + ((t + 1) & 1) * STAGE;
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra);
+            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb);
+        }
+        __syncthreads();
+    }
+    set_round_nearest();
+
+    if (p.C) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = m0 + ty * 4 + i;
+            if (m >= p.M) continue;
+            const int n = n0 + tx * 4;
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) v[j] = (acc[i][j] == 0.0f) ? 0.0f : __builtin_ldexpf(acc[i][j], p.out_exp);
+            float* dst = p.C + (int64_t)m * p.N + n;
+            if (p.c_vec && n + 3 < p.N) {
+                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (n + j < p.N) dst[j] = v[j];
+            }
+        }
+    }
+}
+
 // dst <- Q_acc(add + dst) for the 16 chains of a lane, with exact decisions.
 // Floor: one toward-zero add (the kernel runs in that mode).  Nearest-even: the add is done twice,
 // toward +inf and toward -inf; the smaller magnitude is the truncated sum and the two differ iff the
@@ -752,6 +908,12 @@ static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
 }
 
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
+    if (pl.kernel == KERNEL_FAST && pl.events) {
+        const dim3 grid(pl.grid_x, pl.grid_y), block(256);
+        if (pl.prod_mode == PM_FLUSH) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH>), grid, block, 0, st, pl.kp);
+        else                          hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH_CLAMP>), grid, block, 0, st, pl.kp);
+        return hipGetLastError();
+    }
     if (pl.kernel == KERNEL_FAST) {
         if (pl.tm == 2 && pl.tn == 2)
             return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<2, 2, LBA_ORDER_CHUNK16>(pl, st) : launch_fast<2, 2, LBA_ORDER_SEQ>(pl, st);

@@ -101,11 +101,12 @@ static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp) {
 // with few outputs cannot keep two waves on every SIMD with 16 chains per lane: between 512 and 1024
 // workgroups 2 x 4 measured 3-6 % faster, and up to 64 workgroups (a latency-bound launch) 2 x 2 is
 // about twice as fast.  The choice never changes a result.
-static void pick_tile(int64_t M, int64_t N, int kernel, int* tm, int* tn, int* bk) {
+static void pick_tile(int64_t M, int64_t N, int kernel, int events, int* tm, int* tn, int* bk) {
     *tm = 4; *tn = 4;
-    *bk = (kernel == KERNEL_GEN) ? 32 : LBA_FAST_BK;
+    *bk = (kernel == KERNEL_GEN || events) ? 32 : LBA_FAST_BK;
     if (kernel == KERNEL_FAST) {
         const int64_t blocks = ((M + 63) / 64) * ((N + 63) / 64);
+        if (events) return;                                    // the recompute kernel is 4 x 4 only
         if (blocks <= 64) { *tm = 2; *tn = 2; }
         else if (blocks > 512 && blocks <= 1024) *tm = 2;
     }
@@ -136,7 +137,10 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
     const int bpe = qp.bias < -20 ? -20 : qp.bias;
     const int bae = qa.bias < -20 ? -20 : qa.bias;
 
-    bool fast = !events && !prod_round;
+    bool fast = !prod_round;
+    // the recompute call has a scaled-domain kernel for floor rounding when Q_prod can underflow
+    // (its product-underflow test is the multiply's flush); anything else takes the general kernel
+    if (events && (qa.round != LBA_ROUND_FLOOR || !flush)) fast = false;
     if (fast && qa.round == LBA_ROUND_RNE && !rne_fast_ok(qp, qa, clamp)) fast = false;
     if (fast && (flush || clamp) && std::abs(bae - bpe) > 120) fast = false;   // kc must be an FP32 normal
 
@@ -158,6 +162,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
         if (p.prod_mode == PM_FLUSH_CLAMP) slots += 2;           // med3 on the product
         if (qa.round == LBA_ROUND_RNE) slots += (qa.man_bits == 7) ? 1 : 4;   // M = 7: cvt to bfloat16 replaces and; else bfe, add3
         p.valu_per_mac_x100 = slots * 100;
+        if (events)                                              // 5 full-rate + 7 half-rate instructions, + operand tests
+            p.valu_per_mac_x100 = 1950 + (p.prod_mode == PM_FLUSH_CLAMP ? 200 : 0);
         if (order == LBA_ORDER_CHUNK16)                          // add, and [, bfe, add3], zero per 16 steps
             p.valu_per_mac_x100 += (qa.round == LBA_ROUND_RNE ? 700 : 300) / 16;
     } else {
@@ -170,7 +176,7 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
         kp.prod_rne = (qp.round == LBA_ROUND_RNE) ? 1 : 0;
         p.valu_per_mac_x100 = 0;                           // filled by the launcher's table
     }
-    pick_tile(M, N, p.kernel, &p.tm, &p.tn, &p.bk);
+    pick_tile(M, N, p.kernel, p.events, &p.tm, &p.tn, &p.bk);
     kp.fast_thresh = -1.0f;
     kp.fast_thresh4 = -1.0f;
     if (p.kernel == KERNEL_FAST) {

@@ -108,7 +108,11 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     assert q(64, 64, 64, (5, 4, 15, 0), (4, 7, 7, 0))["kernel"] == 1      # product mantissa is rounded
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 3, 7, 0))["kernel"] == 0      # floor is exact at any M
     assert q(64, 64, 64, (5, 7, 15, 0), (7, 23, 64, 0))["kernel"] == 0
-    assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 1
+    # recompute call: scaled-domain kernel for floor when Q_prod can underflow, else the general one
+    assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 0
+    assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), with_masks=1)["kernel"] == 1
+    assert q(64, 64, 64, (6, 7, 20, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 1
+    assert q(64, 64, 64, (5, 4, 15, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 1
     # chunked order: forward only
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=1)["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 3, 7, 1), order=1)["kernel"] == 1
