@@ -38,17 +38,21 @@ extern "C" {
 /* One quantizer Q_{M,E,b} (Sec. 2.3).  bias is the paper's b (signed): R_UF = 2^-bias and the
  * top exponent is 2^exp_bits - bias - 1.  A per-tensor power-of-two scale of the operands is
  * folded by the caller into bias:  Q_{M,E,b}(2^-T y) = 2^-T Q_{M,E,b-T}(y).
- * Limits (else LBA_ERR_FORMAT): 1 <= man_bits <= 23, 2 <= exp_bits <= 7, round in {0, 1},
+ * Limits (else LBA_ERR_FORMAT): 1 <= man_bits <= 23, 2 <= exp_bits <= 7, round in {0, 1} (+ flag),
  * bias <= 126 and 2^exp_bits - bias - 1 <= 127, i.e. every value of the format is an FP32 normal. */
 typedef struct {
     int32_t exp_bits;   /* E */
     int32_t man_bits;   /* M */
     int32_t bias;       /* b */
-    int32_t round;      /* LBA_ROUND_FLOOR or LBA_ROUND_RNE */
+    int32_t round;      /* LBA_ROUND_FLOOR or LBA_ROUND_RNE, optionally | LBA_NO_UNDERFLOW */
 } lba_qfmt;
 
 enum { LBA_ROUND_FLOOR = 0,   /* truncate the magnitude's mantissa (the paper's LBA rounding) */
-       LBA_ROUND_RNE = 1 };   /* nearest, ties to even (the generic Round of the quantizer)   */
+       LBA_ROUND_RNE = 1,     /* nearest, ties to even (the generic Round of the quantizer)   */
+       LBA_NO_UNDERFLOW = 0x100 }; /* flag OR-ed into `round`: this quantizer never flushes to zero
+                                 (FMAq "excluding underflow events", the first fine-tuning stage of
+                                 Sec. 3 and Fig. 2b): values below R_UF keep an M-bit mantissa as
+                                 if the exponent range had no lower end; R_OF is unchanged */
 
 enum { LBA_ORDER_SEQ = 0,       /* k = 0 .. K-1 in one chain (App. D)                           */
        LBA_ORDER_CHUNK16 = 1 }; /* chunks of 16, then a chain over the chunk sums (Sec. 3, Fig. 1) */
@@ -66,7 +70,7 @@ enum { LBA_OK = 0,
  *   E4M3: 1 sign, 4 exponent (bias 7), 3 mantissa bits; e = 0 is subnormal, m * 2^-9; no inf.
  *   The two NaN codes 0x7f / 0xff are outside the contract; they are read as +-480.
  *   Zero results are stored as +0.0f.  K == 0 stores +0.0f everywhere; M*N == 0 does nothing.
- *   No alignment is required of A, B, C or of K.  Shape limits: M, N, K < 2^31, N <= 2^21.
+ *   No alignment is required of A, B, C or of K.  Shape limits: M, K <= 2^31 - 64, N <= 2^21.
  *   order: LBA_ORDER_SEQ, or LBA_ORDER_CHUNK16 = chunks of 16 consecutive k, each summed by its own
  *   chain from 0, then T_0 = 0, T_{j+1} = Q_acc(T_j + chunk_j) over the chunks in order (a short last
  *   chunk when 16 does not divide K; no Q_prod at the second level). */

@@ -12,6 +12,9 @@
 //       else sign(x) * 2^e * (1 + m),  e = floor(log2|x|),  m = 2^-M Round(2^M (|x| 2^-e - 1))
 //     Round is "floor" (truncate the magnitude; Sec. 3, "floor ... via bit-mask") or
 //     round-to-nearest-even (the generic Round of the equation).
+//     With the no-underflow flag (the first stage of the paper's fine-tuning runs FMAq "excluding
+//     underflow events", Sec. 3; Fig. 2b) the second case is dropped: values below R_UF keep their
+//     M-bit mantissa, as if the exponent range had no lower end.
 //   * FMAq(x, w, s) = Q_acc(Q_prod(x*w) + s), Sec. 3, Eq. (fmaq); x*w and the sum are EXACT reals,
 //     only the two quantizers round.
 //   * the sequential recursion S_0 = 0, S_{i+1} = FMAq(x_i, w_i, S_i), y = S_K over all K products
@@ -47,7 +50,7 @@ namespace {
 typedef unsigned __int128 u128;
 typedef unsigned _BitInt(320) u320;
 
-enum { ROUND_FLOOR = 0, ROUND_RNE = 1 };
+enum { ROUND_FLOOR = 0, ROUND_RNE = 1, FLAG_NO_UNDERFLOW = 0x100 };
 enum { ORDER_SEQ = 0, ORDER_CHUNK16 = 1 };
 enum { REF_OK = 0, REF_ERR_NULL = 1, REF_ERR_SHAPE = 2, REF_ERR_FORMAT = 3, REF_ERR_UNSUPPORTED = 4 };
 enum { EV_OF = 1, EV_UF = 2 };
@@ -57,7 +60,8 @@ struct Fmt { int32_t E, M, b, round; };
 bool fmt_ok(const Fmt& f) {
     if (f.M < 1 || f.M > 23) return false;
     if (f.E < 2 || f.E > 7) return false;
-    if (f.round != ROUND_FLOOR && f.round != ROUND_RNE) return false;
+    const int r = f.round & ~FLAG_NO_UNDERFLOW;
+    if (r != ROUND_FLOOR && r != ROUND_RNE) return false;
     if (f.b > 126) return false;                       // R_UF = 2^-b must be an FP32 normal
     if ((1 << f.E) - f.b - 1 > 127) return false;      // top exponent must be an FP32 exponent
     return true;
@@ -88,9 +92,11 @@ template <> inline int msb_index<u128>(u128 x) {
 // One quantizer bound to the call-wide unit 2^L: all thresholds as integers in that unit.
 template <class T> struct Quant {
     int L, M, round;
+    bool no_uf;
     T rof, ruf;
     void init(const Fmt& f, int L_) {
-        L = L_; M = f.M; round = f.round;
+        L = L_; M = f.M; round = f.round & ~FLAG_NO_UNDERFLOW;
+        no_uf = (f.round & FLAG_NO_UNDERFLOW) != 0;
         ruf = (T)1 << (-f.b - L);
         rof = (((T)1 << (f.M + 1)) - 1) << (top_exp(f) - f.M - L);
     }
@@ -98,7 +104,7 @@ template <class T> struct Quant {
     inline T apply(T x, int* ev) const {
         if (x == 0) return x;
         if (x >= rof) { *ev |= EV_OF; return rof; }
-        if (x < ruf)  { *ev |= EV_UF; return 0; }
+        if (x < ruf && !no_uf) { *ev |= EV_UF; return 0; }
         int drop = msb_index(x) - M;                   // bits below the M-bit mantissa
         if (drop <= 0) return x;
         T q = x >> drop;
@@ -304,13 +310,14 @@ int lba_ref_quantize(double x, lba_ref_qfmt q, double* out, int32_t* events) {
     double rof = std::ldexp(2.0 - std::ldexp(1.0, -f.M), top);
     double res;
     if (std::isinf(ax) || ax >= std::ldexp(1.0, top + 2)) { res = rof; ev = EV_OF; }   // far above R_OF
-    else if (ax < std::ldexp(1.0, -f.b - 2)) { res = 0.0; ev = EV_UF; }                // far below R_UF
+    else if (ax < std::ldexp(1.0, -f.b - 2) && !(f.round & FLAG_NO_UNDERFLOW)) { res = 0.0; ev = EV_UF; }   // far below R_UF
     else {
         int e2;
         double fr = std::frexp(ax, &e2);               // ax = fr * 2^e2, fr in [0.5, 1)
         uint64_t mant = (uint64_t)std::ldexp(fr, 53);  // exact 53-bit integer
         int lsb = e2 - 53;
         int L = std::min(lsb, -f.b - f.M);
+        if (top + 2 - L > 300) return REF_ERR_UNSUPPORTED;   // beyond the 320-bit carrier (no-underflow flag, tiny x)
         Quant<u320> qq; qq.init(f, L);
         u320 mag = (u320)mant << (lsb - L);
         mag = qq.apply(mag, &ev);

@@ -15,6 +15,7 @@ _SRC = os.path.join(_HERE, "lba_ref.cpp")
 _LIB = os.path.join(_HERE, "liblba_ref.so")
 
 FLOOR, RNE = 0, 1
+NO_UNDERFLOW = 0x100          # OR-ed into QFmt.round: this quantizer never flushes to zero
 ORDER_SEQ, ORDER_CHUNK16 = 0, 1
 EV_OF, EV_UF = 1, 2
 
@@ -25,8 +26,9 @@ class QFmt(ctypes.Structure):
                 ("bias", ctypes.c_int32), ("round", ctypes.c_int32)]
 
     def __repr__(self):
-        return "QFmt(E=%d, M=%d, b=%d, %s)" % (self.exp_bits, self.man_bits, self.bias,
-                                               "RNE" if self.round else "FLOOR")
+        return "QFmt(E=%d, M=%d, b=%d, %s%s)" % (self.exp_bits, self.man_bits, self.bias,
+                                                 "RNE" if self.round & 1 else "FLOOR",
+                                                 ", no underflow" if self.round & NO_UNDERFLOW else "")
 
 
 def _compiler():

@@ -42,7 +42,7 @@
 
 namespace lba {
 
-static const int64_t kMaxDim = 2147483647LL;
+static const int64_t kMaxDim = 2147483647LL - 63;   // tile origins and padded k stay below 2^31
 static const int64_t kMaxN = 1LL << 21;
 static const int kMaxProdExp = 17;     // 480 * 480 = 230400 < 2^18
 static const double kMaxProd = 230400.0;
@@ -56,7 +56,8 @@ int validate_shapes(int64_t M, int64_t N, int64_t K) {
 int validate_fmt(const lba_qfmt& q) {
     if (q.man_bits < 1 || q.man_bits > 23) return LBA_ERR_FORMAT;
     if (q.exp_bits < 2 || q.exp_bits > 7) return LBA_ERR_FORMAT;
-    if (q.round != LBA_ROUND_FLOOR && q.round != LBA_ROUND_RNE) return LBA_ERR_FORMAT;
+    const int r = q.round & ~LBA_NO_UNDERFLOW;
+    if (r != LBA_ROUND_FLOOR && r != LBA_ROUND_RNE) return LBA_ERR_FORMAT;
     if (q.bias > 126) return LBA_ERR_FORMAT;
     if ((1 << q.exp_bits) - q.bias - 1 > 127) return LBA_ERR_FORMAT;
     return LBA_OK;
@@ -83,11 +84,12 @@ static bool prod_clamp_possible(const lba_qfmt& qp) {
     return std::ldexp(2.0 - std::ldexp(1.0, -qp.man_bits), top_exp(qp)) <= kMaxProd;
 }
 
-static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp) {
+static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp, bool flush, bool nouf_a) {
     if (qa.man_bits > 10) return false;
     if (qa.man_bits < 7) return false;                     // an 8-bit product would leave the grid
     if (clamp && qp.man_bits > qa.man_bits) return false;  // a saturated product would
-    int bpe = prod_flush_possible(qp) ? qp.bias : 18;      // nonzero |p| >= 2^-bpe
+    if (nouf_a) return true;                               // no flush threshold to disturb
+    int bpe = flush ? qp.bias : 18;                        // nonzero |p| >= 2^-bpe
     if (bpe - qa.bias >= 24) return false;                 // a product could hide below 2^-150
     return true;
 }
@@ -112,12 +114,17 @@ static void pick_tile(int64_t M, int64_t N, int kernel, int events, int* tm, int
     }
 }
 
-int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfmt& qa,
+int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_qfmt& qa_in,
               int order, int events, Plan* out) {
     int rc = validate_shapes(M, N, K);
     if (rc != LBA_OK) return rc;
-    if ((rc = validate_fmt(qp)) != LBA_OK) return rc;
-    if ((rc = validate_fmt(qa)) != LBA_OK) return rc;
+    if ((rc = validate_fmt(qp_in)) != LBA_OK) return rc;
+    if ((rc = validate_fmt(qa_in)) != LBA_OK) return rc;
+    // the no-underflow flag is split off; qp / qa below carry the plain rounding code
+    lba_qfmt qp = qp_in, qa = qa_in;
+    const bool nouf_p = (qp.round & LBA_NO_UNDERFLOW) != 0, nouf_a = (qa.round & LBA_NO_UNDERFLOW) != 0;
+    qp.round &= ~LBA_NO_UNDERFLOW;
+    qa.round &= ~LBA_NO_UNDERFLOW;
     if (order != LBA_ORDER_SEQ && order != LBA_ORDER_CHUNK16) return LBA_ERR_UNSUPPORTED;
     if (order == LBA_ORDER_CHUNK16 && events) return LBA_ERR_UNSUPPORTED;   // planes of the chunked order: not built
 
@@ -129,26 +136,33 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
     KParams& kp = p.kp;
     kp.M = (int32_t)M; kp.N = (int32_t)N; kp.K = (int32_t)K;
 
-    const bool flush = prod_flush_possible(qp);
+    const bool flush = prod_flush_possible(qp) && !nouf_p;
     const bool clamp = prod_clamp_possible(qp);
     const bool prod_round = qp.man_bits < 7;
 
     // effective biases: below -20 every product / every sum underflows anyway
-    const int bpe = qp.bias < -20 ? -20 : qp.bias;
+    const int bpe = !flush ? (qp.bias > 18 ? qp.bias : 18) : (qp.bias < -20 ? -20 : qp.bias);
     const int bae = qa.bias < -20 ? -20 : qa.bias;
+    // kernel domains: the product's R_UF at 2^-126 (or, when Q_prod cannot flush, the smallest
+    // product 2^-18 at or above 2^-126); the accumulator's R_UF at 2^-126, or, with the
+    // no-underflow flag, a fixed 2^-60 that keeps every sum (a multiple of 2^-18) a normal number
+    const int c_p_dom = bpe - 126;
+    const int c_a_dom = nouf_a ? -60 : bae - 126;
 
     bool fast = !prod_round;
     // the recompute call has a scaled-domain kernel for floor rounding when Q_prod can underflow
     // (its product-underflow test is the multiply's flush); anything else takes the general kernel
     if (events && (qa.round != LBA_ROUND_FLOOR || !flush)) fast = false;
-    if (fast && qa.round == LBA_ROUND_RNE && !rne_fast_ok(qp, qa, clamp)) fast = false;
-    if (fast && (flush || clamp) && std::abs(bae - bpe) > 120) fast = false;   // kc must be an FP32 normal
+    if (fast && qa.round == LBA_ROUND_RNE && !rne_fast_ok(qp, qa, clamp, flush, nouf_a)) fast = false;
+    if (fast && (flush || clamp) && std::abs(c_a_dom - c_p_dom) > 120) fast = false;   // kc must be an FP32 normal
+    // the recompute kernel also forms p * kc * 2^60 and S * 2^60
+    if (fast && events && (std::abs(c_a_dom - c_p_dom) > 60 || top_exp(qa) + c_a_dom + 61 > 126)) fast = false;
 
     if (fast) {
         p.kernel = KERNEL_FAST;
         p.prod_mode = clamp ? PM_FLUSH_CLAMP : (flush ? PM_FLUSH : PM_IDENT);
-        const int c_a = bae - 126;                         // accumulator domain: R_UF -> 2^-126
-        const int c_p = (p.prod_mode == PM_IDENT) ? c_a : (bpe - 126);
+        const int c_a = c_a_dom;
+        const int c_p = (p.prod_mode == PM_IDENT) ? c_a : c_p_dom;
         kp.exp_a = c_p / 2;                                // split the product's scale over a and b
         kp.exp_b = c_p - kp.exp_a;
         kp.kc = (float)std::ldexp(1.0, c_a - c_p);
@@ -172,6 +186,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp, const lba_qfm
         kp.exp_a = 0; kp.exp_b = 0; kp.out_exp = 0; kp.kc = 1.0f;
         fill_quant(qa, 0, &kp.mask_a, &kp.half_a, &kp.sh_a, &kp.rof_a, &kp.ruf_a);
         fill_quant(qp, 0, &kp.mask_p, &kp.half_p, &kp.sh_p, &kp.rof_p, &kp.ruf_p);
+        if (nouf_p) kp.ruf_p = 0.0f;                       // nothing is below it
+        if (nouf_a) kp.ruf_a = 0.0f;
         kp.prod_round = prod_round ? 1 : 0;
         kp.prod_rne = (qp.round == LBA_ROUND_RNE) ? 1 : 0;
         p.valu_per_mac_x100 = 0;                           // filled by the launcher's table

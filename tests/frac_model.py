@@ -34,15 +34,23 @@ def rne_int(x):
     return fl
 
 
+NO_UNDERFLOW = 0x100
+
+
 def quant(x, E, M, b, rnd):
+    """rnd: 0 floor, 1 nearest-even; | NO_UNDERFLOW drops the flush-to-zero case."""
+    no_uf = bool(rnd & NO_UNDERFLOW)
+    rnd &= ~NO_UNDERFLOW
     r_of = F(2) ** (2 ** E - b - 1) * (2 - F(1, 2 ** M))
     r_uf = F(2) ** (-b)
     sgn = -1 if x < 0 else 1
     ax = abs(x)
     if ax >= r_of:
         return sgn * r_of, "OF"
-    if ax < r_uf:
-        return F(0), ("UF" if ax != 0 else "")
+    if ax == 0:
+        return F(0), ""
+    if ax < r_uf and not no_uf:
+        return F(0), "UF"
     e = floor_log2(ax)
     frac = (ax / F(2) ** e - 1) * 2 ** M
     m = rne_int(frac) if rnd == 1 else frac.numerator // frac.denominator

@@ -48,7 +48,7 @@ def test_mask_words():
     assert lb.lba_mask_words(0, 5, 33) == 0 and lb.lba_mask_words(4, 5, 0) == 0 and lb.lba_mask_words(-1, 5, 3) == 0
 
 
-BAD_FMTS = [(4, 0, 7, 0), (4, 24, 7, 0), (1, 7, 0, 0), (8, 7, 7, 0), (4, 7, 127, 0), (4, 7, 7, 2), (4, 7, 7, -1),
+BAD_FMTS = [(4, 7, 7, 0x102), (4, 7, 7, 0x200), (4, 0, 7, 0), (4, 24, 7, 0), (1, 7, 0, 0), (8, 7, 7, 0), (4, 7, 127, 0), (4, 7, 7, 2), (4, 7, 7, -1),
             (7, 7, -1, 0), (4, 7, -113, 0)]
 
 
@@ -65,7 +65,8 @@ def test_format_limits_are_rejected_before_any_device_work(bad):
 
 
 def test_edge_formats_are_accepted():
-    for ok in [(4, 7, 126, 0), (7, 23, 0, 1), (2, 1, -124, 0), (7, 7, 64, 1), (4, 7, -112, 0)]:
+    for ok in [(4, 7, 126, 0), (7, 23, 0, 1), (2, 1, -124, 0), (7, 7, 64, 1), (4, 7, -112, 0),
+               (4, 7, 7, 0x100), (4, 7, 7, 0x101)]:
         lb.lba_plan_query(8, 8, 8, ok, ok)
 
 
@@ -108,6 +109,9 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     assert q(64, 64, 64, (5, 4, 15, 0), (4, 7, 7, 0))["kernel"] == 1      # product mantissa is rounded
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 3, 7, 0))["kernel"] == 0      # floor is exact at any M
     assert q(64, 64, 64, (5, 7, 15, 0), (7, 23, 64, 0))["kernel"] == 0
+    # no-underflow flag: still the scaled kernel; a flagged Q_prod that cannot saturate is the identity
+    assert q(64, 64, 64, (5, 7, -1, 0x100), (4, 7, -9, 0x100))["prod_mode"] == 0
+    assert q(64, 64, 64, (5, 7, 15, 0x101), (4, 7, 7, 0x101))["kernel"] == 0
     # recompute call: scaled-domain kernel for floor when Q_prod can underflow, else the general one
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), with_masks=1)["kernel"] == 1

@@ -167,6 +167,36 @@ def test_chunked_order(ref, rnd):
         assert np.count_nonzero(got) > got.size // 2
 
 
+def test_no_underflow_flag(ref):
+    # FMAq "excluding underflow events" (Sec. 3): the flag on either quantizer or both, all kernels
+    NOUF = 0x100
+    rng = np.random.default_rng(80)
+    A = rand_codes(rng, (90, 150), 0, 12); B = rand_codes(rng, (70, 150), 0, 12)
+    A2 = rand_codes(rng, (40, 64), 0, 6); B2 = rand_codes(rng, (50, 64), 0, 6)          # mostly below R_UF
+    for (qp, qa), rnd, (fp, fa), order in itertools.product(
+            [FMT_PAPER[0], FMT_PAPER[1], FMT_PAPER[2], FMT_PAPER[4], FMT_ODD[0], FMT_ODD[1], FMT_SWEEP[0], FMT_SWEEP[11]],
+            (0, 1), ((NOUF, 0), (0, NOUF), (NOUF, NOUF)), (0, 1)):
+        check(ref, A, B, qp + (rnd | fp,), qa + (rnd | fa,), "no-underflow", order=order)
+        check(ref, A2, B2, qp + (rnd | fp,), qa + (rnd | fa,), "no-underflow small", order=order)
+    # event planes with the flag
+    for (qp, qa), rnd, (fp, fa) in itertools.product([FMT_PAPER[0], FMT_PAPER[1], FMT_ODD[1]], (0, 1),
+                                                     ((NOUF, 0), (0, NOUF), (NOUF, NOUF))):
+        qpf, qaf = qp + (rnd | fp,), qa + (rnd | fa,)
+        C, of, uf = lb.gemm_bwd(torch.from_numpy(A2).to(DEV), torch.from_numpy(B2).to(DEV), qpf, qaf)
+        torch.cuda.synchronize()
+        wc, wof, wuf = ref.gemm_bwd(A2, B2, fm(ref, qpf), fm(ref, qaf))
+        assert np.array_equal(bits(C.cpu().numpy()), bits(wc)), (qpf, qaf)
+        assert np.array_equal(of.cpu().numpy().view(np.uint32), wof), (qpf, qaf)
+        assert np.array_equal(uf.cpu().numpy().view(np.uint32), wuf), (qpf, qaf)
+    # at a workload's scale: ReLU x Kaiming with folded biases, the paper's first fine-tuning stage
+    A, ta = inputs.make_operand("relu", 300, 576, 6, 0)
+    B, tb = inputs.make_operand("normal", 128, 576, 6, 1, std=(2.0 / 576) ** 0.5)
+    qp, qa, _ = inputs.folded_formats(ta, tb, (4, 7, 12), (4, 7, 10), 0)
+    qp = qp[:3] + (qp[3] | NOUF,); qa = qa[:3] + (qa[3] | NOUF,)
+    for order in (0, 1):
+        check(ref, A.numpy(), B.numpy(), qp, qa, "no-underflow workload", order=order)
+
+
 def test_every_lane_block(ref):
     # output counts that select each lane block of the fast kernel (2x2, 2x4, 4x4), ragged on both
     # sides, both roundings and both orders; all outputs compared

@@ -14,6 +14,7 @@ import torch
 import frac_model as FM
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
+TINY = [0x00, 0x80, 0x01, 0x81, 0x08, 0x38, 0xB8, 0x39, 0x3F, 0x47, 0x58, 0xDA, 0x7E, 0xFE, 0x77, 0x0F]
 
 
 def rows(name):
@@ -139,6 +140,54 @@ def test_quantizer_against_fraction_model(ref):
         x = -x if rnd.random() < 0.5 else x
         want, _ = FM.quant(Fraction(x), E, M, b, r)
         assert Fraction(ref.quantize(x, ref.QFmt(E, M, b, r))) == want
+
+
+def test_no_underflow_flag(ref):
+    # FMAq "excluding underflow events" (Sec. 3, Fig. 2b): below R_UF the mantissa is still rounded
+    # to M bits instead of flushing; everything else is unchanged.  M7 pins: bfloat16 cast
+    # (nearest-even) and the float32 bit-mask (floor), far below R_UF = 2^-7.
+    g = torch.Generator().manual_seed(12)
+    x = torch.randn(3000, generator=g) * torch.exp2(torch.randint(-60, 8, (3000,), generator=g).float())
+    bf = x.bfloat16().float()
+    fl = (x.view(torch.int32) & ~0xFFFF).view(torch.float32)
+    fr = ref.QFmt(4, 7, 7, ref.RNE | ref.NO_UNDERFLOW)
+    ff = ref.QFmt(4, 7, 7, ref.FLOOR | ref.NO_UNDERFLOW)
+    for i in range(x.numel()):
+        xi = float(x[i])
+        if abs(xi) >= 509.0:
+            continue
+        assert ref.quantize(xi, fr) == float(bf[i])
+        assert ref.quantize(xi, ff) == float(fl[i])
+    assert ref.quantize(1e9, fr) == 510.0 and ref.quantize(-1e9, ff) == -510.0      # overflow unchanged
+    assert ref.quantize(2.0 ** -30, ref.QFmt(4, 7, 7, ref.RNE)) == 0.0              # without the flag: flushed
+    # a chain: sequential bfloat16 accumulation of small products (most are below 2^-7), no overflow
+    rng = np.random.default_rng(13)
+    A = _rand_codes(rng, (10, 100), 0, 7); B = _rand_codes(rng, (9, 100), 0, 7)
+    a = torch.from_numpy(A).view(torch.float8_e4m3fn).float()
+    b = torch.from_numpy(B).view(torch.float8_e4m3fn).float()
+    s = torch.zeros(10, 9)
+    for k in range(100):
+        s = (s + a[:, k:k + 1] * b[:, k:k + 1].T).bfloat16().float()
+    assert float(s.abs().max()) < 500
+    assert (torch.from_numpy(ref.gemm(A, B, fr, fr)) == s).all()
+    with_uf = ref.gemm(A, B, ref.QFmt(4, 7, 7, ref.RNE), ref.QFmt(4, 7, 7, ref.RNE))
+    assert not (torch.from_numpy(with_uf) == s).all()                              # the flag matters here
+    # no underflow events are reported by a flagged quantizer
+    _, of, uf = ref.gemm_bwd(A, B, fr, fr)
+    assert not uf.any()
+    # brute force against the Fraction model, flag on either or both quantizers
+    rnd_gen = random.Random(14)
+    for fp, fa in (((5, 7, 15, 0 | 0x100), (4, 7, 7, 0)), ((5, 7, 15, 1), (4, 7, 7, 1 | 0x100)),
+                   ((4, 4, 6, 1 | 0x100), (3, 4, 3, 0 | 0x100))):
+        for _ in range(150):
+            K = rnd_gen.randint(1, 5)
+            sa = [rnd_gen.choice(TINY) for _ in range(K)]; sb = [rnd_gen.choice(TINY) for _ in range(K)]
+            want, evs = FM.chain(sa, sb, fp, fa)
+            C, of, uf = ref.gemm_bwd(np.array([sa], dtype=np.uint8), np.array([sb], dtype=np.uint8),
+                                     ref.QFmt(*fp), ref.QFmt(*fa))
+            assert Fraction(float(C[0, 0])) == want
+            for k, (o, u_) in enumerate(evs):
+                assert (int(of[0, 0, 0]) >> k) & 1 == int(o) and (int(uf[0, 0, 0]) >> k) & 1 == int(u_)
 
 
 # ------------------------------------------------------------------------------------------
@@ -277,9 +326,6 @@ def test_chain_equals_sequential_half_accumulation(ref):
     f = ref.QFmt(5, 10, 14, ref.RNE)
     C = ref.gemm(A, B, f, f)
     assert (C.astype(np.float64) == s.astype(np.float64)).all()
-
-
-TINY = [0x00, 0x80, 0x01, 0x81, 0x08, 0x38, 0xB8, 0x39, 0x3F, 0x47, 0x58, 0xDA, 0x7E, 0xFE, 0x77, 0x0F]
 
 
 @pytest.mark.parametrize("rnd", [0, 1])
