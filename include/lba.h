@@ -78,6 +78,15 @@ int lba_gemm(const uint8_t* A, const uint8_t* B, float* C,
              int64_t M, int64_t N, int64_t K,
              lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream);
 
+/* `batch` independent forward products in one launch (batched matrix multiplication, e.g. the
+ * attention products of a transformer, which the paper also runs through its LBA GEMM, App. C.2):
+ * member z uses A + z*stride_a, B + z*stride_b (bytes) and C + z*stride_c (floats); a stride of 0
+ * shares that operand between members.  batch <= 65535; everything else as for lba_gemm. */
+int lba_gemm_batched(const uint8_t* A, const uint8_t* B, float* C, int64_t batch,
+                     int64_t stride_a, int64_t stride_b, int64_t stride_c,
+                     int64_t M, int64_t N, int64_t K,
+                     lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream);
+
 /* Forward product re-run for the fine-grained gradient estimators (Sec. 4, App. C.3, App. D): the
  * same deterministic chain, additionally writing one bit per FMAq step and event:
  *   OF_k = [ |Q_prod(x_k w_k) + S_k| >= R_OF of Q_acc ]         (1 - STE^OF of App. D)

@@ -49,6 +49,8 @@ def lib():
         L.lba_gemm.argtypes = [vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, i32, vp]
         L.lba_gemm_bwd.restype = ctypes.c_int
         L.lba_gemm_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, i32, vp]
+        L.lba_gemm_batched.restype = ctypes.c_int
+        L.lba_gemm_batched.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, lba_qfmt, lba_qfmt, i32, vp]
         L.lba_mask_words.restype = ctypes.c_size_t
         L.lba_mask_words.argtypes = [i64, i64, i64]
         L.lba_strerror.restype = ctypes.c_char_p
@@ -96,6 +98,13 @@ def lba_gemm_bwd(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, order=ORDER_SE
                               ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
 
 
+def lba_gemm_batched(A, B, C, batch, stride_a, stride_b, stride_c, M, N, K, qprod, qacc,
+                     order=ORDER_SEQ, hip_stream=None):
+    return lib().lba_gemm_batched(A, B, C, batch, stride_a, stride_b, stride_c, M, N, K, qfmt(qprod),
+                                  qfmt(qacc), order,
+                                  ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
 def lba_mask_words(M, N, K):
     return int(lib().lba_mask_words(M, N, K))
 
@@ -126,6 +135,24 @@ def gemm(A, B, qprod, qacc, order=ORDER_SEQ, out=None, stream=None):
     C = out if out is not None else torch.empty((M, N), dtype=torch.float32, device=A.device)
     _check(lib().lba_gemm(A.data_ptr() or None, B.data_ptr() or None, C.data_ptr() or None,
                           M, N, K, qfmt(qprod), qfmt(qacc), order, _stream(stream)))
+    return C
+
+
+def gemm_batched(A, B, qprod, qacc, order=ORDER_SEQ, stream=None):
+    """A [batch, M, K], B [batch, N, K] or [N, K] (shared) uint8 device tensors -> C [batch, M, N]."""
+    if A.dtype != torch.uint8 or B.dtype != torch.uint8 or not (A.is_cuda and B.is_cuda):
+        raise TypeError("A and B must be uint8 device tensors")
+    A = A.contiguous()
+    B = B.contiguous()
+    batch, M, K = A.shape
+    shared = B.dim() == 2
+    N = B.shape[-2]
+    if B.shape[-1] != K or (not shared and B.shape[0] != batch):
+        raise ValueError("shape mismatch")
+    C = torch.empty((batch, M, N), dtype=torch.float32, device=A.device)
+    _check(lib().lba_gemm_batched(A.data_ptr() or None, B.data_ptr() or None, C.data_ptr() or None, batch,
+                                  M * K, 0 if shared else N * K, M * N, M, N, K,
+                                  qfmt(qprod), qfmt(qacc), order, _stream(stream)))
     return C
 
 

@@ -20,6 +20,8 @@ struct KParams {
     uint32_t* of_mask;
     uint32_t* uf_mask;
     int32_t M, N, K;
+    int32_t batch;           // grid z; member z reads A + z*stride_a, B + z*stride_b, writes C + z*stride_c
+    int64_t stride_a, stride_b, stride_c;   // in elements (bytes for A and B, floats for C)
     int32_t ld_align;        // 16: every row start of A and B is 16-byte aligned; 1: any alignment
     int32_t c_vec;           // 1 if rows of C (and of the planes) can take 16-byte stores
     // operand decode: value(code) * 2^exp_a / 2^exp_b, folded into the lookup tables
@@ -54,7 +56,7 @@ int validate_fmt(const lba_qfmt& q);
 
 // Builds the plan (pointers in kp are left null).  Returns an lba status code.
 int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qprod, const lba_qfmt& qacc,
-              int order, int events, Plan* out);
+              int order, int events, Plan* out, int64_t batch = 1);
 
 }  // namespace lba
 #endif

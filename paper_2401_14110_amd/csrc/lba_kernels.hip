@@ -410,6 +410,10 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
     const int tx = tid & 15, ty = tid >> 4;
     const int tidb = tid - Stage<BN, BK>::kTailShift;       // B's pieces go to the last lanes
     const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    // batch member blockIdx.z (strides are 0 for a single GEMM)
+    const uint8_t* pA = p.A + (int64_t)blockIdx.z * p.stride_a;
+    const uint8_t* pB = p.B + (int64_t)blockIdx.z * p.stride_b;
+    float* pC = p.C ? p.C + (int64_t)blockIdx.z * p.stride_c : nullptr;
 
     const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
     set_flush_f32();
@@ -430,8 +434,8 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
     uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
     const int ntiles = (p.K + BK - 1) / BK;                    // K > 0 here; division by a constant
 
-    fetch_tile<BM, BK>(p.A, p.M, p.K, m0, 0, p.ld_align, tid, ra);
-    fetch_tile<BN, BK>(p.B, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
+    fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
+    fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
     store_tile_cvt<BM, BK>(smem, sc_a, tid, ra);
     store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb);
     __syncthreads();
@@ -441,8 +445,8 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
         const float* Bs = As + BK * BM;
         const bool more = (t + 1) < ntiles;
         if (more) {
-            fetch_tile<BM, BK>(p.A, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
-            fetch_tile<BN, BK>(p.B, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
+            fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
+            fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
         // (Chunked order: the test is on the second-level sums; a first-level sum starts from 0 and
         // is covered by the same bound.)
@@ -488,7 +492,7 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
             const float s = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
             v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);
         }
-        float* dst = p.C + (int64_t)m * p.N + n;
+        float* dst = pC + (int64_t)m * p.N + n;
         if (TN == 4 && p.c_vec && n + 3 < p.N) {
             *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[TN - 2], v[TN - 1]);
         } else if (TN == 2 && p.c_vec && n + 1 < p.N) {
@@ -522,6 +526,10 @@ __global__ void __launch_bounds__(256, 4) lba_fast_bwd_kernel(const KParams p) {
     const int tx = tid & 15, ty = tid >> 4;
     const int tidb = tid - Stage<BN, BK>::kTailShift;
     const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    // batch member blockIdx.z (strides are 0 for a single GEMM)
+    const uint8_t* pA = p.A + (int64_t)blockIdx.z * p.stride_a;
+    const uint8_t* pB = p.B + (int64_t)blockIdx.z * p.stride_b;
+    float* pC = p.C ? p.C + (int64_t)blockIdx.z * p.stride_c : nullptr;
 
     const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
     set_flush_f32();
@@ -542,8 +550,8 @@ __global__ void __launch_bounds__(256, 4) lba_fast_bwd_kernel(const KParams p) {
     uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
     const int ntiles = (p.K + BK - 1) / BK;
 
-    fetch_tile<BM, BK>(p.A, p.M, p.K, m0, 0, p.ld_align, tid, ra);
-    fetch_tile<BN, BK>(p.B, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
+    fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
+    fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
     store_tile_cvt<BM, BK>(smem, sc_a, tid, ra);
     store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb);
     __syncthreads();
@@ -553,8 +561,8 @@ __global__ void __launch_bounds__(256, 4) lba_fast_bwd_kernel(const KParams p) {
         const float* Bs = As + BK * BM;
         const bool more = (t + 1) < ntiles;
         if (more) {
-            fetch_tile<BM, BK>(p.A, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
-            fetch_tile<BN, BK>(p.B, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
+            fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
+            fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
 #pragma unroll 4
         for (int k = 0; k < BK; ++k) {
@@ -636,7 +644,7 @@ __global__ void __launch_bounds__(256, 4) lba_fast_bwd_kernel(const KParams p) {
     }
     set_round_nearest();
 
-    if (p.C) {
+    if (pC) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int m = m0 + ty * 4 + i;
@@ -645,7 +653,7 @@ __global__ void __launch_bounds__(256, 4) lba_fast_bwd_kernel(const KParams p) {
             float v[4];
 #pragma unroll
             for (int j = 0; j < 4; ++j) v[j] = (acc[i][j] == 0.0f) ? 0.0f : __builtin_ldexpf(acc[i][j], p.out_exp);
-            float* dst = p.C + (int64_t)m * p.N + n;
+            float* dst = pC + (int64_t)m * p.N + n;
             if (p.c_vec && n + 3 < p.N) {
                 *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
             } else {
@@ -750,6 +758,10 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    // batch member blockIdx.z (strides are 0 for a single GEMM)
+    const uint8_t* pA = p.A + (int64_t)blockIdx.z * p.stride_a;
+    const uint8_t* pB = p.B + (int64_t)blockIdx.z * p.stride_b;
+    float* pC = p.C ? p.C + (int64_t)blockIdx.z * p.stride_c : nullptr;
 
     lut_a[tid] = decode_entry(tid, p.exp_a);
     lut_b[tid] = decode_entry(tid, p.exp_b);
@@ -767,8 +779,8 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
     const int ntiles = (p.K + BK - 1) / BK;
     const uint32_t rofb = __float_as_uint(p.rof_a), rufb = __float_as_uint(p.ruf_a);
 
-    fetch_tile<BM, BK>(p.A, p.M, p.K, m0, 0, p.ld_align, tid, ra);
-    fetch_tile<BN, BK>(p.B, p.N, p.K, n0, 0, p.ld_align, tid, rb);
+    fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
+    fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tid, rb);
     __syncthreads();
     store_tile<BM, BK>(smem, lut_a, tid, ra);
     store_tile<BN, BK>(smem + BK * BM, lut_b, tid, rb);
@@ -779,8 +791,8 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
         const float* Bs = As + BK * BM;
         const bool more = (t + 1) < ntiles;
         if (more) {
-            fetch_tile<BM, BK>(p.A, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
-            fetch_tile<BN, BK>(p.B, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tid, rb);
+            fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
+            fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tid, rb);
         }
 #pragma unroll 2
         for (int k = 0; k < BK; ++k) {
@@ -843,7 +855,7 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
     }
     set_round_nearest();
 
-    if (p.C) {
+    if (pC) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
             const int m = m0 + ty * 4 + i;
@@ -855,7 +867,7 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
                 const float r = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
                 v[j] = (r == 0.0f) ? 0.0f : r;
             }
-            float* dst = p.C + (int64_t)m * p.N + n;
+            float* dst = pC + (int64_t)m * p.N + n;
             if (p.c_vec && n + 3 < p.N) {
                 *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
             } else {
@@ -881,7 +893,7 @@ __global__ void lba_fill_zero_kernel(float* C, int64_t n) {
 
 template <int TM, int TN, int ORDER>
 static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
-    const dim3 grid(pl.grid_x, pl.grid_y), block(256);
+    const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
     const KParams& kp = pl.kp;
 #define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<TM, TN, LBA_FAST_BK, PM, RND, ORDER>), grid, block, 0, st, kp)
     if (pl.round == LBA_ROUND_FLOOR) {
@@ -909,7 +921,7 @@ static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
 
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
     if (pl.kernel == KERNEL_FAST && pl.events) {
-        const dim3 grid(pl.grid_x, pl.grid_y), block(256);
+        const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
         if (pl.prod_mode == PM_FLUSH) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH>), grid, block, 0, st, pl.kp);
         else                          hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH_CLAMP>), grid, block, 0, st, pl.kp);
         return hipGetLastError();
@@ -921,7 +933,7 @@ static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
             return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<2, 4, LBA_ORDER_CHUNK16>(pl, st) : launch_fast<2, 4, LBA_ORDER_SEQ>(pl, st);
         return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<4, 4, LBA_ORDER_CHUNK16>(pl, st) : launch_fast<4, 4, LBA_ORDER_SEQ>(pl, st);
     }
-    const dim3 grid(pl.grid_x, pl.grid_y), block(256);
+    const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
     const KParams& kp = pl.kp;
     if (pl.order == LBA_ORDER_CHUNK16) {
         if (pl.round == LBA_ROUND_FLOOR) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, false, LBA_ORDER_CHUNK16>), grid, block, 0, st, kp);
@@ -944,28 +956,35 @@ static int gcd_align(const void* ptr, int64_t K) {
 
 static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
                int64_t M, int64_t N, int64_t K, const lba_qfmt& qprod, const lba_qfmt& qacc,
-               int order, int events, void* stream) {
+               int order, int events, void* stream,
+               int64_t batch = 1, int64_t stride_a = 0, int64_t stride_b = 0, int64_t stride_c = 0) {
     Plan pl;
-    int rc = make_plan(M, N, K, qprod, qacc, order, events, &pl);
+    if (batch < 0 || batch > 65535 || stride_a < 0 || stride_b < 0 || stride_c < 0) return LBA_ERR_SHAPE;
+    int rc = make_plan(M, N, K, qprod, qacc, order, events, &pl, batch);
     if (rc != LBA_OK) return rc;
-    if (M == 0 || N == 0) return LBA_OK;
+    if (M == 0 || N == 0 || batch == 0) return LBA_OK;
     if (!events && !C) return LBA_ERR_NULL;
     if (events && !of_mask && !uf_mask) return LBA_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;
     if (K == 0) {                                              // empty chains: S_0 = 0; no mask words
         if (C) {
             const int64_t n = M * N;
-            hipLaunchKernelGGL(lba_fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, C, n);
-            if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
+            for (int64_t z = 0; z < batch; ++z) {
+                hipLaunchKernelGGL(lba_fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                                   C + z * stride_c, n);
+                if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
+            }
         }
         return LBA_OK;
     }
     if (!A || !B) return LBA_ERR_NULL;
     KParams& kp = pl.kp;
     kp.A = A; kp.B = B; kp.C = C; kp.of_mask = of_mask; kp.uf_mask = uf_mask;
+    kp.batch = (int32_t)batch; kp.stride_a = stride_a; kp.stride_b = stride_b; kp.stride_c = stride_c;
     const int la = gcd_align(A, K), lb = gcd_align(B, K);
-    kp.ld_align = la < lb ? la : lb;
-    const bool c_ok = !C || ((uintptr_t)C % 16) == 0;
+    kp.ld_align = (la < lb ? la : lb);
+    if ((stride_a % 16) != 0 || (stride_b % 16) != 0) kp.ld_align = 1;
+    const bool c_ok = (!C || ((uintptr_t)C % 16) == 0) && (stride_c % 4) == 0;
     const bool o_ok = !of_mask || ((uintptr_t)of_mask % 16) == 0;
     const bool u_ok = !uf_mask || ((uintptr_t)uf_mask % 16) == 0;
     kp.c_vec = ((N % 4) == 0 && c_ok && o_ok && u_ok) ? 1 : 0;
@@ -988,6 +1007,14 @@ int lba_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask
                  int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
                  void* hip_stream) {
     return lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, order, 1, hip_stream);
+}
+
+int lba_gemm_batched(const uint8_t* A, const uint8_t* B, float* C, int64_t batch,
+                     int64_t stride_a, int64_t stride_b, int64_t stride_c,
+                     int64_t M, int64_t N, int64_t K,
+                     lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream) {
+    return lba::run(A, B, C, nullptr, nullptr, M, N, K, qprod, qacc, order, 0, hip_stream,
+                    batch, stride_a, stride_b, stride_c);
 }
 
 size_t lba_mask_words(int64_t M, int64_t N, int64_t K) {

@@ -197,6 +197,29 @@ def test_no_underflow_flag(ref):
         check(ref, A.numpy(), B.numpy(), qp, qa, "no-underflow workload", order=order)
 
 
+def test_batched_products(ref):
+    # attention-shaped batched products (scores Q.K^T and context P.V as A.B^T), a shared B, and
+    # strides that break 16-byte alignment
+    rng = np.random.default_rng(90)
+    for (batch, M, N, K), shared in (((12, 128, 128, 64), False), ((12, 128, 64, 128), False),
+                                     ((5, 70, 33, 50), False), ((7, 40, 66, 96), True)):
+        A = rand_codes(rng, (batch, M, K), 3, 11)
+        B = rand_codes(rng, (N, K) if shared else (batch, N, K), 3, 11)
+        for (qp, qa), rnd, order in itertools.product([FMT_PAPER[1], FMT_PAPER[3], FMT_ODD[1]], (0, 1), (0, 1)):
+            qpf, qaf = qp + (rnd,), qa + (rnd,)
+            C = lb.gemm_batched(torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV), qpf, qaf, order=order)
+            torch.cuda.synchronize()
+            got = C.cpu().numpy()
+            for z in range(batch):
+                want = ref.gemm(A[z], B if shared else B[z], fm(ref, qpf), fm(ref, qaf), order=order)
+                assert np.array_equal(bits(got[z]), bits(want)), (batch, M, N, K, shared, qpf, qaf, order, z)
+    # batch limits and the empty batch
+    d = torch.zeros((1, 8, 8), dtype=torch.uint8, device=DEV)
+    assert lb.lba_gemm_batched(d.data_ptr(), d.data_ptr(), None, 0, 64, 64, 64, 8, 8, 8, (5, 7, 15, 0), (4, 7, 7, 0)) == lb.OK
+    assert lb.lba_gemm_batched(d.data_ptr(), d.data_ptr(), None, 65536, 64, 64, 64, 8, 8, 8, (5, 7, 15, 0), (4, 7, 7, 0)) == lb.ERR_SHAPE
+    assert lb.lba_gemm_batched(d.data_ptr(), d.data_ptr(), None, 2, -1, 64, 64, 8, 8, 8, (5, 7, 15, 0), (4, 7, 7, 0)) == lb.ERR_SHAPE
+
+
 def test_every_lane_block(ref):
     # output counts that select each lane block of the fast kernel (2x2, 2x4, 4x4), ragged on both
     # sides, both roundings and both orders; all outputs compared
