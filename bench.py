@@ -9,7 +9,8 @@ floor rounding (the paper's LBA rounding, Sec. 3).  Inputs are synthetic and res
 before the timed region.  Prints ONE JSON line.
 
 Other workloads (for profiling, not the headline): --workload conv (ResNet-18 3x3 conv 64->64 at
-batch 32), bert (BERT-base linears at 4096 tokens), gemm4096 (4096^3).
+batch 32), bert (BERT-base linears at 4096 tokens), gemm4096 (4096^3; --acc E,M sweeps the accumulator
+format), config1 (one 64x64x256 GEMM: launch latency).
 """
 import argparse
 import json
@@ -31,14 +32,16 @@ PROD_FMT = (5, 7, 15)
 ACC_FMT = (4, 7, 7)
 
 
-def cpu_baseline(layer, qp, qa, C_gpu, order=0, budget_macs=2.0e9):
+def cpu_baseline(layer, qp, qa, C_gpu, order=0, threads=None, budget_macs=2.0e9):
     """The oracle, as it stands, on a bounded slab of one layer; also a parity check of the slab."""
     import numpy as np
     from oracle import lba_ref
+    if not threads:
+        threads = min(16, os.cpu_count() or 1)
+    budget_macs = budget_macs * min(1.0, threads / 8.0)           # keeps the leg near 10-30 s
     rows = int(min(layer["M"], max(1, budget_macs // (layer["N"] * layer["K"]))))
     A = layer["A"][:rows].cpu().numpy()
     B = layer["B"].cpu().numpy()
-    threads = min(16, os.cpu_count() or 1)
     t0 = time.perf_counter()
     want = lba_ref.gemm(A, B, lba_ref.QFmt(*qp), lba_ref.QFmt(*qa), order=order, nthreads=threads)
     dt = time.perf_counter() - t0
@@ -60,9 +63,12 @@ def main():
     ap.add_argument("--round", default="floor", choices=["floor", "rne"])
     ap.add_argument("--order", default="seq", choices=["seq", "chunk16"],
                     help="accumulation order: one sequential chain (default) or the paper's chunks of 16")
+    ap.add_argument("--acc", default=None, metavar="E,M",
+                    help="accumulator format with b = 2^(E-1)-1 instead of the 12-bit M7E4 (format sweeps)")
     ap.add_argument("--bwd", action="store_true",
                     help="time lba_gemm_bwd (forward chain + both event planes) instead of lba_gemm")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-threads", type=int, default=0, help="threads of the oracle leg (default: min(16, cores))")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the steps, run a 1 GiB fill and a 1 GiB add (references for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
@@ -81,11 +87,15 @@ def main():
     rnd = 0 if args.round == "floor" else 1
     order = 0 if args.order == "seq" else 1
 
+    acc_fmt = ACC_FMT
+    if args.acc:
+        e, m = (int(v) for v in args.acc.split(","))
+        acc_fmt = (e, m, 2 ** (e - 1) - 1)
     layers = inputs.make_workload(args.workload, dev)
     cmax = max(l["M"] * l["N"] for l in layers)
     Cbuf = torch.empty(cmax, dtype=torch.float32, device=dev)
     for l in layers:
-        l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], PROD_FMT, ACC_FMT, rnd)
+        l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], PROD_FMT, acc_fmt, rnd)
         l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, 1 if args.bwd else 0)
         l["C"] = Cbuf[: l["M"] * l["N"]].view(l["M"], l["N"])
         l["macs"] = l["M"] * l["N"] * l["K"]
@@ -96,9 +106,19 @@ def main():
         uf_buf = torch.empty(wmax, dtype=torch.int32, device=dev)
         stream = torch.cuda.current_stream().cuda_stream
 
+        if order == 1:
+            w2max = max(lb.lba_mask_words_level2(l["M"], l["N"], l["K"]) for l in layers)
+            of2_buf = torch.empty(w2max, dtype=torch.int32, device=dev)
+            uf2_buf = torch.empty(w2max, dtype=torch.int32, device=dev)
+
         def launch(l):
-            rc = lb.lba_gemm_bwd(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
-                                 uf_buf.data_ptr(), l["M"], l["N"], l["K"], l["qp"], l["qa"], order, stream)
+            if order == 1:
+                rc = lb.lba_gemm_bwd_chunked(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
+                                             uf_buf.data_ptr(), of2_buf.data_ptr(), uf2_buf.data_ptr(),
+                                             l["M"], l["N"], l["K"], l["qp"], l["qa"], stream)
+            else:
+                rc = lb.lba_gemm_bwd(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
+                                     uf_buf.data_ptr(), l["M"], l["N"], l["K"], l["qp"], l["qa"], order, stream)
             if rc != 0:
                 raise RuntimeError(lb.lba_strerror(rc))
     else:
@@ -178,9 +198,10 @@ def main():
         "data": "synthetic",
         "config": {"workload": {"resnet50": "ResNet-50 forward, batch 64, 224x224: 53 convs (im2col) + FC as 54 LBA GEMMs",
                                 "conv": "ResNet-18 3x3 conv 64->64, batch 32, 56x56 (M=100352,N=64,K=576)",
-                                "bert": "BERT-base linears, 4096 tokens", "gemm4096": "4096^3 GEMM"}[args.workload],
-                   "macs_per_step": total_macs, "qprod": "M7E5 b=15", "qacc": "M7E4 b=7 (12-bit)",
-                   "call": "lba_gemm_bwd (C + OF and UF planes)" if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b"},
+                                "bert": "BERT-base linears, 4096 tokens", "gemm4096": "4096^3 GEMM",
+                                "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}[args.workload],
+                   "macs_per_step": total_macs, "qprod": "M7E5 b=15", "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
+                   "call": ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else "lba_gemm_bwd (C + OF and UF planes)") if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b"},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline:
@@ -189,7 +210,7 @@ def main():
         l = layers[pick]
         launch(l)
         torch.cuda.synchronize()
-        out["cpu_baseline"] = cpu_baseline(l, l["qp"], l["qa"], l["C"], order)
+        out["cpu_baseline"] = cpu_baseline(l, l["qp"], l["qa"], l["C"], order, args.cpu_threads)
     print(json.dumps(out))
 
 

@@ -51,6 +51,10 @@ def lib():
         L.lba_gemm_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, i32, vp]
         L.lba_gemm_batched.restype = ctypes.c_int
         L.lba_gemm_batched.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, lba_qfmt, lba_qfmt, i32, vp]
+        L.lba_gemm_bwd_chunked.restype = ctypes.c_int
+        L.lba_gemm_bwd_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, vp]
+        L.lba_mask_words_level2.restype = ctypes.c_size_t
+        L.lba_mask_words_level2.argtypes = [i64, i64, i64]
         L.lba_mask_words.restype = ctypes.c_size_t
         L.lba_mask_words.argtypes = [i64, i64, i64]
         L.lba_strerror.restype = ctypes.c_char_p
@@ -105,8 +109,18 @@ def lba_gemm_batched(A, B, C, batch, stride_a, stride_b, stride_c, M, N, K, qpro
                                   ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
 
 
+def lba_gemm_bwd_chunked(A, B, C, of_mask, uf_mask, of_mask2, uf_mask2, M, N, K, qprod, qacc, hip_stream=None):
+    return lib().lba_gemm_bwd_chunked(A, B, C, of_mask, uf_mask, of_mask2, uf_mask2, M, N, K, qfmt(qprod),
+                                      qfmt(qacc),
+                                      ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
 def lba_mask_words(M, N, K):
     return int(lib().lba_mask_words(M, N, K))
+
+
+def lba_mask_words_level2(M, N, K):
+    return int(lib().lba_mask_words_level2(M, N, K))
 
 
 def lba_plan_query(M, N, K, qprod, qacc, order=ORDER_SEQ, with_masks=0):
@@ -170,3 +184,20 @@ def gemm_bwd(A, B, qprod, qacc, order=ORDER_SEQ, want_c=True, stream=None):
                               of.data_ptr() or None, uf.data_ptr() or None,
                               M, N, K, qfmt(qprod), qfmt(qacc), order, _stream(stream)))
     return C, of, uf
+
+
+def gemm_bwd_chunked(A, B, qprod, qacc, want_c=True, stream=None):
+    """Chunked order.  Returns (C or None, OF, UF, OF2, UF2): first-level planes [ceil(K/32), M, N] and
+    second-level planes [ceil(ceil(K/16)/32), M, N], int32 tensors."""
+    A, B = _ops(A, B)
+    M, K = A.shape
+    N = B.shape[0]
+    W = (K + 31) // 32
+    W2 = ((K + 15) // 16 + 31) // 32
+    C = torch.empty((M, N), dtype=torch.float32, device=A.device) if want_c else None
+    planes = [torch.empty((w, M, N), dtype=torch.int32, device=A.device) for w in (W, W, W2, W2)]
+    _check(lib().lba_gemm_bwd_chunked(A.data_ptr() or None, B.data_ptr() or None,
+                                      (C.data_ptr() or None) if want_c else None,
+                                      *[t.data_ptr() or None for t in planes],
+                                      M, N, K, qfmt(qprod), qfmt(qacc), _stream(stream)))
+    return (C, *planes)

@@ -19,6 +19,8 @@ struct KParams {
     float* C;
     uint32_t* of_mask;
     uint32_t* uf_mask;
+    uint32_t* of_mask2;      // second-level planes of the chunked order (bit j%32 of word j/32, chunk j)
+    uint32_t* uf_mask2;
     int32_t M, N, K;
     int32_t batch;           // grid z; member z reads A + z*stride_a, B + z*stride_b, writes C + z*stride_c
     int64_t stride_a, stride_b, stride_c;   // in elements (bytes for A and B, floats for C)

@@ -505,6 +505,43 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
     }
 }
 
+// Stores the 16 event words of a lane for plane word `word` (one word per chain): wof / wuf hold the
+// bits shifted in first-highest, `nbits` of them since the last store; bit 0 of the stored word is the
+// first of them and bits at or above `valid` are cleared.  The registers are zeroed.
+__device__ __forceinline__ void store_event_words(uint32_t* of_plane, uint32_t* uf_plane, int word, int nbits, int valid,
+                                                  uint32_t (&wof)[4][4], uint32_t (&wuf)[4][4],
+                                                  int m0, int n0, int tx, int ty, const KParams& p) {
+    const uint32_t vmask = valid >= 32 ? 0xFFFFFFFFu : ((1u << valid) - 1u);
+    const int up = 32 - nbits;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = m0 + ty * 4 + i;
+        if (m < p.M) {
+            const int n = n0 + tx * 4;
+            const int64_t off = ((int64_t)word * p.M + m) * p.N + n;
+            uint32_t o[4], u[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                o[j] = __builtin_bitreverse32(wof[i][j] << up) & vmask;
+                u[j] = __builtin_bitreverse32(wuf[i][j] << up) & vmask;
+            }
+            if (p.c_vec && n + 3 < p.N) {
+                if (of_plane) *reinterpret_cast<uint4*>(of_plane + off) = make_uint4(o[0], o[1], o[2], o[3]);
+                if (uf_plane) *reinterpret_cast<uint4*>(uf_plane + off) = make_uint4(u[0], u[1], u[2], u[3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (n + j < p.N) {
+                        if (of_plane) of_plane[off + j] = o[j];
+                        if (uf_plane) uf_plane[off + j] = u[j];
+                    }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) { wof[i][j] = 0u; wuf[i][j] = 0u; }
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // fast recompute kernel: forward chain + event planes (floor, sequential order, Q_prod can flush)
 // ---------------------------------------------------------------------------------------------
@@ -516,8 +553,12 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
 //       zero; the exact sum is zero only if p*kc == -S with S != 0, and then p*kc is a normal number
 //       that a plain multiply reproduces exactly
 // One 32-bit word per chain and k-tile: bits are shifted in (first k highest) and reversed at the end.
-template <int PM>
-__global__ void __launch_bounds__(256, 4) lba_fast_bwd_kernel(const KParams p) {
+// Chunked order: after the 16th step of a chunk the chunk sum S joins the second-level sum,
+// T <- Q_acc(T + S) with its own two event bits, and S restarts from 0.  T and S are values of Q_acc's
+// grid (zero or normal numbers), so T + S is exactly zero iff S == -T.  The extra registers (T and the
+// second-level words) are paid for with two instead of four waves per SIMD.
+template <int PM, int ORDER>
+__global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_fast_bwd_kernel(const KParams p) {
     constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
     constexpr int STAGE = BK * (BM + BN);
     __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
@@ -540,12 +581,15 @@ __global__ void __launch_bounds__(256, 4) lba_fast_bwd_kernel(const KParams p) {
     uint32_t mask = p.mask_a;
     asm volatile("" : "+v"(kc), "+v"(rof), "+v"(rofp), "+v"(mask), "+v"(kc_up), "+v"(up));
 
-    float acc[TM][TN];
-    uint32_t wof[TM][TN], wuf[TM][TN];
+    float acc[TM][TN], top[TM][TN];
+    uint32_t wof[TM][TN], wuf[TM][TN], wof2[TM][TN], wuf2[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) { acc[i][j] = 0.0f; wof[i][j] = 0u; wuf[i][j] = 0u; }
+        for (int j = 0; j < TN; ++j) {
+            acc[i][j] = 0.0f; wof[i][j] = 0u; wuf[i][j] = 0u;
+            top[i][j] = 0.0f; wof2[i][j] = 0u; wuf2[i][j] = 0u;
+        }
 
     uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
     const int ntiles = (p.K + BK - 1) / BK;
@@ -606,34 +650,31 @@ __global__ void __launch_bounds__(256, 4) lba_fast_bwd_kernel(const KParams p) {
                     asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof[i][j]) : "s"(of) : "vcc");
                     asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wuf[i][j]) : "s"(uf) : "vcc");
                 }
-        }
-        {
-            const int valid = p.K - t * BK;
-            const uint32_t vmask = valid >= 32 ? 0xFFFFFFFFu : ((1u << valid) - 1u);
+            if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int m = m0 + ty * 4 + i;
-                if (m < p.M) {
-                    const int n = n0 + tx * 4;
-                    const int64_t off = ((int64_t)t * p.M + m) * p.N + n;
-                    uint32_t o[4], u[4];
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < 4; ++j) { o[j] = __builtin_bitreverse32(wof[i][j]) & vmask; u[j] = __builtin_bitreverse32(wuf[i][j]) & vmask; }
-                    if (p.c_vec && n + 3 < p.N) {
-                        if (p.of_mask) *reinterpret_cast<uint4*>(p.of_mask + off) = make_uint4(o[0], o[1], o[2], o[3]);
-                        if (p.uf_mask) *reinterpret_cast<uint4*>(p.uf_mask + off) = make_uint4(u[0], u[1], u[2], u[3]);
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            if (n + j < p.N) {
-                                if (p.of_mask) p.of_mask[off + j] = o[j];
-                                if (p.uf_mask) p.uf_mask[off + j] = u[j];
-                            }
+                    for (int j = 0; j < TN; ++j) {
+                        const uint64_t cancel = __builtin_amdgcn_ballot_w64(acc[i][j] == -top[i][j]);
+                        float u = top[i][j] + acc[i][j];                        // truncated, flushed exact sum
+                        u = __uint_as_float(__float_as_uint(u) & mask);
+                        u = med3(u, -rof, rof);
+                        const uint64_t zu = __builtin_amdgcn_ballot_w64(u == 0.0f);
+                        const uint64_t of = __builtin_amdgcn_ballot_w64(__builtin_fabsf(u) == rof);
+                        const uint64_t uf = zu & ~cancel;
+                        top[i][j] = u;
+                        acc[i][j] = 0.0f;
+                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof2[i][j]) : "s"(of) : "vcc");
+                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wuf2[i][j]) : "s"(uf) : "vcc");
                     }
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) { wof[i][j] = 0u; wuf[i][j] = 0u; }
             }
+        }
+        store_event_words(p.of_mask, p.uf_mask, t, 32, p.K - t * BK, wof, wuf, m0, n0, tx, ty, p);
+        if (ORDER == LBA_ORDER_CHUNK16 && ((t & 15) == 15 || !more)) {
+            // two chunks per k-tile: a second-level word is complete after 16 tiles
+            const int chunks = (p.K + 15) >> 4;
+            store_event_words(p.of_mask2, p.uf_mask2, t >> 4, 2 * ((t & 15) + 1), chunks - 32 * (t >> 4),
+                              wof2, wuf2, m0, n0, tx, ty, p);
         }
         if (more) {
             float* Ad = smem + ((t + 1) & 1) * STAGE;
@@ -652,7 +693,10 @@ __global__ void __launch_bounds__(256, 4) lba_fast_bwd_kernel(const KParams p) {
             const int n = n0 + tx * 4;
             float v[4];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = (acc[i][j] == 0.0f) ? 0.0f : __builtin_ldexpf(acc[i][j], p.out_exp);
+            for (int j = 0; j < 4; ++j) {
+                const float s = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
+                v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);
+            }
             float* dst = pC + (int64_t)m * p.N + n;
             if (p.c_vec && n + 3 < p.N) {
                 *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
@@ -769,11 +813,14 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
     if (RND == LBA_ROUND_FLOOR) set_round_zero();
 
     float acc[TM][TN], top[TM][TN];                            // top: second-level sums (chunked order only)
-    uint32_t wof[TM][TN], wuf[TM][TN];
+    uint32_t wof[TM][TN], wuf[TM][TN], wof2[TM][TN], wuf2[TM][TN], no_uf1[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) { acc[i][j] = 0.0f; top[i][j] = 0.0f; wof[i][j] = 0u; wuf[i][j] = 0u; }
+        for (int j = 0; j < TN; ++j) {
+            acc[i][j] = 0.0f; top[i][j] = 0.0f; wof[i][j] = 0u; wuf[i][j] = 0u;
+            wof2[i][j] = 0u; wuf2[i][j] = 0u; no_uf1[i][j] = 0u;
+        }
 
     uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
     const int ntiles = (p.K + BK - 1) / BK;
@@ -810,7 +857,7 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
             gen_qadd_all<RND, EVENTS>(acc, pq, p, rofb, rufb, uf1, wof, wuf);
             if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
                 // second level (Sec. 3, Fig. 1 right): T <- Q_acc(T + S), S <- 0
-                gen_qadd_all<RND, false>(top, acc, p, rofb, rufb, uf1, wof, wuf);
+                gen_qadd_all<RND, EVENTS>(top, acc, p, rofb, rufb, no_uf1, wof2, wuf2);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -818,32 +865,11 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
             }
         }
         if (EVENTS) {
-            // bits were shifted in first-k-highest; reverse, drop padded steps, store word t
-            const int valid = p.K - t * BK;
-            const uint32_t vmask = valid >= 32 ? 0xFFFFFFFFu : ((1u << valid) - 1u);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const int m = m0 + ty * 4 + i;
-                if (m < p.M) {
-                    const int n = n0 + tx * 4;
-                    const int64_t off = ((int64_t)t * p.M + m) * p.N + n;
-                    uint32_t o[4], u[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) { o[j] = __builtin_bitreverse32(wof[i][j]) & vmask; u[j] = __builtin_bitreverse32(wuf[i][j]) & vmask; }
-                    if (p.c_vec && n + 3 < p.N) {
-                        if (p.of_mask) *reinterpret_cast<uint4*>(p.of_mask + off) = make_uint4(o[0], o[1], o[2], o[3]);
-                        if (p.uf_mask) *reinterpret_cast<uint4*>(p.uf_mask + off) = make_uint4(u[0], u[1], u[2], u[3]);
-                    } else {
-#pragma unroll
-                        for (int j = 0; j < 4; ++j)
-                            if (n + j < p.N) {
-                                if (p.of_mask) p.of_mask[off + j] = o[j];
-                                if (p.uf_mask) p.uf_mask[off + j] = u[j];
-                            }
-                    }
-                }
-#pragma unroll
-                for (int j = 0; j < 4; ++j) { wof[i][j] = 0u; wuf[i][j] = 0u; }
+            store_event_words(p.of_mask, p.uf_mask, t, 32, p.K - t * BK, wof, wuf, m0, n0, tx, ty, p);
+            if (ORDER == LBA_ORDER_CHUNK16 && ((t & 15) == 15 || !more)) {
+                const int chunks = (p.K + 15) >> 4;
+                store_event_words(p.of_mask2, p.uf_mask2, t >> 4, 2 * ((t & 15) + 1), chunks - 32 * (t >> 4),
+                                  wof2, wuf2, m0, n0, tx, ty, p);
             }
         }
         if (more) {
@@ -922,8 +948,13 @@ static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
     if (pl.kernel == KERNEL_FAST && pl.events) {
         const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
-        if (pl.prod_mode == PM_FLUSH) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH>), grid, block, 0, st, pl.kp);
-        else                          hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH_CLAMP>), grid, block, 0, st, pl.kp);
+        if (pl.order == LBA_ORDER_CHUNK16) {
+            if (pl.prod_mode == PM_FLUSH) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH, LBA_ORDER_CHUNK16>), grid, block, 0, st, pl.kp);
+            else                          hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH_CLAMP, LBA_ORDER_CHUNK16>), grid, block, 0, st, pl.kp);
+        } else {
+            if (pl.prod_mode == PM_FLUSH) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH, LBA_ORDER_SEQ>), grid, block, 0, st, pl.kp);
+            else                          hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH_CLAMP, LBA_ORDER_SEQ>), grid, block, 0, st, pl.kp);
+        }
         return hipGetLastError();
     }
     if (pl.kernel == KERNEL_FAST) {
@@ -935,7 +966,10 @@ static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
     }
     const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
     const KParams& kp = pl.kp;
-    if (pl.order == LBA_ORDER_CHUNK16) {
+    if (pl.order == LBA_ORDER_CHUNK16 && pl.events) {
+        if (pl.round == LBA_ROUND_FLOOR) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, true, LBA_ORDER_CHUNK16>), grid, block, 0, st, kp);
+        else                             hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, true, LBA_ORDER_CHUNK16>), grid, block, 0, st, kp);
+    } else if (pl.order == LBA_ORDER_CHUNK16) {
         if (pl.round == LBA_ROUND_FLOOR) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, false, LBA_ORDER_CHUNK16>), grid, block, 0, st, kp);
         else                             hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, false, LBA_ORDER_CHUNK16>), grid, block, 0, st, kp);
     } else if (pl.round == LBA_ROUND_FLOOR) {
@@ -957,14 +991,15 @@ static int gcd_align(const void* ptr, int64_t K) {
 static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
                int64_t M, int64_t N, int64_t K, const lba_qfmt& qprod, const lba_qfmt& qacc,
                int order, int events, void* stream,
-               int64_t batch = 1, int64_t stride_a = 0, int64_t stride_b = 0, int64_t stride_c = 0) {
+               int64_t batch = 1, int64_t stride_a = 0, int64_t stride_b = 0, int64_t stride_c = 0,
+               uint32_t* of_mask2 = nullptr, uint32_t* uf_mask2 = nullptr) {
     Plan pl;
     if (batch < 0 || batch > 65535 || stride_a < 0 || stride_b < 0 || stride_c < 0) return LBA_ERR_SHAPE;
     int rc = make_plan(M, N, K, qprod, qacc, order, events, &pl, batch);
     if (rc != LBA_OK) return rc;
     if (M == 0 || N == 0 || batch == 0) return LBA_OK;
     if (!events && !C) return LBA_ERR_NULL;
-    if (events && !of_mask && !uf_mask) return LBA_ERR_NULL;
+    if (events && !of_mask && !uf_mask && !of_mask2 && !uf_mask2) return LBA_ERR_NULL;
     hipStream_t st = (hipStream_t)stream;
     if (K == 0) {                                              // empty chains: S_0 = 0; no mask words
         if (C) {
@@ -980,6 +1015,7 @@ static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, 
     if (!A || !B) return LBA_ERR_NULL;
     KParams& kp = pl.kp;
     kp.A = A; kp.B = B; kp.C = C; kp.of_mask = of_mask; kp.uf_mask = uf_mask;
+    kp.of_mask2 = of_mask2; kp.uf_mask2 = uf_mask2;
     kp.batch = (int32_t)batch; kp.stride_a = stride_a; kp.stride_b = stride_b; kp.stride_c = stride_c;
     const int la = gcd_align(A, K), lb = gcd_align(B, K);
     kp.ld_align = (la < lb ? la : lb);
@@ -987,7 +1023,8 @@ static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, 
     const bool c_ok = (!C || ((uintptr_t)C % 16) == 0) && (stride_c % 4) == 0;
     const bool o_ok = !of_mask || ((uintptr_t)of_mask % 16) == 0;
     const bool u_ok = !uf_mask || ((uintptr_t)uf_mask % 16) == 0;
-    kp.c_vec = ((N % 4) == 0 && c_ok && o_ok && u_ok) ? 1 : 0;
+    const bool l2_ok = ((uintptr_t)of_mask2 % 16) == 0 && ((uintptr_t)uf_mask2 % 16) == 0;
+    kp.c_vec = ((N % 4) == 0 && c_ok && o_ok && u_ok && l2_ok) ? 1 : 0;
     return launch_plan(pl, st) == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
 }
 
@@ -1006,7 +1043,19 @@ int lba_gemm(const uint8_t* A, const uint8_t* B, float* C, int64_t M, int64_t N,
 int lba_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
                  int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
                  void* hip_stream) {
+    if (order == LBA_ORDER_CHUNK16) {                          // has second-level planes: lba_gemm_bwd_chunked
+        lba::Plan pl;
+        const int rc = lba::make_plan(M, N, K, qprod, qacc, order, 1, &pl);
+        return rc != LBA_OK ? rc : LBA_ERR_UNSUPPORTED;
+    }
     return lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, order, 1, hip_stream);
+}
+
+int lba_gemm_bwd_chunked(const uint8_t* A, const uint8_t* B, float* C,
+                         uint32_t* of_mask, uint32_t* uf_mask, uint32_t* of_mask2, uint32_t* uf_mask2,
+                         int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc, void* hip_stream) {
+    return lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, LBA_ORDER_CHUNK16, 1, hip_stream,
+                    1, 0, 0, 0, of_mask2, uf_mask2);
 }
 
 int lba_gemm_batched(const uint8_t* A, const uint8_t* B, float* C, int64_t batch,
@@ -1020,6 +1069,11 @@ int lba_gemm_batched(const uint8_t* A, const uint8_t* B, float* C, int64_t batch
 size_t lba_mask_words(int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
     return (size_t)((K + 31) / 32) * (size_t)M * (size_t)N;
+}
+
+size_t lba_mask_words_level2(int64_t M, int64_t N, int64_t K) {
+    if (M <= 0 || N <= 0 || K <= 0) return 0;
+    return (size_t)(((K + 15) / 16 + 31) / 32) * (size_t)M * (size_t)N;
 }
 
 const char* lba_strerror(int code) {

@@ -24,8 +24,9 @@
 //                  leading bit; the larger operand then decides the neighbourhood, and if it lies
 //                  ON the M+1-bit grid the sum stays within 2^(e-M-2) of a grid point provided
 //                  the smaller operand has at most 22-M significant bits.  Hence the conditions
-//                  checked in rne_fast_ok(): M <= 10; products on the accumulator grid (8 <= M+1);
-//                  a saturated product (M_prod+1 bits) on it too or impossible; and the flush
+//                  checked in rne_fast_ok(): M <= 10; products on the accumulator grid (8 <= M+1),
+//                  or else every inexact 24-bit sum beyond R_OF; a saturated product
+//                  (M_prod+1 bits) within the same bit budget or impossible; and the flush
 //                  decision near 2^-126 unaffected (no sum can sit within 2^-150 below 2^-126).
 //       Everything else falls to GEN.
 //
@@ -37,6 +38,8 @@
 
 #include <cmath>
 #include <cstring>
+
+#include <algorithm>
 
 #include "lba_internal.h"
 
@@ -84,10 +87,23 @@ static bool prod_clamp_possible(const lba_qfmt& qp) {
     return std::ldexp(2.0 - std::ldexp(1.0, -qp.man_bits), top_exp(qp)) <= kMaxProd;
 }
 
+// Nearest-even in the scaled kernel rounds twice (FP32's 24 bits, then M+1 bits).  That equals one
+// rounding unless the 24-bit result is inexact and lands on a midpoint of the (M+1)-bit grid.
+//  * M >= 7: a product (at most 8 significant bits, M_prod+1 when saturated) lies on the accumulator's
+//    grid, and an inexact sum stays clear of every midpoint (M <= 10).
+//  * M < 7: a product can itself be a midpoint, and a partial sum S too small for the 24-bit window
+//    would be lost before the tie is broken.  Such an S has its lowest bit at or above
+//    l = max(-18, -b - M) (every sum is a multiple of 2^-18; S >= 2^-b has M+1 bits), so the sum is
+//    inexact only from 2^(24+l) on; when that is above R_OF the result saturates whatever the rounding.
 static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp, bool flush, bool nouf_a) {
     if (qa.man_bits > 10) return false;
-    if (qa.man_bits < 7) return false;                     // an 8-bit product would leave the grid
-    if (clamp && qp.man_bits > qa.man_bits) return false;  // a saturated product would
+    if (qa.man_bits >= 7) {
+        if (clamp && qp.man_bits > qa.man_bits) return false;
+    } else {
+        if (clamp && qp.man_bits > 7) return false;        // keep every product within 8 bits
+        const int low = nouf_a ? -18 : std::max(-18, -qa.bias - qa.man_bits);
+        if (24 + low < top_exp(qa) + 1) return false;
+    }
     if (nouf_a) return true;                               // no flush threshold to disturb
     int bpe = flush ? qp.bias : 18;                        // nonzero |p| >= 2^-bpe
     if (bpe - qa.bias >= 24) return false;                 // a product could hide below 2^-150
@@ -126,7 +142,6 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     qp.round &= ~LBA_NO_UNDERFLOW;
     qa.round &= ~LBA_NO_UNDERFLOW;
     if (order != LBA_ORDER_SEQ && order != LBA_ORDER_CHUNK16) return LBA_ERR_UNSUPPORTED;
-    if (order == LBA_ORDER_CHUNK16 && events) return LBA_ERR_UNSUPPORTED;   // planes of the chunked order: not built
 
     Plan p;
     std::memset(&p, 0, sizeof(p));
@@ -179,7 +194,7 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         if (events)                                              // 5 full-rate + 7 half-rate instructions, + operand tests
             p.valu_per_mac_x100 = 1950 + (p.prod_mode == PM_FLUSH_CLAMP ? 200 : 0);
         if (order == LBA_ORDER_CHUNK16)                          // add, and [, bfe, add3], zero per 16 steps
-            p.valu_per_mac_x100 += (qa.round == LBA_ROUND_RNE ? 700 : 300) / 16;
+            p.valu_per_mac_x100 += (events ? 1300 : (qa.round == LBA_ROUND_RNE ? 700 : 300)) / 16;
     } else {
         p.kernel = KERNEL_GEN;
         p.prod_mode = PM_FLUSH_CLAMP;

@@ -172,7 +172,8 @@ def make_workload(name, device="cpu"):
     B [N,K] uint8 codes on `device`, ta / tb the power-of-two scale exponents.  Layers of equal
     operand shape share data.  Workloads: 'resnet50' (ResNet-50 forward, batch 64, 224x224: 54 GEMMs),
     'conv' (ResNet-18 3x3 conv 64->64 at batch 32), 'bert' (BERT-base linears, 4096 tokens),
-    'gemm4096' (4096^3, N(0,1) operands)."""
+    'gemm4096' (4096^3, N(0,1) operands), 'config1' (M=N=64, K=256, N(0,1) operands scaled to
+    max|x| = 448, seed 0)."""
     if name == "resnet50":
         layers = resnet50_gemms(batch=64, image=224)
         seed = 2
@@ -185,10 +186,14 @@ def make_workload(name, device="cpu"):
     elif name == "gemm4096":
         layers = [("gemm4096", 4096, 4096, 4096)]
         seed = 4
+    elif name == "config1":
+        layers = [("gemm64", 64, 64, 256)]
+        seed = 0
     else:
         raise ValueError("unknown workload %r" % name)
     # one operand tensor per distinct (rows, K) and role: layers of equal shape share data
     cache_a, cache_b, out = {}, {}, []
+    mode = "exact448" if name == "config1" else "pow2"
     for idx, (lname, M, N, K) in enumerate(layers):
         if (M, K) not in cache_a:
             if name == "resnet50":
@@ -197,7 +202,8 @@ def make_workload(name, device="cpu"):
                 kind = "relu"
             else:
                 kind = "normal"
-            cache_a[(M, K)] = make_operand(kind, M, K, seed, 2 * len(cache_a), device=device)
+            cache_a[(M, K)] = make_operand(kind, M, K, seed, 2 * len(cache_a), device=device,
+                                           scale_mode=mode)
         if (N, K) not in cache_b:
             if name in ("resnet50", "conv"):
                 std = (2.0 / K) ** 0.5
@@ -206,9 +212,11 @@ def make_workload(name, device="cpu"):
             else:
                 std = 1.0
             cache_b[(N, K)] = make_operand("normal", N, K, seed, 2 * len(cache_b) + 1,
-                                                  device=device, std=std)
+                                           device=device, std=std, scale_mode=mode)
         A, ta = cache_a[(M, K)]
         B, tb = cache_b[(N, K)]
+        if mode == "exact448":
+            ta = tb = 0                            # formats are given in code units there
         out.append(dict(name=lname, M=M, N=N, K=K, A=A, B=B, ta=ta, tb=tb))
     return out
 

@@ -76,9 +76,14 @@ def chain(a_codes, b_codes, qp, qa):
     return s, evs
 
 
-def chain_chunk16(a_codes, b_codes, qp, qa):
+def chain_chunk16(a_codes, b_codes, qp, qa, with_events=False):
+    """Two-level order: chains of 16 from zero, then a chain over the chunk sums (no Q_prod there).
+    With events: (value, [(OF, UF) per step k], [(OF, UF) per chunk j])."""
     t = F(0)
+    ev1, ev2 = [], []
     for k0 in range(0, len(a_codes), 16):
-        c, _ = chain(a_codes[k0:k0 + 16], b_codes[k0:k0 + 16], qp, qa)
-        t, _ = quant(t + c, *qa)
-    return t
+        c, evs = chain(a_codes[k0:k0 + 16], b_codes[k0:k0 + 16], qp, qa)
+        ev1.extend(evs)
+        t, ev = quant(t + c, *qa)
+        ev2.append((ev == "OF", ev == "UF"))
+    return (t, ev1, ev2) if with_events else t

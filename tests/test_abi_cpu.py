@@ -46,6 +46,8 @@ def test_mask_words():
     assert lb.lba_mask_words(4, 5, 33) == 40
     assert lb.lba_mask_words(4096, 4096, 4096) == 128 * 4096 * 4096
     assert lb.lba_mask_words(0, 5, 33) == 0 and lb.lba_mask_words(4, 5, 0) == 0 and lb.lba_mask_words(-1, 5, 3) == 0
+    assert lb.lba_mask_words_level2(4, 5, 1) == 20 and lb.lba_mask_words_level2(4, 5, 512) == 20
+    assert lb.lba_mask_words_level2(4, 5, 513) == 40 and lb.lba_mask_words_level2(4, 0, 513) == 0
 
 
 BAD_FMTS = [(4, 7, 7, 0x102), (4, 7, 7, 0x200), (4, 0, 7, 0), (4, 24, 7, 0), (1, 7, 0, 0), (8, 7, 7, 0), (4, 7, 127, 0), (4, 7, 7, 2), (4, 7, 7, -1),
@@ -102,7 +104,7 @@ def test_plan_picks_the_scaled_kernel_for_the_paper_formats():
 
 def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     q = lb.lba_plan_query
-    assert q(64, 64, 64, (5, 7, 15, 1), (4, 3, 7, 1))["kernel"] == 1      # nearest-even, M_acc < 7
+    assert q(64, 64, 64, (5, 7, 15, 1), (5, 3, 15, 1))["kernel"] == 1     # nearest-even, M_acc < 7, inexact sums below R_OF
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 11, 7, 1))["kernel"] == 1     # nearest-even, M_acc > 10
     assert q(64, 64, 64, (5, 9, 15, 1), (4, 8, 7, 1))["kernel"] == 1      # saturated product off the grid
     assert q(64, 64, 64, (5, 7, 40, 1), (4, 7, -9, 1))["kernel"] == 1     # products far below R_UF of Q_acc
@@ -117,10 +119,15 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), with_masks=1)["kernel"] == 1
     assert q(64, 64, 64, (6, 7, 20, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 1
     assert q(64, 64, 64, (5, 4, 15, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 1
-    # chunked order: forward only
+    # chunked order, forward and recompute
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=1)["kernel"] == 0
-    assert q(64, 64, 64, (5, 7, 15, 1), (4, 3, 7, 1), order=1)["kernel"] == 1
-    with pytest.raises(lb.LbaError):
-        q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=1, with_masks=1)
+    assert q(64, 64, 64, (5, 7, 15, 1), (5, 3, 15, 1), order=1)["kernel"] == 1
+    assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=1, with_masks=1)["kernel"] == 0
+    assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), order=1, with_masks=1)["kernel"] == 1
+    # nearest-even below 7 mantissa bits: scaled kernel only when every inexact FP32 sum overflows
+    assert q(64, 64, 64, (5, 7, 15, 1), (4, 3, 7, 1))["kernel"] == 0
+    assert q(64, 64, 64, (5, 7, 15, 1), (4, 6, 7, 1))["kernel"] == 0
+    assert q(64, 64, 64, (5, 7, 15, 1), (5, 6, 15, 1))["kernel"] == 1
+    assert q(64, 64, 64, (4, 9, 7, 1), (4, 6, 7, 1))["kernel"] == 1       # a saturated product has 10 bits
     with pytest.raises(lb.LbaError):
         q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=2)

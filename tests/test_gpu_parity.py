@@ -305,3 +305,83 @@ def test_event_planes_and_c_of_the_recompute_call(ref):
     _, wof, wuf = ref.gemm_bwd(A.cpu().numpy(), B.cpu().numpy(), ref.QFmt(5, 7, 15, 0), ref.QFmt(4, 7, 7, 0))
     assert C is None and np.array_equal(of.cpu().numpy().view(np.uint32), wof)
     assert np.array_equal(uf.cpu().numpy().view(np.uint32), wuf)
+
+
+def test_nearest_even_below_seven_mantissa_bits_keeps_ties_right(ref):
+    # K = 2 chains: a first product of any small size, then every product of two codes (many are exact
+    # midpoints of a 4..7-bit grid): the tie must be broken by the small partial sum, also when that sum
+    # is far below the 24-bit window of the add.  Formats on both sides of the planner's exactness rule.
+    rng = np.random.default_rng(70)
+    codes = np.arange(256, dtype=np.uint8)
+    codes = np.where((codes & 0x7F) == 0x7F, codes & 0xFE, codes).astype(np.uint8)
+    A = np.stack([rand_codes(rng, (256,), 0, 6), codes], axis=1)
+    B = np.stack([rand_codes(rng, (256,), 0, 6), codes], axis=1)
+    kernels = set()
+    for qp, qa in [((5, 7, 15), (4, 3, 7)), ((5, 7, 15), (4, 6, 7)), ((5, 7, 18), (4, 5, 7)), ((5, 7, 15), (5, 4, 15)),
+                   ((5, 7, 15), (6, 6, 31)), ((6, 7, 20), (5, 3, -2)), ((5, 7, 4), (4, 4, -6)), ((4, 7, 7), (4, 5, 7)),
+                   ((4, 9, 7), (4, 6, 7)), ((5, 7, 15), (3, 6, 2)), ((5, 7, 15), (7, 5, 40))]:
+        qpf, qaf = qp + (1,), qa + (1,)
+        kernels.add(lb.lba_plan_query(256, 256, 2, qpf, qaf)["kernel"])
+        check(ref, A, B, qpf, qaf, "rne small M, K=2")
+        check(ref, A, B, qpf, qaf, "rne small M, K=2, chunked", order=1)
+        check(ref, A, B, qpf, (qa[0], qa[1], qa[2], 0x101), "rne small M, no underflow")
+    assert kernels == {0, 1}
+    # longer chains with the full exponent range
+    A = rand_codes(rng, (130, 100)); B = rand_codes(rng, (70, 100))
+    for M in (3, 4, 5, 6):
+        for E, b in ((4, 7), (4, 0), (4, -6), (5, 15), (3, 3)):
+            check(ref, A, B, (5, 7, 15, 1), (E, M, b, 1), "rne small M")
+
+
+def test_event_planes_of_the_chunked_order(ref):
+    # first-level planes (bit k: step k of its own chunk's chain) and second-level planes (bit j: the add
+    # of chunk j) for K below, at and across chunk, tile and second-level-word (512) boundaries; scaled
+    # and general kernels; ragged M, N
+    rng = np.random.default_rng(80)
+    cases = [((5, 3, 1), 0, 15), ((20, 9, 16), 3, 12), ((33, 70, 17), 3, 12), ((70, 66, 100), 0, 15),
+             ((64, 64, 512), 4, 11), ((37, 68, 530), 2, 12), ((16, 24, 1100), 5, 10)]
+    fmts = [FMT_PAPER[0], FMT_PAPER[1], FMT_PAPER[2], FMT_ODD[1], FMT_ODD[0], FMT_SWEEP[1]]
+    seen = np.zeros(4, dtype=np.int64)
+    kernels = set()
+    for (M, N, K), lo, hi in cases:
+        A = rand_codes(rng, (M, K), lo, hi); B = rand_codes(rng, (N, K), lo, hi)
+        tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+        for (qp, qa), rnd in itertools.product(fmts, (0, 1)):
+            qpf, qaf = qp + (rnd,), qa + (rnd,)
+            kernels.add(lb.lba_plan_query(M, N, K, qpf, qaf, 1, 1)["kernel"])
+            got = lb.gemm_bwd_chunked(tA, tB, qpf, qaf)
+            torch.cuda.synchronize()
+            want = ref.gemm_bwd(A, B, fm(ref, qpf), fm(ref, qaf), order=ref.ORDER_CHUNK16, level2=True)
+            assert np.array_equal(bits(got[0].cpu().numpy()), bits(want[0])), (M, N, K, qpf, qaf)
+            for name, g, w in zip(("OF", "UF", "OF2", "UF2"), got[1:], want[1:]):
+                assert np.array_equal(g.cpu().numpy().view(np.uint32), w), (M, N, K, qpf, qaf, name)
+            seen += [int(np.count_nonzero(w)) for w in want[1:]]
+            assert np.array_equal(bits(run_gpu(A, B, qpf, qaf, order=1)), bits(want[0]))
+    assert kernels == {0, 1} and (seen[:3] > 0).all(), seen
+    # a second-level underflow (cancellation between two grid values): chunk 0 = 1.5 * 2^-7, chunk 1 = -2^-7
+    A = np.zeros((3, 20), dtype=np.uint8); B = np.zeros((2, 20), dtype=np.uint8)
+    A[:, 0], B[:, 0] = 0x3C, 0x04
+    A[:, 16], B[:, 16] = 0xB8, 0x04
+    for rnd in (0, 1):
+        qpf, qaf = (5, 7, 15, rnd), (4, 7, 7, rnd)
+        got = lb.gemm_bwd_chunked(torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV), qpf, qaf)
+        torch.cuda.synchronize()
+        want = ref.gemm_bwd(A, B, fm(ref, qpf), fm(ref, qaf), order=ref.ORDER_CHUNK16, level2=True)
+        assert (want[4] == 2).all()
+        for g, w in zip(got[1:], want[1:]):
+            assert np.array_equal(g.cpu().numpy().view(np.uint32), w)
+        assert (got[0].cpu().numpy() == 0).all()
+    # a single plane, no C; lba_gemm_bwd itself refuses the chunked order
+    tA = torch.from_numpy(rand_codes(rng, (20, 40))).to(DEV); tB = torch.from_numpy(rand_codes(rng, (24, 40))).to(DEV)
+    of2 = torch.full((1, 20, 24), -1, dtype=torch.int32, device=DEV)
+    rc = lb.lba_gemm_bwd_chunked(tA.data_ptr(), tB.data_ptr(), None, None, None, of2.data_ptr(), None, 20, 24, 40,
+                                 (5, 7, 15, 0), (4, 7, 7, 0))
+    torch.cuda.synchronize()
+    assert rc == lb.OK
+    want = ref.gemm_bwd(tA.cpu().numpy(), tB.cpu().numpy(), ref.QFmt(5, 7, 15, 0), ref.QFmt(4, 7, 7, 0),
+                        order=ref.ORDER_CHUNK16, level2=True)
+    assert np.array_equal(of2.cpu().numpy().view(np.uint32), want[3])
+    assert lb.lba_gemm_bwd_chunked(tA.data_ptr(), tB.data_ptr(), None, None, None, None, None, 20, 24, 40,
+                                   (5, 7, 15, 0), (4, 7, 7, 0)) == lb.ERR_NULL
+    assert lb.lba_gemm_bwd(tA.data_ptr(), tB.data_ptr(), None, of2.data_ptr(), None, 20, 24, 40,
+                           (5, 7, 15, 0), (4, 7, 7, 0), order=1) == lb.ERR_UNSUPPORTED

@@ -407,6 +407,51 @@ def test_chunked_order(ref):
                 assert Fraction(float(C[i, j])) == want
 
 
+def test_chunked_order_event_planes(ref):
+    """First- and second-level event bits of the two-level order against the Fraction model."""
+    rng = np.random.default_rng(12)
+
+    def bit(plane, idx, i, j):
+        return bool((int(plane[idx // 32, i, j]) >> (idx % 32)) & 1)
+
+    for (fp, fa), rnd, K, lo, hi in [(((5, 7, 15), (4, 7, 7)), 0, 41, 3, 12), (((5, 7, 15), (4, 7, 7)), 1, 50, 0, 15),
+                                     (((4, 7, 9), (4, 3, 7)), 0, 530, 2, 11), (((3, 4, 6), (3, 4, 6)), 1, 37, 4, 10)]:
+        qp, qa = ref.QFmt(*fp, rnd), ref.QFmt(*fa, rnd)
+        A = _rand_codes(rng, (2, K), lo, hi); B = _rand_codes(rng, (2, K), lo, hi)
+        C, of, uf, of2, uf2 = ref.gemm_bwd(A, B, qp, qa, order=ref.ORDER_CHUNK16, level2=True)
+        assert np.array_equal(C.view(np.uint32), ref.gemm(A, B, qp, qa, order=ref.ORDER_CHUNK16).view(np.uint32))
+        nchunk = (K + 15) // 16
+        assert of.shape[0] == (K + 31) // 32 and of2.shape[0] == (nchunk + 31) // 32
+        seen = [0, 0, 0, 0]
+        for i in range(2):
+            for j in range(2):
+                want, ev1, ev2 = FM.chain_chunk16([int(c) for c in A[i]], [int(c) for c in B[j]],
+                                                  fp + (rnd,), fa + (rnd,), with_events=True)
+                assert Fraction(float(C[i, j])) == want
+                for k in range(K):
+                    assert (bit(of, k, i, j), bit(uf, k, i, j)) == ev1[k], (fp, fa, rnd, i, j, k)
+                    seen[0] += ev1[k][0]; seen[1] += ev1[k][1]
+                for c in range(nchunk):
+                    assert (bit(of2, c, i, j), bit(uf2, c, i, j)) == ev2[c], (fp, fa, rnd, i, j, c)
+                    seen[2] += ev2[c][0]; seen[3] += ev2[c][1]
+                # padding bits are zero
+                for k in range(K, 32 * of.shape[0]):
+                    assert not bit(of, k, i, j) and not bit(uf, k, i, j)
+                for c in range(nchunk, 32 * of2.shape[0]):
+                    assert not bit(of2, c, i, j) and not bit(uf2, c, i, j)
+        print(fp, fa, rnd, "events seen (OF, UF, OF2, UF2):", seen)
+    # a second-level underflow needs cancellation between two values of the grid: chunk 0 sums to
+    # 1.5 * 2^-7, chunk 1 to -2^-7; T_2 = 2^-8 is below R_UF = 2^-7 and not zero
+    A = np.zeros((1, 20), dtype=np.uint8); B = np.zeros((1, 20), dtype=np.uint8)
+    A[0, 0], B[0, 0] = 0x3C, 0x04            # 1.5 * 2^-7
+    A[0, 16], B[0, 16] = 0xB8, 0x04          # -1 * 2^-7
+    for rnd in (0, 1):
+        C, of, uf, of2, uf2 = ref.gemm_bwd(A, B, ref.QFmt(5, 7, 15, rnd), ref.QFmt(4, 7, 7, rnd),
+                                           order=ref.ORDER_CHUNK16, level2=True)
+        assert C[0, 0] == 0.0 and int(uf2[0, 0, 0]) == 0b10 and int(of2[0, 0, 0]) == 0
+        assert int(uf[0, 0, 0]) == 0 and int(of[0, 0, 0]) == 0
+
+
 def test_oracle_rejects_bad_arguments(ref):
     A = np.zeros((2, 4), dtype=np.uint8)
     good = ref.QFmt(4, 7, 7, 0)
