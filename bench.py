@@ -25,9 +25,10 @@ if ROOT not in sys.path:
 # 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz = 78.6e12 full-rate VALU lane-ops per second: the
 # rate behind the published 157.3 TFLOP/s FP32 vector peak (an FMA counts two flops).
 PEAK_LANE_OPS = 256 * 4 * 32 * 2.4e9
-# HBM bytes per launch of the default workload, from the calibrated rocprofv3 FETCH_SIZE / WRITE_SIZE
-# runs summarised in profiles/lba_fast_kernel_resnet50_sweep.md: (2905 + 2714) MiB over 54 launches.
-RESNET50_TRAFFIC_BYTES_PER_LAUNCH = (2905 + 2714) * 2 ** 20 / 54
+# HBM bytes per launch of the dominant kernel of the default workload (the 42 launches of the 4x4 lane
+# block), from the calibrated rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/lba_fast_kernel_resnet50_sweep.md: FETCH_SIZE 1165029.9 KiB x 2.000 + WRITE_SIZE 2641312.6 KiB.
+RESNET50_TRAFFIC_BYTES_PER_LAUNCH = (2.0 * 1165029.875 + 2641312.625) * 1024 / 42
 PROD_FMT = (5, 7, 15)
 ACC_FMT = (4, 7, 7)
 
@@ -165,9 +166,10 @@ def main():
             per_layer_ms[i] += ms / args.steps
             p = l["plan"]
             key = (p["kernel"], p["prod_mode"], p["round"], p["thread_m"], p["thread_n"], p["tile_k"])
-            g = groups.setdefault(key, dict(ms=0.0, macs=0, launches=0, ops=p["valu_per_mac_x100"] / 100.0))
+            g = groups.setdefault(key, dict(ms=0.0, macs=0, launches=0, bytes=0, ops=p["valu_per_mac_x100"] / 100.0))
             g["ms"] += ms
             g["macs"] += l["macs"]
+            g["bytes"] += l["M"] * l["K"] + l["N"] * l["K"] + 4 * l["M"] * l["N"]   # A, B once, C once
             g["launches"] += 1
     dom_key = max(groups, key=lambda k: groups[k]["ms"])
     dom = groups[dom_key]
@@ -179,6 +181,7 @@ def main():
         "kernel": "lba_%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (
             ("fast_bwd" if args.bwd else "fast") if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
             "rne" if dom_key[2] else "floor"),
+        "algorithmic_bytes": dom["bytes"] / dom["launches"],
         "valu_slots_per_mac": dom["ops"], "avg_launch_ms": dom["ms"] / dom["launches"],
         "launches": dom["launches"], "mac_per_s": dom["macs"] / (dom["ms"] * 1e-3),
         "time_share": dom["ms"] / sum(g["ms"] for g in groups.values()),
