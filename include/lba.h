@@ -103,6 +103,43 @@ int lba_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C,
 /* Number of uint32 words in one event plane: ceil(K / 32) * M * N (0 if any size is <= 0). */
 size_t lba_mask_words(int64_t M, int64_t N, int64_t K);
 
+/* ---- gradient side: the fine-grained straight-through estimators of Sec. 4 and App. D ---------
+ *
+ * With g = dL/dC, every FMAq step k of output (m, n) gets a coefficient c[m, n, k] in {0, 1} and
+ *   dX[m, k] = sum_n g[m, n] * value(B[n, k]) * c[m, n, k]      (gradient w.r.t. the codes' values of A)
+ *   dW[n, k] = sum_m g[m, n] * value(A[m, k]) * c[m, n, k]      (gradient w.r.t. the codes' values of B)
+ * value() is the E4M3 value of a code (operand scales are the caller's: scale g).
+ *   LBA_STE_IDENTITY      c = 1
+ *   LBA_STE_IMMEDIATE_OF  c_k = 1 - OF_k: the estimator that treats the partial sum with the identity
+ *                         and the product pair with STE^OF.  Needs of_mask, the first-level OF plane of
+ *                         lba_gemm_bwd or lba_gemm_bwd_chunked (the second level has no product pair).
+ *   LBA_STE_RECURSIVE_OF  c_k = product of STE^OF over all steps i >= k of the sequential chain, i.e.
+ *                         [k > last_of[m, n]].  Needs last_of from lba_last_overflow.  (Chunked order:
+ *                         the path also runs through the second level; not provided.)
+ * Arithmetic: FP32 products and FP32 sums.  The order of the summation is unspecified (the sum may be
+ * split across workgroups and combined with atomic adds), so results are reproducible up to FP32
+ * rounding: |error| <= (terms + 1) * 2^-24 * sum of |terms| to first order.
+ */
+enum { LBA_STE_IDENTITY = 0, LBA_STE_IMMEDIATE_OF = 1, LBA_STE_RECURSIVE_OF = 2 };
+
+/* The recursive estimator's post-pass (App. D): last_of[m*N + n] = the largest k whose bit is set in the
+ * OF plane of lba_gemm_bwd, or -1 when the chain never overflowed.  of_mask: lba_mask_words(M, N, K)
+ * words, last_of: M*N int32, both device pointers owned by the caller.  K == 0 writes -1 everywhere.
+ * Returns LBA_OK, LBA_ERR_NULL, LBA_ERR_SHAPE or LBA_ERR_LAUNCH. */
+int lba_last_overflow(const uint32_t* of_mask, int32_t* last_of, int64_t M, int64_t N, int64_t K,
+                      void* hip_stream);
+
+/* The masked gradient products.  G [M, N] float32, A [M, K] and B [N, K] uint8 codes, dX [M, K] and
+ * dW [N, K] float32, all device pointers owned by the caller; either output may be NULL (then its
+ * operand, B for dX and A for dW, may be NULL too) but not both.  of_mask / last_of as required by
+ * `ste`, else ignored.  Outputs are overwritten.  K <= 64 * 65535 and M * N <= 2^30 (else LBA_ERR_SHAPE).
+ * M == 0 or N == 0 stores zeros.
+ * Returns LBA_OK, LBA_ERR_NULL, LBA_ERR_SHAPE, LBA_ERR_UNSUPPORTED (unknown ste) or LBA_ERR_LAUNCH;
+ * nothing is enqueued on error. */
+int lba_grad(const float* G, const uint8_t* A, const uint8_t* B,
+             const uint32_t* of_mask, const int32_t* last_of,
+             float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* hip_stream);
+
 /* Static, human-readable text for a status code (never NULL). */
 const char* lba_strerror(int code);
 

@@ -12,6 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIBPATH = os.path.join(_HERE, "liblba_hip.so")
 
 ROUND_FLOOR, ROUND_RNE = 0, 1
+STE_IDENTITY, STE_IMMEDIATE_OF, STE_RECURSIVE_OF = 0, 1, 2
 ORDER_SEQ, ORDER_CHUNK16 = 0, 1
 OK, ERR_NULL, ERR_SHAPE, ERR_FORMAT, ERR_UNSUPPORTED, ERR_ALIGN, ERR_LAUNCH = range(7)
 
@@ -55,6 +56,10 @@ def lib():
         L.lba_gemm_bwd_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, vp]
         L.lba_mask_words_level2.restype = ctypes.c_size_t
         L.lba_mask_words_level2.argtypes = [i64, i64, i64]
+        L.lba_last_overflow.restype = ctypes.c_int
+        L.lba_last_overflow.argtypes = [vp, vp, i64, i64, i64, vp]
+        L.lba_grad.restype = ctypes.c_int
+        L.lba_grad.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
         L.lba_mask_words.restype = ctypes.c_size_t
         L.lba_mask_words.argtypes = [i64, i64, i64]
         L.lba_strerror.restype = ctypes.c_char_p
@@ -113,6 +118,16 @@ def lba_gemm_bwd_chunked(A, B, C, of_mask, uf_mask, of_mask2, uf_mask2, M, N, K,
     return lib().lba_gemm_bwd_chunked(A, B, C, of_mask, uf_mask, of_mask2, uf_mask2, M, N, K, qfmt(qprod),
                                       qfmt(qacc),
                                       ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_last_overflow(of_mask, last_of, M, N, K, hip_stream=None):
+    return lib().lba_last_overflow(of_mask, last_of, M, N, K,
+                                   ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_grad(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, hip_stream=None):
+    return lib().lba_grad(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste,
+                          ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
 
 
 def lba_mask_words(M, N, K):
@@ -201,3 +216,27 @@ def gemm_bwd_chunked(A, B, qprod, qacc, want_c=True, stream=None):
                                       *[t.data_ptr() or None for t in planes],
                                       M, N, K, qfmt(qprod), qfmt(qacc), _stream(stream)))
     return (C, *planes)
+
+
+def last_overflow(of_plane, K, stream=None):
+    """int32 [M, N] index of the last overflowing step of every chain (-1: none) from an OF plane."""
+    W, M, N = of_plane.shape
+    out = torch.empty((M, N), dtype=torch.int32, device=of_plane.device)
+    _check(lib().lba_last_overflow(of_plane.data_ptr() or None, out.data_ptr() or None, M, N, K, _stream(stream)))
+    return out
+
+
+def grad(G, A, B, ste, of_plane=None, last_of=None, want_dx=True, want_dw=True, stream=None):
+    """Masked gradient products: returns (dX [M, K] or None, dW [N, K] or None), float32 device tensors."""
+    A, B = _ops(A, B)
+    M, K = A.shape
+    N = B.shape[0]
+    if G.dtype != torch.float32 or tuple(G.shape) != (M, N) or not G.is_cuda:
+        raise ValueError("G must be a float32 device tensor [M, N]")
+    G = G.contiguous()
+    dX = torch.empty((M, K), dtype=torch.float32, device=A.device) if want_dx else None
+    dW = torch.empty((N, K), dtype=torch.float32, device=A.device) if want_dw else None
+    ptr = lambda t: (t.data_ptr() or None) if t is not None else None
+    _check(lib().lba_grad(ptr(G), ptr(A), ptr(B), ptr(of_plane), ptr(last_of), ptr(dX), ptr(dW), M, N, K, ste,
+                          _stream(stream)))
+    return dX, dW

@@ -1,0 +1,319 @@
+// lba_grad.hip -- the gradient side of the LBA product for gfx950: the last-overflow post-pass and
+// the coefficient-masked gradient products of the fine-grained straight-through estimators
+// (Sec. 4 and App. D of the paper).
+//
+//   dX[m, k] = sum_n g[m, n] * value(B[n, k]) * c[m, n, k]
+//   dW[n, k] = sum_m g[m, n] * value(A[m, k]) * c[m, n, k]
+//
+// with c in {0, 1}: 1 (identity), 1 - OF_k (immediate / OF) or [k > last overflow of (m, n)]
+// (recursive / OF under the sequential order).  Both products are the same kernel:
+//
+//   out[r, k] = sum_s g(r, s) * value(V[s, k]) * c(r, s, k)        dX: r = m, s = n, V = B
+//                                                                  dW: r = n, s = m, V = A
+//
+// Mapping.  The 64 lanes of a wave are 64 consecutive k; a wave owns 16 rows r (16 accumulators per
+// lane) and walks over s.  For one (r, s) everything but V is uniform across the wave: g(r, s) is one
+// scalar, and the 64 coefficient bits of k0 .. k0+63 are exactly two words of the plane, i.e. a
+// 64-bit lane mask.  They are fetched with scalar loads and the multiply-add runs with that mask as
+// the wave's execution mask: one VALU instruction per 64 coefficient-masked MACs, no per-lane bit
+// extraction.  The recursive estimator compares the lane's k with the scalar last-overflow index.
+// Reductions over s never cross lanes.  When the launch would have too few waves, s is split over
+// grid z and the partial sums are combined with floating-point atomic adds (the output is zeroed
+// first): the summation order is then not fixed, results agree to FP32 rounding.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lba.h"
+#include "lba_internal.h"
+
+namespace lba {
+
+// Sizes of one launch; the pointers are separate kernel arguments so that they can be declared
+// non-aliasing, which is what lets the compiler fetch the wave-uniform values with scalar loads.
+struct GradDims {
+    int32_t R, S, K;
+    int32_t stride_r, stride_s;   // element (r, s) of G / last_of / one plane word-slab: r*stride_r + s*stride_s
+    int64_t slab;              // M*N: distance between consecutive 32-k word slabs of the plane
+    int32_t s_chunk;           // s values per grid z
+    int32_t atomic;            // 1: gridDim.z > 1, combine with atomic adds
+    int32_t vec_ok;            // 1: G, the plane and last_of are 16-byte aligned and N % 4 == 0 (wide scalar loads)
+};
+
+__device__ __forceinline__ float decode_e4m3(uint32_t code) {
+    float v = __builtin_amdgcn_cvt_f32_fp8((int)code, 0);
+    if ((code & 0x7Fu) == 0x7Fu) v = (code & 0x80u) ? -480.0f : 480.0f;   // the two NaN codes
+    return v;
+}
+
+// acc += g[u] * v[u] on the lanes whose OF bit is clear, u = 0..3: the complement of the two OF words
+// (k0..k0+31 and k0+32..k0+63) is written straight into the execution mask.  The mask is saved and
+// restored inside the statement, so the surrounding code never sees it changed.
+__device__ __forceinline__ void masked_fmac4(float& acc, const uint32_t (&lo)[4], const uint32_t (&hi)[4],
+                                             const float (&g)[4], const float (&v)[4]) {
+    uint64_t save;
+    asm volatile(
+        "s_mov_b64 %[sv], exec\n\t"
+        "s_not_b32 exec_lo, %[l0]\n\ts_not_b32 exec_hi, %[h0]\n\tv_fmac_f32 %[a], %[g0], %[v0]\n\t"
+        "s_not_b32 exec_lo, %[l1]\n\ts_not_b32 exec_hi, %[h1]\n\tv_fmac_f32 %[a], %[g1], %[v1]\n\t"
+        "s_not_b32 exec_lo, %[l2]\n\ts_not_b32 exec_hi, %[h2]\n\tv_fmac_f32 %[a], %[g2], %[v2]\n\t"
+        "s_not_b32 exec_lo, %[l3]\n\ts_not_b32 exec_hi, %[h3]\n\tv_fmac_f32 %[a], %[g3], %[v3]\n\t"
+        "s_mov_b64 exec, %[sv]"
+        : [a] "+v"(acc), [sv] "=&s"(save)
+        : [l0] "s"(lo[0]), [h0] "s"(hi[0]), [g0] "s"(g[0]), [v0] "v"(v[0]),
+          [l1] "s"(lo[1]), [h1] "s"(hi[1]), [g1] "s"(g[1]), [v1] "v"(v[1]),
+          [l2] "s"(lo[2]), [h2] "s"(hi[2]), [g2] "s"(g[2]), [v2] "v"(v[2]),
+          [l3] "s"(lo[3]), [h3] "s"(hi[3]), [g3] "s"(g[3]), [v3] "v"(v[3])
+        : "scc");
+}
+
+// acc += g[u] * v[u] on the lanes whose k exceeds last[u] (recursive estimator).  The four compares run
+// under the full mask first; each result is a lane mask in a scalar register pair.
+__device__ __forceinline__ void recursive_fmac4(float& acc, int k, const int32_t (&last)[4],
+                                                const float (&g)[4], const float (&v)[4]) {
+    uint64_t save, m0, m1, m2, m3;
+    asm volatile(
+        "v_cmp_gt_i32_e64 %[m0], %[k], %[t0]\n\t"
+        "v_cmp_gt_i32_e64 %[m1], %[k], %[t1]\n\t"
+        "v_cmp_gt_i32_e64 %[m2], %[k], %[t2]\n\t"
+        "v_cmp_gt_i32_e64 %[m3], %[k], %[t3]\n\t"
+        "s_mov_b64 %[sv], exec\n\t"
+        "s_mov_b64 exec, %[m0]\n\tv_fmac_f32 %[a], %[g0], %[v0]\n\t"
+        "s_mov_b64 exec, %[m1]\n\tv_fmac_f32 %[a], %[g1], %[v1]\n\t"
+        "s_mov_b64 exec, %[m2]\n\tv_fmac_f32 %[a], %[g2], %[v2]\n\t"
+        "s_mov_b64 exec, %[m3]\n\tv_fmac_f32 %[a], %[g3], %[v3]\n\t"
+        "s_mov_b64 exec, %[sv]"
+        : [a] "+v"(acc), [sv] "=&s"(save), [m0] "=&s"(m0), [m1] "=&s"(m1), [m2] "=&s"(m2), [m3] "=&s"(m3)
+        : [k] "v"(k), [t0] "s"(last[0]), [t1] "s"(last[1]), [t2] "s"(last[2]), [t3] "s"(last[3]),
+          [g0] "s"(g[0]), [g1] "s"(g[1]), [g2] "s"(g[2]), [g3] "s"(g[3]),
+          [v0] "v"(v[0]), [v1] "v"(v[1]), [v2] "v"(v[2]), [v3] "v"(v[3]));
+}
+
+// The 4 x 4 block (rows ib..ib+3 of the wave, s..s+3) of scalars and the masked multiply-adds on it.
+// FAST: all 16 elements exist and the four 16-byte groups along the contiguous index are aligned, so
+// each is one wide scalar load; otherwise indices are clamped and g is zeroed outside the range.
+// S_CONTIG: element (r, s) is contiguous along s (dX) or along r (dW).  Element offsets fit 32 bits.
+// Where the plane has no second word slab (the last 64 k with K % 64 <= 32) P1 aliases P0: lanes 32..63
+// then hold k >= K, whose operand value is 0 and whose sums are never stored.
+template <int MODE, bool S_CONTIG, bool FAST>
+__device__ __forceinline__ void grad_block(float (&acc)[16], int ib, int r0, int s, int s_end, int k,
+                                           const float (&v)[4], const float* __restrict__ G,
+                                           const uint32_t* __restrict__ P0, const uint32_t* __restrict__ P1,
+                                           const int32_t* __restrict__ L, const GradDims& d) {
+    uint32_t lo[4][4], hi[4][4];
+    int32_t last[4][4];
+    float g[4][4];
+    if (FAST) {
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+            const uint32_t off = S_CONTIG ? (uint32_t)(r0 + ib + a) * (uint32_t)d.stride_r + (uint32_t)s
+                                          : (uint32_t)(s + a) * (uint32_t)d.stride_s + (uint32_t)(r0 + ib);
+            const float4 gv = *reinterpret_cast<const float4*>(G + off);
+            const float ga[4] = {gv.x, gv.y, gv.z, gv.w};
+            uint32_t la[4] = {0u, 0u, 0u, 0u}, ha[4] = {0u, 0u, 0u, 0u};
+            int32_t ta[4] = {0, 0, 0, 0};
+            if (MODE == LBA_STE_IMMEDIATE_OF) {
+                const uint4 lv = *reinterpret_cast<const uint4*>(P0 + off);
+                const uint4 hv = *reinterpret_cast<const uint4*>(P1 + off);
+                la[0] = lv.x; la[1] = lv.y; la[2] = lv.z; la[3] = lv.w;
+                ha[0] = hv.x; ha[1] = hv.y; ha[2] = hv.z; ha[3] = hv.w;
+            }
+            if (MODE == LBA_STE_RECURSIVE_OF) {
+                const int4 tv = *reinterpret_cast<const int4*>(L + off);
+                ta[0] = tv.x; ta[1] = tv.y; ta[2] = tv.z; ta[3] = tv.w;
+            }
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int i = S_CONTIG ? a : b, u = S_CONTIG ? b : a;
+                g[i][u] = ga[b]; lo[i][u] = la[b]; hi[i][u] = ha[b]; last[i][u] = ta[b];
+            }
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool in = (r0 + ib + i < d.R) && (s + u < s_end);
+                const uint32_t off = (uint32_t)min(r0 + ib + i, d.R - 1) * (uint32_t)d.stride_r
+                                   + (uint32_t)min(s + u, d.S - 1) * (uint32_t)d.stride_s;
+                const float gl = G[off];
+                g[i][u] = in ? gl : 0.0f;
+                lo[i][u] = hi[i][u] = 0u;
+                last[i][u] = 0;
+                if (MODE == LBA_STE_IMMEDIATE_OF) { lo[i][u] = P0[off]; hi[i][u] = P1[off]; }
+                if (MODE == LBA_STE_RECURSIVE_OF) last[i][u] = L[off];
+            }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (MODE == LBA_STE_IDENTITY) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc[ib + i] = __builtin_fmaf(g[i][u], v[u], acc[ib + i]);
+        } else if (MODE == LBA_STE_IMMEDIATE_OF) {
+            masked_fmac4(acc[ib + i], lo[i], hi[i], g[i], v);
+        } else {
+            recursive_fmac4(acc[ib + i], k, last[i], g[i], v);
+        }
+    }
+}
+
+template <int MODE, bool S_CONTIG>
+__global__ void __launch_bounds__(256) lba_grad_kernel(const float* __restrict__ G, const uint8_t* __restrict__ V,
+                                                       const uint32_t* __restrict__ plane,
+                                                       const int32_t* __restrict__ last_of,
+                                                       float* __restrict__ out, const GradDims d) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int k0 = blockIdx.y * 64;
+    const int k = k0 + lane;
+    const int r0 = (blockIdx.x * 4 + wave) * 16;
+    if (r0 >= d.R) return;                                     // whole wave (uniform)
+    const int s_begin = blockIdx.z * d.s_chunk;
+    const int s_end = min(d.S, s_begin + d.s_chunk);
+    const bool has_hi = k0 + 32 < d.K;                         // does the plane have a second word slab here
+    const uint32_t* __restrict__ P0 = plane + (int64_t)(k0 >> 5) * d.slab;    // not dereferenced unless MODE needs it
+    const uint32_t* __restrict__ P1 = has_hi ? P0 + d.slab : P0;
+    const bool rows_fast = d.vec_ok && r0 + 16 <= d.R;
+
+    float acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+
+    for (int s = s_begin; s < s_end; s += 4) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int su = min(s + u, d.S - 1);
+            const uint32_t code = (k < d.K) ? V[(int64_t)su * d.K + k] : 0u;
+            v[u] = decode_e4m3(code);
+        }
+        if (rows_fast && s + 4 <= s_end) {                     // uniform
+#pragma unroll
+            for (int ib = 0; ib < 16; ib += 4)
+                grad_block<MODE, S_CONTIG, true>(acc, ib, r0, s, s_end, k, v, G, P0, P1, last_of, d);
+        } else {
+#pragma unroll
+            for (int ib = 0; ib < 16; ib += 4)
+                grad_block<MODE, S_CONTIG, false>(acc, ib, r0, s, s_end, k, v, G, P0, P1, last_of, d);
+        }
+    }
+
+    if (k < d.K) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            if (r0 + i < d.R) {
+                float* dst = out + (int64_t)(r0 + i) * d.K + k;
+                if (d.atomic) unsafeAtomicAdd(dst, acc[i]);
+                else          *dst = acc[i];
+            }
+        }
+    }
+}
+
+__global__ void lba_grad_zero_kernel(float* x, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) x[i] = 0.0f;
+}
+
+// last_of[m, n] = highest k whose bit is set in the plane, -1 if none: one lane per output, walking
+// the word slabs from the top; consecutive lanes read consecutive words.
+__global__ void __launch_bounds__(256) lba_last_overflow_kernel(const uint32_t* __restrict__ plane, int32_t* __restrict__ last_of,
+                                                                int64_t MN, int32_t words) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= MN) return;
+    int32_t last = -1;
+    for (int w = words - 1; w >= 0; --w) {
+        const uint32_t x = plane[(int64_t)w * MN + i];
+        if (x) { last = w * 32 + 31 - __builtin_clz(x); break; }
+    }
+    last_of[i] = last;
+}
+
+template <bool S_CONTIG>
+static hipError_t launch_grad(int ste, const float* G, const uint8_t* V, const uint32_t* plane, const int32_t* last_of,
+                              float* out, const GradDims& gp, dim3 grid, hipStream_t st) {
+#define LBA_GRAD_LAUNCH(MODE) hipLaunchKernelGGL((lba_grad_kernel<MODE, S_CONTIG>), grid, dim3(256), 0, st, G, V, plane, last_of, out, gp)
+    switch (ste) {
+        case LBA_STE_IDENTITY:     LBA_GRAD_LAUNCH(LBA_STE_IDENTITY); break;
+        case LBA_STE_IMMEDIATE_OF: LBA_GRAD_LAUNCH(LBA_STE_IMMEDIATE_OF); break;
+        default:                   LBA_GRAD_LAUNCH(LBA_STE_RECURSIVE_OF); break;
+    }
+#undef LBA_GRAD_LAUNCH
+    return hipGetLastError();
+}
+
+// One of the two products.  Splits s over grid z when the (r, k) grid alone would leave the chip idle.
+static int run_grad_side(bool dx, const float* G, const uint8_t* V, const uint32_t* plane, const int32_t* last_of,
+                         float* out, int64_t M, int64_t N, int64_t K, int ste, hipStream_t st) {
+    GradDims gp;
+    gp.K = (int32_t)K;
+    gp.slab = M * N;
+    if (dx) { gp.R = (int32_t)M; gp.S = (int32_t)N; gp.stride_r = (int32_t)N; gp.stride_s = 1; }
+    else    { gp.R = (int32_t)N; gp.S = (int32_t)M; gp.stride_r = 1; gp.stride_s = (int32_t)N; }
+    const int64_t gx = (gp.R + 63) / 64, gy = (K + 63) / 64;      // row blocks on x (no 65535 limit there)
+    int split = 1;
+    plan_grad_split(gx * gy, gp.S, &split, &gp.s_chunk);
+    gp.atomic = split > 1 ? 1 : 0;
+    const uintptr_t al = (uintptr_t)G | (uintptr_t)plane | (uintptr_t)last_of;
+    gp.vec_ok = ((al % 16) == 0 && (N % 4) == 0) ? 1 : 0;
+    if (gp.atomic) {
+        const int64_t n = (int64_t)gp.R * K;
+        hipLaunchKernelGGL(lba_grad_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, out, n);
+        if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
+    }
+    const dim3 grid((unsigned)gx, (unsigned)gy, (unsigned)split);
+    const hipError_t e = dx ? launch_grad<true>(ste, G, V, plane, last_of, out, gp, grid, st)
+                            : launch_grad<false>(ste, G, V, plane, last_of, out, gp, grid, st);
+    return e == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
+}
+
+}  // namespace lba
+
+extern "C" {
+
+int lba_last_overflow(const uint32_t* of_mask, int32_t* last_of, int64_t M, int64_t N, int64_t K, void* hip_stream) {
+    int rc = lba::validate_shapes(M, N, K);
+    if (rc != LBA_OK) return rc;
+    if (M == 0 || N == 0) return LBA_OK;
+    if (!last_of || (K > 0 && !of_mask)) return LBA_ERR_NULL;
+    const int64_t mn = M * N;
+    hipLaunchKernelGGL(lba::lba_last_overflow_kernel, dim3((unsigned)((mn + 255) / 256)), dim3(256), 0,
+                       (hipStream_t)hip_stream, of_mask, last_of, mn, (int32_t)((K + 31) / 32));
+    return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
+}
+
+int lba_grad(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
+             float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* hip_stream) {
+    int rc = lba::validate_shapes(M, N, K);
+    if (rc != LBA_OK) return rc;
+    if (ste != LBA_STE_IDENTITY && ste != LBA_STE_IMMEDIATE_OF && ste != LBA_STE_RECURSIVE_OF) return LBA_ERR_UNSUPPORTED;
+    if ((K + 63) / 64 > 65535) return LBA_ERR_SHAPE;           // k blocks are grid y
+    if (M * N > ((int64_t)1 << 30)) return LBA_ERR_SHAPE;      // element offsets of G and of a word slab are 32-bit
+    if (!dX && !dW) return LBA_ERR_NULL;
+    if (K == 0) return LBA_OK;                                 // dX and dW are empty
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (M == 0 || N == 0) {                                    // empty sums: the non-empty gradient is zero
+        float* o = M == 0 ? dW : dX;
+        const int64_t n = (M == 0 ? N : M) * K;
+        if (o && n > 0) {
+            hipLaunchKernelGGL(lba::lba_grad_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, o, n);
+            if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
+        }
+        return LBA_OK;
+    }
+    if (!G) return LBA_ERR_NULL;
+    if (ste == LBA_STE_IMMEDIATE_OF && !of_mask) return LBA_ERR_NULL;
+    if (ste == LBA_STE_RECURSIVE_OF && !last_of) return LBA_ERR_NULL;
+    if (dX) {
+        if (!B) return LBA_ERR_NULL;
+        rc = lba::run_grad_side(true, G, B, of_mask, last_of, dX, M, N, K, ste, st);
+        if (rc != LBA_OK) return rc;
+    }
+    if (dW) {
+        if (!A) return LBA_ERR_NULL;
+        rc = lba::run_grad_side(false, G, A, of_mask, last_of, dW, M, N, K, ste, st);
+        if (rc != LBA_OK) return rc;
+    }
+    return LBA_OK;
+}
+
+}  // extern "C"

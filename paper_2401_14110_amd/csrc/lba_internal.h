@@ -60,5 +60,9 @@ int validate_fmt(const lba_qfmt& q);
 int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qprod, const lba_qfmt& qacc,
               int order, int events, Plan* out, int64_t batch = 1);
 
+// Gradient products: how many slices of the summation index s a launch of `blocks` workgroups (4 waves
+// of 16 rows each) is cut into so that the chip has enough waves, and the slice length (a multiple of 4).
+void plan_grad_split(int64_t blocks, int64_t S, int* split, int32_t* s_chunk);
+
 }  // namespace lba
 #endif

@@ -236,4 +236,20 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     return LBA_OK;
 }
 
+// 256 CUs x 4 SIMDs x 4 waves want about 4096 waves = 1024 workgroups; a slice keeps at least 64 values
+// of s so that the atomic adds stay a small fraction of the work.
+void plan_grad_split(int64_t blocks, int64_t S, int* split, int32_t* s_chunk) {
+    int64_t want = blocks > 0 ? (1024 + blocks - 1) / blocks : 1;
+    const int64_t most = S > 64 ? S / 64 : 1;
+    if (want > most) want = most;
+    if (want > 65535) want = 65535;
+    if (want < 1) want = 1;
+    int64_t chunk = (S + want - 1) / want;
+    chunk = (chunk + 3) / 4 * 4;
+    if (chunk < 4) chunk = 4;
+    *s_chunk = (int32_t)chunk;
+    *split = (int)((S + chunk - 1) / chunk);
+    if (*split < 1) *split = 1;
+}
+
 }  // namespace lba

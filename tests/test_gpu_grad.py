@@ -1,0 +1,136 @@
+"""GPU parity of the gradient side (lba_last_overflow, lba_grad) against the float64 gradient oracle.
+Two bars: bit-exact where every FP32 product and partial sum is exactly representable (small dyadic g,
+narrow operand range), and the derived FP32 bound  (terms + 1) * 2^-24 * sum|terms|  (times 2) on
+general data, where the order of the summation is not fixed."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2401_14110_amd import binding as lb
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+QP, QA = (5, 7, 15, 0), (4, 7, 7, 0)
+
+
+@pytest.fixture(scope="module")
+def gref(ref):
+    from oracle import lba_grad_ref
+    return lba_grad_ref
+
+
+def codes(rng, shape, lo=0, hi=15):
+    e = rng.integers(lo, hi + 1, shape); m = rng.integers(0, 8, shape); s = rng.integers(0, 2, shape)
+    c = (s << 7) | (e << 3) | m
+    return np.where((c & 0x7F) == 0x7F, c & 0xFE, c).astype(np.uint8)
+
+
+def gpu_inputs(ref, A, B, qp, qa, order=0):
+    tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    if order == 0:
+        _, of, _ = lb.gemm_bwd(tA, tB, qp, qa, want_c=False)
+    else:
+        _, of, _, _, _ = lb.gemm_bwd_chunked(tA, tB, qp, qa, want_c=False)
+    return tA, tB, of
+
+
+def run_grad(tG, tA, tB, ste, of, K):
+    last = lb.last_overflow(of, K) if ste == lb.STE_RECURSIVE_OF else None
+    dX, dW = lb.grad(tG, tA, tB, ste, of_plane=of if ste == lb.STE_IMMEDIATE_OF else None, last_of=last)
+    torch.cuda.synchronize()
+    return dX.cpu().numpy(), dW.cpu().numpy()
+
+
+def test_last_overflow_index(ref, gref):
+    rng = np.random.default_rng(90)
+    seen_some = seen_none = False
+    for (M, N, K), lo, hi in [((70, 66, 100), 0, 15), ((33, 130, 64), 3, 12), ((5, 3, 31), 0, 15), ((64, 64, 1), 8, 15),
+                              ((20, 24, 200), 2, 8)]:
+        A = codes(rng, (M, K), lo, hi); B = codes(rng, (N, K), lo, hi)
+        _, _, of = gpu_inputs(ref, A, B, QP, QA)
+        got = lb.last_overflow(of, K)
+        torch.cuda.synchronize()
+        _, wof, _ = ref.gemm_bwd(A, B, ref.QFmt(*QP), ref.QFmt(*QA))
+        want = gref.last_overflow(wof, K)
+        assert np.array_equal(got.cpu().numpy(), want), (M, N, K)
+        seen_some |= bool((want >= 0).any()); seen_none |= bool((want < 0).any())
+    assert seen_some and seen_none
+
+
+@pytest.mark.parametrize("ste", [0, 1, 2])
+def test_exactly_representable_sums_are_bit_exact(ref, gref, ste):
+    # g in {-2, ..., 2} in steps of 1/4 and operand values that are multiples of 2^-5 below 16: every term
+    # and every partial sum is exact in FP32, so any summation order gives the oracle's value bit for bit.
+    # Shapes: ragged rows and columns, K across the 64-lane and word boundaries, N % 4 != 0 (the general
+    # path), tall M (the sum over m is split and combined with atomic adds).
+    rng = np.random.default_rng(91 + ste)
+    QP, QA = (4, 7, 12, 0), (4, 7, 10, 0)                          # R_OF = 63.75: these operands overflow often
+    differs = 0
+    for (M, N, K) in [(64, 64, 64), (70, 66, 100), (33, 130, 65), (5, 3, 31), (16, 4, 33), (3000, 24, 40), (40, 2100, 70)]:
+        A = codes(rng, (M, K), 5, 10); B = codes(rng, (N, K), 5, 10)
+        G = (rng.integers(-8, 9, (M, N)) / 4.0).astype(np.float32)
+        tA, tB, of = gpu_inputs(ref, A, B, QP, QA)
+        dX, dW = run_grad(torch.from_numpy(G).to(DEV), tA, tB, ste, of, K)
+        wX, wW = gref.grad(G, A, B, ref.QFmt(*QP), ref.QFmt(*QA), ste)
+        assert np.array_equal(dX, wX.astype(np.float32)), (M, N, K, "dX", np.abs(dX - wX).max())
+        assert np.array_equal(dW, wW.astype(np.float32)), (M, N, K, "dW", np.abs(dW - wW).max())
+        iX, _ = gref.grad(G, A, B, ref.QFmt(*QP), ref.QFmt(*QA), 0)
+        differs += int(not np.array_equal(wX, iX))
+    assert differs == (0 if ste == 0 else 7)                        # every case has overflow events
+
+
+@pytest.mark.parametrize("order", [0, 1])
+def test_general_data_within_the_fp32_bound(ref, gref, order):
+    rng = np.random.default_rng(95 + order)
+    for (M, N, K), qp, qa in [((130, 70, 200), QP, QA), ((66, 300, 96), (4, 7, 9, 0), (4, 3, 7, 0)),
+                              ((300, 64, 147), (5, 7, 15, 1), (4, 7, 7, 1))]:
+        A = codes(rng, (M, K)); B = codes(rng, (N, K))
+        G = rng.standard_normal((M, N)).astype(np.float32)
+        tA, tB, of = gpu_inputs(ref, A, B, qp, qa, order)
+        for ste in ((0, 1, 2) if order == 0 else (1,)):           # recursive: sequential order only
+            dX, dW = run_grad(torch.from_numpy(G).to(DEV), tA, tB, ste, of, K)
+            wX, wW = gref.grad(G, A, B, ref.QFmt(*qp), ref.QFmt(*qa), ste, order)
+            aX, aW = gref.grad_abs(G, A, B, ref.QFmt(*qp), ref.QFmt(*qa), ste, order)
+            tolX = 2 * (N + 1) * 2.0 ** -24 * aX + 1e-30
+            tolW = 2 * (M + 1) * 2.0 ** -24 * aW + 1e-30
+            assert (np.abs(dX - wX) <= tolX).all(), (M, N, K, ste, "dX", (np.abs(dX - wX) / tolX).max())
+            assert (np.abs(dW - wW) <= tolW).all(), (M, N, K, ste, "dW", (np.abs(dW - wW) / tolW).max())
+
+
+def test_arguments_views_and_degenerate_sizes(ref, gref):
+    rng = np.random.default_rng(99)
+    M, N, K = 40, 36, 50
+    A = codes(rng, (M, K), 5, 10); B = codes(rng, (N, K), 5, 10)
+    G = (rng.integers(-8, 9, (M, N)) / 4.0).astype(np.float32)
+    tA, tB, of = gpu_inputs(ref, A, B, QP, QA)
+    wX, wW = gref.grad(G, A, B, ref.QFmt(*QP), ref.QFmt(*QA), 1)
+    # G at an address that is not 16-byte aligned: the general path
+    buf = torch.zeros(M * N + 1, dtype=torch.float32, device=DEV)
+    buf[1:] = torch.from_numpy(G).to(DEV).reshape(-1)
+    tG = buf[1:].view(M, N)
+    dX, dW = lb.grad(tG, tA, tB, 1, of_plane=of)
+    torch.cuda.synchronize()
+    assert np.array_equal(dX.cpu().numpy(), wX.astype(np.float32)) and np.array_equal(dW.cpu().numpy(), wW.astype(np.float32))
+    # one output only
+    tG = torch.from_numpy(G).to(DEV)
+    dX, none = lb.grad(tG, tA, tB, 1, of_plane=of, want_dw=False)
+    none2, dW = lb.grad(tG, tA, tB, 1, of_plane=of, want_dx=False)
+    torch.cuda.synchronize()
+    assert none is None and none2 is None
+    assert np.array_equal(dX.cpu().numpy(), wX.astype(np.float32)) and np.array_equal(dW.cpu().numpy(), wW.astype(np.float32))
+    # status codes; nothing runs on these
+    g, a, b, o = tG.data_ptr(), tA.data_ptr(), tB.data_ptr(), of.data_ptr()
+    x = torch.empty(M * K, dtype=torch.float32, device=DEV).data_ptr()
+    assert lb.lba_grad(g, a, b, o, None, None, None, M, N, K, 1) == lb.ERR_NULL
+    assert lb.lba_grad(g, a, b, None, None, x, None, M, N, K, 1) == lb.ERR_NULL          # immediate needs the plane
+    assert lb.lba_grad(g, a, b, o, None, x, None, M, N, K, 2) == lb.ERR_NULL             # recursive needs last_of
+    assert lb.lba_grad(None, a, b, o, None, x, None, M, N, K, 0) == lb.ERR_NULL
+    assert lb.lba_grad(g, a, b, o, None, x, None, M, N, K, 7) == lb.ERR_UNSUPPORTED
+    assert lb.lba_grad(g, a, b, o, None, x, None, -1, N, K, 0) == lb.ERR_SHAPE
+    assert lb.lba_last_overflow(o, None, M, N, K) == lb.ERR_NULL
+    # empty sums: N == 0 gives dX = 0
+    dXz = torch.full((M, K), 7.0, dtype=torch.float32, device=DEV)
+    assert lb.lba_grad(None, None, None, None, None, dXz.data_ptr(), None, M, 0, K, 0) == lb.OK
+    torch.cuda.synchronize()
+    assert (dXz == 0).all()
+    assert lb.lba_grad(g, a, b, None, None, x, None, M, N, 0, 0) == lb.OK
