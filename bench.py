@@ -68,6 +68,9 @@ def main():
                     help="accumulator format with b = 2^(E-1)-1 instead of the 12-bit M7E4 (format sweeps)")
     ap.add_argument("--bwd", action="store_true",
                     help="time lba_gemm_bwd (forward chain + both event planes) instead of lba_gemm")
+    ap.add_argument("--grad", default=None, choices=["identity", "immediate", "recursive"],
+                    help="time lba_grad (dX and dW with that estimator's coefficients; the OF planes / last-overflow "
+                         "indices are computed before the timed region) instead of lba_gemm; 2 MACs per forward MAC")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=0, help="threads of the oracle leg (default: min(16, cores))")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
@@ -100,8 +103,36 @@ def main():
         l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, 1 if args.bwd else 0)
         l["C"] = Cbuf[: l["M"] * l["N"]].view(l["M"], l["N"])
         l["macs"] = l["M"] * l["N"] * l["K"]
+    if args.grad:
+        ste = {"identity": 0, "immediate": 1, "recursive": 2}[args.grad]
+        stream = torch.cuda.current_stream().cuda_stream
+        Gbuf = torch.randn(cmax, dtype=torch.float32, device=dev)
+        dXbuf = torch.empty(max(l["M"] * l["K"] for l in layers), dtype=torch.float32, device=dev)
+        dWbuf = torch.empty(max(l["N"] * l["K"] for l in layers), dtype=torch.float32, device=dev)
+        for l in layers:
+            l["macs"] *= 2                                     # dX and dW
+            # VALU issue slots per masked MAC (one wave instruction = 64 MACs; half-rate forms count 2):
+            # v_fmac with a scalar operand 2; + two v_readlane (immediate) or one v_cmp (recursive)
+            l["plan"] = dict(l["plan"], kernel=2, prod_mode=ste, valu_per_mac_x100=(200, 600, 400)[ste])
+            l["of"] = l["last"] = None
+            if ste:
+                _, l["of"], _ = lb.gemm_bwd(l["A"], l["B"], l["qp"], l["qa"], want_c=False)
+            if ste == 2:
+                l["last"] = lb.last_overflow(l["of"], l["K"])
+                l["of"] = None
+        torch.cuda.synchronize()
+
+        def launch(l):
+            rc = lb.lba_grad(Gbuf.data_ptr(), l["A"].data_ptr(), l["B"].data_ptr(),
+                             l["of"].data_ptr() if l["of"] is not None else None,
+                             l["last"].data_ptr() if l["last"] is not None else None,
+                             dXbuf.data_ptr(), dWbuf.data_ptr(), l["M"], l["N"], l["K"], ste, stream)
+            if rc != 0:
+                raise RuntimeError(lb.lba_strerror(rc))
     total_macs = sum(l["macs"] for l in layers)
-    if args.bwd:
+    if args.grad:
+        pass
+    elif args.bwd:
         wmax = max(lb.lba_mask_words(l["M"], l["N"], l["K"]) for l in layers)
         of_buf = torch.empty(wmax, dtype=torch.int32, device=dev)
         uf_buf = torch.empty(wmax, dtype=torch.int32, device=dev)
@@ -169,7 +200,12 @@ def main():
             g = groups.setdefault(key, dict(ms=0.0, macs=0, launches=0, bytes=0, ops=p["valu_per_mac_x100"] / 100.0))
             g["ms"] += ms
             g["macs"] += l["macs"]
-            g["bytes"] += l["M"] * l["K"] + l["N"] * l["K"] + 4 * l["M"] * l["N"]   # A, B once, C once
+            if args.grad:     # g (and the plane or the last-overflow indices) once per product, codes once, outputs once
+                per_prod = 4 * l["M"] * l["N"] + {"identity": 0, "immediate": l["M"] * l["N"] * ((l["K"] + 31) // 32) * 4,
+                                                  "recursive": 4 * l["M"] * l["N"]}[args.grad]
+                g["bytes"] += 2 * per_prod + 5 * (l["M"] * l["K"] + l["N"] * l["K"])
+            else:
+                g["bytes"] += l["M"] * l["K"] + l["N"] * l["K"] + 4 * l["M"] * l["N"]   # A, B once, C once
             g["launches"] += 1
     dom_key = max(groups, key=lambda k: groups[k]["ms"])
     dom = groups[dom_key]
@@ -177,8 +213,8 @@ def main():
     roofline = {
         "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
         "frac": achieved / PEAK_LANE_OPS,
-        "traffic": RESNET50_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "resnet50" and rnd == 0 and order == 0 and not args.bwd) else None,
-        "kernel": "lba_%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (
+        "traffic": RESNET50_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "resnet50" and rnd == 0 and order == 0 and not args.bwd and not args.grad) else None,
+        "kernel": ("lba_grad_kernel<%s>" % args.grad) if args.grad else "lba_%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (
             ("fast_bwd" if args.bwd else "fast") if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
             "rne" if dom_key[2] else "floor"),
         "algorithmic_bytes": dom["bytes"] / dom["launches"],
@@ -204,10 +240,10 @@ def main():
                                 "bert": "BERT-base linears, 4096 tokens", "gemm4096": "4096^3 GEMM",
                                 "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}[args.workload],
                    "macs_per_step": total_macs, "qprod": "M7E5 b=15", "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
-                   "call": ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else "lba_gemm_bwd (C + OF and UF planes)") if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b"},
+                   "call": ("lba_grad, %s estimator: dX and dW (2 masked MACs per forward MAC)" % args.grad) if args.grad else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else "lba_gemm_bwd (C + OF and UF planes)") if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b"},
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not args.grad:
         # a mid-sized layer whose output is still in the shared buffer: recompute it last
         pick = max(range(len(layers)), key=lambda i: (layers[i]["K"] == 576, layers[i]["M"]))
         l = layers[pick]

@@ -156,6 +156,105 @@ __device__ __forceinline__ void grad_block(float (&acc)[16], int ib, int r0, int
     }
 }
 
+// Immediate estimator, plane words delivered through vector registers: w0..w3 hold (already complemented)
+// plane words, one per lane; the word pair of fmac u sits in lanes L<u> (k0..k0+31) and L<u> + 32
+// (k0+32..k0+63) of register w<u>.  v_readlane moves it to scalar registers, from there into the execution
+// mask.  v_readlane ignores the execution mask, so the changed mask does not disturb the next read.
+template <int L0, int L1, int L2, int L3>
+__device__ __forceinline__ void masked_fmac4_lanes(float& acc, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3,
+                                                   const float (&g)[4], const float (&v)[4]) {
+    uint64_t save;
+    uint32_t tl, th;
+    asm volatile(
+        "s_mov_b64 %[sv], exec\n\t"
+        "v_readlane_b32 %[tl], %[w0], %[a0]\n\tv_readlane_b32 %[th], %[w0], %[b0]\n\t"
+        "s_mov_b32 exec_lo, %[tl]\n\ts_mov_b32 exec_hi, %[th]\n\tv_fmac_f32 %[a], %[g0], %[v0]\n\t"
+        "v_readlane_b32 %[tl], %[w1], %[a1]\n\tv_readlane_b32 %[th], %[w1], %[b1]\n\t"
+        "s_mov_b32 exec_lo, %[tl]\n\ts_mov_b32 exec_hi, %[th]\n\tv_fmac_f32 %[a], %[g1], %[v1]\n\t"
+        "v_readlane_b32 %[tl], %[w2], %[a2]\n\tv_readlane_b32 %[th], %[w2], %[b2]\n\t"
+        "s_mov_b32 exec_lo, %[tl]\n\ts_mov_b32 exec_hi, %[th]\n\tv_fmac_f32 %[a], %[g2], %[v2]\n\t"
+        "v_readlane_b32 %[tl], %[w3], %[a3]\n\tv_readlane_b32 %[th], %[w3], %[b3]\n\t"
+        "s_mov_b32 exec_lo, %[tl]\n\ts_mov_b32 exec_hi, %[th]\n\tv_fmac_f32 %[a], %[g3], %[v3]\n\t"
+        "s_mov_b64 exec, %[sv]"
+        : [a] "+v"(acc), [sv] "=&s"(save), [tl] "=&s"(tl), [th] "=&s"(th)
+        : [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3),
+          [a0] "n"(L0), [b0] "n"(L0 + 32), [a1] "n"(L1), [b1] "n"(L1 + 32),
+          [a2] "n"(L2), [b2] "n"(L2 + 32), [a3] "n"(L3), [b3] "n"(L3 + 32),
+          [g0] "s"(g[0]), [g1] "s"(g[1]), [g2] "s"(g[2]), [g3] "s"(g[3]),
+          [v0] "v"(v[0]), [v1] "v"(v[1]), [v2] "v"(v[2]), [v3] "v"(v[3]));
+}
+
+// One accumulator row I (0..15) against the four s of group UB (0..3) of a 16-s super-step.
+// Word (i, u) of slab h lives in lane h*32 + a*2 + (b >> 3), register w[b & 7], with (a, b) = (i, u)
+// when the plane is contiguous along s and (u, i) when it is contiguous along r.
+template <bool S_CONTIG, int I, int UB>
+__device__ __forceinline__ void lanes_row(float& acc, const uint32_t (&w)[8], const float (&g)[4], const float (&v)[4]) {
+    constexpr int U0 = 4 * UB;
+    if (S_CONTIG) {
+        constexpr int L = I * 2 + (U0 >> 3);                 // the four u share a lane, registers (U0 & 7) ..
+        masked_fmac4_lanes<L, L, L, L>(acc, w[(U0 & 7) + 0], w[(U0 & 7) + 1], w[(U0 & 7) + 2], w[(U0 & 7) + 3], g, v);
+    } else {
+        constexpr int R = I & 7, H = I >> 3;                 // one register, lanes of the four u
+        masked_fmac4_lanes<(U0 + 0) * 2 + H, (U0 + 1) * 2 + H, (U0 + 2) * 2 + H, (U0 + 3) * 2 + H>(acc, w[R], w[R], w[R], w[R], g, v);
+    }
+}
+
+template <bool S_CONTIG, int IB, int UB>
+__device__ __forceinline__ void lanes_block(float (&acc)[16], int r0, int s, const float (&v)[16],
+                                            const float* __restrict__ G, const uint32_t (&w)[8], const GradDims& d) {
+    float g[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a) {
+        const uint32_t off = S_CONTIG ? (uint32_t)(r0 + 4 * IB + a) * (uint32_t)d.stride_r + (uint32_t)(s + 4 * UB)
+                                      : (uint32_t)(s + 4 * UB + a) * (uint32_t)d.stride_s + (uint32_t)(r0 + 4 * IB);
+        const float4 gv = *reinterpret_cast<const float4*>(G + off);
+        const float ga[4] = {gv.x, gv.y, gv.z, gv.w};
+#pragma unroll
+        for (int b = 0; b < 4; ++b) g[S_CONTIG ? a : b][S_CONTIG ? b : a] = ga[b];
+    }
+    const float vv[4] = {v[4 * UB + 0], v[4 * UB + 1], v[4 * UB + 2], v[4 * UB + 3]};
+    lanes_row<S_CONTIG, 4 * IB + 0, UB>(acc[4 * IB + 0], w, g[0], vv);
+    lanes_row<S_CONTIG, 4 * IB + 1, UB>(acc[4 * IB + 1], w, g[1], vv);
+    lanes_row<S_CONTIG, 4 * IB + 2, UB>(acc[4 * IB + 2], w, g[2], vv);
+    lanes_row<S_CONTIG, 4 * IB + 3, UB>(acc[4 * IB + 3], w, g[3], vv);
+}
+
+template <bool S_CONTIG, int IB>
+__device__ __forceinline__ void lanes_rows(float (&acc)[16], int r0, int s, const float (&v)[16],
+                                           const float* __restrict__ G, const uint32_t (&w)[8], const GradDims& d) {
+    lanes_block<S_CONTIG, IB, 0>(acc, r0, s, v, G, w, d);
+    lanes_block<S_CONTIG, IB, 1>(acc, r0, s, v, G, w, d);
+    lanes_block<S_CONTIG, IB, 2>(acc, r0, s, v, G, w, d);
+    lanes_block<S_CONTIG, IB, 3>(acc, r0, s, v, G, w, d);
+}
+
+// 16 rows x 16 s of the immediate estimator.  The 512 plane words of the step (two slabs) are fetched with
+// two 16-byte vector loads per lane (many in flight: the plane is streamed once and never reused, which
+// the scalar-load path cannot sustain), complemented, and handed out lane by lane.
+template <bool S_CONTIG>
+__device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, int s, int k, int lane,
+                                                    const uint8_t* __restrict__ V, const float* __restrict__ G,
+                                                    const uint32_t* __restrict__ P0, const uint32_t* __restrict__ P1,
+                                                    const GradDims& d) {
+    const int q = lane & 31, a = q >> 1, half8 = (q & 1) * 8;
+    const uint32_t* __restrict__ P = (lane & 32) ? P1 : P0;
+    const uint32_t off = S_CONTIG ? (uint32_t)(r0 + a) * (uint32_t)d.stride_r + (uint32_t)(s + half8)
+                                  : (uint32_t)(s + a) * (uint32_t)d.stride_s + (uint32_t)(r0 + half8);
+    const uint4 x = *reinterpret_cast<const uint4*>(P + off);
+    const uint4 y = *reinterpret_cast<const uint4*>(P + off + 4);
+    const uint32_t w[8] = {~x.x, ~x.y, ~x.z, ~x.w, ~y.x, ~y.y, ~y.z, ~y.w};   // c = 1 - OF
+    float v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const uint32_t code = (k < d.K) ? V[(int64_t)(s + u) * d.K + k] : 0u;
+        v[u] = decode_e4m3(code);
+    }
+    lanes_rows<S_CONTIG, 0>(acc, r0, s, v, G, w, d);
+    lanes_rows<S_CONTIG, 1>(acc, r0, s, v, G, w, d);
+    lanes_rows<S_CONTIG, 2>(acc, r0, s, v, G, w, d);
+    lanes_rows<S_CONTIG, 3>(acc, r0, s, v, G, w, d);
+}
+
 template <int MODE, bool S_CONTIG>
 __global__ void __launch_bounds__(256) lba_grad_kernel(const float* __restrict__ G, const uint8_t* __restrict__ V,
                                                        const uint32_t* __restrict__ plane,
@@ -178,7 +277,11 @@ __global__ void __launch_bounds__(256) lba_grad_kernel(const float* __restrict__
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
 
-    for (int s = s_begin; s < s_end; s += 4) {
+    int s = s_begin;
+    if (MODE == LBA_STE_IMMEDIATE_OF && rows_fast) {
+        for (; s + 16 <= s_end; s += 16) immediate_superstep<S_CONTIG>(acc, r0, s, k, lane, V, G, P0, P1, d);
+    }
+    for (; s < s_end; s += 4) {
         float v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
