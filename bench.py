@@ -68,6 +68,7 @@ def main():
                     help="accumulator format with b = 2^(E-1)-1 instead of the 12-bit M7E4 (format sweeps)")
     ap.add_argument("--bwd", action="store_true",
                     help="time lba_gemm_bwd (forward chain + both event planes) instead of lba_gemm")
+    ap.add_argument("--of-only", action="store_true", help="with --bwd: ask for the overflow plane only")
     ap.add_argument("--grad", default=None, choices=["identity", "immediate", "recursive"],
                     help="time lba_grad (dX and dW with that estimator's coefficients; the OF planes / last-overflow "
                          "indices are computed before the timed region) instead of lba_gemm; 2 MACs per forward MAC")
@@ -150,7 +151,7 @@ def main():
                                              l["M"], l["N"], l["K"], l["qp"], l["qa"], stream)
             else:
                 rc = lb.lba_gemm_bwd(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
-                                     uf_buf.data_ptr(), l["M"], l["N"], l["K"], l["qp"], l["qa"], order, stream)
+                                     None if args.of_only else uf_buf.data_ptr(), l["M"], l["N"], l["K"], l["qp"], l["qa"], order, stream)
             if rc != 0:
                 raise RuntimeError(lb.lba_strerror(rc))
     else:
@@ -240,7 +241,7 @@ def main():
                                 "bert": "BERT-base linears, 4096 tokens", "gemm4096": "4096^3 GEMM",
                                 "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}[args.workload],
                    "macs_per_step": total_macs, "qprod": "M7E5 b=15", "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
-                   "call": ("lba_grad, %s estimator: dX and dW (2 masked MACs per forward MAC)" % args.grad) if args.grad else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else "lba_gemm_bwd (C + OF and UF planes)") if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b"},
+                   "call": ("lba_grad, %s estimator: dX and dW (2 masked MACs per forward MAC)" % args.grad) if args.grad else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else ("lba_gemm_bwd (C + OF plane)" if args.of_only else "lba_gemm_bwd (C + OF and UF planes)")) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b"},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline and not args.grad:

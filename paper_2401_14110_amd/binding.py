@@ -185,35 +185,36 @@ def gemm_batched(A, B, qprod, qacc, order=ORDER_SEQ, stream=None):
     return C
 
 
-def gemm_bwd(A, B, qprod, qacc, order=ORDER_SEQ, want_c=True, stream=None):
-    """Returns (C or None, OF plane, UF plane); planes are int32 tensors [ceil(K/32), M, N]."""
+def gemm_bwd(A, B, qprod, qacc, order=ORDER_SEQ, want_c=True, stream=None, want_uf=True):
+    """Returns (C or None, OF plane, UF plane or None); planes are int32 tensors [ceil(K/32), M, N]."""
     A, B = _ops(A, B)
     M, K = A.shape
     N = B.shape[0]
     W = (K + 31) // 32
     C = torch.empty((M, N), dtype=torch.float32, device=A.device) if want_c else None
     of = torch.empty((W, M, N), dtype=torch.int32, device=A.device)
-    uf = torch.empty((W, M, N), dtype=torch.int32, device=A.device)
+    uf = torch.empty((W, M, N), dtype=torch.int32, device=A.device) if want_uf else None
     _check(lib().lba_gemm_bwd(A.data_ptr() or None, B.data_ptr() or None,
                               (C.data_ptr() or None) if want_c else None,
-                              of.data_ptr() or None, uf.data_ptr() or None,
+                              of.data_ptr() or None, (uf.data_ptr() or None) if want_uf else None,
                               M, N, K, qfmt(qprod), qfmt(qacc), order, _stream(stream)))
     return C, of, uf
 
 
-def gemm_bwd_chunked(A, B, qprod, qacc, want_c=True, stream=None):
+def gemm_bwd_chunked(A, B, qprod, qacc, want_c=True, stream=None, want_uf=True):
     """Chunked order.  Returns (C or None, OF, UF, OF2, UF2): first-level planes [ceil(K/32), M, N] and
-    second-level planes [ceil(ceil(K/16)/32), M, N], int32 tensors."""
+    second-level planes [ceil(ceil(K/16)/32), M, N], int32 tensors (UF, UF2 are None without want_uf)."""
     A, B = _ops(A, B)
     M, K = A.shape
     N = B.shape[0]
     W = (K + 31) // 32
     W2 = ((K + 15) // 16 + 31) // 32
     C = torch.empty((M, N), dtype=torch.float32, device=A.device) if want_c else None
-    planes = [torch.empty((w, M, N), dtype=torch.int32, device=A.device) for w in (W, W, W2, W2)]
+    planes = [torch.empty((w, M, N), dtype=torch.int32, device=A.device) if (want_uf or i % 2 == 0) else None
+              for i, w in enumerate((W, W, W2, W2))]
     _check(lib().lba_gemm_bwd_chunked(A.data_ptr() or None, B.data_ptr() or None,
                                       (C.data_ptr() or None) if want_c else None,
-                                      *[t.data_ptr() or None for t in planes],
+                                      *[(t.data_ptr() or None) if t is not None else None for t in planes],
                                       M, N, K, qfmt(qprod), qfmt(qacc), _stream(stream)))
     return (C, *planes)
 

@@ -557,7 +557,10 @@ __device__ __forceinline__ void store_event_words(uint32_t* of_plane, uint32_t* 
 // T <- Q_acc(T + S) with its own two event bits, and S restarts from 0.  T and S are values of Q_acc's
 // grid (zero or normal numbers), so T + S is exactly zero iff S == -T.  The extra registers (T and the
 // second-level words) are paid for with two instead of four waves per SIMD.
-template <int PM, int ORDER>
+// UF = false (no underflow plane asked for): the underflow tests are dropped, and under the sequential
+// order a k-tile that starts with every |S| of the wave below R_OF - BK * max|p| cannot overflow at all:
+// it runs the forward kernel's clamp-free tile and its OF words are zero.
+template <int PM, int ORDER, bool UF>
 __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_fast_bwd_kernel(const KParams p) {
     constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
     constexpr int STAGE = BK * (BM + BN);
@@ -580,6 +583,10 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
     float kc = p.kc, rof = p.rof_a, rofp = p.rof_p, kc_up = p.kc * 0x1p60f, up = 0x1p60f;
     uint32_t mask = p.mask_a;
     asm volatile("" : "+v"(kc), "+v"(rof), "+v"(rofp), "+v"(mask), "+v"(kc_up), "+v"(up));
+    FastConst fc;
+    fc.kc = kc; fc.rof = rof; fc.rofp = rofp; fc.mask = mask; fc.half = 0u; fc.sh = p.sh_a;
+    float thresh = p.fast_thresh;
+    asm volatile("" : "+v"(thresh));
 
     float acc[TM][TN], top[TM][TN];
     uint32_t wof[TM][TN], wuf[TM][TN], wof2[TM][TN], wuf2[TM][TN];
@@ -608,6 +615,61 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
             fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
             fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
+        bool quiet = false;                                    // no sum of this tile can reach R_OF
+        if (!UF && ORDER == LBA_ORDER_SEQ) {
+            float mx = 0.0f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; j += 2)
+                    mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(acc[i][j]), __builtin_fabsf(acc[i][j + 1])));
+            quiet = __all(mx < thresh);
+        }
+        if (quiet) {
+            fast_tile<PM, LBA_ROUND_FLOOR, LBA_ORDER_SEQ, false, TM, TN, BK, BM, BN>(acc, top, As, Bs, tx, ty, fc);
+        } else if (!UF) {
+#pragma unroll 4
+            for (int k = 0; k < BK; ++k) {
+                float a[TM], b[TN];
+                read_operands<TM, TN, BM, BN>(As, Bs, k, tx, ty, a, b);
+                float q[TM][TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) q[i][j] = a[i] * b[j];
+                if (PM == PM_FLUSH_CLAMP) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) q[i][j] = med3(q[i][j], -rofp, rofp);
+                }
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        float tsum = __builtin_fmaf(q[i][j], kc, acc[i][j]);
+                        tsum = __uint_as_float(__float_as_uint(tsum) & mask);
+                        tsum = med3(tsum, -rof, rof);
+                        const uint64_t of = __builtin_amdgcn_ballot_w64(__builtin_fabsf(tsum) == rof);
+                        acc[i][j] = tsum;
+                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof[i][j]) : "s"(of) : "vcc");
+                    }
+                if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) {
+                            float u = top[i][j] + acc[i][j];
+                            u = __uint_as_float(__float_as_uint(u) & mask);
+                            u = med3(u, -rof, rof);
+                            const uint64_t of = __builtin_amdgcn_ballot_w64(__builtin_fabsf(u) == rof);
+                            top[i][j] = u;
+                            acc[i][j] = 0.0f;
+                            asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof2[i][j]) : "s"(of) : "vcc");
+                        }
+                }
+            }
+        } else
 #pragma unroll 4
         for (int k = 0; k < BK; ++k) {
             float a[TM], b[TN];
@@ -669,11 +731,11 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
                     }
             }
         }
-        store_event_words(p.of_mask, p.uf_mask, t, 32, p.K - t * BK, wof, wuf, m0, n0, tx, ty, p);
+        store_event_words(p.of_mask, UF ? p.uf_mask : nullptr, t, 32, p.K - t * BK, wof, wuf, m0, n0, tx, ty, p);
         if (ORDER == LBA_ORDER_CHUNK16 && ((t & 15) == 15 || !more)) {
             // two chunks per k-tile: a second-level word is complete after 16 tiles
             const int chunks = (p.K + 15) >> 4;
-            store_event_words(p.of_mask2, p.uf_mask2, t >> 4, 2 * ((t & 15) + 1), chunks - 32 * (t >> 4),
+            store_event_words(p.of_mask2, UF ? p.uf_mask2 : nullptr, t >> 4, 2 * ((t & 15) + 1), chunks - 32 * (t >> 4),
                               wof2, wuf2, m0, n0, tx, ty, p);
         }
         if (more) {
@@ -948,13 +1010,16 @@ static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
     if (pl.kernel == KERNEL_FAST && pl.events) {
         const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
+        const bool uf = pl.kp.uf_mask != nullptr || pl.kp.uf_mask2 != nullptr;
+#define LBA_BWD(PM, ORDER, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, ORDER, UF>), grid, block, 0, st, pl.kp)
         if (pl.order == LBA_ORDER_CHUNK16) {
-            if (pl.prod_mode == PM_FLUSH) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH, LBA_ORDER_CHUNK16>), grid, block, 0, st, pl.kp);
-            else                          hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH_CLAMP, LBA_ORDER_CHUNK16>), grid, block, 0, st, pl.kp);
+            if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD(PM_FLUSH, LBA_ORDER_CHUNK16, true); else LBA_BWD(PM_FLUSH, LBA_ORDER_CHUNK16, false); }
+            else                          { if (uf) LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_CHUNK16, true); else LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_CHUNK16, false); }
         } else {
-            if (pl.prod_mode == PM_FLUSH) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH, LBA_ORDER_SEQ>), grid, block, 0, st, pl.kp);
-            else                          hipLaunchKernelGGL((lba_fast_bwd_kernel<PM_FLUSH_CLAMP, LBA_ORDER_SEQ>), grid, block, 0, st, pl.kp);
+            if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD(PM_FLUSH, LBA_ORDER_SEQ, true); else LBA_BWD(PM_FLUSH, LBA_ORDER_SEQ, false); }
+            else                          { if (uf) LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_SEQ, true); else LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_SEQ, false); }
         }
+#undef LBA_BWD
         return hipGetLastError();
     }
     if (pl.kernel == KERNEL_FAST) {

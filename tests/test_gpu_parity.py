@@ -385,3 +385,32 @@ def test_event_planes_of_the_chunked_order(ref):
                                    (5, 7, 15, 0), (4, 7, 7, 0)) == lb.ERR_NULL
     assert lb.lba_gemm_bwd(tA.data_ptr(), tB.data_ptr(), None, of2.data_ptr(), None, 20, 24, 40,
                            (5, 7, 15, 0), (4, 7, 7, 0), order=1) == lb.ERR_UNSUPPORTED
+
+
+def test_overflow_plane_alone(ref):
+    # without an underflow plane the recompute call runs its overflow-only variant; under the sequential
+    # order k-tiles that cannot overflow take the forward kernel's tile.  Small operands (no event at all),
+    # full-range operands (events in most tiles) and a mix (quiet start, loud end) must all give the
+    # oracle's OF plane and C.
+    rng = np.random.default_rng(85)
+    for (M, N, K), lo, hi in [((70, 66, 200), 0, 6), ((70, 66, 200), 0, 15), ((64, 64, 96), 3, 9), ((33, 130, 530), 2, 10),
+                              ((5, 3, 31), 0, 15)]:
+        A = rand_codes(rng, (M, K), lo, hi); B = rand_codes(rng, (N, K), lo, hi)
+        if (lo, hi) == (3, 9):
+            A[:, 64:] = rand_codes(rng, (M, K - 64), 10, 15)           # loud last tile
+        tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+        for qp, qa in [FMT_PAPER[0], FMT_PAPER[1], FMT_PAPER[2], FMT_ODD[1]]:
+            qpf, qaf = qp + (0,), qa + (0,)
+            C, of, none = lb.gemm_bwd(tA, tB, qpf, qaf, want_uf=False)
+            torch.cuda.synchronize()
+            wc, wof, _ = ref.gemm_bwd(A, B, fm(ref, qpf), fm(ref, qaf))
+            assert none is None
+            assert np.array_equal(bits(C.cpu().numpy()), bits(wc)), (M, N, K, qpf, qaf)
+            assert np.array_equal(of.cpu().numpy().view(np.uint32), wof), (M, N, K, qpf, qaf)
+            got = lb.gemm_bwd_chunked(tA, tB, qpf, qaf, want_uf=False)
+            torch.cuda.synchronize()
+            want = ref.gemm_bwd(A, B, fm(ref, qpf), fm(ref, qaf), order=ref.ORDER_CHUNK16, level2=True)
+            assert got[2] is None and got[4] is None
+            assert np.array_equal(bits(got[0].cpu().numpy()), bits(want[0]))
+            assert np.array_equal(got[1].cpu().numpy().view(np.uint32), want[1])
+            assert np.array_equal(got[3].cpu().numpy().view(np.uint32), want[3])
