@@ -115,12 +115,29 @@ size_t lba_mask_words(int64_t M, int64_t N, int64_t K);
  *                         lba_gemm_bwd or lba_gemm_bwd_chunked (the second level has no product pair).
  *   LBA_STE_RECURSIVE_OF  c_k = product of STE^OF over all steps i >= k of the sequential chain, i.e.
  *                         [k > last_of[m, n]].  Needs last_of from lba_last_overflow.  (Chunked order:
- *                         the path also runs through the second level; not provided.)
+ *                         the path also runs through the second level: build the coefficient plane
+ *                         with lba_ste_plane and pass it with LBA_STE_COEF_PLANE.)
+ *   LBA_STE_COEF_PLANE    c is read from of_mask as it is (a plane written by lba_ste_plane).
  * Arithmetic: FP32 products and FP32 sums.  The order of the summation is unspecified (the sum may be
  * split across workgroups and combined with atomic adds), so results are reproducible up to FP32
  * rounding: |error| <= (terms + 1) * 2^-24 * sum of |terms| to first order.
  */
-enum { LBA_STE_IDENTITY = 0, LBA_STE_IMMEDIATE_OF = 1, LBA_STE_RECURSIVE_OF = 2 };
+enum { LBA_STE_IDENTITY = 0, LBA_STE_IMMEDIATE_OF = 1, LBA_STE_RECURSIVE_OF = 2,
+       LBA_STE_COEF_PLANE = 3 };   /* lba_grad only: of_mask holds the coefficients themselves (lba_ste_plane) */
+
+/* Coefficient plane of an estimator from the event planes of the recompute call: bit k % 32 of word
+ * ((k/32)*M + m)*N + n is c[m, n, k] (1: the gradient of that step passes); bits for k >= K are 0.
+ *   ste = LBA_STE_IMMEDIATE_OF: c_k = 1 - OF_k (either order; of_mask2 is ignored).
+ *   ste = LBA_STE_RECURSIVE_OF, order = LBA_ORDER_SEQ: c_k = 1 iff no step i >= k overflowed.
+ *   ste = LBA_STE_RECURSIVE_OF, order = LBA_ORDER_CHUNK16: the path of step k is the rest of its chunk's
+ *     chain and then the second-level adds of the chunks j >= k / 16 (App. D, last paragraph: the tree of
+ *     Fig. 1 with the arrows reversed): c_k = 1 iff none of them overflowed.  Needs of_mask2, the
+ *     second-level OF plane of lba_gemm_bwd_chunked.
+ * coef has lba_mask_words(M, N, K) words and may be the same buffer as of_mask (in place).  The plane is
+ * consumed by lba_grad with ste = LBA_STE_COEF_PLANE.
+ * Returns LBA_OK, LBA_ERR_NULL, LBA_ERR_SHAPE, LBA_ERR_UNSUPPORTED (ste or order) or LBA_ERR_LAUNCH. */
+int lba_ste_plane(const uint32_t* of_mask, const uint32_t* of_mask2, uint32_t* coef,
+                  int64_t M, int64_t N, int64_t K, int32_t ste, int32_t order, void* hip_stream);
 
 /* The recursive estimator's post-pass (App. D): last_of[m*N + n] = the largest k whose bit is set in the
  * OF plane of lba_gemm_bwd, or -1 when the chain never overflowed.  of_mask: lba_mask_words(M, N, K)

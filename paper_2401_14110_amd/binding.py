@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIBPATH = os.path.join(_HERE, "liblba_hip.so")
 
 ROUND_FLOOR, ROUND_RNE = 0, 1
-STE_IDENTITY, STE_IMMEDIATE_OF, STE_RECURSIVE_OF = 0, 1, 2
+STE_IDENTITY, STE_IMMEDIATE_OF, STE_RECURSIVE_OF, STE_COEF_PLANE = 0, 1, 2, 3
 ORDER_SEQ, ORDER_CHUNK16 = 0, 1
 OK, ERR_NULL, ERR_SHAPE, ERR_FORMAT, ERR_UNSUPPORTED, ERR_ALIGN, ERR_LAUNCH = range(7)
 
@@ -58,6 +58,8 @@ def lib():
         L.lba_mask_words_level2.argtypes = [i64, i64, i64]
         L.lba_last_overflow.restype = ctypes.c_int
         L.lba_last_overflow.argtypes = [vp, vp, i64, i64, i64, vp]
+        L.lba_ste_plane.restype = ctypes.c_int
+        L.lba_ste_plane.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
         L.lba_grad.restype = ctypes.c_int
         L.lba_grad.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
         L.lba_mask_words.restype = ctypes.c_size_t
@@ -123,6 +125,11 @@ def lba_gemm_bwd_chunked(A, B, C, of_mask, uf_mask, of_mask2, uf_mask2, M, N, K,
 def lba_last_overflow(of_mask, last_of, M, N, K, hip_stream=None):
     return lib().lba_last_overflow(of_mask, last_of, M, N, K,
                                    ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_ste_plane(of_mask, of_mask2, coef, M, N, K, ste, order, hip_stream=None):
+    return lib().lba_ste_plane(of_mask, of_mask2, coef, M, N, K, ste, order,
+                               ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
 
 
 def lba_grad(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, hip_stream=None):
@@ -241,3 +248,13 @@ def grad(G, A, B, ste, of_plane=None, last_of=None, want_dx=True, want_dw=True, 
     _check(lib().lba_grad(ptr(G), ptr(A), ptr(B), ptr(of_plane), ptr(last_of), ptr(dX), ptr(dW), M, N, K, ste,
                           _stream(stream)))
     return dX, dW
+
+
+def ste_plane(of_plane, K, ste, order=ORDER_SEQ, of_plane2=None, stream=None):
+    """Coefficient plane (int32 [ceil(K/32), M, N], bit = 1: passes) of an estimator from the OF plane(s)."""
+    W, M, N = of_plane.shape
+    out = torch.empty_like(of_plane)
+    _check(lib().lba_ste_plane(of_plane.data_ptr() or None,
+                               (of_plane2.data_ptr() or None) if of_plane2 is not None else None,
+                               out.data_ptr() or None, M, N, K, ste, order, _stream(stream)))
+    return out

@@ -37,6 +37,7 @@ struct GradDims {
     int32_t s_chunk;           // s values per grid z
     int32_t atomic;            // 1: gridDim.z > 1, combine with atomic adds
     int32_t vec_ok;            // 1: G, the plane and last_of are 16-byte aligned and N % 4 == 0 (wide scalar loads)
+    uint32_t plane_xor;        // 0xFFFFFFFF: the plane holds OF bits (c = 1 - bit); 0: it holds the coefficients
 };
 
 __device__ __forceinline__ float decode_e4m3(uint32_t code) {
@@ -45,24 +46,25 @@ __device__ __forceinline__ float decode_e4m3(uint32_t code) {
     return v;
 }
 
-// acc += g[u] * v[u] on the lanes whose OF bit is clear, u = 0..3: the complement of the two OF words
-// (k0..k0+31 and k0+32..k0+63) is written straight into the execution mask.  The mask is saved and
-// restored inside the statement, so the surrounding code never sees it changed.
+// acc += g[u] * v[u] on the lanes whose coefficient bit is set, u = 0..3: the two plane words
+// (k0..k0+31 and k0+32..k0+63), xor-ed with `flip` (all ones for an OF plane, whose complement is the
+// coefficient), are written straight into the execution mask.  The mask is saved and restored inside
+// the statement, so the surrounding code never sees it changed.
 __device__ __forceinline__ void masked_fmac4(float& acc, const uint32_t (&lo)[4], const uint32_t (&hi)[4],
-                                             const float (&g)[4], const float (&v)[4]) {
+                                             const float (&g)[4], const float (&v)[4], uint32_t flip) {
     uint64_t save;
     asm volatile(
         "s_mov_b64 %[sv], exec\n\t"
-        "s_not_b32 exec_lo, %[l0]\n\ts_not_b32 exec_hi, %[h0]\n\tv_fmac_f32 %[a], %[g0], %[v0]\n\t"
-        "s_not_b32 exec_lo, %[l1]\n\ts_not_b32 exec_hi, %[h1]\n\tv_fmac_f32 %[a], %[g1], %[v1]\n\t"
-        "s_not_b32 exec_lo, %[l2]\n\ts_not_b32 exec_hi, %[h2]\n\tv_fmac_f32 %[a], %[g2], %[v2]\n\t"
-        "s_not_b32 exec_lo, %[l3]\n\ts_not_b32 exec_hi, %[h3]\n\tv_fmac_f32 %[a], %[g3], %[v3]\n\t"
+        "s_xor_b32 exec_lo, %[l0], %[f]\n\ts_xor_b32 exec_hi, %[h0], %[f]\n\tv_fmac_f32 %[a], %[g0], %[v0]\n\t"
+        "s_xor_b32 exec_lo, %[l1], %[f]\n\ts_xor_b32 exec_hi, %[h1], %[f]\n\tv_fmac_f32 %[a], %[g1], %[v1]\n\t"
+        "s_xor_b32 exec_lo, %[l2], %[f]\n\ts_xor_b32 exec_hi, %[h2], %[f]\n\tv_fmac_f32 %[a], %[g2], %[v2]\n\t"
+        "s_xor_b32 exec_lo, %[l3], %[f]\n\ts_xor_b32 exec_hi, %[h3], %[f]\n\tv_fmac_f32 %[a], %[g3], %[v3]\n\t"
         "s_mov_b64 exec, %[sv]"
         : [a] "+v"(acc), [sv] "=&s"(save)
         : [l0] "s"(lo[0]), [h0] "s"(hi[0]), [g0] "s"(g[0]), [v0] "v"(v[0]),
           [l1] "s"(lo[1]), [h1] "s"(hi[1]), [g1] "s"(g[1]), [v1] "v"(v[1]),
           [l2] "s"(lo[2]), [h2] "s"(hi[2]), [g2] "s"(g[2]), [v2] "v"(v[2]),
-          [l3] "s"(lo[3]), [h3] "s"(hi[3]), [g3] "s"(g[3]), [v3] "v"(v[3])
+          [l3] "s"(lo[3]), [h3] "s"(hi[3]), [g3] "s"(g[3]), [v3] "v"(v[3]), [f] "s"(flip)
         : "scc");
 }
 
@@ -149,7 +151,7 @@ __device__ __forceinline__ void grad_block(float (&acc)[16], int ib, int r0, int
 #pragma unroll
             for (int u = 0; u < 4; ++u) acc[ib + i] = __builtin_fmaf(g[i][u], v[u], acc[ib + i]);
         } else if (MODE == LBA_STE_IMMEDIATE_OF) {
-            masked_fmac4(acc[ib + i], lo[i], hi[i], g[i], v);
+            masked_fmac4(acc[ib + i], lo[i], hi[i], g[i], v, d.plane_xor);
         } else {
             recursive_fmac4(acc[ib + i], k, last[i], g[i], v);
         }
@@ -230,7 +232,7 @@ __device__ __forceinline__ void lanes_rows(float (&acc)[16], int r0, int s, cons
 
 // 16 rows x 16 s of the immediate estimator.  The 512 plane words of the step (two slabs) are fetched with
 // two 16-byte vector loads per lane (many in flight: the plane is streamed once and never reused, which
-// the scalar-load path cannot sustain), complemented, and handed out lane by lane.
+// the scalar-load path cannot sustain), turned into coefficients, and handed out lane by lane.
 template <bool S_CONTIG>
 __device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, int s, int k, int lane,
                                                     const uint8_t* __restrict__ V, const float* __restrict__ G,
@@ -242,7 +244,8 @@ __device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, in
                                   : (uint32_t)(s + a) * (uint32_t)d.stride_s + (uint32_t)(r0 + half8);
     const uint4 x = *reinterpret_cast<const uint4*>(P + off);
     const uint4 y = *reinterpret_cast<const uint4*>(P + off + 4);
-    const uint32_t w[8] = {~x.x, ~x.y, ~x.z, ~x.w, ~y.x, ~y.y, ~y.z, ~y.w};   // c = 1 - OF
+    const uint32_t f = d.plane_xor;                            // OF plane: c = 1 - OF
+    const uint32_t w[8] = {x.x ^ f, x.y ^ f, x.z ^ f, x.w ^ f, y.x ^ f, y.y ^ f, y.z ^ f, y.w ^ f};
     float v[16];
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
@@ -331,6 +334,51 @@ __global__ void __launch_bounds__(256) lba_last_overflow_kernel(const uint32_t* 
     last_of[i] = last;
 }
 
+// Bits of a 32-bit (or, with `width` = 16, 16-bit) event field strictly above its highest set bit; all of
+// them when no bit is set: the steps after the last overflow of the field.
+__device__ __forceinline__ uint32_t above_last(uint32_t x, uint32_t field) {
+    if (x == 0u) return field;
+    const int msb = 31 - __builtin_clz(x);
+    return msb == 31 ? 0u : (field & ~((2u << msb) - 1u));
+}
+
+// Coefficient plane (bit = 1: the gradient of that step passes) from the event planes; one lane per output,
+// walking the word slabs from the top with the "no overflow further along the path" state.
+//   immediate: c_k = 1 - OF_k.
+//   recursive, sequential order: c_k = no OF at any step >= k.
+//   recursive, chunked order: c_k = no OF at the steps >= k of k's chunk and no OF2 at the chunks >= k / 16.
+template <int STE, int ORDER>
+__global__ void __launch_bounds__(256) lba_ste_plane_kernel(const uint32_t* of1, const uint32_t* of2, uint32_t* coef,
+                                                            int64_t MN, int32_t K) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= MN) return;
+    const int words = (K + 31) >> 5;
+    bool alive = true;                                         // sequential: no OF above; chunked: no OF2 above
+    uint32_t x2 = 0u;
+    for (int w = words - 1; w >= 0; --w) {
+        const int valid = K - 32 * w;
+        const uint32_t vmask = valid >= 32 ? 0xFFFFFFFFu : ((1u << valid) - 1u);
+        const uint32_t x = of1[(int64_t)w * MN + i];
+        uint32_t c;
+        if (STE == LBA_STE_IMMEDIATE_OF) {
+            c = ~x;
+        } else if (ORDER == LBA_ORDER_SEQ) {
+            c = alive ? above_last(x, 0xFFFFFFFFu) : 0u;
+            alive = alive && x == 0u;
+        } else {
+            // chunks 2w (bits 0..15) and 2w+1 (bits 16..31); their second-level bits sit in word w / 16 of of2
+            if ((w & 15) == 15 || w == words - 1) x2 = of2[(int64_t)(w >> 4) * MN + i];
+            const uint32_t b = (x2 >> (2 * (w & 15))) & 3u;
+            alive = alive && !(b & 2u);
+            const uint32_t hi = alive ? above_last(x >> 16, 0xFFFFu) : 0u;
+            alive = alive && !(b & 1u);
+            const uint32_t lo = alive ? above_last(x & 0xFFFFu, 0xFFFFu) : 0u;
+            c = (hi << 16) | lo;
+        }
+        coef[(int64_t)w * MN + i] = c & vmask;
+    }
+}
+
 template <bool S_CONTIG>
 static hipError_t launch_grad(int ste, const float* G, const uint8_t* V, const uint32_t* plane, const int32_t* last_of,
                               float* out, const GradDims& gp, dim3 grid, hipStream_t st) {
@@ -348,6 +396,8 @@ static hipError_t launch_grad(int ste, const float* G, const uint8_t* V, const u
 static int run_grad_side(bool dx, const float* G, const uint8_t* V, const uint32_t* plane, const int32_t* last_of,
                          float* out, int64_t M, int64_t N, int64_t K, int ste, hipStream_t st) {
     GradDims gp;
+    gp.plane_xor = (ste == LBA_STE_COEF_PLANE) ? 0u : 0xFFFFFFFFu;
+    if (ste == LBA_STE_COEF_PLANE) ste = LBA_STE_IMMEDIATE_OF;   // same kernel, bits taken as they are
     gp.K = (int32_t)K;
     gp.slab = M * N;
     if (dx) { gp.R = (int32_t)M; gp.S = (int32_t)N; gp.stride_r = (int32_t)N; gp.stride_s = 1; }
@@ -384,11 +434,34 @@ int lba_last_overflow(const uint32_t* of_mask, int32_t* last_of, int64_t M, int6
     return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
 }
 
+int lba_ste_plane(const uint32_t* of_mask, const uint32_t* of_mask2, uint32_t* coef, int64_t M, int64_t N, int64_t K,
+                  int32_t ste, int32_t order, void* hip_stream) {
+    int rc = lba::validate_shapes(M, N, K);
+    if (rc != LBA_OK) return rc;
+    if (ste != LBA_STE_IMMEDIATE_OF && ste != LBA_STE_RECURSIVE_OF) return LBA_ERR_UNSUPPORTED;
+    if (order != LBA_ORDER_SEQ && order != LBA_ORDER_CHUNK16) return LBA_ERR_UNSUPPORTED;
+    if (M == 0 || N == 0 || K == 0) return LBA_OK;
+    if (!of_mask || !coef) return LBA_ERR_NULL;
+    const bool two = ste == LBA_STE_RECURSIVE_OF && order == LBA_ORDER_CHUNK16;
+    if (two && !of_mask2) return LBA_ERR_NULL;
+    const int64_t mn = M * N;
+    const dim3 grid((unsigned)((mn + 255) / 256)), block(256);
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (ste == LBA_STE_IMMEDIATE_OF)
+        hipLaunchKernelGGL((lba::lba_ste_plane_kernel<LBA_STE_IMMEDIATE_OF, LBA_ORDER_SEQ>), grid, block, 0, st, of_mask, of_mask2, coef, mn, (int32_t)K);
+    else if (two)
+        hipLaunchKernelGGL((lba::lba_ste_plane_kernel<LBA_STE_RECURSIVE_OF, LBA_ORDER_CHUNK16>), grid, block, 0, st, of_mask, of_mask2, coef, mn, (int32_t)K);
+    else
+        hipLaunchKernelGGL((lba::lba_ste_plane_kernel<LBA_STE_RECURSIVE_OF, LBA_ORDER_SEQ>), grid, block, 0, st, of_mask, of_mask2, coef, mn, (int32_t)K);
+    return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
+}
+
 int lba_grad(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
              float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* hip_stream) {
     int rc = lba::validate_shapes(M, N, K);
     if (rc != LBA_OK) return rc;
-    if (ste != LBA_STE_IDENTITY && ste != LBA_STE_IMMEDIATE_OF && ste != LBA_STE_RECURSIVE_OF) return LBA_ERR_UNSUPPORTED;
+    if (ste != LBA_STE_IDENTITY && ste != LBA_STE_IMMEDIATE_OF && ste != LBA_STE_RECURSIVE_OF &&
+        ste != LBA_STE_COEF_PLANE) return LBA_ERR_UNSUPPORTED;
     if ((K + 63) / 64 > 65535) return LBA_ERR_SHAPE;           // k blocks are grid y
     if (M * N > ((int64_t)1 << 30)) return LBA_ERR_SHAPE;      // element offsets of G and of a word slab are 32-bit
     if (!dX && !dW) return LBA_ERR_NULL;
@@ -404,7 +477,7 @@ int lba_grad(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t*
         return LBA_OK;
     }
     if (!G) return LBA_ERR_NULL;
-    if (ste == LBA_STE_IMMEDIATE_OF && !of_mask) return LBA_ERR_NULL;
+    if ((ste == LBA_STE_IMMEDIATE_OF || ste == LBA_STE_COEF_PLANE) && !of_mask) return LBA_ERR_NULL;
     if (ste == LBA_STE_RECURSIVE_OF && !last_of) return LBA_ERR_NULL;
     if (dX) {
         if (!B) return LBA_ERR_NULL;

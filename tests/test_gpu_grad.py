@@ -134,3 +134,48 @@ def test_arguments_views_and_degenerate_sizes(ref, gref):
     torch.cuda.synchronize()
     assert (dXz == 0).all()
     assert lb.lba_grad(g, a, b, None, None, x, None, M, N, 0, 0) == lb.OK
+
+
+def pack_plane(c):
+    """bool [M, N, K] -> uint32 [ceil(K/32), M, N], bit k % 32 of word k // 32."""
+    M, N, K = c.shape
+    W = (K + 31) // 32
+    pad = np.zeros((M, N, W * 32), dtype=np.uint64)
+    pad[:, :, :K] = c
+    words = (pad.reshape(M, N, W, 32) << np.arange(32, dtype=np.uint64)).sum(axis=3).astype(np.uint32)
+    return np.ascontiguousarray(np.moveaxis(words, 2, 0))
+
+
+def test_coefficient_planes_and_the_recursive_estimator_of_the_chunked_order(ref, gref):
+    rng = np.random.default_rng(97)
+    QP2, QA2 = (4, 7, 12, 0), (4, 7, 10, 0)
+    for (M, N, K) in [(64, 64, 64), (37, 68, 530), (70, 66, 100), (5, 3, 31), (16, 24, 1100)]:
+        A = codes(rng, (M, K), 5, 10); B = codes(rng, (N, K), 5, 10)
+        G = (rng.integers(-8, 9, (M, N)) / 4.0).astype(np.float32)
+        tA, tB, tG = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV), torch.from_numpy(G).to(DEV)
+        for order in (0, 1):
+            if order == 0:
+                _, of, _ = lb.gemm_bwd(tA, tB, QP2, QA2, want_c=False, want_uf=False)
+                of2 = None
+            else:
+                _, of, _, of2, _ = lb.gemm_bwd_chunked(tA, tB, QP2, QA2, want_c=False, want_uf=False)
+            for ste in (lb.STE_IMMEDIATE_OF, lb.STE_RECURSIVE_OF):
+                coef = lb.ste_plane(of, K, ste, order, of2)
+                torch.cuda.synchronize()
+                want_c = gref.coefficients(A, B, ref.QFmt(*QP2), ref.QFmt(*QA2), ste, order)
+                assert np.array_equal(coef.cpu().numpy().view(np.uint32), pack_plane(want_c)), (M, N, K, order, ste)
+                assert 0 < want_c.sum() < want_c.size
+                dX, dW = lb.grad(tG, tA, tB, lb.STE_COEF_PLANE, of_plane=coef)
+                torch.cuda.synchronize()
+                wX, wW = gref.grad(G, A, B, ref.QFmt(*QP2), ref.QFmt(*QA2), ste, order)
+                assert np.array_equal(dX.cpu().numpy(), wX.astype(np.float32)), (M, N, K, order, ste, "dX")
+                assert np.array_equal(dW.cpu().numpy(), wW.astype(np.float32)), (M, N, K, order, ste, "dW")
+            # in place
+            keep = lb.ste_plane(of, K, lb.STE_RECURSIVE_OF, order, of2).cpu()
+            assert lb.lba_ste_plane(of.data_ptr(), of2.data_ptr() if of2 is not None else None, of.data_ptr(),
+                                    M, N, K, lb.STE_RECURSIVE_OF, order) == lb.OK
+            torch.cuda.synchronize()
+            assert torch.equal(of.cpu(), keep)
+    assert lb.lba_ste_plane(of.data_ptr(), None, of.data_ptr(), M, N, K, lb.STE_RECURSIVE_OF, 1) == lb.ERR_NULL
+    assert lb.lba_ste_plane(of.data_ptr(), None, of.data_ptr(), M, N, K, lb.STE_IDENTITY, 0) == lb.ERR_UNSUPPORTED
+    assert lb.lba_ste_plane(None, None, of.data_ptr(), M, N, K, lb.STE_IMMEDIATE_OF, 0) == lb.ERR_NULL
