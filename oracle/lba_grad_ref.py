@@ -78,24 +78,27 @@ def coefficients(A, B, qprod, qacc, ste, order=lba_ref.ORDER_SEQ):
     raise ValueError("unknown estimator / order")
 
 
-def grad(G, A, B, qprod, qacc, ste, order=lba_ref.ORDER_SEQ):
-    """(dX [M, K], dW [N, K]) in float64 from g = G [M, N] and the uint8 operand codes."""
+def grad(G, A, B, qprod, qacc, ste, order=lba_ref.ORDER_SEQ, c=None):
+    """(dX [M, K], dW [N, K]) in float64 from g = G [M, N] and the uint8 operand codes.
+    c: the coefficient tensor if the caller already has it (coefficients(...) of the same arguments)."""
     G = np.asarray(G, dtype=np.float64)
     tab = decode_table()
     X = tab[np.asarray(A, dtype=np.uint8)]             # [M, K]
     Wv = tab[np.asarray(B, dtype=np.uint8)]            # [N, K]
-    c = coefficients(A, B, qprod, qacc, ste, order)
+    if c is None:
+        c = coefficients(A, B, qprod, qacc, ste, order)
     gc = G[:, :, None] * c                              # [M, N, K]
     dX = np.einsum("mnk,nk->mk", gc, Wv)
     dW = np.einsum("mnk,mk->nk", gc, X)
     return dX, dW
 
 
-def grad_abs(G, A, B, qprod, qacc, ste, order=lba_ref.ORDER_SEQ):
+def grad_abs(G, A, B, qprod, qacc, ste, order=lba_ref.ORDER_SEQ, c=None):
     """Sums of |terms| of dX and dW: the scale of a float32 accumulation's rounding error."""
     G = np.abs(np.asarray(G, dtype=np.float64))
     tab = np.abs(decode_table())
-    c = coefficients(A, B, qprod, qacc, ste, order)
+    if c is None:
+        c = coefficients(A, B, qprod, qacc, ste, order)
     gc = G[:, :, None] * c
     return (np.einsum("mnk,nk->mk", gc, tab[np.asarray(B, dtype=np.uint8)]),
             np.einsum("mnk,mk->nk", gc, tab[np.asarray(A, dtype=np.uint8)]))

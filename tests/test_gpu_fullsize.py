@@ -158,3 +158,62 @@ def test_event_planes_full_512_and_slab_of_4096(ref):
     assert np.array_equal(of.index_select(1, idx).cpu().numpy().view(np.uint32), wof)
     assert np.array_equal(uf.index_select(1, idx).cpu().numpy().view(np.uint32), wuf)
     assert torch.equal(lb.gemm(l["A"], l["B"], qp, qa).view(torch.int32), C.view(torch.int32))
+
+
+def _grad_check(got, want, scale, terms, what):
+    tol = 2 * (terms + 1) * 2.0 ** -24 * scale + 1e-30
+    err = np.abs(got - want)
+    assert (err <= tol).all(), "%s: worst error / tolerance %.3g" % (what, float((err / tol).max()))
+    # and far from a trivially passing bound: a dropped term would show
+    assert float((err / tol).max()) < 0.5
+
+
+def test_gradient_products_at_benchmark_sizes(ref):
+    """lba_grad at the sizes bench.py --grad times, on sampled outputs: rows of dX (each needs all n of its
+    rows) and columns n of dW (each needs all m of its columns), for the three estimators on the BERT-base
+    attention-output linear, and rows of dX on the ResNet-18 conv configuration."""
+    from oracle import lba_grad_ref as gref
+
+    def sampled(layer, G, dX, dW, ste, qp, qa, what):
+        M, N, K = layer["M"], layer["N"], layer["K"]
+        fp, fa = ref.QFmt(*qp), ref.QFmt(*qa)
+        rows = sample_rows(M, n_random=12)
+        idx = torch.from_numpy(rows).to(DEV)
+        A = layer["A"].index_select(0, idx).cpu().numpy(); Gs = G.index_select(0, idx).cpu().numpy()
+        B = layer["B"].cpu().numpy()
+        c = gref.coefficients(A, B, fp, fa, ste)
+        wX, _ = gref.grad(Gs, A, B, fp, fa, ste, c=c)
+        aX, _ = gref.grad_abs(Gs, A, B, fp, fa, ste, c=c)
+        _grad_check(dX.index_select(0, idx).cpu().numpy(), wX, aX, N, what + " dX rows")
+        if dW is not None:
+            cols = sample_rows(N, n_random=4)[:12]
+            jdx = torch.from_numpy(cols).to(DEV)
+            A = layer["A"].cpu().numpy(); Bs = layer["B"].index_select(0, jdx).cpu().numpy()
+            Gs = G.index_select(1, jdx).cpu().numpy()
+            c = gref.coefficients(A, Bs, fp, fa, ste)
+            _, wW = gref.grad(Gs, A, Bs, fp, fa, ste, c=c)
+            _, aW = gref.grad_abs(Gs, A, Bs, fp, fa, ste, c=c)
+            _grad_check(dW.index_select(0, jdx).cpu().numpy(), wW, aW, M, what + " dW columns")
+        return int((~c).sum())
+
+    layer = [l for l in inputs.make_workload("bert", DEV) if l["name"] == "attn_out"][0]
+    # b = 16 puts R_OF near 1, where these sums (standard deviation about 0.55) overflow now and then
+    qp, qa, _ = inputs.folded_formats(layer["ta"], layer["tb"], PROD, (4, 7, 16), 0)
+    G = torch.from_numpy(np.random.default_rng(5).standard_normal((layer["M"], layer["N"])).astype(np.float32)).to(DEV)
+    _, of, _ = lb.gemm_bwd(layer["A"], layer["B"], qp, qa, want_c=False, want_uf=False)
+    last = lb.last_overflow(of, layer["K"])
+    blocked = 0
+    for ste in (lb.STE_IDENTITY, lb.STE_IMMEDIATE_OF, lb.STE_RECURSIVE_OF):
+        dX, dW = lb.grad(G, layer["A"], layer["B"], ste, of_plane=of if ste == lb.STE_IMMEDIATE_OF else None,
+                         last_of=last if ste == lb.STE_RECURSIVE_OF else None)
+        torch.cuda.synchronize()
+        blocked += sampled(layer, G, dX, dW, ste, qp, qa, "attn_out ste=%d" % ste)
+    assert blocked > 0
+    # ResNet-18 conv configuration (M = 100352): rows of dX, immediate estimator
+    layer = inputs.make_workload("conv", DEV)[0]
+    qp, qa, _ = inputs.folded_formats(layer["ta"], layer["tb"], PROD, ACC, 0)
+    G = torch.from_numpy(np.random.default_rng(6).standard_normal((layer["M"], layer["N"])).astype(np.float32)).to(DEV)
+    _, of, _ = lb.gemm_bwd(layer["A"], layer["B"], qp, qa, want_c=False, want_uf=False)
+    dX, _ = lb.grad(G, layer["A"], layer["B"], lb.STE_IMMEDIATE_OF, of_plane=of, want_dw=False)
+    torch.cuda.synchronize()
+    sampled(layer, G, dX, None, lb.STE_IMMEDIATE_OF, qp, qa, "conv")
