@@ -30,6 +30,10 @@
 // Inputs are OCP FP8 E4M3 codes (1 sign, 4 exponent, 3 mantissa bits, exponent bias 7, no inf):
 //   e == 0: (-1)^s * m * 2^-9 ;  e > 0: (-1)^s * (8+m) * 2^(e-10).  The two NaN codes (0x7f, 0xff)
 //   are read as the bit pattern's normal number (+-480) so that behaviour is defined.
+// The *_in entry points take any 8-bit code format "1 sign, E exponent, M = 7 - E mantissa bits,
+// integer exponent bias" per operand (the paper's weights and activations are M4E3 with a per-tensor
+// "flex" bias, Sec. 3.1): e == 0: (-1)^s * m * 2^(1-bias-M) ; e > 0: (-1)^s * (2^M + m) * 2^(e-bias-M);
+// every code is finite.  E4M3 above is (E, M, bias) = (4, 3, 7).
 //
 // Exactness: every quantity is an integer multiple of 2^L for one call-wide L, held as an exact
 // unsigned integer magnitude plus a sign.  The integer type is chosen from the bit span the two
@@ -78,6 +82,23 @@ inline Dec decode_e4m3(uint8_t c) {
     else        { d.sig = 8 + m; d.lsb = e - 10; }
     return d;
 }
+
+// Operand code format of the *_in entry points: 1 sign bit, E exponent bits, M = 7 - E mantissa bits.
+struct InFmt { int32_t E, M, bias; };
+const InFmt kE4M3 = {4, 3, 7};
+bool infmt_ok(const InFmt& f) {
+    return f.E >= 2 && f.E <= 5 && f.M == 7 - f.E && f.bias >= -32 && f.bias <= 32;
+}
+inline Dec decode_in(uint8_t c, const InFmt& f) {
+    Dec d;
+    d.neg = (c >> 7) != 0;
+    int e = (c >> f.M) & ((1 << f.E) - 1), m = c & ((1 << f.M) - 1);
+    if (e == 0) { d.sig = m; d.lsb = 1 - f.bias - f.M; }
+    else        { d.sig = (1 << f.M) + m; d.lsb = e - f.bias - f.M; }
+    return d;
+}
+inline int in_min_lsb(const InFmt& f) { return 1 - f.bias - f.M; }                 // unit of the subnormals
+inline int in_top_exp(const InFmt& f) { return (1 << f.E) - 1 - f.bias; }          // largest value < 2^(top+1)
 
 template <class T> inline int msb_index(T x) {        // index of the highest set bit, x != 0
     int i = -1;
@@ -139,9 +160,13 @@ template <class T> inline float to_float(SVal<T> v, int L) {
 template <class T> struct Chain {
     Quant<T> qp, qa;
     int L;
+    Dec ta[256], tb[256];                              // decoded operand codes
+    void set_inputs(const InFmt& fa, const InFmt& fb) {
+        for (int c = 0; c < 256; ++c) { ta[c] = decode_in((uint8_t)c, fa); tb[c] = decode_in((uint8_t)c, fb); }
+    }
     // one FMAq step: S <- Q_acc(Q_prod(a*b) + S); returns the event bits of this step
     inline int step(SVal<T>& S, uint8_t ca, uint8_t cb) const {
-        Dec a = decode_e4m3(ca), b = decode_e4m3(cb);
+        Dec a = ta[ca], b = tb[cb];
         int ev_p = 0, ev_a = 0, ev = 0;
         SVal<T> p;
         p.mag = (T)(uint32_t)(a.sig * b.sig) << (a.lsb + b.lsb - L);
@@ -207,11 +232,12 @@ void gemm_rows(const Chain<T>& ch, const uint8_t* A, const uint8_t* B, float* C,
 }
 
 // Smallest unit exponent and bit span needed by a pair of formats.
-void span_of(const Fmt& qp, const Fmt& qa, int* L, int* bits) {
-    int l = -18;                                       // unit of the smallest E4M3 product, (2^-9)^2
+void span_of(const Fmt& qp, const Fmt& qa, int* L, int* bits, const InFmt& ia = kE4M3, const InFmt& ib = kE4M3) {
+    int l = in_min_lsb(ia) + in_min_lsb(ib);           // unit of the smallest product (E4M3: (2^-9)^2)
     l = std::min(l, -qp.b - qp.M);
     l = std::min(l, -qa.b - qa.M);
-    int top = std::max(std::max(top_exp(qp), top_exp(qa)), 17);   // 480*480 < 2^18
+    int ptop = in_top_exp(ia) + in_top_exp(ib) + 1;    // every product is below 2^(ptop+1) (E4M3: 480*480 < 2^18)
+    int top = std::max(std::max(top_exp(qp), top_exp(qa)), ptop);
     *L = l;
     *bits = (top + 1) + 1 - l + 1;                     // a sum of two such values, plus one spare
 }
@@ -220,11 +246,12 @@ template <class T>
 int run_gemm(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
              uint32_t* of2_mask, uint32_t* uf2_mask,
              int64_t M, int64_t N, int64_t K, const Fmt& qp, const Fmt& qa, int order, int L,
-             int nthreads) {
+             int nthreads, const InFmt& ia, const InFmt& ib) {
     Chain<T> ch;
     ch.L = L;
     ch.qp.init(qp, L);
     ch.qa.init(qa, L);
+    ch.set_inputs(ia, ib);
     int64_t W = (K + 31) / 32;
     if (of_mask) std::memset(of_mask, 0, sizeof(uint32_t) * (size_t)(W * M * N));
     if (uf_mask) std::memset(uf_mask, 0, sizeof(uint32_t) * (size_t)(W * M * N));
@@ -252,16 +279,18 @@ int run_gemm(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, ui
 
 int gemm_entry(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
                uint32_t* of2_mask, uint32_t* uf2_mask,
-               int64_t M, int64_t N, int64_t K, Fmt qp, Fmt qa, int order, int nthreads) {
+               int64_t M, int64_t N, int64_t K, Fmt qp, Fmt qa, int order, int nthreads,
+               InFmt ia = kE4M3, InFmt ib = kE4M3) {
     if (M < 0 || N < 0 || K < 0) return REF_ERR_SHAPE;
-    if (!fmt_ok(qp) || !fmt_ok(qa)) return REF_ERR_FORMAT;
+    if (!fmt_ok(qp) || !fmt_ok(qa) || !infmt_ok(ia) || !infmt_ok(ib)) return REF_ERR_FORMAT;
     if (order != ORDER_SEQ && order != ORDER_CHUNK16) return REF_ERR_UNSUPPORTED;
     if (M * N > 0 && ((K > 0 && (!A || !B)))) return REF_ERR_NULL;
     int L, bits;
-    span_of(qp, qa, &L, &bits);
+    span_of(qp, qa, &L, &bits, ia, ib);
+    if (bits > 318) return REF_ERR_FORMAT;
     if (bits <= 126)
-        return run_gemm<u128>(A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, qp, qa, order, L, nthreads);
-    return run_gemm<u320>(A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, qp, qa, order, L, nthreads);
+        return run_gemm<u128>(A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, qp, qa, order, L, nthreads, ia, ib);
+    return run_gemm<u320>(A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, qp, qa, order, L, nthreads, ia, ib);
 }
 
 }  // namespace
@@ -287,6 +316,26 @@ int lba_ref_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_
                      int64_t M, int64_t N, int64_t K,
                      lba_ref_qfmt qprod, lba_ref_qfmt qacc, int32_t order, int32_t nthreads) {
     return gemm_entry(A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, cvt(qprod), cvt(qacc), order, nthreads);
+}
+
+typedef struct { int32_t exp_bits, man_bits, bias; } lba_ref_infmt;
+static InFmt cvt_in(lba_ref_infmt f) { InFmt r = {f.exp_bits, f.man_bits, f.bias}; return r; }
+
+// lba_ref_gemm / lba_ref_gemm_bwd for operands in any 8-bit sign-exponent-mantissa code format.
+int lba_ref_gemm_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
+                    int64_t M, int64_t N, int64_t K, lba_ref_infmt fmt_a, lba_ref_infmt fmt_b,
+                    lba_ref_qfmt qprod, lba_ref_qfmt qacc, int32_t order, int32_t nthreads) {
+    return gemm_entry(A, B, C, of_mask, uf_mask, nullptr, nullptr, M, N, K, cvt(qprod), cvt(qacc), order, nthreads,
+                      cvt_in(fmt_a), cvt_in(fmt_b));
+}
+
+// Value of a code of such a format as a double (exact); NaN for an invalid format.
+double lba_ref_decode_in(uint8_t code, lba_ref_infmt f) {
+    InFmt g = cvt_in(f);
+    if (!infmt_ok(g)) return std::nan("");
+    Dec d = decode_in(code, g);
+    double v = std::ldexp((double)d.sig, d.lsb);
+    return d.neg ? -v : v;
 }
 
 // Value of an E4M3 code as a double (exact).
@@ -341,7 +390,7 @@ int lba_ref_fmaq(uint8_t a, uint8_t b, double s, lba_ref_qfmt qprod, lba_ref_qfm
     if (!fmt_ok(fp) || !fmt_ok(fa) || !out) return REF_ERR_FORMAT;
     int L, bits;
     span_of(fp, fa, &L, &bits);
-    Chain<u320> ch; ch.L = L; ch.qp.init(fp, L); ch.qa.init(fa, L);
+    Chain<u320> ch; ch.L = L; ch.qp.init(fp, L); ch.qa.init(fa, L); ch.set_inputs(kE4M3, kE4M3);
     SVal<u320> S = {false, 0};
     if (s != 0.0) {
         int e2; double fr = std::frexp(std::fabs(s), &e2);

@@ -31,6 +31,15 @@ class QFmt(ctypes.Structure):
                                                  ", no underflow" if self.round & NO_UNDERFLOW else "")
 
 
+class InFmt(ctypes.Structure):
+    """8-bit operand code format: 1 sign, E exponent, M = 7 - E mantissa bits, integer exponent bias
+    (the paper's weights / activations: M4E3 with a per-tensor "flex" bias, Sec. 3.1)."""
+    _fields_ = [("exp_bits", ctypes.c_int32), ("man_bits", ctypes.c_int32), ("bias", ctypes.c_int32)]
+
+    def __repr__(self):
+        return "InFmt(E=%d, M=%d, bias=%d)" % (self.exp_bits, self.man_bits, self.bias)
+
+
 def _compiler():
     for c in ("/opt/rocm/lib/llvm/bin/clang++", "/opt/rocm/llvm/bin/clang++", "clang++"):
         if os.path.sep not in c or os.path.exists(c):
@@ -64,6 +73,12 @@ def lib():
                                        ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                        QFmt, QFmt, ctypes.c_int32, ctypes.c_int32]
+        L.lba_ref_gemm_in.restype = ctypes.c_int
+        L.lba_ref_gemm_in.argtypes = [u8p, u8p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+                                      ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, InFmt, InFmt,
+                                      QFmt, QFmt, ctypes.c_int32, ctypes.c_int32]
+        L.lba_ref_decode_in.restype = ctypes.c_double
+        L.lba_ref_decode_in.argtypes = [ctypes.c_uint8, InFmt]
         L.lba_ref_decode.restype = ctypes.c_double
         L.lba_ref_decode.argtypes = [ctypes.c_uint8]
         L.lba_ref_quantize.restype = ctypes.c_int
@@ -126,6 +141,31 @@ def gemm(A, B, qprod, qacc, order=ORDER_SEQ, nthreads=None):
     if rc != 0:
         raise ValueError("lba_ref_gemm error %d" % rc)
     return C
+
+
+def decode_in(code, fmt):
+    return lib().lba_ref_decode_in(int(code) & 0xFF, fmt)
+
+
+def gemm_in(A, B, fmt_a, fmt_b, qprod, qacc, order=ORDER_SEQ, nthreads=None, planes=False):
+    """gemm (or, with planes, gemm_bwd under the sequential order) for operands coded in fmt_a / fmt_b."""
+    A = _u8(A)
+    B = _u8(B)
+    M, K = A.shape
+    N, K2 = B.shape
+    assert K == K2
+    C = np.empty((M, N), dtype=np.float32)
+    of = uf = None
+    if planes:
+        W = (K + 31) // 32
+        of = np.empty((W, M, N), dtype=np.uint32)
+        uf = np.empty((W, M, N), dtype=np.uint32)
+    rc = lib().lba_ref_gemm_in(A.ctypes.data, B.ctypes.data, C.ctypes.data,
+                               of.ctypes.data if planes else None, uf.ctypes.data if planes else None,
+                               M, N, K, fmt_a, fmt_b, qprod, qacc, order, _threads(nthreads))
+    if rc != 0:
+        raise ValueError("lba_ref_gemm_in error %d" % rc)
+    return (C, of, uf) if planes else C
 
 
 def mask_words(M, N, K):

@@ -17,6 +17,16 @@ def e4m3_value(code):
     return s * (1 + F(m, 8)) * F(2) ** (e - 7)
 
 
+def code_value(code, E, M, bias):
+    """8-bit code, 1 sign / E exponent / M mantissa bits: subnormals at e = 0, every code finite."""
+    s = -1 if code & 0x80 else 1
+    e = (code >> M) & ((1 << E) - 1)
+    m = code & ((1 << M) - 1)
+    if e == 0:
+        return s * F(m, 2 ** M) * F(2) ** (1 - bias)
+    return s * (1 + F(m, 2 ** M)) * F(2) ** (e - bias)
+
+
 def floor_log2(x):
     """floor(log2 x) for a positive Fraction."""
     e = x.numerator.bit_length() - x.denominator.bit_length()
@@ -57,8 +67,10 @@ def quant(x, E, M, b, rnd):
     return sgn * F(2) ** e * (1 + F(m, 2 ** M)), ""
 
 
-def fmaq(a_code, b_code, s, qp, qa):
-    xw = e4m3_value(a_code) * e4m3_value(b_code)
+def fmaq(a_code, b_code, s, qp, qa, in_a=None, in_b=None):
+    va = e4m3_value(a_code) if in_a is None else code_value(a_code, *in_a)
+    vb = e4m3_value(b_code) if in_b is None else code_value(b_code, *in_b)
+    xw = va * vb
     p, _ = quant(xw, *qp)
     t = p + s
     z, ev = quant(t, *qa)
@@ -67,11 +79,11 @@ def fmaq(a_code, b_code, s, qp, qa):
     return z, of, uf
 
 
-def chain(a_codes, b_codes, qp, qa):
+def chain(a_codes, b_codes, qp, qa, in_a=None, in_b=None):
     s = F(0)
     evs = []
     for a, b in zip(a_codes, b_codes):
-        s, of, uf = fmaq(a, b, s, qp, qa)
+        s, of, uf = fmaq(a, b, s, qp, qa, in_a, in_b)
         evs.append((of, uf))
     return s, evs
 

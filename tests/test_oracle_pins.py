@@ -452,6 +452,53 @@ def test_chunked_order_event_planes(ref):
         assert int(uf[0, 0, 0]) == 0 and int(of[0, 0, 0]) == 0
 
 
+def test_input_code_formats(ref):
+    """Operands in other 8-bit formats (the paper's M4E3 with a per-tensor bias, Sec. 3.1)."""
+    import torch
+    # decode: library casts where a standard format exists, the closed form everywhere
+    for c in range(256):
+        if (c & 0x7F) != 0x7F:
+            t = torch.tensor([c], dtype=torch.uint8).view(torch.float8_e4m3fn).float().item()
+            assert ref.decode_in(c, ref.InFmt(4, 3, 7)) == t == ref.decode(c)
+        if ((c >> 2) & 31) != 31:                                    # binary8 E5M2: e = 31 is inf / NaN there
+            t = torch.tensor([c], dtype=torch.uint8).view(torch.float8_e5m2).float().item()
+            assert ref.decode_in(c, ref.InFmt(5, 2, 15)) == t
+        for (E, M, b) in ((3, 4, 3), (3, 4, -2), (2, 5, 1), (5, 2, 20), (4, 3, 0)):
+            assert Fraction(ref.decode_in(c, ref.InFmt(E, M, b))) == FM.code_value(c, E, M, b)
+    assert ref.decode_in(0x7F, ref.InFmt(3, 4, 3)) == 31.0 and ref.decode_in(0x01, ref.InFmt(3, 4, 3)) == 2.0 ** -6
+    # a 10-bit product that Q_prod (M = 7) must round: (1 + 13/16)(1 + 11/16) = 783/256 = 1100001111b * 2^-8
+    A = np.array([[0x3D]], dtype=np.uint8); B = np.array([[0x3B]], dtype=np.uint8)   # e = 3 -> 2^0 with bias 3
+    f = ref.InFmt(3, 4, 3)
+    wide = ref.QFmt(6, 12, 20, 0)
+    assert ref.gemm_in(A, B, f, f, ref.QFmt(5, 7, 15, 0), wide)[0, 0] == 195 / 64      # floor
+    assert ref.gemm_in(A, B, f, f, ref.QFmt(5, 7, 15, 1), wide)[0, 0] == 196 / 64      # nearest
+    assert ref.gemm_in(A, B, f, f, ref.QFmt(5, 9, 15, 0), wide)[0, 0] == 783 / 256     # wide enough: exact
+    # brute force against the Fraction model, events included, product rounding active
+    rng = np.random.default_rng(21)
+    for (ia, ib), (fp, fa), rnd, K in [(((3, 4, 3), (3, 4, 5)), ((5, 7, 15), (4, 7, 7)), 0, 30),
+                                       (((3, 4, 2), (4, 3, 7)), ((5, 7, 15), (4, 7, 7)), 1, 30),
+                                       (((2, 5, 0), (5, 2, 12)), ((5, 5, 12), (5, 9, 14)), 1, 24),
+                                       (((3, 4, 4), (3, 4, 4)), ((3, 4, 6), (3, 4, 6)), 0, 20)]:
+        A = rng.integers(0, 256, (3, K)).astype(np.uint8); B = rng.integers(0, 256, (2, K)).astype(np.uint8)
+        C, of, uf = ref.gemm_in(A, B, ref.InFmt(*ia), ref.InFmt(*ib), ref.QFmt(*fp, rnd), ref.QFmt(*fa, rnd), planes=True)
+        for i in range(3):
+            for j in range(2):
+                want, evs = FM.chain([int(c) for c in A[i]], [int(c) for c in B[j]], fp + (rnd,), fa + (rnd,), ia, ib)
+                assert Fraction(float(C[i, j])) == want, (ia, ib, fp, fa, rnd, i, j)
+                for k in range(K):
+                    got = (bool((int(of[0, i, j]) >> k) & 1), bool((int(uf[0, i, j]) >> k) & 1))
+                    assert got == evs[k], (ia, ib, k)
+    # the exponent biases are power-of-two scales: moving them moves the quantizers' biases and the result
+    A = rng.integers(0, 256, (6, 50)).astype(np.uint8); B = rng.integers(0, 256, (5, 50)).astype(np.uint8)
+    base = ref.gemm_in(A, B, ref.InFmt(3, 4, 3), ref.InFmt(3, 4, 3), ref.QFmt(5, 7, 15, 0), ref.QFmt(4, 7, 7, 0))
+    moved = ref.gemm_in(A, B, ref.InFmt(3, 4, 5), ref.InFmt(3, 4, 0), ref.QFmt(5, 7, 14, 0), ref.QFmt(4, 7, 6, 0))
+    assert np.array_equal(moved, base * 2.0) and np.count_nonzero(base) > 20
+    with pytest.raises(ValueError):
+        ref.gemm_in(A, B, ref.InFmt(3, 3, 3), ref.InFmt(3, 4, 3), ref.QFmt(5, 7, 15, 0), ref.QFmt(4, 7, 7, 0))
+    with pytest.raises(ValueError):
+        ref.gemm_in(A, B, ref.InFmt(3, 4, 40), ref.InFmt(3, 4, 3), ref.QFmt(5, 7, 15, 0), ref.QFmt(4, 7, 7, 0))
+
+
 def test_oracle_rejects_bad_arguments(ref):
     A = np.zeros((2, 4), dtype=np.uint8)
     good = ref.QFmt(4, 7, 7, 0)
