@@ -78,6 +78,32 @@ int lba_gemm(const uint8_t* A, const uint8_t* B, float* C,
              int64_t M, int64_t N, int64_t K,
              lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream);
 
+/* Operand code format for the *_in calls: 8-bit codes with 1 sign bit, exp_bits exponent bits and
+ * man_bits = 7 - exp_bits mantissa bits; e == 0: (-1)^s * m * 2^(1 - bias - man_bits), e > 0:
+ * (-1)^s * (1 + m / 2^man_bits) * 2^(e - bias); every code is a finite number.  bias is an integer per
+ * tensor: the paper's weights and activations are M4E3 (exp_bits 3, man_bits 4) with the largest bias
+ * that avoids overflow of the tensor ("flex-bias", Sec. 3.1).  {4, 3, 7} is the E4M3 of lba_gemm.
+ * Limits (else LBA_ERR_FORMAT): 2 <= exp_bits <= 5, man_bits == 7 - exp_bits, -32 <= bias <= 32. */
+typedef struct {
+    int32_t exp_bits;
+    int32_t man_bits;
+    int32_t bias;
+} lba_infmt;
+
+/* lba_gemm for operands coded in fmt_a (A) and fmt_b (B).  A product of two such values can have up to
+ * man_a + man_b + 2 significant bits, so Q_prod's mantissa rounding takes part (with E4M3 operands and
+ * the usual 7-bit Q_prod mantissa it never does).  The two biases act as one power-of-two scale
+ * 2^-(bias_a + bias_b) and are folded into the quantizers' biases (Q_{M,E,b}(2^-T y) = 2^-T Q_{M,E,b-T}(y));
+ * the folded biases must stay inside lba_qfmt's limits (else LBA_ERR_FORMAT).  Everything else as lba_gemm. */
+int lba_gemm_in(const uint8_t* A, const uint8_t* B, float* C, int64_t M, int64_t N, int64_t K,
+                lba_infmt fmt_a, lba_infmt fmt_b, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
+                void* hip_stream);
+
+/* lba_gemm_bwd (sequential order) for operands coded in fmt_a / fmt_b. */
+int lba_gemm_bwd_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
+                    int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,
+                    lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream);
+
 /* `batch` independent forward products in one launch (batched matrix multiplication, e.g. the
  * attention products of a transformer, which the paper also runs through its LBA GEMM, App. C.2):
  * member z uses A + z*stride_a, B + z*stride_b (bytes) and C + z*stride_c (floats); a stride of 0

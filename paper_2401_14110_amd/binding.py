@@ -22,6 +22,14 @@ class lba_qfmt(ctypes.Structure):
                 ("bias", ctypes.c_int32), ("round", ctypes.c_int32)]
 
 
+class lba_infmt(ctypes.Structure):
+    _fields_ = [("exp_bits", ctypes.c_int32), ("man_bits", ctypes.c_int32), ("bias", ctypes.c_int32)]
+
+
+def infmt(f):
+    return f if isinstance(f, lba_infmt) else lba_infmt(*[int(v) for v in f])
+
+
 class lba_plan_info(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "kernel", "prod_mode", "round", "tile_m", "tile_n", "tile_k", "thread_m", "thread_n",
@@ -56,6 +64,10 @@ def lib():
         L.lba_gemm_bwd_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, vp]
         L.lba_mask_words_level2.restype = ctypes.c_size_t
         L.lba_mask_words_level2.argtypes = [i64, i64, i64]
+        L.lba_gemm_in.restype = ctypes.c_int
+        L.lba_gemm_in.argtypes = [vp, vp, vp, i64, i64, i64, lba_infmt, lba_infmt, lba_qfmt, lba_qfmt, i32, vp]
+        L.lba_gemm_bwd_in.restype = ctypes.c_int
+        L.lba_gemm_bwd_in.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, lba_infmt, lba_infmt, lba_qfmt, lba_qfmt, i32, vp]
         L.lba_last_overflow.restype = ctypes.c_int
         L.lba_last_overflow.argtypes = [vp, vp, i64, i64, i64, vp]
         L.lba_ste_plane.restype = ctypes.c_int
@@ -120,6 +132,17 @@ def lba_gemm_bwd_chunked(A, B, C, of_mask, uf_mask, of_mask2, uf_mask2, M, N, K,
     return lib().lba_gemm_bwd_chunked(A, B, C, of_mask, uf_mask, of_mask2, uf_mask2, M, N, K, qfmt(qprod),
                                       qfmt(qacc),
                                       ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_gemm_in(A, B, C, M, N, K, fmt_a, fmt_b, qprod, qacc, order=ORDER_SEQ, hip_stream=None):
+    return lib().lba_gemm_in(A, B, C, M, N, K, infmt(fmt_a), infmt(fmt_b), qfmt(qprod), qfmt(qacc), order,
+                             ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_gemm_bwd_in(A, B, C, of_mask, uf_mask, M, N, K, fmt_a, fmt_b, qprod, qacc, order=ORDER_SEQ, hip_stream=None):
+    return lib().lba_gemm_bwd_in(A, B, C, of_mask, uf_mask, M, N, K, infmt(fmt_a), infmt(fmt_b), qfmt(qprod),
+                                 qfmt(qacc), order,
+                                 ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
 
 
 def lba_last_overflow(of_mask, last_of, M, N, K, hip_stream=None):
@@ -258,3 +281,22 @@ def ste_plane(of_plane, K, ste, order=ORDER_SEQ, of_plane2=None, stream=None):
                                (of_plane2.data_ptr() or None) if of_plane2 is not None else None,
                                out.data_ptr() or None, M, N, K, ste, order, _stream(stream)))
     return out
+
+
+def gemm_in(A, B, fmt_a, fmt_b, qprod, qacc, order=ORDER_SEQ, planes=False, stream=None):
+    """lba_gemm_in (or, with planes, lba_gemm_bwd_in: returns (C, OF, UF)) on uint8 device tensors."""
+    A, B = _ops(A, B)
+    M, K = A.shape
+    N = B.shape[0]
+    C = torch.empty((M, N), dtype=torch.float32, device=A.device)
+    if not planes:
+        _check(lib().lba_gemm_in(A.data_ptr() or None, B.data_ptr() or None, C.data_ptr() or None, M, N, K,
+                                 infmt(fmt_a), infmt(fmt_b), qfmt(qprod), qfmt(qacc), order, _stream(stream)))
+        return C
+    W = (K + 31) // 32
+    of = torch.empty((W, M, N), dtype=torch.int32, device=A.device)
+    uf = torch.empty((W, M, N), dtype=torch.int32, device=A.device)
+    _check(lib().lba_gemm_bwd_in(A.data_ptr() or None, B.data_ptr() or None, C.data_ptr() or None,
+                                 of.data_ptr() or None, uf.data_ptr() or None, M, N, K,
+                                 infmt(fmt_a), infmt(fmt_b), qfmt(qprod), qfmt(qacc), order, _stream(stream)))
+    return C, of, uf

@@ -10,7 +10,8 @@
 namespace lba {
 
 enum { KERNEL_FAST = 0, KERNEL_GEN = 1 };
-enum { PM_IDENT = 0, PM_FLUSH = 1, PM_FLUSH_CLAMP = 2 };
+enum { PM_IDENT = 0, PM_FLUSH = 1, PM_FLUSH_CLAMP = 2,
+       PM_TRUNC = 3, PM_TRUNC_CLAMP = 4 };   // + the product's mantissa truncated to Q_prod's M bits
 
 // Uniform (scalar-register) parameters of a launch.  All thresholds are exact FP32 values.
 struct KParams {
@@ -36,7 +37,10 @@ struct KParams {
     uint32_t mask_a; uint32_t half_a; int32_t sh_a; float rof_a; float ruf_a;
     // product quantizer
     uint32_t mask_p; uint32_t half_p; int32_t sh_p; float rof_p; float ruf_p;
-    int32_t prod_round;      // GEN: product mantissa narrower than an E4M3 product (M_prod < 7)
+    // operand code formats as the kernels decode them (canonical bias 2^(E-1) - 1; the caller's bias
+    // is folded into the quantizers and out_exp): {4, 3} takes the hardware FP8 conversion
+    int32_t in_ea, in_ma, in_eb, in_mb;
+    int32_t prod_round;      // GEN: product mantissa narrower than a product of two operands
     int32_t prod_rne;        // GEN: its rounding
 };
 
@@ -52,13 +56,25 @@ struct Plan {
     KParams kp;
 };
 
+// What the planner needs to know about the operand formats (canonical biases).
+struct InSpec {
+    int ea, ma, eb, mb;      // exponent / mantissa bits of A's and B's codes
+    int sig_bits;            // most significant bits a product can have: (ma + 1) + (mb + 1)
+    int min_lsb;             // every product is a multiple of 2^min_lsb
+    int ptop;                // every |product| < 2^(ptop + 1)
+    double max_prod;         // largest |product|
+    int delta;               // (bias_a - canonical) + (bias_b - canonical): folded into the quantizers
+};
+int make_in_spec(const lba_infmt& fa, const lba_infmt& fb, InSpec* out);   // LBA_OK or LBA_ERR_FORMAT
+const InSpec& e4m3_spec();
+
 // Validation shared by every entry point; returns an lba status code.
 int validate_shapes(int64_t M, int64_t N, int64_t K);
 int validate_fmt(const lba_qfmt& q);
 
 // Builds the plan (pointers in kp are left null).  Returns an lba status code.
 int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qprod, const lba_qfmt& qacc,
-              int order, int events, Plan* out, int64_t batch = 1);
+              int order, int events, Plan* out, int64_t batch = 1, const InSpec* in = nullptr);
 
 // Gradient products: how many slices of the summation index s a launch of `blocks` workgroups (4 waves
 // of 16 rows each) is cut into so that the chip has enough waves, and the slice length (a multiple of 4).

@@ -41,10 +41,12 @@ __device__ __forceinline__ float med3(float x, float lo, float hi) { return __bu
 // ---------------------------------------------------------------------------------------------
 // operand decode table: E4M3 code -> value * 2^e as an exact FP32 (Sec. "inputs" of lba.h)
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ float decode_entry(int code, int e) {
-    const int ex = (code >> 3) & 15, m = code & 7;
-    const int sig = ex ? (8 + m) : m;
-    const int lsb = ex ? (ex - 10) : -9;
+// (E exponent bits, M mantissa bits, bias 2^(E-1) - 1; E = 4, M = 3 is E4M3)
+__device__ __forceinline__ float decode_entry(int code, int e, int E, int M) {
+    const int ex = (code >> M) & ((1 << E) - 1), m = code & ((1 << M) - 1);
+    const int bias = (1 << (E - 1)) - 1;
+    const int sig = ex ? ((1 << M) + m) : m;
+    const int lsb = (ex ? ex : 1) - bias - M;
     const float v = __builtin_ldexpf((float)sig, lsb + e);
     return (code & 0x80) ? -v : v;
 }
@@ -74,7 +76,7 @@ __device__ __forceinline__ float rne_to_8_bits(float t) {
 // FP32 / bitwise VALU ops issue at twice the rate when all their operands are VGPRs.
 struct FastConst {
     float kc, rof, rofp;
-    uint32_t mask, half;
+    uint32_t mask, half, maskp;
     int sh;
 };
 
@@ -98,7 +100,14 @@ __device__ __forceinline__ void fast_group(float (&accf)[TM][NJ], const float (&
 #pragma unroll
             for (int j = 0; j < NJ; ++j) q[i][j] = a[i] * b[j];        // exact; flushed below Q_prod's R_UF
         __builtin_amdgcn_sched_barrier(0);
-        if (PM == PM_FLUSH_CLAMP) {
+        if (PM == PM_TRUNC || PM == PM_TRUNC_CLAMP) {                   // Q_prod's mantissa, by truncation
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) q[i][j] = __uint_as_float(__float_as_uint(q[i][j]) & c.maskp);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (PM == PM_FLUSH_CLAMP || PM == PM_TRUNC_CLAMP) {
 #pragma unroll
             for (int i = 0; i < NI; ++i)
 #pragma unroll
@@ -267,10 +276,30 @@ __device__ __forceinline__ void store_tile(float* __restrict__ dst /* [BK][ROWS]
 // Same, decoding with the hardware FP8 conversion (gfx950 decodes OCP E4M3) and one exact
 // multiply by the power-of-two scale.  The two NaN codes, which the conversion would turn into NaN,
 // are patched to +-480 * scale on a rarely taken path so that every code has a defined value.
+// Codes of another format (E exponent bits, not 4) are decoded arithmetically: integer significand
+// times a power of two, exact.
 template <int ROWS, int BK>
 __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][ROWS] */, float scale,
-                                               int tid, const uint4 (&regs)[Stage<ROWS, BK>::kPerLane]) {
+                                               int tid, const uint4 (&regs)[Stage<ROWS, BK>::kPerLane],
+                                               int E = 4, int M = 3, int scale_exp = 0) {
     typedef float v2f __attribute__((ext_vector_type(2)));
+    if (E != 4) {                                              // uniform
+#pragma unroll
+        for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
+            const int c = tid + i * 256;
+            if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
+                const int row = c & (ROWS - 1);
+                const int kq = c >> Stage<ROWS, BK>::kRowShift;
+                const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int code = (int)((w[j >> 2] >> (8 * (j & 3))) & 0xFFu);
+                    dst[(kq * 16 + j) * ROWS + row] = decode_entry(code, scale_exp, E, M);
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
         const int c = tid + i * 256;
@@ -420,10 +449,10 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
     if (RND == LBA_ROUND_FLOOR) set_round_zero();
 
     FastConst c;
-    c.kc = p.kc; c.rof = p.rof_a; c.rofp = p.rof_p; c.mask = p.mask_a; c.half = p.half_a; c.sh = p.sh_a;
+    c.kc = p.kc; c.rof = p.rof_a; c.rofp = p.rof_p; c.mask = p.mask_a; c.half = p.half_a; c.sh = p.sh_a; c.maskp = p.mask_p;
     float thresh = p.fast_thresh, thresh4 = p.fast_thresh4;
     int safe_tiles = 0;
-    asm volatile("" : "+v"(c.kc), "+v"(c.rof), "+v"(c.rofp), "+v"(c.mask), "+v"(c.half), "+v"(thresh), "+v"(thresh4));
+    asm volatile("" : "+v"(c.kc), "+v"(c.rof), "+v"(c.rofp), "+v"(c.mask), "+v"(c.half), "+v"(c.maskp), "+v"(thresh), "+v"(thresh4));
 
     float acc[TM][TN], top[TM][TN];                            // top: second-level sums (chunked order only)
 #pragma unroll
@@ -436,8 +465,8 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
 
     fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
     fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
-    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra);
-    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb);
+    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, p.in_ea, p.in_ma, p.exp_a);
+    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, p.in_eb, p.in_mb, p.exp_b);
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
@@ -473,8 +502,8 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
         }
         if (more) {
             float* Ad = smem + ((t + 1) & 1) * STAGE;
-            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra);
-            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb);
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, p.in_ea, p.in_ma, p.exp_a);
+            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, p.in_eb, p.in_mb, p.exp_b);
         }
         __syncthreads();
     }
@@ -584,7 +613,7 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
     uint32_t mask = p.mask_a;
     asm volatile("" : "+v"(kc), "+v"(rof), "+v"(rofp), "+v"(mask), "+v"(kc_up), "+v"(up));
     FastConst fc;
-    fc.kc = kc; fc.rof = rof; fc.rofp = rofp; fc.mask = mask; fc.half = 0u; fc.sh = p.sh_a;
+    fc.kc = kc; fc.rof = rof; fc.rofp = rofp; fc.mask = mask; fc.half = 0u; fc.sh = p.sh_a; fc.maskp = p.mask_p;
     float thresh = p.fast_thresh;
     asm volatile("" : "+v"(thresh));
 
@@ -603,8 +632,8 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
 
     fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
     fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
-    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra);
-    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb);
+    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, p.in_ea, p.in_ma, p.exp_a);
+    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, p.in_eb, p.in_mb, p.exp_b);
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
@@ -740,8 +769,8 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
         }
         if (more) {
             float* Ad = smem + ((t + 1) & 1) * STAGE;
-            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra);
-            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb);
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, p.in_ea, p.in_ma, p.exp_a);
+            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, p.in_eb, p.in_mb, p.exp_b);
         }
         __syncthreads();
     }
@@ -869,8 +898,8 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
     const uint8_t* pB = p.B + (int64_t)blockIdx.z * p.stride_b;
     float* pC = p.C ? p.C + (int64_t)blockIdx.z * p.stride_c : nullptr;
 
-    lut_a[tid] = decode_entry(tid, p.exp_a);
-    lut_b[tid] = decode_entry(tid, p.exp_b);
+    lut_a[tid] = decode_entry(tid, p.exp_a, p.in_ea, p.in_ma);
+    lut_b[tid] = decode_entry(tid, p.exp_b, p.in_eb, p.in_mb);
     set_flush_f32();
     if (RND == LBA_ROUND_FLOOR) set_round_zero();
 
@@ -953,7 +982,7 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float r = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
-                v[j] = (r == 0.0f) ? 0.0f : r;
+                v[j] = (r == 0.0f) ? 0.0f : __builtin_ldexpf(r, p.out_exp);     // out_exp: the operand biases' scale
             }
             float* dst = pC + (int64_t)m * p.N + n;
             if (p.c_vec && n + 3 < p.N) {
@@ -984,25 +1013,24 @@ static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
     const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
     const KParams& kp = pl.kp;
 #define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<TM, TN, LBA_FAST_BK, PM, RND, ORDER>), grid, block, 0, st, kp)
-    if (pl.round == LBA_ROUND_FLOOR) {
-        switch (pl.prod_mode) {
-            case PM_IDENT: LBA_LAUNCH(PM_IDENT, LBA_ROUND_FLOOR); break;
-            case PM_FLUSH: LBA_LAUNCH(PM_FLUSH, LBA_ROUND_FLOOR); break;
-            default:       LBA_LAUNCH(PM_FLUSH_CLAMP, LBA_ROUND_FLOOR); break;
-        }
-    } else if (pl.kp.sh_a == 16) {                           // M = 7: rounding by the bfloat16 conversion
-        switch (pl.prod_mode) {
-            case PM_IDENT: LBA_LAUNCH(PM_IDENT, RND_RNE_BF16); break;
-            case PM_FLUSH: LBA_LAUNCH(PM_FLUSH, RND_RNE_BF16); break;
-            default:       LBA_LAUNCH(PM_FLUSH_CLAMP, RND_RNE_BF16); break;
-        }
-    } else {
-        switch (pl.prod_mode) {
-            case PM_IDENT: LBA_LAUNCH(PM_IDENT, LBA_ROUND_RNE); break;
-            case PM_FLUSH: LBA_LAUNCH(PM_FLUSH, LBA_ROUND_RNE); break;
-            default:       LBA_LAUNCH(PM_FLUSH_CLAMP, LBA_ROUND_RNE); break;
-        }
+    // the truncating product modes (operand formats whose products exceed Q_prod's mantissa) exist for
+    // the 4 x 4 lane block only; the planner never asks for them with another
+#define LBA_LAUNCH_ROUNDING(RND)                                                        \
+    switch (pl.prod_mode) {                                                             \
+        case PM_IDENT:       LBA_LAUNCH(PM_IDENT, RND); break;                          \
+        case PM_FLUSH:       LBA_LAUNCH(PM_FLUSH, RND); break;                          \
+        case PM_FLUSH_CLAMP: LBA_LAUNCH(PM_FLUSH_CLAMP, RND); break;                    \
+        case PM_TRUNC:       if constexpr (TM == 4 && TN == 4) { LBA_LAUNCH(PM_TRUNC, RND); break; } else return hipErrorInvalidValue;        \
+        default:             if constexpr (TM == 4 && TN == 4) { LBA_LAUNCH(PM_TRUNC_CLAMP, RND); break; } else return hipErrorInvalidValue;  \
     }
+    if (pl.round == LBA_ROUND_FLOOR) {
+        LBA_LAUNCH_ROUNDING(LBA_ROUND_FLOOR)
+    } else if (pl.kp.sh_a == 16) {                           // M = 7: rounding by the bfloat16 conversion
+        LBA_LAUNCH_ROUNDING(RND_RNE_BF16)
+    } else {
+        LBA_LAUNCH_ROUNDING(LBA_ROUND_RNE)
+    }
+#undef LBA_LAUNCH_ROUNDING
 #undef LBA_LAUNCH
     return hipGetLastError();
 }
@@ -1057,11 +1085,12 @@ static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, 
                int64_t M, int64_t N, int64_t K, const lba_qfmt& qprod, const lba_qfmt& qacc,
                int order, int events, void* stream,
                int64_t batch = 1, int64_t stride_a = 0, int64_t stride_b = 0, int64_t stride_c = 0,
-               uint32_t* of_mask2 = nullptr, uint32_t* uf_mask2 = nullptr) {
+               uint32_t* of_mask2 = nullptr, uint32_t* uf_mask2 = nullptr, const InSpec* in = nullptr) {
     Plan pl;
     if (batch < 0 || batch > 65535 || stride_a < 0 || stride_b < 0 || stride_c < 0) return LBA_ERR_SHAPE;
-    int rc = make_plan(M, N, K, qprod, qacc, order, events, &pl, batch);
+    int rc = make_plan(M, N, K, qprod, qacc, order, events, &pl, batch, in);
     if (rc != LBA_OK) return rc;
+    if (in) pl.kp.out_exp -= in->delta;                        // the operand biases' power-of-two scale
     if (M == 0 || N == 0 || batch == 0) return LBA_OK;
     if (!events && !C) return LBA_ERR_NULL;
     if (events && !of_mask && !uf_mask && !of_mask2 && !uf_mask2) return LBA_ERR_NULL;
@@ -1121,6 +1150,33 @@ int lba_gemm_bwd_chunked(const uint8_t* A, const uint8_t* B, float* C,
                          int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc, void* hip_stream) {
     return lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, LBA_ORDER_CHUNK16, 1, hip_stream,
                     1, 0, 0, 0, of_mask2, uf_mask2);
+}
+
+// Operand biases are one power-of-two scale 2^-delta: C = 2^-delta * LBA(codes at canonical biases) with
+// both quantizer biases lowered by delta (Sec. 2.3: Q_{M,E,b}(2^-T y) = 2^-T Q_{M,E,b-T}(y)).
+static int run_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
+                  int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b, lba_qfmt qprod, lba_qfmt qacc,
+                  int32_t order, int events, void* hip_stream) {
+    lba::InSpec in;
+    int rc = lba::make_in_spec(fmt_a, fmt_b, &in);
+    if (rc != LBA_OK) return rc;
+    if ((rc = lba::validate_fmt(qprod)) != LBA_OK || (rc = lba::validate_fmt(qacc)) != LBA_OK) return rc;
+    qprod.bias -= in.delta;
+    qacc.bias -= in.delta;
+    return lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, order, events, hip_stream, 1, 0, 0, 0,
+                    nullptr, nullptr, &in);
+}
+
+int lba_gemm_in(const uint8_t* A, const uint8_t* B, float* C, int64_t M, int64_t N, int64_t K,
+                lba_infmt fmt_a, lba_infmt fmt_b, lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream) {
+    return run_in(A, B, C, nullptr, nullptr, M, N, K, fmt_a, fmt_b, qprod, qacc, order, 0, hip_stream);
+}
+
+int lba_gemm_bwd_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
+                    int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,
+                    lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream) {
+    if (order == LBA_ORDER_CHUNK16) return LBA_ERR_UNSUPPORTED;
+    return run_in(A, B, C, of_mask, uf_mask, M, N, K, fmt_a, fmt_b, qprod, qacc, order, 1, hip_stream);
 }
 
 int lba_gemm_batched(const uint8_t* A, const uint8_t* B, float* C, int64_t batch,

@@ -47,8 +47,32 @@ namespace lba {
 
 static const int64_t kMaxDim = 2147483647LL - 63;   // tile origins and padded k stay below 2^31
 static const int64_t kMaxN = 1LL << 21;
-static const int kMaxProdExp = 17;     // 480 * 480 = 230400 < 2^18
-static const double kMaxProd = 230400.0;
+
+static inline int canon_bias(int E) { return (1 << (E - 1)) - 1; }
+
+int make_in_spec(const lba_infmt& fa, const lba_infmt& fb, InSpec* out) {
+    const lba_infmt* f[2] = {&fa, &fb};
+    for (int i = 0; i < 2; ++i) {
+        if (f[i]->exp_bits < 2 || f[i]->exp_bits > 5 || f[i]->man_bits != 7 - f[i]->exp_bits) return LBA_ERR_FORMAT;
+        if (f[i]->bias < -32 || f[i]->bias > 32) return LBA_ERR_FORMAT;
+    }
+    InSpec s;
+    s.ea = fa.exp_bits; s.ma = fa.man_bits; s.eb = fb.exp_bits; s.mb = fb.man_bits;
+    s.sig_bits = s.ma + s.mb + 2;
+    const int ba = canon_bias(s.ea), bb = canon_bias(s.eb);
+    s.min_lsb = (1 - ba - s.ma) + (1 - bb - s.mb);                     // subnormal unit x subnormal unit
+    const int ta = (1 << s.ea) - 1 - ba, tb = (1 << s.eb) - 1 - bb;    // top exponents
+    s.ptop = ta + tb + 1;
+    s.max_prod = std::ldexp(2.0 - std::ldexp(1.0, -s.ma), ta) * std::ldexp(2.0 - std::ldexp(1.0, -s.mb), tb);
+    s.delta = (fa.bias - ba) + (fb.bias - bb);
+    *out = s;
+    return LBA_OK;
+}
+
+const InSpec& e4m3_spec() {                                  // 480 * 480 = 230400 < 2^18, multiples of 2^-18
+    static const InSpec s = {4, 3, 4, 3, 8, -18, 17, 230400.0, 0};
+    return s;
+}
 
 int validate_shapes(int64_t M, int64_t N, int64_t K) {
     if (M < 0 || N < 0 || K < 0) return LBA_ERR_SHAPE;
@@ -82,30 +106,35 @@ static void fill_quant(const lba_qfmt& q, int shift, uint32_t* mask, uint32_t* h
 }
 
 // Can Q_prod's underflow / overflow ever fire on a product of two E4M3 values?
-static bool prod_flush_possible(const lba_qfmt& qp) { return qp.bias < 18; }          // R_UF > 2^-18
-static bool prod_clamp_possible(const lba_qfmt& qp) {
-    return std::ldexp(2.0 - std::ldexp(1.0, -qp.man_bits), top_exp(qp)) <= kMaxProd;
+static bool prod_flush_possible(const lba_qfmt& qp, const InSpec& in) { return qp.bias < -in.min_lsb; }   // R_UF above the smallest product
+static bool prod_clamp_possible(const lba_qfmt& qp, const InSpec& in) {
+    return std::ldexp(2.0 - std::ldexp(1.0, -qp.man_bits), top_exp(qp)) <= in.max_prod;
 }
 
 // Nearest-even in the scaled kernel rounds twice (FP32's 24 bits, then M+1 bits).  That equals one
 // rounding unless the 24-bit result is inexact and lands on a midpoint of the (M+1)-bit grid.
-//  * M >= 7: a product (at most 8 significant bits, M_prod+1 when saturated) lies on the accumulator's
-//    grid, and an inexact sum stays clear of every midpoint (M <= 10).
-//  * M < 7: a product can itself be a midpoint, and a partial sum S too small for the 24-bit window
-//    would be lost before the tie is broken.  Such an S has its lowest bit at or above
-//    l = max(-18, -b - M) (every sum is a multiple of 2^-18; S >= 2^-b has M+1 bits), so the sum is
-//    inexact only from 2^(24+l) on; when that is above R_OF the result saturates whatever the rounding.
-static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp, bool flush, bool nouf_a) {
+// Let pb be the significant bits of a product after Q_prod (at most 8 for E4M3 operands).
+//  * The sum is inexact because of low bits of the product only when the product is far below the
+//    partial sum S (a grid point); it then stays within 2^(e-23+pb) of S and clear of every midpoint
+//    (at least 2^(e-M-2) away) provided pb + M <= 20.
+//  * It is inexact because of low bits of S only when S is far below the product.  If products lie
+//    on the accumulator's grid (pb <= M+1) the same argument applies with the roles swapped.  Else a
+//    product can itself be a midpoint and a tiny S must break the tie: such an S has its lowest bit at
+//    or above l = max(min_lsb, -b - M) (every sum is a multiple of 2^min_lsb; S >= 2^-b has M+1
+//    bits), so the sum is inexact only from 2^(24+l) on; when that is above R_OF the result saturates
+//    whatever the rounding.
+static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp, bool flush, bool nouf_a,
+                        const InSpec& in) {
     if (qa.man_bits > 10) return false;
-    if (qa.man_bits >= 7) {
-        if (clamp && qp.man_bits > qa.man_bits) return false;
-    } else {
-        if (clamp && qp.man_bits > 7) return false;        // keep every product within 8 bits
-        const int low = nouf_a ? -18 : std::max(-18, -qa.bias - qa.man_bits);
+    int pb = in.sig_bits < qp.man_bits + 1 ? in.sig_bits : qp.man_bits + 1;
+    if (clamp && qp.man_bits + 1 > pb) pb = qp.man_bits + 1;            // a saturated product has M_prod+1 bits
+    if (pb + qa.man_bits > 20) return false;
+    if (pb > qa.man_bits + 1) {
+        const int low = nouf_a ? in.min_lsb : std::max(in.min_lsb, -qa.bias - qa.man_bits);
         if (24 + low < top_exp(qa) + 1) return false;
     }
     if (nouf_a) return true;                               // no flush threshold to disturb
-    int bpe = flush ? qp.bias : 18;                        // nonzero |p| >= 2^-bpe
+    int bpe = flush ? qp.bias : -in.min_lsb;               // nonzero |p| >= 2^-bpe
     if (bpe - qa.bias >= 24) return false;                 // a product could hide below 2^-150
     return true;
 }
@@ -119,19 +148,21 @@ static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp, bool
 // with few outputs cannot keep two waves on every SIMD with 16 chains per lane: between 512 and 1024
 // workgroups 2 x 4 measured 3-6 % faster, and up to 64 workgroups (a latency-bound launch) 2 x 2 is
 // about twice as fast.  The choice never changes a result.
-static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int events, int* tm, int* tn, int* bk) {
+static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int events, int prod_mode, int* tm, int* tn, int* bk) {
     *tm = 4; *tn = 4;
     *bk = (kernel == KERNEL_GEN || events) ? 32 : LBA_FAST_BK;
     if (kernel == KERNEL_FAST) {
         const int64_t blocks = ((M + 63) / 64) * ((N + 63) / 64) * (batch > 0 ? batch : 1);
         if (events) return;                                    // the recompute kernel is 4 x 4 only
+        if (prod_mode == PM_TRUNC || prod_mode == PM_TRUNC_CLAMP) return;   // built for 4 x 4 only
         if (blocks <= 64) { *tm = 2; *tn = 2; }
         else if (blocks > 512 && blocks <= 1024) *tm = 2;
     }
 }
 
 int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_qfmt& qa_in,
-              int order, int events, Plan* out, int64_t batch) {
+              int order, int events, Plan* out, int64_t batch, const InSpec* in_spec) {
+    const InSpec& in = in_spec ? *in_spec : e4m3_spec();
     int rc = validate_shapes(M, N, K);
     if (rc != LBA_OK) return rc;
     if ((rc = validate_fmt(qp_in)) != LBA_OK) return rc;
@@ -151,31 +182,35 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     KParams& kp = p.kp;
     kp.M = (int32_t)M; kp.N = (int32_t)N; kp.K = (int32_t)K;
 
-    const bool flush = prod_flush_possible(qp) && !nouf_p;
-    const bool clamp = prod_clamp_possible(qp);
-    const bool prod_round = qp.man_bits < 7;
+    kp.in_ea = in.ea; kp.in_ma = in.ma; kp.in_eb = in.eb; kp.in_mb = in.mb;
+    const bool flush = prod_flush_possible(qp, in) && !nouf_p;
+    const bool clamp = prod_clamp_possible(qp, in);
+    const bool prod_round = qp.man_bits + 1 < in.sig_bits;   // Q_prod's mantissa is narrower than a product
 
-    // effective biases: below -20 every product / every sum underflows anyway
-    const int bpe = !flush ? (qp.bias > 18 ? qp.bias : 18) : (qp.bias < -20 ? -20 : qp.bias);
-    const int bae = qa.bias < -20 ? -20 : qa.bias;
+    // effective biases: with R_UF at 2^(ptop+3) or above every product / every sum underflows anyway
+    const int lowest = -(in.ptop + 3);
+    const int bpe = !flush ? (qp.bias > -in.min_lsb ? qp.bias : -in.min_lsb) : (qp.bias < lowest ? lowest : qp.bias);
+    const int bae = qa.bias < lowest ? lowest : qa.bias;
     // kernel domains: the product's R_UF at 2^-126 (or, when Q_prod cannot flush, the smallest
     // product 2^-18 at or above 2^-126); the accumulator's R_UF at 2^-126, or, with the
     // no-underflow flag, a fixed 2^-60 that keeps every sum (a multiple of 2^-18) a normal number
     const int c_p_dom = bpe - 126;
     const int c_a_dom = nouf_a ? -60 : bae - 126;
 
-    bool fast = !prod_round;
+    // a narrower product mantissa is a bit mask when Q_prod rounds by truncation (forward call only)
+    bool fast = !prod_round || (qp.round == LBA_ROUND_FLOOR && !events);
     // the recompute call has a scaled-domain kernel for floor rounding when Q_prod can underflow
     // (its product-underflow test is the multiply's flush); anything else takes the general kernel
     if (events && (qa.round != LBA_ROUND_FLOOR || !flush)) fast = false;
-    if (fast && qa.round == LBA_ROUND_RNE && !rne_fast_ok(qp, qa, clamp, flush, nouf_a)) fast = false;
+    if (fast && qa.round == LBA_ROUND_RNE && !rne_fast_ok(qp, qa, clamp, flush, nouf_a, in)) fast = false;
     if (fast && (flush || clamp) && std::abs(c_a_dom - c_p_dom) > 120) fast = false;   // kc must be an FP32 normal
     // the recompute kernel also forms p * kc * 2^60 and S * 2^60
     if (fast && events && (std::abs(c_a_dom - c_p_dom) > 60 || top_exp(qa) + c_a_dom + 61 > 126)) fast = false;
 
     if (fast) {
         p.kernel = KERNEL_FAST;
-        p.prod_mode = clamp ? PM_FLUSH_CLAMP : (flush ? PM_FLUSH : PM_IDENT);
+        p.prod_mode = prod_round ? (clamp ? PM_TRUNC_CLAMP : PM_TRUNC)
+                                 : (clamp ? PM_FLUSH_CLAMP : (flush ? PM_FLUSH : PM_IDENT));
         const int c_a = c_a_dom;
         const int c_p = (p.prod_mode == PM_IDENT) ? c_a : c_p_dom;
         kp.exp_a = c_p / 2;                                // split the product's scale over a and b
@@ -188,7 +223,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         // (v_mul_f32 / v_fma_f32 / v_and_b32 with register operands: 32 lanes per clock per SIMD).
         // v_med3_f32, v_bfe_u32 and v_add3_u32 issue at half that rate and count 2.
         int slots = (p.prod_mode == PM_IDENT) ? 2 : 3;           // [mul,] fma, and
-        if (p.prod_mode == PM_FLUSH_CLAMP) slots += 2;           // med3 on the product
+        if (p.prod_mode == PM_FLUSH_CLAMP || p.prod_mode == PM_TRUNC_CLAMP) slots += 2;   // med3 on the product
+        if (prod_round) slots += 1;                              // and on the product
         if (qa.round == LBA_ROUND_RNE) slots += (qa.man_bits == 7) ? 1 : 4;   // M = 7: cvt to bfloat16 replaces and; else bfe, add3
         p.valu_per_mac_x100 = slots * 100;
         if (events)                                              // 5 full-rate + 7 half-rate instructions, + operand tests
@@ -207,7 +243,7 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         kp.prod_rne = (qp.round == LBA_ROUND_RNE) ? 1 : 0;
         p.valu_per_mac_x100 = 0;                           // filled by the launcher's table
     }
-    pick_tile(M, N, batch, p.kernel, p.events, &p.tm, &p.tn, &p.bk);
+    pick_tile(M, N, batch, p.kernel, p.events, p.prod_mode, &p.tm, &p.tn, &p.bk);
     kp.batch = 1;
     kp.fast_thresh = -1.0f;
     kp.fast_thresh4 = -1.0f;
@@ -215,7 +251,7 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         // |S| can grow by at most max|p| per step (and by the rounding, for nearest-even): below
         // this bound at the start of n k-tiles, no sum inside them reaches R_OF of Q_acc.
         const int c_a = -kp.out_exp;
-        double pmax = kMaxProd;
+        double pmax = in.max_prod;
         if (clamp) pmax = std::ldexp(2.0 - std::ldexp(1.0, -qp.man_bits), top_exp(qp));
         pmax = std::ldexp(pmax, c_a);
         for (int n = 1; n <= 4; n += 3) {

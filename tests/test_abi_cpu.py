@@ -106,9 +106,12 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     q = lb.lba_plan_query
     assert q(64, 64, 64, (5, 7, 15, 1), (5, 3, 15, 1))["kernel"] == 1     # nearest-even, M_acc < 7, inexact sums below R_OF
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 11, 7, 1))["kernel"] == 1     # nearest-even, M_acc > 10
-    assert q(64, 64, 64, (5, 9, 15, 1), (4, 8, 7, 1))["kernel"] == 1      # saturated product off the grid
+    assert q(64, 64, 64, (5, 9, 15, 1), (5, 8, 15, 1))["kernel"] == 1     # saturated product off the grid, sums below R_OF
+    assert q(64, 64, 64, (5, 9, 15, 1), (4, 8, 7, 1))["kernel"] == 0      # same product, but then every sum saturates
     assert q(64, 64, 64, (5, 7, 40, 1), (4, 7, -9, 1))["kernel"] == 1     # products far below R_UF of Q_acc
-    assert q(64, 64, 64, (5, 4, 15, 0), (4, 7, 7, 0))["kernel"] == 1      # product mantissa is rounded
+    assert q(64, 64, 64, (5, 4, 15, 1), (4, 7, 7, 1))["kernel"] == 1      # product mantissa is rounded to nearest
+    assert q(64, 64, 64, (5, 4, 15, 0), (4, 7, 7, 0))["prod_mode"] == 4   # ... truncated (and clamped): a bit mask in the scaled kernel
+    assert q(64, 64, 64, (6, 4, 20, 0), (4, 7, 7, 0))["prod_mode"] == 3   # ... truncated, cannot saturate
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 3, 7, 0))["kernel"] == 0      # floor is exact at any M
     assert q(64, 64, 64, (5, 7, 15, 0), (7, 23, 64, 0))["kernel"] == 0
     # no-underflow flag: still the scaled kernel; a flagged Q_prod that cannot saturate is the identity
@@ -128,6 +131,7 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 3, 7, 1))["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 6, 7, 1))["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 1), (5, 6, 15, 1))["kernel"] == 1
-    assert q(64, 64, 64, (4, 9, 7, 1), (4, 6, 7, 1))["kernel"] == 1       # a saturated product has 10 bits
+    assert q(64, 64, 64, (4, 9, 7, 1), (4, 6, 7, 1))["kernel"] == 0       # a saturated product has 10 bits: still clear of midpoints
+    assert q(64, 64, 64, (4, 12, 7, 1), (4, 9, 7, 1))["kernel"] == 1      # 13 + 9 bits: an inexact sum could reach one
     with pytest.raises(lb.LbaError):
         q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=2)

@@ -414,3 +414,50 @@ def test_overflow_plane_alone(ref):
             assert np.array_equal(bits(got[0].cpu().numpy()), bits(want[0]))
             assert np.array_equal(got[1].cpu().numpy().view(np.uint32), want[1])
             assert np.array_equal(got[3].cpu().numpy().view(np.uint32), want[3])
+
+
+def test_operand_code_formats(ref):
+    # lba_gemm_in / lba_gemm_bwd_in: operands in other 8-bit formats (the paper's M4E3 with a per-tensor
+    # bias, E5M2, E2M5, mixed with E4M3).  Products have up to 12 significant bits, so Q_prod's mantissa
+    # rounding is active: truncation runs in the scaled kernel, nearest-even in the general one.
+    rng = np.random.default_rng(110)
+    shapes = [(70, 66, 100), (33, 130, 64), (5, 3, 31), (64, 64, 200)]
+    combos = [((3, 4, 3), (3, 4, 3), (5, 7, 15), (4, 7, 7)),        # canonical biases
+              ((3, 4, 6), (3, 4, 1), (5, 7, 15), (4, 7, 7)),        # flex biases: folded into the quantizers
+              ((3, 4, -2), (4, 3, 9), (4, 7, 12), (4, 7, 10)),      # mixed with E4M3; the paper's (10, 12) pair
+              ((5, 2, 15), (5, 2, 17), (5, 7, 15), (4, 7, 7)),      # E5M2: 6-bit products
+              ((2, 5, 1), (2, 5, 0), (5, 7, 15), (4, 7, 7)),        # E2M5: 12-bit products
+              ((3, 4, 3), (3, 4, 3), (6, 9, 20), (4, 7, 7)),        # Q_prod wide enough: no product rounding
+              ((3, 4, 3), (3, 4, 3), (5, 5, 15), (5, 10, 15)),      # narrow Q_prod, wide accumulator
+              ((3, 4, 4), (3, 4, 4), (3, 4, 6), (3, 4, 6))]         # 8-bit accumulator
+    for (M, N, K) in shapes:
+        A = rng.integers(0, 256, (M, K)).astype(np.uint8); B = rng.integers(0, 256, (N, K)).astype(np.uint8)
+        tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+        for (fa, fb, qp, qa), rnd, order in itertools.product(combos, (0, 1), (0, 1)):
+            qpf, qaf = qp + (rnd,), qa + (rnd,)
+            got = lb.gemm_in(tA, tB, fa, fb, qpf, qaf, order=order)
+            torch.cuda.synchronize()
+            want = ref.gemm_in(A, B, ref.InFmt(*fa), ref.InFmt(*fb), fm(ref, qpf), fm(ref, qaf), order=order)
+            bad = bits(got.cpu().numpy()) != bits(want)
+            assert not bad.any(), ((M, N, K), fa, fb, qpf, qaf, order, int(bad.sum()), got.cpu().numpy()[bad][:3], want[bad][:3])
+        # the recompute call (sequential order)
+        for (fa, fb, qp, qa), rnd in itertools.product(combos[:3], (0, 1)):
+            qpf, qaf = qp + (rnd,), qa + (rnd,)
+            C, of, uf = lb.gemm_in(tA, tB, fa, fb, qpf, qaf, planes=True)
+            torch.cuda.synchronize()
+            wc, wof, wuf = ref.gemm_in(A, B, ref.InFmt(*fa), ref.InFmt(*fb), fm(ref, qpf), fm(ref, qaf), planes=True)
+            assert np.array_equal(bits(C.cpu().numpy()), bits(wc)), (fa, fb, qpf, qaf)
+            assert np.array_equal(of.cpu().numpy().view(np.uint32), wof) and np.array_equal(uf.cpu().numpy().view(np.uint32), wuf)
+    # E4M3 through the general entry point is lba_gemm
+    A = rand_codes(rng, (40, 50)); B = rand_codes(rng, (30, 50))
+    tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    assert torch.equal(lb.gemm_in(tA, tB, (4, 3, 7), (4, 3, 7), (5, 7, 15, 0), (4, 7, 7, 0)), lb.gemm(tA, tB, (5, 7, 15, 0), (4, 7, 7, 0)))
+    # limits
+    a, b = tA.data_ptr(), tB.data_ptr()
+    c = torch.empty((40, 30), dtype=torch.float32, device=DEV).data_ptr()
+    assert lb.lba_gemm_in(a, b, c, 40, 30, 50, (3, 3, 3), (3, 4, 3), (5, 7, 15, 0), (4, 7, 7, 0)) == lb.ERR_FORMAT
+    assert lb.lba_gemm_in(a, b, c, 40, 30, 50, (3, 4, 33), (3, 4, 3), (5, 7, 15, 0), (4, 7, 7, 0)) == lb.ERR_FORMAT
+    assert lb.lba_gemm_in(a, b, c, 40, 30, 50, (3, 4, 32), (3, 4, 32), (5, 7, 120, 0), (4, 7, 7, 0)) == lb.OK
+    assert lb.lba_gemm_in(a, b, c, 40, 30, 50, (3, 4, -32), (3, 4, -32), (5, 7, 120, 0), (4, 7, 7, 0)) == lb.ERR_FORMAT   # folded bias 190
+    assert lb.lba_gemm_bwd_in(a, b, c, c, None, 40, 30, 50, (3, 4, 3), (3, 4, 3), (5, 7, 15, 0), (4, 7, 7, 0), order=1) == lb.ERR_UNSUPPORTED
+    torch.cuda.synchronize()
