@@ -44,7 +44,11 @@ def cpu_baseline(layer, qp, qa, C_gpu, order=0, threads=None, budget_macs=2.0e9)
     A = layer["A"][:rows].cpu().numpy()
     B = layer["B"].cpu().numpy()
     t0 = time.perf_counter()
-    want = lba_ref.gemm(A, B, lba_ref.QFmt(*qp), lba_ref.QFmt(*qa), order=order, nthreads=threads)
+    if "fa" in layer:
+        want = lba_ref.gemm_in(A, B, lba_ref.InFmt(*layer["fa"]), lba_ref.InFmt(*layer["fb"]), lba_ref.QFmt(*qp),
+                               lba_ref.QFmt(*qa), order=order, nthreads=threads)
+    else:
+        want = lba_ref.gemm(A, B, lba_ref.QFmt(*qp), lba_ref.QFmt(*qa), order=order, nthreads=threads)
     dt = time.perf_counter() - t0
     got = C_gpu[:rows].cpu().numpy()
     parity = bool(np.array_equal(got.view(np.uint32), want.view(np.uint32)))
@@ -66,6 +70,8 @@ def main():
                     help="accumulation order: one sequential chain (default) or the paper's chunks of 16")
     ap.add_argument("--acc", default=None, metavar="E,M",
                     help="accumulator format with b = 2^(E-1)-1 instead of the 12-bit M7E4 (format sweeps)")
+    ap.add_argument("--in-fmt", default=None, metavar="E,M",
+                    help="operands in that 8-bit format with per-tensor flex bias (3,4 = the paper's M4E3) through lba_gemm_in")
     ap.add_argument("--bwd", action="store_true",
                     help="time lba_gemm_bwd (forward chain + both event planes) instead of lba_gemm")
     ap.add_argument("--of-only", action="store_true", help="with --bwd: ask for the overflow plane only")
@@ -96,12 +102,25 @@ def main():
     if args.acc:
         e, m = (int(v) for v in args.acc.split(","))
         acc_fmt = (e, m, 2 ** (e - 1) - 1)
-    layers = inputs.make_workload(args.workload, dev)
+    in_fmt = tuple(int(v) for v in args.in_fmt.split(",")) if args.in_fmt else None
+    if in_fmt and (args.bwd or args.grad):
+        raise SystemExit("bench.py: --in-fmt times the forward call only")
+    layers = inputs.make_workload(args.workload, dev, in_fmt=in_fmt)
     cmax = max(l["M"] * l["N"] for l in layers)
     Cbuf = torch.empty(cmax, dtype=torch.float32, device=dev)
     for l in layers:
-        l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], PROD_FMT, acc_fmt, rnd)
-        l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, 1 if args.bwd else 0)
+        if in_fmt:                                          # biases stay in real units: the library folds the flex biases
+            l["qp"], l["qa"] = PROD_FMT + (rnd,), acc_fmt + (rnd,)
+            l["fa"], l["fb"] = in_fmt + (l["ta"],), in_fmt + (l["tb"],)
+            qpq, qaq, _ = inputs.folded_formats(l["ta"] - (2 ** (in_fmt[0] - 1) - 1), l["tb"] - (2 ** (in_fmt[0] - 1) - 1), PROD_FMT, acc_fmt, rnd)
+            # the plan of an E4M3 call with the same folded quantizers names tile and grid; the product mode is
+            # "truncating" when Q_prod's mantissa is narrower than the 2M+2 bits of a product
+            l["plan"] = dict(lb.lba_plan_query(l["M"], l["N"], l["K"], qpq, qaq, order, 0))
+            if PROD_FMT[1] + 1 < 2 * in_fmt[1] + 2 and rnd == 0:
+                l["plan"].update(prod_mode=4, thread_m=4, thread_n=4, valu_per_mac_x100=l["plan"]["valu_per_mac_x100"] + 100)
+        else:
+            l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], PROD_FMT, acc_fmt, rnd)
+            l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, 1 if args.bwd else 0)
         l["C"] = Cbuf[: l["M"] * l["N"]].view(l["M"], l["N"])
         l["macs"] = l["M"] * l["N"] * l["K"]
     if args.grad:
@@ -155,8 +174,16 @@ def main():
             if rc != 0:
                 raise RuntimeError(lb.lba_strerror(rc))
     else:
+        stream0 = torch.cuda.current_stream().cuda_stream
+
         def launch(l):
-            lb.gemm(l["A"], l["B"], l["qp"], l["qa"], order=order, out=l["C"])
+            if in_fmt:
+                rc = lb.lba_gemm_in(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), l["M"], l["N"], l["K"],
+                                    l["fa"], l["fb"], l["qp"], l["qa"], order, stream0)
+                if rc != 0:
+                    raise RuntimeError(lb.lba_strerror(rc))
+            else:
+                lb.gemm(l["A"], l["B"], l["qp"], l["qa"], order=order, out=l["C"])
 
     def one_step(events=None):
         for i, l in enumerate(layers):
@@ -241,7 +268,8 @@ def main():
                                 "bert": "BERT-base linears, 4096 tokens", "gemm4096": "4096^3 GEMM",
                                 "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}[args.workload],
                    "macs_per_step": total_macs, "qprod": "M7E5 b=15", "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
-                   "call": ("lba_grad, %s estimator: dX and dW (2 masked MACs per forward MAC)" % args.grad) if args.grad else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else ("lba_gemm_bwd (C + OF plane)" if args.of_only else "lba_gemm_bwd (C + OF and UF planes)")) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b"},
+                   "call": ("lba_grad, %s estimator: dX and dW (2 masked MACs per forward MAC)" % args.grad) if args.grad else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else ("lba_gemm_bwd (C + OF plane)" if args.of_only else "lba_gemm_bwd (C + OF and UF planes)")) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
+                   "operands": ("E%dM%d codes with per-tensor flex bias (lba_gemm_in)" % in_fmt) if in_fmt else "E4M3"},
         "roofline": roofline,
     }
     if not args.no_cpu_baseline and not args.grad:

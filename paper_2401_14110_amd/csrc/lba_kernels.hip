@@ -36,6 +36,9 @@ __device__ __forceinline__ void set_round_ninf()    { asm volatile("s_setreg_imm
 __device__ __forceinline__ void set_round_zero()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 3\n\ts_nop 1" ::: "memory"); }
 __device__ __forceinline__ void set_flush_f32()     { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 4, 2), 0\n\ts_nop 1" ::: "memory"); }
 
+// FP16 denormals on (MODE[7:6] = 3): the staging decodes 8-bit codes through an exact FP16 image
+__device__ __forceinline__ void set_denorm_f16()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 6, 2), 3\n\ts_nop 1" ::: "memory"); }
+
 __device__ __forceinline__ float med3(float x, float lo, float hi) { return __builtin_amdgcn_fmed3f(x, lo, hi); }
 
 // ---------------------------------------------------------------------------------------------
@@ -276,8 +279,10 @@ __device__ __forceinline__ void store_tile(float* __restrict__ dst /* [BK][ROWS]
 // Same, decoding with the hardware FP8 conversion (gfx950 decodes OCP E4M3) and one exact
 // multiply by the power-of-two scale.  The two NaN codes, which the conversion would turn into NaN,
 // are patched to +-480 * scale on a rarely taken path so that every code has a defined value.
-// Codes of another format (E exponent bits, not 4) are decoded arithmetically: integer significand
-// times a power of two, exact.
+// Codes of another format with E < 4 go through FP16: sign | (e << 10) | (m << (10 - M)) is the FP16 number
+// value(code) * 2^(bias - 15), subnormals included, so the hardware FP16 -> FP32 conversion and one exact
+// multiply by 2^(15 - bias + scale_exp) decode it.  E = 5 would put e = 31 on FP16's inf / NaN codes and is
+// decoded arithmetically (integer significand times a power of two).
 template <int ROWS, int BK>
 __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][ROWS] */, float scale,
                                                int tid, const uint4 (&regs)[Stage<ROWS, BK>::kPerLane],
@@ -291,10 +296,21 @@ __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][R
                 const int row = c & (ROWS - 1);
                 const int kq = c >> Stage<ROWS, BK>::kRowShift;
                 const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
+                const float sc16 = __builtin_ldexpf(1.0f, 15 - ((1 << (E - 1)) - 1) + scale_exp);
+                const int up = 10 - M;
+                if (E < 4) {
 #pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const int code = (int)((w[j >> 2] >> (8 * (j & 3))) & 0xFFu);
-                    dst[(kq * 16 + j) * ROWS + row] = decode_entry(code, scale_exp, E, M);
+                    for (int j = 0; j < 16; ++j) {
+                        const uint32_t code = (w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
+                        const uint16_t h = (uint16_t)(((code & 0x80u) << 8) | ((code & 0x7Fu) << up));
+                        dst[(kq * 16 + j) * ROWS + row] = (float)__builtin_bit_cast(_Float16, h) * sc16;
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 16; ++j) {
+                        const int code = (int)((w[j >> 2] >> (8 * (j & 3))) & 0xFFu);
+                        dst[(kq * 16 + j) * ROWS + row] = decode_entry(code, scale_exp, E, M);
+                    }
                 }
             }
         }
@@ -446,6 +462,7 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
 
     const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
     set_flush_f32();
+    set_denorm_f16();
     if (RND == LBA_ROUND_FLOOR) set_round_zero();
 
     FastConst c;
@@ -606,6 +623,7 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
 
     const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
     set_flush_f32();
+    set_denorm_f16();
     set_round_zero();
 
     // kc_up / up: the same product and accumulator moved up by 2^60, where neither can flush

@@ -90,6 +90,47 @@ def to_e4m3(x):
     return code.to(torch.uint8)
 
 
+def fp8_max(E, M):
+    """Largest value of the 8-bit format (1 sign, E exponent, M mantissa bits, bias 2^(E-1) - 1, every
+    code finite)."""
+    return (2.0 - 2.0 ** -M) * 2.0 ** ((1 << E) - 1 - ((1 << (E - 1)) - 1))
+
+
+def to_fp8_code(x, E, M):
+    """float64 tensor -> uint8 codes of that format at its canonical bias: round-to-nearest-even,
+    saturating at +-fp8_max(E, M).  (E, M) = (3, 4) is the paper's M4E3 weight / activation format."""
+    bias = (1 << (E - 1)) - 1
+    emin = 1 - bias
+    ax = x.abs().clamp(max=fp8_max(E, M))
+    _, ex = torch.frexp(ax)
+    e = (ex - 1).clamp(min=emin)                  # below 2^emin the grid is the subnormal one
+    q = torch.round(ax / torch.ldexp(torch.ones_like(ax), e - M))
+    v = q * torch.ldexp(torch.ones_like(ax), e - M)
+    _, ex2 = torch.frexp(v)
+    e2 = (ex2 - 1).clamp(min=emin)                # a mantissa carry moves to the next binade
+    m = torch.round(v / torch.ldexp(torch.ones_like(v), e2 - M)).to(torch.int64)    # 0 .. 2^(M+1) - 1
+    normal_code = ((e2 + bias).to(torch.int64) << M) + (m - (1 << M))
+    code = torch.where(m >= (1 << M), normal_code, m)
+    code = code + (torch.signbit(x).to(torch.int64) << 7)
+    return code.to(torch.uint8)
+
+
+def quantize_tensor_fp8(x, E, M):
+    """Per-tensor "flex-bias" cast (Sec. 3.1 of the paper): the largest integer exponent bias that keeps
+    max|x| inside the format.  Returns (uint8 codes, bias): value(code) = (canonical value) * 2^(canonical - bias)."""
+    mx = float(x.abs().max())
+    top = fp8_max(E, M)
+    t = 0
+    if mx > 0.0 and math.isfinite(mx):
+        t = math.floor(math.log2(top / mx))
+        while mx * 2.0 ** (t + 1) <= top:
+            t += 1
+        while mx * 2.0 ** t > top:
+            t -= 1
+    codes = to_fp8_code(torch.ldexp(x, torch.tensor(t, device=x.device)), E, M)
+    return codes, ((1 << (E - 1)) - 1) + t
+
+
 def pow2_scale_exp(x):
     """Largest integer t with max|x| * 2^t <= 448 (the per-tensor power-of-two scale)."""
     mx = float(x.abs().max())
@@ -117,9 +158,10 @@ def quantize_tensor(x, scale_mode="pow2"):
 
 
 def make_operand(kind, rows, cols, seed, stream, device="cpu", scale_mode="pow2", std=1.0,
-                 row_chunk=None):
+                 row_chunk=None, in_fmt=None):
     """One operand matrix [rows, cols] of E4M3 codes.  kind: 'normal' N(0,std^2) or 'relu'
-    ReLU(N(0,1)).  Returns (codes uint8 [rows, cols], t)."""
+    ReLU(N(0,1)).  Returns (codes uint8 [rows, cols], t); with in_fmt = (E, M) the codes are of that
+    format and t is its flex bias."""
     n = rows * cols
     x = normal(seed, stream, n, device=device)
     if kind == "relu":
@@ -129,7 +171,10 @@ def make_operand(kind, rows, cols, seed, stream, device="cpu", scale_mode="pow2"
             x = x * std
     else:
         raise ValueError(kind)
-    codes, t = quantize_tensor(x, scale_mode)
+    if in_fmt is not None:
+        codes, t = quantize_tensor_fp8(x, *in_fmt)
+    else:
+        codes, t = quantize_tensor(x, scale_mode)
     return codes.reshape(rows, cols), t
 
 
@@ -167,13 +212,14 @@ def bert_base_gemms(batch=32, seq=128):
             ("ffn_in", m, 3072, 768), ("ffn_out", m, 768, 3072)]
 
 
-def make_workload(name, device="cpu"):
+def make_workload(name, device="cpu", in_fmt=None):
     """Operands of a named workload as a list of dicts (name, M, N, K, A, B, ta, tb): A [M,K] and
     B [N,K] uint8 codes on `device`, ta / tb the power-of-two scale exponents.  Layers of equal
     operand shape share data.  Workloads: 'resnet50' (ResNet-50 forward, batch 64, 224x224: 54 GEMMs),
     'conv' (ResNet-18 3x3 conv 64->64 at batch 32), 'bert' (BERT-base linears, 4096 tokens),
     'gemm4096' (4096^3, N(0,1) operands), 'config1' (M=N=64, K=256, N(0,1) operands scaled to
-    max|x| = 448, seed 0)."""
+    max|x| = 448, seed 0).  With in_fmt = (E, M) the codes are of that 8-bit format and ta / tb are the
+    per-tensor flex biases (for lba_gemm_in, with the quantizers' biases in real units)."""
     if name == "resnet50":
         layers = resnet50_gemms(batch=64, image=224)
         seed = 2
@@ -203,7 +249,7 @@ def make_workload(name, device="cpu"):
             else:
                 kind = "normal"
             cache_a[(M, K)] = make_operand(kind, M, K, seed, 2 * len(cache_a), device=device,
-                                           scale_mode=mode)
+                                           scale_mode=mode, in_fmt=in_fmt)
         if (N, K) not in cache_b:
             if name in ("resnet50", "conv"):
                 std = (2.0 / K) ** 0.5
@@ -212,7 +258,7 @@ def make_workload(name, device="cpu"):
             else:
                 std = 1.0
             cache_b[(N, K)] = make_operand("normal", N, K, seed, 2 * len(cache_b) + 1,
-                                           device=device, std=std, scale_mode=mode)
+                                           device=device, std=std, scale_mode=mode, in_fmt=in_fmt)
         A, ta = cache_a[(M, K)]
         B, tb = cache_b[(N, K)]
         if mode == "exact448":

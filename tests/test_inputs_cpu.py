@@ -1,0 +1,49 @@
+"""The seeded input generators (shared by the HIP path's callers and the oracle's tests; they hold none
+of the method's arithmetic): determinism, the FP8 casts against torch's, the scale rules, the layer lists."""
+import numpy as np
+import torch
+
+from paper_2401_14110_amd import inputs
+
+
+def test_counter_rng_is_deterministic_and_chunk_independent():
+    a = inputs.normal(3, 1, 5000)
+    b = inputs.normal(3, 1, 5000, chunk=777)
+    assert torch.equal(a, b) and not torch.equal(a, inputs.normal(3, 2, 5000))
+    assert abs(float(a.mean())) < 0.05 and abs(float(a.std()) - 1.0) < 0.05
+
+
+def test_casts_match_torch_float8():
+    x = torch.cat([inputs.normal(1, 0, 200000) * 30.0, torch.tensor([0.0, -0.0, 448.0, -448.0, 2.0 ** -9, 2.0 ** -10, 1e-9,
+                                                                      0.001953125 * 1.5, 17.0, 464.0, 1e6], dtype=torch.float64)])
+    sat = x.clamp(-448.0, 448.0)
+    want = sat.float().to(torch.float8_e4m3fn).view(torch.uint8)
+    got = inputs.to_e4m3(x)
+    same = got == want
+    assert bool(same[sat.abs() > 0].all())                       # (torch keeps the sign of -0.0; so does the cast)
+    inside = x.abs() <= 448.0
+    assert torch.equal(inputs.to_fp8_code(x, 4, 3)[inside], got[inside])
+    inside = x.abs() <= 57344.0                                  # binary8 E5M2 ends there (e = 31 is inf / NaN)
+    assert torch.equal(inputs.to_fp8_code(x, 5, 2)[inside], x.float().to(torch.float8_e5m2).view(torch.uint8)[inside])
+    assert int(inputs.to_fp8_code(x, 5, 2)[-1]) == 0x7F          # every code is finite here: saturation at the top code
+    assert inputs.fp8_max(3, 4) == 31.0 and inputs.fp8_max(4, 3) == 480.0 and inputs.fp8_max(5, 2) == 114688.0
+
+
+def test_scale_rules():
+    x = inputs.normal(2, 0, 10000) * 0.02
+    codes, t = inputs.quantize_tensor(x)
+    mx = float(x.abs().max())
+    assert mx * 2.0 ** t <= 448.0 < mx * 2.0 ** (t + 1)
+    codes, bias = inputs.quantize_tensor_fp8(x, 3, 4)
+    t = bias - 3
+    assert mx * 2.0 ** t <= 31.0 < mx * 2.0 ** (t + 1)
+    assert int(codes.max()) >= 0x70                               # the top binade is used
+
+
+def test_layer_lists():
+    l = inputs.resnet50_gemms()
+    assert len(l) == 54 and sum(M * N * K for _, M, N, K in l) == 261707792384
+    assert min(K for _, _, _, K in l) == 64 and max(K for _, _, _, K in l) == 4608
+    assert [s[1:] for s in inputs.bert_base_gemms()] == [(4096, 2304, 768), (4096, 768, 768), (4096, 3072, 768), (4096, 768, 3072)]
+    w = inputs.make_workload("config1")
+    assert w[0]["A"].shape == (64, 256) and w[0]["ta"] == 0 and int(w[0]["A"].max()) >= 0x7E - 0x08
