@@ -104,6 +104,31 @@ int lba_gemm_bwd_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_m
                     int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,
                     lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream);
 
+/* Convolution straight from the activation tensor (implicit im2col; App. A: a convolution is the same
+ * dot product with shared weights).  X [n, h, w, c] codes (NHWC), W [cout, kh, kw, c] codes,
+ * Y [n, oh, ow, cout] float32 with oh = (h + 2 pad - kh) / stride + 1, ow likewise; all device pointers.
+ * It is lba_gemm with M = n*oh*ow rows, N = cout, K = kh*kw*c, where row (n, oh, ow) holds
+ * X[n, oh*stride - pad + i, ow*stride - pad + j, ch] at k = (i*kw + j)*c + ch (c fastest: this IS the
+ * accumulation order of every output's chain), and taps outside the image hold code 0 (the value +0).
+ * Limits (else LBA_ERR_SHAPE): every field >= 1 (pad >= 0), c < 2^14, kw < 2^14, K < 2^24, oh, ow >= 1,
+ * n*oh*ow <= 2^31 - 64.  Everything else as lba_gemm. */
+typedef struct {
+    int32_t n, h, w, c;     /* activation tensor */
+    int32_t kh, kw;         /* filter taps */
+    int32_t stride, pad;    /* same in both directions; dilation 1 */
+} lba_conv2d_desc;
+
+int lba_conv2d(const uint8_t* X, const uint8_t* W, float* Y, lba_conv2d_desc desc, int64_t cout,
+               lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream);
+
+/* lba_gemm_bwd of the same product (sequential order): planes of lba_mask_words(n*oh*ow, cout, kh*kw*c) words. */
+int lba_conv2d_bwd(const uint8_t* X, const uint8_t* W, float* Y, uint32_t* of_mask, uint32_t* uf_mask,
+                   lba_conv2d_desc desc, int64_t cout, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
+                   void* hip_stream);
+
+/* oh, ow of a descriptor (LBA_ERR_SHAPE if it is outside the limits above). */
+int lba_conv2d_out_shape(lba_conv2d_desc desc, int32_t* oh, int32_t* ow);
+
 /* `batch` independent forward products in one launch (batched matrix multiplication, e.g. the
  * attention products of a transformer, which the paper also runs through its LBA GEMM, App. C.2):
  * member z uses A + z*stride_a, B + z*stride_b (bytes) and C + z*stride_c (floats); a stride of 0

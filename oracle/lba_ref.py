@@ -168,6 +168,23 @@ def gemm_in(A, B, fmt_a, fmt_b, qprod, qacc, order=ORDER_SEQ, nthreads=None, pla
     return (C, of, uf) if planes else C
 
 
+def im2col_nhwc(X, kh, kw, stride=1, pad=0):
+    """The GEMM operand of a convolution, written out: X [n, h, w, c] uint8 codes -> [n*oh*ow, kh*kw*c] with
+    k = (i*kw + j)*c + ch and code 0 (the value +0) for taps outside the image (App. A of the paper: a
+    convolution is the same dot product with shared weights)."""
+    X = np.asarray(X, dtype=np.uint8)
+    n, h, w, c = X.shape
+    oh = (h + 2 * pad - kh) // stride + 1
+    ow = (w + 2 * pad - kw) // stride + 1
+    Xp = np.zeros((n, h + 2 * pad, w + 2 * pad, c), dtype=np.uint8)
+    Xp[:, pad:pad + h, pad:pad + w, :] = X
+    cols = np.empty((n, oh, ow, kh, kw, c), dtype=np.uint8)
+    for i in range(kh):
+        for j in range(kw):
+            cols[:, :, :, i, j, :] = Xp[:, i:i + stride * (oh - 1) + 1:stride, j:j + stride * (ow - 1) + 1:stride, :]
+    return cols.reshape(n * oh * ow, kh * kw * c)
+
+
 def mask_words(M, N, K):
     return ((K + 31) // 32) * M * N
 

@@ -30,6 +30,10 @@ def infmt(f):
     return f if isinstance(f, lba_infmt) else lba_infmt(*[int(v) for v in f])
 
 
+class lba_conv2d_desc(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("n", "h", "w", "c", "kh", "kw", "stride", "pad")]
+
+
 class lba_plan_info(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "kernel", "prod_mode", "round", "tile_m", "tile_n", "tile_k", "thread_m", "thread_n",
@@ -68,6 +72,12 @@ def lib():
         L.lba_gemm_in.argtypes = [vp, vp, vp, i64, i64, i64, lba_infmt, lba_infmt, lba_qfmt, lba_qfmt, i32, vp]
         L.lba_gemm_bwd_in.restype = ctypes.c_int
         L.lba_gemm_bwd_in.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, lba_infmt, lba_infmt, lba_qfmt, lba_qfmt, i32, vp]
+        L.lba_conv2d.restype = ctypes.c_int
+        L.lba_conv2d.argtypes = [vp, vp, vp, lba_conv2d_desc, i64, lba_qfmt, lba_qfmt, i32, vp]
+        L.lba_conv2d_bwd.restype = ctypes.c_int
+        L.lba_conv2d_bwd.argtypes = [vp, vp, vp, vp, vp, lba_conv2d_desc, i64, lba_qfmt, lba_qfmt, i32, vp]
+        L.lba_conv2d_out_shape.restype = ctypes.c_int
+        L.lba_conv2d_out_shape.argtypes = [lba_conv2d_desc, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
         L.lba_last_overflow.restype = ctypes.c_int
         L.lba_last_overflow.argtypes = [vp, vp, i64, i64, i64, vp]
         L.lba_ste_plane.restype = ctypes.c_int
@@ -143,6 +153,27 @@ def lba_gemm_bwd_in(A, B, C, of_mask, uf_mask, M, N, K, fmt_a, fmt_b, qprod, qac
     return lib().lba_gemm_bwd_in(A, B, C, of_mask, uf_mask, M, N, K, infmt(fmt_a), infmt(fmt_b), qfmt(qprod),
                                  qfmt(qacc), order,
                                  ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def _desc(d):
+    return d if isinstance(d, lba_conv2d_desc) else lba_conv2d_desc(*[int(v) for v in d])
+
+
+def lba_conv2d(X, W, Y, desc, cout, qprod, qacc, order=ORDER_SEQ, hip_stream=None):
+    return lib().lba_conv2d(X, W, Y, _desc(desc), cout, qfmt(qprod), qfmt(qacc), order,
+                            ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_conv2d_bwd(X, W, Y, of_mask, uf_mask, desc, cout, qprod, qacc, order=ORDER_SEQ, hip_stream=None):
+    return lib().lba_conv2d_bwd(X, W, Y, of_mask, uf_mask, _desc(desc), cout, qfmt(qprod), qfmt(qacc), order,
+                                ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_conv2d_out_shape(desc):
+    """(status, oh, ow)"""
+    oh, ow = ctypes.c_int32(0), ctypes.c_int32(0)
+    rc = lib().lba_conv2d_out_shape(_desc(desc), ctypes.byref(oh), ctypes.byref(ow))
+    return rc, oh.value, ow.value
 
 
 def lba_last_overflow(of_mask, last_of, M, N, K, hip_stream=None):
@@ -300,3 +331,31 @@ def gemm_in(A, B, fmt_a, fmt_b, qprod, qacc, order=ORDER_SEQ, planes=False, stre
                                  of.data_ptr() or None, uf.data_ptr() or None, M, N, K,
                                  infmt(fmt_a), infmt(fmt_b), qfmt(qprod), qfmt(qacc), order, _stream(stream)))
     return C, of, uf
+
+
+def conv2d(X, W, qprod, qacc, stride=1, pad=0, order=ORDER_SEQ, planes=False, stream=None):
+    """X [n, h, w, c] and W [cout, kh, kw, c] uint8 device tensors -> Y [n, oh, ow, cout] float32
+    (with planes: also the OF and UF planes [ceil(K/32), n*oh*ow, cout] of the recompute call)."""
+    if X.dtype != torch.uint8 or W.dtype != torch.uint8 or not (X.is_cuda and W.is_cuda):
+        raise TypeError("X and W must be uint8 device tensors")
+    X = X.contiguous()
+    W = W.contiguous()
+    n, h, w, c = X.shape
+    cout, kh, kw, c2 = W.shape
+    if c != c2:
+        raise ValueError("channel mismatch")
+    desc = lba_conv2d_desc(n, h, w, c, kh, kw, stride, pad)
+    rc, oh, ow = lba_conv2d_out_shape(desc)
+    _check(rc)
+    Y = torch.empty((n, oh, ow, cout), dtype=torch.float32, device=X.device)
+    if not planes:
+        _check(lib().lba_conv2d(X.data_ptr() or None, W.data_ptr() or None, Y.data_ptr() or None, desc, cout,
+                                qfmt(qprod), qfmt(qacc), order, _stream(stream)))
+        return Y
+    M, K = n * oh * ow, kh * kw * c
+    of = torch.empty(((K + 31) // 32, M, cout), dtype=torch.int32, device=X.device)
+    uf = torch.empty_like(of)
+    _check(lib().lba_conv2d_bwd(X.data_ptr() or None, W.data_ptr() or None, Y.data_ptr() or None,
+                                of.data_ptr() or None, uf.data_ptr() or None, desc, cout,
+                                qfmt(qprod), qfmt(qacc), order, _stream(stream)))
+    return Y, of, uf

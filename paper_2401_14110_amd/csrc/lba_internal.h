@@ -40,6 +40,11 @@ struct KParams {
     // operand code formats as the kernels decode them (canonical bias 2^(E-1) - 1; the caller's bias
     // is folded into the quantizers and out_exp): {4, 3} takes the hardware FP8 conversion
     int32_t in_ea, in_ma, in_eb, in_mb;
+    // implicit im2col (conv = 1): A is an NHWC activation tensor [n, cv_h, cv_w, cv_c]; row m of the GEMM is
+    // output pixel (n, oh, ow) and k runs over (kh, kw, c), c fastest; taps outside the image read as code 0
+    int32_t conv, cv_vec;    // cv_vec: cv_c % 16 == 0 and A 16-byte aligned (a 16-byte piece is one load)
+    int32_t cv_h, cv_w, cv_c, cv_kw, cv_stride, cv_pad, cv_oh, cv_ow;
+    uint64_t cv_magic_c, cv_magic_kw;   // ceil(2^40 / d): x / d == (x * magic) >> 40 for x < 2^24, d < 2^14
     int32_t prod_round;      // GEN: product mantissa narrower than a product of two operands
     int32_t prod_rne;        // GEN: its rounding
 };

@@ -256,6 +256,62 @@ __device__ __forceinline__ void fetch_tile(const uint8_t* __restrict__ G, int ro
     }
 }
 
+// Implicit im2col: the same pieces gathered from an NHWC activation tensor.  Row r is output pixel
+// (n, oh, ow); byte k of the row is X[n, oh*stride - pad + kh, ow*stride - pad + kw, c] with
+// k = (kh * KW + kw) * C + c, or code 0 (the value +0) outside the image.  With C % 16 == 0 a 16-byte
+// piece lies inside one tap and is one aligned load; otherwise its bytes are gathered one by one.
+__device__ __forceinline__ uint32_t div_magic(uint32_t x, uint64_t magic) { return (uint32_t)(((uint64_t)x * magic) >> 40); }
+
+template <int ROWS, int BK>
+__device__ __forceinline__ void fetch_tile_conv(const uint8_t* __restrict__ X, const KParams& p, int r0, int k0,
+                                                int tid, uint4 (&regs)[Stage<ROWS, BK>::kPerLane]) {
+#pragma unroll
+    for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
+        const int c = tid + i * 256;
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
+            const int row = c & (ROWS - 1);
+            const int kq = c >> Stage<ROWS, BK>::kRowShift;
+            const int r = r0 + row, k = k0 + kq * 16;
+            if (r < p.M && k < p.K) {
+                const int ow = r % p.cv_ow, t = r / p.cv_ow;            // the lane's row never changes: hoisted
+                const int oh = t % p.cv_oh, n = t / p.cv_oh;
+                const int ih0 = oh * p.cv_stride - p.cv_pad, iw0 = ow * p.cv_stride - p.cv_pad;
+                const int64_t img = (int64_t)n * p.cv_h;
+                if (p.cv_vec) {
+                    const int tap = (int)div_magic((uint32_t)k, p.cv_magic_c), ch = k - tap * p.cv_c;
+                    const int kh = (int)div_magic((uint32_t)tap, p.cv_magic_kw), kw = tap - kh * p.cv_kw;
+                    const int ih = ih0 + kh, iw = iw0 + kw;
+                    if (ih >= 0 && ih < p.cv_h && iw >= 0 && iw < p.cv_w)
+                        v = *reinterpret_cast<const uint4*>(X + ((img + ih) * p.cv_w + iw) * p.cv_c + ch);
+                } else {
+                    uint32_t w[4] = {0u, 0u, 0u, 0u};
+                    for (int j = 0; j < 16; ++j) {
+                        const int kk = k + j;
+                        if (kk < p.K) {
+                            const int tap = (int)div_magic((uint32_t)kk, p.cv_magic_c), ch = kk - tap * p.cv_c;
+                            const int kh = (int)div_magic((uint32_t)tap, p.cv_magic_kw), kw = tap - kh * p.cv_kw;
+                            const int ih = ih0 + kh, iw = iw0 + kw;
+                            if (ih >= 0 && ih < p.cv_h && iw >= 0 && iw < p.cv_w)
+                                w[j >> 2] |= (uint32_t)X[((img + ih) * p.cv_w + iw) * p.cv_c + ch] << (8 * (j & 3));
+                        }
+                    }
+                    v = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+        }
+        regs[i] = v;
+    }
+}
+
+// A's pieces: a row-major matrix, or an activation tensor read as im2col rows.
+template <int ROWS, int BK>
+__device__ __forceinline__ void fetch_tile_a(const uint8_t* __restrict__ A, const KParams& p, int r0, int k0,
+                                             int tid, uint4 (&regs)[Stage<ROWS, BK>::kPerLane]) {
+    if (p.conv) fetch_tile_conv<ROWS, BK>(A, p, r0, k0, tid, regs);     // uniform
+    else        fetch_tile<ROWS, BK>(A, p.M, p.K, r0, k0, p.ld_align, tid, regs);
+}
+
 // Decode the fetched pieces through the table and store them k-major into one LDS stage.
 template <int ROWS, int BK>
 __device__ __forceinline__ void store_tile(float* __restrict__ dst /* [BK][ROWS] */, const float* __restrict__ lut,
@@ -480,7 +536,7 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
     uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
     const int ntiles = (p.K + BK - 1) / BK;                    // K > 0 here; division by a constant
 
-    fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
+    fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
     fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
     store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, p.in_ea, p.in_ma, p.exp_a);
     store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, p.in_eb, p.in_mb, p.exp_b);
@@ -491,7 +547,7 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
         const float* Bs = As + BK * BM;
         const bool more = (t + 1) < ntiles;
         if (more) {
-            fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
+            fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
             fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
         // (Chunked order: the test is on the second-level sums; a first-level sum starts from 0 and
@@ -648,7 +704,7 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
     uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
     const int ntiles = (p.K + BK - 1) / BK;
 
-    fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
+    fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
     fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
     store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, p.in_ea, p.in_ma, p.exp_a);
     store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, p.in_eb, p.in_mb, p.exp_b);
@@ -659,7 +715,7 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
         const float* Bs = As + BK * BM;
         const bool more = (t + 1) < ntiles;
         if (more) {
-            fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
+            fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
             fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
         bool quiet = false;                                    // no sum of this tile can reach R_OF
@@ -935,7 +991,7 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
     const int ntiles = (p.K + BK - 1) / BK;
     const uint32_t rofb = __float_as_uint(p.rof_a), rufb = __float_as_uint(p.ruf_a);
 
-    fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
+    fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
     fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tid, rb);
     __syncthreads();
     store_tile<BM, BK>(smem, lut_a, tid, ra);
@@ -947,7 +1003,7 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
         const float* Bs = As + BK * BM;
         const bool more = (t + 1) < ntiles;
         if (more) {
-            fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
+            fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
             fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tid, rb);
         }
 #pragma unroll 2
@@ -1103,7 +1159,8 @@ static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, 
                int64_t M, int64_t N, int64_t K, const lba_qfmt& qprod, const lba_qfmt& qacc,
                int order, int events, void* stream,
                int64_t batch = 1, int64_t stride_a = 0, int64_t stride_b = 0, int64_t stride_c = 0,
-               uint32_t* of_mask2 = nullptr, uint32_t* uf_mask2 = nullptr, const InSpec* in = nullptr) {
+               uint32_t* of_mask2 = nullptr, uint32_t* uf_mask2 = nullptr, const InSpec* in = nullptr,
+               const lba_conv2d_desc* conv = nullptr, int conv_oh = 0, int conv_ow = 0) {
     Plan pl;
     if (batch < 0 || batch > 65535 || stride_a < 0 || stride_b < 0 || stride_c < 0) return LBA_ERR_SHAPE;
     int rc = make_plan(M, N, K, qprod, qacc, order, events, &pl, batch, in);
@@ -1129,7 +1186,17 @@ static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, 
     kp.A = A; kp.B = B; kp.C = C; kp.of_mask = of_mask; kp.uf_mask = uf_mask;
     kp.of_mask2 = of_mask2; kp.uf_mask2 = uf_mask2;
     kp.batch = (int32_t)batch; kp.stride_a = stride_a; kp.stride_b = stride_b; kp.stride_c = stride_c;
-    const int la = gcd_align(A, K), lb = gcd_align(B, K);
+    int la = gcd_align(A, K);
+    const int lb = gcd_align(B, K);
+    if (conv) {                                                // A is gathered; only B's rows need the alignment
+        kp.conv = 1;
+        kp.cv_h = conv->h; kp.cv_w = conv->w; kp.cv_c = conv->c; kp.cv_kw = conv->kw;
+        kp.cv_stride = conv->stride; kp.cv_pad = conv->pad; kp.cv_oh = conv_oh; kp.cv_ow = conv_ow;
+        kp.cv_vec = ((conv->c % 16) == 0 && ((uintptr_t)A % 16) == 0) ? 1 : 0;
+        kp.cv_magic_c = (((uint64_t)1 << 40) + (uint64_t)conv->c - 1) / (uint64_t)conv->c;
+        kp.cv_magic_kw = (((uint64_t)1 << 40) + (uint64_t)conv->kw - 1) / (uint64_t)conv->kw;
+        la = lb;
+    }
     kp.ld_align = (la < lb ? la : lb);
     if ((stride_a % 16) != 0 || (stride_b % 16) != 0) kp.ld_align = 1;
     const bool c_ok = (!C || ((uintptr_t)C % 16) == 0) && (stride_c % 4) == 0;
@@ -1195,6 +1262,41 @@ int lba_gemm_bwd_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_m
                     lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream) {
     if (order == LBA_ORDER_CHUNK16) return LBA_ERR_UNSUPPORTED;
     return run_in(A, B, C, of_mask, uf_mask, M, N, K, fmt_a, fmt_b, qprod, qacc, order, 1, hip_stream);
+}
+
+int lba_conv2d_out_shape(lba_conv2d_desc d, int32_t* oh, int32_t* ow) {
+    if (d.n < 1 || d.h < 1 || d.w < 1 || d.c < 1 || d.kh < 1 || d.kw < 1 || d.stride < 1 || d.pad < 0) return LBA_ERR_SHAPE;
+    if (d.c >= (1 << 14) || d.kw >= (1 << 14) || d.kh >= (1 << 14)) return LBA_ERR_SHAPE;
+    if ((int64_t)d.kh * d.kw * d.c >= ((int64_t)1 << 24)) return LBA_ERR_SHAPE;
+    const int64_t eh = (int64_t)d.h + 2 * (int64_t)d.pad - d.kh, ew = (int64_t)d.w + 2 * (int64_t)d.pad - d.kw;
+    if (eh < 0 || ew < 0) return LBA_ERR_SHAPE;
+    const int64_t o_h = eh / d.stride + 1, o_w = ew / d.stride + 1;
+    if ((int64_t)d.n * o_h * o_w > (int64_t)2147483647 - 63) return LBA_ERR_SHAPE;
+    if (oh) *oh = (int32_t)o_h;
+    if (ow) *ow = (int32_t)o_w;
+    return LBA_OK;
+}
+
+static int run_conv(const uint8_t* X, const uint8_t* W, float* Y, uint32_t* of_mask, uint32_t* uf_mask,
+                    const lba_conv2d_desc& d, int64_t cout, lba_qfmt qprod, lba_qfmt qacc, int32_t order, int events,
+                    void* hip_stream) {
+    int32_t oh = 0, ow = 0;
+    const int rc = lba_conv2d_out_shape(d, &oh, &ow);
+    if (rc != LBA_OK) return rc;
+    return lba::run(X, W, Y, of_mask, uf_mask, (int64_t)d.n * oh * ow, cout, (int64_t)d.kh * d.kw * d.c, qprod, qacc,
+                    order, events, hip_stream, 1, 0, 0, 0, nullptr, nullptr, nullptr, &d, oh, ow);
+}
+
+int lba_conv2d(const uint8_t* X, const uint8_t* W, float* Y, lba_conv2d_desc desc, int64_t cout,
+               lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream) {
+    return run_conv(X, W, Y, nullptr, nullptr, desc, cout, qprod, qacc, order, 0, hip_stream);
+}
+
+int lba_conv2d_bwd(const uint8_t* X, const uint8_t* W, float* Y, uint32_t* of_mask, uint32_t* uf_mask,
+                   lba_conv2d_desc desc, int64_t cout, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
+                   void* hip_stream) {
+    if (order == LBA_ORDER_CHUNK16) return LBA_ERR_UNSUPPORTED;
+    return run_conv(X, W, Y, of_mask, uf_mask, desc, cout, qprod, qacc, order, 1, hip_stream);
 }
 
 int lba_gemm_batched(const uint8_t* A, const uint8_t* B, float* C, int64_t batch,

@@ -499,6 +499,31 @@ def test_input_code_formats(ref):
         ref.gemm_in(A, B, ref.InFmt(3, 4, 40), ref.InFmt(3, 4, 3), ref.QFmt(5, 7, 15, 0), ref.QFmt(4, 7, 7, 0))
 
 
+def test_im2col_against_the_definition(ref):
+    """The written-out convolution operand, element by element from the definition of a padded, strided window,
+    and against torch's unfold (channel-major there, so the taps are compared after a transpose)."""
+    import torch
+    rng = np.random.default_rng(31)
+    for (n, h, w, c, kh, kw, stride, pad) in [(2, 4, 5, 3, 3, 3, 2, 1), (1, 6, 6, 2, 1, 1, 2, 0), (2, 5, 7, 4, 3, 2, 1, 2)]:
+        X = rng.integers(0, 256, (n, h, w, c)).astype(np.uint8)
+        A = ref.im2col_nhwc(X, kh, kw, stride, pad)
+        oh = (h + 2 * pad - kh) // stride + 1
+        ow = (w + 2 * pad - kw) // stride + 1
+        assert A.shape == (n * oh * ow, kh * kw * c)
+        for m in range(A.shape[0]):
+            img, rem = divmod(m, oh * ow)
+            y, x = divmod(rem, ow)
+            for i in range(kh):
+                for j in range(kw):
+                    ih, iw = y * stride - pad + i, x * stride - pad + j
+                    inside = 0 <= ih < h and 0 <= iw < w
+                    for ch in range(c):
+                        assert A[m, (i * kw + j) * c + ch] == (X[img, ih, iw, ch] if inside else 0)
+        U = torch.nn.functional.unfold(torch.from_numpy(X).permute(0, 3, 1, 2).float(), (kh, kw), padding=pad, stride=stride)
+        U = U.reshape(n, c, kh * kw, oh * ow).permute(0, 3, 2, 1).reshape(n * oh * ow, kh * kw * c)     # (c, tap) -> (tap, c)
+        assert np.array_equal(U.numpy().astype(np.uint8), A)
+
+
 def test_oracle_rejects_bad_arguments(ref):
     A = np.zeros((2, 4), dtype=np.uint8)
     good = ref.QFmt(4, 7, 7, 0)
