@@ -72,6 +72,8 @@ def main():
                     help="accumulator format with b = 2^(E-1)-1 instead of the 12-bit M7E4 (format sweeps)")
     ap.add_argument("--in-fmt", default=None, metavar="E,M",
                     help="operands in that 8-bit format with per-tensor flex bias (3,4 = the paper's M4E3) through lba_gemm_in")
+    ap.add_argument("--implicit", action="store_true",
+                    help="resnet50 / conv workloads: convolutions straight from NHWC activation tensors (lba_conv2d)")
     ap.add_argument("--bwd", action="store_true",
                     help="time lba_gemm_bwd (forward chain + both event planes) instead of lba_gemm")
     ap.add_argument("--of-only", action="store_true", help="with --bwd: ask for the overflow plane only")
@@ -105,7 +107,9 @@ def main():
     in_fmt = tuple(int(v) for v in args.in_fmt.split(",")) if args.in_fmt else None
     if in_fmt and (args.bwd or args.grad):
         raise SystemExit("bench.py: --in-fmt times the forward call only")
-    layers = inputs.make_workload(args.workload, dev, in_fmt=in_fmt)
+    if args.implicit and (in_fmt or args.bwd or args.grad):
+        raise SystemExit("bench.py: --implicit times the forward call on E4M3 operands only")
+    layers = inputs.make_conv_workload(args.workload, dev) if args.implicit else inputs.make_workload(args.workload, dev, in_fmt=in_fmt)
     cmax = max(l["M"] * l["N"] for l in layers)
     Cbuf = torch.empty(cmax, dtype=torch.float32, device=dev)
     for l in layers:
@@ -177,7 +181,12 @@ def main():
         stream0 = torch.cuda.current_stream().cuda_stream
 
         def launch(l):
-            if in_fmt:
+            if args.implicit:
+                rc = lb.lba_conv2d(l["X"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), l["desc"], l["cout"],
+                                   l["qp"], l["qa"], order, stream0)
+                if rc != 0:
+                    raise RuntimeError(lb.lba_strerror(rc))
+            elif in_fmt:
                 rc = lb.lba_gemm_in(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), l["M"], l["N"], l["K"],
                                     l["fa"], l["fb"], l["qp"], l["qa"], order, stream0)
                 if rc != 0:
@@ -269,10 +278,11 @@ def main():
                                 "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}[args.workload],
                    "macs_per_step": total_macs, "qprod": "M7E5 b=15", "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
                    "call": ("lba_grad, %s estimator: dX and dW (2 masked MACs per forward MAC)" % args.grad) if args.grad else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else ("lba_gemm_bwd (C + OF plane)" if args.of_only else "lba_gemm_bwd (C + OF and UF planes)")) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
+                   "conv": "implicit im2col from NHWC activations (lba_conv2d)" if args.implicit else "operand A is the written-out im2col matrix",
                    "operands": ("E%dM%d codes with per-tensor flex bias (lba_gemm_in)" % in_fmt) if in_fmt else "E4M3"},
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline and not args.grad:
+    if not args.no_cpu_baseline and not args.grad and not args.implicit:
         # a mid-sized layer whose output is still in the shared buffer: recompute it last
         pick = max(range(len(layers)), key=lambda i: (layers[i]["K"] == 576, layers[i]["M"]))
         l = layers[pick]

@@ -206,10 +206,62 @@ def resnet50_gemms(batch=64, image=224):
     return layers
 
 
+def resnet50_convs(batch=64, image=224):
+    """The same layers as resnet50_gemms, in the same order, as convolution descriptors
+    (name, n, h, w, c, cout, kh, kw, stride, pad) on NHWC activations; the FC layer is a 1x1 convolution
+    on a 1x1 image."""
+    layers = []
+    layers.append(("conv1", batch, image, image, 3, 64, 7, 7, 2, 3))
+    h = image // 4                                # after conv1 / 2 and maxpool / 2
+    inplanes = 64
+    for si, (planes, blocks, stride) in enumerate(((64, 3, 1), (128, 4, 2), (256, 6, 2), (512, 3, 2))):
+        for bi in range(blocks):
+            s = stride if bi == 0 else 1
+            name = "layer%d.%d" % (si + 1, bi)
+            layers.append((name + ".conv1", batch, h, h, inplanes, planes, 1, 1, 1, 0))
+            layers.append((name + ".conv2", batch, h, h, planes, planes, 3, 3, s, 1))
+            ho = h // s
+            layers.append((name + ".conv3", batch, ho, ho, planes, planes * 4, 1, 1, 1, 0))
+            if bi == 0:
+                layers.append((name + ".downsample", batch, h, h, inplanes, planes * 4, 1, 1, s, 0))
+            inplanes = planes * 4
+            h = ho
+    layers.append(("fc", batch, 1, 1, 2048, 1000, 1, 1, 1, 0))
+    return layers
+
+
 def bert_base_gemms(batch=32, seq=128):
     m = batch * seq
     return [("qkv", m, 2304, 768), ("attn_out", m, 768, 768),
             ("ffn_in", m, 3072, 768), ("ffn_out", m, 768, 3072)]
+
+
+def make_conv_workload(name, device="cpu"):
+    """'resnet50' or 'conv' as convolutions on NHWC activation tensors (for lba_conv2d): a list of dicts
+    (name, desc = (n, h, w, c, kh, kw, stride, pad), cout, M, N, K, X [n, h, w, c], B [cout, kh*kw*c], ta, tb).
+    Value distributions as in make_workload; layers of equal tensor shape share data."""
+    if name == "resnet50":
+        convs, seed = resnet50_convs(64, 224), 2
+    elif name == "conv":
+        convs, seed = [("resnet18.layer1.conv", 32, 56, 56, 64, 64, 3, 3, 1, 1)], 1
+    else:
+        raise ValueError("no convolution form of workload %r" % name)
+    cache_x, cache_b, out = {}, {}, []
+    for (lname, n, h, w, c, cout, kh, kw, stride, pad) in convs:
+        K = kh * kw * c
+        oh, ow = (h + 2 * pad - kh) // stride + 1, (w + 2 * pad - kw) // stride + 1
+        if (n, h, w, c) not in cache_x:
+            kind = "normal" if lname == "conv1" else "relu"
+            X, ta = make_operand(kind, n * h * w, c, seed, 2 * len(cache_x), device=device)
+            cache_x[(n, h, w, c)] = (X.view(n, h, w, c), ta)
+        if (cout, K) not in cache_b:
+            cache_b[(cout, K)] = make_operand("normal", cout, K, seed, 2 * len(cache_b) + 1, device=device,
+                                              std=(2.0 / K) ** 0.5)
+        X, ta = cache_x[(n, h, w, c)]
+        B, tb = cache_b[(cout, K)]
+        out.append(dict(name=lname, desc=(n, h, w, c, kh, kw, stride, pad), cout=cout, M=n * oh * ow, N=cout, K=K,
+                        X=X, A=X, B=B, ta=ta, tb=tb))
+    return out
 
 
 def make_workload(name, device="cpu", in_fmt=None):

@@ -45,5 +45,10 @@ def test_layer_lists():
     assert len(l) == 54 and sum(M * N * K for _, M, N, K in l) == 261707792384
     assert min(K for _, _, _, K in l) == 64 and max(K for _, _, _, K in l) == 4608
     assert [s[1:] for s in inputs.bert_base_gemms()] == [(4096, 2304, 768), (4096, 768, 768), (4096, 3072, 768), (4096, 768, 3072)]
+    convs = inputs.resnet50_convs()
+    assert len(convs) == 54
+    for (_, M, N, K), (_, n, h, w_, c, cout, kh, kw, s_, p_) in zip(l, convs):
+        oh, ow = (h + 2 * p_ - kh) // s_ + 1, (w_ + 2 * p_ - kw) // s_ + 1
+        assert (M, N, K) == (n * oh * ow, cout, kh * kw * c)
     w = inputs.make_workload("config1")
     assert w[0]["A"].shape == (64, 256) and w[0]["ta"] == 0 and int(w[0]["A"].max()) >= 0x7E - 0x08
