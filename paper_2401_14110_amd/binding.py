@@ -9,7 +9,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIBPATH = os.path.join(_HERE, "liblba_hip.so")
+# LBA_HIP_LIB names another build of the same library (A/B measurements); the default is the in-tree one
+_LIBPATH = os.environ.get("LBA_HIP_LIB") or os.path.join(_HERE, "liblba_hip.so")
 
 ROUND_FLOOR, ROUND_RNE = 0, 1
 STE_IDENTITY, STE_IMMEDIATE_OF, STE_RECURSIVE_OF, STE_COEF_PLANE = 0, 1, 2, 3

@@ -58,6 +58,7 @@ struct Plan {
     int tm, tn, bk;          // outputs per lane (tm x tn), k-depth of a tile; tile = 16tm x 16tn
     int grid_x, grid_y;
     int valu_per_mac_x100;
+    int amode;               // 1: A is read as im2col rows and / or an operand is not E4M3 (4 x 4 lane block only)
     KParams kp;
 };
 
@@ -79,7 +80,7 @@ int validate_fmt(const lba_qfmt& q);
 
 // Builds the plan (pointers in kp are left null).  Returns an lba status code.
 int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qprod, const lba_qfmt& qacc,
-              int order, int events, Plan* out, int64_t batch = 1, const InSpec* in = nullptr);
+              int order, int events, Plan* out, int64_t batch = 1, const InSpec* in = nullptr, bool conv = false);
 
 // Gradient products: how many slices of the summation index s a launch of `blocks` workgroups (4 waves
 // of 16 rows each) is cut into so that the chip has enough waves, and the slice length (a multiple of 4).

@@ -500,7 +500,9 @@ __device__ __forceinline__ void fast_tile(float (&acc)[TM][TN], float (&top)[TM]
 #define LBA_FAST_MIN_WAVES 4        // waves per SIMD the register allocation must allow
 #endif
 
-template <int TM, int TN, int BK, int PM, int RND, int ORDER>
+// AMODE 0: A is a row-major matrix of E4M3 codes and so is B (the default; no other case costs it anything).
+// AMODE 1: A may be an activation tensor read as im2col rows and either operand may use another code format.
+template <int TM, int TN, int BK, int PM, int RND, int ORDER, int AMODE = 0>
 __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const KParams p) {
     static_assert(BK % 16 == 0, "chunk boundaries must fall on fixed positions of a k-tile");
     constexpr int BM = 16 * TM, BN = 16 * TN;
@@ -518,7 +520,7 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
 
     const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
     set_flush_f32();
-    set_denorm_f16();
+    if (AMODE) set_denorm_f16();
     if (RND == LBA_ROUND_FLOOR) set_round_zero();
 
     FastConst c;
@@ -536,10 +538,11 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
     uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
     const int ntiles = (p.K + BK - 1) / BK;                    // K > 0 here; division by a constant
 
-    fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
+    if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
+    else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
     fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
-    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, p.in_ea, p.in_ma, p.exp_a);
-    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, p.in_eb, p.in_mb, p.exp_b);
+    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
+    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
@@ -547,7 +550,8 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
         const float* Bs = As + BK * BM;
         const bool more = (t + 1) < ntiles;
         if (more) {
-            fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
+            if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
+            else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
             fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
         // (Chunked order: the test is on the second-level sums; a first-level sum starts from 0 and
@@ -575,8 +579,8 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
         }
         if (more) {
             float* Ad = smem + ((t + 1) & 1) * STAGE;
-            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, p.in_ea, p.in_ma, p.exp_a);
-            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, p.in_eb, p.in_mb, p.exp_b);
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
+            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
         }
         __syncthreads();
     }
@@ -662,7 +666,7 @@ __device__ __forceinline__ void store_event_words(uint32_t* of_plane, uint32_t* 
 // UF = false (no underflow plane asked for): the underflow tests are dropped, and under the sequential
 // order a k-tile that starts with every |S| of the wave below R_OF - BK * max|p| cannot overflow at all:
 // it runs the forward kernel's clamp-free tile and its OF words are zero.
-template <int PM, int ORDER, bool UF>
+template <int PM, int ORDER, bool UF, int AMODE = 0>
 __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_fast_bwd_kernel(const KParams p) {
     constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
     constexpr int STAGE = BK * (BM + BN);
@@ -679,7 +683,7 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
 
     const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
     set_flush_f32();
-    set_denorm_f16();
+    if (AMODE) set_denorm_f16();
     set_round_zero();
 
     // kc_up / up: the same product and accumulator moved up by 2^60, where neither can flush
@@ -704,10 +708,11 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
     uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
     const int ntiles = (p.K + BK - 1) / BK;
 
-    fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
+    if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
+    else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
     fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
-    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, p.in_ea, p.in_ma, p.exp_a);
-    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, p.in_eb, p.in_mb, p.exp_b);
+    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
+    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
@@ -715,7 +720,8 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
         const float* Bs = As + BK * BM;
         const bool more = (t + 1) < ntiles;
         if (more) {
-            fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
+            if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
+            else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
             fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
         bool quiet = false;                                    // no sum of this tile can reach R_OF
@@ -843,8 +849,8 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
         }
         if (more) {
             float* Ad = smem + ((t + 1) & 1) * STAGE;
-            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, p.in_ea, p.in_ma, p.exp_a);
-            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, p.in_eb, p.in_mb, p.exp_b);
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
+            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
         }
         __syncthreads();
     }
@@ -1082,11 +1088,11 @@ __global__ void lba_fill_zero_kernel(float* C, int64_t n) {
 #define LBA_FAST_BK 32              // k-depth of a tile of the fast kernel (a multiple of 16)
 #endif
 
-template <int TM, int TN, int ORDER>
+template <int TM, int TN, int ORDER, int AMODE = 0>
 static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
     const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
     const KParams& kp = pl.kp;
-#define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<TM, TN, LBA_FAST_BK, PM, RND, ORDER>), grid, block, 0, st, kp)
+#define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<TM, TN, LBA_FAST_BK, PM, RND, ORDER, AMODE>), grid, block, 0, st, kp)
     // the truncating product modes (operand formats whose products exceed Q_prod's mantissa) exist for
     // the 4 x 4 lane block only; the planner never asks for them with another
 #define LBA_LAUNCH_ROUNDING(RND)                                                        \
@@ -1099,7 +1105,7 @@ static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
     }
     if (pl.round == LBA_ROUND_FLOOR) {
         LBA_LAUNCH_ROUNDING(LBA_ROUND_FLOOR)
-    } else if (pl.kp.sh_a == 16) {                           // M = 7: rounding by the bfloat16 conversion
+    } else if (pl.kp.sh_a == 16 && AMODE == 0) {             // M = 7: rounding by the bfloat16 conversion
         LBA_LAUNCH_ROUNDING(RND_RNE_BF16)
     } else {
         LBA_LAUNCH_ROUNDING(LBA_ROUND_RNE)
@@ -1113,6 +1119,14 @@ static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
     if (pl.kernel == KERNEL_FAST && pl.events) {
         const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
         const bool uf = pl.kp.uf_mask != nullptr || pl.kp.uf_mask2 != nullptr;
+        if (pl.amode) {                                        // im2col rows / other operand formats: sequential order only
+#define LBA_BWD1(PM, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, LBA_ORDER_SEQ, UF, 1>), grid, block, 0, st, pl.kp)
+            if (pl.order != LBA_ORDER_SEQ) return hipErrorInvalidValue;
+            if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD1(PM_FLUSH, true); else LBA_BWD1(PM_FLUSH, false); }
+            else                          { if (uf) LBA_BWD1(PM_FLUSH_CLAMP, true); else LBA_BWD1(PM_FLUSH_CLAMP, false); }
+#undef LBA_BWD1
+            return hipGetLastError();
+        }
 #define LBA_BWD(PM, ORDER, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, ORDER, UF>), grid, block, 0, st, pl.kp)
         if (pl.order == LBA_ORDER_CHUNK16) {
             if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD(PM_FLUSH, LBA_ORDER_CHUNK16, true); else LBA_BWD(PM_FLUSH, LBA_ORDER_CHUNK16, false); }
@@ -1124,6 +1138,8 @@ static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
 #undef LBA_BWD
         return hipGetLastError();
     }
+    if (pl.kernel == KERNEL_FAST && pl.amode)                  // the planner keeps these on the 4 x 4 lane block
+        return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<4, 4, LBA_ORDER_CHUNK16, 1>(pl, st) : launch_fast<4, 4, LBA_ORDER_SEQ, 1>(pl, st);
     if (pl.kernel == KERNEL_FAST) {
         if (pl.tm == 2 && pl.tn == 2)
             return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<2, 2, LBA_ORDER_CHUNK16>(pl, st) : launch_fast<2, 2, LBA_ORDER_SEQ>(pl, st);
@@ -1163,7 +1179,7 @@ static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, 
                const lba_conv2d_desc* conv = nullptr, int conv_oh = 0, int conv_ow = 0) {
     Plan pl;
     if (batch < 0 || batch > 65535 || stride_a < 0 || stride_b < 0 || stride_c < 0) return LBA_ERR_SHAPE;
-    int rc = make_plan(M, N, K, qprod, qacc, order, events, &pl, batch, in);
+    int rc = make_plan(M, N, K, qprod, qacc, order, events, &pl, batch, in, conv != nullptr);
     if (rc != LBA_OK) return rc;
     if (in) pl.kp.out_exp -= in->delta;                        // the operand biases' power-of-two scale
     if (M == 0 || N == 0 || batch == 0) return LBA_OK;

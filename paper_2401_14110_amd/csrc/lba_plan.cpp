@@ -148,20 +148,20 @@ static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp, bool
 // with few outputs cannot keep two waves on every SIMD with 16 chains per lane: between 512 and 1024
 // workgroups 2 x 4 measured 3-6 % faster, and up to 64 workgroups (a latency-bound launch) 2 x 2 is
 // about twice as fast.  The choice never changes a result.
-static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int events, int prod_mode, int* tm, int* tn, int* bk) {
+static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int events, int prod_mode, int amode, int* tm, int* tn, int* bk) {
     *tm = 4; *tn = 4;
     *bk = (kernel == KERNEL_GEN || events) ? 32 : LBA_FAST_BK;
     if (kernel == KERNEL_FAST) {
         const int64_t blocks = ((M + 63) / 64) * ((N + 63) / 64) * (batch > 0 ? batch : 1);
         if (events) return;                                    // the recompute kernel is 4 x 4 only
-        if (prod_mode == PM_TRUNC || prod_mode == PM_TRUNC_CLAMP) return;   // built for 4 x 4 only
+        if (prod_mode == PM_TRUNC || prod_mode == PM_TRUNC_CLAMP || amode) return;   // built for 4 x 4 only
         if (blocks <= 64) { *tm = 2; *tn = 2; }
         else if (blocks > 512 && blocks <= 1024) *tm = 2;
     }
 }
 
 int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_qfmt& qa_in,
-              int order, int events, Plan* out, int64_t batch, const InSpec* in_spec) {
+              int order, int events, Plan* out, int64_t batch, const InSpec* in_spec, bool conv) {
     const InSpec& in = in_spec ? *in_spec : e4m3_spec();
     int rc = validate_shapes(M, N, K);
     if (rc != LBA_OK) return rc;
@@ -243,7 +243,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         kp.prod_rne = (qp.round == LBA_ROUND_RNE) ? 1 : 0;
         p.valu_per_mac_x100 = 0;                           // filled by the launcher's table
     }
-    pick_tile(M, N, batch, p.kernel, p.events, p.prod_mode, &p.tm, &p.tn, &p.bk);
+    p.amode = (conv || in.ea != 4 || in.eb != 4) ? 1 : 0;
+    pick_tile(M, N, batch, p.kernel, p.events, p.prod_mode, p.amode, &p.tm, &p.tn, &p.bk);
     kp.batch = 1;
     kp.fast_thresh = -1.0f;
     kp.fast_thresh4 = -1.0f;
