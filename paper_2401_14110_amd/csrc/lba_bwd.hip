@@ -1,0 +1,28 @@
+// lba_bwd.hip -- instantiations of lba_fast_bwd_kernel (the recompute call in the scaled domain).
+#include "lba_device.h"
+#include "lba_launch.h"
+
+namespace lba {
+hipError_t launch_fast_bwd(const Plan& pl, hipStream_t st) {
+    const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
+    const bool uf = pl.kp.uf_mask != nullptr || pl.kp.uf_mask2 != nullptr;
+    if (pl.amode) {                                        // im2col rows / other operand formats: sequential order only
+#define LBA_BWD1(PM, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, LBA_ORDER_SEQ, UF, 1>), grid, block, 0, st, pl.kp)
+        if (pl.order != LBA_ORDER_SEQ) return hipErrorInvalidValue;
+        if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD1(PM_FLUSH, true); else LBA_BWD1(PM_FLUSH, false); }
+        else                          { if (uf) LBA_BWD1(PM_FLUSH_CLAMP, true); else LBA_BWD1(PM_FLUSH_CLAMP, false); }
+#undef LBA_BWD1
+        return hipGetLastError();
+    }
+#define LBA_BWD(PM, ORDER, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, ORDER, UF>), grid, block, 0, st, pl.kp)
+    if (pl.order == LBA_ORDER_CHUNK16) {
+        if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD(PM_FLUSH, LBA_ORDER_CHUNK16, true); else LBA_BWD(PM_FLUSH, LBA_ORDER_CHUNK16, false); }
+        else                          { if (uf) LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_CHUNK16, true); else LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_CHUNK16, false); }
+    } else {
+        if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD(PM_FLUSH, LBA_ORDER_SEQ, true); else LBA_BWD(PM_FLUSH, LBA_ORDER_SEQ, false); }
+        else                          { if (uf) LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_SEQ, true); else LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_SEQ, false); }
+    }
+#undef LBA_BWD
+    return hipGetLastError();
+}
+}  // namespace lba

@@ -1,1168 +1,27 @@
-// lba_kernels.hip -- gfx950 kernels and C ABI of the simulated low-bit-width-accumulator GEMM.
-//
-// One FMAq step is  S <- Q_acc(Q_prod(a*b) + S)  (arXiv 2401.14110, Sec. 3) with the quantizer of
-// Sec. 2.3; each output element C[m,n] is the K-long sequential chain of App. D.  The chain is a
-// strict dependency in k, so parallelism is over outputs only: every lane owns a TM x TN block of
-// independent chains held in registers, a 256-lane workgroup owns a (16 TM) x (16 TN) tile of C,
-// and k advances in lock-step through tiles of A and B staged in LDS.
-//
-// Data path per k-tile (depth BK):
-//   global: each lane fetches 16 contiguous bytes (one row, 16 k) of A and/or B   [coalescing is
-//           irrelevant here: < 0.1 byte per MAC]
-//   decode: byte -> FP32 through a 256-entry LDS table built once per workgroup; the table holds
-//           value(code) * 2^exp, so operands arrive pre-scaled into the kernel's domain
-//   LDS:    tiles are stored k-major ([k][row], row contiguous) so that a lane reads its 4 / 8
-//           operand values of one k with one / two 16-byte reads, without bank conflicts
-//   VALU:   TM*TN chains advance by one step; all FP32 ops are exact or a single rounding
-//           (see lba_plan.cpp for the argument)
-// Two LDS stages; the next tile's global loads are in flight while the current one is consumed.
-//
-// The wave's FP mode is changed with s_setreg (rounding mode) and the translation unit is built
-// with FP32 denormals flushed; no runtime integer division is used inside the kernels.
-
+// lba_kernels.hip -- host side of the HIP library: plan -> launch, and the C ABI of include/lba.h.
+// The device code is in lba_device.h; its instantiations are in lba_fast_*.hip, lba_bwd.hip, lba_gen.hip.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include "lba_internal.h"
+#include "lba_launch.h"
 
 namespace lba {
-
-// ---------------------------------------------------------------------------------------------
-// wave FP mode
-// ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void set_round_nearest() { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 0\n\ts_nop 1" ::: "memory"); }
-__device__ __forceinline__ void set_round_pinf()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 1\n\ts_nop 1" ::: "memory"); }
-__device__ __forceinline__ void set_round_ninf()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 2\n\ts_nop 1" ::: "memory"); }
-__device__ __forceinline__ void set_round_zero()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 3\n\ts_nop 1" ::: "memory"); }
-__device__ __forceinline__ void set_flush_f32()     { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 4, 2), 0\n\ts_nop 1" ::: "memory"); }
-
-// FP16 denormals on (MODE[7:6] = 3): the staging decodes 8-bit codes through an exact FP16 image
-__device__ __forceinline__ void set_denorm_f16()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 6, 2), 3\n\ts_nop 1" ::: "memory"); }
-
-__device__ __forceinline__ float med3(float x, float lo, float hi) { return __builtin_amdgcn_fmed3f(x, lo, hi); }
-
-// ---------------------------------------------------------------------------------------------
-// operand decode table: E4M3 code -> value * 2^e as an exact FP32 (Sec. "inputs" of lba.h)
-// ---------------------------------------------------------------------------------------------
-// (E exponent bits, M mantissa bits, bias 2^(E-1) - 1; E = 4, M = 3 is E4M3)
-__device__ __forceinline__ float decode_entry(int code, int e, int E, int M) {
-    const int ex = (code >> M) & ((1 << E) - 1), m = code & ((1 << M) - 1);
-    const int bias = (1 << (E - 1)) - 1;
-    const int sig = ex ? ((1 << M) + m) : m;
-    const int lsb = (ex ? ex : 1) - bias - M;
-    const float v = __builtin_ldexpf((float)sig, lsb + e);
-    return (code & 0x80) ? -v : v;
-}
-
-// ---------------------------------------------------------------------------------------------
-// FMAq step policies
-// ---------------------------------------------------------------------------------------------
-// Mantissa rounding of an FP32 word to the top (23 - sh) mantissa bits, nearest-even, for a word
-// that is already the exact value or a harmless first rounding of it.
-__device__ __forceinline__ uint32_t rne_bits(uint32_t u, uint32_t half, int sh, uint32_t mask) {
-    return (u + half + ((u >> sh) & 1u)) & mask;
-}
-
-// Internal rounding code of the fast kernel: nearest-even to 8 significant bits (M = 7) done by
-// the hardware float -> bfloat16 conversion, whose packed result with a zero low half is the FP32
-// word of the rounded value.  Same function as the bfe/add3/and sequence, in one instruction.
-enum { RND_RNE_BF16 = 2 };
-
-__device__ __forceinline__ float rne_to_8_bits(float t) {
-    typedef float v2f __attribute__((ext_vector_type(2)));
-    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
-    const v2f v = {0.0f, t};
-    return __uint_as_float(__builtin_bit_cast(uint32_t, __builtin_convertvector(v, v2bf)));
-}
-
-// Per-wave constants of the fast kernel, forced into vector registers: on gfx950 the simple
-// FP32 / bitwise VALU ops issue at twice the rate when all their operands are VGPRs.
-struct FastConst {
-    float kc, rof, rofp;
-    uint32_t mask, half, maskp;
-    int sh;
-};
-
-// One k-step for a GROUP of NCH independent chains, written phase by phase (all products, then
-// all adds, then all roundings) so that consecutive instructions never depend on each other.
-// CLAMP = false is used for k-tiles in which no chain can reach R_OF (see lba_fast_kernel).
-template <int PM, int RND, bool CLAMP, int I0, int NI, int TM, int NJ>
-__device__ __forceinline__ void fast_group(float (&accf)[TM][NJ], const float (&af)[TM], const float (&b)[NJ],
-                                           const FastConst& c) {
-    float (*acc)[NJ] = &accf[I0];
-    const float* a = &af[I0];
-    if (PM == PM_IDENT) {
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_fmaf(a[i], b[j], acc[i][j]);
-    } else {
-        float q[NI][NJ];
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) q[i][j] = a[i] * b[j];        // exact; flushed below Q_prod's R_UF
-        __builtin_amdgcn_sched_barrier(0);
-        if (PM == PM_TRUNC || PM == PM_TRUNC_CLAMP) {                   // Q_prod's mantissa, by truncation
-#pragma unroll
-            for (int i = 0; i < NI; ++i)
-#pragma unroll
-                for (int j = 0; j < NJ; ++j) q[i][j] = __uint_as_float(__float_as_uint(q[i][j]) & c.maskp);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if (PM == PM_FLUSH_CLAMP || PM == PM_TRUNC_CLAMP) {
-#pragma unroll
-            for (int i = 0; i < NI; ++i)
-#pragma unroll
-                for (int j = 0; j < NJ; ++j) q[i][j] = med3(q[i][j], -c.rofp, c.rofp);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_fmaf(q[i][j], c.kc, acc[i][j]);   // one rounding of the exact sum
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    if (RND == RND_RNE_BF16) {
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) acc[i][j] = rne_to_8_bits(acc[i][j]);
-    } else {
-        if (RND == LBA_ROUND_RNE) {
-            uint32_t l[NI][NJ];
-#pragma unroll
-            for (int i = 0; i < NI; ++i)
-#pragma unroll
-                for (int j = 0; j < NJ; ++j) l[i][j] = (__float_as_uint(acc[i][j]) >> c.sh) & 1u;
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < NI; ++i)
-#pragma unroll
-                for (int j = 0; j < NJ; ++j) acc[i][j] = __uint_as_float(__float_as_uint(acc[i][j]) + c.half + l[i][j]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) acc[i][j] = __uint_as_float(__float_as_uint(acc[i][j]) & c.mask);
-    }
-    if (CLAMP) {
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) acc[i][j] = med3(acc[i][j], -c.rof, c.rof);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-}
-
-// General step: plain domain, every sub-step explicit.  EVENTS adds the two event bits.
-struct GenOut { float S; uint32_t of; uint32_t uf; };
-
-template <int RND>
-__device__ __forceinline__ float gen_product(float a, float b, const KParams& p, uint32_t* uf1) {
-    float pr = a * b;                                          // exact
-    uint32_t u = __float_as_uint(pr);
-    if (p.prod_round) {
-        if (p.prod_rne) u = rne_bits(u, p.half_p, p.sh_p, p.mask_p);   // input exact: one rounding
-        else u &= p.mask_p;
-    }
-    float q = __uint_as_float(u);
-    const bool fl = __builtin_fabsf(pr) < p.ruf_p;             // decided on the un-rounded product
-    *uf1 = (fl && pr != 0.0f) ? 1u : 0u;
-    q = fl ? 0.0f : q;
-    return med3(q, -p.rof_p, p.rof_p);
-}
-
-// Accumulator quantizer from the truncated sum's word uz (sign-magnitude, exact decisions) and
-// the sticky bit.
-__device__ __forceinline__ float gen_acc_rne(uint32_t uz, uint32_t sticky, const KParams& p,
-                                             uint32_t* of, bool* small) {
-    const uint32_t mag = uz & 0x7FFFFFFFu;
-    const uint32_t sign = uz & 0x80000000u;
-    const uint32_t rofb = __float_as_uint(p.rof_a), rufb = __float_as_uint(p.ruf_a);
-    *of = mag >= rofb ? 1u : 0u;
-    *small = mag < rufb;
-    const int s1 = p.sh_a + 1;
-    uint32_t w = (mag << 1) | sticky;                          // one more bit of precision
-    const uint32_t lowmask = (1u << s1) - 1u;
-    w = (w + (lowmask >> 1) + ((w >> s1) & 1u)) & ~lowmask;
-    uint32_t r = sign | (w >> 1);
-    r = *of ? (sign | rofb) : r;
-    r = *small ? 0u : r;
-    return __uint_as_float(r);
-}
-
-// ---------------------------------------------------------------------------------------------
-// tile kernel
-// ---------------------------------------------------------------------------------------------
-template <int ROWS, int BK>
-struct Stage {
-    static constexpr int kChunks = ROWS * BK / 16;                         // 16-byte pieces per tile
-    static constexpr int kPerLane = (kChunks + 255) / 256;
-    static constexpr int kRowShift = ROWS == 16 ? 4 : ROWS == 32 ? 5 : ROWS == 64 ? 6 : ROWS == 128 ? 7 : 8;
-    static_assert((1 << kRowShift) == ROWS, "tile rows must be a power of two");
-    // lanes that take B's pieces: the highest-numbered ones, so that A and B share the work
-    static constexpr int kTailShift = kChunks < 256 ? 256 - kChunks : 0;
-};
-
-// Fetch this lane's 16-byte pieces of one operand tile into registers (zero outside the matrix).
-// ld_align == 16: every piece is 16-byte aligned and wholly inside its row (K % 16 == 0).
-// Otherwise: five 4-byte-aligned loads cover the piece at any byte offset and are funnel-shifted
-// into place.  Each load address is clamped to the aligned word holding the last valid byte, so
-// every word read contains at least one byte of the matrix (it cannot cross into another page).
-template <int ROWS, int BK>
-__device__ __forceinline__ void fetch_tile(const uint8_t* __restrict__ G, int rows, int K, int r0, int k0,
-                                           int ld_align, int tid, uint4 (&regs)[Stage<ROWS, BK>::kPerLane]) {
-#pragma unroll
-    for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
-        const int c = tid + i * 256;
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
-            const int row = c & (ROWS - 1);
-            const int kq = c >> Stage<ROWS, BK>::kRowShift;                 // ROWS is a power of two
-            const int r = r0 + row, k = k0 + kq * 16;
-            if (r < rows && k < K) {
-                const uint8_t* src = G + (int64_t)r * K + k;
-                if (ld_align == 16) {
-                    v = *reinterpret_cast<const uint4*>(src);
-                } else {
-                    const int nvalid = (K - k) < 16 ? (K - k) : 16;         // bytes of this piece inside the row
-                    const uintptr_t a0 = reinterpret_cast<uintptr_t>(src);
-                    const uintptr_t first = a0 & ~(uintptr_t)3;
-                    const uintptr_t last = (a0 + (uintptr_t)(nvalid - 1)) & ~(uintptr_t)3;
-                    uint32_t d[5];
-#pragma unroll
-                    for (int j = 0; j < 5; ++j) {
-                        uintptr_t a = first + 4u * j;
-                        a = a < last ? a : last;
-                        d[j] = *reinterpret_cast<const uint32_t*>(a);
-                    }
-                    const uint32_t sh = (uint32_t)(a0 & 3u) * 8u;
-                    uint32_t w[4];
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) {
-                        w[j] = __builtin_amdgcn_alignbit(d[j + 1], d[j], sh);   // ({d[j+1], d[j]} >> sh)[31:0]
-                        const int nb = nvalid - 4 * j;                      // valid bytes in this word
-                        const uint32_t keep = nb >= 4 ? 0xFFFFFFFFu : (nb <= 0 ? 0u : ((1u << (8 * nb)) - 1u));
-                        w[j] &= keep;
-                    }
-                    v = make_uint4(w[0], w[1], w[2], w[3]);
-                }
-            }
-        }
-        regs[i] = v;
-    }
-}
-
-// Implicit im2col: the same pieces gathered from an NHWC activation tensor.  Row r is output pixel
-// (n, oh, ow); byte k of the row is X[n, oh*stride - pad + kh, ow*stride - pad + kw, c] with
-// k = (kh * KW + kw) * C + c, or code 0 (the value +0) outside the image.  With C % 16 == 0 a 16-byte
-// piece lies inside one tap and is one aligned load; otherwise its bytes are gathered one by one.
-__device__ __forceinline__ uint32_t div_magic(uint32_t x, uint64_t magic) { return (uint32_t)(((uint64_t)x * magic) >> 40); }
-
-template <int ROWS, int BK>
-__device__ __forceinline__ void fetch_tile_conv(const uint8_t* __restrict__ X, const KParams& p, int r0, int k0,
-                                                int tid, uint4 (&regs)[Stage<ROWS, BK>::kPerLane]) {
-#pragma unroll
-    for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
-        const int c = tid + i * 256;
-        uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
-            const int row = c & (ROWS - 1);
-            const int kq = c >> Stage<ROWS, BK>::kRowShift;
-            const int r = r0 + row, k = k0 + kq * 16;
-            if (r < p.M && k < p.K) {
-                const int ow = r % p.cv_ow, t = r / p.cv_ow;            // the lane's row never changes: hoisted
-                const int oh = t % p.cv_oh, n = t / p.cv_oh;
-                const int ih0 = oh * p.cv_stride - p.cv_pad, iw0 = ow * p.cv_stride - p.cv_pad;
-                const int64_t img = (int64_t)n * p.cv_h;
-                if (p.cv_vec) {
-                    const int tap = (int)div_magic((uint32_t)k, p.cv_magic_c), ch = k - tap * p.cv_c;
-                    const int kh = (int)div_magic((uint32_t)tap, p.cv_magic_kw), kw = tap - kh * p.cv_kw;
-                    const int ih = ih0 + kh, iw = iw0 + kw;
-                    if (ih >= 0 && ih < p.cv_h && iw >= 0 && iw < p.cv_w)
-                        v = *reinterpret_cast<const uint4*>(X + ((img + ih) * p.cv_w + iw) * p.cv_c + ch);
-                } else {
-                    uint32_t w[4] = {0u, 0u, 0u, 0u};
-                    for (int j = 0; j < 16; ++j) {
-                        const int kk = k + j;
-                        if (kk < p.K) {
-                            const int tap = (int)div_magic((uint32_t)kk, p.cv_magic_c), ch = kk - tap * p.cv_c;
-                            const int kh = (int)div_magic((uint32_t)tap, p.cv_magic_kw), kw = tap - kh * p.cv_kw;
-                            const int ih = ih0 + kh, iw = iw0 + kw;
-                            if (ih >= 0 && ih < p.cv_h && iw >= 0 && iw < p.cv_w)
-                                w[j >> 2] |= (uint32_t)X[((img + ih) * p.cv_w + iw) * p.cv_c + ch] << (8 * (j & 3));
-                        }
-                    }
-                    v = make_uint4(w[0], w[1], w[2], w[3]);
-                }
-            }
-        }
-        regs[i] = v;
-    }
-}
-
-// A's pieces: a row-major matrix, or an activation tensor read as im2col rows.
-template <int ROWS, int BK>
-__device__ __forceinline__ void fetch_tile_a(const uint8_t* __restrict__ A, const KParams& p, int r0, int k0,
-                                             int tid, uint4 (&regs)[Stage<ROWS, BK>::kPerLane]) {
-    if (p.conv) fetch_tile_conv<ROWS, BK>(A, p, r0, k0, tid, regs);     // uniform
-    else        fetch_tile<ROWS, BK>(A, p.M, p.K, r0, k0, p.ld_align, tid, regs);
-}
-
-// Decode the fetched pieces through the table and store them k-major into one LDS stage.
-template <int ROWS, int BK>
-__device__ __forceinline__ void store_tile(float* __restrict__ dst /* [BK][ROWS] */, const float* __restrict__ lut,
-                                           int tid, const uint4 (&regs)[Stage<ROWS, BK>::kPerLane]) {
-#pragma unroll
-    for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
-        const int c = tid + i * 256;
-        if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
-            const int row = c & (ROWS - 1);
-            const int kq = c >> Stage<ROWS, BK>::kRowShift;
-            const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
-#pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const uint32_t code = (w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
-                dst[(kq * 16 + j) * ROWS + row] = lut[code];
-            }
-        }
-    }
-}
-
-// Same, decoding with the hardware FP8 conversion (gfx950 decodes OCP E4M3) and one exact
-// multiply by the power-of-two scale.  The two NaN codes, which the conversion would turn into NaN,
-// are patched to +-480 * scale on a rarely taken path so that every code has a defined value.
-// Codes of another format with E < 4 go through FP16: sign | (e << 10) | (m << (10 - M)) is the FP16 number
-// value(code) * 2^(bias - 15), subnormals included, so the hardware FP16 -> FP32 conversion and one exact
-// multiply by 2^(15 - bias + scale_exp) decode it.  E = 5 would put e = 31 on FP16's inf / NaN codes and is
-// decoded arithmetically (integer significand times a power of two).
-template <int ROWS, int BK>
-__device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][ROWS] */, float scale,
-                                               int tid, const uint4 (&regs)[Stage<ROWS, BK>::kPerLane],
-                                               int E = 4, int M = 3, int scale_exp = 0) {
-    typedef float v2f __attribute__((ext_vector_type(2)));
-    if (E != 4) {                                              // uniform
-#pragma unroll
-        for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
-            const int c = tid + i * 256;
-            if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
-                const int row = c & (ROWS - 1);
-                const int kq = c >> Stage<ROWS, BK>::kRowShift;
-                const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
-                const float sc16 = __builtin_ldexpf(1.0f, 15 - ((1 << (E - 1)) - 1) + scale_exp);
-                const int up = 10 - M;
-                if (E < 4) {
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        const uint32_t code = (w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
-                        const uint16_t h = (uint16_t)(((code & 0x80u) << 8) | ((code & 0x7Fu) << up));
-                        dst[(kq * 16 + j) * ROWS + row] = (float)__builtin_bit_cast(_Float16, h) * sc16;
-                    }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 16; ++j) {
-                        const int code = (int)((w[j >> 2] >> (8 * (j & 3))) & 0xFFu);
-                        dst[(kq * 16 + j) * ROWS + row] = decode_entry(code, scale_exp, E, M);
-                    }
-                }
-            }
-        }
-        return;
-    }
-#pragma unroll
-    for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
-        const int c = tid + i * 256;
-        if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
-            const int row = c & (ROWS - 1);
-            const int kq = c >> Stage<ROWS, BK>::kRowShift;
-            const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
-            float f[16];
-            uint32_t nan_any = 0u;
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[d], false);
-                const v2f hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[d], true);
-                f[4 * d + 0] = lo.x * scale; f[4 * d + 1] = lo.y * scale;
-                f[4 * d + 2] = hi.x * scale; f[4 * d + 3] = hi.y * scale;
-                nan_any |= ((w[d] & 0x7F7F7F7Fu) + 0x01010101u) & 0x80808080u;   // a byte with low 7 bits all set
-            }
-            if (nan_any) {
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const uint32_t code = (w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
-                    if ((code & 0x7Fu) == 0x7Fu) f[j] = (code & 0x80u) ? -480.0f * scale : 480.0f * scale;
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 16; ++j) dst[(kq * 16 + j) * ROWS + row] = f[j];
-        }
-    }
-}
-
-// Reads the TM + TN operand values of one k from an LDS stage (TM, TN in {2, 4}): the lane's
-// rows ty*TM .. and columns tx*TN .. are contiguous in the k-major tiles.
-template <int TM, int TN, int BM, int BN>
-__device__ __forceinline__ void read_operands(const float* As, const float* Bs, int k, int tx, int ty,
-                                              float (&a)[TM], float (&b)[TN]) {
-    static_assert((TM == 2 || TM == 4) && (TN == 2 || TN == 4), "lane block");
-    if (TM == 4) {
-        const float4 v = *reinterpret_cast<const float4*>(As + k * BM + ty * 4);
-        a[0] = v.x; a[1] = v.y; a[TM - 2] = v.z; a[TM - 1] = v.w;
-    } else {
-        const float2 v = *reinterpret_cast<const float2*>(As + k * BM + ty * 2);
-        a[0] = v.x; a[1] = v.y;
-    }
-    if (TN == 4) {
-        const float4 w = *reinterpret_cast<const float4*>(Bs + k * BN + tx * 4);
-        b[0] = w.x; b[1] = w.y; b[TN - 2] = w.z; b[TN - 1] = w.w;
-    } else {
-        const float2 w = *reinterpret_cast<const float2*>(Bs + k * BN + tx * 2);
-        b[0] = w.x; b[1] = w.y;
-    }
-}
-
-// Second level of the chunked order (Sec. 3, Fig. 1 right): T <- Q_acc(T + S), then S <- 0,
-// for all chains of the lane, phase by phase.  T and S are both values of Q_acc's grid, so the
-// same one-rounding argument as for a product step applies.
-template <int RND, bool CLAMP, int TM, int TN>
-__device__ __forceinline__ void fast_level2(float (&top)[TM][TN], float (&acc)[TM][TN], const FastConst& c) {
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) top[i][j] = top[i][j] + acc[i][j];
-    __builtin_amdgcn_sched_barrier(0);
-    if (RND == RND_RNE_BF16) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) { top[i][j] = rne_to_8_bits(top[i][j]); acc[i][j] = 0.0f; }
-    } else {
-        if (RND == LBA_ROUND_RNE) {
-            uint32_t l[TM][TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) l[i][j] = (__float_as_uint(top[i][j]) >> c.sh) & 1u;
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) top[i][j] = __uint_as_float(__float_as_uint(top[i][j]) + c.half + l[i][j]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                top[i][j] = __uint_as_float(__float_as_uint(top[i][j]) & c.mask);
-                acc[i][j] = 0.0f;
-            }
-    }
-    if (CLAMP) {
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) top[i][j] = med3(top[i][j], -c.rof, c.rof);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-}
-
-// All chains of the lane advance by one k.
-template <int PM, int RND, bool CLAMP, int TM, int TN>
-__device__ __forceinline__ void fast_kstep(float (&acc)[TM][TN], const float (&a)[TM], const float (&b)[TN],
-                                           const FastConst& c) {
-    fast_group<PM, RND, CLAMP, 0, TM, TM, TN>(acc, a, b, c);
-}
-
-// One k-tile from LDS, fully unrolled; operands are read one k ahead of their use.  With the
-// chunked order every 16th step is followed by the second-level step (tiles start at multiples
-// of 16, so chunk boundaries are compile-time positions).
-template <int PM, int RND, int ORDER, bool CLAMP, int TM, int TN, int BK, int BM, int BN>
-__device__ __forceinline__ void fast_tile(float (&acc)[TM][TN], float (&top)[TM][TN], const float* As, const float* Bs,
-                                          int tx, int ty, const FastConst& c) {
-    float a0[TM], b0[TN], a1[TM], b1[TN];
-    read_operands<TM, TN, BM, BN>(As, Bs, 0, tx, ty, a0, b0);
-#pragma unroll
-    for (int k = 0; k < BK; k += 2) {
-        read_operands<TM, TN, BM, BN>(As, Bs, k + 1, tx, ty, a1, b1);
-        fast_kstep<PM, RND, CLAMP, TM, TN>(acc, a0, b0, c);
-        if (k + 2 < BK) read_operands<TM, TN, BM, BN>(As, Bs, k + 2, tx, ty, a0, b0);
-        fast_kstep<PM, RND, CLAMP, TM, TN>(acc, a1, b1, c);
-        if (ORDER == LBA_ORDER_CHUNK16 && ((k + 2) & 15) == 0) fast_level2<RND, CLAMP, TM, TN>(top, acc, c);
-    }
-}
-
-#ifndef LBA_FAST_MIN_WAVES
-#define LBA_FAST_MIN_WAVES 4        // waves per SIMD the register allocation must allow
-#endif
-
-// AMODE 0: A is a row-major matrix of E4M3 codes and so is B (the default; no other case costs it anything).
-// AMODE 1: A may be an activation tensor read as im2col rows and either operand may use another code format.
-template <int TM, int TN, int BK, int PM, int RND, int ORDER, int AMODE = 0>
-__global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const KParams p) {
-    static_assert(BK % 16 == 0, "chunk boundaries must fall on fixed positions of a k-tile");
-    constexpr int BM = 16 * TM, BN = 16 * TN;
-    constexpr int STAGE = BK * (BM + BN);
-    __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
-
-    const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;
-    const int tidb = tid - Stage<BN, BK>::kTailShift;       // B's pieces go to the last lanes
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    // batch member blockIdx.z (strides are 0 for a single GEMM)
-    const uint8_t* pA = p.A + (int64_t)blockIdx.z * p.stride_a;
-    const uint8_t* pB = p.B + (int64_t)blockIdx.z * p.stride_b;
-    float* pC = p.C ? p.C + (int64_t)blockIdx.z * p.stride_c : nullptr;
-
-    const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
-    set_flush_f32();
-    if (AMODE) set_denorm_f16();
-    if (RND == LBA_ROUND_FLOOR) set_round_zero();
-
-    FastConst c;
-    c.kc = p.kc; c.rof = p.rof_a; c.rofp = p.rof_p; c.mask = p.mask_a; c.half = p.half_a; c.sh = p.sh_a; c.maskp = p.mask_p;
-    float thresh = p.fast_thresh, thresh4 = p.fast_thresh4;
-    int safe_tiles = 0;
-    asm volatile("" : "+v"(c.kc), "+v"(c.rof), "+v"(c.rofp), "+v"(c.mask), "+v"(c.half), "+v"(c.maskp), "+v"(thresh), "+v"(thresh4));
-
-    float acc[TM][TN], top[TM][TN];                            // top: second-level sums (chunked order only)
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) { acc[i][j] = 0.0f; top[i][j] = 0.0f; }
-
-    uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
-    const int ntiles = (p.K + BK - 1) / BK;                    // K > 0 here; division by a constant
-
-    if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
-    else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
-    fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
-    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
-    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
-    __syncthreads();
-
-    for (int t = 0; t < ntiles; ++t) {
-        const float* As = smem + (t & 1) * STAGE;
-        const float* Bs = As + BK * BM;
-        const bool more = (t + 1) < ntiles;
-        if (more) {
-            if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
-            else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
-            fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
-        }
-        // (Chunked order: the test is on the second-level sums; a first-level sum starts from 0 and
-        // is covered by the same bound.)
-        // If every chain of the wave starts a tile below R_OF - n * BK * max|p| (scaled down further
-        // for nearest-even), no sum inside the next n tiles can reach R_OF: the clamp is a no-op there
-        // and a clamp-free copy of the loop runs.  The test is per wave (uniform branch) and is made
-        // for n = 4 and n = 1; after a successful n = 4 test the next three tiles are not tested.
-        if (safe_tiles == 0) {
-            float mx = 0.0f;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; j += 2)
-                    mx = (ORDER == LBA_ORDER_CHUNK16)
-                             ? __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(top[i][j]), __builtin_fabsf(top[i][j + 1])))
-                             : __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(acc[i][j]), __builtin_fabsf(acc[i][j + 1])));
-            safe_tiles = __all(mx < thresh4) ? 4 : (__all(mx < thresh) ? 1 : 0);
-        }
-        if (safe_tiles > 0) {
-            --safe_tiles;
-            fast_tile<PM, RND, ORDER, false, TM, TN, BK, BM, BN>(acc, top, As, Bs, tx, ty, c);
-        } else {
-            fast_tile<PM, RND, ORDER, true, TM, TN, BK, BM, BN>(acc, top, As, Bs, tx, ty, c);
-        }
-        if (more) {
-            float* Ad = smem + ((t + 1) & 1) * STAGE;
-            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
-            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
-        }
-        __syncthreads();
-    }
-    if (RND == LBA_ROUND_FLOOR) set_round_nearest();
-
-    // C = S * 2^out_exp, zero written as +0
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        const int m = m0 + ty * TM + i;
-        if (m >= p.M) continue;
-        const int n = n0 + tx * TN;
-        float v[TN];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const float s = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
-            v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);
-        }
-        float* dst = pC + (int64_t)m * p.N + n;
-        if (TN == 4 && p.c_vec && n + 3 < p.N) {
-            *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[TN - 2], v[TN - 1]);
-        } else if (TN == 2 && p.c_vec && n + 1 < p.N) {
-            *reinterpret_cast<float2*>(dst) = make_float2(v[0], v[1]);
-        } else {
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                if (n + j < p.N) dst[j] = v[j];
-        }
-    }
-}
-
-// Stores the 16 event words of a lane for plane word `word` (one word per chain): wof / wuf hold the
-// bits shifted in first-highest, `nbits` of them since the last store; bit 0 of the stored word is the
-// first of them and bits at or above `valid` are cleared.  The registers are zeroed.
-__device__ __forceinline__ void store_event_words(uint32_t* of_plane, uint32_t* uf_plane, int word, int nbits, int valid,
-                                                  uint32_t (&wof)[4][4], uint32_t (&wuf)[4][4],
-                                                  int m0, int n0, int tx, int ty, const KParams& p) {
-    const uint32_t vmask = valid >= 32 ? 0xFFFFFFFFu : ((1u << valid) - 1u);
-    const int up = 32 - nbits;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + ty * 4 + i;
-        if (m < p.M) {
-            const int n = n0 + tx * 4;
-            const int64_t off = ((int64_t)word * p.M + m) * p.N + n;
-            uint32_t o[4], u[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                o[j] = __builtin_bitreverse32(wof[i][j] << up) & vmask;
-                u[j] = __builtin_bitreverse32(wuf[i][j] << up) & vmask;
-            }
-            if (p.c_vec && n + 3 < p.N) {
-                if (of_plane) *reinterpret_cast<uint4*>(of_plane + off) = make_uint4(o[0], o[1], o[2], o[3]);
-                if (uf_plane) *reinterpret_cast<uint4*>(uf_plane + off) = make_uint4(u[0], u[1], u[2], u[3]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (n + j < p.N) {
-                        if (of_plane) of_plane[off + j] = o[j];
-                        if (uf_plane) uf_plane[off + j] = u[j];
-                    }
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) { wof[i][j] = 0u; wuf[i][j] = 0u; }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// fast recompute kernel: forward chain + event planes (floor, sequential order, Q_prod can flush)
-// ---------------------------------------------------------------------------------------------
-// Same scaled domain as lba_fast_kernel, so both underflows are hardware flushes, and every decision
-// is exact under the toward-zero mode:
-//   OF_k  <=>  |t| >= R_OF  <=>  the clamped, truncated sum has magnitude exactly R_OF
-//   product underflow  <=>  the flushed product is 0 although both operands are non-zero
-//   accumulator underflow  <=>  the flushed sum is 0, the product is not, and the exact sum is not
-//       zero; the exact sum is zero only if p*kc == -S with S != 0, and then p*kc is a normal number
-//       that a plain multiply reproduces exactly
-// One 32-bit word per chain and k-tile: bits are shifted in (first k highest) and reversed at the end.
-// Chunked order: after the 16th step of a chunk the chunk sum S joins the second-level sum,
-// T <- Q_acc(T + S) with its own two event bits, and S restarts from 0.  T and S are values of Q_acc's
-// grid (zero or normal numbers), so T + S is exactly zero iff S == -T.  The extra registers (T and the
-// second-level words) are paid for with two instead of four waves per SIMD.
-// UF = false (no underflow plane asked for): the underflow tests are dropped, and under the sequential
-// order a k-tile that starts with every |S| of the wave below R_OF - BK * max|p| cannot overflow at all:
-// it runs the forward kernel's clamp-free tile and its OF words are zero.
-template <int PM, int ORDER, bool UF, int AMODE = 0>
-__global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_fast_bwd_kernel(const KParams p) {
-    constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
-    constexpr int STAGE = BK * (BM + BN);
-    __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
-
-    const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;
-    const int tidb = tid - Stage<BN, BK>::kTailShift;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    // batch member blockIdx.z (strides are 0 for a single GEMM)
-    const uint8_t* pA = p.A + (int64_t)blockIdx.z * p.stride_a;
-    const uint8_t* pB = p.B + (int64_t)blockIdx.z * p.stride_b;
-    float* pC = p.C ? p.C + (int64_t)blockIdx.z * p.stride_c : nullptr;
-
-    const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
-    set_flush_f32();
-    if (AMODE) set_denorm_f16();
-    set_round_zero();
-
-    // kc_up / up: the same product and accumulator moved up by 2^60, where neither can flush
-    float kc = p.kc, rof = p.rof_a, rofp = p.rof_p, kc_up = p.kc * 0x1p60f, up = 0x1p60f;
-    uint32_t mask = p.mask_a;
-    asm volatile("" : "+v"(kc), "+v"(rof), "+v"(rofp), "+v"(mask), "+v"(kc_up), "+v"(up));
-    FastConst fc;
-    fc.kc = kc; fc.rof = rof; fc.rofp = rofp; fc.mask = mask; fc.half = 0u; fc.sh = p.sh_a; fc.maskp = p.mask_p;
-    float thresh = p.fast_thresh;
-    asm volatile("" : "+v"(thresh));
-
-    float acc[TM][TN], top[TM][TN];
-    uint32_t wof[TM][TN], wuf[TM][TN], wof2[TM][TN], wuf2[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            acc[i][j] = 0.0f; wof[i][j] = 0u; wuf[i][j] = 0u;
-            top[i][j] = 0.0f; wof2[i][j] = 0u; wuf2[i][j] = 0u;
-        }
-
-    uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
-    const int ntiles = (p.K + BK - 1) / BK;
-
-    if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
-    else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
-    fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
-    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
-    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
-    __syncthreads();
-
-    for (int t = 0; t < ntiles; ++t) {
-        const float* As = smem + (t & 1) * STAGE;
-        const float* Bs = As + BK * BM;
-        const bool more = (t + 1) < ntiles;
-        if (more) {
-            if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
-            else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
-            fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
-        }
-        bool quiet = false;                                    // no sum of this tile can reach R_OF
-        if (!UF && ORDER == LBA_ORDER_SEQ) {
-            float mx = 0.0f;
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; j += 2)
-                    mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(acc[i][j]), __builtin_fabsf(acc[i][j + 1])));
-            quiet = __all(mx < thresh);
-        }
-        if (quiet) {
-            fast_tile<PM, LBA_ROUND_FLOOR, LBA_ORDER_SEQ, false, TM, TN, BK, BM, BN>(acc, top, As, Bs, tx, ty, fc);
-        } else if (!UF) {
-#pragma unroll 4
-            for (int k = 0; k < BK; ++k) {
-                float a[TM], b[TN];
-                read_operands<TM, TN, BM, BN>(As, Bs, k, tx, ty, a, b);
-                float q[TM][TN];
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) q[i][j] = a[i] * b[j];
-                if (PM == PM_FLUSH_CLAMP) {
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) q[i][j] = med3(q[i][j], -rofp, rofp);
-                }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        float tsum = __builtin_fmaf(q[i][j], kc, acc[i][j]);
-                        tsum = __uint_as_float(__float_as_uint(tsum) & mask);
-                        tsum = med3(tsum, -rof, rof);
-                        const uint64_t of = __builtin_amdgcn_ballot_w64(__builtin_fabsf(tsum) == rof);
-                        acc[i][j] = tsum;
-                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof[i][j]) : "s"(of) : "vcc");
-                    }
-                if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) {
-                            float u = top[i][j] + acc[i][j];
-                            u = __uint_as_float(__float_as_uint(u) & mask);
-                            u = med3(u, -rof, rof);
-                            const uint64_t of = __builtin_amdgcn_ballot_w64(__builtin_fabsf(u) == rof);
-                            top[i][j] = u;
-                            acc[i][j] = 0.0f;
-                            asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof2[i][j]) : "s"(of) : "vcc");
-                        }
-                }
-            }
-        } else
-#pragma unroll 4
-        for (int k = 0; k < BK; ++k) {
-            float a[TM], b[TN];
-            read_operands<TM, TN, BM, BN>(As, Bs, k, tx, ty, a, b);
-            // all tests produce 64-bit lane masks; the event logic runs on the scalar unit
-            uint64_t nza[TM], nzb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) nza[i] = __builtin_amdgcn_ballot_w64(a[i] != 0.0f);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) nzb[j] = __builtin_amdgcn_ballot_w64(b[j] != 0.0f);
-            float q[TM][TN], w[TM][TN], su[TM][TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) q[i][j] = a[i] * b[j];            // flushed below Q_prod's R_UF
-            if (PM == PM_FLUSH_CLAMP) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) q[i][j] = med3(q[i][j], -rofp, rofp);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) { w[i][j] = q[i][j] * kc_up; su[i][j] = acc[i][j] * up; }   // exact, never flushed
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const uint64_t cancel = __builtin_amdgcn_ballot_w64(w[i][j] == -su[i][j]);   // exact sum is zero (or p = S = 0)
-                    float tsum = __builtin_fmaf(q[i][j], kc, acc[i][j]);       // truncated, flushed exact sum
-                    tsum = __uint_as_float(__float_as_uint(tsum) & mask);
-                    tsum = med3(tsum, -rof, rof);
-                    const uint64_t zq = __builtin_amdgcn_ballot_w64(q[i][j] == 0.0f);
-                    const uint64_t zt = __builtin_amdgcn_ballot_w64(tsum == 0.0f);
-                    const uint64_t of = __builtin_amdgcn_ballot_w64(__builtin_fabsf(tsum) == rof);
-                    const uint64_t uf = (zq & nza[i] & nzb[j]) | (zt & ~zq & ~cancel);
-                    acc[i][j] = tsum;
-                    // word <- 2 * word + (this lane's bit of the mask): add with the mask as carry-in
-                    asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof[i][j]) : "s"(of) : "vcc");
-                    asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wuf[i][j]) : "s"(uf) : "vcc");
-                }
-            if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        const uint64_t cancel = __builtin_amdgcn_ballot_w64(acc[i][j] == -top[i][j]);
-                        float u = top[i][j] + acc[i][j];                        // truncated, flushed exact sum
-                        u = __uint_as_float(__float_as_uint(u) & mask);
-                        u = med3(u, -rof, rof);
-                        const uint64_t zu = __builtin_amdgcn_ballot_w64(u == 0.0f);
-                        const uint64_t of = __builtin_amdgcn_ballot_w64(__builtin_fabsf(u) == rof);
-                        const uint64_t uf = zu & ~cancel;
-                        top[i][j] = u;
-                        acc[i][j] = 0.0f;
-                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof2[i][j]) : "s"(of) : "vcc");
-                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wuf2[i][j]) : "s"(uf) : "vcc");
-                    }
-            }
-        }
-        store_event_words(p.of_mask, UF ? p.uf_mask : nullptr, t, 32, p.K - t * BK, wof, wuf, m0, n0, tx, ty, p);
-        if (ORDER == LBA_ORDER_CHUNK16 && ((t & 15) == 15 || !more)) {
-            // two chunks per k-tile: a second-level word is complete after 16 tiles
-            const int chunks = (p.K + 15) >> 4;
-            store_event_words(p.of_mask2, UF ? p.uf_mask2 : nullptr, t >> 4, 2 * ((t & 15) + 1), chunks - 32 * (t >> 4),
-                              wof2, wuf2, m0, n0, tx, ty, p);
-        }
-        if (more) {
-            float* Ad = smem + ((t + 1) & 1) * STAGE;
-            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
-            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
-        }
-        __syncthreads();
-    }
-    set_round_nearest();
-
-    if (pC) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int m = m0 + ty * 4 + i;
-            if (m >= p.M) continue;
-            const int n = n0 + tx * 4;
-            float v[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float s = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
-                v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);
-            }
-            float* dst = pC + (int64_t)m * p.N + n;
-            if (p.c_vec && n + 3 < p.N) {
-                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (n + j < p.N) dst[j] = v[j];
-            }
-        }
-    }
-}
-
-// dst <- Q_acc(add + dst) for the 16 chains of a lane, with exact decisions.
-// Floor: one toward-zero add (the kernel runs in that mode).  Nearest-even: the add is done twice,
-// toward +inf and toward -inf; the smaller magnitude is the truncated sum and the two differ iff the
-// sum was inexact (the sticky bit).  With EVENTS, one OF and one UF bit per chain are shifted into
-// wof / wuf (uf1 = product-underflow flags of this step).
-template <int RND, bool EVENTS>
-__device__ __forceinline__ void gen_qadd_all(float (&dst)[4][4], const float (&add)[4][4], const KParams& p,
-                                             uint32_t rofb, uint32_t rufb, const uint32_t (&uf1)[4][4],
-                                             uint32_t (&wof)[4][4], uint32_t (&wuf)[4][4]) {
-    constexpr int TM = 4, TN = 4;
-    if (RND == LBA_ROUND_FLOOR) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const float S = dst[i][j];
-                const float tz = add[i][j] + S;                             // toward zero: truncated exact sum
-                const uint32_t uz = __float_as_uint(tz);
-                const uint32_t mag = uz & 0x7FFFFFFFu;
-                const bool of = mag >= rofb, small = mag < rufb;
-                uint32_t r = uz & p.mask_a;
-                r = of ? ((uz & 0x80000000u) | rofb) : r;
-                r = small ? 0u : r;
-                dst[i][j] = __uint_as_float(r);
-                if (EVENTS) {
-                    const bool nz = add[i][j] != -S;                        // exact sum is not zero
-                    wof[i][j] = (wof[i][j] << 1) | (of ? 1u : 0u);
-                    wuf[i][j] = (wuf[i][j] << 1) | ((uf1[i][j] || (small && nz)) ? 1u : 0u);
-                }
-            }
-    } else {
-        float tp[TM][TN], tn[TM][TN], tr[TM][TN];
-        if (p.sh_a == 0) {
-            // M = 23: the 24-bit nearest-even sum is the mantissa rounding itself; the two
-            // directed sums below still give the exact over/underflow decisions
-            set_round_nearest();
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    asm volatile("v_add_f32 %0, %1, %2" : "=v"(tr[i][j]) : "v"(add[i][j]), "v"(dst[i][j]));
-        }
-        set_round_pinf();
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                asm volatile("v_add_f32 %0, %1, %2" : "=v"(tp[i][j]) : "v"(add[i][j]), "v"(dst[i][j]));
-        set_round_ninf();
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-                asm volatile("v_add_f32 %0, %1, %2" : "=v"(tn[i][j]) : "v"(add[i][j]), "v"(dst[i][j]));
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const float S = dst[i][j];
-                const uint32_t up = __float_as_uint(tp[i][j]), un = __float_as_uint(tn[i][j]);
-                const uint32_t sticky = (up ^ un) & 1u;                     // the two differ iff inexact
-                const uint32_t uz = up < un ? up : un;                      // smaller magnitude (same sign)
-                uint32_t of; bool small;
-                float r = gen_acc_rne(uz, sticky, p, &of, &small);
-                if (p.sh_a == 0) {
-                    const uint32_t sign = uz & 0x80000000u;
-                    uint32_t w = __float_as_uint(tr[i][j]);
-                    w = of ? (sign | rofb) : w;
-                    w = small ? 0u : w;
-                    r = __uint_as_float(w);
-                }
-                dst[i][j] = r;
-                if (EVENTS) {
-                    const bool nz = add[i][j] != -S;
-                    wof[i][j] = (wof[i][j] << 1) | of;
-                    wuf[i][j] = (wuf[i][j] << 1) | ((uf1[i][j] || (small && nz)) ? 1u : 0u);
-                }
-            }
-    }
-}
-
-// General kernel: 4 x 4 outputs per lane, 64 x 64 tile, BK = 32 (one event word per tile).
-template <int RND, bool EVENTS, int ORDER>
-__global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
-    constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
-    constexpr int STAGE = BK * (BM + BN);
-    __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
-    __shared__ float lut_a[256];
-    __shared__ float lut_b[256];
-
-    const int tid = threadIdx.x;
-    const int tx = tid & 15, ty = tid >> 4;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
-    // batch member blockIdx.z (strides are 0 for a single GEMM)
-    const uint8_t* pA = p.A + (int64_t)blockIdx.z * p.stride_a;
-    const uint8_t* pB = p.B + (int64_t)blockIdx.z * p.stride_b;
-    float* pC = p.C ? p.C + (int64_t)blockIdx.z * p.stride_c : nullptr;
-
-    lut_a[tid] = decode_entry(tid, p.exp_a, p.in_ea, p.in_ma);
-    lut_b[tid] = decode_entry(tid, p.exp_b, p.in_eb, p.in_mb);
-    set_flush_f32();
-    if (RND == LBA_ROUND_FLOOR) set_round_zero();
-
-    float acc[TM][TN], top[TM][TN];                            // top: second-level sums (chunked order only)
-    uint32_t wof[TM][TN], wuf[TM][TN], wof2[TM][TN], wuf2[TM][TN], no_uf1[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            acc[i][j] = 0.0f; top[i][j] = 0.0f; wof[i][j] = 0u; wuf[i][j] = 0u;
-            wof2[i][j] = 0u; wuf2[i][j] = 0u; no_uf1[i][j] = 0u;
-        }
-
-    uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
-    const int ntiles = (p.K + BK - 1) / BK;
-    const uint32_t rofb = __float_as_uint(p.rof_a), rufb = __float_as_uint(p.ruf_a);
-
-    fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
-    fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tid, rb);
-    __syncthreads();
-    store_tile<BM, BK>(smem, lut_a, tid, ra);
-    store_tile<BN, BK>(smem + BK * BM, lut_b, tid, rb);
-    __syncthreads();
-
-    for (int t = 0; t < ntiles; ++t) {
-        const float* As = smem + (t & 1) * STAGE;
-        const float* Bs = As + BK * BM;
-        const bool more = (t + 1) < ntiles;
-        if (more) {
-            fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
-            fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tid, rb);
-        }
-#pragma unroll 2
-        for (int k = 0; k < BK; ++k) {
-            const float4 av = *reinterpret_cast<const float4*>(As + k * BM + ty * 4);
-            const float4 bv = *reinterpret_cast<const float4*>(Bs + k * BN + tx * 4);
-            const float a[4] = {av.x, av.y, av.z, av.w};
-            const float b[4] = {bv.x, bv.y, bv.z, bv.w};
-            float pq[TM][TN];
-            uint32_t uf1[TM][TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) pq[i][j] = gen_product<RND>(a[i], b[j], p, &uf1[i][j]);
-
-            gen_qadd_all<RND, EVENTS>(acc, pq, p, rofb, rufb, uf1, wof, wuf);
-            if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
-                // second level (Sec. 3, Fig. 1 right): T <- Q_acc(T + S), S <- 0
-                gen_qadd_all<RND, EVENTS>(top, acc, p, rofb, rufb, no_uf1, wof2, wuf2);
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) acc[i][j] = 0.0f;
-            }
-        }
-        if (EVENTS) {
-            store_event_words(p.of_mask, p.uf_mask, t, 32, p.K - t * BK, wof, wuf, m0, n0, tx, ty, p);
-            if (ORDER == LBA_ORDER_CHUNK16 && ((t & 15) == 15 || !more)) {
-                const int chunks = (p.K + 15) >> 4;
-                store_event_words(p.of_mask2, p.uf_mask2, t >> 4, 2 * ((t & 15) + 1), chunks - 32 * (t >> 4),
-                                  wof2, wuf2, m0, n0, tx, ty, p);
-            }
-        }
-        if (more) {
-            float* Ad = smem + ((t + 1) & 1) * STAGE;
-            store_tile<BM, BK>(Ad, lut_a, tid, ra);
-            store_tile<BN, BK>(Ad + BK * BM, lut_b, tid, rb);
-        }
-        __syncthreads();
-    }
-    set_round_nearest();
-
-    if (pC) {
-#pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int m = m0 + ty * 4 + i;
-            if (m >= p.M) continue;
-            const int n = n0 + tx * 4;
-            float v[4];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const float r = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
-                v[j] = (r == 0.0f) ? 0.0f : __builtin_ldexpf(r, p.out_exp);     // out_exp: the operand biases' scale
-            }
-            float* dst = pC + (int64_t)m * p.N + n;
-            if (p.c_vec && n + 3 < p.N) {
-                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
-            } else {
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    if (n + j < p.N) dst[j] = v[j];
-            }
-        }
-    }
-}
 
 __global__ void lba_fill_zero_kernel(float* C, int64_t n) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) C[i] = 0.0f;
 }
 
-// ---------------------------------------------------------------------------------------------
-// launchers
-// ---------------------------------------------------------------------------------------------
-#ifndef LBA_FAST_BK
-#define LBA_FAST_BK 32              // k-depth of a tile of the fast kernel (a multiple of 16)
-#endif
-
-template <int TM, int TN, int ORDER, int AMODE = 0>
-static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
-    const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
-    const KParams& kp = pl.kp;
-#define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<TM, TN, LBA_FAST_BK, PM, RND, ORDER, AMODE>), grid, block, 0, st, kp)
-    // the truncating product modes (operand formats whose products exceed Q_prod's mantissa) exist for
-    // the 4 x 4 lane block only; the planner never asks for them with another
-#define LBA_LAUNCH_ROUNDING(RND)                                                        \
-    switch (pl.prod_mode) {                                                             \
-        case PM_IDENT:       LBA_LAUNCH(PM_IDENT, RND); break;                          \
-        case PM_FLUSH:       LBA_LAUNCH(PM_FLUSH, RND); break;                          \
-        case PM_FLUSH_CLAMP: LBA_LAUNCH(PM_FLUSH_CLAMP, RND); break;                    \
-        case PM_TRUNC:       if constexpr (TM == 4 && TN == 4) { LBA_LAUNCH(PM_TRUNC, RND); break; } else return hipErrorInvalidValue;        \
-        default:             if constexpr (TM == 4 && TN == 4) { LBA_LAUNCH(PM_TRUNC_CLAMP, RND); break; } else return hipErrorInvalidValue;  \
-    }
-    if (pl.round == LBA_ROUND_FLOOR) {
-        LBA_LAUNCH_ROUNDING(LBA_ROUND_FLOOR)
-    } else if (pl.kp.sh_a == 16 && AMODE == 0) {             // M = 7: rounding by the bfloat16 conversion
-        LBA_LAUNCH_ROUNDING(RND_RNE_BF16)
-    } else {
-        LBA_LAUNCH_ROUNDING(LBA_ROUND_RNE)
-    }
-#undef LBA_LAUNCH_ROUNDING
-#undef LBA_LAUNCH
-    return hipGetLastError();
-}
-
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
-    if (pl.kernel == KERNEL_FAST && pl.events) {
-        const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
-        const bool uf = pl.kp.uf_mask != nullptr || pl.kp.uf_mask2 != nullptr;
-        if (pl.amode) {                                        // im2col rows / other operand formats: sequential order only
-#define LBA_BWD1(PM, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, LBA_ORDER_SEQ, UF, 1>), grid, block, 0, st, pl.kp)
-            if (pl.order != LBA_ORDER_SEQ) return hipErrorInvalidValue;
-            if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD1(PM_FLUSH, true); else LBA_BWD1(PM_FLUSH, false); }
-            else                          { if (uf) LBA_BWD1(PM_FLUSH_CLAMP, true); else LBA_BWD1(PM_FLUSH_CLAMP, false); }
-#undef LBA_BWD1
-            return hipGetLastError();
-        }
-#define LBA_BWD(PM, ORDER, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, ORDER, UF>), grid, block, 0, st, pl.kp)
-        if (pl.order == LBA_ORDER_CHUNK16) {
-            if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD(PM_FLUSH, LBA_ORDER_CHUNK16, true); else LBA_BWD(PM_FLUSH, LBA_ORDER_CHUNK16, false); }
-            else                          { if (uf) LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_CHUNK16, true); else LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_CHUNK16, false); }
-        } else {
-            if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD(PM_FLUSH, LBA_ORDER_SEQ, true); else LBA_BWD(PM_FLUSH, LBA_ORDER_SEQ, false); }
-            else                          { if (uf) LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_SEQ, true); else LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_SEQ, false); }
-        }
-#undef LBA_BWD
-        return hipGetLastError();
-    }
-    if (pl.kernel == KERNEL_FAST && pl.amode)                  // the planner keeps these on the 4 x 4 lane block
-        return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<4, 4, LBA_ORDER_CHUNK16, 1>(pl, st) : launch_fast<4, 4, LBA_ORDER_SEQ, 1>(pl, st);
+    if (pl.kernel == KERNEL_FAST && pl.events) return launch_fast_bwd(pl, st);
+    if (pl.kernel == KERNEL_FAST && pl.amode) return launch_fast_amode(pl, st);   // the planner keeps these on 4 x 4
     if (pl.kernel == KERNEL_FAST) {
-        if (pl.tm == 2 && pl.tn == 2)
-            return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<2, 2, LBA_ORDER_CHUNK16>(pl, st) : launch_fast<2, 2, LBA_ORDER_SEQ>(pl, st);
-        if (pl.tm == 2)
-            return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<2, 4, LBA_ORDER_CHUNK16>(pl, st) : launch_fast<2, 4, LBA_ORDER_SEQ>(pl, st);
-        return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<4, 4, LBA_ORDER_CHUNK16>(pl, st) : launch_fast<4, 4, LBA_ORDER_SEQ>(pl, st);
+        if (pl.tm == 2 && pl.tn == 2) return launch_fast_22(pl, st);
+        if (pl.tm == 2) return launch_fast_24(pl, st);
+        return launch_fast_44(pl, st);
     }
-    const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
-    const KParams& kp = pl.kp;
-    if (pl.order == LBA_ORDER_CHUNK16 && pl.events) {
-        if (pl.round == LBA_ROUND_FLOOR) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, true, LBA_ORDER_CHUNK16>), grid, block, 0, st, kp);
-        else                             hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, true, LBA_ORDER_CHUNK16>), grid, block, 0, st, kp);
-    } else if (pl.order == LBA_ORDER_CHUNK16) {
-        if (pl.round == LBA_ROUND_FLOOR) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, false, LBA_ORDER_CHUNK16>), grid, block, 0, st, kp);
-        else                             hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, false, LBA_ORDER_CHUNK16>), grid, block, 0, st, kp);
-    } else if (pl.round == LBA_ROUND_FLOOR) {
-        if (pl.events) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, true, LBA_ORDER_SEQ>), grid, block, 0, st, kp);
-        else           hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_FLOOR, false, LBA_ORDER_SEQ>), grid, block, 0, st, kp);
-    } else {
-        if (pl.events) hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, true, LBA_ORDER_SEQ>), grid, block, 0, st, kp);
-        else           hipLaunchKernelGGL((lba_gen_kernel<LBA_ROUND_RNE, false, LBA_ORDER_SEQ>), grid, block, 0, st, kp);
-    }
-    return hipGetLastError();
+    return launch_gen(pl, st);
 }
 
 static int gcd_align(const void* ptr, int64_t K) {

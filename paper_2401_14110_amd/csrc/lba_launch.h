@@ -1,0 +1,24 @@
+// lba_launch.h -- launchers of the kernel instantiations.  The instantiations are spread over several
+// translation units (lba_fast_*.hip, lba_bwd.hip, lba_gen.hip) so that they compile in parallel; each
+// defines the launchers declared here for its group of template arguments.
+#ifndef LBA_LAUNCH_H_
+#define LBA_LAUNCH_H_
+
+#include <hip/hip_runtime.h>
+
+#include "lba_internal.h"
+
+namespace lba {
+
+// forward, scaled-domain kernel; lane block tm x tn of the plan (amode plans: 4 x 4)
+hipError_t launch_fast_44(const Plan& pl, hipStream_t st);
+hipError_t launch_fast_24(const Plan& pl, hipStream_t st);
+hipError_t launch_fast_22(const Plan& pl, hipStream_t st);
+hipError_t launch_fast_amode(const Plan& pl, hipStream_t st);
+// recompute call, scaled-domain kernel
+hipError_t launch_fast_bwd(const Plan& pl, hipStream_t st);
+// general kernel (forward and recompute)
+hipError_t launch_gen(const Plan& pl, hipStream_t st);
+
+}  // namespace lba
+#endif

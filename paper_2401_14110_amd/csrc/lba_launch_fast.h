@@ -1,0 +1,48 @@
+// lba_launch_fast.h -- the launcher template of lba_fast_kernel, included by the lba_fast_*.hip units.
+#ifndef LBA_LAUNCH_FAST_H_
+#define LBA_LAUNCH_FAST_H_
+
+#include "lba_device.h"
+#include "lba_launch.h"
+
+namespace lba {
+
+#ifndef LBA_FAST_BK
+#define LBA_FAST_BK 32              // k-depth of a tile of the fast kernel (a multiple of 16)
+#endif
+
+template <int TM, int TN, int ORDER, int AMODE = 0>
+static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
+    const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
+    const KParams& kp = pl.kp;
+#define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<TM, TN, LBA_FAST_BK, PM, RND, ORDER, AMODE>), grid, block, 0, st, kp)
+    // the truncating product modes (operand formats whose products exceed Q_prod's mantissa) exist for
+    // the 4 x 4 lane block only; the planner never asks for them with another
+#define LBA_LAUNCH_ROUNDING(RND)                                                        \
+    switch (pl.prod_mode) {                                                             \
+        case PM_IDENT:       LBA_LAUNCH(PM_IDENT, RND); break;                          \
+        case PM_FLUSH:       LBA_LAUNCH(PM_FLUSH, RND); break;                          \
+        case PM_FLUSH_CLAMP: LBA_LAUNCH(PM_FLUSH_CLAMP, RND); break;                    \
+        case PM_TRUNC:       if constexpr (TM == 4 && TN == 4) { LBA_LAUNCH(PM_TRUNC, RND); break; } else return hipErrorInvalidValue;        \
+        default:             if constexpr (TM == 4 && TN == 4) { LBA_LAUNCH(PM_TRUNC_CLAMP, RND); break; } else return hipErrorInvalidValue;  \
+    }
+    if (pl.round == LBA_ROUND_FLOOR) {
+        LBA_LAUNCH_ROUNDING(LBA_ROUND_FLOOR)
+    } else if (pl.kp.sh_a == 16 && AMODE == 0) {             // M = 7: rounding by the bfloat16 conversion
+        LBA_LAUNCH_ROUNDING(RND_RNE_BF16)
+    } else {
+        LBA_LAUNCH_ROUNDING(LBA_ROUND_RNE)
+    }
+#undef LBA_LAUNCH_ROUNDING
+#undef LBA_LAUNCH
+    return hipGetLastError();
+}
+
+template <int TM, int TN, int AMODE>
+static hipError_t launch_fast_orders(const Plan& pl, hipStream_t st) {
+    return pl.order == LBA_ORDER_CHUNK16 ? launch_fast<TM, TN, LBA_ORDER_CHUNK16, AMODE>(pl, st)
+                                         : launch_fast<TM, TN, LBA_ORDER_SEQ, AMODE>(pl, st);
+}
+
+}  // namespace lba
+#endif
