@@ -116,15 +116,15 @@ def main():
         if in_fmt:                                          # biases stay in real units: the library folds the flex biases
             l["qp"], l["qa"] = PROD_FMT + (rnd,), acc_fmt + (rnd,)
             l["fa"], l["fb"] = in_fmt + (l["ta"],), in_fmt + (l["tb"],)
-            qpq, qaq, _ = inputs.folded_formats(l["ta"] - (2 ** (in_fmt[0] - 1) - 1), l["tb"] - (2 ** (in_fmt[0] - 1) - 1), PROD_FMT, acc_fmt, rnd)
-            # the plan of an E4M3 call with the same folded quantizers names tile and grid; the product mode is
-            # "truncating" when Q_prod's mantissa is narrower than the 2M+2 bits of a product
-            l["plan"] = dict(lb.lba_plan_query(l["M"], l["N"], l["K"], qpq, qaq, order, 0))
-            if PROD_FMT[1] + 1 < 2 * in_fmt[1] + 2 and rnd == 0:
-                l["plan"].update(prod_mode=4, thread_m=4, thread_n=4, valu_per_mac_x100=l["plan"]["valu_per_mac_x100"] + 100)
+            l["plan"] = lb.lba_plan_query_in(l["M"], l["N"], l["K"], l["fa"], l["fb"], l["qp"], l["qa"], order, 0)
         else:
             l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], PROD_FMT, acc_fmt, rnd)
             l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, 1 if args.bwd else 0)
+            if args.bwd and args.of_only and order == 0:
+                # priced like the forward call: k-tiles that cannot overflow run the forward tile (3 slots per MAC);
+                # tiles that can add a clamp, a compare and a carry-in add per MAC, which this count leaves out
+                fwd = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, 0)
+                l["plan"] = dict(l["plan"], valu_per_mac_x100=fwd["valu_per_mac_x100"])
         l["C"] = Cbuf[: l["M"] * l["N"]].view(l["M"], l["N"])
         l["macs"] = l["M"] * l["N"] * l["K"]
     if args.grad:

@@ -228,6 +228,10 @@ typedef struct {
 int lba_plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc,
                    int32_t order, int32_t with_masks, lba_plan_info* out);
 
+/* lba_plan_query for the operand formats of lba_gemm_in (the biases are folded as that call folds them). */
+int lba_plan_query_in(int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,
+                      lba_qfmt qprod, lba_qfmt qacc, int32_t order, int32_t with_masks, lba_plan_info* out);
+
 #ifdef __cplusplus
 }
 #endif

@@ -79,6 +79,9 @@ def lib():
         L.lba_conv2d_bwd.argtypes = [vp, vp, vp, vp, vp, lba_conv2d_desc, i64, lba_qfmt, lba_qfmt, i32, vp]
         L.lba_conv2d_out_shape.restype = ctypes.c_int
         L.lba_conv2d_out_shape.argtypes = [lba_conv2d_desc, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+        L.lba_plan_query_in.restype = ctypes.c_int
+        L.lba_plan_query_in.argtypes = [i64, i64, i64, lba_infmt, lba_infmt, lba_qfmt, lba_qfmt, i32, i32,
+                                        ctypes.POINTER(lba_plan_info)]
         L.lba_last_overflow.restype = ctypes.c_int
         L.lba_last_overflow.argtypes = [vp, vp, i64, i64, i64, vp]
         L.lba_ste_plane.restype = ctypes.c_int
@@ -198,6 +201,13 @@ def lba_mask_words(M, N, K):
 
 def lba_mask_words_level2(M, N, K):
     return int(lib().lba_mask_words_level2(M, N, K))
+
+
+def lba_plan_query_in(M, N, K, fmt_a, fmt_b, qprod, qacc, order=ORDER_SEQ, with_masks=0):
+    info = lba_plan_info()
+    _check(lib().lba_plan_query_in(M, N, K, infmt(fmt_a), infmt(fmt_b), qfmt(qprod), qfmt(qacc), order, with_masks,
+                                   ctypes.byref(info)))
+    return {n: getattr(info, n) for n, _ in lba_plan_info._fields_}
 
 
 def lba_plan_query(M, N, K, qprod, qacc, order=ORDER_SEQ, with_masks=0):

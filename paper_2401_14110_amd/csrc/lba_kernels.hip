@@ -205,11 +205,11 @@ const char* lba_strerror(int code) {
     }
 }
 
-int lba_plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
-                   int32_t with_masks, lba_plan_info* out) {
+static int plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
+                      int32_t with_masks, const lba::InSpec* in, lba_plan_info* out) {
     if (!out) return LBA_ERR_NULL;
     lba::Plan pl;
-    int rc = lba::make_plan(M, N, K, qprod, qacc, order, with_masks, &pl);
+    int rc = lba::make_plan(M, N, K, qprod, qacc, order, with_masks, &pl, 1, in);
     if (rc != LBA_OK) return rc;
     out->kernel = pl.kernel; out->prod_mode = pl.prod_mode; out->round = pl.round;
     out->tile_m = 16 * pl.tm; out->tile_n = 16 * pl.tn; out->tile_k = pl.bk;
@@ -217,6 +217,22 @@ int lba_plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qac
     out->grid_x = pl.grid_x; out->grid_y = pl.grid_y;
     out->valu_per_mac_x100 = pl.valu_per_mac_x100;
     return LBA_OK;
+}
+
+int lba_plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
+                   int32_t with_masks, lba_plan_info* out) {
+    return plan_query(M, N, K, qprod, qacc, order, with_masks, nullptr, out);
+}
+
+int lba_plan_query_in(int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,
+                      lba_qfmt qprod, lba_qfmt qacc, int32_t order, int32_t with_masks, lba_plan_info* out) {
+    lba::InSpec in;
+    int rc = lba::make_in_spec(fmt_a, fmt_b, &in);
+    if (rc != LBA_OK) return rc;
+    if ((rc = lba::validate_fmt(qprod)) != LBA_OK || (rc = lba::validate_fmt(qacc)) != LBA_OK) return rc;
+    qprod.bias -= in.delta;
+    qacc.bias -= in.delta;
+    return plan_query(M, N, K, qprod, qacc, order, with_masks, &in, out);
 }
 
 }  // extern "C"
