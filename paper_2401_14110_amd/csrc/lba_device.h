@@ -82,8 +82,8 @@ __device__ __forceinline__ float rne_to_8_bits(float t) {
 // FP32 / bitwise VALU ops issue at twice the rate when all their operands are VGPRs.
 struct FastConst {
     float kc, rof, rofp;
-    uint32_t mask, half, maskp;
-    int sh;
+    uint32_t mask, half, maskp, halfp;
+    int sh, shp;
 };
 
 // One k-step for a GROUP of NCH independent chains, written phase by phase (all products, then
@@ -113,7 +113,22 @@ __device__ __forceinline__ void fast_group(float (&accf)[TM][NJ], const float (&
                 for (int j = 0; j < NJ; ++j) q[i][j] = __uint_as_float(__float_as_uint(q[i][j]) & c.maskp);
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (PM == PM_FLUSH_CLAMP || PM == PM_TRUNC_CLAMP) {
+        if (PM == PM_RNE || PM == PM_RNE_CLAMP) {
+            // the product is exact in FP32, so this is Q_prod's one nearest-even rounding (a carry moves
+            // to the next binade by itself); the flush above was decided on the unrounded product
+            uint32_t l[NI][NJ];
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) l[i][j] = (__float_as_uint(q[i][j]) >> c.shp) & 1u;
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) q[i][j] = __uint_as_float((__float_as_uint(q[i][j]) + c.halfp + l[i][j]) & c.maskp);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if (PM == PM_FLUSH_CLAMP || PM == PM_TRUNC_CLAMP || PM == PM_RNE_CLAMP) {
 #pragma unroll
             for (int i = 0; i < NI; ++i)
 #pragma unroll
@@ -527,10 +542,10 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
     if (RND == LBA_ROUND_FLOOR) set_round_zero();
 
     FastConst c;
-    c.kc = p.kc; c.rof = p.rof_a; c.rofp = p.rof_p; c.mask = p.mask_a; c.half = p.half_a; c.sh = p.sh_a; c.maskp = p.mask_p;
+    c.kc = p.kc; c.rof = p.rof_a; c.rofp = p.rof_p; c.mask = p.mask_a; c.half = p.half_a; c.sh = p.sh_a; c.maskp = p.mask_p; c.halfp = p.half_p; c.shp = p.sh_p;
     float thresh = p.fast_thresh, thresh4 = p.fast_thresh4;
     int safe_tiles = 0;
-    asm volatile("" : "+v"(c.kc), "+v"(c.rof), "+v"(c.rofp), "+v"(c.mask), "+v"(c.half), "+v"(c.maskp), "+v"(thresh), "+v"(thresh4));
+    asm volatile("" : "+v"(c.kc), "+v"(c.rof), "+v"(c.rofp), "+v"(c.mask), "+v"(c.half), "+v"(c.maskp), "+v"(c.halfp), "+v"(thresh), "+v"(thresh4));
 
     float acc[TM][TN], top[TM][TN];                            // top: second-level sums (chunked order only)
 #pragma unroll
@@ -694,7 +709,7 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
     uint32_t mask = p.mask_a;
     asm volatile("" : "+v"(kc), "+v"(rof), "+v"(rofp), "+v"(mask), "+v"(kc_up), "+v"(up));
     FastConst fc;
-    fc.kc = kc; fc.rof = rof; fc.rofp = rofp; fc.mask = mask; fc.half = 0u; fc.sh = p.sh_a; fc.maskp = p.mask_p;
+    fc.kc = kc; fc.rof = rof; fc.rofp = rofp; fc.mask = mask; fc.half = 0u; fc.sh = p.sh_a; fc.maskp = p.mask_p; fc.halfp = p.half_p; fc.shp = p.sh_p;
     float thresh = p.fast_thresh;
     asm volatile("" : "+v"(thresh));
 

@@ -11,7 +11,8 @@ namespace lba {
 
 enum { KERNEL_FAST = 0, KERNEL_GEN = 1 };
 enum { PM_IDENT = 0, PM_FLUSH = 1, PM_FLUSH_CLAMP = 2,
-       PM_TRUNC = 3, PM_TRUNC_CLAMP = 4 };   // + the product's mantissa truncated to Q_prod's M bits
+       PM_TRUNC = 3, PM_TRUNC_CLAMP = 4,     // + the product's mantissa truncated to Q_prod's M bits
+       PM_RNE = 5, PM_RNE_CLAMP = 6 };       // + ... rounded to nearest-even (kernels with AMODE = 1 only)
 
 // Uniform (scalar-register) parameters of a launch.  All thresholds are exact FP32 values.
 struct KParams {

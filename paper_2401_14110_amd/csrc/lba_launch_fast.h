@@ -17,14 +17,16 @@ static hipError_t launch_fast(const Plan& pl, hipStream_t st) {
     const KParams& kp = pl.kp;
 #define LBA_LAUNCH(PM, RND) hipLaunchKernelGGL((lba_fast_kernel<TM, TN, LBA_FAST_BK, PM, RND, ORDER, AMODE>), grid, block, 0, st, kp)
     // the truncating product modes (operand formats whose products exceed Q_prod's mantissa) exist for
-    // the 4 x 4 lane block only; the planner never asks for them with another
+    // the 4 x 4 lane block only, the nearest-even ones for AMODE = 1 only; the planner never asks for them otherwise
 #define LBA_LAUNCH_ROUNDING(RND)                                                        \
     switch (pl.prod_mode) {                                                             \
         case PM_IDENT:       LBA_LAUNCH(PM_IDENT, RND); break;                          \
         case PM_FLUSH:       LBA_LAUNCH(PM_FLUSH, RND); break;                          \
         case PM_FLUSH_CLAMP: LBA_LAUNCH(PM_FLUSH_CLAMP, RND); break;                    \
         case PM_TRUNC:       if constexpr (TM == 4 && TN == 4) { LBA_LAUNCH(PM_TRUNC, RND); break; } else return hipErrorInvalidValue;        \
-        default:             if constexpr (TM == 4 && TN == 4) { LBA_LAUNCH(PM_TRUNC_CLAMP, RND); break; } else return hipErrorInvalidValue;  \
+        case PM_TRUNC_CLAMP: if constexpr (TM == 4 && TN == 4) { LBA_LAUNCH(PM_TRUNC_CLAMP, RND); break; } else return hipErrorInvalidValue;  \
+        case PM_RNE:         if constexpr (AMODE == 1) { LBA_LAUNCH(PM_RNE, RND); break; } else return hipErrorInvalidValue;                  \
+        default:             if constexpr (AMODE == 1) { LBA_LAUNCH(PM_RNE_CLAMP, RND); break; } else return hipErrorInvalidValue;            \
     }
     if (pl.round == LBA_ROUND_FLOOR) {
         LBA_LAUNCH_ROUNDING(LBA_ROUND_FLOOR)

@@ -197,8 +197,9 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     const int c_p_dom = bpe - 126;
     const int c_a_dom = nouf_a ? -60 : bae - 126;
 
-    // a narrower product mantissa is a bit mask when Q_prod rounds by truncation (forward call only)
-    bool fast = !prod_round || (qp.round == LBA_ROUND_FLOOR && !events);
+    // a narrower product mantissa is one bit mask (truncation) or bfe / add3 / and (nearest-even) on the
+    // exact FP32 product (forward call only)
+    bool fast = !prod_round || !events;
     // the recompute call has a scaled-domain kernel for floor rounding when Q_prod can underflow
     // (its product-underflow test is the multiply's flush); anything else takes the general kernel
     if (events && (qa.round != LBA_ROUND_FLOOR || !flush)) fast = false;
@@ -209,8 +210,9 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
 
     if (fast) {
         p.kernel = KERNEL_FAST;
-        p.prod_mode = prod_round ? (clamp ? PM_TRUNC_CLAMP : PM_TRUNC)
-                                 : (clamp ? PM_FLUSH_CLAMP : (flush ? PM_FLUSH : PM_IDENT));
+        p.prod_mode = !prod_round ? (clamp ? PM_FLUSH_CLAMP : (flush ? PM_FLUSH : PM_IDENT))
+                      : qp.round == LBA_ROUND_FLOOR ? (clamp ? PM_TRUNC_CLAMP : PM_TRUNC)
+                                                    : (clamp ? PM_RNE_CLAMP : PM_RNE);
         const int c_a = c_a_dom;
         const int c_p = (p.prod_mode == PM_IDENT) ? c_a : c_p_dom;
         kp.exp_a = c_p / 2;                                // split the product's scale over a and b
@@ -223,8 +225,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         // (v_mul_f32 / v_fma_f32 / v_and_b32 with register operands: 32 lanes per clock per SIMD).
         // v_med3_f32, v_bfe_u32 and v_add3_u32 issue at half that rate and count 2.
         int slots = (p.prod_mode == PM_IDENT) ? 2 : 3;           // [mul,] fma, and
-        if (p.prod_mode == PM_FLUSH_CLAMP || p.prod_mode == PM_TRUNC_CLAMP) slots += 2;   // med3 on the product
-        if (prod_round) slots += 1;                              // and on the product
+        if (p.prod_mode == PM_FLUSH_CLAMP || p.prod_mode == PM_TRUNC_CLAMP || p.prod_mode == PM_RNE_CLAMP) slots += 2;   // med3 on the product
+        if (prod_round) slots += (qp.round == LBA_ROUND_FLOOR) ? 1 : 5;   // and [, bfe, add3] on the product
         if (qa.round == LBA_ROUND_RNE) slots += (qa.man_bits == 7) ? 1 : 4;   // M = 7: cvt to bfloat16 replaces and; else bfe, add3
         p.valu_per_mac_x100 = slots * 100;
         if (events)                                              // 5 full-rate + 7 half-rate instructions, + operand tests
@@ -243,7 +245,7 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         kp.prod_rne = (qp.round == LBA_ROUND_RNE) ? 1 : 0;
         p.valu_per_mac_x100 = 0;                           // filled by the launcher's table
     }
-    p.amode = (conv || in.ea != 4 || in.eb != 4) ? 1 : 0;
+    p.amode = (conv || in.ea != 4 || in.eb != 4 || p.prod_mode == PM_RNE || p.prod_mode == PM_RNE_CLAMP) ? 1 : 0;
     pick_tile(M, N, batch, p.kernel, p.events, p.prod_mode, p.amode, &p.tm, &p.tn, &p.bk);
     kp.batch = 1;
     kp.fast_thresh = -1.0f;

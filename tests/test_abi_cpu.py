@@ -109,7 +109,8 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     assert q(64, 64, 64, (5, 9, 15, 1), (5, 8, 15, 1))["kernel"] == 1     # saturated product off the grid, sums below R_OF
     assert q(64, 64, 64, (5, 9, 15, 1), (4, 8, 7, 1))["kernel"] == 0      # same product, but then every sum saturates
     assert q(64, 64, 64, (5, 7, 40, 1), (4, 7, -9, 1))["kernel"] == 1     # products far below R_UF of Q_acc
-    assert q(64, 64, 64, (5, 4, 15, 1), (4, 7, 7, 1))["kernel"] == 1      # product mantissa is rounded to nearest
+    assert q(64, 64, 64, (5, 4, 15, 1), (4, 7, 7, 1))["prod_mode"] == 6   # product mantissa rounded to nearest (and clamped): still the scaled kernel
+    assert q(64, 64, 64, (5, 4, 15, 1), (4, 7, 7, 1), with_masks=1)["kernel"] == 1   # ... the recompute call: general kernel
     assert q(64, 64, 64, (5, 4, 15, 0), (4, 7, 7, 0))["prod_mode"] == 4   # ... truncated (and clamped): a bit mask in the scaled kernel
     assert q(64, 64, 64, (6, 4, 20, 0), (4, 7, 7, 0))["prod_mode"] == 3   # ... truncated, cannot saturate
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 3, 7, 0))["kernel"] == 0      # floor is exact at any M
