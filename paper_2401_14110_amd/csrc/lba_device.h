@@ -9,8 +9,9 @@
 // Data path per k-tile (depth BK):
 //   global: each lane fetches 16 contiguous bytes (one row, 16 k) of A and/or B   [coalescing is
 //           irrelevant here: < 0.1 byte per MAC]
-//   decode: byte -> FP32 through a 256-entry LDS table built once per workgroup; the table holds
-//           value(code) * 2^exp, so operands arrive pre-scaled into the kernel's domain
+//   decode: E4M3 bytes -> FP32 with the hardware FP8 conversion times a power-of-two scale (other code
+//           formats through an exact FP16 image, or arithmetically); the general kernel uses a 256-entry
+//           LDS table of value(code) * 2^exp; operands arrive pre-scaled into the kernel's domain
 //   LDS:    tiles are stored k-major ([k][row], row contiguous) so that a lane reads its 4 / 8
 //           operand values of one k with one / two 16-byte reads, without bank conflicts
 //   VALU:   TM*TN chains advance by one step; all FP32 ops are exact or a single rounding
@@ -18,7 +19,7 @@
 // Two LDS stages; the next tile's global loads are in flight while the current one is consumed.
 //
 // The wave's FP mode is changed with s_setreg (rounding mode) and the translation unit is built
-// with FP32 denormals flushed; no runtime integer division is used inside the kernels.
+// with FP32 denormals flushed.
 
 #ifndef LBA_DEVICE_H_
 #define LBA_DEVICE_H_
