@@ -215,7 +215,8 @@ const char* lba_strerror(int code);
  * The numeric result never depends on this choice; it is exposed for benchmarking reports. */
 typedef struct {
     int32_t kernel;        /* 0: scaled-domain FP32-carrier kernel, 1: general kernel            */
-    int32_t prod_mode;     /* kernel 0: 0 Q_prod is the identity, 1 flush only, 2 flush + clamp   */
+    int32_t prod_mode;     /* kernel 0: 0 Q_prod is the identity, 1 flush only, 2 flush + clamp,
+                              3 / 4 truncated mantissa (+ clamp), 5 / 6 nearest-even mantissa (+ clamp) */
     int32_t round;         /* rounding of Q_acc as executed                                       */
     int32_t tile_m, tile_n, tile_k;   /* workgroup tile                                           */
     int32_t thread_m, thread_n;       /* outputs per lane                                         */
@@ -223,6 +224,9 @@ typedef struct {
     int32_t valu_per_mac_x100;        /* kernel 0: full-rate VALU issue slots per MAC of the inner
                                          loop without the accumulator clamp, times 100 (a half-rate
                                          instruction counts as 2 slots); kernel 1: 0 (not modelled) */
+    int32_t tail_blocks;              /* > 0: mixed grid: grid_x counts grid_x - tail_blocks workgroups of
+                                         tile_m x tile_n plus tail_blocks workgroups of 32 x 32 (2 x 2 outputs
+                                         per lane) on the last rows; grid_y is 1                            */
 } lba_plan_info;
 
 int lba_plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc,

@@ -521,17 +521,16 @@ __device__ __forceinline__ void fast_tile(float (&acc)[TM][TN], float (&top)[TM]
 
 // AMODE 0: A is a row-major matrix of E4M3 codes and so is B (the default; no other case costs it anything).
 // AMODE 1: A may be an activation tensor read as im2col rows and either operand may use another code format.
-template <int TM, int TN, int BK, int PM, int RND, int ORDER, int AMODE = 0>
-__global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const KParams p) {
+// The work of one workgroup: the (16 TM) x (16 TN) tile of C at (m0, n0); smem holds two stages.
+template <int TM, int TN, int BK, int PM, int RND, int ORDER, int AMODE>
+__device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ smem, int m0, int n0) {
     static_assert(BK % 16 == 0, "chunk boundaries must fall on fixed positions of a k-tile");
     constexpr int BM = 16 * TM, BN = 16 * TN;
     constexpr int STAGE = BK * (BM + BN);
-    __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int tidb = tid - Stage<BN, BK>::kTailShift;       // B's pieces go to the last lanes
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
     // batch member blockIdx.z (strides are 0 for a single GEMM)
     const uint8_t* pA = p.A + (int64_t)blockIdx.z * p.stride_a;
     const uint8_t* pB = p.B + (int64_t)blockIdx.z * p.stride_b;
@@ -664,6 +663,30 @@ __device__ __forceinline__ void store_event_words(uint32_t* of_plane, uint32_t* 
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) { wof[i][j] = 0u; wuf[i][j] = 0u; }
+    }
+}
+
+template <int TM, int TN, int BK, int PM, int RND, int ORDER, int AMODE = 0>
+__global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const KParams p) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * BK * 16 * (TM + TN)];
+    fast_body<TM, TN, BK, PM, RND, ORDER, AMODE>(p, smem, blockIdx.x * 16 * TM, blockIdx.y * 16 * TN);
+}
+
+// Mixed grid for launches that would leave the last round of 64 x 64 workgroups half empty: the first
+// mix_main workgroups (rows below mix_m_main) take 64 x 64 tiles with 4 x 4 outputs per lane, the rest
+// covers the remaining rows with 32 x 32 tiles (2 x 2 per lane), a quarter of the work each, so that the
+// tail of the launch is cut four times finer.  Workgroups are numbered rows-first in both regions.
+template <int BK, int PM, int RND, int ORDER>
+__global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_mixed_kernel(const KParams p) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * BK * 16 * 8];
+    const int b = blockIdx.x;
+    if (b < p.mix_main) {                                      // uniform
+        const int by = b / p.mix_gx_main, bx = b - by * p.mix_gx_main;
+        fast_body<4, 4, BK, PM, RND, ORDER, 0>(p, smem, bx * 64, by * 64);
+    } else {
+        const int t = b - p.mix_main;
+        const int by = t / p.mix_gx_tail, bx = t - by * p.mix_gx_tail;
+        fast_body<2, 2, BK, PM, RND, ORDER, 0>(p, smem, p.mix_m_main + bx * 32, by * 32);
     }
 }
 

@@ -46,6 +46,9 @@ struct KParams {
     int32_t conv, cv_vec;    // cv_vec: cv_c % 16 == 0 and A 16-byte aligned (a 16-byte piece is one load)
     int32_t cv_h, cv_w, cv_c, cv_kw, cv_stride, cv_pad, cv_oh, cv_ow;
     uint64_t cv_magic_c, cv_magic_kw;   // ceil(2^40 / d): x / d == (x * magic) >> 40 for x < 2^24, d < 2^14
+    // mixed grid (lba_fast_mixed_kernel): workgroups below mix_main take 64 x 64 tiles of the rows below
+    // mix_m_main (mix_gx_main of them per tile column), the rest 32 x 32 tiles of the remaining rows
+    int32_t mix_main, mix_gx_main, mix_gx_tail, mix_m_main;
     int32_t prod_round;      // GEN: product mantissa narrower than a product of two operands
     int32_t prod_rne;        // GEN: its rounding
 };
@@ -59,6 +62,7 @@ struct Plan {
     int tm, tn, bk;          // outputs per lane (tm x tn), k-depth of a tile; tile = 16tm x 16tn
     int grid_x, grid_y;
     int valu_per_mac_x100;
+    int mix_tail;            // > 0: mixed grid with that many 32 x 32 workgroups after kp.mix_main 64 x 64 ones
     int amode;               // 1: A is read as im2col rows and / or an operand is not E4M3 (4 x 4 lane block only)
     KParams kp;
 };

@@ -16,6 +16,7 @@ __global__ void lba_fill_zero_kernel(float* C, int64_t n) {
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
     if (pl.kernel == KERNEL_FAST && pl.events) return launch_fast_bwd(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.amode) return launch_fast_amode(pl, st);   // the planner keeps these on 4 x 4
+    if (pl.kernel == KERNEL_FAST && pl.mix_tail > 0) return launch_fast_mixed(pl, st);
     if (pl.kernel == KERNEL_FAST) {
         if (pl.tm == 2 && pl.tn == 2) return launch_fast_22(pl, st);
         if (pl.tm == 2) return launch_fast_24(pl, st);
@@ -216,6 +217,7 @@ static int plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt 
     out->thread_m = pl.tm; out->thread_n = pl.tn;
     out->grid_x = pl.grid_x; out->grid_y = pl.grid_y;
     out->valu_per_mac_x100 = pl.valu_per_mac_x100;
+    out->tail_blocks = pl.mix_tail;
     return LBA_OK;
 }
 

@@ -15,6 +15,7 @@ hipError_t launch_fast_44(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_24(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_22(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_amode(const Plan& pl, hipStream_t st);
+hipError_t launch_fast_mixed(const Plan& pl, hipStream_t st);   // plans with mix_tail > 0
 // recompute call, scaled-domain kernel
 hipError_t launch_fast_bwd(const Plan& pl, hipStream_t st);
 // general kernel (forward and recompute)

@@ -160,6 +160,36 @@ static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int event
     }
 }
 
+// A launch of B equal workgroups on 256 CUs takes ceil(B / 256) rounds of one workgroup per CU (four
+// run side by side, but they share the CU's issue slots); when the last round is mostly empty, the rows
+// of that round are cut into 32 x 32 tiles instead (a quarter of the work each, at about 0.8 of the
+// efficiency), which the launch then finishes in quarter rounds.  Used when the model says 3 % or more.
+static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
+    p->mix_tail = 0;
+    if (p->kernel != KERNEL_FAST || p->events || p->amode || batch != 1) return;
+    if (p->prod_mode != PM_IDENT && p->prod_mode != PM_FLUSH && p->prod_mode != PM_FLUSH_CLAMP) return;
+    const int64_t gx = (M + 63) / 64, gy = (N + 63) / 64, blocks = gx * gy;
+    if (blocks <= 256 || blocks > 256 * 16) return;
+    const int64_t rounds = blocks / 256;
+    const int64_t gx_main = (rounds * 256) / gy;               // whole tile rows inside the full rounds
+    if (gx_main < 1 || gx_main >= gx) return;
+    const int64_t m_main = gx_main * 64;
+    const int64_t gx_tail = (M - m_main + 31) / 32, gy_tail = (N + 31) / 32, tail = gx_tail * gy_tail;
+    if (gx_main * gy + tail > 2147483647LL) return;
+    double plain = (double)((blocks + 255) / 256);
+    if (p->tm == 2 && p->tn == 4) plain = 0.5 * (double)((2 * blocks + 255) / 256) / 0.95;   // the 32 x 64 choice
+    const double mixed = (double)(gx_main * gy) / 256.0 + (double)((tail + 255) / 256) * 0.25 / 0.8;
+    if (mixed > 0.97 * plain) return;
+    p->mix_tail = (int)tail;
+    p->tm = 4; p->tn = 4;
+    p->kp.mix_main = (int32_t)(gx_main * gy);
+    p->kp.mix_gx_main = (int32_t)gx_main;
+    p->kp.mix_gx_tail = (int32_t)gx_tail;
+    p->kp.mix_m_main = (int32_t)m_main;
+    p->grid_x = (int)(gx_main * gy + tail);
+    p->grid_y = 1;
+}
+
 int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_qfmt& qa_in,
               int order, int events, Plan* out, int64_t batch, const InSpec* in_spec, bool conv) {
     const InSpec& in = in_spec ? *in_spec : e4m3_spec();
@@ -271,6 +301,7 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     const int64_t bm = 16 * p.tm, bn = 16 * p.tn;
     p.grid_x = (int)((M + bm - 1) / bm);
     p.grid_y = (int)((N + bn - 1) / bn);
+    plan_mixed_grid(M, N, batch, &p);
     *out = p;
     return LBA_OK;
 }

@@ -224,7 +224,7 @@ def test_every_lane_block(ref):
     # output counts that select each lane block of the fast kernel (2x2, 2x4, 4x4), ragged on both
     # sides, both roundings and both orders; all outputs compared
     rng = np.random.default_rng(70)
-    for (M, N, K), want_tile in (((130, 70, 70), (32, 32)), ((1500, 1530, 70), (32, 64)), ((2100, 2110, 70), (64, 64))):
+    for (M, N, K), want_tile in (((130, 70, 70), (32, 32)), ((1530, 2045, 70), (32, 64)), ((2100, 2110, 70), (64, 64))):
         A = rand_codes(rng, (M, K), 3, 12)
         B = rand_codes(rng, (N, K), 3, 12)
         for (qp, qa), rnd, order in itertools.product([FMT_PAPER[1], FMT_PAPER[3], FMT_PAPER[4]], (0, 1), (0, 1)):
@@ -461,3 +461,24 @@ def test_operand_code_formats(ref):
     assert lb.lba_gemm_in(a, b, c, 40, 30, 50, (3, 4, -32), (3, 4, -32), (5, 7, 120, 0), (4, 7, 7, 0)) == lb.ERR_FORMAT   # folded bias 190
     assert lb.lba_gemm_bwd_in(a, b, c, c, None, 40, 30, 50, (3, 4, 3), (3, 4, 3), (5, 7, 15, 0), (4, 7, 7, 0), order=1) == lb.ERR_UNSUPPORTED
     torch.cuda.synchronize()
+
+
+def test_mixed_grid(ref):
+    # launches whose last round of 64 x 64 workgroups would be mostly empty finish their last rows with
+    # 32 x 32 workgroups: both regions, their seam and the ragged edges against the oracle
+    rng = np.random.default_rng(130)
+    mixed = 0
+    for (M, N, K) in [(64 * 300 + 17, 60, 100), (64 * 392, 64, 40), (64 * 150 + 33, 130, 64)]:
+        A = rand_codes(rng, (M, K), 3, 12); B = rand_codes(rng, (N, K), 3, 12)
+        for (qp, qa), rnd, order in itertools.product([FMT_PAPER[0], FMT_PAPER[2], FMT_PAPER[4], FMT_SWEEP[4]], (0, 1), (0, 1)):
+            qpf, qaf = qp + (rnd,), qa + (rnd,)
+            plan = lb.lba_plan_query(M, N, K, qpf, qaf, order)
+            assert plan["kernel"] == 1 or (plan["tail_blocks"] > 0 and plan["grid_y"] == 1), plan
+            mixed += plan["kernel"] == 0
+            check(ref, A, B, qpf, qaf, "mixed grid", order=order)
+    assert mixed >= 36
+    # not used where it cannot help: exact multiples of a round, tiny and huge grids, the recompute call
+    assert lb.lba_plan_query(64 * 256, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
+    assert lb.lba_plan_query(64 * 40, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
+    assert lb.lba_plan_query(64 * 12544, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
+    assert lb.lba_plan_query(64 * 300, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), 0, 1)["tail_blocks"] == 0
