@@ -25,10 +25,10 @@ if ROOT not in sys.path:
 # 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz = 78.6e12 full-rate VALU lane-ops per second: the
 # rate behind the published 157.3 TFLOP/s FP32 vector peak (an FMA counts two flops).
 PEAK_LANE_OPS = 256 * 4 * 32 * 2.4e9
-# HBM bytes per launch of the dominant kernel of the default workload (the 42 launches of the 4x4 lane
-# block), from the calibrated rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/lba_fast_kernel_resnet50_sweep.md: FETCH_SIZE 1165029.9 KiB x 2.000 + WRITE_SIZE 2641312.6 KiB.
-RESNET50_TRAFFIC_BYTES_PER_LAUNCH = (2.0 * 1165029.875 + 2641312.625) * 1024 / 42
+# HBM bytes per launch of the dominant kernel of the default workload (the 42 launches of the mixed-grid
+# kernel), from the calibrated rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
+# profiles/lba_fast_kernel_resnet50_sweep.md: FETCH_SIZE 875129.9 KiB x 2.000 + WRITE_SIZE 1173244.3 KiB.
+RESNET50_TRAFFIC_BYTES_PER_LAUNCH = (2.0 * 875129.9375 + 1173244.25) * 1024 / 42
 PROD_FMT = (5, 7, 15)
 ACC_FMT = (4, 7, 7)
 
@@ -233,7 +233,7 @@ def main():
             ms = ev[s][i][0].elapsed_time(ev[s][i][1])
             per_layer_ms[i] += ms / args.steps
             p = l["plan"]
-            key = (p["kernel"], p["prod_mode"], p["round"], p["thread_m"], p["thread_n"], p["tile_k"])
+            key = (p["kernel"], p["prod_mode"], p["round"], p["thread_m"], p["thread_n"], p["tile_k"], p.get("tail_blocks", 0) > 0)
             g = groups.setdefault(key, dict(ms=0.0, macs=0, launches=0, bytes=0, ops=p["valu_per_mac_x100"] / 100.0))
             g["ms"] += ms
             g["macs"] += l["macs"]
@@ -252,7 +252,7 @@ def main():
         "frac": achieved / PEAK_LANE_OPS,
         "traffic": RESNET50_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "resnet50" and rnd == 0 and order == 0 and not args.bwd and not args.grad) else None,
         "kernel": ("lba_grad_kernel<%s>" % args.grad) if args.grad else "lba_%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (
-            ("fast_bwd" if args.bwd else "fast") if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
+            ("fast_bwd" if args.bwd else ("fast_mixed" if dom_key[6] else "fast")) if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
             "rne" if dom_key[2] else "floor"),
         "algorithmic_bytes": dom["bytes"] / dom["launches"],
         "valu_slots_per_mac": dom["ops"], "avg_launch_ms": dom["ms"] / dom["launches"],
