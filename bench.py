@@ -105,8 +105,8 @@ def main():
         e, m = (int(v) for v in args.acc.split(","))
         acc_fmt = (e, m, 2 ** (e - 1) - 1)
     in_fmt = tuple(int(v) for v in args.in_fmt.split(",")) if args.in_fmt else None
-    if in_fmt and (args.bwd or args.grad):
-        raise SystemExit("bench.py: --in-fmt times the forward call only")
+    if in_fmt and (args.grad or (args.bwd and order == 1)):
+        raise SystemExit("bench.py: --in-fmt times lba_gemm_in or lba_gemm_bwd_in (sequential order)")
     if args.implicit and (in_fmt or args.bwd or args.grad):
         raise SystemExit("bench.py: --implicit times the forward call on E4M3 operands only")
     layers = inputs.make_conv_workload(args.workload, dev) if args.implicit else inputs.make_workload(args.workload, dev, in_fmt=in_fmt)
@@ -116,7 +116,10 @@ def main():
         if in_fmt:                                          # biases stay in real units: the library folds the flex biases
             l["qp"], l["qa"] = PROD_FMT + (rnd,), acc_fmt + (rnd,)
             l["fa"], l["fb"] = in_fmt + (l["ta"],), in_fmt + (l["tb"],)
-            l["plan"] = lb.lba_plan_query_in(l["M"], l["N"], l["K"], l["fa"], l["fb"], l["qp"], l["qa"], order, 0)
+            l["plan"] = lb.lba_plan_query_in(l["M"], l["N"], l["K"], l["fa"], l["fb"], l["qp"], l["qa"], order, 1 if args.bwd else 0)
+            if args.bwd and args.of_only:
+                fwd = lb.lba_plan_query_in(l["M"], l["N"], l["K"], l["fa"], l["fb"], l["qp"], l["qa"], order, 0)
+                l["plan"] = dict(l["plan"], valu_per_mac_x100=fwd["valu_per_mac_x100"])
         else:
             l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], PROD_FMT, acc_fmt, rnd)
             l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, 1 if args.bwd else 0)
@@ -168,7 +171,11 @@ def main():
             uf2_buf = torch.empty(w2max, dtype=torch.int32, device=dev)
 
         def launch(l):
-            if order == 1:
+            if in_fmt:
+                rc = lb.lba_gemm_bwd_in(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
+                                        None if args.of_only else uf_buf.data_ptr(), l["M"], l["N"], l["K"],
+                                        l["fa"], l["fb"], l["qp"], l["qa"], order, stream)
+            elif order == 1:
                 rc = lb.lba_gemm_bwd_chunked(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
                                              uf_buf.data_ptr(), of2_buf.data_ptr(), uf2_buf.data_ptr(),
                                              l["M"], l["N"], l["K"], l["qp"], l["qa"], stream)

@@ -9,8 +9,13 @@ hipError_t launch_fast_bwd(const Plan& pl, hipStream_t st) {
     if (pl.amode) {                                        // im2col rows / other operand formats: sequential order only
 #define LBA_BWD1(PM, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, LBA_ORDER_SEQ, UF, 1>), grid, block, 0, st, pl.kp)
         if (pl.order != LBA_ORDER_SEQ) return hipErrorInvalidValue;
-        if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD1(PM_FLUSH, true); else LBA_BWD1(PM_FLUSH, false); }
-        else                          { if (uf) LBA_BWD1(PM_FLUSH_CLAMP, true); else LBA_BWD1(PM_FLUSH_CLAMP, false); }
+        switch (pl.prod_mode) {
+            case PM_FLUSH:       if (uf) LBA_BWD1(PM_FLUSH, true); else LBA_BWD1(PM_FLUSH, false); break;
+            case PM_FLUSH_CLAMP: if (uf) LBA_BWD1(PM_FLUSH_CLAMP, true); else LBA_BWD1(PM_FLUSH_CLAMP, false); break;
+            case PM_TRUNC:       if (uf) LBA_BWD1(PM_TRUNC, true); else LBA_BWD1(PM_TRUNC, false); break;
+            case PM_TRUNC_CLAMP: if (uf) LBA_BWD1(PM_TRUNC_CLAMP, true); else LBA_BWD1(PM_TRUNC_CLAMP, false); break;
+            default: return hipErrorInvalidValue;
+        }
 #undef LBA_BWD1
         return hipGetLastError();
     }

@@ -730,10 +730,10 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
 
     // kc_up / up: the same product and accumulator moved up by 2^60, where neither can flush
     float kc = p.kc, rof = p.rof_a, rofp = p.rof_p, kc_up = p.kc * 0x1p60f, up = 0x1p60f;
-    uint32_t mask = p.mask_a;
-    asm volatile("" : "+v"(kc), "+v"(rof), "+v"(rofp), "+v"(mask), "+v"(kc_up), "+v"(up));
+    uint32_t mask = p.mask_a, maskp = p.mask_p;
+    asm volatile("" : "+v"(kc), "+v"(rof), "+v"(rofp), "+v"(mask), "+v"(maskp), "+v"(kc_up), "+v"(up));
     FastConst fc;
-    fc.kc = kc; fc.rof = rof; fc.rofp = rofp; fc.mask = mask; fc.half = 0u; fc.sh = p.sh_a; fc.maskp = p.mask_p; fc.halfp = p.half_p; fc.shp = p.sh_p;
+    fc.kc = kc; fc.rof = rof; fc.rofp = rofp; fc.mask = mask; fc.half = 0u; fc.sh = p.sh_a; fc.maskp = maskp; fc.halfp = p.half_p; fc.shp = p.sh_p;
     float thresh = p.fast_thresh;
     asm volatile("" : "+v"(thresh));
 
@@ -788,7 +788,13 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j) q[i][j] = a[i] * b[j];
-                if (PM == PM_FLUSH_CLAMP) {
+                if (PM == PM_TRUNC || PM == PM_TRUNC_CLAMP) {          // Q_prod's mantissa, by truncation
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j) q[i][j] = __uint_as_float(__float_as_uint(q[i][j]) & maskp);
+                }
+                if (PM == PM_FLUSH_CLAMP || PM == PM_TRUNC_CLAMP) {
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -836,7 +842,13 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) q[i][j] = a[i] * b[j];            // flushed below Q_prod's R_UF
-            if (PM == PM_FLUSH_CLAMP) {
+            if (PM == PM_TRUNC || PM == PM_TRUNC_CLAMP) {              // a non-zero product stays non-zero
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) q[i][j] = __uint_as_float(__float_as_uint(q[i][j]) & maskp);
+            }
+            if (PM == PM_FLUSH_CLAMP || PM == PM_TRUNC_CLAMP) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll

@@ -228,8 +228,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     const int c_a_dom = nouf_a ? -60 : bae - 126;
 
     // a narrower product mantissa is one bit mask (truncation) or bfe / add3 / and (nearest-even) on the
-    // exact FP32 product (forward call only)
-    bool fast = !prod_round || !events;
+    // exact FP32 product (the recompute call: truncation only)
+    bool fast = !prod_round || !events || (qp.round == LBA_ROUND_FLOOR && order == LBA_ORDER_SEQ);
     // the recompute call has a scaled-domain kernel for floor rounding when Q_prod can underflow
     // (its product-underflow test is the multiply's flush); anything else takes the general kernel
     if (events && (qa.round != LBA_ROUND_FLOOR || !flush)) fast = false;
@@ -275,7 +275,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         kp.prod_rne = (qp.round == LBA_ROUND_RNE) ? 1 : 0;
         p.valu_per_mac_x100 = 0;                           // filled by the launcher's table
     }
-    p.amode = (conv || in.ea != 4 || in.eb != 4 || p.prod_mode == PM_RNE || p.prod_mode == PM_RNE_CLAMP) ? 1 : 0;
+    p.amode = (conv || in.ea != 4 || in.eb != 4 || p.prod_mode == PM_RNE || p.prod_mode == PM_RNE_CLAMP ||
+               (events && (p.prod_mode == PM_TRUNC || p.prod_mode == PM_TRUNC_CLAMP))) ? 1 : 0;
     pick_tile(M, N, batch, p.kernel, p.events, p.prod_mode, p.amode, &p.tm, &p.tn, &p.bk);
     kp.batch = 1;
     kp.fast_thresh = -1.0f;

@@ -111,6 +111,8 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     assert q(64, 64, 64, (5, 7, 40, 1), (4, 7, -9, 1))["kernel"] == 1     # products far below R_UF of Q_acc
     assert q(64, 64, 64, (5, 4, 15, 1), (4, 7, 7, 1))["prod_mode"] == 6   # product mantissa rounded to nearest (and clamped): still the scaled kernel
     assert q(64, 64, 64, (5, 4, 15, 1), (4, 7, 7, 1), with_masks=1)["kernel"] == 1   # ... the recompute call: general kernel
+    assert q(64, 64, 64, (5, 4, 15, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 0   # truncated products: scaled recompute kernel
+    assert q(64, 64, 64, (5, 4, 15, 0), (4, 7, 7, 0), order=1, with_masks=1)["kernel"] == 1   # ... not for the chunked order
     assert q(64, 64, 64, (5, 4, 15, 0), (4, 7, 7, 0))["prod_mode"] == 4   # ... truncated (and clamped): a bit mask in the scaled kernel
     assert q(64, 64, 64, (6, 4, 20, 0), (4, 7, 7, 0))["prod_mode"] == 3   # ... truncated, cannot saturate
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 3, 7, 0))["kernel"] == 0      # floor is exact at any M
@@ -122,7 +124,6 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), with_masks=1)["kernel"] == 1
     assert q(64, 64, 64, (6, 7, 20, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 1
-    assert q(64, 64, 64, (5, 4, 15, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 1
     # chunked order, forward and recompute
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=1)["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 1), (5, 3, 15, 1), order=1)["kernel"] == 1
