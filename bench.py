@@ -77,6 +77,8 @@ def main():
     ap.add_argument("--bwd", action="store_true",
                     help="time lba_gemm_bwd (forward chain + both event planes) instead of lba_gemm")
     ap.add_argument("--of-only", action="store_true", help="with --bwd: ask for the overflow plane only")
+    ap.add_argument("--diff", type=float, default=None, metavar="EPS2",
+                    help="with --bwd: time lba_gemm_bwd_diff (C + the DIFF plane for that threshold) instead")
     ap.add_argument("--grad", default=None, choices=["identity", "immediate", "recursive"],
                     help="time lba_grad (dX and dW with that estimator's coefficients; the OF planes / last-overflow "
                          "indices are computed before the timed region) instead of lba_gemm; 2 MACs per forward MAC")
@@ -105,6 +107,9 @@ def main():
         e, m = (int(v) for v in args.acc.split(","))
         acc_fmt = (e, m, 2 ** (e - 1) - 1)
     in_fmt = tuple(int(v) for v in args.in_fmt.split(",")) if args.in_fmt else None
+    if args.diff is not None and (not args.bwd or args.of_only or args.in_fmt or args.grad):
+        raise SystemExit("bench.py: --diff goes with --bwd alone (E4M3 operands)")
+    with_masks = 2 if args.diff is not None else (1 if args.bwd else 0)
     if in_fmt and (args.grad or (args.bwd and order == 1)):
         raise SystemExit("bench.py: --in-fmt times lba_gemm_in or lba_gemm_bwd_in (sequential order)")
     if args.implicit and (in_fmt or args.bwd or args.grad):
@@ -122,7 +127,7 @@ def main():
                 l["plan"] = dict(l["plan"], valu_per_mac_x100=fwd["valu_per_mac_x100"])
         else:
             l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], PROD_FMT, acc_fmt, rnd)
-            l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, 1 if args.bwd else 0)
+            l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, with_masks)
             if args.bwd and args.of_only and order == 0:
                 # priced like the forward call: k-tiles that cannot overflow run the forward tile (3 slots per MAC);
                 # tiles that can add a clamp, a compare and a carry-in add per MAC, which this count leaves out
@@ -171,7 +176,10 @@ def main():
             uf2_buf = torch.empty(w2max, dtype=torch.int32, device=dev)
 
         def launch(l):
-            if in_fmt:
+            if args.diff is not None:
+                rc = lb.lba_gemm_bwd_diff(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
+                                          l["M"], l["N"], l["K"], l["qp"], l["qa"], order, args.diff, stream)
+            elif in_fmt:
                 rc = lb.lba_gemm_bwd_in(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
                                         None if args.of_only else uf_buf.data_ptr(), l["M"], l["N"], l["K"],
                                         l["fa"], l["fb"], l["qp"], l["qa"], order, stream)
@@ -259,7 +267,7 @@ def main():
         "frac": achieved / PEAK_LANE_OPS,
         "traffic": RESNET50_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "resnet50" and rnd == 0 and order == 0 and not args.bwd and not args.grad) else None,
         "kernel": ("lba_grad_kernel<%s>" % args.grad) if args.grad else "lba_%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (
-            ("fast_bwd" if args.bwd else ("fast_mixed" if dom_key[6] else "fast")) if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
+            ("fast_diff" if args.diff is not None else "fast_bwd" if args.bwd else ("fast_mixed" if dom_key[6] else "fast")) if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
             "rne" if dom_key[2] else "floor"),
         "algorithmic_bytes": dom["bytes"] / dom["launches"],
         "valu_slots_per_mac": dom["ops"], "avg_launch_ms": dom["ms"] / dom["launches"],
@@ -284,7 +292,7 @@ def main():
                                 "bert": "BERT-base linears, 4096 tokens", "gemm4096": "4096^3 GEMM",
                                 "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}[args.workload],
                    "macs_per_step": total_macs, "qprod": "M7E5 b=15", "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
-                   "call": ("lba_grad, %s estimator: dX and dW (2 masked MACs per forward MAC)" % args.grad) if args.grad else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else ("lba_gemm_bwd (C + OF plane)" if args.of_only else "lba_gemm_bwd (C + OF and UF planes)")) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
+                   "call": ("lba_grad, %s estimator: dX and dW (2 masked MACs per forward MAC)" % args.grad) if args.grad else ("lba_gemm_bwd_diff (C + DIFF plane, eps2 = %g)" % args.diff) if args.diff is not None else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else ("lba_gemm_bwd (C + OF plane)" if args.of_only else "lba_gemm_bwd (C + OF and UF planes)")) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
                    "conv": "implicit im2col from NHWC activations (lba_conv2d)" if args.implicit else "operand A is the written-out im2col matrix",
                    "operands": ("E%dM%d codes with per-tensor flex bias (lba_gemm_in)" % in_fmt) if in_fmt else "E4M3"},
         "roofline": roofline,

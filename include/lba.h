@@ -151,6 +151,24 @@ int lba_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C,
                  int64_t M, int64_t N, int64_t K,
                  lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream);
 
+/* The DIFF plane of the same re-run (Sec. 4, "Immediate / DIFF"; App. D, STE^DIFF): with
+ * z_k = FMAq(x_k, w_k, S_k), the paper's estimator is STE^DIFF_k = [ |z_k - S_k| / (|x_k w_k| + eps1) > eps2 ]:
+ * zero on overflow, product underflow and full swamping, whatever the FMAq does inside.  The paper
+ * gives no values for its two constants and adds eps1 only to keep the denominator valid; this call
+ * takes eps1 -> 0+ (a zero product has ratio 0) and eps2 from the caller:
+ *   DIFF_k = 1 - STE^DIFF_k = [ |S_{k+1} - S_k| <= eps2 * |x_k w_k| ]      (exact reals; x_k w_k un-quantized)
+ * written with the layout and polarity of the OF plane (1 = the gradient of that product pair is
+ * blocked), so lba_grad (LBA_STE_IMMEDIATE_OF), lba_ste_plane and lba_last_overflow take it in place of
+ * an OF plane.  eps2 = 0 gives the "no change" plane [ S_{k+1} == S_k ].  Either order; under
+ * LBA_ORDER_CHUNK16 the bits are those of the first-level steps (S_k is the sum of k's own chunk; the
+ * second level has no product pair).  C may be NULL, else it equals lba_gemm's bit for bit.
+ * eps2 must be 0, or in [2^-32, 16] with at most 12 significant bits (so that eps2 * |x w| is exact in
+ * the kernel's arithmetic): anything else is LBA_ERR_FORMAT.  Operand scales: the ratio is scale-free,
+ * fold them into the biases as for lba_gemm. */
+int lba_gemm_bwd_diff(const uint8_t* A, const uint8_t* B, float* C, uint32_t* diff_mask,
+                      int64_t M, int64_t N, int64_t K,
+                      lba_qfmt qprod, lba_qfmt qacc, int32_t order, float eps2, void* hip_stream);
+
 /* Number of uint32 words in one event plane: ceil(K / 32) * M * N (0 if any size is <= 0). */
 size_t lba_mask_words(int64_t M, int64_t N, int64_t K);
 
@@ -229,6 +247,7 @@ typedef struct {
                                          per lane) on the last rows; grid_y is 1                            */
 } lba_plan_info;
 
+/* with_masks: 0 the forward call, 1 the recompute call with event planes, 2 lba_gemm_bwd_diff. */
 int lba_plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc,
                    int32_t order, int32_t with_masks, lba_plan_info* out);
 

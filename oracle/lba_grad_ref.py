@@ -18,12 +18,15 @@ estimators give every step k of every output (m, n) a coefficient c[m, n, k] in 
                 chunked order: the path of step k is the rest of its chunk's chain, then the
                 second-level adds of chunks j >= k // 16 (App. D, last paragraph: the tree of Fig. 1
                 with the arrows reversed)
+  immediate/DIFF c_k = STE^DIFF_k = 1 - DIFF_k         (Sec. 4: zero on overflow, underflow and full swamping,
+                detected as |z - s| <= eps2 |x w|; lba_ref.gemm_diff; first-level steps under either order)
 """
 import numpy as np
 
 from . import lba_ref
 
 STE_IDENTITY, STE_IMMEDIATE_OF, STE_RECURSIVE_OF = 0, 1, 2
+STE_IMMEDIATE_DIFF = 4         # oracle-side name only: the library consumes the DIFF plane like an OF plane
 
 
 def decode_table():
@@ -46,12 +49,15 @@ def last_overflow(of_plane, K):
     return idx.max(axis=2).astype(np.int32) if K > 0 else np.full(of.shape[:2], -1, dtype=np.int32)
 
 
-def coefficients(A, B, qprod, qacc, ste, order=lba_ref.ORDER_SEQ):
-    """bool [M, N, K] coefficient tensor c of the chosen estimator."""
+def coefficients(A, B, qprod, qacc, ste, order=lba_ref.ORDER_SEQ, eps2=None):
+    """bool [M, N, K] coefficient tensor c of the chosen estimator (eps2: the DIFF threshold)."""
     M, K = A.shape
     N = B.shape[0]
     if ste == STE_IDENTITY:
         return np.ones((M, N, K), dtype=bool)
+    if ste == STE_IMMEDIATE_DIFF:
+        _, diff = lba_ref.gemm_diff(A, B, qprod, qacc, eps2, order=order)
+        return ~unpack_plane(diff, K)
     if order == lba_ref.ORDER_SEQ:
         _, of, _ = lba_ref.gemm_bwd(A, B, qprod, qacc, order=order)
         ok = ~unpack_plane(of, K)

@@ -26,6 +26,13 @@
 //   * per-step event bits for the fine-grained gradient estimators (Sec. 4, App. D, STE^OF):
 //       OF_k = [ |Q_prod(x_k w_k) + S_k| >= R_OF^acc ]
 //       UF_k = [ x_k w_k != 0 and Q_prod(x_k w_k) == 0 ]  or  [ t_k != 0 and |t_k| < R_UF^acc ]
+//     and for STE^DIFF (Sec. 4 "Immediate / DIFF", App. D): with z = FMAq(x_k, w_k, S_k),
+//       STE^DIFF_k = [ |z - S_k| / (|x_k w_k| + eps1) > eps2 ]
+//     read with eps1 -> 0+ (the paper adds it only to keep the denominator valid: a zero product
+//     gives the ratio 0), i.e. STE^DIFF_k = [ |z - S_k| > eps2 * |x_k w_k| ] over exact reals, with
+//     x_k w_k the un-quantized product.  The plane holds DIFF_k = 1 - STE^DIFF_k (1 = gradient
+//     blocked, the polarity of OF_k).  eps2 is a parameter of the call; eps2 = 0 is the "no change"
+//     plane [ z == S_k ].
 //
 // Inputs are OCP FP8 E4M3 codes (1 sign, 4 exponent, 3 mantissa bits, exponent bias 7, no inf):
 //   e == 0: (-1)^s * m * 2^-9 ;  e > 0: (-1)^s * (8+m) * 2^(e-10).  The two NaN codes (0x7f, 0xff)
@@ -57,7 +64,7 @@ typedef unsigned _BitInt(320) u320;
 enum { ROUND_FLOOR = 0, ROUND_RNE = 1, FLAG_NO_UNDERFLOW = 0x100 };
 enum { ORDER_SEQ = 0, ORDER_CHUNK16 = 1 };
 enum { REF_OK = 0, REF_ERR_NULL = 1, REF_ERR_SHAPE = 2, REF_ERR_FORMAT = 3, REF_ERR_UNSUPPORTED = 4 };
-enum { EV_OF = 1, EV_UF = 2 };
+enum { EV_OF = 1, EV_UF = 2, EV_DIFF = 4 };
 
 struct Fmt { int32_t E, M, b, round; };
 
@@ -157,9 +164,14 @@ template <class T> inline float to_float(SVal<T> v, int L) {
     return v.neg ? -f : f;
 }
 
+// eps2 of STE^DIFF as an exact dyadic number m * 2^e (m = 0: the "no change" limit)
+struct DiffEps { bool on; uint64_t m; int e; };
+const DiffEps kNoDiff = {false, 0, 0};
+
 template <class T> struct Chain {
     Quant<T> qp, qa;
     int L;
+    DiffEps eps = kNoDiff;
     Dec ta[256], tb[256];                              // decoded operand codes
     void set_inputs(const InFmt& fa, const InFmt& fb) {
         for (int c = 0; c < 256; ++c) { ta[c] = decode_in((uint8_t)c, fa); tb[c] = decode_in((uint8_t)c, fb); }
@@ -175,10 +187,21 @@ template <class T> struct Chain {
         p.mag = qp.apply(p.mag, &ev_p);
         if (p.mag == 0) p.neg = false;
         if (prod_nonzero && p.mag == 0) ev |= EV_UF;   // product underflow
+        T raw = (T)(uint32_t)(a.sig * b.sig) << (a.lsb + b.lsb - L);   // |x w|, before Q_prod
+        SVal<T> S_old = S;
         SVal<T> t = add_exact(p, S);
         S.mag = qa.apply(t.mag, &ev_a);
         S.neg = (S.mag != 0) && t.neg;
         ev |= ev_a;                                    // accumulator overflow / underflow
+        if (eps.on) {
+            // STE^DIFF = [ |z - S_old| > eps2 |x w| ]; both sides scaled to integers of one unit
+            SVal<T> minus_old = S_old;
+            if (minus_old.mag != 0) minus_old.neg = !minus_old.neg;
+            T d = add_exact(S, minus_old).mag;
+            T rhs = raw * (T)eps.m;                    // raw has at most 12 bits, eps.m at most 53
+            if (eps.e >= 0) rhs <<= eps.e; else d <<= -eps.e;
+            if (!(d > rhs)) ev |= EV_DIFF;
+        }
         return ev;
     }
     // second-level step of chunked accumulation: T <- Q_acc(T + c)
@@ -197,7 +220,7 @@ inline void set_bit(uint32_t* plane, int64_t M, int64_t N, int64_t m, int64_t n,
 
 template <class T>
 void gemm_rows(const Chain<T>& ch, const uint8_t* A, const uint8_t* B, float* C,
-               uint32_t* of_mask, uint32_t* uf_mask, uint32_t* of2_mask, uint32_t* uf2_mask,
+               uint32_t* of_mask, uint32_t* uf_mask, uint32_t* of2_mask, uint32_t* uf2_mask, uint32_t* diff_mask,
                int64_t M, int64_t N, int64_t K, int order, int64_t m_lo, int64_t m_hi) {
     for (int64_t m = m_lo; m < m_hi; ++m) {
         const uint8_t* a = A + m * K;
@@ -209,6 +232,7 @@ void gemm_rows(const Chain<T>& ch, const uint8_t* A, const uint8_t* B, float* C,
                     int ev = ch.step(S, a[k], b[k]);
                     if (of_mask && (ev & EV_OF)) set_bit(of_mask, M, N, m, n, k);
                     if (uf_mask && (ev & EV_UF)) set_bit(uf_mask, M, N, m, n, k);
+                    if (diff_mask && (ev & EV_DIFF)) set_bit(diff_mask, M, N, m, n, k);
                 }
             } else {
                 SVal<T> Tacc = {false, 0};
@@ -219,6 +243,7 @@ void gemm_rows(const Chain<T>& ch, const uint8_t* A, const uint8_t* B, float* C,
                         int ev = ch.step(S, a[k], b[k]);
                         if (of_mask && (ev & EV_OF)) set_bit(of_mask, M, N, m, n, k);
                         if (uf_mask && (ev & EV_UF)) set_bit(uf_mask, M, N, m, n, k);
+                        if (diff_mask && (ev & EV_DIFF)) set_bit(diff_mask, M, N, m, n, k);
                     }
                     int ev2 = ch.step2(Tacc, S);
                     if (of2_mask && (ev2 & EV_OF)) set_bit(of2_mask, M, N, m, n, j);
@@ -246,15 +271,17 @@ template <class T>
 int run_gemm(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
              uint32_t* of2_mask, uint32_t* uf2_mask,
              int64_t M, int64_t N, int64_t K, const Fmt& qp, const Fmt& qa, int order, int L,
-             int nthreads, const InFmt& ia, const InFmt& ib) {
+             int nthreads, const InFmt& ia, const InFmt& ib, uint32_t* diff_mask, DiffEps eps) {
     Chain<T> ch;
     ch.L = L;
+    ch.eps = eps;
     ch.qp.init(qp, L);
     ch.qa.init(qa, L);
     ch.set_inputs(ia, ib);
     int64_t W = (K + 31) / 32;
     if (of_mask) std::memset(of_mask, 0, sizeof(uint32_t) * (size_t)(W * M * N));
     if (uf_mask) std::memset(uf_mask, 0, sizeof(uint32_t) * (size_t)(W * M * N));
+    if (diff_mask) std::memset(diff_mask, 0, sizeof(uint32_t) * (size_t)(W * M * N));
     int64_t W2 = ((K + 15) / 16 + 31) / 32;
     if (of2_mask) std::memset(of2_mask, 0, sizeof(uint32_t) * (size_t)(W2 * M * N));
     if (uf2_mask) std::memset(uf2_mask, 0, sizeof(uint32_t) * (size_t)(W2 * M * N));
@@ -262,7 +289,7 @@ int run_gemm(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, ui
     int nt = std::max(1, nthreads);
     nt = (int)std::min<int64_t>(nt, M);
     if (nt == 1) {
-        gemm_rows<T>(ch, A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, order, 0, M);
+        gemm_rows<T>(ch, A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, diff_mask, M, N, K, order, 0, M);
         return REF_OK;
     }
     // rows are split in contiguous slabs; two threads never touch the same output or mask word
@@ -270,7 +297,7 @@ int run_gemm(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, ui
     for (int t = 0; t < nt; ++t) {
         int64_t lo = M * t / nt, hi = M * (t + 1) / nt;
         pool.emplace_back([=, &ch]() {
-            gemm_rows<T>(ch, A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, order, lo, hi);
+            gemm_rows<T>(ch, A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, diff_mask, M, N, K, order, lo, hi);
         });
     }
     for (auto& th : pool) th.join();
@@ -280,17 +307,18 @@ int run_gemm(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, ui
 int gemm_entry(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
                uint32_t* of2_mask, uint32_t* uf2_mask,
                int64_t M, int64_t N, int64_t K, Fmt qp, Fmt qa, int order, int nthreads,
-               InFmt ia = kE4M3, InFmt ib = kE4M3) {
+               InFmt ia = kE4M3, InFmt ib = kE4M3, uint32_t* diff_mask = nullptr, DiffEps eps = kNoDiff) {
     if (M < 0 || N < 0 || K < 0) return REF_ERR_SHAPE;
     if (!fmt_ok(qp) || !fmt_ok(qa) || !infmt_ok(ia) || !infmt_ok(ib)) return REF_ERR_FORMAT;
     if (order != ORDER_SEQ && order != ORDER_CHUNK16) return REF_ERR_UNSUPPORTED;
     if (M * N > 0 && ((K > 0 && (!A || !B)))) return REF_ERR_NULL;
     int L, bits;
     span_of(qp, qa, &L, &bits, ia, ib);
+    if (eps.on) bits += 54 + std::abs(eps.e);          // room for the scaled sides of the DIFF comparison
     if (bits > 318) return REF_ERR_FORMAT;
     if (bits <= 126)
-        return run_gemm<u128>(A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, qp, qa, order, L, nthreads, ia, ib);
-    return run_gemm<u320>(A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, qp, qa, order, L, nthreads, ia, ib);
+        return run_gemm<u128>(A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, qp, qa, order, L, nthreads, ia, ib, diff_mask, eps);
+    return run_gemm<u320>(A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, qp, qa, order, L, nthreads, ia, ib, diff_mask, eps);
 }
 
 }  // namespace
@@ -316,6 +344,27 @@ int lba_ref_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_
                      int64_t M, int64_t N, int64_t K,
                      lba_ref_qfmt qprod, lba_ref_qfmt qacc, int32_t order, int32_t nthreads) {
     return gemm_entry(A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, cvt(qprod), cvt(qacc), order, nthreads);
+}
+
+// The DIFF plane (1 - STE^DIFF per step, first-level steps under either order) for a threshold
+// eps2 >= 0 given as a double; its exact value is used (any finite double is a dyadic number with an
+// odd integer mantissa below 2^53).
+int lba_ref_gemm_diff(const uint8_t* A, const uint8_t* B, float* C, uint32_t* diff_mask,
+                      int64_t M, int64_t N, int64_t K,
+                      lba_ref_qfmt qprod, lba_ref_qfmt qacc, int32_t order, double eps2, int32_t nthreads) {
+    if (!diff_mask && M * N * K > 0) return REF_ERR_NULL;
+    if (!(eps2 >= 0.0) || std::isinf(eps2)) return REF_ERR_FORMAT;
+    DiffEps eps = {true, 0, 0};
+    if (eps2 > 0.0) {
+        int e2;
+        double fr = std::frexp(eps2, &e2);
+        uint64_t mant = (uint64_t)std::ldexp(fr, 53);
+        int e = e2 - 53;
+        while ((mant & 1) == 0) { mant >>= 1; ++e; }
+        eps.m = mant; eps.e = e;
+    }
+    return gemm_entry(A, B, C, nullptr, nullptr, nullptr, nullptr, M, N, K, cvt(qprod), cvt(qacc), order, nthreads,
+                      kE4M3, kE4M3, diff_mask, eps);
 }
 
 typedef struct { int32_t exp_bits, man_bits, bias; } lba_ref_infmt;

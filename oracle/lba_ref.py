@@ -73,6 +73,10 @@ def lib():
                                        ctypes.c_void_p, ctypes.c_void_p,
                                        ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                        QFmt, QFmt, ctypes.c_int32, ctypes.c_int32]
+        L.lba_ref_gemm_diff.restype = ctypes.c_int
+        L.lba_ref_gemm_diff.argtypes = [u8p, u8p, ctypes.c_void_p, ctypes.c_void_p,
+                                        ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
+                                        QFmt, QFmt, ctypes.c_int32, ctypes.c_double, ctypes.c_int32]
         L.lba_ref_gemm_in.restype = ctypes.c_int
         L.lba_ref_gemm_in.argtypes = [u8p, u8p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                       ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, InFmt, InFmt,
@@ -215,6 +219,23 @@ def gemm_bwd(A, B, qprod, qacc, order=ORDER_SEQ, nthreads=None, level2=False):
     if level2:
         return C, of, uf, of2, uf2
     return C, of, uf
+
+
+def gemm_diff(A, B, qprod, qacc, eps2, order=ORDER_SEQ, nthreads=None):
+    """(C, DIFF plane): bit k of an output's words is 1 - STE^DIFF of step k (Sec. 4, App. D of the paper) for
+    the threshold eps2 >= 0 (eps1 -> 0+), first-level steps under either order; uint32 [ceil(K/32), M, N]."""
+    A = _u8(A)
+    B = _u8(B)
+    M, K = A.shape
+    N, K2 = B.shape
+    assert K == K2
+    C = np.empty((M, N), dtype=np.float32)
+    diff = np.empty(((K + 31) // 32, M, N), dtype=np.uint32)
+    rc = lib().lba_ref_gemm_diff(A.ctypes.data, B.ctypes.data, C.ctypes.data, diff.ctypes.data, M, N, K,
+                                 qprod, qacc, order, float(eps2), _threads(nthreads))
+    if rc != 0:
+        raise ValueError("lba_ref_gemm_diff error %d" % rc)
+    return C, diff
 
 
 def carrier_bits(qprod, qacc):

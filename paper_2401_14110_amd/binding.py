@@ -65,6 +65,8 @@ def lib():
         L.lba_gemm_bwd.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, i32, vp]
         L.lba_gemm_batched.restype = ctypes.c_int
         L.lba_gemm_batched.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, lba_qfmt, lba_qfmt, i32, vp]
+        L.lba_gemm_bwd_diff.restype = ctypes.c_int
+        L.lba_gemm_bwd_diff.argtypes = [vp, vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, i32, ctypes.c_float, vp]
         L.lba_gemm_bwd_chunked.restype = ctypes.c_int
         L.lba_gemm_bwd_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, vp]
         L.lba_mask_words_level2.restype = ctypes.c_size_t
@@ -140,6 +142,10 @@ def lba_gemm_batched(A, B, C, batch, stride_a, stride_b, stride_c, M, N, K, qpro
     return lib().lba_gemm_batched(A, B, C, batch, stride_a, stride_b, stride_c, M, N, K, qfmt(qprod),
                                   qfmt(qacc), order,
                                   ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_gemm_bwd_diff(A, B, C, diff_mask, M, N, K, qprod, qacc, order, eps2, hip_stream=None):
+    return lib().lba_gemm_bwd_diff(A, B, C, diff_mask, M, N, K, qfmt(qprod), qfmt(qacc), order, float(eps2), hip_stream)
 
 
 def lba_gemm_bwd_chunked(A, B, C, of_mask, uf_mask, of_mask2, uf_mask2, M, N, K, qprod, qacc, hip_stream=None):
@@ -271,6 +277,19 @@ def gemm_bwd(A, B, qprod, qacc, order=ORDER_SEQ, want_c=True, stream=None, want_
                               of.data_ptr() or None, (uf.data_ptr() or None) if want_uf else None,
                               M, N, K, qfmt(qprod), qfmt(qacc), order, _stream(stream)))
     return C, of, uf
+
+
+def gemm_bwd_diff(A, B, qprod, qacc, eps2, order=ORDER_SEQ, want_c=True, stream=None):
+    """Returns (C or None, DIFF plane [ceil(K/32), M, N] int32): bit k is 1 - STE^DIFF of step k."""
+    A, B = _ops(A, B)
+    M, K = A.shape
+    N = B.shape[0]
+    C = torch.empty((M, N), dtype=torch.float32, device=A.device) if want_c else None
+    diff = torch.empty(((K + 31) // 32, M, N), dtype=torch.int32, device=A.device)
+    _check(lib().lba_gemm_bwd_diff(A.data_ptr() or None, B.data_ptr() or None, (C.data_ptr() or None) if want_c else None,
+                                   diff.data_ptr() or None, M, N, K, qfmt(qprod), qfmt(qacc), order, float(eps2),
+                                   _stream(stream)))
+    return C, diff
 
 
 def gemm_bwd_chunked(A, B, qprod, qacc, want_c=True, stream=None, want_uf=True):

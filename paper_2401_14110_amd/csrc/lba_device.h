@@ -934,12 +934,133 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
     }
 }
 
+// Recompute call for the DIFF plane (Sec. 4 "Immediate / DIFF", App. D, eps1 -> 0+) in the scaled domain:
+// floor rounding, E4M3 operands, Q_prod without mantissa rounding, and an accumulator format narrow enough
+// (2^E + M + 1 <= 24, flush kept) that the difference of two of its sums is exact in FP32.  Per step:
+//   DIFF = [ |S' - S| <= eps2 * |x w| ],  both sides formed 2^60 above the accumulator's domain, where
+// neither can be flushed: S' - S is a multiple of the grid's unit below 2^24 units (exact), and
+// eps2 * |x w| has at most 12 + 8 significant bits (exact).  A product that Q_prod flushes leaves S' = S,
+// so the flushed multiply (zero) gives the right bit too.  Writes the plane through p.of_mask.
+template <int PM, int ORDER>
+__global__ void __launch_bounds__(256, 3) lba_fast_diff_kernel(const KParams p) {
+    constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
+    constexpr int STAGE = BK * (BM + BN);
+    __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
+
+    const int tid = threadIdx.x;
+    const int tx = tid & 15, ty = tid >> 4;
+    const int tidb = tid - Stage<BN, BK>::kTailShift;
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const uint8_t* pA = p.A + (int64_t)blockIdx.z * p.stride_a;
+    const uint8_t* pB = p.B + (int64_t)blockIdx.z * p.stride_b;
+    float* pC = p.C ? p.C + (int64_t)blockIdx.z * p.stride_c : nullptr;
+
+    const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
+    set_flush_f32();
+    set_round_zero();
+
+    float kc = p.kc, rof = p.rof_a, rofp = p.rof_p, up = 0x1p60f, ce = p.kc * 0x1p60f * p.diff_eps;
+    uint32_t mask = p.mask_a;
+    asm volatile("" : "+v"(kc), "+v"(rof), "+v"(rofp), "+v"(mask), "+v"(up), "+v"(ce));
+
+    float acc[TM][TN], accu[TM][TN], top[TM][TN];              // accu = acc * 2^60
+    uint32_t wdf[TM][TN], unused[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) { acc[i][j] = 0.0f; accu[i][j] = 0.0f; top[i][j] = 0.0f; wdf[i][j] = 0u; unused[i][j] = 0u; }
+
+    uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
+    const int ntiles = (p.K + BK - 1) / BK;
+
+    fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
+    fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
+    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, 4, 3, p.exp_a);
+    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, 4, 3, p.exp_b);
+    __syncthreads();
+
+    for (int t = 0; t < ntiles; ++t) {
+        const float* As = smem + (t & 1) * STAGE;
+        const float* Bs = As + BK * BM;
+        const bool more = (t + 1) < ntiles;
+        if (more) {
+            fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
+            fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
+        }
+#pragma unroll 4
+        for (int k = 0; k < BK; ++k) {
+            float a[TM], b[TN];
+            read_operands<TM, TN, BM, BN>(As, Bs, k, tx, ty, a, b);
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const float q0 = a[i] * b[j];                           // exact, or flushed below Q_prod's R_UF
+                    const float q = (PM == PM_FLUSH_CLAMP) ? med3(q0, -rofp, rofp) : q0;
+                    float tsum = __builtin_fmaf(q, kc, acc[i][j]);
+                    tsum = __uint_as_float(__float_as_uint(tsum) & mask);
+                    tsum = med3(tsum, -rof, rof);
+                    const float su = tsum * up;
+                    const float d = su - accu[i][j];
+                    const float rhs = __builtin_fabsf(q0) * ce;
+                    const uint64_t blocked = __builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d) > rhs));
+                    acc[i][j] = tsum;
+                    accu[i][j] = su;
+                    asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wdf[i][j]) : "s"(blocked) : "vcc");
+                }
+            if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        float u = top[i][j] + acc[i][j];
+                        u = __uint_as_float(__float_as_uint(u) & mask);
+                        top[i][j] = med3(u, -rof, rof);
+                        acc[i][j] = 0.0f;
+                        accu[i][j] = 0.0f;
+                    }
+            }
+        }
+        store_event_words(p.of_mask, nullptr, t, 32, p.K - t * BK, wdf, unused, m0, n0, tx, ty, p);
+        if (more) {
+            float* Ad = smem + ((t + 1) & 1) * STAGE;
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, 4, 3, p.exp_a);
+            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, 4, 3, p.exp_b);
+        }
+        __syncthreads();
+    }
+    set_round_nearest();
+
+    if (pC) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int m = m0 + ty * 4 + i;
+            if (m >= p.M) continue;
+            const int n = n0 + tx * 4;
+            float v[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float s = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
+                v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);
+            }
+            float* dst = pC + (int64_t)m * p.N + n;
+            if (p.c_vec && n + 3 < p.N) {
+                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    if (n + j < p.N) dst[j] = v[j];
+            }
+        }
+    }
+}
+
 // dst <- Q_acc(add + dst) for the 16 chains of a lane, with exact decisions.
 // Floor: one toward-zero add (the kernel runs in that mode).  Nearest-even: the add is done twice,
 // toward +inf and toward -inf; the smaller magnitude is the truncated sum and the two differ iff the
 // sum was inexact (the sticky bit).  With EVENTS, one OF and one UF bit per chain are shifted into
 // wof / wuf (uf1 = product-underflow flags of this step).
-template <int RND, bool EVENTS>
+template <int RND, bool EVENTS, bool MODESW = false>
 __device__ __forceinline__ void gen_qadd_all(float (&dst)[4][4], const float (&add)[4][4], const KParams& p,
                                              uint32_t rofb, uint32_t rufb, const uint32_t (&uf1)[4][4],
                                              uint32_t (&wof)[4][4], uint32_t (&wuf)[4][4]) {
@@ -950,7 +1071,9 @@ __device__ __forceinline__ void gen_qadd_all(float (&dst)[4][4], const float (&a
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const float S = dst[i][j];
-                const float tz = add[i][j] + S;                             // toward zero: truncated exact sum
+                float tz;                                                   // toward zero: truncated exact sum
+                if (MODESW) asm volatile("v_add_f32 %0, %1, %2" : "=v"(tz) : "v"(add[i][j]), "v"(S));   // ordered after the mode write
+                else tz = add[i][j] + S;
                 const uint32_t uz = __float_as_uint(tz);
                 const uint32_t mag = uz & 0x7FFFFFFFu;
                 const bool of = mag >= rofb, small = mag < rufb;
@@ -1015,8 +1138,34 @@ __device__ __forceinline__ void gen_qadd_all(float (&dst)[4][4], const float (&a
     }
 }
 
+// DIFF bits of one step for the 16 chains of a lane (Sec. 4 "Immediate / DIFF", App. D with eps1 -> 0+):
+// wdf <- 2 * wdf + [ |S_new - S_old| <= eps2 * |x w| ].  The right-hand side is exact in FP32 (a product of
+// two operands has at most 12 significant bits and eps2 at most 12); the difference is formed as
+// max - min >= 0 rounded toward +inf, which exceeds a representable number iff the exact difference does.
+// Both are FP32 normals or 0: sums of E4M3 products are multiples of 2^-18.  Leaves the rounding mode at
+// +inf (FLOOR: back at toward-zero).
+template <int RND>
+__device__ __forceinline__ void gen_diff_all(const float (&s_old)[4][4], const float (&s_new)[4][4],
+                                             const float (&a)[4], const float (&b)[4], float eps2,
+                                             uint32_t (&wdf)[4][4]) {
+    set_round_pinf();
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float hi = __builtin_fmaxf(s_old[i][j], s_new[i][j]);
+            const float lo = __builtin_fminf(s_old[i][j], s_new[i][j]);
+            float d;
+            asm volatile("v_sub_f32 %0, %1, %2" : "=v"(d) : "v"(hi), "v"(lo));
+            const float rhs = __builtin_fabsf(a[i] * b[j]) * eps2;
+            wdf[i][j] = (wdf[i][j] << 1) | (d > rhs ? 0u : 1u);
+        }
+    if (RND == LBA_ROUND_FLOOR) set_round_zero();
+}
+
 // General kernel: 4 x 4 outputs per lane, 64 x 64 tile, BK = 32 (one event word per tile).
-template <int RND, bool EVENTS, int ORDER>
+// DIFF (with EVENTS = false): writes the DIFF plane of the first-level steps through p.of_mask.
+template <int RND, bool EVENTS, int ORDER, bool DIFF = false>
 __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
     constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
     constexpr int STAGE = BK * (BM + BN);
@@ -1079,16 +1228,25 @@ __global__ void __launch_bounds__(256) lba_gen_kernel(const KParams p) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j) pq[i][j] = gen_product<RND>(a[i], b[j], p, &uf1[i][j]);
 
-            gen_qadd_all<RND, EVENTS>(acc, pq, p, rofb, rufb, uf1, wof, wuf);
+            float s_old[TM][TN];
+            if (DIFF) {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) s_old[i][j] = acc[i][j];
+            }
+            gen_qadd_all<RND, EVENTS, DIFF>(acc, pq, p, rofb, rufb, uf1, wof, wuf);
+            if (DIFF) gen_diff_all<RND>(s_old, acc, a, b, p.diff_eps, wof);
             if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
                 // second level (Sec. 3, Fig. 1 right): T <- Q_acc(T + S), S <- 0
-                gen_qadd_all<RND, EVENTS>(top, acc, p, rofb, rufb, no_uf1, wof2, wuf2);
+                gen_qadd_all<RND, EVENTS, DIFF>(top, acc, p, rofb, rufb, no_uf1, wof2, wuf2);
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j) acc[i][j] = 0.0f;
             }
         }
+        if (DIFF) store_event_words(p.of_mask, nullptr, t, 32, p.K - t * BK, wof, wuf, m0, n0, tx, ty, p);
         if (EVENTS) {
             store_event_words(p.of_mask, p.uf_mask, t, 32, p.K - t * BK, wof, wuf, m0, n0, tx, ty, p);
             if (ORDER == LBA_ORDER_CHUNK16 && ((t & 15) == 15 || !more)) {

@@ -1,0 +1,18 @@
+// lba_diff.hip -- instantiations of lba_fast_diff_kernel (the DIFF plane in the scaled domain).
+#include "lba_device.h"
+#include "lba_launch.h"
+
+namespace lba {
+hipError_t launch_fast_diff(const Plan& pl, hipStream_t st) {
+    const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
+#define LBA_DIFF(PM, ORDER) hipLaunchKernelGGL((lba_fast_diff_kernel<PM, ORDER>), grid, block, 0, st, pl.kp)
+    if (pl.amode || (pl.prod_mode != PM_FLUSH && pl.prod_mode != PM_FLUSH_CLAMP)) return hipErrorInvalidValue;
+    if (pl.order == LBA_ORDER_CHUNK16) {
+        if (pl.prod_mode == PM_FLUSH) LBA_DIFF(PM_FLUSH, LBA_ORDER_CHUNK16); else LBA_DIFF(PM_FLUSH_CLAMP, LBA_ORDER_CHUNK16);
+    } else {
+        if (pl.prod_mode == PM_FLUSH) LBA_DIFF(PM_FLUSH, LBA_ORDER_SEQ); else LBA_DIFF(PM_FLUSH_CLAMP, LBA_ORDER_SEQ);
+    }
+#undef LBA_DIFF
+    return hipGetLastError();
+}
+}  // namespace lba

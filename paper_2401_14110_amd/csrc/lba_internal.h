@@ -51,13 +51,14 @@ struct KParams {
     int32_t mix_main, mix_gx_main, mix_gx_tail, mix_m_main;
     int32_t prod_round;      // GEN: product mantissa narrower than a product of two operands
     int32_t prod_rne;        // GEN: its rounding
+    float diff_eps;          // DIFF plane (written through of_mask): the threshold eps2, exact
 };
 
 struct Plan {
     int kernel;              // KERNEL_FAST / KERNEL_GEN
     int prod_mode;           // PM_*
     int round;               // LBA_ROUND_*
-    int events;              // also write the event planes
+    int events;              // 1: also write the event planes; 2: write the DIFF plane (through kp.of_mask)
     int order;               // LBA_ORDER_*
     int tm, tn, bk;          // outputs per lane (tm x tn), k-depth of a tile; tile = 16tm x 16tn
     int grid_x, grid_y;

@@ -14,6 +14,7 @@ __global__ void lba_fill_zero_kernel(float* C, int64_t n) {
 }
 
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
+    if (pl.kernel == KERNEL_FAST && pl.events == 2) return launch_fast_diff(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.events) return launch_fast_bwd(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.amode) return launch_fast_amode(pl, st);   // the planner keeps these on 4 x 4
     if (pl.kernel == KERNEL_FAST && pl.mix_tail > 0) return launch_fast_mixed(pl, st);
@@ -36,7 +37,7 @@ static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, 
                int order, int events, void* stream,
                int64_t batch = 1, int64_t stride_a = 0, int64_t stride_b = 0, int64_t stride_c = 0,
                uint32_t* of_mask2 = nullptr, uint32_t* uf_mask2 = nullptr, const InSpec* in = nullptr,
-               const lba_conv2d_desc* conv = nullptr, int conv_oh = 0, int conv_ow = 0) {
+               const lba_conv2d_desc* conv = nullptr, int conv_oh = 0, int conv_ow = 0, float diff_eps = 0.0f) {
     Plan pl;
     if (batch < 0 || batch > 65535 || stride_a < 0 || stride_b < 0 || stride_c < 0) return LBA_ERR_SHAPE;
     int rc = make_plan(M, N, K, qprod, qacc, order, events, &pl, batch, in, conv != nullptr);
@@ -44,7 +45,7 @@ static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, 
     if (in) pl.kp.out_exp -= in->delta;                        // the operand biases' power-of-two scale
     if (M == 0 || N == 0 || batch == 0) return LBA_OK;
     if (!events && !C) return LBA_ERR_NULL;
-    if (events && !of_mask && !uf_mask && !of_mask2 && !uf_mask2) return LBA_ERR_NULL;
+    if (events && K > 0 && !of_mask && !uf_mask && !of_mask2 && !uf_mask2) return LBA_ERR_NULL;   // K = 0: planes have no words
     hipStream_t st = (hipStream_t)stream;
     if (K == 0) {                                              // empty chains: S_0 = 0; no mask words
         if (C) {
@@ -61,6 +62,7 @@ static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, 
     KParams& kp = pl.kp;
     kp.A = A; kp.B = B; kp.C = C; kp.of_mask = of_mask; kp.uf_mask = uf_mask;
     kp.of_mask2 = of_mask2; kp.uf_mask2 = uf_mask2;
+    kp.diff_eps = diff_eps;
     kp.batch = (int32_t)batch; kp.stride_a = stride_a; kp.stride_b = stride_b; kp.stride_c = stride_c;
     int la = gcd_align(A, K);
     const int lb = gcd_align(B, K);
@@ -104,6 +106,28 @@ int lba_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask
         return rc != LBA_OK ? rc : LBA_ERR_UNSUPPORTED;
     }
     return lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, order, 1, hip_stream);
+}
+
+// eps2 must make eps2 * |x w| exact in FP32: at most 12 significant bits, and a range that keeps the
+// product of any non-zero |x w| in [2^-18, 2^18] an FP32 normal.
+static bool diff_eps_ok(float eps2) {
+    if (eps2 == 0.0f) return true;
+    if (!(eps2 >= 0x1p-32f && eps2 <= 16.0f)) return false;    // also refuses NaN and negative values
+    uint32_t u;
+    __builtin_memcpy(&u, &eps2, 4);
+    return (u & 0xFFFu) == 0u;
+}
+
+int lba_gemm_bwd_diff(const uint8_t* A, const uint8_t* B, float* C, uint32_t* diff_mask,
+                      int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
+                      float eps2, void* hip_stream) {
+    lba::Plan pl;
+    const int rc = lba::make_plan(M, N, K, qprod, qacc, order, 2, &pl);
+    if (rc != LBA_OK) return rc;
+    if (!diff_eps_ok(eps2)) return LBA_ERR_FORMAT;
+    if (!diff_mask && M * N * K > 0) return LBA_ERR_NULL;
+    return lba::run(A, B, C, diff_mask, nullptr, M, N, K, qprod, qacc, order, 2, hip_stream,
+                    1, 0, 0, 0, nullptr, nullptr, nullptr, nullptr, 0, 0, eps2);
 }
 
 int lba_gemm_bwd_chunked(const uint8_t* A, const uint8_t* B, float* C,

@@ -18,6 +18,8 @@ hipError_t launch_fast_amode(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_mixed(const Plan& pl, hipStream_t st);   // plans with mix_tail > 0
 // recompute call, scaled-domain kernel
 hipError_t launch_fast_bwd(const Plan& pl, hipStream_t st);
+// the DIFF plane, scaled-domain kernel (plans with events == 2)
+hipError_t launch_fast_diff(const Plan& pl, hipStream_t st);
 // general kernel (forward and recompute)
 hipError_t launch_gen(const Plan& pl, hipStream_t st);
 

@@ -89,6 +89,20 @@ def test_shape_order_and_null_errors():
     assert lb.lba_gemm(None, None, None, 8, 0, 8, GOOD_P, GOOD_A) == lb.OK
 
 
+def test_diff_threshold_is_validated():
+    A = B = C = D = ctypes.c_void_p(0x1000)
+    call = lambda eps2, **kw: lb.lba_gemm_bwd_diff(A, B, C, D, kw.get("M", 0), 8, 8, GOOD_P, kw.get("qa", GOOD_A),
+                                                   kw.get("order", 0), eps2)
+    for ok in (0.0, 2.0 ** -32, 0.5, 0.75, 4095 * 2.0 ** -14, 16.0):
+        assert call(ok) == lb.OK, ok                      # M = 0: validated, nothing launched
+    for bad in (-0.5, 2.0 ** -33, 17.0, 4097 * 2.0 ** -14, 0.1, float("nan"), float("inf")):
+        assert call(bad) == lb.ERR_FORMAT, bad
+    assert call(0.5, qa=(4, 7, 200, 0)) == lb.ERR_FORMAT
+    assert call(0.5, order=7) == lb.ERR_UNSUPPORTED
+    assert call(0.5, order=1) == lb.OK
+    assert lb.lba_gemm_bwd_diff(A, B, C, None, 8, 8, 8, GOOD_P, GOOD_A, 0, 0.5) == lb.ERR_NULL
+
+
 def test_plan_picks_the_scaled_kernel_for_the_paper_formats():
     # 12-bit accumulator M7E4 with an M7E5 product format (Sec. 3.1), floor and nearest-even
     for rnd in (0, 1):

@@ -160,6 +160,28 @@ def test_event_planes_full_512_and_slab_of_4096(ref):
     assert torch.equal(lb.gemm(l["A"], l["B"], qp, qa).view(torch.int32), C.view(torch.int32))
 
 
+def test_diff_plane_full_512_and_slab_of_4096(ref):
+    (l,) = inputs.make_workload("gemm4096", DEV)
+    A = l["A"][:512, :512].contiguous(); B = l["B"][:512, :512].contiguous()
+    for acc, rnd, order, eps2 in (((4, 3, 7), 0, 0, 0.25), ((4, 7, 7), 0, 1, 0.5), ((5, 7, 15), 0, 0, 0.25), ((4, 7, 7), 1, 0, 0.0)):
+        qp, qa, _ = inputs.folded_formats(l["ta"], l["tb"], PROD, acc, rnd)
+        C, diff = lb.gemm_bwd_diff(A, B, qp, qa, eps2, order=order)
+        torch.cuda.synchronize()
+        wc, wd = ref.gemm_diff(A.cpu().numpy(), B.cpu().numpy(), ref.QFmt(*qp), ref.QFmt(*qa), eps2, order=order)
+        assert np.array_equal(C.cpu().numpy().view(np.uint32), wc.view(np.uint32)), (acc, rnd, order)
+        assert np.array_equal(diff.cpu().numpy().view(np.uint32), wd), (acc, rnd, order)
+    # the 4096^3 problem in the configuration the benchmark times: a 48-row slab against the oracle
+    qp, qa, _ = inputs.folded_formats(l["ta"], l["tb"], PROD, (4, 7, 7), 0)
+    C, diff = lb.gemm_bwd_diff(l["A"], l["B"], qp, qa, 0.25)
+    torch.cuda.synchronize()
+    rows = np.concatenate([np.arange(0, 16), np.arange(2040, 2056), np.arange(4080, 4096)])
+    idx = torch.from_numpy(rows).to(DEV)
+    wc, wd = ref.gemm_diff(l["A"].index_select(0, idx).cpu().numpy(), l["B"].cpu().numpy(), ref.QFmt(*qp), ref.QFmt(*qa), 0.25)
+    assert np.array_equal(C.index_select(0, idx).cpu().numpy().view(np.uint32), wc.view(np.uint32))
+    assert np.array_equal(diff.index_select(1, idx).cpu().numpy().view(np.uint32), wd)
+    assert 0.01 < np.unpackbits(wd.view(np.uint8)).mean() < 0.99
+
+
 def _grad_check(got, want, scale, terms, what):
     tol = 2 * (terms + 1) * 2.0 ** -24 * scale + 1e-30
     err = np.abs(got - want)

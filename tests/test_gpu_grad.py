@@ -97,6 +97,25 @@ def test_general_data_within_the_fp32_bound(ref, gref, order):
             assert (np.abs(dW - wW) <= tolW).all(), (M, N, K, ste, "dW", (np.abs(dW - wW) / tolW).max())
 
 
+def test_immediate_estimator_with_the_diff_plane(ref, gref):
+    # "Immediate / DIFF" (Sec. 4): the DIFF plane of lba_gemm_bwd_diff goes where the OF plane goes.
+    rng = np.random.default_rng(99)
+    QPd, QAd = (4, 7, 12, 0), (4, 7, 10, 0)
+    for (M, N, K), order, eps2 in [((70, 66, 100), 0, 0.25), ((33, 130, 65), 1, 0.25), ((64, 24, 40), 0, 0.0)]:
+        A = codes(rng, (M, K), 5, 10); B = codes(rng, (N, K), 5, 10)
+        G = (rng.integers(-8, 9, (M, N)) / 4.0).astype(np.float32)
+        tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+        _, diff = lb.gemm_bwd_diff(tA, tB, QPd, QAd, eps2, order=order, want_c=False)
+        dX, dW = lb.grad(torch.from_numpy(G).to(DEV), tA, tB, lb.STE_IMMEDIATE_OF, of_plane=diff)
+        torch.cuda.synchronize()
+        wX, wW = gref.grad(G, A, B, ref.QFmt(*QPd), ref.QFmt(*QAd), gref.STE_IMMEDIATE_DIFF, order,
+                           c=gref.coefficients(A, B, ref.QFmt(*QPd), ref.QFmt(*QAd), gref.STE_IMMEDIATE_DIFF, order, eps2))
+        assert np.array_equal(dX.cpu().numpy(), wX.astype(np.float32)), (M, N, K, "dX")
+        assert np.array_equal(dW.cpu().numpy(), wW.astype(np.float32)), (M, N, K, "dW")
+        oX, _ = gref.grad(G, A, B, ref.QFmt(*QPd), ref.QFmt(*QAd), gref.STE_IMMEDIATE_OF, order)
+        assert not np.array_equal(wX, oX)                               # DIFF blocks more than overflow alone
+
+
 def test_arguments_views_and_degenerate_sizes(ref, gref):
     rng = np.random.default_rng(99)
     M, N, K = 40, 36, 50

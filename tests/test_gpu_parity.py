@@ -416,6 +416,48 @@ def test_overflow_plane_alone(ref):
             assert np.array_equal(got[3].cpu().numpy().view(np.uint32), want[3])
 
 
+def test_diff_plane(ref):
+    # lba_gemm_bwd_diff: 1 - STE^DIFF per step (Sec. 4 "Immediate / DIFF", App. D) for several thresholds, both
+    # roundings, both orders; ragged shapes across tile and word boundaries; operands from full range (overflow
+    # and swamping), small (product underflow) and mixed.  The planes must differ between thresholds (the
+    # comparison is live) and C must be the forward call's.
+    rng = np.random.default_rng(123)
+    cases = [((70, 66, 100), 0, 15), ((33, 130, 64), 3, 12), ((5, 3, 31), 0, 15), ((64, 64, 33), 5, 10), ((130, 20, 530), 0, 9)]
+    fmts = [FMT_PAPER[0], FMT_PAPER[1], FMT_PAPER[2], FMT_ODD[0], FMT_ODD[1], FMT_ODD[3], FMT_SWEEP[1], FMT_SWEEP[5],
+            ((7, 23, 64), (7, 23, 64)), ((5, 7, 15), (4, 23, 7))]
+    distinct = 0
+    for ci, ((M, N, K), lo, hi) in enumerate(cases):
+        A = rand_codes(rng, (M, K), lo, hi); B = rand_codes(rng, (N, K), lo, hi)
+        tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+        for fi, ((qp, qa), rnd) in enumerate(itertools.product(fmts, (0, 1))):
+            if (ci + fi) % 2:                                          # half of the grid: keeps the oracle's time down
+                continue
+            qpf, qaf = qp + (rnd,), qa + (rnd,)
+            for order in (0, 1):
+                prev = None
+                for eps2 in (0.0, 2.0 ** -6, 0.5, 0.75, 1.0):
+                    C, diff = lb.gemm_bwd_diff(tA, tB, qpf, qaf, eps2, order=order)
+                    torch.cuda.synchronize()
+                    wc, wd = ref.gemm_diff(A, B, fm(ref, qpf), fm(ref, qaf), eps2, order=order)
+                    assert np.array_equal(bits(C.cpu().numpy()), bits(wc)), (M, N, K, qpf, qaf, order, eps2)
+                    got = diff.cpu().numpy().view(np.uint32)
+                    bad = got != wd
+                    assert not bad.any(), (M, N, K, qpf, qaf, order, eps2, int(bad.sum()), np.argwhere(bad)[0])
+                    distinct += int(prev is not None and not np.array_equal(prev, got))
+                    prev = got
+    assert distinct > 100
+    # the plane alone; a threshold with 12 significant bits
+    C, diff = lb.gemm_bwd_diff(tA, tB, (5, 7, 15, 0), (4, 7, 7, 0), 2731 * 2.0 ** -13, want_c=False)
+    torch.cuda.synchronize()
+    _, wd = ref.gemm_diff(A, B, ref.QFmt(5, 7, 15, 0), ref.QFmt(4, 7, 7, 0), 2731 * 2.0 ** -13)
+    assert C is None and np.array_equal(diff.cpu().numpy().view(np.uint32), wd)
+    # empty chains and empty outputs
+    z = torch.empty((4, 0), dtype=torch.uint8, device=DEV)
+    C, diff = lb.gemm_bwd_diff(z, z, (5, 7, 15, 0), (4, 7, 7, 0), 0.5)
+    torch.cuda.synchronize()
+    assert diff.numel() == 0 and (C == 0).all() and tuple(C.shape) == (4, 4)
+
+
 def test_operand_code_formats(ref):
     # lba_gemm_in / lba_gemm_bwd_in: operands in other 8-bit formats (the paper's M4E3 with a per-tensor
     # bias, E5M2, E2M5, mixed with E4M3).  Products have up to 12 significant bits, so Q_prod's mantissa

@@ -452,6 +452,91 @@ def test_chunked_order_event_planes(ref):
         assert int(uf[0, 0, 0]) == 0 and int(of[0, 0, 0]) == 0
 
 
+def test_hand_worked_diff_estimator(ref):
+    qp, qa = (5, 7, 16), (4, 7, 7)
+    tab = list(rows("chain_diff.txt"))
+    a = np.array([[int(r[1], 16) for r in tab]], dtype=np.uint8)
+    b = np.array([[int(r[2], 16) for r in tab]], dtype=np.uint8)
+    for rnd, col in ((ref.FLOOR, 3), (ref.RNE, 6)):
+        fp, fa = ref.QFmt(*qp, rnd), ref.QFmt(*qa, rnd)
+        for c, eps2 in enumerate((0.0, 0.5, 0.75)):
+            C, diff = ref.gemm_diff(a, b, fp, fa, eps2)
+            assert C[0, 0] == 510.0
+            for k, r in enumerate(tab):
+                assert (int(diff[0, 0, 0]) >> k) & 1 == 1 - int(r[col + c]), (rnd, eps2, k)   # the plane holds 1 - STE
+            assert int(diff[0, 0, 0]) >> len(tab) == 0
+        # a ratio equal to the threshold does not pass (strict inequality): step 0 has ratio exactly 1
+        assert int(ref.gemm_diff(a, b, fp, fa, 1.0)[1][0, 0, 0]) & 1 == 1
+        assert int(ref.gemm_diff(a, b, fp, fa, 0.999)[1][0, 0, 0]) & 1 == 0
+
+
+@pytest.mark.parametrize("rnd", [0, 1])
+def test_diff_estimator_against_fraction_model(ref, rnd):
+    """The DIFF plane against the ratio written out with Fractions, for dyadic and non-dyadic thresholds; a
+    finite eps1 far below every quantity in play gives the same bits as the limit the oracle implements."""
+    fmts = [((5, 7, 15), (4, 7, 7)), ((5, 7, 16), (4, 3, 2)), ((4, 4, 6), (3, 4, 3)), ((5, 7, -1), (4, 7, -9)),
+            ((6, 2, 10), (5, 10, 12)), ((5, 7, 15), (4, 7, 7 | 0)), ((5, 7, 12), (4, 7, 10))]
+    rng = random.Random(21)
+    seen = {0: 0, 1: 0}
+    for qp, qa in fmts:
+        fp, fa = ref.QFmt(*qp, rnd), ref.QFmt(*qa, rnd)
+        seqs = [([x], [y]) for x in TINY[::2] for y in TINY[::3]]
+        for K in (2, 3, 5):
+            seqs += [([rng.choice(TINY) for _ in range(K)], [rng.choice(TINY) for _ in range(K)]) for _ in range(60)]
+        for eps2 in (0.0, 2.0 ** -6, 0.3, 0.5, 1.0, 1.75):
+            for sa, sb in seqs:
+                want_s, ste = FM.chain_diff(sa, sb, qp + (rnd,), qa + (rnd,), Fraction(eps2))
+                _, ste_e1 = FM.chain_diff(sa, sb, qp + (rnd,), qa + (rnd,), Fraction(eps2), Fraction(1, 2 ** 90))
+                if eps2 > 0:
+                    assert ste == ste_e1
+                A = np.array([sa], dtype=np.uint8); B = np.array([sb], dtype=np.uint8)
+                C, diff = ref.gemm_diff(A, B, fp, fa, eps2)
+                assert Fraction(float(C[0, 0])) == want_s
+                for k, v in enumerate(ste):
+                    assert (int(diff[0, 0, 0]) >> k) & 1 == 1 - v, (qp, qa, eps2, sa, sb, k)
+                    seen[v] += 1
+    assert seen[0] > 500 and seen[1] > 500
+
+
+def test_diff_plane_properties(ref):
+    """eps2 = 0 marks exactly the steps that leave the sum unchanged; the blocked set grows with eps2; product
+    underflows are always blocked; the value C does not depend on eps2; under the chunked order the bits are
+    those of each chunk's own chain from zero."""
+    rng = np.random.default_rng(5)
+    A = rng.integers(0, 256, size=(6, 70), dtype=np.uint8); A[(A & 0x7F) == 0x7F] = 0x3A
+    B = rng.integers(0, 256, size=(5, 70), dtype=np.uint8); B[(B & 0x7F) == 0x7F] = 0x41
+    for rnd in (ref.FLOOR, ref.RNE):
+        fp, fa = ref.QFmt(5, 7, 12, rnd), ref.QFmt(4, 7, 10, rnd)
+        C0, of, uf = ref.gemm_bwd(A, B, fp, fa)
+        prev = None
+        for eps2 in (0.0, 2.0 ** -8, 0.125, 0.5, 1.0, 4.0):
+            C, diff = ref.gemm_diff(A, B, fp, fa, eps2)
+            assert np.array_equal(C, C0)
+            if prev is not None:
+                assert (prev & ~diff).max() == 0 and (diff & ~prev).max() > 0
+            prev = diff
+        # eps2 = 0: replay every chain one step at a time and mark the steps that did not move the sum
+        _, nc = ref.gemm_diff(A, B, fp, fa, 0.0)
+        for m in range(A.shape[0]):
+            for n in range(B.shape[0]):
+                s = 0.0
+                for k in range(A.shape[1]):
+                    z, ev = ref.fmaq(int(A[m, k]), int(B[n, k]), s, fp, fa)
+                    assert (int(nc[k // 32, m, n]) >> (k % 32)) & 1 == int(z == s)
+                    if ev & ref.EV_UF and ref.decode(A[m, k]) * ref.decode(B[n, k]) != 0 and z == s:
+                        assert (int(prev[k // 32, m, n]) >> (k % 32)) & 1
+                    s = z
+        assert nc.max() > 0
+        # chunked order: chunk j's bits = the bits of the product of columns 16j .. 16j+15 alone
+        _, dch = ref.gemm_diff(A, B, fp, fa, 0.25, order=ref.ORDER_CHUNK16)
+        for j in range(0, 70, 16):
+            _, dj = ref.gemm_diff(A[:, j:j + 16], B[:, j:j + 16], fp, fa, 0.25)
+            got = (dch[j // 32] >> (j % 32)) & ((1 << min(16, 70 - j)) - 1)
+            assert np.array_equal(got, dj[0])
+        assert np.array_equal(ref.gemm_diff(A, B, fp, fa, 0.25, order=ref.ORDER_CHUNK16)[0],
+                              ref.gemm(A, B, fp, fa, order=ref.ORDER_CHUNK16))
+
+
 def test_input_code_formats(ref):
     """Operands in other 8-bit formats (the paper's M4E3 with a per-tensor bias, Sec. 3.1)."""
     import torch
