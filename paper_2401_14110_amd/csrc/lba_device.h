@@ -38,6 +38,10 @@ __device__ __forceinline__ void set_round_nearest() { asm volatile("s_setreg_imm
 __device__ __forceinline__ void set_round_pinf()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 1\n\ts_nop 1" ::: "memory"); }
 __device__ __forceinline__ void set_round_ninf()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 2\n\ts_nop 1" ::: "memory"); }
 __device__ __forceinline__ void set_round_zero()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 3\n\ts_nop 1" ::: "memory"); }
+// the same two without the memory clobber, for inner loops whose mode-dependent operations are all
+// volatile assembly themselves (volatile statements keep their order; loads may still move across)
+__device__ __forceinline__ void set_round_pinf_nm() { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 1\n\ts_nop 1"); }
+__device__ __forceinline__ void set_round_ninf_nm() { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 2\n\ts_nop 1"); }
 __device__ __forceinline__ void set_flush_f32()     { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 4, 2), 0\n\ts_nop 1" ::: "memory"); }
 
 // FP16 denormals on (MODE[7:6] = 3): the staging decodes 8-bit codes through an exact FP16 image
@@ -71,6 +75,19 @@ __device__ __forceinline__ uint32_t rne_bits(uint32_t u, uint32_t half, int sh, 
 // the hardware float -> bfloat16 conversion, whose packed result with a zero low half is the FP32
 // word of the rounded value.  Same function as the bfe/add3/and sequence, in one instruction.
 enum { RND_RNE_BF16 = 2 };
+// Internal rounding code: nearest-even that is exact for every M <= 21.  The exact sum is formed twice,
+// rounded toward +inf and toward -inf (the wave's mode is switched once per k-step for all chains of a
+// lane); the two results are equal iff the sum is exact and otherwise neighbours, and the one whose last
+// bit is 1 is the sum rounded to odd at 24 bits.  Nearest-even at M + 1 <= 22 bits of that word equals
+// nearest-even of the exact sum (the odd last bit keeps an inexact sum off every midpoint and on its side).
+enum { RND_RNE_ODD = 3 };
+
+// of two words that are equal or neighbours: the one with the odd last bit
+__device__ __forceinline__ float odd_of(float up, float un) {
+    const uint32_t u = __float_as_uint(up), n = __float_as_uint(un);
+    const uint32_t pick = (uint32_t)(((int32_t)(u << 31)) >> 31);               // all ones iff up is odd
+    return __uint_as_float((u & pick) | (n & ~pick));
+}
 
 __device__ __forceinline__ float rne_to_8_bits(float t) {
     typedef float v2f __attribute__((ext_vector_type(2)));
@@ -95,7 +112,23 @@ __device__ __forceinline__ void fast_group(float (&accf)[TM][NJ], const float (&
                                            const FastConst& c) {
     float (*acc)[NJ] = &accf[I0];
     const float* a = &af[I0];
-    if (PM == PM_IDENT) {
+    if (PM == PM_IDENT && RND == RND_RNE_ODD) {
+        float up[NI][NJ], un[NI][NJ];
+        set_round_pinf_nm();
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(up[i][j]) : "v"(a[i]), "v"(b[j]), "v"(acc[i][j]));
+        set_round_ninf_nm();
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(un[i][j]) : "v"(a[i]), "v"(b[j]), "v"(acc[i][j]));
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) acc[i][j] = odd_of(up[i][j], un[i][j]);
+    } else if (PM == PM_IDENT) {
 #pragma unroll
         for (int i = 0; i < NI; ++i)
 #pragma unroll
@@ -136,10 +169,28 @@ __device__ __forceinline__ void fast_group(float (&accf)[TM][NJ], const float (&
                 for (int j = 0; j < NJ; ++j) q[i][j] = med3(q[i][j], -c.rofp, c.rofp);
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (RND == RND_RNE_ODD) {
+            float up[NI][NJ], un[NI][NJ];
+            set_round_pinf_nm();
 #pragma unroll
-        for (int i = 0; i < NI; ++i)
+            for (int i = 0; i < NI; ++i)
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_fmaf(q[i][j], c.kc, acc[i][j]);   // one rounding of the exact sum
+                for (int j = 0; j < NJ; ++j) asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(up[i][j]) : "v"(q[i][j]), "v"(c.kc), "v"(acc[i][j]));
+            set_round_ninf_nm();
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(un[i][j]) : "v"(q[i][j]), "v"(c.kc), "v"(acc[i][j]));
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) acc[i][j] = odd_of(up[i][j], un[i][j]);
+        } else {
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) acc[i][j] = __builtin_fmaf(q[i][j], c.kc, acc[i][j]);   // one rounding of the exact sum
+        }
     }
     __builtin_amdgcn_sched_barrier(0);
     if (RND == RND_RNE_BF16) {
@@ -148,7 +199,7 @@ __device__ __forceinline__ void fast_group(float (&accf)[TM][NJ], const float (&
 #pragma unroll
             for (int j = 0; j < NJ; ++j) acc[i][j] = rne_to_8_bits(acc[i][j]);
     } else {
-        if (RND == LBA_ROUND_RNE) {
+        if (RND == LBA_ROUND_RNE || RND == RND_RNE_ODD) {
             uint32_t l[NI][NJ];
 #pragma unroll
             for (int i = 0; i < NI; ++i)
@@ -448,10 +499,28 @@ __device__ __forceinline__ void read_operands(const float* As, const float* Bs, 
 // same one-rounding argument as for a product step applies.
 template <int RND, bool CLAMP, int TM, int TN>
 __device__ __forceinline__ void fast_level2(float (&top)[TM][TN], float (&acc)[TM][TN], const FastConst& c) {
+    if (RND == RND_RNE_ODD) {
+        float up[TM][TN], un[TM][TN];
+        set_round_pinf_nm();
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) top[i][j] = top[i][j] + acc[i][j];
+            for (int j = 0; j < TN; ++j) asm volatile("v_add_f32 %0, %1, %2" : "=v"(up[i][j]) : "v"(top[i][j]), "v"(acc[i][j]));
+        set_round_ninf_nm();
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) asm volatile("v_add_f32 %0, %1, %2" : "=v"(un[i][j]) : "v"(top[i][j]), "v"(acc[i][j]));
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) top[i][j] = odd_of(up[i][j], un[i][j]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) top[i][j] = top[i][j] + acc[i][j];
+    }
     __builtin_amdgcn_sched_barrier(0);
     if (RND == RND_RNE_BF16) {
 #pragma unroll
@@ -459,7 +528,7 @@ __device__ __forceinline__ void fast_level2(float (&top)[TM][TN], float (&acc)[T
 #pragma unroll
             for (int j = 0; j < TN; ++j) { top[i][j] = rne_to_8_bits(top[i][j]); acc[i][j] = 0.0f; }
     } else {
-        if (RND == LBA_ROUND_RNE) {
+        if (RND == LBA_ROUND_RNE || RND == RND_RNE_ODD) {
             uint32_t l[TM][TN];
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -602,7 +671,7 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
         }
         __syncthreads();
     }
-    if (RND == LBA_ROUND_FLOOR) set_round_nearest();
+    if (RND == LBA_ROUND_FLOOR || RND == RND_RNE_ODD) set_round_nearest();
 
     // C = S * 2^out_exp, zero written as +0
 #pragma unroll

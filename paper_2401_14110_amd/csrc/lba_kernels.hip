@@ -16,6 +16,7 @@ __global__ void lba_fill_zero_kernel(float* C, int64_t n) {
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
     if (pl.kernel == KERNEL_FAST && pl.events == 2) return launch_fast_diff(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.events) return launch_fast_bwd(pl, st);
+    if (pl.kernel == KERNEL_FAST && pl.rne_odd) return launch_fast_odd(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.amode) return launch_fast_amode(pl, st);   // the planner keeps these on 4 x 4
     if (pl.kernel == KERNEL_FAST && pl.mix_tail > 0) return launch_fast_mixed(pl, st);
     if (pl.kernel == KERNEL_FAST) {

@@ -16,6 +16,7 @@ hipError_t launch_fast_24(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_22(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_amode(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_mixed(const Plan& pl, hipStream_t st);   // plans with mix_tail > 0
+hipError_t launch_fast_odd(const Plan& pl, hipStream_t st);     // plans with rne_odd
 // recompute call, scaled-domain kernel
 hipError_t launch_fast_bwd(const Plan& pl, hipStream_t st);
 // the DIFF plane, scaled-domain kernel (plans with events == 2)

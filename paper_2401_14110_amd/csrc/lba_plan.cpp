@@ -139,6 +139,15 @@ static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp, bool
     return true;
 }
 
+// The round-to-odd variant (two directed sums per step) has no double rounding: it is exact whenever the
+// second rounding keeps at most 22 bits, with the same condition at the flush threshold as above.
+static bool rne_odd_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool flush, bool nouf_a, const InSpec& in) {
+    if (qa.man_bits > 21) return false;
+    if (nouf_a) return true;
+    const int bpe = flush ? qp.bias : -in.min_lsb;
+    return bpe - qa.bias < 24;
+}
+
 #ifndef LBA_FAST_BK
 #define LBA_FAST_BK 32
 #endif
@@ -148,13 +157,13 @@ static bool rne_fast_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool clamp, bool
 // with few outputs cannot keep two waves on every SIMD with 16 chains per lane: between 512 and 1024
 // workgroups 2 x 4 measured 3-6 % faster, and up to 64 workgroups (a latency-bound launch) 2 x 2 is
 // about twice as fast.  The choice never changes a result.
-static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int events, int prod_mode, int amode, int* tm, int* tn, int* bk) {
+static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int events, int prod_mode, int amode, int rne_odd, int* tm, int* tn, int* bk) {
     *tm = 4; *tn = 4;
     *bk = (kernel == KERNEL_GEN || events) ? 32 : LBA_FAST_BK;
     if (kernel == KERNEL_FAST) {
         const int64_t blocks = ((M + 63) / 64) * ((N + 63) / 64) * (batch > 0 ? batch : 1);
         if (events) return;                                    // the recompute kernel is 4 x 4 only
-        if (prod_mode == PM_TRUNC || prod_mode == PM_TRUNC_CLAMP || amode) return;   // built for 4 x 4 only
+        if (prod_mode == PM_TRUNC || prod_mode == PM_TRUNC_CLAMP || amode || rne_odd) return;   // built for 4 x 4 only
         if (blocks <= 64) { *tm = 2; *tn = 2; }
         else if (blocks > 512 && blocks <= 1024) *tm = 2;
     }
@@ -166,7 +175,7 @@ static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int event
 // efficiency), which the launch then finishes in quarter rounds.  Used when the model says 3 % or more.
 static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
     p->mix_tail = 0;
-    if (p->kernel != KERNEL_FAST || p->events || p->amode || batch != 1) return;
+    if (p->kernel != KERNEL_FAST || p->events || p->amode || p->rne_odd || batch != 1) return;
     if (p->prod_mode != PM_IDENT && p->prod_mode != PM_FLUSH && p->prod_mode != PM_FLUSH_CLAMP) return;
     const int64_t gx = (M + 63) / 64, gy = (N + 63) / 64, blocks = gx * gy;
     if (blocks <= 256 || blocks > 256 * 16) return;
@@ -233,7 +242,12 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     // the recompute call has a scaled-domain kernel for floor rounding when Q_prod can underflow
     // (its product-underflow test is the multiply's flush); anything else takes the general kernel
     if (events && (qa.round != LBA_ROUND_FLOOR || !flush)) fast = false;
-    if (fast && qa.round == LBA_ROUND_RNE && !rne_fast_ok(qp, qa, clamp, flush, nouf_a, in)) fast = false;
+    bool rne_odd = false;
+    if (fast && qa.round == LBA_ROUND_RNE && !rne_fast_ok(qp, qa, clamp, flush, nouf_a, in)) {
+        // E4M3 matrices, Q_prod without mantissa rounding, forward call: the round-to-odd variant
+        rne_odd = !events && !prod_round && !conv && in.ea == 4 && in.eb == 4 && rne_odd_ok(qp, qa, flush, nouf_a, in);
+        if (!rne_odd) fast = false;
+    }
     if (fast && (flush || clamp) && std::abs(c_a_dom - c_p_dom) > 120) fast = false;   // kc must be an FP32 normal
     // the recompute kernel also forms p * kc * 2^60 and S * 2^60
     if (fast && events && (std::abs(c_a_dom - c_p_dom) > 60 || top_exp(qa) + c_a_dom + 61 > 126)) fast = false;
@@ -261,7 +275,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         int slots = (p.prod_mode == PM_IDENT) ? 2 : 3;           // [mul,] fma, and
         if (p.prod_mode == PM_FLUSH_CLAMP || p.prod_mode == PM_TRUNC_CLAMP || p.prod_mode == PM_RNE_CLAMP) slots += 2;   // med3 on the product
         if (prod_round) slots += (qp.round == LBA_ROUND_FLOOR) ? 1 : 5;   // and [, bfe, add3] on the product
-        if (qa.round == LBA_ROUND_RNE) slots += (qa.man_bits == 7) ? 1 : 4;   // M = 7: cvt to bfloat16 replaces and; else bfe, add3
+        if (qa.round == LBA_ROUND_RNE) slots += (qa.man_bits == 7 && !rne_odd) ? 1 : 4;   // M = 7: cvt to bfloat16 replaces and; else bfe, add3
+        if (rne_odd) slots += 4;                                  // second fma, bfe, bfi
         p.valu_per_mac_x100 = slots * 100;
         if (events)                                              // 5 full-rate + 7 half-rate instructions, + operand tests
             p.valu_per_mac_x100 = 1950 + (p.prod_mode == PM_FLUSH_CLAMP ? 200 : 0);
@@ -283,7 +298,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     }
     p.amode = (conv || in.ea != 4 || in.eb != 4 || p.prod_mode == PM_RNE || p.prod_mode == PM_RNE_CLAMP ||
                (events && (p.prod_mode == PM_TRUNC || p.prod_mode == PM_TRUNC_CLAMP))) ? 1 : 0;
-    pick_tile(M, N, batch, p.kernel, p.events, p.prod_mode, p.amode, &p.tm, &p.tn, &p.bk);
+    p.rne_odd = (fast && rne_odd) ? 1 : 0;
+    pick_tile(M, N, batch, p.kernel, p.events, p.prod_mode, p.amode, p.rne_odd, &p.tm, &p.tn, &p.bk);
     kp.batch = 1;
     kp.fast_thresh = -1.0f;
     kp.fast_thresh4 = -1.0f;

@@ -118,9 +118,16 @@ def test_plan_picks_the_scaled_kernel_for_the_paper_formats():
 
 def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     q = lb.lba_plan_query
-    assert q(64, 64, 64, (5, 7, 15, 1), (5, 3, 15, 1))["kernel"] == 1     # nearest-even, M_acc < 7, inexact sums below R_OF
-    assert q(64, 64, 64, (5, 7, 15, 1), (4, 11, 7, 1))["kernel"] == 1     # nearest-even, M_acc > 10
-    assert q(64, 64, 64, (5, 9, 15, 1), (5, 8, 15, 1))["kernel"] == 1     # saturated product off the grid, sums below R_OF
+    # nearest-even where one FP32 rounding first would not be exact (M_acc < 7 with inexact sums below R_OF,
+    # M_acc > 10, a saturated product off the grid): the scaled kernel's round-to-odd variant (two directed
+    # sums, 4 slots more), up to M = 21; the general kernel beyond
+    for qp, qa in (((5, 7, 15, 1), (5, 3, 15, 1)), ((5, 7, 15, 1), (4, 11, 7, 1)), ((5, 9, 15, 1), (5, 8, 15, 1)),
+                   ((5, 7, 15, 1), (5, 21, 15, 1))):
+        plan = q(64, 64, 64, qp, qa)
+        assert plan["kernel"] == 0 and (plan["thread_m"], plan["thread_n"]) == (4, 4)
+        assert plan["valu_per_mac_x100"] == q(64, 64, 64, qp, (4, 8, 7, 1))["valu_per_mac_x100"] + 400
+    assert q(64, 64, 64, (5, 7, 15, 1), (5, 22, 15, 1))["kernel"] == 1
+    assert q(64, 64, 64, (5, 7, 15, 1), (5, 3, 15, 1), with_masks=1)["kernel"] == 1
     assert q(64, 64, 64, (5, 9, 15, 1), (4, 8, 7, 1))["kernel"] == 0      # same product, but then every sum saturates
     assert q(64, 64, 64, (5, 7, 40, 1), (4, 7, -9, 1))["kernel"] == 1     # products far below R_UF of Q_acc
     assert q(64, 64, 64, (5, 4, 15, 1), (4, 7, 7, 1))["prod_mode"] == 6   # product mantissa rounded to nearest (and clamped): still the scaled kernel
@@ -140,14 +147,15 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     assert q(64, 64, 64, (6, 7, 20, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 1
     # chunked order, forward and recompute
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=1)["kernel"] == 0
-    assert q(64, 64, 64, (5, 7, 15, 1), (5, 3, 15, 1), order=1)["kernel"] == 1
+    assert q(64, 64, 64, (5, 7, 15, 1), (5, 3, 15, 1), order=1)["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=1, with_masks=1)["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), order=1, with_masks=1)["kernel"] == 1
     # nearest-even below 7 mantissa bits: scaled kernel only when every inexact FP32 sum overflows
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 3, 7, 1))["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 6, 7, 1))["kernel"] == 0
-    assert q(64, 64, 64, (5, 7, 15, 1), (5, 6, 15, 1))["kernel"] == 1
+    assert q(64, 64, 64, (5, 7, 15, 1), (5, 6, 15, 1))["valu_per_mac_x100"] == 1300     # round-to-odd variant
     assert q(64, 64, 64, (4, 9, 7, 1), (4, 6, 7, 1))["kernel"] == 0       # a saturated product has 10 bits: still clear of midpoints
-    assert q(64, 64, 64, (4, 12, 7, 1), (4, 9, 7, 1))["kernel"] == 1      # 13 + 9 bits: an inexact sum could reach one
+    base = q(64, 64, 64, (4, 9, 7, 1), (4, 9, 7, 1))["valu_per_mac_x100"]
+    assert q(64, 64, 64, (4, 12, 7, 1), (4, 9, 7, 1))["valu_per_mac_x100"] == base + 400   # 13 + 9 bits: an inexact sum could reach one
     with pytest.raises(lb.LbaError):
         q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=2)

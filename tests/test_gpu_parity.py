@@ -316,21 +316,29 @@ def test_nearest_even_below_seven_mantissa_bits_keeps_ties_right(ref):
     codes = np.where((codes & 0x7F) == 0x7F, codes & 0xFE, codes).astype(np.uint8)
     A = np.stack([rand_codes(rng, (256,), 0, 6), codes], axis=1)
     B = np.stack([rand_codes(rng, (256,), 0, 6), codes], axis=1)
-    kernels = set()
+    variants = set()
     for qp, qa in [((5, 7, 15), (4, 3, 7)), ((5, 7, 15), (4, 6, 7)), ((5, 7, 18), (4, 5, 7)), ((5, 7, 15), (5, 4, 15)),
                    ((5, 7, 15), (6, 6, 31)), ((6, 7, 20), (5, 3, -2)), ((5, 7, 4), (4, 4, -6)), ((4, 7, 7), (4, 5, 7)),
                    ((4, 9, 7), (4, 6, 7)), ((5, 7, 15), (3, 6, 2)), ((5, 7, 15), (7, 5, 40))]:
         qpf, qaf = qp + (1,), qa + (1,)
-        kernels.add(lb.lba_plan_query(256, 256, 2, qpf, qaf)["kernel"])
+        plan = lb.lba_plan_query(256, 256, 2, qpf, qaf)
+        plain = lb.lba_plan_query(256, 256, 2, qpf, (4, 8, 7, 1))          # a format that needs one FP32 rounding only
+        variants.add((plan["kernel"], plan["valu_per_mac_x100"] - plain["valu_per_mac_x100"]))
         check(ref, A, B, qpf, qaf, "rne small M, K=2")
         check(ref, A, B, qpf, qaf, "rne small M, K=2, chunked", order=1)
         check(ref, A, B, qpf, (qa[0], qa[1], qa[2], 0x101), "rne small M, no underflow")
-    assert kernels == {0, 1}
+    assert {(0, 0), (0, 400)} <= variants                   # the plain scaled kernel and its two-directed-sums variant
+    # mantissas between 11 and 21 bits take that variant too (22 and 23: the general kernel)
+    for qa in ((5, 11, 15), (4, 16, 7), (5, 21, 15), (6, 13, 31), (4, 22, 7)):
+        check(ref, A, B, (5, 7, 15, 1), qa + (1,), "rne wide M, K=2")
     # longer chains with the full exponent range
     A = rand_codes(rng, (130, 100)); B = rand_codes(rng, (70, 100))
-    for M in (3, 4, 5, 6):
-        for E, b in ((4, 7), (4, 0), (4, -6), (5, 15), (3, 3)):
-            check(ref, A, B, (5, 7, 15, 1), (E, M, b, 1), "rne small M")
+    for M in (3, 4, 5, 6, 12, 19, 21):
+        for E, b in ((4, 7), (4, 0), (4, -6), (5, 15), (3, 3), (6, 31)):
+            check(ref, A, B, (5, 7, 15, 1), (E, M, b, 1), "rne M=%d" % M)
+            if M in (5, 12):
+                check(ref, A, B, (5, 7, 15, 1), (E, M, b, 1), "rne M=%d chunked" % M, order=1)
+                check(ref, A, B, (6, 7, 20, 1), (E, M, b, 1), "rne M=%d, Q_prod identity" % M)
 
 
 def test_event_planes_of_the_chunked_order(ref):
@@ -515,8 +523,9 @@ def test_mixed_grid(ref):
         for (qp, qa), rnd, order in itertools.product([FMT_PAPER[0], FMT_PAPER[2], FMT_PAPER[4], FMT_SWEEP[4]], (0, 1), (0, 1)):
             qpf, qaf = qp + (rnd,), qa + (rnd,)
             plan = lb.lba_plan_query(M, N, K, qpf, qaf, order)
-            assert plan["kernel"] == 1 or (plan["tail_blocks"] > 0 and plan["grid_y"] == 1), plan
-            mixed += plan["kernel"] == 0
+            two_sums = rnd == 1 and plan["valu_per_mac_x100"] >= 1000      # the round-to-odd variant has no mixed grid
+            assert plan["kernel"] == 1 or two_sums or (plan["tail_blocks"] > 0 and plan["grid_y"] == 1), plan
+            mixed += plan["tail_blocks"] > 0
             check(ref, A, B, qpf, qaf, "mixed grid", order=order)
     assert mixed >= 36
     # not used where it cannot help: exact multiples of a round, tiny and huge grids, the recompute call
