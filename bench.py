@@ -90,7 +90,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU (every output chain is independent; "
-                         "see DESIGN.md for how it would shard). Use --gpus 1.")
+                         "rows of A and of C would shard across GPUs with B replicated and nothing exchanged). Use --gpus 1.")
     import torch
     from paper_2401_14110_amd import binding as lb
     from paper_2401_14110_amd import inputs

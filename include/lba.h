@@ -169,6 +169,11 @@ int lba_gemm_bwd_diff(const uint8_t* A, const uint8_t* B, float* C, uint32_t* di
                       int64_t M, int64_t N, int64_t K,
                       lba_qfmt qprod, lba_qfmt qacc, int32_t order, float eps2, void* hip_stream);
 
+/* lba_gemm_bwd_diff for operands coded in fmt_a / fmt_b (x_k w_k is the product of the decoded codes). */
+int lba_gemm_bwd_diff_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* diff_mask,
+                         int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,
+                         lba_qfmt qprod, lba_qfmt qacc, int32_t order, float eps2, void* hip_stream);
+
 /* Number of uint32 words in one event plane: ceil(K / 32) * M * N (0 if any size is <= 0). */
 size_t lba_mask_words(int64_t M, int64_t N, int64_t K);
 

@@ -346,29 +346,47 @@ int lba_ref_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_
     return gemm_entry(A, B, C, of_mask, uf_mask, of2_mask, uf2_mask, M, N, K, cvt(qprod), cvt(qacc), order, nthreads);
 }
 
-// The DIFF plane (1 - STE^DIFF per step, first-level steps under either order) for a threshold
-// eps2 >= 0 given as a double; its exact value is used (any finite double is a dyadic number with an
-// odd integer mantissa below 2^53).
-int lba_ref_gemm_diff(const uint8_t* A, const uint8_t* B, float* C, uint32_t* diff_mask,
-                      int64_t M, int64_t N, int64_t K,
-                      lba_ref_qfmt qprod, lba_ref_qfmt qacc, int32_t order, double eps2, int32_t nthreads) {
-    if (!diff_mask && M * N * K > 0) return REF_ERR_NULL;
-    if (!(eps2 >= 0.0) || std::isinf(eps2)) return REF_ERR_FORMAT;
-    DiffEps eps = {true, 0, 0};
+typedef struct { int32_t exp_bits, man_bits, bias; } lba_ref_infmt;
+static InFmt cvt_in(lba_ref_infmt f) { InFmt r = {f.exp_bits, f.man_bits, f.bias}; return r; }
+
+// eps2 >= 0 as an exact dyadic number (any finite double is one, with an odd mantissa below 2^53)
+static bool parse_eps(double eps2, DiffEps* eps) {
+    if (!(eps2 >= 0.0) || std::isinf(eps2)) return false;
+    eps->on = true; eps->m = 0; eps->e = 0;
     if (eps2 > 0.0) {
         int e2;
         double fr = std::frexp(eps2, &e2);
         uint64_t mant = (uint64_t)std::ldexp(fr, 53);
         int e = e2 - 53;
         while ((mant & 1) == 0) { mant >>= 1; ++e; }
-        eps.m = mant; eps.e = e;
+        eps->m = mant; eps->e = e;
     }
+    return true;
+}
+
+// The DIFF plane (1 - STE^DIFF per step, first-level steps under either order) for a threshold
+// eps2 >= 0 given as a double; its exact value is used.
+int lba_ref_gemm_diff(const uint8_t* A, const uint8_t* B, float* C, uint32_t* diff_mask,
+                      int64_t M, int64_t N, int64_t K,
+                      lba_ref_qfmt qprod, lba_ref_qfmt qacc, int32_t order, double eps2, int32_t nthreads) {
+    if (!diff_mask && M * N * K > 0) return REF_ERR_NULL;
+    DiffEps eps;
+    if (!parse_eps(eps2, &eps)) return REF_ERR_FORMAT;
     return gemm_entry(A, B, C, nullptr, nullptr, nullptr, nullptr, M, N, K, cvt(qprod), cvt(qacc), order, nthreads,
                       kE4M3, kE4M3, diff_mask, eps);
 }
 
-typedef struct { int32_t exp_bits, man_bits, bias; } lba_ref_infmt;
-static InFmt cvt_in(lba_ref_infmt f) { InFmt r = {f.exp_bits, f.man_bits, f.bias}; return r; }
+// ... for operands in any 8-bit sign-exponent-mantissa code format
+int lba_ref_gemm_diff_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* diff_mask,
+                         int64_t M, int64_t N, int64_t K, lba_ref_infmt fmt_a, lba_ref_infmt fmt_b,
+                         lba_ref_qfmt qprod, lba_ref_qfmt qacc, int32_t order, double eps2, int32_t nthreads) {
+    if (!diff_mask && M * N * K > 0) return REF_ERR_NULL;
+    DiffEps eps;
+    if (!parse_eps(eps2, &eps)) return REF_ERR_FORMAT;
+    return gemm_entry(A, B, C, nullptr, nullptr, nullptr, nullptr, M, N, K, cvt(qprod), cvt(qacc), order, nthreads,
+                      cvt_in(fmt_a), cvt_in(fmt_b), diff_mask, eps);
+}
+
 
 // lba_ref_gemm / lba_ref_gemm_bwd for operands in any 8-bit sign-exponent-mantissa code format.
 int lba_ref_gemm_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,

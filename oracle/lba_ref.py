@@ -77,6 +77,10 @@ def lib():
         L.lba_ref_gemm_diff.argtypes = [u8p, u8p, ctypes.c_void_p, ctypes.c_void_p,
                                         ctypes.c_int64, ctypes.c_int64, ctypes.c_int64,
                                         QFmt, QFmt, ctypes.c_int32, ctypes.c_double, ctypes.c_int32]
+        L.lba_ref_gemm_diff_in.restype = ctypes.c_int
+        L.lba_ref_gemm_diff_in.argtypes = [u8p, u8p, ctypes.c_void_p, ctypes.c_void_p,
+                                           ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, InFmt, InFmt,
+                                           QFmt, QFmt, ctypes.c_int32, ctypes.c_double, ctypes.c_int32]
         L.lba_ref_gemm_in.restype = ctypes.c_int
         L.lba_ref_gemm_in.argtypes = [u8p, u8p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
                                       ctypes.c_int64, ctypes.c_int64, ctypes.c_int64, InFmt, InFmt,
@@ -221,9 +225,10 @@ def gemm_bwd(A, B, qprod, qacc, order=ORDER_SEQ, nthreads=None, level2=False):
     return C, of, uf
 
 
-def gemm_diff(A, B, qprod, qacc, eps2, order=ORDER_SEQ, nthreads=None):
+def gemm_diff(A, B, qprod, qacc, eps2, order=ORDER_SEQ, nthreads=None, fmt_a=None, fmt_b=None):
     """(C, DIFF plane): bit k of an output's words is 1 - STE^DIFF of step k (Sec. 4, App. D of the paper) for
-    the threshold eps2 >= 0 (eps1 -> 0+), first-level steps under either order; uint32 [ceil(K/32), M, N]."""
+    the threshold eps2 >= 0 (eps1 -> 0+), first-level steps under either order; uint32 [ceil(K/32), M, N].
+    fmt_a / fmt_b: operand code formats (default E4M3)."""
     A = _u8(A)
     B = _u8(B)
     M, K = A.shape
@@ -231,8 +236,13 @@ def gemm_diff(A, B, qprod, qacc, eps2, order=ORDER_SEQ, nthreads=None):
     assert K == K2
     C = np.empty((M, N), dtype=np.float32)
     diff = np.empty(((K + 31) // 32, M, N), dtype=np.uint32)
-    rc = lib().lba_ref_gemm_diff(A.ctypes.data, B.ctypes.data, C.ctypes.data, diff.ctypes.data, M, N, K,
-                                 qprod, qacc, order, float(eps2), _threads(nthreads))
+    if fmt_a is not None or fmt_b is not None:
+        rc = lib().lba_ref_gemm_diff_in(A.ctypes.data, B.ctypes.data, C.ctypes.data, diff.ctypes.data, M, N, K,
+                                        fmt_a or InFmt(4, 3, 7), fmt_b or InFmt(4, 3, 7),
+                                        qprod, qacc, order, float(eps2), _threads(nthreads))
+    else:
+        rc = lib().lba_ref_gemm_diff(A.ctypes.data, B.ctypes.data, C.ctypes.data, diff.ctypes.data, M, N, K,
+                                     qprod, qacc, order, float(eps2), _threads(nthreads))
     if rc != 0:
         raise ValueError("lba_ref_gemm_diff error %d" % rc)
     return C, diff

@@ -67,6 +67,9 @@ def lib():
         L.lba_gemm_batched.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, i64, i64, lba_qfmt, lba_qfmt, i32, vp]
         L.lba_gemm_bwd_diff.restype = ctypes.c_int
         L.lba_gemm_bwd_diff.argtypes = [vp, vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, i32, ctypes.c_float, vp]
+        L.lba_gemm_bwd_diff_in.restype = ctypes.c_int
+        L.lba_gemm_bwd_diff_in.argtypes = [vp, vp, vp, vp, i64, i64, i64, lba_infmt, lba_infmt, lba_qfmt, lba_qfmt, i32,
+                                           ctypes.c_float, vp]
         L.lba_gemm_bwd_chunked.restype = ctypes.c_int
         L.lba_gemm_bwd_chunked.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, vp]
         L.lba_mask_words_level2.restype = ctypes.c_size_t
@@ -146,6 +149,11 @@ def lba_gemm_batched(A, B, C, batch, stride_a, stride_b, stride_c, M, N, K, qpro
 
 def lba_gemm_bwd_diff(A, B, C, diff_mask, M, N, K, qprod, qacc, order, eps2, hip_stream=None):
     return lib().lba_gemm_bwd_diff(A, B, C, diff_mask, M, N, K, qfmt(qprod), qfmt(qacc), order, float(eps2), hip_stream)
+
+
+def lba_gemm_bwd_diff_in(A, B, C, diff_mask, M, N, K, fmt_a, fmt_b, qprod, qacc, order, eps2, hip_stream=None):
+    return lib().lba_gemm_bwd_diff_in(A, B, C, diff_mask, M, N, K, infmt(fmt_a), infmt(fmt_b), qfmt(qprod), qfmt(qacc),
+                                      order, float(eps2), hip_stream)
 
 
 def lba_gemm_bwd_chunked(A, B, C, of_mask, uf_mask, of_mask2, uf_mask2, M, N, K, qprod, qacc, hip_stream=None):
@@ -279,13 +287,20 @@ def gemm_bwd(A, B, qprod, qacc, order=ORDER_SEQ, want_c=True, stream=None, want_
     return C, of, uf
 
 
-def gemm_bwd_diff(A, B, qprod, qacc, eps2, order=ORDER_SEQ, want_c=True, stream=None):
-    """Returns (C or None, DIFF plane [ceil(K/32), M, N] int32): bit k is 1 - STE^DIFF of step k."""
+def gemm_bwd_diff(A, B, qprod, qacc, eps2, order=ORDER_SEQ, want_c=True, stream=None, fmt_a=None, fmt_b=None):
+    """Returns (C or None, DIFF plane [ceil(K/32), M, N] int32): bit k is 1 - STE^DIFF of step k.
+    With fmt_a / fmt_b: lba_gemm_bwd_diff_in."""
     A, B = _ops(A, B)
     M, K = A.shape
     N = B.shape[0]
     C = torch.empty((M, N), dtype=torch.float32, device=A.device) if want_c else None
     diff = torch.empty(((K + 31) // 32, M, N), dtype=torch.int32, device=A.device)
+    if fmt_a is not None or fmt_b is not None:
+        _check(lib().lba_gemm_bwd_diff_in(A.data_ptr() or None, B.data_ptr() or None,
+                                          (C.data_ptr() or None) if want_c else None, diff.data_ptr() or None, M, N, K,
+                                          infmt(fmt_a or (4, 3, 7)), infmt(fmt_b or (4, 3, 7)), qfmt(qprod), qfmt(qacc),
+                                          order, float(eps2), _stream(stream)))
+        return C, diff
     _check(lib().lba_gemm_bwd_diff(A.data_ptr() or None, B.data_ptr() or None, (C.data_ptr() or None) if want_c else None,
                                    diff.data_ptr() or None, M, N, K, qfmt(qprod), qfmt(qacc), order, float(eps2),
                                    _stream(stream)))

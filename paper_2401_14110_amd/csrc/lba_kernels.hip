@@ -142,7 +142,7 @@ int lba_gemm_bwd_chunked(const uint8_t* A, const uint8_t* B, float* C,
 // both quantizer biases lowered by delta (Sec. 2.3: Q_{M,E,b}(2^-T y) = 2^-T Q_{M,E,b-T}(y)).
 static int run_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
                   int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b, lba_qfmt qprod, lba_qfmt qacc,
-                  int32_t order, int events, void* hip_stream) {
+                  int32_t order, int events, void* hip_stream, float diff_eps = 0.0f) {
     lba::InSpec in;
     int rc = lba::make_in_spec(fmt_a, fmt_b, &in);
     if (rc != LBA_OK) return rc;
@@ -150,7 +150,7 @@ static int run_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mas
     qprod.bias -= in.delta;
     qacc.bias -= in.delta;
     return lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, order, events, hip_stream, 1, 0, 0, 0,
-                    nullptr, nullptr, &in);
+                    nullptr, nullptr, &in, nullptr, 0, 0, diff_eps);
 }
 
 int lba_gemm_in(const uint8_t* A, const uint8_t* B, float* C, int64_t M, int64_t N, int64_t K,
@@ -163,6 +163,16 @@ int lba_gemm_bwd_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_m
                     lba_qfmt qprod, lba_qfmt qacc, int32_t order, void* hip_stream) {
     if (order == LBA_ORDER_CHUNK16) return LBA_ERR_UNSUPPORTED;
     return run_in(A, B, C, of_mask, uf_mask, M, N, K, fmt_a, fmt_b, qprod, qacc, order, 1, hip_stream);
+}
+
+int lba_gemm_bwd_diff_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* diff_mask,
+                         int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,
+                         lba_qfmt qprod, lba_qfmt qacc, int32_t order, float eps2, void* hip_stream) {
+    if (!diff_eps_ok(eps2)) {                                  // reported after a format error, like lba_gemm_bwd_diff
+        const int rc = run_in(nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, 0, fmt_a, fmt_b, qprod, qacc, order, 2, hip_stream);
+        return rc != LBA_OK ? rc : LBA_ERR_FORMAT;
+    }
+    return run_in(A, B, C, diff_mask, nullptr, M, N, K, fmt_a, fmt_b, qprod, qacc, order, 2, hip_stream, eps2);
 }
 
 int lba_conv2d_out_shape(lba_conv2d_desc d, int32_t* oh, int32_t* ow) {

@@ -101,12 +101,14 @@ def chain_chunk16(a_codes, b_codes, qp, qa, with_events=False):
     return (t, ev1, ev2) if with_events else t
 
 
-def ste_diff(a_code, b_code, s, qp, qa, eps2, eps1=None):
+def ste_diff(a_code, b_code, s, qp, qa, eps2, eps1=None, in_a=None, in_b=None):
     """STE^DIFF of one step (Sec. 4 / App. D): 1 iff |FMAq(x, w, s) - s| / (|x w| + eps1) > eps2, as the ratio
     it is written as.  eps1 = None is the limit eps1 -> 0+: a zero product makes the ratio 0 (the numerator is 0
     too: Q_acc(0 + s) = s for s on the accumulator's grid)."""
-    xw = e4m3_value(a_code) * e4m3_value(b_code)
-    z, _, _ = fmaq(a_code, b_code, s, qp, qa)
+    va = e4m3_value(a_code) if in_a is None else code_value(a_code, *in_a)
+    vb = e4m3_value(b_code) if in_b is None else code_value(b_code, *in_b)
+    xw = va * vb
+    z, _, _ = fmaq(a_code, b_code, s, qp, qa, in_a, in_b)
     num = abs(z - s)
     if eps1 is None:
         if xw == 0:
@@ -118,11 +120,11 @@ def ste_diff(a_code, b_code, s, qp, qa, eps2, eps1=None):
     return 1 if ratio > F(eps2) else 0
 
 
-def chain_diff(a_codes, b_codes, qp, qa, eps2, eps1=None):
+def chain_diff(a_codes, b_codes, qp, qa, eps2, eps1=None, in_a=None, in_b=None):
     """(value, [STE^DIFF per step]) of a sequential chain."""
     s = F(0)
     out = []
     for a, b in zip(a_codes, b_codes):
-        out.append(ste_diff(a, b, s, qp, qa, eps2, eps1))
-        s, _, _ = fmaq(a, b, s, qp, qa)
+        out.append(ste_diff(a, b, s, qp, qa, eps2, eps1, in_a, in_b))
+        s, _, _ = fmaq(a, b, s, qp, qa, in_a, in_b)
     return s, out

@@ -101,6 +101,11 @@ def test_diff_threshold_is_validated():
     assert call(0.5, order=7) == lb.ERR_UNSUPPORTED
     assert call(0.5, order=1) == lb.OK
     assert lb.lba_gemm_bwd_diff(A, B, C, None, 8, 8, 8, GOOD_P, GOOD_A, 0, 0.5) == lb.ERR_NULL
+    m4e3 = (3, 4, 3)
+    assert lb.lba_gemm_bwd_diff_in(A, B, C, D, 0, 8, 8, m4e3, m4e3, GOOD_P, GOOD_A, 1, 0.5) == lb.OK
+    assert lb.lba_gemm_bwd_diff_in(A, B, C, D, 0, 8, 8, m4e3, m4e3, GOOD_P, GOOD_A, 0, 0.3) == lb.ERR_FORMAT
+    assert lb.lba_gemm_bwd_diff_in(A, B, C, D, 0, 8, 8, (3, 3, 3), m4e3, GOOD_P, GOOD_A, 0, 0.5) == lb.ERR_FORMAT
+    assert lb.lba_gemm_bwd_diff_in(A, B, C, None, 8, 8, 8, m4e3, m4e3, GOOD_P, GOOD_A, 0, 0.5) == lb.ERR_NULL
 
 
 def test_plan_picks_the_scaled_kernel_for_the_paper_formats():

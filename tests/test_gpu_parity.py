@@ -459,6 +459,20 @@ def test_diff_plane(ref):
     torch.cuda.synchronize()
     _, wd = ref.gemm_diff(A, B, ref.QFmt(5, 7, 15, 0), ref.QFmt(4, 7, 7, 0), 2731 * 2.0 ** -13)
     assert C is None and np.array_equal(diff.cpu().numpy().view(np.uint32), wd)
+    # other operand formats (the paper's M4E3 weights and activations with per-tensor biases): lba_gemm_bwd_diff_in
+    A = rng.integers(0, 256, (70, 100)).astype(np.uint8); B = rng.integers(0, 256, (66, 100)).astype(np.uint8)
+    tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    for (ia, ib), (qp, qa), rnd, order in [(((3, 4, 3), (3, 4, 5)), ((5, 7, 15), (4, 7, 7)), 0, 0),
+                                           (((3, 4, 2), (4, 3, 7)), ((5, 7, 15), (4, 7, 7)), 1, 1),
+                                           (((2, 5, 0), (5, 2, 12)), ((5, 5, 12), (5, 9, 14)), 1, 0),
+                                           (((3, 4, 4), (3, 4, 4)), ((3, 4, 6), (3, 4, 6)), 0, 1)]:
+        for eps2 in (0.0, 0.25, 0.875):
+            C, diff = lb.gemm_bwd_diff(tA, tB, qp + (rnd,), qa + (rnd,), eps2, order=order, fmt_a=ia, fmt_b=ib)
+            torch.cuda.synchronize()
+            wc, wd = ref.gemm_diff(A, B, fm(ref, qp + (rnd,)), fm(ref, qa + (rnd,)), eps2, order=order,
+                                   fmt_a=ref.InFmt(*ia), fmt_b=ref.InFmt(*ib))
+            assert np.array_equal(bits(C.cpu().numpy()), bits(wc)), (ia, ib, qp, qa, rnd, order, eps2)
+            assert np.array_equal(diff.cpu().numpy().view(np.uint32), wd), (ia, ib, qp, qa, rnd, order, eps2)
     # empty chains and empty outputs
     z = torch.empty((4, 0), dtype=torch.uint8, device=DEV)
     C, diff = lb.gemm_bwd_diff(z, z, (5, 7, 15, 0), (4, 7, 7, 0), 0.5)

@@ -573,6 +573,16 @@ def test_input_code_formats(ref):
                 for k in range(K):
                     got = (bool((int(of[0, i, j]) >> k) & 1), bool((int(uf[0, i, j]) >> k) & 1))
                     assert got == evs[k], (ia, ib, k)
+        # the DIFF plane with these operand formats: the un-quantized product is the one of the decoded codes
+        for eps2 in (0.0, 0.25, 0.875):
+            Cd, diff = ref.gemm_diff(A, B, ref.QFmt(*fp, rnd), ref.QFmt(*fa, rnd), eps2, fmt_a=ref.InFmt(*ia), fmt_b=ref.InFmt(*ib))
+            assert np.array_equal(Cd, C)
+            for i in range(3):
+                for j in range(2):
+                    _, ste = FM.chain_diff([int(c) for c in A[i]], [int(c) for c in B[j]], fp + (rnd,), fa + (rnd,),
+                                           Fraction(eps2), None, ia, ib)
+                    for k in range(K):
+                        assert (int(diff[0, i, j]) >> k) & 1 == 1 - ste[k], (ia, ib, eps2, i, j, k)
     # the exponent biases are power-of-two scales: moving them moves the quantizers' biases and the result
     A = rng.integers(0, 256, (6, 50)).astype(np.uint8); B = rng.integers(0, 256, (5, 50)).astype(np.uint8)
     base = ref.gemm_in(A, B, ref.InFmt(3, 4, 3), ref.InFmt(3, 4, 3), ref.QFmt(5, 7, 15, 0), ref.QFmt(4, 7, 7, 0))
