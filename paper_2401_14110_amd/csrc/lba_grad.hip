@@ -28,6 +28,11 @@
 
 namespace lba {
 
+// lba_grad_mfma.hip: the identity estimator as a dense contraction on the matrix cores
+bool grad_dense_ok(const float* G, const uint8_t* V, const int32_t* last_of, int64_t M, int64_t N, int64_t K);
+int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* last_of, float* out,
+                   int64_t M, int64_t N, int64_t K, hipStream_t st);
+
 // Sizes of one launch; the pointers are separate kernel arguments so that they can be declared
 // non-aliasing, which is what lets the compiler fetch the wave-uniform values with scalar loads.
 struct GradDims {
@@ -395,6 +400,11 @@ static hipError_t launch_grad(int ste, const float* G, const uint8_t* V, const u
 // One of the two products.  Splits s over grid z when the (r, k) grid alone would leave the chip idle.
 static int run_grad_side(bool dx, const float* G, const uint8_t* V, const uint32_t* plane, const int32_t* last_of,
                          float* out, int64_t M, int64_t N, int64_t K, int ste, hipStream_t st) {
+    // coefficients that are constant inside a k tile: the matrix-core path (identity; recursive, with a sliver pass)
+    if (ste == LBA_STE_IDENTITY && grad_dense_ok(G, V, nullptr, M, N, K))
+        return run_grad_dense(dx, G, V, nullptr, out, M, N, K, st);
+    if (ste == LBA_STE_RECURSIVE_OF && grad_dense_ok(G, V, last_of, M, N, K))
+        return run_grad_dense(dx, G, V, last_of, out, M, N, K, st);
     GradDims gp;
     gp.plane_xor = (ste == LBA_STE_COEF_PLANE) ? 0u : 0xFFFFFFFFu;
     if (ste == LBA_STE_COEF_PLANE) ste = LBA_STE_IMMEDIATE_OF;   // same kernel, bits taken as they are

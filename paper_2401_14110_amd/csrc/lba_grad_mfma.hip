@@ -1,0 +1,292 @@
+// lba_grad_mfma.hip -- the gradient products whose coefficients do not depend on k inside a tile, as a
+// dense contraction on the matrix cores of gfx950.
+//
+//   out[r, k] = sum_s g'(r, s) * value(V[s, k])          dX: r = m, s = n, V = B;  dW: r = n, s = m, V = A
+//
+// With the identity estimator (Sec. 4 of the paper: c = 1) g' = g and this is a plain matrix product of an
+// FP32 matrix with a matrix of FP8 values.  The FP32 factor is split exactly into three bfloat16 pieces
+// (g = hi + mid + lo, 8 significant bits each: truncate, subtract, truncate, subtract; every step is exact),
+// an E4M3 value is a bfloat16 number as it is, so the three bfloat16 products hi*v, mid*v, lo*v are exact
+// and their FP32 accumulation in v_mfma_f32_32x32x16_bf16 is the FP32 sum of products the interface
+// promises (order of summation unspecified; pieces or products below the FP32 normal range, i.e. gradients
+// under about 2^-100, may be flushed).  Three MFMA passes at the bfloat16 rate are about five times
+// the FP32 rate of the vector units or of the FP32 MFMA.
+//
+// The recursive estimator under the sequential order (App. D: c = [k > last overflow index L(r, s)]) is the same
+// contraction for all but a sliver of the work: inside a 128-wide k tile starting at k0 a pair (r, s) with
+// L < k0 has c = 1 for every k of the tile, a pair with L beyond the tile has c = 0, so the tile is the dense
+// product with g' = [L < k0] g (the mask is applied while G is staged).  What is left are the k between L and
+// the end of L's own 128-block, at most 127 per pair: lba_grad_boundary_kernel visits every pair once
+// (one workgroup per row r, its K sums in LDS, a wave per pair with lanes along k) and adds that sliver.
+//
+// Tiling: a workgroup of four waves owns 128 rows x 128 k; a wave owns 64 x 64 (2 x 2 MFMA blocks of
+// 32 x 32, 64 accumulator registers).  s advances in steps of 32: the lanes fetch 4 x 4 patches of G (FP32)
+// and of V (codes), split / decode them and store bfloat16 rows [row][s] (G) and [k][s] (V, transposed) in
+// LDS with a pitch of 40 elements, which makes the 16-byte fragment reads of a wave conflict-free.
+// Operand fragments: lane l holds row (or column) l % 32 and the eight s values 8 * (l / 32) .. + 7 of a
+// 16-deep step, the same mapping for both operands, so the contraction pairs equal s whatever order the
+// hardware walks them in.  Results: register t of lane l is row 8 * (t / 4) + 4 * (l / 32) + t % 4, column l % 32.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lba.h"
+#include "lba_internal.h"
+
+namespace lba {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+struct DenseDims {
+    int32_t R, S, K;
+    int32_t s_chunk;           // s values per grid z (a multiple of 32)
+    int32_t atomic;            // 1: gridDim.z > 1, combine with atomic adds into a zeroed output
+    int32_t ld_g;              // N: G[m * N + n]
+};
+
+constexpr int DTR = 128, DTK = 128, DBS = 32, DPITCH = 40;
+static_assert(DTK == 128, "lba_grad_boundary_kernel cuts k into the same 128-blocks (its shift by 7)");
+
+__device__ __forceinline__ float dense_decode_e4m3(uint32_t code) {
+    float v = __builtin_amdgcn_cvt_f32_fp8((int)code, 0);
+    if ((code & 0x7Fu) == 0x7Fu) v = (code & 0x80u) ? -480.0f : 480.0f;   // the two NaN codes
+    return v;
+}
+
+// g = hi + mid + lo with 8 significant bits each; returns the three bfloat16 words (top halves)
+__device__ __forceinline__ void split3(float g, uint32_t& hi, uint32_t& mid, uint32_t& lo) {
+    const uint32_t h = __float_as_uint(g) & 0xFFFF0000u;
+    const float r1 = g - __uint_as_float(h);                   // exact: the low 16 bits of g's significand
+    const uint32_t m = __float_as_uint(r1) & 0xFFFF0000u;
+    const float r2 = r1 - __uint_as_float(m);                  // exact, at most 8 significant bits
+    hi = h >> 16; mid = m >> 16; lo = __float_as_uint(r2) >> 16;
+}
+
+// S_CONTIG: G(r, s) = G[r * ld + s] (dX); else G(r, s) = G[s * ld + r] (dW).  MASKED: L (same layout as G)
+// holds last-overflow indices and g' = [L < k0] g.
+template <bool S_CONTIG, bool MASKED>
+__global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __restrict__ G, const uint8_t* __restrict__ V,
+                                                                const int32_t* __restrict__ L,
+                                                                float* __restrict__ out, const DenseDims d) {
+    __shared__ __attribute__((aligned(16))) uint16_t sA[3][DTR * DPITCH];
+    __shared__ __attribute__((aligned(16))) uint16_t sB[DTK * DPITCH];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wy = wave >> 1, wx = wave & 1;
+    const int r0 = blockIdx.x * DTR, k0 = blockIdx.y * DTK;
+    const int s_begin = blockIdx.z * d.s_chunk;
+    const int s_end = min(d.S, s_begin + d.s_chunk);
+
+    // this lane's 4 x 4 patch of the G tile and of the V tile
+    const int a_pr = S_CONTIG ? (tid >> 3) : (tid & 31);       // patch row (4 rows r)
+    const int a_ps = S_CONTIG ? (tid & 7) : (tid >> 5);        // patch column (4 values of s)
+    const int b_ps = tid >> 5, b_pk = tid & 31;                // 4 rows s, 4 codes k
+
+    float4 gl[4];
+    uint32_t vl[4];
+    auto fetch = [&](int sb) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            float4 g = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            if (S_CONTIG) {                                    // q: row within the patch; the float4 runs along s
+                const int r = r0 + 4 * a_pr + q, s = sb + 4 * a_ps;
+                if (r < d.R && s < s_end) {
+                    g = *reinterpret_cast<const float4*>(G + (int64_t)r * d.ld_g + s);
+                    if (MASKED) {
+                        const int4 t = *reinterpret_cast<const int4*>(L + (int64_t)r * d.ld_g + s);
+                        g.x = t.x < k0 ? g.x : 0.0f; g.y = t.y < k0 ? g.y : 0.0f;
+                        g.z = t.z < k0 ? g.z : 0.0f; g.w = t.w < k0 ? g.w : 0.0f;
+                    }
+                }
+                if (s + 3 >= s_end) {                          // a chunk may end inside the float4 (s_chunk % 4 == 0: never; kept for S % 4)
+                    if (s + 1 >= s_end) g.y = 0.0f;
+                    if (s + 2 >= s_end) g.z = 0.0f;
+                    if (s + 3 >= s_end) g.w = 0.0f;
+                }
+            } else {                                           // q: s within the patch; the float4 runs along r
+                const int r = r0 + 4 * a_pr, s = sb + 4 * a_ps + q;
+                if (r < d.R && s < s_end) {
+                    g = *reinterpret_cast<const float4*>(G + (int64_t)s * d.ld_g + r);
+                    if (MASKED) {
+                        const int4 t = *reinterpret_cast<const int4*>(L + (int64_t)s * d.ld_g + r);
+                        g.x = t.x < k0 ? g.x : 0.0f; g.y = t.y < k0 ? g.y : 0.0f;
+                        g.z = t.z < k0 ? g.z : 0.0f; g.w = t.w < k0 ? g.w : 0.0f;
+                    }
+                }
+            }
+            gl[q] = g;
+            const int sv = sb + 4 * b_ps + q, kv = k0 + 4 * b_pk;
+            vl[q] = (sv < s_end && kv < d.K) ? *reinterpret_cast<const uint32_t*>(V + (int64_t)sv * d.K + kv) : 0u;
+        }
+    };
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.0f;
+
+    fetch(s_begin);
+    for (int sb = s_begin; sb < s_end; sb += DBS) {
+        // split / decode this step's patches into LDS
+        {
+            float g[4][4];                                     // [row a][s b]
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float x[4] = {gl[q].x, gl[q].y, gl[q].z, gl[q].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    if (S_CONTIG) g[q][e] = x[e]; else g[e][q] = x[e];
+                }
+            }
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+                uint32_t h[4], m[4], l[4];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) split3(g[a][b], h[b], m[b], l[b]);
+                const int off = (4 * a_pr + a) * DPITCH + 4 * a_ps;
+                *reinterpret_cast<uint2*>(&sA[0][off]) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
+                *reinterpret_cast<uint2*>(&sA[1][off]) = make_uint2(m[0] | (m[1] << 16), m[2] | (m[3] << 16));
+                *reinterpret_cast<uint2*>(&sA[2][off]) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {                      // code c of each of the four rows s
+                uint32_t w[4];
+#pragma unroll
+                for (int b = 0; b < 4; ++b) w[b] = __float_as_uint(dense_decode_e4m3((vl[b] >> (8 * c)) & 0xFFu)) >> 16;
+                *reinterpret_cast<uint2*>(&sB[(4 * b_pk + c) * DPITCH + 4 * b_ps]) = make_uint2(w[0] | (w[1] << 16), w[2] | (w[3] << 16));
+            }
+        }
+        __syncthreads();
+        if (sb + DBS < s_end) fetch(sb + DBS);                 // in flight during the MFMAs
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            const int so = kk * 16 + 8 * (lane >> 5);
+            bf16x8 bf[2];
+#pragma unroll
+            for (int bj = 0; bj < 2; ++bj)
+                bf[bj] = *reinterpret_cast<const bf16x8*>(&sB[(wx * 64 + bj * 32 + (lane & 31)) * DPITCH + so]);
+#pragma unroll
+            for (int sp = 0; sp < 3; ++sp)
+#pragma unroll
+                for (int bi = 0; bi < 2; ++bi) {
+                    const bf16x8 af = *reinterpret_cast<const bf16x8*>(&sA[sp][(wy * 64 + bi * 32 + (lane & 31)) * DPITCH + so]);
+#pragma unroll
+                    for (int bj = 0; bj < 2; ++bj)
+                        acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf[bj], acc[bi][bj], 0, 0, 0);
+                }
+        }
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 2; ++bj) {
+            const int col = k0 + wx * 64 + bj * 32 + (lane & 31);
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+                const int row = r0 + wy * 64 + bi * 32 + 8 * (t >> 2) + 4 * (lane >> 5) + (t & 3);
+                if (row < d.R && col < d.K) {
+                    float* dst = out + (int64_t)row * d.K + col;
+                    if (d.atomic) unsafeAtomicAdd(dst, acc[bi][bj][t]);
+                    else          *dst = acc[bi][bj][t];
+                }
+            }
+        }
+}
+
+// The sliver of the recursive estimator that the masked dense product leaves out: for every pair (r, s) with
+// L = L(r, s) >= 0 the terms g(r, s) * value(V[s, k]) for L < k < end of L's 128-block.  One workgroup per row r
+// keeps the K sums of that row in LDS; a wave takes 64 consecutive s at a time (their L and g in its lanes),
+// then one pair after the other with its lanes along k.  out[r, :] += sums (the dense part is already there).
+template <bool S_CONTIG>
+__global__ void __launch_bounds__(256) lba_grad_boundary_kernel(const float* __restrict__ G, const uint8_t* __restrict__ V,
+                                                                const int32_t* __restrict__ L,
+                                                                float* __restrict__ out, const DenseDims d) {
+    extern __shared__ float row[];                             // K sums
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = blockIdx.x;
+    for (int k = tid; k < d.K; k += 256) row[k] = 0.0f;
+    __syncthreads();
+    for (int s0 = wave * 64; s0 < d.S; s0 += 256) {
+        const int s = s0 + lane;
+        int32_t lv = -1;
+        float gv = 0.0f;
+        if (s < d.S) {
+            const int64_t off = S_CONTIG ? (int64_t)r * d.ld_g + s : (int64_t)s * d.ld_g + r;
+            lv = L[off];
+            gv = G[off];
+        }
+        uint64_t todo = __builtin_amdgcn_ballot_w64(lv >= 0 && gv != 0.0f);
+        while (todo) {                                         // wave-uniform loop over the pairs that have a sliver
+            const int j = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const int32_t lj = __builtin_amdgcn_readlane(lv, j);
+            const float gj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(gv), j));
+            const int k_end = min(d.K, ((lj >> 7) + 1) << 7);
+            const uint8_t* __restrict__ vrow = V + (int64_t)(s0 + j) * d.K;
+            for (int k = lj + 1 + lane; k < k_end; k += 64)
+                atomicAdd(&row[k], gj * dense_decode_e4m3(vrow[k]));
+        }
+    }
+    __syncthreads();
+    for (int k = tid; k < d.K; k += 256) {
+        const float x = row[k];
+        if (x != 0.0f) out[(int64_t)r * d.K + k] += x;
+    }
+}
+
+__global__ void lba_grad_dense_zero_kernel(float* x, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) x[i] = 0.0f;
+}
+
+// Can the matrix-core path take this product?  16-byte rows of G (and of last_of) in both directions, 4-byte
+// groups of codes; with last_of also a row of K sums within 48 KB of LDS.
+bool grad_dense_ok(const float* G, const uint8_t* V, const int32_t* last_of, int64_t M, int64_t N, int64_t K) {
+    if (((uintptr_t)G % 16) != 0 || ((uintptr_t)V % 4) != 0 || (N % 4) != 0 || (K % 4) != 0 || (K + DTK - 1) / DTK > 65535)
+        return false;
+    if (last_of && (((uintptr_t)last_of % 16) != 0 || K > 12288)) return false;
+    return true;
+}
+
+// One of the two products with the identity coefficients (last_of == NULL) or the recursive ones.
+// LBA_OK or LBA_ERR_LAUNCH.
+int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* last_of, float* out,
+                   int64_t M, int64_t N, int64_t K, hipStream_t st) {
+    DenseDims d;
+    d.R = (int32_t)(dx ? M : N); d.S = (int32_t)(dx ? N : M); d.K = (int32_t)K; d.ld_g = (int32_t)N;
+    const int64_t gx = (d.R + DTR - 1) / DTR, gy = (K + DTK - 1) / DTK;
+    // enough workgroups for two per CU: cut s into slices of a multiple of 32
+    int64_t split = 1;
+    const int64_t steps = (d.S + DBS - 1) / DBS;
+    while (gx * gy * split < 512 && split * 2 <= steps && split < 64) split *= 2;
+    const int64_t per = (steps + split - 1) / split;
+    d.s_chunk = (int32_t)(per * DBS);
+    split = (d.S + d.s_chunk - 1) / d.s_chunk;
+    d.atomic = split > 1 ? 1 : 0;
+    if (d.atomic) {
+        const int64_t n = (int64_t)d.R * K;
+        hipLaunchKernelGGL(lba_grad_dense_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, out, n);
+        if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
+    }
+    const dim3 grid((unsigned)gx, (unsigned)gy, (unsigned)split);
+    if (!last_of) {
+        if (dx) hipLaunchKernelGGL((lba_grad_dense_kernel<true, false>), grid, dim3(256), 0, st, G, V, last_of, out, d);
+        else    hipLaunchKernelGGL((lba_grad_dense_kernel<false, false>), grid, dim3(256), 0, st, G, V, last_of, out, d);
+        return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
+    }
+    if (dx) hipLaunchKernelGGL((lba_grad_dense_kernel<true, true>), grid, dim3(256), 0, st, G, V, last_of, out, d);
+    else    hipLaunchKernelGGL((lba_grad_dense_kernel<false, true>), grid, dim3(256), 0, st, G, V, last_of, out, d);
+    if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
+    const dim3 rows((unsigned)d.R);
+    const size_t lds = (size_t)K * sizeof(float);
+    if (dx) hipLaunchKernelGGL((lba_grad_boundary_kernel<true>), rows, dim3(256), lds, st, G, V, last_of, out, d);
+    else    hipLaunchKernelGGL((lba_grad_boundary_kernel<false>), rows, dim3(256), lds, st, G, V, last_of, out, d);
+    return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
+}
+
+}  // namespace lba

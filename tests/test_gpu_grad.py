@@ -116,6 +116,57 @@ def test_immediate_estimator_with_the_diff_plane(ref, gref):
         assert not np.array_equal(wX, oX)                               # DIFF blocks more than overflow alone
 
 
+def test_matrix_core_path_identity_and_recursive(ref, gref):
+    # Shapes the dense (matrix-core) path takes (N % 4 == 0, K % 4 == 0): ragged against its 128 x 128 tiles and
+    # 32-deep steps, several k blocks, sums split over workgroups.  The recursive estimator gets last-overflow
+    # indices written by hand: every position relative to the 128-blocks (first and last k of a block, K - 1,
+    # none), so that the masked dense part and the sliver pass must meet exactly.  Bit-exact on data whose
+    # sums are exactly representable, then the FP32 bound on general data.
+    rng = np.random.default_rng(314)
+    for (M, N, K) in [(130, 68, 260), (260, 132, 132), (64, 516, 640), (3000, 24, 40), (40, 2100, 72), (128, 128, 128),
+                      (257, 36, 1028)]:
+        A = codes(rng, (M, K), 5, 10); B = codes(rng, (N, K), 5, 10)
+        tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+        last = rng.integers(-1, K, (M, N)).astype(np.int32)
+        edge = rng.integers(0, 8, (M, N))
+        last = np.where(edge == 0, -1, last)
+        last = np.where(edge == 1, K - 1, last)
+        last = np.where(edge == 2, (last // 128) * 128, last)                     # first k of a block
+        last = np.where(edge == 3, np.minimum((last // 128) * 128 + 127, K - 1), last)   # last k of a block
+        tL = torch.from_numpy(last).to(DEV)
+        c_rec = np.arange(K)[None, None, :] > last[:, :, None]
+        for exact in (True, False):
+            G = (rng.integers(-8, 9, (M, N)) / 4.0).astype(np.float32) if exact else rng.standard_normal((M, N)).astype(np.float32)
+            tG = torch.from_numpy(G).to(DEV)
+            for ste, c in ((lb.STE_IDENTITY, None), (lb.STE_RECURSIVE_OF, c_rec)):
+                dX, dW = lb.grad(tG, tA, tB, ste, last_of=tL if ste == lb.STE_RECURSIVE_OF else None)
+                torch.cuda.synchronize()
+                dX, dW = dX.cpu().numpy(), dW.cpu().numpy()
+                cc = c if c is not None else np.ones((M, N, K), dtype=bool)
+                wX, wW = gref.grad(G, A, B, None, None, ste, c=cc)
+                if exact:
+                    assert np.array_equal(dX, wX.astype(np.float32)), (M, N, K, ste, "dX", np.abs(dX - wX).max())
+                    assert np.array_equal(dW, wW.astype(np.float32)), (M, N, K, ste, "dW", np.abs(dW - wW).max())
+                else:
+                    aX, aW = gref.grad_abs(G, A, B, None, None, ste, c=cc)
+                    assert (np.abs(dX - wX) <= 2 * (N + 1) * 2.0 ** -24 * aX + 1e-30).all(), (M, N, K, ste, "dX")
+                    assert (np.abs(dW - wW) <= 2 * (M + 1) * 2.0 ** -24 * aW + 1e-30).all(), (M, N, K, ste, "dW")
+    # the split of an FP32 factor into three bfloat16 pieces is exact (as long as the pieces and the products stay
+    # FP32 normals): one term per sum, so the product itself must come back
+    g = np.array([[1.0 + 2.0 ** -23, -3.1415927, 2.0 ** -80 * 1.6180339, 2.0 ** -60 * (1 + 2.0 ** -12)],
+                  [16777215.0, -1e30, 2.0 ** 100, 7.0]], dtype=np.float32)
+    M, N, K = 2, 4, 8
+    A = np.zeros((M, K), dtype=np.uint8); B = np.zeros((N, K), dtype=np.uint8)
+    B[:, :] = np.array([0x38, 0x3C, 0xC1, 0x7E, 0x01, 0x08, 0xB9, 0x30], dtype=np.uint8)[None, :]
+    for n in range(N):                                               # one non-zero g per output sum
+        Gn = np.zeros_like(g); Gn[:, n] = g[:, n]
+        dX, _ = lb.grad(torch.from_numpy(Gn).to(DEV), torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV), lb.STE_IDENTITY)
+        torch.cuda.synchronize()
+        vals = np.array([ref.decode(int(c)) for c in B[n]], dtype=np.float64)
+        want = (Gn[:, n].astype(np.float64)[:, None] * vals[None, :]).astype(np.float32)
+        assert np.array_equal(dX.cpu().numpy(), want), n
+
+
 def test_arguments_views_and_degenerate_sizes(ref, gref):
     rng = np.random.default_rng(99)
     M, N, K = 40, 36, 50

@@ -341,6 +341,36 @@ def test_nearest_even_below_seven_mantissa_bits_keeps_ties_right(ref):
                 check(ref, A, B, (6, 7, 20, 1), (E, M, b, 1), "rne M=%d, Q_prod identity" % M)
 
 
+def test_random_formats(ref):
+    # a seeded sweep over the whole format space the ABI admits (E 2..7, M 1..23, biases that keep every value an
+    # FP32 normal, both roundings, the no-underflow flag, both orders): whichever kernel the planner picks
+    # (scaled, its round-to-odd variant, general) must give the oracle's bits
+    rng = np.random.default_rng(2024)
+    pyr = random.Random(2024)
+    A = rand_codes(rng, (40, 70)); B = rand_codes(rng, (36, 70))
+    picked = set()
+    done = 0
+    while done < 90:
+        fmts = []
+        for _ in range(2):
+            E = pyr.randint(2, 7); M = pyr.choice([1, 2, 3, 4, 5, 6, 7, 8, 10, 11, 13, 16, 20, 21, 22, 23])
+            lo, hi = (1 << E) - 128, 126                       # 2^E - b - 1 <= 127 and b <= 126
+            b = pyr.randint(max(lo, -20), min(hi, 40))
+            fmts.append((E, M, b))
+        rnd = pyr.randint(0, 1)
+        flags = pyr.choice([0, 0, 0, 0x100])
+        qpf, qaf = fmts[0] + (rnd | flags,), fmts[1] + (rnd | pyr.choice([0, 0, 0, 0x100]),)
+        order = pyr.randint(0, 1)
+        try:
+            plan = lb.lba_plan_query(40, 36, 70, qpf, qaf, order)
+        except lb.LbaError:
+            continue
+        picked.add((plan["kernel"], rnd, plan["valu_per_mac_x100"] >= 1000))
+        check(ref, A, B, qpf, qaf, "random format %d" % done, order=order)
+        done += 1
+    assert {(0, 0, False), (0, 1, False), (0, 1, True), (1, 1, False)} <= picked, picked
+
+
 def test_event_planes_of_the_chunked_order(ref):
     # first-level planes (bit k: step k of its own chunk's chain) and second-level planes (bit j: the add
     # of chunk j) for K below, at and across chunk, tile and second-level-word (512) boundaries; scaled
