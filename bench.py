@@ -146,6 +146,10 @@ def main():
             # VALU issue slots per masked MAC (one wave instruction = 64 MACs; half-rate forms count 2):
             # v_fmac with a scalar operand 2; + two v_readlane (immediate) or one v_cmp (recursive)
             l["plan"] = dict(l["plan"], kernel=2, prod_mode=ste, valu_per_mac_x100=(200, 600, 400)[ste])
+            # identity and (sequential) recursive coefficients are constant inside a k tile: lba_grad runs them as a
+            # dense product on the matrix cores when rows of G and groups of codes are aligned
+            if ste != 1 and l["N"] % 4 == 0 and l["K"] % 4 == 0 and (ste == 0 or l["K"] <= 12288):
+                l["plan"] = dict(l["plan"], kernel=3, valu_per_mac_x100=0)
             l["of"] = l["last"] = None
             if ste:
                 _, l["of"], _ = lb.gemm_bwd(l["A"], l["B"], l["qp"], l["qa"], want_c=False)
@@ -274,6 +278,14 @@ def main():
         "launches": dom["launches"], "mac_per_s": dom["macs"] / (dom["ms"] * 1e-3),
         "time_share": dom["ms"] / sum(g["ms"] for g in groups.values()),
     }
+
+    if args.grad and dom_key[0] == 3:
+        # three bfloat16 MFMA passes per FP32 x FP8 product (g is split exactly into three bfloat16 pieces):
+        # issued flops = 3 x 2 per masked MAC, against the dense bfloat16 peak of the matrix cores
+        issued = dom["macs"] * 6 / (dom["ms"] * 1e-3)
+        roofline.update({"bound": "mfma", "achieved": issued / 1e12, "peak": 2500.0, "unit": "TFLOP/s", "frac": issued / 2.5e15,
+                         "kernel": "lba_grad_dense_kernel<%s> (v_mfma_f32_32x32x16_bf16, 3 passes)" % args.grad,
+                         "algorithmic_tflops": dom["macs"] * 2 / (dom["ms"] * 1e-3) / 1e12, "valu_slots_per_mac": None})
 
     if args.per_layer:
         for i, l in enumerate(layers):

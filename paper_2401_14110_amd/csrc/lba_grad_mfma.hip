@@ -13,14 +13,14 @@
 // the FP32 rate of the vector units or of the FP32 MFMA.
 //
 // The recursive estimator under the sequential order (App. D: c = [k > last overflow index L(r, s)]) is the same
-// contraction for all but a sliver of the work: inside a 128-wide k tile starting at k0 a pair (r, s) with
+// contraction for all but a sliver of the work: inside a k tile (128 or 256 wide) starting at k0 a pair (r, s) with
 // L < k0 has c = 1 for every k of the tile, a pair with L beyond the tile has c = 0, so the tile is the dense
 // product with g' = [L < k0] g (the mask is applied while G is staged).  What is left are the k between L and
-// the end of L's own 128-block, at most 127 per pair: lba_grad_boundary_kernel visits every pair once
+// the end of L's own k block, fewer than the tile width per pair: lba_grad_boundary_kernel visits every pair once
 // (one workgroup per row r, its K sums in LDS, a wave per pair with lanes along k) and adds that sliver.
 //
-// Tiling: a workgroup of four waves owns 128 rows x 128 k; a wave owns 64 x 64 (2 x 2 MFMA blocks of
-// 32 x 32, 64 accumulator registers).  s advances in steps of 32: the lanes fetch 4 x 4 patches of G (FP32)
+// Tiling: a workgroup of four waves owns 128 rows x 128 (or 256) k; a wave owns 64 x 64 (or 64 x 128): 2 x 2
+// (2 x 4) MFMA blocks of 32 x 32, 64 (128) accumulator registers.  s advances in steps of 32: the lanes fetch 4 x 4 patches of G (FP32)
 // and of V (codes), split / decode them and store bfloat16 rows [row][s] (G) and [k][s] (V, transposed) in
 // LDS with a pitch of 40 elements, which makes the 16-byte fragment reads of a wave conflict-free.
 // Operand fragments: lane l holds row (or column) l % 32 and the eight s values 8 * (l / 32) .. + 7 of a
@@ -42,10 +42,13 @@ struct DenseDims {
     int32_t s_chunk;           // s values per grid z (a multiple of 32)
     int32_t atomic;            // 1: gridDim.z > 1, combine with atomic adds into a zeroed output
     int32_t ld_g;              // N: G[m * N + n]
+    int32_t b_chunk;           // sliver pass: s values per grid y (a multiple of 256)
+    int32_t k_shift;           // log2 of the k tile of the dense pass (the sliver pass cuts k into the same blocks)
 };
 
-constexpr int DTR = 128, DTK = 128, DBS = 32, DPITCH = 40;
-static_assert(DTK == 128, "lba_grad_boundary_kernel cuts k into the same 128-blocks (its shift by 7)");
+// DTK (a template argument): 128 or 256 columns k per workgroup; the wider tile splits G half as often and is
+// taken when it still leaves two workgroups per CU
+constexpr int DTR = 128, DBS = 32, DPITCH = 40;
 
 __device__ __forceinline__ float dense_decode_e4m3(uint32_t code) {
     float v = __builtin_amdgcn_cvt_f32_fp8((int)code, 0);
@@ -53,21 +56,38 @@ __device__ __forceinline__ float dense_decode_e4m3(uint32_t code) {
     return v;
 }
 
-// g = hi + mid + lo with 8 significant bits each; returns the three bfloat16 words (top halves)
+// g = hi + mid + lo with 8 significant bits each; returns the three pieces as FP32 words whose low halves are zero
 __device__ __forceinline__ void split3(float g, uint32_t& hi, uint32_t& mid, uint32_t& lo) {
-    const uint32_t h = __float_as_uint(g) & 0xFFFF0000u;
-    const float r1 = g - __uint_as_float(h);                   // exact: the low 16 bits of g's significand
-    const uint32_t m = __float_as_uint(r1) & 0xFFFF0000u;
-    const float r2 = r1 - __uint_as_float(m);                  // exact, at most 8 significant bits
-    hi = h >> 16; mid = m >> 16; lo = __float_as_uint(r2) >> 16;
+    hi = __float_as_uint(g) & 0xFFFF0000u;
+    const float r1 = g - __uint_as_float(hi);                  // exact: the low 16 bits of g's significand
+    mid = __float_as_uint(r1) & 0xFFFF0000u;
+    lo = __float_as_uint(r1 - __uint_as_float(mid));           // exact, at most 8 significant bits: low half zero
+}
+
+// two bfloat16 values (the high halves of two FP32 words) in one register, x in the low half
+__device__ __forceinline__ uint32_t pack_hi(uint32_t x, uint32_t y) { return __builtin_amdgcn_perm(y, x, 0x07060302u); }
+
+// four E4M3 codes of one word -> four FP32 values; the NaN codes are patched to +-480 on a rarely taken path
+__device__ __forceinline__ void decode4(uint32_t w, float (&v)[4]) {
+    typedef float v2f __attribute__((ext_vector_type(2)));
+    const v2f a = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false), b = __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true);
+    v[0] = a[0]; v[1] = a[1]; v[2] = b[0]; v[3] = b[1];
+    if ((((w & 0x7F7F7F7Fu) + 0x01010101u) & 0x80808080u) != 0u) {     // some byte has all of its low seven bits set
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t code = (w >> (8 * c)) & 0xFFu;
+            if ((code & 0x7Fu) == 0x7Fu) v[c] = (code & 0x80u) ? -480.0f : 480.0f;
+        }
+    }
 }
 
 // S_CONTIG: G(r, s) = G[r * ld + s] (dX); else G(r, s) = G[s * ld + r] (dW).  MASKED: L (same layout as G)
 // holds last-overflow indices and g' = [L < k0] g.
-template <bool S_CONTIG, bool MASKED>
+template <bool S_CONTIG, bool MASKED, int DTK>
 __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __restrict__ G, const uint8_t* __restrict__ V,
                                                                 const int32_t* __restrict__ L,
                                                                 float* __restrict__ out, const DenseDims d) {
+    constexpr int DNBJ = DTK / 64;                             // MFMA column blocks per wave (two waves side by side)
     __shared__ __attribute__((aligned(16))) uint16_t sA[3][DTR * DPITCH];
     __shared__ __attribute__((aligned(16))) uint16_t sB[DTK * DPITCH];
 
@@ -83,7 +103,7 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
     const int b_ps = tid >> 5, b_pk = tid & 31;                // 4 rows s, 4 codes k
 
     float4 gl[4];
-    uint32_t vl[4];
+    uint32_t vl[DTK / 128][4];
     auto fetch = [&](int sb) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -115,16 +135,19 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
                 }
             }
             gl[q] = g;
-            const int sv = sb + 4 * b_ps + q, kv = k0 + 4 * b_pk;
-            vl[q] = (sv < s_end && kv < d.K) ? *reinterpret_cast<const uint32_t*>(V + (int64_t)sv * d.K + kv) : 0u;
+#pragma unroll
+            for (int h = 0; h < DTK / 128; ++h) {
+                const int sv = sb + 4 * b_ps + q, kv = k0 + 128 * h + 4 * b_pk;
+                vl[h][q] = (sv < s_end && kv < d.K) ? *reinterpret_cast<const uint32_t*>(V + (int64_t)sv * d.K + kv) : 0u;
+            }
         }
     };
 
-    f32x16 acc[2][2];
+    f32x16 acc[2][DNBJ];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < DNBJ; ++j)
 #pragma unroll
             for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.0f;
 
@@ -147,16 +170,20 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
 #pragma unroll
                 for (int b = 0; b < 4; ++b) split3(g[a][b], h[b], m[b], l[b]);
                 const int off = (4 * a_pr + a) * DPITCH + 4 * a_ps;
-                *reinterpret_cast<uint2*>(&sA[0][off]) = make_uint2(h[0] | (h[1] << 16), h[2] | (h[3] << 16));
-                *reinterpret_cast<uint2*>(&sA[1][off]) = make_uint2(m[0] | (m[1] << 16), m[2] | (m[3] << 16));
-                *reinterpret_cast<uint2*>(&sA[2][off]) = make_uint2(l[0] | (l[1] << 16), l[2] | (l[3] << 16));
+                *reinterpret_cast<uint2*>(&sA[0][off]) = make_uint2(pack_hi(h[0], h[1]), pack_hi(h[2], h[3]));
+                *reinterpret_cast<uint2*>(&sA[1][off]) = make_uint2(pack_hi(m[0], m[1]), pack_hi(m[2], m[3]));
+                *reinterpret_cast<uint2*>(&sA[2][off]) = make_uint2(pack_hi(l[0], l[1]), pack_hi(l[2], l[3]));
             }
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {                      // code c of each of the four rows s
-                uint32_t w[4];
+            for (int h = 0; h < DTK / 128; ++h) {
+                float vv[4][4];                                // [row s b][code c]
 #pragma unroll
-                for (int b = 0; b < 4; ++b) w[b] = __float_as_uint(dense_decode_e4m3((vl[b] >> (8 * c)) & 0xFFu)) >> 16;
-                *reinterpret_cast<uint2*>(&sB[(4 * b_pk + c) * DPITCH + 4 * b_ps]) = make_uint2(w[0] | (w[1] << 16), w[2] | (w[3] << 16));
+                for (int b = 0; b < 4; ++b) decode4(vl[h][b], vv[b]);
+#pragma unroll
+                for (int c = 0; c < 4; ++c)                    // code c of each of the four rows s: an E4M3 value is a bfloat16 number
+                    *reinterpret_cast<uint2*>(&sB[(128 * h + 4 * b_pk + c) * DPITCH + 4 * b_ps]) =
+                        make_uint2(pack_hi(__float_as_uint(vv[0][c]), __float_as_uint(vv[1][c])),
+                                   pack_hi(__float_as_uint(vv[2][c]), __float_as_uint(vv[3][c])));
             }
         }
         __syncthreads();
@@ -164,17 +191,17 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
             const int so = kk * 16 + 8 * (lane >> 5);
-            bf16x8 bf[2];
+            bf16x8 bf[DNBJ];
 #pragma unroll
-            for (int bj = 0; bj < 2; ++bj)
-                bf[bj] = *reinterpret_cast<const bf16x8*>(&sB[(wx * 64 + bj * 32 + (lane & 31)) * DPITCH + so]);
+            for (int bj = 0; bj < DNBJ; ++bj)
+                bf[bj] = *reinterpret_cast<const bf16x8*>(&sB[(wx * (DTK / 2) + bj * 32 + (lane & 31)) * DPITCH + so]);
 #pragma unroll
             for (int sp = 0; sp < 3; ++sp)
 #pragma unroll
                 for (int bi = 0; bi < 2; ++bi) {
                     const bf16x8 af = *reinterpret_cast<const bf16x8*>(&sA[sp][(wy * 64 + bi * 32 + (lane & 31)) * DPITCH + so]);
 #pragma unroll
-                    for (int bj = 0; bj < 2; ++bj)
+                    for (int bj = 0; bj < DNBJ; ++bj)
                         acc[bi][bj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf[bj], acc[bi][bj], 0, 0, 0);
                 }
         }
@@ -184,8 +211,8 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
 #pragma unroll
     for (int bi = 0; bi < 2; ++bi)
 #pragma unroll
-        for (int bj = 0; bj < 2; ++bj) {
-            const int col = k0 + wx * 64 + bj * 32 + (lane & 31);
+        for (int bj = 0; bj < DNBJ; ++bj) {
+            const int col = k0 + wx * (DTK / 2) + bj * 32 + (lane & 31);
 #pragma unroll
             for (int t = 0; t < 16; ++t) {
                 const int row = r0 + wy * 64 + bi * 32 + 8 * (t >> 2) + 4 * (lane >> 5) + (t & 3);
@@ -199,7 +226,7 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
 }
 
 // The sliver of the recursive estimator that the masked dense product leaves out: for every pair (r, s) with
-// L = L(r, s) >= 0 the terms g(r, s) * value(V[s, k]) for L < k < end of L's 128-block.  One workgroup per row r
+// L = L(r, s) >= 0 the terms g(r, s) * value(V[s, k]) for L < k < end of L's k block.  One workgroup per row r
 // keeps the K sums of that row in LDS; a wave takes 64 consecutive s at a time (their L and g in its lanes),
 // then one pair after the other with its lanes along k.  out[r, :] += sums (the dense part is already there).
 template <bool S_CONTIG>
@@ -211,11 +238,13 @@ __global__ void __launch_bounds__(256) lba_grad_boundary_kernel(const float* __r
     const int r = blockIdx.x;
     for (int k = tid; k < d.K; k += 256) row[k] = 0.0f;
     __syncthreads();
-    for (int s0 = wave * 64; s0 < d.S; s0 += 256) {
+    // grid y cuts s into slices of b_chunk (a multiple of 256) when there are few rows
+    const int s_lo = blockIdx.y * d.b_chunk, s_hi = min(d.S, s_lo + d.b_chunk);
+    for (int s0 = s_lo + wave * 64; s0 < s_hi; s0 += 256) {
         const int s = s0 + lane;
         int32_t lv = -1;
         float gv = 0.0f;
-        if (s < d.S) {
+        if (s < s_hi) {
             const int64_t off = S_CONTIG ? (int64_t)r * d.ld_g + s : (int64_t)s * d.ld_g + r;
             lv = L[off];
             gv = G[off];
@@ -226,7 +255,7 @@ __global__ void __launch_bounds__(256) lba_grad_boundary_kernel(const float* __r
             todo &= todo - 1;
             const int32_t lj = __builtin_amdgcn_readlane(lv, j);
             const float gj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(gv), j));
-            const int k_end = min(d.K, ((lj >> 7) + 1) << 7);
+            const int k_end = min(d.K, ((lj >> d.k_shift) + 1) << d.k_shift);
             const uint8_t* __restrict__ vrow = V + (int64_t)(s0 + j) * d.K;
             for (int k = lj + 1 + lane; k < k_end; k += 64)
                 atomicAdd(&row[k], gj * dense_decode_e4m3(vrow[k]));
@@ -235,7 +264,10 @@ __global__ void __launch_bounds__(256) lba_grad_boundary_kernel(const float* __r
     __syncthreads();
     for (int k = tid; k < d.K; k += 256) {
         const float x = row[k];
-        if (x != 0.0f) out[(int64_t)r * d.K + k] += x;
+        if (x != 0.0f) {
+            if (gridDim.y > 1) unsafeAtomicAdd(out + (int64_t)r * d.K + k, x);
+            else               out[(int64_t)r * d.K + k] += x;
+        }
     }
 }
 
@@ -247,7 +279,7 @@ __global__ void lba_grad_dense_zero_kernel(float* x, int64_t n) {
 // Can the matrix-core path take this product?  16-byte rows of G (and of last_of) in both directions, 4-byte
 // groups of codes; with last_of also a row of K sums within 48 KB of LDS.
 bool grad_dense_ok(const float* G, const uint8_t* V, const int32_t* last_of, int64_t M, int64_t N, int64_t K) {
-    if (((uintptr_t)G % 16) != 0 || ((uintptr_t)V % 4) != 0 || (N % 4) != 0 || (K % 4) != 0 || (K + DTK - 1) / DTK > 65535)
+    if (((uintptr_t)G % 16) != 0 || ((uintptr_t)V % 4) != 0 || (N % 4) != 0 || (K % 4) != 0 || (K + 127) / 128 > 65535)
         return false;
     if (last_of && (((uintptr_t)last_of % 16) != 0 || K > 12288)) return false;
     return true;
@@ -259,7 +291,12 @@ int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* las
                    int64_t M, int64_t N, int64_t K, hipStream_t st) {
     DenseDims d;
     d.R = (int32_t)(dx ? M : N); d.S = (int32_t)(dx ? N : M); d.K = (int32_t)K; d.ld_g = (int32_t)N;
-    const int64_t gx = (d.R + DTR - 1) / DTR, gy = (K + DTK - 1) / DTK;
+    d.b_chunk = d.S;
+    const int64_t gx = (d.R + DTR - 1) / DTR;
+    const bool wide = gx * ((K + 255) / 256) >= 512;           // 128 x 256 tiles still give two workgroups per CU
+    const int dtk = wide ? 256 : 128;
+    d.k_shift = wide ? 8 : 7;
+    const int64_t gy = (K + dtk - 1) / dtk;
     // enough workgroups for two per CU: cut s into slices of a multiple of 32
     int64_t split = 1;
     const int64_t steps = (d.S + DBS - 1) / DBS;
@@ -274,15 +311,23 @@ int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* las
         if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
     }
     const dim3 grid((unsigned)gx, (unsigned)gy, (unsigned)split);
+#define LBA_DENSE(SC, MK) do { if (wide) hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 256>), grid, dim3(256), 0, st, G, V, last_of, out, d); \
+                               else      hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 128>), grid, dim3(256), 0, st, G, V, last_of, out, d); } while (0)
     if (!last_of) {
-        if (dx) hipLaunchKernelGGL((lba_grad_dense_kernel<true, false>), grid, dim3(256), 0, st, G, V, last_of, out, d);
-        else    hipLaunchKernelGGL((lba_grad_dense_kernel<false, false>), grid, dim3(256), 0, st, G, V, last_of, out, d);
+        if (dx) LBA_DENSE(true, false); else LBA_DENSE(false, false);
         return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
     }
-    if (dx) hipLaunchKernelGGL((lba_grad_dense_kernel<true, true>), grid, dim3(256), 0, st, G, V, last_of, out, d);
-    else    hipLaunchKernelGGL((lba_grad_dense_kernel<false, true>), grid, dim3(256), 0, st, G, V, last_of, out, d);
+    if (dx) LBA_DENSE(true, true); else LBA_DENSE(false, true);
+#undef LBA_DENSE
     if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
-    const dim3 rows((unsigned)d.R);
+    // the sliver pass: one workgroup per row, and with few rows also slices of s, to have about 1024 workgroups
+    int64_t slices = d.R >= 1024 ? 1 : (1024 + d.R - 1) / d.R;
+    const int64_t groups = (d.S + 255) / 256;
+    if (slices > groups) slices = groups;
+    if (slices > 65535) slices = 65535;
+    d.b_chunk = (int32_t)(((groups + slices - 1) / slices) * 256);
+    slices = (d.S + d.b_chunk - 1) / d.b_chunk;
+    const dim3 rows((unsigned)d.R, (unsigned)slices);
     const size_t lds = (size_t)K * sizeof(float);
     if (dx) hipLaunchKernelGGL((lba_grad_boundary_kernel<true>), rows, dim3(256), lds, st, G, V, last_of, out, d);
     else    hipLaunchKernelGGL((lba_grad_boundary_kernel<false>), rows, dim3(256), lds, st, G, V, last_of, out, d);

@@ -123,8 +123,9 @@ def test_matrix_core_path_identity_and_recursive(ref, gref):
     # none), so that the masked dense part and the sliver pass must meet exactly.  Bit-exact on data whose
     # sums are exactly representable, then the FP32 bound on general data.
     rng = np.random.default_rng(314)
+    # (7300, 4, 2052): enough row tiles for the 128 x 256 variant of the dense kernel (256-wide k blocks)
     for (M, N, K) in [(130, 68, 260), (260, 132, 132), (64, 516, 640), (3000, 24, 40), (40, 2100, 72), (128, 128, 128),
-                      (257, 36, 1028)]:
+                      (257, 36, 1028), (7300, 4, 2052)]:
         A = codes(rng, (M, K), 5, 10); B = codes(rng, (N, K), 5, 10)
         tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
         last = rng.integers(-1, K, (M, N)).astype(np.int32)
