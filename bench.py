@@ -25,6 +25,9 @@ if ROOT not in sys.path:
 # 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz = 78.6e12 full-rate VALU lane-ops per second: the
 # rate behind the published 157.3 TFLOP/s FP32 vector peak (an FMA counts two flops).
 PEAK_LANE_OPS = 256 * 4 * 32 * 2.4e9
+# what the issue-rate probe sustains with the inner loop's own mix (mul | fma | and, phased, 4 waves per SIMD):
+# 114.5 of the 128 lane-ops per clock per CU (profiles/valu_issue_rates_gfx950.md)
+MEASURED_LANE_OPS = 256 * 114.5 * 2.4e9
 # HBM bytes per launch of the dominant kernel of the default workload (the 42 launches of the mixed-grid
 # kernel), from the calibrated rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
 # profiles/lba_fast_kernel_resnet50_sweep.md: FETCH_SIZE 875129.9 KiB x 2.000 + WRITE_SIZE 1173244.3 KiB.
@@ -269,6 +272,7 @@ def main():
     roofline = {
         "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
         "frac": achieved / PEAK_LANE_OPS,
+        "peak_measured": MEASURED_LANE_OPS / 1e12, "frac_of_measured": achieved / MEASURED_LANE_OPS,
         "traffic": RESNET50_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "resnet50" and rnd == 0 and order == 0 and not args.bwd and not args.grad) else None,
         "kernel": ("lba_grad_kernel<%s>" % args.grad) if args.grad else "lba_%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (
             ("fast_diff" if args.diff is not None else "fast_bwd" if args.bwd else ("fast_mixed" if dom_key[6] else "fast")) if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
@@ -285,7 +289,8 @@ def main():
         issued = dom["macs"] * 6 / (dom["ms"] * 1e-3)
         roofline.update({"bound": "mfma", "achieved": issued / 1e12, "peak": 2500.0, "unit": "TFLOP/s", "frac": issued / 2.5e15,
                          "kernel": "lba_grad_dense_kernel<%s> (v_mfma_f32_32x32x16_bf16, 3 passes)" % args.grad,
-                         "algorithmic_tflops": dom["macs"] * 2 / (dom["ms"] * 1e-3) / 1e12, "valu_slots_per_mac": None})
+                         "algorithmic_tflops": dom["macs"] * 2 / (dom["ms"] * 1e-3) / 1e12, "valu_slots_per_mac": None,
+                         "peak_measured": None, "frac_of_measured": None})
 
     if args.per_layer:
         for i, l in enumerate(layers):

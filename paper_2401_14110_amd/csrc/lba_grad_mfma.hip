@@ -108,7 +108,8 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             float4 g = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-            if (S_CONTIG) {                                    // q: row within the patch; the float4 runs along s
+            if (S_CONTIG) {                                    // q: row within the patch; the float4 runs along s (S % 4 == 0 and
+                                                               // s_chunk % 32 == 0: it is inside the range or outside, never across)
                 const int r = r0 + 4 * a_pr + q, s = sb + 4 * a_ps;
                 if (r < d.R && s < s_end) {
                     g = *reinterpret_cast<const float4*>(G + (int64_t)r * d.ld_g + s);
@@ -117,11 +118,6 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
                         g.x = t.x < k0 ? g.x : 0.0f; g.y = t.y < k0 ? g.y : 0.0f;
                         g.z = t.z < k0 ? g.z : 0.0f; g.w = t.w < k0 ? g.w : 0.0f;
                     }
-                }
-                if (s + 3 >= s_end) {                          // a chunk may end inside the float4 (s_chunk % 4 == 0: never; kept for S % 4)
-                    if (s + 1 >= s_end) g.y = 0.0f;
-                    if (s + 2 >= s_end) g.z = 0.0f;
-                    if (s + 3 >= s_end) g.w = 0.0f;
                 }
             } else {                                           // q: s within the patch; the float4 runs along r
                 const int r = r0 + 4 * a_pr, s = sb + 4 * a_ps + q;
