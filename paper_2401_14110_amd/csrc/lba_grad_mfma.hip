@@ -222,45 +222,59 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
 }
 
 // The sliver of the recursive estimator that the masked dense product leaves out: for every pair (r, s) with
-// L = L(r, s) >= 0 the terms g(r, s) * value(V[s, k]) for L < k < end of L's k block.  One workgroup per row r
-// keeps the K sums of that row in LDS; a wave takes 64 consecutive s at a time (their L and g in its lanes),
-// then one pair after the other with its lanes along k.  out[r, :] += sums (the dense part is already there).
-template <bool S_CONTIG>
+// L = L(r, s) >= 0 the terms g(r, s) * value(V[s, k]) for L < k < end of L's k block.  One workgroup per ROWS rows r
+// keeps their K sums each in LDS; a wave takes 64 consecutive s at a time (their L and g in its lanes), then
+// one pair after the other with its lanes along k.  out[r, :] += sums (the dense part is already there).
+// ROWS = 2 (rows contiguous in memory, dW): a lane fetches the two rows' values with one 8-byte load, which
+// halves the sectors touched by the strided walk over s.
+template <bool S_CONTIG, int ROWS>
 __global__ void __launch_bounds__(256) lba_grad_boundary_kernel(const float* __restrict__ G, const uint8_t* __restrict__ V,
                                                                 const int32_t* __restrict__ L,
                                                                 float* __restrict__ out, const DenseDims d) {
-    extern __shared__ float row[];                             // K sums
+    static_assert(ROWS == 1 || (ROWS == 2 && !S_CONTIG), "two rows only where rows are contiguous");
+    extern __shared__ float row[];                             // ROWS x K sums
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int r = blockIdx.x;
-    for (int k = tid; k < d.K; k += 256) row[k] = 0.0f;
+    const int r = blockIdx.x * ROWS;
+    for (int k = tid; k < ROWS * d.K; k += 256) row[k] = 0.0f;
     __syncthreads();
     // grid y cuts s into slices of b_chunk (a multiple of 256) when there are few rows
     const int s_lo = blockIdx.y * d.b_chunk, s_hi = min(d.S, s_lo + d.b_chunk);
     for (int s0 = s_lo + wave * 64; s0 < s_hi; s0 += 256) {
         const int s = s0 + lane;
-        int32_t lv = -1;
-        float gv = 0.0f;
+        int32_t lv[ROWS];
+        float gv[ROWS];
+#pragma unroll
+        for (int i = 0; i < ROWS; ++i) { lv[i] = -1; gv[i] = 0.0f; }
         if (s < s_hi) {
             const int64_t off = S_CONTIG ? (int64_t)r * d.ld_g + s : (int64_t)s * d.ld_g + r;
-            lv = L[off];
-            gv = G[off];
+            if (ROWS == 2) {                                   // r even and ld_g % 4 == 0: 8-byte aligned; R % 4 == 0: both rows exist
+                const int2 l2 = *reinterpret_cast<const int2*>(L + off);
+                const float2 g2 = *reinterpret_cast<const float2*>(G + off);
+                lv[0] = l2.x; lv[ROWS - 1] = l2.y; gv[0] = g2.x; gv[ROWS - 1] = g2.y;
+            } else {
+                lv[0] = L[off];
+                gv[0] = G[off];
+            }
         }
-        uint64_t todo = __builtin_amdgcn_ballot_w64(lv >= 0 && gv != 0.0f);
-        while (todo) {                                         // wave-uniform loop over the pairs that have a sliver
-            const int j = __builtin_ctzll(todo);
-            todo &= todo - 1;
-            const int32_t lj = __builtin_amdgcn_readlane(lv, j);
-            const float gj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(gv), j));
-            const int k_end = min(d.K, ((lj >> d.k_shift) + 1) << d.k_shift);
-            const uint8_t* __restrict__ vrow = V + (int64_t)(s0 + j) * d.K;
-            for (int k = lj + 1 + lane; k < k_end; k += 64)
-                atomicAdd(&row[k], gj * dense_decode_e4m3(vrow[k]));
+#pragma unroll
+        for (int i = 0; i < ROWS; ++i) {
+            uint64_t todo = __builtin_amdgcn_ballot_w64(lv[i] >= 0 && gv[i] != 0.0f);
+            while (todo) {                                     // wave-uniform loop over the pairs that have a sliver
+                const int j = __builtin_ctzll(todo);
+                todo &= todo - 1;
+                const int32_t lj = __builtin_amdgcn_readlane(lv[i], j);
+                const float gj = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(gv[i]), j));
+                const int k_end = min(d.K, ((lj >> d.k_shift) + 1) << d.k_shift);
+                const uint8_t* __restrict__ vrow = V + (int64_t)(s0 + j) * d.K;
+                for (int k = lj + 1 + lane; k < k_end; k += 64)
+                    atomicAdd(&row[i * d.K + k], gj * dense_decode_e4m3(vrow[k]));
+            }
         }
     }
     __syncthreads();
-    for (int k = tid; k < d.K; k += 256) {
+    for (int k = tid; k < ROWS * d.K; k += 256) {
         const float x = row[k];
-        if (x != 0.0f) {
+        if (x != 0.0f) {                                       // row[i * K + k'] belongs to out[(r + i) * K + k']: the same offset from out + r * K
             if (gridDim.y > 1) unsafeAtomicAdd(out + (int64_t)r * d.K + k, x);
             else               out[(int64_t)r * d.K + k] += x;
         }
@@ -317,16 +331,20 @@ int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* las
 #undef LBA_DENSE
     if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
     // the sliver pass: one workgroup per row, and with few rows also slices of s, to have about 1024 workgroups
-    int64_t slices = d.R >= 1024 ? 1 : (1024 + d.R - 1) / d.R;
+    int64_t slices = d.R >= 2048 ? 1 : (2048 + d.R - 1) / d.R;
     const int64_t groups = (d.S + 255) / 256;
     if (slices > groups) slices = groups;
     if (slices > 65535) slices = 65535;
     d.b_chunk = (int32_t)(((groups + slices - 1) / slices) * 256);
     slices = (d.S + d.b_chunk - 1) / d.b_chunk;
-    const dim3 rows((unsigned)d.R, (unsigned)slices);
     const size_t lds = (size_t)K * sizeof(float);
-    if (dx) hipLaunchKernelGGL((lba_grad_boundary_kernel<true>), rows, dim3(256), lds, st, G, V, last_of, out, d);
-    else    hipLaunchKernelGGL((lba_grad_boundary_kernel<false>), rows, dim3(256), lds, st, G, V, last_of, out, d);
+    if (dx) {
+        hipLaunchKernelGGL((lba_grad_boundary_kernel<true, 1>), dim3((unsigned)d.R, (unsigned)slices), dim3(256), lds, st, G, V, last_of, out, d);
+    } else if (2 * lds <= 49152) {                             // dW: R = N is a multiple of 4, rows come in pairs
+        hipLaunchKernelGGL((lba_grad_boundary_kernel<false, 2>), dim3((unsigned)(d.R / 2), (unsigned)slices), dim3(256), 2 * lds, st, G, V, last_of, out, d);
+    } else {
+        hipLaunchKernelGGL((lba_grad_boundary_kernel<false, 1>), dim3((unsigned)d.R, (unsigned)slices), dim3(256), lds, st, G, V, last_of, out, d);
+    }
     return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
 }
 
