@@ -52,3 +52,28 @@ def test_layer_lists():
         assert (M, N, K) == (n * oh * ow, cout, kh * kw * c)
     w = inputs.make_workload("config1")
     assert w[0]["A"].shape == (64, 256) and w[0]["ta"] == 0 and int(w[0]["A"].max()) >= 0x7E - 0x08
+
+
+def test_checksum_function_and_golden_file():
+    """tests/digest.py (the checksum the full-size GPU checks use) on the CPU: position-sensitive, independent of
+    the chunking; the golden file holds one row per GEMM of the benchmark configurations."""
+    import os
+    import torch
+    from digest import digest
+    g = torch.Generator().manual_seed(5)
+    x = torch.randint(0, 256, (70001,), dtype=torch.uint8, generator=g)
+    f = torch.randn((333, 77), generator=g)
+    assert digest(x) == digest(x.clone()) and digest(f, chunk=1000) == digest(f) and digest(x, chunk=4097) == digest(x)
+    y = x.clone(); y[11] ^= 1
+    assert digest(y) != digest(x)
+    z = f.clone().view(-1); z[[3, 4]] = z[[4, 3]]
+    assert digest(z) != digest(f) or z[3] == z[4]
+    assert digest(torch.zeros(5)) != digest(torch.zeros(6))                 # a missing word changes the sum
+    rows = {}
+    path = os.path.join(os.path.dirname(__file__), "golden", "full_digests.txt")
+    for line in open(path):
+        t = line.split()
+        if t and not line.startswith("#"):
+            assert len(t) == 11 and all(len(v) == 16 for v in t[8:])
+            rows[t[0]] = rows.get(t[0], 0) + 1
+    assert rows == {"conv": 2, "bert": 4, "gemm4096": 1, "resnet50": 54}
