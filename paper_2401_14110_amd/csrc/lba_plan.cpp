@@ -155,8 +155,9 @@ static bool rne_odd_ok(const lba_qfmt& qp, const lba_qfmt& qa, bool flush, bool 
 // Lane block (outputs per lane).  4 x 4 (64 x 64 per workgroup) was the fastest on every large GEMM
 // measured (8 x 8, 8 x 4 and 4 x 8 lost to it through lower occupancy and coarser grids).  GEMMs
 // with few outputs cannot keep two waves on every SIMD with 16 chains per lane: between 512 and 1024
-// workgroups 2 x 4 measured 3-6 % faster, and up to 64 workgroups (a latency-bound launch) 2 x 2 is
-// about twice as fast.  The choice never changes a result.
+// workgroups 2 x 4 measured 3-6 % faster; up to 256 workgroups of 64 x 64 a CU would hold one wave per SIMD,
+// which issues at half rate, so those grids take 2 x 4 (129-256) or 2 x 2 (up to 128): 1.6-3 times faster.
+// The choice never changes a result.
 static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int events, int prod_mode, int amode, int rne_odd, int* tm, int* tn, int* bk) {
     *tm = 4; *tn = 4;
     *bk = (kernel == KERNEL_GEN || events) ? 32 : LBA_FAST_BK;
@@ -164,7 +165,10 @@ static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int event
         const int64_t blocks = ((M + 63) / 64) * ((N + 63) / 64) * (batch > 0 ? batch : 1);
         if (events) return;                                    // the recompute kernel is 4 x 4 only
         if (prod_mode == PM_TRUNC || prod_mode == PM_TRUNC_CLAMP || amode || rne_odd) return;   // built for 4 x 4 only
-        if (blocks <= 64) { *tm = 2; *tn = 2; }
+        // a single wave per SIMD issues at half rate (256 workgroups of 64 x 64 take as long as 512): small
+        // grids are cut finer until every CU has two workgroups
+        if (blocks <= 128) { *tm = 2; *tn = 2; }
+        else if (blocks <= 384) *tm = 2;
         else if (blocks > 512 && blocks <= 1024) *tm = 2;
     }
 }
@@ -178,7 +182,7 @@ static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
     if (p->kernel != KERNEL_FAST || p->events || p->amode || p->rne_odd || batch != 1) return;
     if (p->prod_mode != PM_IDENT && p->prod_mode != PM_FLUSH && p->prod_mode != PM_FLUSH_CLAMP) return;
     const int64_t gx = (M + 63) / 64, gy = (N + 63) / 64, blocks = gx * gy;
-    if (blocks <= 256 || blocks > 256 * 16) return;
+    if (blocks <= 384 || blocks > 256 * 16) return;
     const int64_t rounds = blocks / 256;
     const int64_t gx_main = (rounds * 256) / gy;               // whole tile rows inside the full rounds
     if (gx_main < 1 || gx_main >= gx) return;

@@ -562,7 +562,7 @@ def test_mixed_grid(ref):
     # 32 x 32 workgroups: both regions, their seam and the ragged edges against the oracle
     rng = np.random.default_rng(130)
     mixed = 0
-    for (M, N, K) in [(64 * 300 + 17, 60, 100), (64 * 392, 64, 40), (64 * 150 + 33, 130, 64)]:
+    for (M, N, K) in [(64 * 420 + 17, 60, 100), (64 * 392, 64, 40), (64 * 150 + 33, 130, 64)]:
         A = rand_codes(rng, (M, K), 3, 12); B = rand_codes(rng, (N, K), 3, 12)
         for (qp, qa), rnd, order in itertools.product([FMT_PAPER[0], FMT_PAPER[2], FMT_PAPER[4], FMT_SWEEP[4]], (0, 1), (0, 1)):
             qpf, qaf = qp + (rnd,), qa + (rnd,)
@@ -575,5 +575,9 @@ def test_mixed_grid(ref):
     # not used where it cannot help: exact multiples of a round, tiny and huge grids, the recompute call
     assert lb.lba_plan_query(64 * 256, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
     assert lb.lba_plan_query(64 * 40, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
+    # up to 384 workgroups of 64 x 64 a CU would run a single wave per SIMD (half rate): finer plain tiles instead
+    small = lb.lba_plan_query(64 * 300, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))
+    assert small["tail_blocks"] == 0 and (small["thread_m"], small["thread_n"]) == (2, 4)
+    assert lb.lba_plan_query(64 * 100, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["thread_n"] == 2
     assert lb.lba_plan_query(64 * 12544, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
     assert lb.lba_plan_query(64 * 300, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), 0, 1)["tail_blocks"] == 0
