@@ -98,11 +98,16 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
     const int s_end = min(d.S, s_begin + d.s_chunk);
 
     // this lane's 4 x 4 patch of the G tile and of the V tile
-    const int a_pr = S_CONTIG ? (tid >> 3) : (tid & 31);       // patch row (4 rows r)
-    const int a_ps = S_CONTIG ? (tid & 7) : (tid >> 5);        // patch column (4 values of s)
-    const int b_ps = tid >> 5, b_pk = tid & 31;                // 4 rows s, 4 codes k
+    // Consecutive lanes take consecutive s: the eight lanes of a row write 64 contiguous bytes of LDS and the next
+    // eight are 4 rows = 320 bytes = 16 banks further, so every 16 lanes of an 8-byte store cover all banks once
+    // (the other order, consecutive lanes along rows, put 32 lanes on two bank pairs).  In global memory a wave
+    // then reads 128 contiguous bytes of eight rows of G, or 32 bytes of eight rows of codes.
+    const int a_pr = tid >> 3, a_ps = tid & 7;                 // patch row (4 rows r), patch column (4 values of s)
+    const int b_ps = tid & 7, b_pk = tid >> 3;                 // 4 rows s, 4 codes k
 
     float4 gl[4];
+    int4 ll[MASKED ? 4 : 1];                                   // last-overflow indices of the G patch: compared when the
+                                                               // patch is staged, so that the loads stay in flight meanwhile
     uint32_t vl[DTK / 128][4];
     auto fetch = [&](int sb) {
 #pragma unroll
@@ -113,21 +118,13 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
                 const int r = r0 + 4 * a_pr + q, s = sb + 4 * a_ps;
                 if (r < d.R && s < s_end) {
                     g = *reinterpret_cast<const float4*>(G + (int64_t)r * d.ld_g + s);
-                    if (MASKED) {
-                        const int4 t = *reinterpret_cast<const int4*>(L + (int64_t)r * d.ld_g + s);
-                        g.x = t.x < k0 ? g.x : 0.0f; g.y = t.y < k0 ? g.y : 0.0f;
-                        g.z = t.z < k0 ? g.z : 0.0f; g.w = t.w < k0 ? g.w : 0.0f;
-                    }
+                    if (MASKED) ll[q] = *reinterpret_cast<const int4*>(L + (int64_t)r * d.ld_g + s);
                 }
             } else {                                           // q: s within the patch; the float4 runs along r
                 const int r = r0 + 4 * a_pr, s = sb + 4 * a_ps + q;
                 if (r < d.R && s < s_end) {
                     g = *reinterpret_cast<const float4*>(G + (int64_t)s * d.ld_g + r);
-                    if (MASKED) {
-                        const int4 t = *reinterpret_cast<const int4*>(L + (int64_t)s * d.ld_g + r);
-                        g.x = t.x < k0 ? g.x : 0.0f; g.y = t.y < k0 ? g.y : 0.0f;
-                        g.z = t.z < k0 ? g.z : 0.0f; g.w = t.w < k0 ? g.w : 0.0f;
-                    }
+                    if (MASKED) ll[q] = *reinterpret_cast<const int4*>(L + (int64_t)s * d.ld_g + r);
                 }
             }
             gl[q] = g;
@@ -154,7 +151,12 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
             float g[4][4];                                     // [row a][s b]
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const float x[4] = {gl[q].x, gl[q].y, gl[q].z, gl[q].w};
+                float x[4] = {gl[q].x, gl[q].y, gl[q].z, gl[q].w};
+                if (MASKED) {                                  // g' = [L < k0] g (where nothing was fetched g is 0 already)
+                    const int4 t = ll[MASKED ? q : 0];
+                    x[0] = t.x < k0 ? x[0] : 0.0f; x[1] = t.y < k0 ? x[1] : 0.0f;
+                    x[2] = t.z < k0 ? x[2] : 0.0f; x[3] = t.w < k0 ? x[3] : 0.0f;
+                }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     if (S_CONTIG) g[q][e] = x[e]; else g[e][q] = x[e];
