@@ -170,25 +170,26 @@ __device__ __forceinline__ void grad_block(float (&acc)[16], int ib, int r0, int
 template <int L0, int L1, int L2, int L3>
 __device__ __forceinline__ void masked_fmac4_lanes(float& acc, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3,
                                                    const float (&g)[4], const float (&v)[4]) {
+    // the word pair is read into a fixed aligned scalar pair so that one 64-bit move loads the execution mask
     uint64_t save;
-    uint32_t tl, th;
     asm volatile(
         "s_mov_b64 %[sv], exec\n\t"
-        "v_readlane_b32 %[tl], %[w0], %[a0]\n\tv_readlane_b32 %[th], %[w0], %[b0]\n\t"
-        "s_mov_b32 exec_lo, %[tl]\n\ts_mov_b32 exec_hi, %[th]\n\tv_fmac_f32 %[a], %[g0], %[v0]\n\t"
-        "v_readlane_b32 %[tl], %[w1], %[a1]\n\tv_readlane_b32 %[th], %[w1], %[b1]\n\t"
-        "s_mov_b32 exec_lo, %[tl]\n\ts_mov_b32 exec_hi, %[th]\n\tv_fmac_f32 %[a], %[g1], %[v1]\n\t"
-        "v_readlane_b32 %[tl], %[w2], %[a2]\n\tv_readlane_b32 %[th], %[w2], %[b2]\n\t"
-        "s_mov_b32 exec_lo, %[tl]\n\ts_mov_b32 exec_hi, %[th]\n\tv_fmac_f32 %[a], %[g2], %[v2]\n\t"
-        "v_readlane_b32 %[tl], %[w3], %[a3]\n\tv_readlane_b32 %[th], %[w3], %[b3]\n\t"
-        "s_mov_b32 exec_lo, %[tl]\n\ts_mov_b32 exec_hi, %[th]\n\tv_fmac_f32 %[a], %[g3], %[v3]\n\t"
+        "v_readlane_b32 s100, %[w0], %[a0]\n\tv_readlane_b32 s101, %[w0], %[b0]\n\t"
+        "s_mov_b64 exec, s[100:101]\n\tv_fmac_f32 %[a], %[g0], %[v0]\n\t"
+        "v_readlane_b32 s100, %[w1], %[a1]\n\tv_readlane_b32 s101, %[w1], %[b1]\n\t"
+        "s_mov_b64 exec, s[100:101]\n\tv_fmac_f32 %[a], %[g1], %[v1]\n\t"
+        "v_readlane_b32 s100, %[w2], %[a2]\n\tv_readlane_b32 s101, %[w2], %[b2]\n\t"
+        "s_mov_b64 exec, s[100:101]\n\tv_fmac_f32 %[a], %[g2], %[v2]\n\t"
+        "v_readlane_b32 s100, %[w3], %[a3]\n\tv_readlane_b32 s101, %[w3], %[b3]\n\t"
+        "s_mov_b64 exec, s[100:101]\n\tv_fmac_f32 %[a], %[g3], %[v3]\n\t"
         "s_mov_b64 exec, %[sv]"
-        : [a] "+v"(acc), [sv] "=&s"(save), [tl] "=&s"(tl), [th] "=&s"(th)
+        : [a] "+v"(acc), [sv] "=&s"(save)
         : [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3),
           [a0] "n"(L0), [b0] "n"(L0 + 32), [a1] "n"(L1), [b1] "n"(L1 + 32),
           [a2] "n"(L2), [b2] "n"(L2 + 32), [a3] "n"(L3), [b3] "n"(L3 + 32),
           [g0] "s"(g[0]), [g1] "s"(g[1]), [g2] "s"(g[2]), [g3] "s"(g[3]),
-          [v0] "v"(v[0]), [v1] "v"(v[1]), [v2] "v"(v[2]), [v3] "v"(v[3]));
+          [v0] "v"(v[0]), [v1] "v"(v[1]), [v2] "v"(v[2]), [v3] "v"(v[3])
+        : "s100", "s101");
 }
 
 // One accumulator row I (0..15) against the four s of group UB (0..3) of a 16-s super-step.
