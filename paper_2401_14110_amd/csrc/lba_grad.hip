@@ -170,10 +170,10 @@ __device__ __forceinline__ void grad_block(float (&acc)[16], int ib, int r0, int
 template <int L0, int L1, int L2, int L3>
 __device__ __forceinline__ void masked_fmac4_lanes(float& acc, uint32_t w0, uint32_t w1, uint32_t w2, uint32_t w3,
                                                    const float (&g)[4], const float (&v)[4]) {
-    // the word pair is read into a fixed aligned scalar pair so that one 64-bit move loads the execution mask
-    uint64_t save;
+    // the word pair is read into a fixed aligned scalar pair so that one 64-bit move loads the execution mask.
+    // The kernel runs this with every lane active (whole waves only leave early), so the mask is put back to
+    // all ones instead of being saved and restored.
     asm volatile(
-        "s_mov_b64 %[sv], exec\n\t"
         "v_readlane_b32 s100, %[w0], %[a0]\n\tv_readlane_b32 s101, %[w0], %[b0]\n\t"
         "s_mov_b64 exec, s[100:101]\n\tv_fmac_f32 %[a], %[g0], %[v0]\n\t"
         "v_readlane_b32 s100, %[w1], %[a1]\n\tv_readlane_b32 s101, %[w1], %[b1]\n\t"
@@ -182,8 +182,8 @@ __device__ __forceinline__ void masked_fmac4_lanes(float& acc, uint32_t w0, uint
         "s_mov_b64 exec, s[100:101]\n\tv_fmac_f32 %[a], %[g2], %[v2]\n\t"
         "v_readlane_b32 s100, %[w3], %[a3]\n\tv_readlane_b32 s101, %[w3], %[b3]\n\t"
         "s_mov_b64 exec, s[100:101]\n\tv_fmac_f32 %[a], %[g3], %[v3]\n\t"
-        "s_mov_b64 exec, %[sv]"
-        : [a] "+v"(acc), [sv] "=&s"(save)
+        "s_mov_b64 exec, -1"
+        : [a] "+v"(acc)
         : [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3),
           [a0] "n"(L0), [b0] "n"(L0 + 32), [a1] "n"(L1), [b1] "n"(L1 + 32),
           [a2] "n"(L2), [b2] "n"(L2 + 32), [a3] "n"(L3), [b3] "n"(L3 + 32),
@@ -207,15 +207,18 @@ __device__ __forceinline__ void lanes_row(float& acc, const uint32_t (&w)[8], co
     }
 }
 
+// gp[i]: where the 16 contiguous scalars g of line i of the super-step start (a row r0 + i when g is contiguous
+// along s, a column s + i when it is contiguous along r); block (IB, UB) takes four 16-byte scalar loads at
+// constant offsets from four of them (computing each address from r, s and the strides cost four scalar
+// instructions per load).
 template <bool S_CONTIG, int IB, int UB>
-__device__ __forceinline__ void lanes_block(float (&acc)[16], int r0, int s, const float (&v)[16],
-                                            const float* __restrict__ G, const uint32_t (&w)[8], const GradDims& d) {
+__device__ __forceinline__ void lanes_block(float (&acc)[16], const float (&v)[16], const float* const (&gp)[16],
+                                            const uint32_t (&w)[8]) {
     float g[4][4];
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
-        const uint32_t off = S_CONTIG ? (uint32_t)(r0 + 4 * IB + a) * (uint32_t)d.stride_r + (uint32_t)(s + 4 * UB)
-                                      : (uint32_t)(s + 4 * UB + a) * (uint32_t)d.stride_s + (uint32_t)(r0 + 4 * IB);
-        const float4 gv = *reinterpret_cast<const float4*>(G + off);
+        const float4 gv = S_CONTIG ? *reinterpret_cast<const float4*>(gp[4 * IB + a] + 4 * UB)
+                                   : *reinterpret_cast<const float4*>(gp[4 * UB + a] + 4 * IB);
         const float ga[4] = {gv.x, gv.y, gv.z, gv.w};
 #pragma unroll
         for (int b = 0; b < 4; ++b) g[S_CONTIG ? a : b][S_CONTIG ? b : a] = ga[b];
@@ -228,12 +231,12 @@ __device__ __forceinline__ void lanes_block(float (&acc)[16], int r0, int s, con
 }
 
 template <bool S_CONTIG, int IB>
-__device__ __forceinline__ void lanes_rows(float (&acc)[16], int r0, int s, const float (&v)[16],
-                                           const float* __restrict__ G, const uint32_t (&w)[8], const GradDims& d) {
-    lanes_block<S_CONTIG, IB, 0>(acc, r0, s, v, G, w, d);
-    lanes_block<S_CONTIG, IB, 1>(acc, r0, s, v, G, w, d);
-    lanes_block<S_CONTIG, IB, 2>(acc, r0, s, v, G, w, d);
-    lanes_block<S_CONTIG, IB, 3>(acc, r0, s, v, G, w, d);
+__device__ __forceinline__ void lanes_rows(float (&acc)[16], const float (&v)[16], const float* const (&gp)[16],
+                                           const uint32_t (&w)[8]) {
+    lanes_block<S_CONTIG, IB, 0>(acc, v, gp, w);
+    lanes_block<S_CONTIG, IB, 1>(acc, v, gp, w);
+    lanes_block<S_CONTIG, IB, 2>(acc, v, gp, w);
+    lanes_block<S_CONTIG, IB, 3>(acc, v, gp, w);
 }
 
 // 16 rows x 16 s of the immediate estimator.  The 512 plane words of the step (two slabs) are fetched with
@@ -258,10 +261,15 @@ __device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, in
         const uint32_t code = (k < d.K) ? V[(int64_t)(s + u) * d.K + k] : 0u;
         v[u] = decode_e4m3(code);
     }
-    lanes_rows<S_CONTIG, 0>(acc, r0, s, v, G, w, d);
-    lanes_rows<S_CONTIG, 1>(acc, r0, s, v, G, w, d);
-    lanes_rows<S_CONTIG, 2>(acc, r0, s, v, G, w, d);
-    lanes_rows<S_CONTIG, 3>(acc, r0, s, v, G, w, d);
+    const float* gp[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+        gp[i] = S_CONTIG ? G + ((uint32_t)(r0 + i) * (uint32_t)d.stride_r + (uint32_t)s)
+                         : G + ((uint32_t)(s + i) * (uint32_t)d.stride_s + (uint32_t)r0);
+    lanes_rows<S_CONTIG, 0>(acc, v, gp, w);
+    lanes_rows<S_CONTIG, 1>(acc, v, gp, w);
+    lanes_rows<S_CONTIG, 2>(acc, v, gp, w);
+    lanes_rows<S_CONTIG, 3>(acc, v, gp, w);
 }
 
 template <int MODE, bool S_CONTIG>
