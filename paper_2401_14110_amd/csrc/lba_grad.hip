@@ -211,10 +211,9 @@ __device__ __forceinline__ void lanes_row(float& acc, const uint32_t (&w)[8], co
 // along s, a column s + i when it is contiguous along r); block (IB, UB) takes four 16-byte scalar loads at
 // constant offsets from four of them (computing each address from r, s and the strides cost four scalar
 // instructions per load).
+// The 4 x 4 scalars g of block (IB, UB): four 16-byte scalar loads at constant offsets from four of the lines.
 template <bool S_CONTIG, int IB, int UB>
-__device__ __forceinline__ void lanes_block(float (&acc)[16], const float (&v)[16], const float* const (&gp)[16],
-                                            const uint32_t (&w)[8]) {
-    float g[4][4];
+__device__ __forceinline__ void load_g_block(float (&g)[4][4], const float* const (&gp)[16]) {
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
         const float4 gv = S_CONTIG ? *reinterpret_cast<const float4*>(gp[4 * IB + a] + 4 * UB)
@@ -223,20 +222,23 @@ __device__ __forceinline__ void lanes_block(float (&acc)[16], const float (&v)[1
 #pragma unroll
         for (int b = 0; b < 4; ++b) g[S_CONTIG ? a : b][S_CONTIG ? b : a] = ga[b];
     }
+}
+
+// Block B = 4 * IB + UB of the 16 blocks of a super-step.  The scalars of block B + 1 are requested before block
+// B runs on the ones requested one block earlier (the scheduling barriers pin that order: left alone, the loads
+// sit right in front of their first use and every block waits for memory).
+template <bool S_CONTIG, int B>
+__device__ __forceinline__ void lanes_block(float (&acc)[16], const float (&v)[16], const float* const (&gp)[16],
+                                            const uint32_t (&w)[8], const float (&g)[4][4], float (&g_next)[4][4]) {
+    constexpr int IB = B / 4, UB = B % 4, NB = (B + 1) % 16;
+    if (B < 15) load_g_block<S_CONTIG, NB / 4, NB % 4>(g_next, gp);
+    __builtin_amdgcn_sched_barrier(0);
     const float vv[4] = {v[4 * UB + 0], v[4 * UB + 1], v[4 * UB + 2], v[4 * UB + 3]};
     lanes_row<S_CONTIG, 4 * IB + 0, UB>(acc[4 * IB + 0], w, g[0], vv);
     lanes_row<S_CONTIG, 4 * IB + 1, UB>(acc[4 * IB + 1], w, g[1], vv);
     lanes_row<S_CONTIG, 4 * IB + 2, UB>(acc[4 * IB + 2], w, g[2], vv);
     lanes_row<S_CONTIG, 4 * IB + 3, UB>(acc[4 * IB + 3], w, g[3], vv);
-}
-
-template <bool S_CONTIG, int IB>
-__device__ __forceinline__ void lanes_rows(float (&acc)[16], const float (&v)[16], const float* const (&gp)[16],
-                                           const uint32_t (&w)[8]) {
-    lanes_block<S_CONTIG, IB, 0>(acc, v, gp, w);
-    lanes_block<S_CONTIG, IB, 1>(acc, v, gp, w);
-    lanes_block<S_CONTIG, IB, 2>(acc, v, gp, w);
-    lanes_block<S_CONTIG, IB, 3>(acc, v, gp, w);
+    __builtin_amdgcn_sched_barrier(0);
 }
 
 // 16 rows x 16 s of the immediate estimator.  The 512 plane words of the step (two slabs) are fetched with
@@ -266,10 +268,16 @@ __device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, in
     for (int i = 0; i < 16; ++i)
         gp[i] = S_CONTIG ? G + ((uint32_t)(r0 + i) * (uint32_t)d.stride_r + (uint32_t)s)
                          : G + ((uint32_t)(s + i) * (uint32_t)d.stride_s + (uint32_t)r0);
-    lanes_rows<S_CONTIG, 0>(acc, v, gp, w);
-    lanes_rows<S_CONTIG, 1>(acc, v, gp, w);
-    lanes_rows<S_CONTIG, 2>(acc, v, gp, w);
-    lanes_rows<S_CONTIG, 3>(acc, v, gp, w);
+    float ga[4][4], gb[4][4];
+    load_g_block<S_CONTIG, 0, 0>(ga, gp);
+    lanes_block<S_CONTIG, 0>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 1>(acc, v, gp, w, gb, ga);
+    lanes_block<S_CONTIG, 2>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 3>(acc, v, gp, w, gb, ga);
+    lanes_block<S_CONTIG, 4>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 5>(acc, v, gp, w, gb, ga);
+    lanes_block<S_CONTIG, 6>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 7>(acc, v, gp, w, gb, ga);
+    lanes_block<S_CONTIG, 8>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 9>(acc, v, gp, w, gb, ga);
+    lanes_block<S_CONTIG, 10>(acc, v, gp, w, ga, gb);  lanes_block<S_CONTIG, 11>(acc, v, gp, w, gb, ga);
+    lanes_block<S_CONTIG, 12>(acc, v, gp, w, ga, gb);  lanes_block<S_CONTIG, 13>(acc, v, gp, w, gb, ga);
+    lanes_block<S_CONTIG, 14>(acc, v, gp, w, ga, gb);  lanes_block<S_CONTIG, 15>(acc, v, gp, w, gb, ga);
 }
 
 template <int MODE, bool S_CONTIG>
