@@ -133,3 +133,29 @@ def test_relations_between_the_estimators(ref, gref):
     G1 = rng.standard_normal((12, 10)); G2 = rng.standard_normal((12, 10))
     d1 = gref.grad(G1, A, B, qp, qa, 2); d2 = gref.grad(G2, A, B, qp, qa, 2); d3 = gref.grad(G1 + 2 * G2, A, B, qp, qa, 2)
     assert np.allclose(d3[0], d1[0] + 2 * d2[0], rtol=1e-12, atol=1e-9) and np.allclose(d3[1], d1[1] + 2 * d2[1], rtol=1e-12, atol=1e-9)
+
+
+def test_immediate_diff_coefficients_against_fraction_model(ref, gref):
+    """'Immediate / DIFF' (Sec. 4): the coefficients are STE^DIFF itself, step by step, from the ratio written
+    with Fractions; they block at least every overflow that moved the sum by less than eps2 |x w|, every fully
+    swamped step and every product underflow, and the gradient is the plain sum over the kept terms."""
+    rng = np.random.default_rng(12)
+    for (fp, fa), rnd, K, lo, hi, eps2 in [(((5, 7, 15), (4, 7, 7)), 0, 37, 3, 12, 0.25), (((4, 7, 9), (4, 3, 7)), 1, 40, 2, 12, 0.5),
+                                           (((3, 4, 6), (3, 4, 6)), 0, 20, 4, 10, 0.0)]:
+        A = _codes(rng, (3, K), lo, hi); B = _codes(rng, (2, K), lo, hi)
+        qp, qa = ref.QFmt(*fp, rnd), ref.QFmt(*fa, rnd)
+        c = gref.coefficients(A, B, qp, qa, gref.STE_IMMEDIATE_DIFF, eps2=eps2)
+        for m in range(3):
+            for n in range(2):
+                _, ste = FM.chain_diff([int(x) for x in A[m]], [int(x) for x in B[n]], fp + (rnd,), fa + (rnd,), Fraction(eps2))
+                assert [int(v) for v in c[m, n]] == ste, (fp, fa, m, n)
+        assert 0 < c.sum() < c.size
+        G = rng.integers(-8, 9, (3, 2)) / 4.0
+        dX, dW = gref.grad(G, A, B, qp, qa, gref.STE_IMMEDIATE_DIFF, c=c)
+        tab = gref.decode_table()
+        for m in range(3):
+            for k in range(K):
+                assert dX[m, k] == sum(G[m, n] * tab[B[n, k]] * c[m, n, k] for n in range(2))
+        for n in range(2):
+            for k in range(K):
+                assert dW[n, k] == sum(G[m, n] * tab[A[m, k]] * c[m, n, k] for m in range(3))
