@@ -42,6 +42,7 @@ __device__ __forceinline__ void set_round_zero()    { asm volatile("s_setreg_imm
 // volatile assembly themselves (volatile statements keep their order; loads may still move across)
 __device__ __forceinline__ void set_round_pinf_nm() { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 1\n\ts_nop 1"); }
 __device__ __forceinline__ void set_round_ninf_nm() { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 2\n\ts_nop 1"); }
+__device__ __forceinline__ void set_round_zero_nm() { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 3\n\ts_nop 1"); }
 __device__ __forceinline__ void set_flush_f32()     { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 4, 2), 0\n\ts_nop 1" ::: "memory"); }
 
 // FP16 denormals on (MODE[7:6] = 3): the staging decodes 8-bit codes through an exact FP16 image
@@ -1004,12 +1005,15 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
 }
 
 // Recompute call for the DIFF plane (Sec. 4 "Immediate / DIFF", App. D, eps1 -> 0+) in the scaled domain:
-// floor rounding, E4M3 operands, Q_prod without mantissa rounding, and an accumulator format narrow enough
-// (2^E + M + 1 <= 24, flush kept) that the difference of two of its sums is exact in FP32.  Per step:
+// floor rounding, E4M3 operands, Q_prod without mantissa rounding, flush kept.  Per step:
 //   DIFF = [ |S' - S| <= eps2 * |x w| ],  both sides formed 2^60 above the accumulator's domain, where
-// neither can be flushed: S' - S is a multiple of the grid's unit below 2^24 units (exact), and
-// eps2 * |x w| has at most 12 + 8 significant bits (exact).  A product that Q_prod flushes leaves S' = S,
-// so the flushed multiply (zero) gives the right bit too.  Writes the plane through p.of_mask.
+// neither can be flushed; eps2 * |x w| has at most 12 + 8 significant bits (exact).  A product that Q_prod
+// flushes leaves S' = S, so the flushed multiply (zero) gives the right bit too.
+// The magnitude max(S', S) - min(S', S) is subtracted in the toward +inf mode: the right-hand side is a
+// representable number, so the rounded-up difference exceeds it exactly when the exact one does, whatever
+// the accumulator's width.  The mode-dependent operations of a step (product, sum, subtraction) are
+// volatile assembly, which keeps them on their side of the two mode writes; everything else is exact.
+// Writes the plane through p.of_mask.
 template <int PM, int ORDER>
 __global__ void __launch_bounds__(256, 3) lba_fast_diff_kernel(const KParams p) {
     constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
@@ -1060,29 +1064,47 @@ __global__ void __launch_bounds__(256, 3) lba_fast_diff_kernel(const KParams p) 
         for (int k = 0; k < BK; ++k) {
             float a[TM], b[TN];
             read_operands<TM, TN, BM, BN>(As, Bs, k, tx, ty, a, b);
+            {
+                float hi[TM][TN], lo[TM][TN], rhs[TM][TN];
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+                for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const float q0 = a[i] * b[j];                           // exact, or flushed below Q_prod's R_UF
-                    const float q = (PM == PM_FLUSH_CLAMP) ? med3(q0, -rofp, rofp) : q0;
-                    float tsum = __builtin_fmaf(q, kc, acc[i][j]);
-                    tsum = __uint_as_float(__float_as_uint(tsum) & mask);
-                    tsum = med3(tsum, -rof, rof);
-                    const float su = tsum * up;
-                    const float d = su - accu[i][j];
-                    const float rhs = __builtin_fabsf(q0) * ce;
-                    const uint64_t blocked = __builtin_amdgcn_ballot_w64(!(__builtin_fabsf(d) > rhs));
-                    acc[i][j] = tsum;
-                    accu[i][j] = su;
-                    asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wdf[i][j]) : "s"(blocked) : "vcc");
-                }
+                    for (int j = 0; j < TN; ++j) {                          // toward zero
+                        float q0, tsum;
+                        asm volatile("v_mul_f32 %0, %1, %2" : "=v"(q0) : "v"(a[i]), "v"(b[j]));
+                        const float q = (PM == PM_FLUSH_CLAMP) ? med3(q0, -rofp, rofp) : q0;
+                        asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(tsum) : "v"(q), "v"(kc), "v"(acc[i][j]));
+                        tsum = __uint_as_float(__float_as_uint(tsum) & mask);
+                        tsum = med3(tsum, -rof, rof);
+                        const float su = tsum * up;                         // exact
+                        hi[i][j] = __builtin_fmaxf(su, accu[i][j]);
+                        lo[i][j] = __builtin_fminf(su, accu[i][j]);
+                        rhs[i][j] = __builtin_fabsf(q0) * ce;               // exact
+                        acc[i][j] = tsum;
+                        accu[i][j] = su;
+                    }
+                set_round_pinf_nm();
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        asm volatile("v_sub_f32 %0, %1, %2" : "=v"(hi[i][j]) : "v"(hi[i][j]), "v"(lo[i][j]));
+                set_round_zero_nm();
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        const uint64_t blocked = __builtin_amdgcn_ballot_w64(!(hi[i][j] > rhs[i][j]));
+                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wdf[i][j]) : "s"(blocked) : "vcc");
+                    }
+            }
             if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j) {
-                        float u = top[i][j] + acc[i][j];
+                        float u;
+                        asm volatile("v_add_f32 %0, %1, %2" : "=v"(u) : "v"(top[i][j]), "v"(acc[i][j]));   // stays in the toward-zero part
                         u = __uint_as_float(__float_as_uint(u) & mask);
                         top[i][j] = med3(u, -rof, rof);
                         acc[i][j] = 0.0f;

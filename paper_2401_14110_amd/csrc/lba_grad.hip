@@ -174,14 +174,14 @@ __device__ __forceinline__ void masked_fmac4_lanes(float& acc, uint32_t w0, uint
     // The kernel runs this with every lane active (whole waves only leave early), so the mask is put back to
     // all ones instead of being saved and restored.
     asm volatile(
-        "v_readlane_b32 s100, %[w0], %[a0]\n\tv_readlane_b32 s101, %[w0], %[b0]\n\t"
-        "s_mov_b64 exec, s[100:101]\n\tv_fmac_f32 %[a], %[g0], %[v0]\n\t"
-        "v_readlane_b32 s100, %[w1], %[a1]\n\tv_readlane_b32 s101, %[w1], %[b1]\n\t"
-        "s_mov_b64 exec, s[100:101]\n\tv_fmac_f32 %[a], %[g1], %[v1]\n\t"
-        "v_readlane_b32 s100, %[w2], %[a2]\n\tv_readlane_b32 s101, %[w2], %[b2]\n\t"
-        "s_mov_b64 exec, s[100:101]\n\tv_fmac_f32 %[a], %[g2], %[v2]\n\t"
-        "v_readlane_b32 s100, %[w3], %[a3]\n\tv_readlane_b32 s101, %[w3], %[b3]\n\t"
-        "s_mov_b64 exec, s[100:101]\n\tv_fmac_f32 %[a], %[g3], %[v3]\n\t"
+        "v_readlane_b32 s94, %[w0], %[a0]\n\tv_readlane_b32 s95, %[w0], %[b0]\n\t"
+        "s_mov_b64 exec, s[94:95]\n\tv_fmac_f32 %[a], %[g0], %[v0]\n\t"
+        "v_readlane_b32 s94, %[w1], %[a1]\n\tv_readlane_b32 s95, %[w1], %[b1]\n\t"
+        "s_mov_b64 exec, s[94:95]\n\tv_fmac_f32 %[a], %[g1], %[v1]\n\t"
+        "v_readlane_b32 s94, %[w2], %[a2]\n\tv_readlane_b32 s95, %[w2], %[b2]\n\t"
+        "s_mov_b64 exec, s[94:95]\n\tv_fmac_f32 %[a], %[g2], %[v2]\n\t"
+        "v_readlane_b32 s94, %[w3], %[a3]\n\tv_readlane_b32 s95, %[w3], %[b3]\n\t"
+        "s_mov_b64 exec, s[94:95]\n\tv_fmac_f32 %[a], %[g3], %[v3]\n\t"
         "s_mov_b64 exec, -1"
         : [a] "+v"(acc)
         : [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3),
@@ -189,7 +189,7 @@ __device__ __forceinline__ void masked_fmac4_lanes(float& acc, uint32_t w0, uint
           [a2] "n"(L2), [b2] "n"(L2 + 32), [a3] "n"(L3), [b3] "n"(L3 + 32),
           [g0] "s"(g[0]), [g1] "s"(g[1]), [g2] "s"(g[2]), [g3] "s"(g[3]),
           [v0] "v"(v[0]), [v1] "v"(v[1]), [v2] "v"(v[2]), [v3] "v"(v[3])
-        : "s100", "s101");
+        : "s94", "s95");
 }
 
 // One accumulator row I (0..15) against the four s of group UB (0..3) of a 16-s super-step.

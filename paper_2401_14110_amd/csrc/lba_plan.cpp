@@ -255,10 +255,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     if (fast && (flush || clamp) && std::abs(c_a_dom - c_p_dom) > 120) fast = false;   // kc must be an FP32 normal
     // the recompute kernel also forms p * kc * 2^60 and S * 2^60
     if (fast && events && (std::abs(c_a_dom - c_p_dom) > 60 || top_exp(qa) + c_a_dom + 61 > 126)) fast = false;
-    // the DIFF plane's scaled-domain kernel: E4M3 operands, Q_prod without mantissa rounding, and an
-    // accumulator whose sums differ by fewer than 2^24 grid units (the difference is then exact in FP32)
-    if (events == 2 && (prod_round || nouf_a || conv || in.ea != 4 || in.eb != 4 ||
-                        (1 << qa.exp_bits) + qa.man_bits + 1 > 24)) fast = false;
+    // the DIFF plane's scaled-domain kernel: E4M3 operands, Q_prod without mantissa rounding
+    if (events == 2 && (prod_round || nouf_a || conv || in.ea != 4 || in.eb != 4)) fast = false;
 
     if (fast) {
         p.kernel = KERNEL_FAST;
@@ -284,8 +282,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         p.valu_per_mac_x100 = slots * 100;
         if (events)                                              // 5 full-rate + 7 half-rate instructions, + operand tests
             p.valu_per_mac_x100 = 1950 + (p.prod_mode == PM_FLUSH_CLAMP ? 200 : 0);
-        if (events == 2)                                         // mul, fma, and, mul, sub, mul; med3, cmp, addc at half rate
-            p.valu_per_mac_x100 = 1200 + (p.prod_mode == PM_FLUSH_CLAMP ? 200 : 0);
+        if (events == 2)                                         // mul, fma, and, mul, max, min, mul, sub, cmp; med3, addc at half rate
+            p.valu_per_mac_x100 = 1300 + (p.prod_mode == PM_FLUSH_CLAMP ? 200 : 0);
         if (order == LBA_ORDER_CHUNK16)                          // add, and [, bfe, add3], zero per 16 steps
             p.valu_per_mac_x100 += (events ? 1300 : (qa.round == LBA_ROUND_RNE ? 700 : 300)) / 16;
     } else {
