@@ -59,7 +59,7 @@ enum { LBA_ORDER_SEQ = 0,       /* k = 0 .. K-1 in one chain (App. D)           
 
 enum { LBA_OK = 0,
        LBA_ERR_NULL = 1,         /* a required pointer is NULL                                  */
-       LBA_ERR_SHAPE = 2,        /* negative or too large M, N, K                               */
+       LBA_ERR_SHAPE = 2,        /* negative or too large M, N, K (or M*N, where a call says so)  */
        LBA_ERR_FORMAT = 3,       /* a quantizer format outside the limits above                 */
        LBA_ERR_UNSUPPORTED = 4,  /* unknown order, or lba_gemm_bwd with the chunked order        */
        LBA_ERR_ALIGN = 5,        /* reserved: no entry point requires alignment                 */
@@ -70,7 +70,8 @@ enum { LBA_OK = 0,
  *   E4M3: 1 sign, 4 exponent (bias 7), 3 mantissa bits; e = 0 is subnormal, m * 2^-9; no inf.
  *   The two NaN codes 0x7f / 0xff are outside the contract; they are read as +-480.
  *   Zero results are stored as +0.0f.  K == 0 stores +0.0f everywhere; M*N == 0 does nothing.
- *   No alignment is required of A, B, C or of K.  Shape limits: M, K <= 2^31 - 64, N <= 2^21.
+ *   No alignment is required of A, B, C or of K.  Shape limits: M <= 2^30 - 64, K <= 2^31 - 64,
+ *   N <= 2^21 (else LBA_ERR_SHAPE).
  *   order: LBA_ORDER_SEQ, or LBA_ORDER_CHUNK16 = chunks of 16 consecutive k, each summed by its own
  *   chain from 0, then T_0 = 0, T_{j+1} = Q_acc(T_j + chunk_j) over the chunks in order (a short last
  *   chunk when 16 does not divide K; no Q_prod at the second level). */
@@ -111,7 +112,7 @@ int lba_gemm_bwd_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_m
  * X[n, oh*stride - pad + i, ow*stride - pad + j, ch] at k = (i*kw + j)*c + ch (c fastest: this IS the
  * accumulation order of every output's chain), and taps outside the image hold code 0 (the value +0).
  * Limits (else LBA_ERR_SHAPE): every field >= 1 (pad >= 0), c < 2^14, kw < 2^14, K < 2^24, oh, ow >= 1,
- * n*oh*ow <= 2^31 - 64.  Everything else as lba_gemm. */
+ * n*oh*ow <= 2^30 - 64.  Everything else as lba_gemm. */
 typedef struct {
     int32_t n, h, w, c;     /* activation tensor */
     int32_t kh, kw;         /* filter taps */
@@ -212,7 +213,7 @@ enum { LBA_STE_IDENTITY = 0, LBA_STE_IMMEDIATE_OF = 1, LBA_STE_RECURSIVE_OF = 2,
  *     Fig. 1 with the arrows reversed): c_k = 1 iff none of them overflowed.  Needs of_mask2, the
  *     second-level OF plane of lba_gemm_bwd_chunked.
  * coef has lba_mask_words(M, N, K) words and may be the same buffer as of_mask (in place).  The plane is
- * consumed by lba_grad with ste = LBA_STE_COEF_PLANE.
+ * consumed by lba_grad with ste = LBA_STE_COEF_PLANE.  M * N <= 2^31 (else LBA_ERR_SHAPE).
  * Returns LBA_OK, LBA_ERR_NULL, LBA_ERR_SHAPE, LBA_ERR_UNSUPPORTED (ste or order) or LBA_ERR_LAUNCH. */
 int lba_ste_plane(const uint32_t* of_mask, const uint32_t* of_mask2, uint32_t* coef,
                   int64_t M, int64_t N, int64_t K, int32_t ste, int32_t order, void* hip_stream);
@@ -220,6 +221,7 @@ int lba_ste_plane(const uint32_t* of_mask, const uint32_t* of_mask2, uint32_t* c
 /* The recursive estimator's post-pass (App. D): last_of[m*N + n] = the largest k whose bit is set in the
  * OF plane of lba_gemm_bwd, or -1 when the chain never overflowed.  of_mask: lba_mask_words(M, N, K)
  * words, last_of: M*N int32, both device pointers owned by the caller.  K == 0 writes -1 everywhere.
+ * M * N <= 2^31 (else LBA_ERR_SHAPE).
  * Returns LBA_OK, LBA_ERR_NULL, LBA_ERR_SHAPE or LBA_ERR_LAUNCH. */
 int lba_last_overflow(const uint32_t* of_mask, int32_t* last_of, int64_t M, int64_t N, int64_t K,
                       void* hip_stream);

@@ -453,6 +453,7 @@ extern "C" {
 int lba_last_overflow(const uint32_t* of_mask, int32_t* last_of, int64_t M, int64_t N, int64_t K, void* hip_stream) {
     int rc = lba::validate_shapes(M, N, K);
     if (rc != LBA_OK) return rc;
+    if (M * N > ((int64_t)1 << 31)) return LBA_ERR_SHAPE;      // one lane per output, fewer than 2^32 lanes per launch
     if (M == 0 || N == 0) return LBA_OK;
     if (!last_of || (K > 0 && !of_mask)) return LBA_ERR_NULL;
     const int64_t mn = M * N;
@@ -467,6 +468,7 @@ int lba_ste_plane(const uint32_t* of_mask, const uint32_t* of_mask2, uint32_t* c
     if (rc != LBA_OK) return rc;
     if (ste != LBA_STE_IMMEDIATE_OF && ste != LBA_STE_RECURSIVE_OF) return LBA_ERR_UNSUPPORTED;
     if (order != LBA_ORDER_SEQ && order != LBA_ORDER_CHUNK16) return LBA_ERR_UNSUPPORTED;
+    if (M * N > ((int64_t)1 << 31)) return LBA_ERR_SHAPE;      // one lane per output, fewer than 2^32 lanes per launch
     if (M == 0 || N == 0 || K == 0) return LBA_OK;
     if (!of_mask || !coef) return LBA_ERR_NULL;
     const bool two = ste == LBA_STE_RECURSIVE_OF && order == LBA_ORDER_CHUNK16;

@@ -182,7 +182,7 @@ int lba_conv2d_out_shape(lba_conv2d_desc d, int32_t* oh, int32_t* ow) {
     const int64_t eh = (int64_t)d.h + 2 * (int64_t)d.pad - d.kh, ew = (int64_t)d.w + 2 * (int64_t)d.pad - d.kw;
     if (eh < 0 || ew < 0) return LBA_ERR_SHAPE;
     const int64_t o_h = eh / d.stride + 1, o_w = ew / d.stride + 1;
-    if ((int64_t)d.n * o_h * o_w > (int64_t)2147483647 - 63) return LBA_ERR_SHAPE;
+    if ((int64_t)d.n * o_h * o_w > (((int64_t)1 << 30) - 64)) return LBA_ERR_SHAPE;   // the rows of the product
     if (oh) *oh = (int32_t)o_h;
     if (ow) *ow = (int32_t)o_w;
     return LBA_OK;
@@ -232,7 +232,7 @@ const char* lba_strerror(int code) {
     switch (code) {
         case LBA_OK: return "ok";
         case LBA_ERR_NULL: return "a required pointer is NULL";
-        case LBA_ERR_SHAPE: return "invalid shape (negative, or M/K >= 2^31, or N > 2^21)";
+        case LBA_ERR_SHAPE: return "invalid shape (negative, M > 2^30 - 64, K > 2^31 - 64, N > 2^21, or beyond the call's own limit)";
         case LBA_ERR_FORMAT: return "quantizer format outside the supported limits";
         case LBA_ERR_UNSUPPORTED: return "unknown or unimplemented accumulation order";
         case LBA_ERR_ALIGN: return "alignment (reserved)";

@@ -45,7 +45,10 @@
 
 namespace lba {
 
-static const int64_t kMaxDim = 2147483647LL - 63;   // tile origins and padded k stay below 2^31
+static const int64_t kMaxK = 2147483647LL - 63;     // padded k stays below 2^31
+// one workgroup of 256 lanes per 64 rows along grid x: a launch holds fewer than 2^32 lanes per grid
+// dimension (larger grids are cut short without an error), i.e. at most 2^24 - 1 workgroups
+static const int64_t kMaxM = ((1LL << 24) - 1) * 64;
 static const int64_t kMaxN = 1LL << 21;
 
 static inline int canon_bias(int E) { return (1 << (E - 1)) - 1; }
@@ -76,7 +79,7 @@ const InSpec& e4m3_spec() {                                  // 480 * 480 = 2304
 
 int validate_shapes(int64_t M, int64_t N, int64_t K) {
     if (M < 0 || N < 0 || K < 0) return LBA_ERR_SHAPE;
-    if (M > kMaxDim || K > kMaxDim || N > kMaxN) return LBA_ERR_SHAPE;
+    if (M > kMaxM || K > kMaxK || N > kMaxN) return LBA_ERR_SHAPE;
     return LBA_OK;
 }
 

@@ -79,6 +79,13 @@ def test_shape_order_and_null_errors():
     assert lb.lba_gemm(A, B, C, 8, 8, -1, GOOD_P, GOOD_A) == lb.ERR_SHAPE
     assert lb.lba_gemm(A, B, C, 1 << 31, 8, 8, GOOD_P, GOOD_A) == lb.ERR_SHAPE
     assert lb.lba_gemm(A, B, C, 8, (1 << 21) + 1, 8, GOOD_P, GOOD_A) == lb.ERR_SHAPE
+    # the largest M is 2^24 - 1 workgroups of 64 rows (a launch holds fewer than 2^32 lanes along x)
+    assert lb.lba_gemm(A, B, C, (1 << 30) - 63, 8, 8, GOOD_P, GOOD_A) == lb.ERR_SHAPE
+    assert lb.lba_plan_query((1 << 30) - 64, 8, 8, GOOD_P, GOOD_A)["grid_x"] == (1 << 24) - 1
+    assert lb.lba_gemm(A, B, C, 8, 8, (1 << 31) - 63, GOOD_P, GOOD_A) == lb.ERR_SHAPE
+    # one lane per output in the plane post-passes: M * N <= 2^31
+    assert lb.lba_last_overflow(A, C, 1 << 20, (1 << 11) + 1, 8) == lb.ERR_SHAPE
+    assert lb.lba_ste_plane(A, None, C, 1 << 20, (1 << 11) + 1, 8, 1, 0) == lb.ERR_SHAPE
     assert lb.lba_gemm(A, B, C, 8, 8, 8, GOOD_P, GOOD_A, order=5) == lb.ERR_UNSUPPORTED
     assert lb.lba_gemm(A, B, None, 8, 8, 8, GOOD_P, GOOD_A) == lb.ERR_NULL
     assert lb.lba_gemm(None, B, C, 8, 8, 8, GOOD_P, GOOD_A) == lb.ERR_NULL

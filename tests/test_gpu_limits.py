@@ -1,0 +1,128 @@
+"""GPU parity at the documented shape limits and at extreme aspect ratios: the largest M, operand
+matrices beyond 2^31 and 2^32 bytes, chains of more than 2^24 steps, the largest N, and the shapes just
+outside the limits (which must be refused, not run).  Operands are seeded; huge ones repeat a seeded
+block with a prime period, so that an index that wraps at a power of two lands on different data."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2401_14110_amd import binding as lb
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+PROD = (5, 7, 15)
+ACC = (4, 7, 7)
+PERIOD = 1000003                                                       # prime
+
+
+def codes(rng, shape, lo_e=0, hi_e=15):
+    e = rng.integers(lo_e, hi_e + 1, shape)
+    c = (rng.integers(0, 2, shape) << 7) | (e << 3) | rng.integers(0, 8, shape)
+    return np.where((c & 0x7F) == 0x7F, c & 0xFE, c).astype(np.uint8)
+
+
+def periodic_rows(rng, M, K, lo_e=0, hi_e=15):
+    """[M, K] codes on the GPU: row m is row m % PERIOD of a seeded block."""
+    block = torch.from_numpy(codes(rng, (PERIOD, K), lo_e, hi_e)).to(DEV)
+    reps = (M + PERIOD - 1) // PERIOD
+    return block.repeat(reps, 1)[:M].contiguous()
+
+
+def bits(x):
+    return np.ascontiguousarray(x).view(np.uint32)
+
+
+def test_largest_m(ref):
+    # M = 2^30 - 64 (the limit: 2^24 - 1 workgroups of 256 lanes along grid x), N = K = 1: one FMAq per output,
+    # so the whole 4.3 GB result is checked against the oracle's 256-entry table of Q_acc(Q_prod(a * b)); M one
+    # larger is refused
+    M = 2 ** 30 - 64
+    rng = np.random.default_rng(2031)
+    A = periodic_rows(rng, M, 1)
+    b = np.array([[0x3A]], dtype=np.uint8)                             # 1.25
+    for rnd in (0, 1):
+        qp, qa = PROD + (rnd,), ACC + (rnd,)
+        table = ref.gemm(np.arange(256, dtype=np.uint8).reshape(256, 1), b, ref.QFmt(*qp), ref.QFmt(*qa))
+        tb = torch.from_numpy(table.view(np.int32).reshape(256)).to(DEV)
+        C = lb.gemm(A, torch.from_numpy(b).to(DEV), qp, qa)
+        torch.cuda.synchronize()
+        got = C.view(torch.int32).reshape(-1)
+        step = 1 << 28
+        for s in range(0, M, step):
+            want = tb[A[s:s + step, 0].long()]
+            assert torch.equal(got[s:s + step], want), (rnd, s)
+        del C, got
+    with pytest.raises(lb.LbaError):
+        lb.lba_plan_query(M + 1, 1, 1, PROD + (0,), ACC + (0,))
+
+
+def test_operand_beyond_4_gib_and_its_planes(ref):
+    # A of 2^25 + 3 rows x 136 bytes = 4.56e9 bytes: sampled rows (first, last, around byte offsets 2^31 and 2^32,
+    # random) of C and of both event planes against the oracle, both roundings and both orders
+    M, N, K = 2 ** 25 + 3, 2, 136
+    rng = np.random.default_rng(2032)
+    A = periodic_rows(rng, M, K, 3, 11)
+    Bh = codes(rng, (N, K), 3, 11)
+    B = torch.from_numpy(Bh).to(DEV)
+    rows = {0, 1, 63, 64, M - 1, M - 2, M - 65, PERIOD - 1, PERIOD, PERIOD + 1}
+    for off in (2 ** 31, 2 ** 32):
+        rows |= {off // K + d for d in (-1, 0, 1, 2)}
+    rows |= set(int(r) for r in rng.integers(0, M, 300))
+    rows = np.array(sorted(rows))
+    idx = torch.from_numpy(rows).to(DEV)
+    Ah = A.index_select(0, idx).cpu().numpy()
+    for rnd, order in ((0, 0), (1, 0), (0, 1), (1, 1)):
+        qp, qa = PROD + (rnd,), ACC + (rnd,)
+        wants = ref.gemm_bwd(Ah, Bh, ref.QFmt(*qp), ref.QFmt(*qa), order=order, level2=bool(order))
+        C = lb.gemm(A, B, qp, qa, order=order)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(C.index_select(0, idx).cpu().numpy()), bits(wants[0])), (rnd, order, "C")
+        del C
+        gots = lb.gemm_bwd_chunked(A, B, qp, qa) if order else lb.gemm_bwd(A, B, qp, qa)
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(gots[0].index_select(0, idx).cpu().numpy()), bits(wants[0])), (rnd, order, "C of the recompute call")
+        for i in range(1, len(wants)):                                 # OF, UF [, second-level OF, UF]
+            assert np.array_equal(gots[i].index_select(1, idx).cpu().numpy().view(np.uint32), wants[i]), (rnd, order, i)
+        del gots
+
+
+def test_chains_longer_than_2_to_24(ref):
+    # K = 2^24 + 7 (odd: unaligned rows), 3 x 5 outputs: complete comparison, both roundings and orders; the
+    # recompute call at K = 2^22 + 5 with complete planes
+    rng = np.random.default_rng(2033)
+    M, N, K = 3, 5, 2 ** 24 + 7
+    A = codes(rng, (M, K), 2, 9); B = codes(rng, (N, K), 2, 9)
+    tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    for rnd, order in ((0, 0), (1, 0), (0, 1), (1, 1)):
+        qp, qa = PROD + (rnd,), (5, 10, 15, rnd)
+        C = lb.gemm(tA, tB, qp, qa, order=order)
+        torch.cuda.synchronize()
+        want = ref.gemm(A, B, ref.QFmt(*qp), ref.QFmt(*qa), order=order)
+        assert np.array_equal(bits(C.cpu().numpy()), bits(want)), (rnd, order)
+    K2 = 2 ** 22 + 5
+    A2, B2 = np.ascontiguousarray(A[:, :K2]), np.ascontiguousarray(B[:, :K2])
+    tA2, tB2 = torch.from_numpy(A2).to(DEV), torch.from_numpy(B2).to(DEV)
+    for rnd in (0, 1):
+        qp, qa = PROD + (rnd,), ACC + (rnd,)
+        C, of, uf = lb.gemm_bwd(tA2, tB2, qp, qa)
+        torch.cuda.synchronize()
+        want, wof, wuf = ref.gemm_bwd(A2, B2, ref.QFmt(*qp), ref.QFmt(*qa))
+        assert np.array_equal(bits(C.cpu().numpy()), bits(want)), rnd
+        assert np.array_equal(of.cpu().numpy().view(np.uint32), wof), rnd
+        assert np.array_equal(uf.cpu().numpy().view(np.uint32), wuf), rnd
+
+
+def test_largest_n(ref):
+    # N = 2^21 (the limit) with M = 2, K = 3: complete comparison; N one larger is refused
+    rng = np.random.default_rng(2034)
+    M, N, K = 2, 2 ** 21, 3
+    A = codes(rng, (M, K)); B = codes(rng, (N, K))
+    for rnd in (0, 1):
+        qp, qa = PROD + (rnd,), ACC + (rnd,)
+        C = lb.gemm(torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV), qp, qa)
+        torch.cuda.synchronize()
+        want = ref.gemm(A, B, ref.QFmt(*qp), ref.QFmt(*qa))
+        assert np.array_equal(bits(C.cpu().numpy()), bits(want)), rnd
+    with pytest.raises(lb.LbaError):
+        lb.lba_plan_query(M, N + 1, K, PROD + (0,), ACC + (0,))
