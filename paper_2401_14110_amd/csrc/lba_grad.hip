@@ -337,9 +337,15 @@ __global__ void __launch_bounds__(256) lba_grad_kernel(const float* __restrict__
     }
 }
 
+// x[0..n) = 0 with a grid-stride loop (the launch caps the grid: a grid dimension holds fewer than 2^32 lanes)
 __global__ void lba_grad_zero_kernel(float* x, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) x[i] = 0.0f;
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += step) x[i] = 0.0f;
+}
+
+static inline dim3 zero_grid(int64_t n) {
+    const int64_t blocks = (n + 255) / 256;
+    return dim3((unsigned)(blocks < (1 << 20) ? blocks : (1 << 20)));
 }
 
 // last_of[m, n] = highest k whose bit is set in the plane, -1 if none: one lane per output, walking
@@ -437,7 +443,7 @@ static int run_grad_side(bool dx, const float* G, const uint8_t* V, const uint32
     gp.vec_ok = ((al % 16) == 0 && (N % 4) == 0) ? 1 : 0;
     if (gp.atomic) {
         const int64_t n = (int64_t)gp.R * K;
-        hipLaunchKernelGGL(lba_grad_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, out, n);
+        hipLaunchKernelGGL(lba_grad_zero_kernel, zero_grid(n), dim3(256), 0, st, out, n);
         if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
     }
     const dim3 grid((unsigned)gx, (unsigned)gy, (unsigned)split);
@@ -500,7 +506,7 @@ int lba_grad(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t*
         float* o = M == 0 ? dW : dX;
         const int64_t n = (M == 0 ? N : M) * K;
         if (o && n > 0) {
-            hipLaunchKernelGGL(lba::lba_grad_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, o, n);
+            hipLaunchKernelGGL(lba::lba_grad_zero_kernel, lba::zero_grid(n), dim3(256), 0, st, o, n);
             if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
         }
         return LBA_OK;

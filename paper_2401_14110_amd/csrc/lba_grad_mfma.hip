@@ -284,8 +284,8 @@ __global__ void __launch_bounds__(256) lba_grad_boundary_kernel(const float* __r
 }
 
 __global__ void lba_grad_dense_zero_kernel(float* x, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) x[i] = 0.0f;
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += step) x[i] = 0.0f;
 }
 
 // Can the matrix-core path take this product?  16-byte rows of G (and of last_of) in both directions, 4-byte
@@ -319,7 +319,7 @@ int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* las
     d.atomic = split > 1 ? 1 : 0;
     if (d.atomic) {
         const int64_t n = (int64_t)d.R * K;
-        hipLaunchKernelGGL(lba_grad_dense_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, out, n);
+        hipLaunchKernelGGL(lba_grad_dense_zero_kernel, dim3((unsigned)((n + 255) / 256 < (1 << 20) ? (n + 255) / 256 : (1 << 20))), dim3(256), 0, st, out, n);
         if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
     }
     const dim3 grid((unsigned)gx, (unsigned)gy, (unsigned)split);

@@ -8,9 +8,10 @@
 
 namespace lba {
 
+// C[0..n) = +0 with a grid-stride loop (n may exceed what one grid dimension holds, 2^32 - 1 lanes)
 __global__ void lba_fill_zero_kernel(float* C, int64_t n) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) C[i] = 0.0f;
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += step) C[i] = 0.0f;
 }
 
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
@@ -50,9 +51,9 @@ static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, 
     hipStream_t st = (hipStream_t)stream;
     if (K == 0) {                                              // empty chains: S_0 = 0; no mask words
         if (C) {
-            const int64_t n = M * N;
+            const int64_t n = M * N, blocks = (n + 255) / 256;
             for (int64_t z = 0; z < batch; ++z) {
-                hipLaunchKernelGGL(lba_fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                hipLaunchKernelGGL(lba_fill_zero_kernel, dim3((unsigned)(blocks < (1 << 20) ? blocks : (1 << 20))), dim3(256), 0, st,
                                    C + z * stride_c, n);
                 if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
             }

@@ -126,3 +126,64 @@ def test_largest_n(ref):
         assert np.array_equal(bits(C.cpu().numpy()), bits(want)), rnd
     with pytest.raises(lb.LbaError):
         lb.lba_plan_query(M, N + 1, K, PROD + (0,), ACC + (0,))
+
+
+def _grad_check(got, want, scale, terms, what):
+    tol = 2 * (terms + 1) * 2.0 ** -24 * scale + 1e-30
+    err = np.abs(got - want)
+    assert (err <= tol).all(), "%s: worst error / tolerance %.3g" % (what, float((err / tol).max()))
+    assert float((err / tol).max()) < 0.5
+
+
+def test_gradient_products_at_the_largest_m_times_n(ref):
+    # lba_grad with M * N = 2^30 (its limit; G is 4 GiB, the OF plane 8 GiB): sampled rows of dX and sampled
+    # columns of dW for the three estimators; one more row is refused
+    from oracle import lba_grad_ref as gref
+    M, N, K = 2 ** 20, 2 ** 10, 64
+    rng = np.random.default_rng(2035)
+    Ah = codes(rng, (M, K), 3, 11); Bh = codes(rng, (N, K), 3, 11)
+    A, B = torch.from_numpy(Ah).to(DEV), torch.from_numpy(Bh).to(DEV)
+    torch.manual_seed(2035)
+    G = torch.randn((M, N), dtype=torch.float32, device=DEV)
+    qp, qa = PROD + (0,), ACC + (0,)
+    fp, fa = ref.QFmt(*qp), ref.QFmt(*qa)
+    _, of, _ = lb.gemm_bwd(A, B, qp, qa, want_c=False, want_uf=False)
+    last = lb.last_overflow(of, K)
+    rows = np.array(sorted({0, 1, 63, 64, M - 1, M - 2, M - 65, M // 2} | set(int(r) for r in rng.integers(0, M, 16))))
+    cols = np.array([1, N - 1])                                        # each needs all 2^20 rows in the oracle
+    idx, jdx = torch.from_numpy(rows).to(DEV), torch.from_numpy(cols).to(DEV)
+    Gr = G.index_select(0, idx).cpu().numpy(); Gc = G.index_select(1, jdx).cpu().numpy()
+    blocked = 0
+    for ste in (lb.STE_IDENTITY, lb.STE_IMMEDIATE_OF, lb.STE_RECURSIVE_OF):
+        dX, dW = lb.grad(G, A, B, ste, of_plane=of if ste == lb.STE_IMMEDIATE_OF else None,
+                         last_of=last if ste == lb.STE_RECURSIVE_OF else None)
+        torch.cuda.synchronize()
+        c = gref.coefficients(Ah[rows], Bh, fp, fa, ste)
+        blocked += int((~c).sum())
+        wX, _ = gref.grad(Gr, Ah[rows], Bh, fp, fa, ste, c=c)
+        aX, _ = gref.grad_abs(Gr, Ah[rows], Bh, fp, fa, ste, c=c)
+        _grad_check(dX.index_select(0, idx).cpu().numpy(), wX, aX, N, "ste=%d dX rows" % ste)
+        c = gref.coefficients(Ah, Bh[cols], fp, fa, ste)
+        _, wW = gref.grad(Gc, Ah, Bh[cols], fp, fa, ste, c=c)
+        _, aW = gref.grad_abs(Gc, Ah, Bh[cols], fp, fa, ste, c=c)
+        _grad_check(dW.index_select(0, jdx).cpu().numpy(), wW, aW, M, "ste=%d dW columns" % ste)
+        del dX, dW, c
+    assert blocked > 0
+    assert lb.lba_grad(G.data_ptr(), A.data_ptr(), B.data_ptr(), None, None, G.data_ptr(), None, M + 1, N, K,
+                       lb.STE_IDENTITY) == lb.ERR_SHAPE            # refused before any pointer is used
+
+
+def test_zero_fills_beyond_2_to_32_elements():
+    # K == 0 stores +0 in all of C, M == 0 stores zeros in all of dW: both with more than 2^32 outputs
+    M, N = 2 ** 22 + 1, 2 ** 10 + 3
+    C = torch.full((M, N), 1.0, dtype=torch.float32, device=DEV)
+    z = torch.empty((M, 0), dtype=torch.uint8, device=DEV)
+    lb.gemm(z, torch.empty((N, 0), dtype=torch.uint8, device=DEV), PROD + (0,), ACC + (0,), out=C)
+    torch.cuda.synchronize()
+    assert int(C.view(torch.int32).count_nonzero()) == 0
+    del C
+    N, K = 2 ** 21, 2112
+    dW = torch.full((N, K), 1.0, dtype=torch.float32, device=DEV)
+    rc = lb.lba_grad(None, None, None, None, None, None, dW.data_ptr(), 0, N, K, lb.STE_IDENTITY)
+    torch.cuda.synchronize()
+    assert rc == lb.OK and int(dW.view(torch.int32).count_nonzero()) == 0
