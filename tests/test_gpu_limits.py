@@ -187,3 +187,66 @@ def test_zero_fills_beyond_2_to_32_elements():
     rc = lb.lba_grad(None, None, None, None, None, None, dW.data_ptr(), 0, N, K, lb.STE_IDENTITY)
     torch.cuda.synchronize()
     assert rc == lb.OK and int(dW.view(torch.int32).count_nonzero()) == 0
+
+
+def test_plane_post_passes_at_two_to_31_outputs():
+    # lba_last_overflow and lba_ste_plane with M * N = 2^31 (their limit) and K = 32 (one word per output, so
+    # the expected values follow from each word alone): last = index of the highest set bit or -1; immediate
+    # coefficients = complement; recursive (sequential) coefficients = the bits above `last`
+    M, N, K = 2 ** 20, 2 ** 11, 32
+    torch.manual_seed(2036)
+    of = torch.randint(-2 ** 31, 2 ** 31, (1, M, N), dtype=torch.int32, device=DEV)
+    of &= torch.randint(-2 ** 31, 2 ** 31, (1, M, N), dtype=torch.int32, device=DEV)
+    of &= torch.randint(-2 ** 31, 2 ** 31, (1, M, N), dtype=torch.int32, device=DEV)     # sparser bits
+    of.view(-1)[::7] = 0                                                                   # chains without overflow
+    last = lb.last_overflow(of, K)
+    imm = lb.ste_plane(of, K, lb.STE_IMMEDIATE_OF)
+    rec = lb.ste_plane(of, K, lb.STE_RECURSIVE_OF)
+    torch.cuda.synchronize()
+    fo, fl, fi, fr = of.view(-1), last.view(-1), imm.view(-1), rec.view(-1)
+    step = 1 << 27
+    for s in range(0, M * N, step):
+        w = fo[s:s + step].long() & 0xFFFFFFFF
+        want_last = torch.where(w == 0, torch.full_like(w, -1), torch.log2(w.double()).floor().long())
+        assert torch.equal(fl[s:s + step].long(), want_last), s
+        assert torch.equal(fi[s:s + step].long() & 0xFFFFFFFF, w ^ 0xFFFFFFFF), s
+        want_rec = (torch.full_like(w, 0xFFFFFFFF) << (want_last + 1)) & 0xFFFFFFFF
+        assert torch.equal(fr[s:s + step].long() & 0xFFFFFFFF, want_rec), s
+    assert lb.lba_last_overflow(of.data_ptr(), last.data_ptr(), M + 1, N, K) == lb.ERR_SHAPE
+
+
+def test_largest_batch(ref):
+    # lba_gemm_batched with 65535 members (the limit) sharing B: equals one product on the stacked rows
+    rng = np.random.default_rng(2037)
+    batch, M, N, K = 65535, 5, 7, 19
+    A = codes(rng, (batch, M, K), 3, 11); B = codes(rng, (N, K), 3, 11)
+    for rnd in (0, 1):
+        qp, qa = PROD + (rnd,), ACC + (rnd,)
+        C = lb.gemm_batched(torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV), qp, qa)
+        torch.cuda.synchronize()
+        want = ref.gemm(A.reshape(batch * M, K), B, ref.QFmt(*qp), ref.QFmt(*qa))
+        assert np.array_equal(bits(C.cpu().numpy().reshape(batch * M, N)), bits(want)), rnd
+    assert lb.lba_gemm_batched(1, 1, 1, 65536, M * K, 0, M * N, M, N, K, PROD + (0,), ACC + (0,)) == lb.ERR_SHAPE
+
+
+def test_convolution_descriptor_limits(ref):
+    # lba_conv2d at the descriptor's limits: c = 2^14 - 1 (bytes gathered one by one), the largest c that takes
+    # the 16-byte path, kw = 2^14 - 1, and kh * kw * c just below 2^24; complete outputs against the oracle on the
+    # written-out im2col matrix.  The descriptors just outside are refused.
+    rng = np.random.default_rng(2038)
+    cases = [(1, 3, 3, 16383, 5, 1, 1, 1, 0), (1, 4, 4, 16368, 8, 1, 1, 1, 0), (1, 2, 16390, 1, 4, 1, 16383, 1, 0),
+             (2, 127, 127, 1023, 3, 127, 127, 1, 0)]
+    for (n, h, w, c, cout, kh, kw, stride, pad) in cases:
+        X = codes(rng, (n, h, w, c), 3, 10); W = codes(rng, (cout, kh, kw, c), 3, 10)
+        A = ref.im2col_nhwc(X, kh, kw, stride, pad)
+        B = W.reshape(cout, kh * kw * c)
+        for rnd in (0, 1):
+            qp, qa = PROD + (rnd,), (5, 10, 15, rnd)
+            Y = lb.conv2d(torch.from_numpy(X).to(DEV), torch.from_numpy(W).to(DEV), qp, qa, stride=stride, pad=pad)
+            torch.cuda.synchronize()
+            want = ref.gemm(A, B, ref.QFmt(*qp), ref.QFmt(*qa))
+            assert np.array_equal(bits(Y.cpu().numpy().reshape(want.shape)), bits(want)), ((n, h, w, c, cout, kh, kw), rnd)
+    assert lb.lba_conv2d_out_shape((1, 128, 128, 1024, 128, 128, 1, 0))[0] == lb.ERR_SHAPE    # kh * kw * c = 2^24
+    assert lb.lba_conv2d_out_shape((1, 1, 1 << 14, 1, 1, 1 << 14, 1, 0))[0] == lb.ERR_SHAPE   # kw = 2^14
+    assert lb.lba_conv2d_out_shape((1 << 16, 128, 128, 1, 1, 1, 1, 0))[0] == lb.ERR_SHAPE     # 2^30 rows
+    assert lb.lba_conv2d_out_shape((1 << 16, 128, 128, 1, 2, 2, 1, 0))[0] == lb.OK
