@@ -581,3 +581,92 @@ def test_mixed_grid(ref):
     assert lb.lba_plan_query(64 * 100, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["thread_n"] == 2
     assert lb.lba_plan_query(64 * 12544, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
     assert lb.lba_plan_query(64 * 300, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), 0, 1)["tail_blocks"] == 0
+
+
+def test_calls_on_side_streams(ref):
+    # Every kernel of a call runs on the caller's stream: a chain of dependent calls (recompute call -> last
+    # overflow -> coefficient plane -> gradient products with their zero fill and atomic adds) is queued on a
+    # non-default stream without any synchronisation in between, twice at once on two streams with different
+    # operands.  The integer results equal the oracle's; the gradients equal those of the same calls on the
+    # default stream up to the summation order.
+    rng = np.random.default_rng(321)
+    qp, qa = (5, 7, 15, 0), (4, 7, 7, 0)
+    jobs = []
+    for (M, N, K) in ((520, 260, 500), (300, 516, 260)):
+        A = rand_codes(rng, (M, K), 3, 11); B = rand_codes(rng, (N, K), 3, 11)
+        G = rng.standard_normal((M, N)).astype(np.float32)
+        jobs.append((A, B, G, torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV), torch.from_numpy(G).to(DEV)))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    outs = []
+    for (A, B, G, tA, tB, tG), st in zip(jobs, streams):
+        K = A.shape[1]
+        with torch.cuda.stream(st):                                    # allocations of the binding follow the stream
+            C, of, uf = lb.gemm_bwd(tA, tB, qp, qa, stream=st)
+            last = lb.last_overflow(of, K, stream=st)
+            coef = lb.ste_plane(of, K, lb.STE_RECURSIVE_OF, stream=st)
+            dX, dW = lb.grad(tG, tA, tB, lb.STE_COEF_PLANE, of_plane=coef, stream=st)
+            dX2, dW2 = lb.grad(tG, tA, tB, lb.STE_RECURSIVE_OF, last_of=last, stream=st)
+        outs.append((C, of, uf, last, coef, dX, dW, dX2, dW2))
+    for st in streams:
+        st.synchronize()
+    for (A, B, G, tA, tB, tG), (C, of, uf, last, coef, dX, dW, dX2, dW2) in zip(jobs, outs):
+        K = A.shape[1]
+        wc, wof, wuf = ref.gemm_bwd(A, B, fm(ref, qp), fm(ref, qa))
+        assert np.array_equal(bits(C.cpu().numpy()), bits(wc))
+        assert np.array_equal(of.cpu().numpy().view(np.uint32), wof) and np.array_equal(uf.cpu().numpy().view(np.uint32), wuf)
+        last0 = lb.last_overflow(of, K)
+        dXr, dWr = lb.grad(tG, tA, tB, lb.STE_RECURSIVE_OF, last_of=last0)
+        torch.cuda.synchronize()
+        assert torch.equal(last, last0) and int((last >= 0).sum()) > 0
+        scale = float(dXr.abs().max()) + float(dWr.abs().max())
+        for got, want in ((dX, dXr), (dX2, dXr), (dW, dWr), (dW2, dWr)):
+            assert float((got - want).abs().max()) <= 1e-4 * scale
+
+
+def test_hip_graph_replays(ref):
+    # The library only launches kernels (no allocation, no memset, no synchronisation), so a sequence of calls can
+    # be captured into a HIP graph.  The graph is replayed three times with new operands written into the same
+    # buffers, with eager work and synchronisations between the replays; every replay is checked against the
+    # oracle (integers) and against the eager gradient products.
+    rng = np.random.default_rng(322)
+    qp, qa = (5, 7, 15, 0), (4, 7, 7, 0)
+    M, N, K = 200, 132, 300
+    tA = torch.zeros((M, K), dtype=torch.uint8, device=DEV); tB = torch.zeros((N, K), dtype=torch.uint8, device=DEV)
+    tG = torch.zeros((M, N), dtype=torch.float32, device=DEV)
+    C = torch.empty((M, N), dtype=torch.float32, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                      # one eager pass before the capture
+        lb.gemm(tA, tB, qp, qa, out=C)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lb.gemm(tA, tB, qp, qa, out=C)
+        Cc = lb.gemm(tA, tB, qp, qa, order=1)
+        C2, of, uf = lb.gemm_bwd(tA, tB, qp, qa)
+        last = lb.last_overflow(of, K)
+        dX, dW = lb.grad(tG, tA, tB, lb.STE_RECURSIVE_OF, last_of=last)
+        dXi, dWi = lb.grad(tG, tA, tB, lb.STE_IMMEDIATE_OF, of_plane=of)
+    for rep in range(3):
+        A = rand_codes(rng, (M, K), 3, 11); B = rand_codes(rng, (N, K), 3, 11)
+        G = rng.standard_normal((M, N)).astype(np.float32)
+        tA.copy_(torch.from_numpy(A)); tB.copy_(torch.from_numpy(B)); tG.copy_(torch.from_numpy(G))
+        for t in (C, Cc, C2, dX, dW, dXi, dWi):
+            t.fill_(7.0)                                               # stale values must not survive
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        wc, wof, wuf = ref.gemm_bwd(A, B, fm(ref, qp), fm(ref, qa))
+        assert np.array_equal(bits(C.cpu().numpy()), bits(wc)) and np.array_equal(bits(C2.cpu().numpy()), bits(wc)), rep
+        assert np.array_equal(bits(Cc.cpu().numpy()), bits(ref.gemm(A, B, fm(ref, qp), fm(ref, qa), order=1))), rep
+        assert np.array_equal(of.cpu().numpy().view(np.uint32), wof) and np.array_equal(uf.cpu().numpy().view(np.uint32), wuf), rep
+        last0 = lb.last_overflow(of, K)
+        eX, eW = lb.grad(tG, tA, tB, lb.STE_RECURSIVE_OF, last_of=last0)
+        eXi, eWi = lb.grad(tG, tA, tB, lb.STE_IMMEDIATE_OF, of_plane=of)
+        torch.cuda.synchronize()
+        assert torch.equal(last, last0), rep
+        scale = float(eX.abs().max()) + float(eW.abs().max())
+        for got, want in ((dX, eX), (dW, eW), (dXi, eXi), (dWi, eWi)):
+            assert float((got - want).abs().max()) <= 1e-4 * scale, rep
