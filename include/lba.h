@@ -258,7 +258,8 @@ typedef struct {
                                          per lane) on the last rows; grid_y is 1                            */
 } lba_plan_info;
 
-/* with_masks: 0 the forward call, 1 the recompute call with event planes, 2 lba_gemm_bwd_diff. */
+/* with_masks: 0 the forward call, 1 the recompute call with event planes, 2 lba_gemm_bwd_diff,
+ * 3 lba_gemm_bwd with the overflow plane alone (uf_mask == NULL). */
 int lba_plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc,
                    int32_t order, int32_t with_masks, lba_plan_info* out);
 

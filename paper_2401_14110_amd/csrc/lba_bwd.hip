@@ -19,6 +19,14 @@ hipError_t launch_fast_bwd(const Plan& pl, hipStream_t st) {
 #undef LBA_BWD1
         return hipGetLastError();
     }
+    if (pl.mix_tail > 0) {                                 // overflow plane alone, sequential order: mixed grid
+        if (uf || pl.order != LBA_ORDER_SEQ) return hipErrorInvalidValue;
+        const dim3 mgrid(pl.grid_x, 1, 1);
+        if (pl.prod_mode == PM_FLUSH)            hipLaunchKernelGGL((lba_fast_bwd_mixed_kernel<PM_FLUSH>), mgrid, block, 0, st, pl.kp);
+        else if (pl.prod_mode == PM_FLUSH_CLAMP) hipLaunchKernelGGL((lba_fast_bwd_mixed_kernel<PM_FLUSH_CLAMP>), mgrid, block, 0, st, pl.kp);
+        else return hipErrorInvalidValue;
+        return hipGetLastError();
+    }
 #define LBA_BWD(PM, ORDER, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, ORDER, UF>), grid, block, 0, st, pl.kp)
     if (pl.order == LBA_ORDER_CHUNK16) {
         if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD(PM_FLUSH, LBA_ORDER_CHUNK16, true); else LBA_BWD(PM_FLUSH, LBA_ORDER_CHUNK16, false); }

@@ -702,29 +702,36 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
 // Stores the 16 event words of a lane for plane word `word` (one word per chain): wof / wuf hold the
 // bits shifted in first-highest, `nbits` of them since the last store; bit 0 of the stored word is the
 // first of them and bits at or above `valid` are cleared.  The registers are zeroed.
+template <int TM, int TN>
 __device__ __forceinline__ void store_event_words(uint32_t* of_plane, uint32_t* uf_plane, int word, int nbits, int valid,
-                                                  uint32_t (&wof)[4][4], uint32_t (&wuf)[4][4],
+                                                  uint32_t (&wof)[TM][TN], uint32_t (&wuf)[TM][TN],
                                                   int m0, int n0, int tx, int ty, const KParams& p) {
+    static_assert(TN == 4 || TN == 2, "4 or 2 outputs per lane along n");
     const uint32_t vmask = valid >= 32 ? 0xFFFFFFFFu : ((1u << valid) - 1u);
     const int up = 32 - nbits;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = m0 + ty * 4 + i;
+    for (int i = 0; i < TM; ++i) {
+        const int m = m0 + ty * TM + i;
         if (m < p.M) {
-            const int n = n0 + tx * 4;
+            const int n = n0 + tx * TN;
             const int64_t off = ((int64_t)word * p.M + m) * p.N + n;
-            uint32_t o[4], u[4];
+            uint32_t o[TN], u[TN];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < TN; ++j) {
                 o[j] = __builtin_bitreverse32(wof[i][j] << up) & vmask;
                 u[j] = __builtin_bitreverse32(wuf[i][j] << up) & vmask;
             }
-            if (p.c_vec && n + 3 < p.N) {
-                if (of_plane) *reinterpret_cast<uint4*>(of_plane + off) = make_uint4(o[0], o[1], o[2], o[3]);
-                if (uf_plane) *reinterpret_cast<uint4*>(uf_plane + off) = make_uint4(u[0], u[1], u[2], u[3]);
+            if (p.c_vec && n + TN - 1 < p.N) {                 // N % 4 == 0 and aligned planes: 16- or 8-byte stores
+                if (TN == 4) {
+                    if (of_plane) *reinterpret_cast<uint4*>(of_plane + off) = make_uint4(o[0], o[1], o[TN - 2], o[TN - 1]);
+                    if (uf_plane) *reinterpret_cast<uint4*>(uf_plane + off) = make_uint4(u[0], u[1], u[TN - 2], u[TN - 1]);
+                } else {
+                    if (of_plane) *reinterpret_cast<uint2*>(of_plane + off) = make_uint2(o[0], o[1]);
+                    if (uf_plane) *reinterpret_cast<uint2*>(uf_plane + off) = make_uint2(u[0], u[1]);
+                }
             } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < TN; ++j)
                     if (n + j < p.N) {
                         if (of_plane) of_plane[off + j] = o[j];
                         if (uf_plane) uf_plane[off + j] = u[j];
@@ -732,7 +739,7 @@ __device__ __forceinline__ void store_event_words(uint32_t* of_plane, uint32_t* 
             }
         }
 #pragma unroll
-        for (int j = 0; j < 4; ++j) { wof[i][j] = 0u; wuf[i][j] = 0u; }
+        for (int j = 0; j < TN; ++j) { wof[i][j] = 0u; wuf[i][j] = 0u; }
     }
 }
 
@@ -778,16 +785,14 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_mixed_kernel
 // UF = false (no underflow plane asked for): the underflow tests are dropped, and under the sequential
 // order a k-tile that starts with every |S| of the wave below R_OF - BK * max|p| cannot overflow at all:
 // it runs the forward kernel's clamp-free tile and its OF words are zero.
-template <int PM, int ORDER, bool UF, int AMODE = 0>
-__global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_fast_bwd_kernel(const KParams p) {
-    constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
+template <int TM, int TN, int PM, int ORDER, bool UF, int AMODE>
+__device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, const int m0, const int n0) {
+    constexpr int BK = 32, BM = 16 * TM, BN = 16 * TN;
     constexpr int STAGE = BK * (BM + BN);
-    __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int tidb = tid - Stage<BN, BK>::kTailShift;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
     // batch member blockIdx.z (strides are 0 for a single GEMM)
     const uint8_t* pA = p.A + (int64_t)blockIdx.z * p.stride_a;
     const uint8_t* pB = p.B + (int64_t)blockIdx.z * p.stride_b;
@@ -983,24 +988,47 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
     if (pC) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const int m = m0 + ty * 4 + i;
+            const int m = m0 + ty * TM + i;
             if (m >= p.M) continue;
-            const int n = n0 + tx * 4;
-            float v[4];
+            const int n = n0 + tx * TN;
+            float v[TN];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < TN; ++j) {
                 const float s = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
                 v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);
             }
             float* dst = pC + (int64_t)m * p.N + n;
-            if (p.c_vec && n + 3 < p.N) {
-                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            if (p.c_vec && n + TN - 1 < p.N) {
+                if (TN == 4) *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[TN - 2], v[TN - 1]);
+                else         *reinterpret_cast<float2*>(dst) = make_float2(v[0], v[1]);
             } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < TN; ++j)
                     if (n + j < p.N) dst[j] = v[j];
             }
         }
+    }
+}
+
+template <int PM, int ORDER, bool UF, int AMODE = 0>
+__global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_fast_bwd_kernel(const KParams p) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
+    fast_bwd_body<4, 4, PM, ORDER, UF, AMODE>(p, smem, blockIdx.x * 64, blockIdx.y * 64);
+}
+
+// The overflow plane alone (sequential order, E4M3 matrices) on the mixed grid of lba_fast_mixed_kernel: 64 x 64
+// workgroups for the full rounds, 32 x 32 ones on the last rows.
+template <int PM>
+__global__ void __launch_bounds__(256, 4) lba_fast_bwd_mixed_kernel(const KParams p) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
+    const int b = blockIdx.x;
+    if (b < p.mix_main) {                                      // uniform
+        const int by = b / p.mix_gx_main, bx = b - by * p.mix_gx_main;
+        fast_bwd_body<4, 4, PM, LBA_ORDER_SEQ, false, 0>(p, smem, bx * 64, by * 64);
+    } else {
+        const int t = b - p.mix_main;
+        const int by = t / p.mix_gx_tail, bx = t - by * p.mix_gx_tail;
+        fast_bwd_body<2, 2, PM, LBA_ORDER_SEQ, false, 0>(p, smem, p.mix_m_main + bx * 32, by * 32);
     }
 }
 

@@ -64,6 +64,7 @@ struct Plan {
     int grid_x, grid_y;
     int valu_per_mac_x100;
     int mix_tail;            // > 0: mixed grid with that many 32 x 32 workgroups after kp.mix_main 64 x 64 ones
+    int of_only;             // 1 (events == 1): only the overflow plane is asked for (no underflow tests)
     int rne_odd;             // 1: nearest-even through two directed sums and round-to-odd (RND_RNE_ODD; 4 x 4 only)
     int amode;               // 1: A is read as im2col rows and / or an operand is not E4M3 (4 x 4 lane block only)
     KParams kp;

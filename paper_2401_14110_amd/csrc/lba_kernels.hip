@@ -107,7 +107,8 @@ int lba_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask
         const int rc = lba::make_plan(M, N, K, qprod, qacc, order, 1, &pl);
         return rc != LBA_OK ? rc : LBA_ERR_UNSUPPORTED;
     }
-    return lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, order, 1, hip_stream);
+    // 3: the overflow plane alone (the planner may then cut the last rows finer)
+    return lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, order, (of_mask && !uf_mask) ? 3 : 1, hip_stream);
 }
 
 // eps2 must make eps2 * |x w| exact in FP32: at most 12 significant bits, and a range that keeps the

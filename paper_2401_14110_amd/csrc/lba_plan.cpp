@@ -182,7 +182,9 @@ static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int event
 // efficiency), which the launch then finishes in quarter rounds.  Used when the model says 3 % or more.
 static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
     p->mix_tail = 0;
-    if (p->kernel != KERNEL_FAST || p->events || p->amode || p->rne_odd || batch != 1) return;
+    if (p->kernel != KERNEL_FAST || p->amode || p->rne_odd || batch != 1) return;
+    // the recompute call has the mixed grid for the overflow plane alone under the sequential order
+    if (p->events && !(p->events == 1 && p->of_only && p->order == LBA_ORDER_SEQ)) return;
     if (p->prod_mode != PM_IDENT && p->prod_mode != PM_FLUSH && p->prod_mode != PM_FLUSH_CLAMP) return;
     const int64_t gx = (M + 63) / 64, gy = (N + 63) / 64, blocks = gx * gy;
     if (blocks <= 384 || blocks > 256 * 16) return;
@@ -223,6 +225,7 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     Plan p;
     std::memset(&p, 0, sizeof(p));
     p.events = events == 2 ? 2 : (events ? 1 : 0);
+    p.of_only = events == 3 ? 1 : 0;
     p.order = order;
     p.round = qa.round;
     KParams& kp = p.kp;

@@ -581,6 +581,26 @@ def test_mixed_grid(ref):
     assert lb.lba_plan_query(64 * 100, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["thread_n"] == 2
     assert lb.lba_plan_query(64 * 12544, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
     assert lb.lba_plan_query(64 * 300, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), 0, 1)["tail_blocks"] == 0
+    # the recompute call has the mixed grid when only the overflow plane is asked for (sequential order): quiet
+    # operands (k-tiles that take the forward tile), loud ones, and a quiet start with a loud end
+    for (M, N, K), lo, hi in [((64 * 420 + 17, 60, 100), 3, 8), ((64 * 392, 64, 72), 0, 15), ((64 * 150 + 33, 130, 96), 3, 9)]:
+        A = rand_codes(rng, (M, K), lo, hi); B = rand_codes(rng, (N, K), lo, hi)
+        if (lo, hi) == (3, 9):
+            A[:, 64:] = rand_codes(rng, (M, K - 64), 10, 15)
+        tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+        for qp, qa in (FMT_PAPER[0], FMT_PAPER[2], FMT_SWEEP[4]):
+            qpf, qaf = qp + (0,), qa + (0,)
+            plan = lb.lba_plan_query(M, N, K, qpf, qaf, 0, 3)
+            assert plan["kernel"] == 0 and plan["tail_blocks"] > 0 and plan["grid_y"] == 1, plan
+            assert lb.lba_plan_query(M, N, K, qpf, qaf, 0, 1)["tail_blocks"] == 0        # both planes: plain grid
+            C, of, _ = lb.gemm_bwd(tA, tB, qpf, qaf, want_uf=False)
+            torch.cuda.synchronize()
+            wc, wof, _ = ref.gemm_bwd(A, B, fm(ref, qpf), fm(ref, qaf))
+            assert np.array_equal(bits(C.cpu().numpy()), bits(wc)), (M, N, K, qpf, qaf)
+            assert np.array_equal(of.cpu().numpy().view(np.uint32), wof), (M, N, K, qpf, qaf)
+            _, of2, _ = lb.gemm_bwd(tA, tB, qpf, qaf, want_uf=False, want_c=False)       # the plane alone
+            torch.cuda.synchronize()
+            assert torch.equal(of, of2)
 
 
 def test_calls_on_side_streams(ref):
