@@ -275,7 +275,7 @@ def main():
         "peak_measured": MEASURED_LANE_OPS / 1e12, "frac_of_measured": achieved / MEASURED_LANE_OPS,
         "traffic": RESNET50_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "resnet50" and rnd == 0 and order == 0 and not args.bwd and not args.grad) else None,
         "kernel": ("lba_grad_kernel<%s>" % args.grad) if args.grad else "lba_%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (
-            ("fast_diff" if args.diff is not None else ("fast_bwd_mixed" if dom_key[6] else "fast_bwd") if args.bwd else ("fast_mixed" if dom_key[6] else "fast")) if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
+            (("fast_diff_mixed" if dom_key[6] else "fast_diff") if args.diff is not None else ("fast_bwd_mixed" if dom_key[6] else "fast_bwd") if args.bwd else ("fast_mixed" if dom_key[6] else "fast")) if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
             "rne" if dom_key[2] else "floor"),
         "algorithmic_bytes": dom["bytes"] / dom["launches"],
         "valu_slots_per_mac": dom["ops"], "avg_launch_ms": dom["ms"] / dom["launches"],

@@ -1042,16 +1042,14 @@ __global__ void __launch_bounds__(256, 4) lba_fast_bwd_mixed_kernel(const KParam
 // the accumulator's width.  The mode-dependent operations of a step (product, sum, subtraction) are
 // volatile assembly, which keeps them on their side of the two mode writes; everything else is exact.
 // Writes the plane through p.of_mask.
-template <int PM, int ORDER>
-__global__ void __launch_bounds__(256, 3) lba_fast_diff_kernel(const KParams p) {
-    constexpr int TM = 4, TN = 4, BK = 32, BM = 64, BN = 64;
+template <int TM, int TN, int PM, int ORDER>
+__device__ __forceinline__ void fast_diff_body(const KParams& p, float* smem, const int m0, const int n0) {
+    constexpr int BK = 32, BM = 16 * TM, BN = 16 * TN;
     constexpr int STAGE = BK * (BM + BN);
-    __shared__ __attribute__((aligned(16))) float smem[2 * STAGE];
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
     const int tidb = tid - Stage<BN, BK>::kTailShift;
-    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
     const uint8_t* pA = p.A + (int64_t)blockIdx.z * p.stride_a;
     const uint8_t* pB = p.B + (int64_t)blockIdx.z * p.stride_b;
     float* pC = p.C ? p.C + (int64_t)blockIdx.z * p.stride_c : nullptr;
@@ -1153,24 +1151,47 @@ __global__ void __launch_bounds__(256, 3) lba_fast_diff_kernel(const KParams p) 
     if (pC) {
 #pragma unroll
         for (int i = 0; i < TM; ++i) {
-            const int m = m0 + ty * 4 + i;
+            const int m = m0 + ty * TM + i;
             if (m >= p.M) continue;
-            const int n = n0 + tx * 4;
-            float v[4];
+            const int n = n0 + tx * TN;
+            float v[TN];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < TN; ++j) {
                 const float s = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
                 v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);
             }
             float* dst = pC + (int64_t)m * p.N + n;
-            if (p.c_vec && n + 3 < p.N) {
-                *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[2], v[3]);
+            if (p.c_vec && n + TN - 1 < p.N) {
+                if (TN == 4) *reinterpret_cast<float4*>(dst) = make_float4(v[0], v[1], v[TN - 2], v[TN - 1]);
+                else         *reinterpret_cast<float2*>(dst) = make_float2(v[0], v[1]);
             } else {
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < TN; ++j)
                     if (n + j < p.N) dst[j] = v[j];
             }
         }
+    }
+}
+
+template <int PM, int ORDER>
+__global__ void __launch_bounds__(256, 3) lba_fast_diff_kernel(const KParams p) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
+    fast_diff_body<4, 4, PM, ORDER>(p, smem, blockIdx.x * 64, blockIdx.y * 64);
+}
+
+// The same on the mixed grid of lba_fast_mixed_kernel: 64 x 64 workgroups for the full rounds, 32 x 32 ones on the
+// last rows of the launch.
+template <int PM, int ORDER>
+__global__ void __launch_bounds__(256, 3) lba_fast_diff_mixed_kernel(const KParams p) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
+    const int b = blockIdx.x;
+    if (b < p.mix_main) {                                      // uniform
+        const int by = b / p.mix_gx_main, bx = b - by * p.mix_gx_main;
+        fast_diff_body<4, 4, PM, ORDER>(p, smem, bx * 64, by * 64);
+    } else {
+        const int t = b - p.mix_main;
+        const int by = t / p.mix_gx_tail, bx = t - by * p.mix_gx_tail;
+        fast_diff_body<2, 2, PM, ORDER>(p, smem, p.mix_m_main + bx * 32, by * 32);
     }
 }
 

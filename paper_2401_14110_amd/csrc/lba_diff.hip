@@ -4,8 +4,13 @@
 
 namespace lba {
 hipError_t launch_fast_diff(const Plan& pl, hipStream_t st) {
-    const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
-#define LBA_DIFF(PM, ORDER) hipLaunchKernelGGL((lba_fast_diff_kernel<PM, ORDER>), grid, block, 0, st, pl.kp)
+    const bool mixed = pl.mix_tail > 0;                     // 64 x 64 workgroups, then 32 x 32 ones on the last rows
+    const dim3 grid(pl.grid_x, mixed ? 1 : pl.grid_y, mixed ? 1 : pl.kp.batch), block(256);
+#define LBA_DIFF(PM, ORDER)                                                                                      \
+    do {                                                                                                        \
+        if (mixed) hipLaunchKernelGGL((lba_fast_diff_mixed_kernel<PM, ORDER>), grid, block, 0, st, pl.kp);      \
+        else       hipLaunchKernelGGL((lba_fast_diff_kernel<PM, ORDER>), grid, block, 0, st, pl.kp);            \
+    } while (0)
     if (pl.amode || (pl.prod_mode != PM_FLUSH && pl.prod_mode != PM_FLUSH_CLAMP)) return hipErrorInvalidValue;
     if (pl.order == LBA_ORDER_CHUNK16) {
         if (pl.prod_mode == PM_FLUSH) LBA_DIFF(PM_FLUSH, LBA_ORDER_CHUNK16); else LBA_DIFF(PM_FLUSH_CLAMP, LBA_ORDER_CHUNK16);

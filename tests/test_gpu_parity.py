@@ -601,6 +601,14 @@ def test_mixed_grid(ref):
             _, of2, _ = lb.gemm_bwd(tA, tB, qpf, qaf, want_uf=False, want_c=False)       # the plane alone
             torch.cuda.synchronize()
             assert torch.equal(of, of2)
+            # the DIFF plane on the same grid, both orders
+            for order in (0, 1):
+                assert lb.lba_plan_query(M, N, K, qpf, qaf, order, 2)["tail_blocks"] > 0
+                C, diff = lb.gemm_bwd_diff(tA, tB, qpf, qaf, 0.25, order=order)
+                torch.cuda.synchronize()
+                wc, wd = ref.gemm_diff(A, B, fm(ref, qpf), fm(ref, qaf), 0.25, order=order)
+                assert np.array_equal(bits(C.cpu().numpy()), bits(wc)), (M, N, K, qpf, qaf, order)
+                assert np.array_equal(diff.cpu().numpy().view(np.uint32), wd), (M, N, K, qpf, qaf, order)
 
 
 def test_calls_on_side_streams(ref):
