@@ -19,12 +19,15 @@ hipError_t launch_fast_bwd(const Plan& pl, hipStream_t st) {
 #undef LBA_BWD1
         return hipGetLastError();
     }
-    if (pl.mix_tail > 0) {                                 // overflow plane alone, sequential order: mixed grid
-        if (uf || pl.order != LBA_ORDER_SEQ) return hipErrorInvalidValue;
+    if (pl.mix_tail > 0) {                                 // sequential order: mixed grid
+        if (pl.order != LBA_ORDER_SEQ) return hipErrorInvalidValue;
         const dim3 mgrid(pl.grid_x, 1, 1);
-        if (pl.prod_mode == PM_FLUSH)            hipLaunchKernelGGL((lba_fast_bwd_mixed_kernel<PM_FLUSH>), mgrid, block, 0, st, pl.kp);
-        else if (pl.prod_mode == PM_FLUSH_CLAMP) hipLaunchKernelGGL((lba_fast_bwd_mixed_kernel<PM_FLUSH_CLAMP>), mgrid, block, 0, st, pl.kp);
+#define LBA_BWDM(PM) do { if (uf) hipLaunchKernelGGL((lba_fast_bwd_mixed_kernel<PM, true>), mgrid, block, 0, st, pl.kp); \
+                          else    hipLaunchKernelGGL((lba_fast_bwd_mixed_kernel<PM, false>), mgrid, block, 0, st, pl.kp); } while (0)
+        if (pl.prod_mode == PM_FLUSH)            LBA_BWDM(PM_FLUSH);
+        else if (pl.prod_mode == PM_FLUSH_CLAMP) LBA_BWDM(PM_FLUSH_CLAMP);
         else return hipErrorInvalidValue;
+#undef LBA_BWDM
         return hipGetLastError();
     }
 #define LBA_BWD(PM, ORDER, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, ORDER, UF>), grid, block, 0, st, pl.kp)

@@ -1016,19 +1016,19 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
     fast_bwd_body<4, 4, PM, ORDER, UF, AMODE>(p, smem, blockIdx.x * 64, blockIdx.y * 64);
 }
 
-// The overflow plane alone (sequential order, E4M3 matrices) on the mixed grid of lba_fast_mixed_kernel: 64 x 64
-// workgroups for the full rounds, 32 x 32 ones on the last rows.
-template <int PM>
+// The sequential order on E4M3 matrices on the mixed grid of lba_fast_mixed_kernel: 64 x 64 workgroups for the
+// full rounds, 32 x 32 ones on the last rows.
+template <int PM, bool UF>
 __global__ void __launch_bounds__(256, 4) lba_fast_bwd_mixed_kernel(const KParams p) {
     __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
     const int b = blockIdx.x;
     if (b < p.mix_main) {                                      // uniform
         const int by = b / p.mix_gx_main, bx = b - by * p.mix_gx_main;
-        fast_bwd_body<4, 4, PM, LBA_ORDER_SEQ, false, 0>(p, smem, bx * 64, by * 64);
+        fast_bwd_body<4, 4, PM, LBA_ORDER_SEQ, UF, 0>(p, smem, bx * 64, by * 64);
     } else {
         const int t = b - p.mix_main;
         const int by = t / p.mix_gx_tail, bx = t - by * p.mix_gx_tail;
-        fast_bwd_body<2, 2, PM, LBA_ORDER_SEQ, false, 0>(p, smem, p.mix_m_main + bx * 32, by * 32);
+        fast_bwd_body<2, 2, PM, LBA_ORDER_SEQ, UF, 0>(p, smem, p.mix_m_main + bx * 32, by * 32);
     }
 }
 

@@ -183,9 +183,8 @@ static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int event
 static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
     p->mix_tail = 0;
     if (p->kernel != KERNEL_FAST || p->amode || p->rne_odd || batch != 1) return;
-    // the recompute call has the mixed grid for the overflow plane alone under the sequential order, and for the
-    // DIFF plane
-    if (p->events == 1 && !(p->of_only && p->order == LBA_ORDER_SEQ)) return;
+    // the recompute call has the mixed grid under the sequential order, and for the DIFF plane under both
+    if (p->events == 1 && p->order != LBA_ORDER_SEQ) return;
     if (p->prod_mode != PM_IDENT && p->prod_mode != PM_FLUSH && p->prod_mode != PM_FLUSH_CLAMP) return;
     const int64_t gx = (M + 63) / 64, gy = (N + 63) / 64, blocks = gx * gy;
     if (blocks <= 384 || blocks > 256 * 16) return;

@@ -572,7 +572,7 @@ def test_mixed_grid(ref):
             mixed += plan["tail_blocks"] > 0
             check(ref, A, B, qpf, qaf, "mixed grid", order=order)
     assert mixed >= 36
-    # not used where it cannot help: exact multiples of a round, tiny and huge grids, the recompute call
+    # not used where it cannot help: exact multiples of a round, tiny and huge grids (for the recompute call too)
     assert lb.lba_plan_query(64 * 256, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
     assert lb.lba_plan_query(64 * 40, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
     # up to 384 workgroups of 64 x 64 a CU would run a single wave per SIMD (half rate): finer plain tiles instead
@@ -581,7 +581,7 @@ def test_mixed_grid(ref):
     assert lb.lba_plan_query(64 * 100, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["thread_n"] == 2
     assert lb.lba_plan_query(64 * 12544, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
     assert lb.lba_plan_query(64 * 300, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), 0, 1)["tail_blocks"] == 0
-    # the recompute call has the mixed grid when only the overflow plane is asked for (sequential order): quiet
+    # the recompute call has the mixed grid under the sequential order (both planes, or the overflow plane alone): quiet
     # operands (k-tiles that take the forward tile), loud ones, and a quiet start with a loud end
     for (M, N, K), lo, hi in [((64 * 420 + 17, 60, 100), 3, 8), ((64 * 392, 64, 72), 0, 15), ((64 * 150 + 33, 130, 96), 3, 9)]:
         A = rand_codes(rng, (M, K), lo, hi); B = rand_codes(rng, (N, K), lo, hi)
@@ -592,7 +592,13 @@ def test_mixed_grid(ref):
             qpf, qaf = qp + (0,), qa + (0,)
             plan = lb.lba_plan_query(M, N, K, qpf, qaf, 0, 3)
             assert plan["kernel"] == 0 and plan["tail_blocks"] > 0 and plan["grid_y"] == 1, plan
-            assert lb.lba_plan_query(M, N, K, qpf, qaf, 0, 1)["tail_blocks"] == 0        # both planes: plain grid
+            assert lb.lba_plan_query(M, N, K, qpf, qaf, 0, 1)["tail_blocks"] > 0         # both planes: the same grid
+            assert lb.lba_plan_query(M, N, K, qpf, qaf, 1, 1)["tail_blocks"] == 0        # chunked recompute: plain grid
+            C, of, uf = lb.gemm_bwd(tA, tB, qpf, qaf)
+            torch.cuda.synchronize()
+            wc, wof, wuf = ref.gemm_bwd(A, B, fm(ref, qpf), fm(ref, qaf))
+            assert np.array_equal(bits(C.cpu().numpy()), bits(wc)), (M, N, K, qpf, qaf)
+            assert np.array_equal(of.cpu().numpy().view(np.uint32), wof) and np.array_equal(uf.cpu().numpy().view(np.uint32), wuf)
             C, of, _ = lb.gemm_bwd(tA, tB, qpf, qaf, want_uf=False)
             torch.cuda.synchronize()
             wc, wof, _ = ref.gemm_bwd(A, B, fm(ref, qpf), fm(ref, qaf))
