@@ -196,8 +196,8 @@ size_t lba_mask_words(int64_t M, int64_t N, int64_t K);
  * Arithmetic: FP32 products and FP32 sums.  The order of the summation is unspecified (the sum may be
  * split across workgroups and combined with atomic adds), so results are reproducible up to FP32
  * rounding: |error| <= (terms + 1) * 2^-24 * sum of |terms| to first order.  The identity and the
- * recursive estimator run on the matrix cores when G (and last_of) are 16-byte aligned, A / B 4-byte
- * aligned, N % 4 == 0 and K % 4 == 0 (recursive: K <= 12288): g is split exactly into three bfloat16
+ * recursive estimator run on the matrix cores when G (and last_of) are 16-byte aligned and N % 4 == 0
+ * (recursive: K <= 12288): g is split exactly into three bfloat16
  * pieces whose products with the FP8 values are exact; gradient values below about 2^-100 may lose
  * pieces to the flush of subnormal numbers there.
  */

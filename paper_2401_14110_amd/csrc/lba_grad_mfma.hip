@@ -44,6 +44,7 @@ struct DenseDims {
     int32_t ld_g;              // N: G[m * N + n]
     int32_t b_chunk;           // sliver pass: s values per grid y (a multiple of 256)
     int32_t k_shift;           // log2 of the k tile of the dense pass (the sliver pass cuts k into the same blocks)
+    int32_t v_vec;             // 1: every row of codes starts 4-byte aligned (V % 4 == 0, K % 4 == 0)
 };
 
 // DTK (a template argument): 128 or 256 columns k per workgroup; the wider tile splits G half as often and is
@@ -131,7 +132,18 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
 #pragma unroll
             for (int h = 0; h < DTK / 128; ++h) {
                 const int sv = sb + 4 * b_ps + q, kv = k0 + 128 * h + 4 * b_pk;
-                vl[h][q] = (sv < s_end && kv < d.K) ? *reinterpret_cast<const uint32_t*>(V + (int64_t)sv * d.K + kv) : 0u;
+                uint32_t w = 0u;                               // four codes along k; code 0 (the value +0) beyond K
+                if (sv < s_end && kv < d.K) {
+                    const uint8_t* __restrict__ src = V + (int64_t)sv * d.K + kv;
+                    if (d.v_vec) {                             // rows of codes are 4-byte aligned and K % 4 == 0
+                        w = *reinterpret_cast<const uint32_t*>(src);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (kv + e < d.K) w |= (uint32_t)src[e] << (8 * e);
+                    }
+                }
+                vl[h][q] = w;
             }
         }
     };
@@ -288,10 +300,12 @@ __global__ void lba_grad_dense_zero_kernel(float* x, int64_t n) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += step) x[i] = 0.0f;
 }
 
-// Can the matrix-core path take this product?  16-byte rows of G (and of last_of) in both directions, 4-byte
-// groups of codes; with last_of also a row of K sums within 48 KB of LDS.
+// Can the matrix-core path take this product?  16-byte rows of G (and of last_of) in both directions; with last_of
+// also a row of K sums within 48 KB of LDS.  (Codes are read in 4-byte groups when their rows are aligned, byte by
+// byte otherwise.)
 bool grad_dense_ok(const float* G, const uint8_t* V, const int32_t* last_of, int64_t M, int64_t N, int64_t K) {
-    if (((uintptr_t)G % 16) != 0 || ((uintptr_t)V % 4) != 0 || (N % 4) != 0 || (K % 4) != 0 || (K + 127) / 128 > 65535)
+    (void)V;
+    if (((uintptr_t)G % 16) != 0 || (N % 4) != 0 || (K + 127) / 128 > 65535)
         return false;
     if (last_of && (((uintptr_t)last_of % 16) != 0 || K > 12288)) return false;
     return true;
@@ -304,6 +318,7 @@ int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* las
     DenseDims d;
     d.R = (int32_t)(dx ? M : N); d.S = (int32_t)(dx ? N : M); d.K = (int32_t)K; d.ld_g = (int32_t)N;
     d.b_chunk = d.S;
+    d.v_vec = (((uintptr_t)V % 4) == 0 && (K % 4) == 0) ? 1 : 0;
     const int64_t gx = (d.R + DTR - 1) / DTR;
     const bool wide = gx * ((K + 255) / 256) >= 512;           // 128 x 256 tiles still give two workgroups per CU
     const int dtk = wide ? 256 : 128;
@@ -312,7 +327,7 @@ int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* las
     // enough workgroups for two per CU: cut s into slices of a multiple of 32
     int64_t split = 1;
     const int64_t steps = (d.S + DBS - 1) / DBS;
-    while (gx * gy * split < 512 && split * 2 <= steps && split < 64) split *= 2;
+    while (gx * gy * split < 512 && split * 2 <= steps && split < 512) split *= 2;
     const int64_t per = (steps + split - 1) / split;
     d.s_chunk = (int32_t)(per * DBS);
     split = (d.S + d.s_chunk - 1) / d.s_chunk;

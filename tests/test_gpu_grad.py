@@ -117,7 +117,7 @@ def test_immediate_estimator_with_the_diff_plane(ref, gref):
 
 
 def test_matrix_core_path_identity_and_recursive(ref, gref):
-    # Shapes the dense (matrix-core) path takes (N % 4 == 0, K % 4 == 0): ragged against its 128 x 128 tiles and
+    # Shapes the dense (matrix-core) path takes (N % 4 == 0; K odd: rows of codes read byte by byte): ragged against its 128 x 128 tiles and
     # 32-deep steps, several k blocks, sums split over workgroups.  The recursive estimator gets last-overflow
     # indices written by hand: every position relative to the 128-blocks (first and last k of a block, K - 1,
     # none), so that the masked dense part and the sliver pass must meet exactly.  Bit-exact on data whose
@@ -125,7 +125,7 @@ def test_matrix_core_path_identity_and_recursive(ref, gref):
     rng = np.random.default_rng(314)
     # (7300, 4, 2052): enough row tiles for the 128 x 256 variant of the dense kernel (256-wide k blocks)
     for (M, N, K) in [(130, 68, 260), (260, 132, 132), (64, 516, 640), (3000, 24, 40), (40, 2100, 72), (128, 128, 128),
-                      (257, 36, 1028), (7300, 4, 2052)]:
+                      (257, 36, 1028), (7300, 4, 2052), (1500, 64, 147), (70, 20, 1), (33, 8, 259)]:
         A = codes(rng, (M, K), 5, 10); B = codes(rng, (N, K), 5, 10)
         tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
         last = rng.integers(-1, K, (M, N)).astype(np.int32)
