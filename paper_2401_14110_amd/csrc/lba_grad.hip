@@ -241,6 +241,20 @@ __device__ __forceinline__ void lanes_block(float (&acc)[16], const float (&v)[1
     __builtin_amdgcn_sched_barrier(0);
 }
 
+// The same block with every coefficient 1: plain multiply-adds, in the same order as the masked ones.
+template <bool S_CONTIG, int B>
+__device__ __forceinline__ void plain_block(float (&acc)[16], const float (&v)[16], const float* const (&gp)[16],
+                                            const float (&g)[4][4], float (&g_next)[4][4]) {
+    constexpr int IB = B / 4, UB = B % 4, NB = (B + 1) % 16;
+    if (B < 15) load_g_block<S_CONTIG, NB / 4, NB % 4>(g_next, gp);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[4 * IB + a] = __builtin_fmaf(g[a][b], v[4 * UB + b], acc[4 * IB + a]);
+    __builtin_amdgcn_sched_barrier(0);
+}
+
 // 16 rows x 16 s of the immediate estimator.  The 512 plane words of the step (two slabs) are fetched with
 // two 16-byte vector loads per lane (many in flight: the plane is streamed once and never reused, which
 // the scalar-load path cannot sustain), turned into coefficients, and handed out lane by lane.
@@ -270,6 +284,21 @@ __device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, in
                          : G + ((uint32_t)(s + i) * (uint32_t)d.stride_s + (uint32_t)r0);
     float ga[4][4], gb[4][4];
     load_g_block<S_CONTIG, 0, 0>(ga, gp);
+    // Overflows are rare where the formats fit the data: a step whose 512 words hold no blocked coefficient at all
+    // (lanes beyond K carry the value +0, so their bits do not matter) is a plain product, one multiply-add per 64
+    // terms without the lane-mask traffic
+    const uint32_t every = w[0] & w[1] & w[2] & w[3] & w[4] & w[5] & w[6] & w[7];
+    if (__builtin_amdgcn_ballot_w64(every != 0xFFFFFFFFu) == 0) {                      // uniform
+        plain_block<S_CONTIG, 0>(acc, v, gp, ga, gb);   plain_block<S_CONTIG, 1>(acc, v, gp, gb, ga);
+        plain_block<S_CONTIG, 2>(acc, v, gp, ga, gb);   plain_block<S_CONTIG, 3>(acc, v, gp, gb, ga);
+        plain_block<S_CONTIG, 4>(acc, v, gp, ga, gb);   plain_block<S_CONTIG, 5>(acc, v, gp, gb, ga);
+        plain_block<S_CONTIG, 6>(acc, v, gp, ga, gb);   plain_block<S_CONTIG, 7>(acc, v, gp, gb, ga);
+        plain_block<S_CONTIG, 8>(acc, v, gp, ga, gb);   plain_block<S_CONTIG, 9>(acc, v, gp, gb, ga);
+        plain_block<S_CONTIG, 10>(acc, v, gp, ga, gb);  plain_block<S_CONTIG, 11>(acc, v, gp, gb, ga);
+        plain_block<S_CONTIG, 12>(acc, v, gp, ga, gb);  plain_block<S_CONTIG, 13>(acc, v, gp, gb, ga);
+        plain_block<S_CONTIG, 14>(acc, v, gp, ga, gb);  plain_block<S_CONTIG, 15>(acc, v, gp, gb, ga);
+        return;
+    }
     lanes_block<S_CONTIG, 0>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 1>(acc, v, gp, w, gb, ga);
     lanes_block<S_CONTIG, 2>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 3>(acc, v, gp, w, gb, ga);
     lanes_block<S_CONTIG, 4>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 5>(acc, v, gp, w, gb, ga);

@@ -216,6 +216,45 @@ def pack_plane(c):
     words = (pad.reshape(M, N, W, 32) << np.arange(32, dtype=np.uint64)).sum(axis=3).astype(np.uint32)
     return np.ascontiguousarray(np.moveaxis(words, 2, 0))
 
+def test_immediate_estimator_on_clean_and_nearly_clean_planes(ref, gref):
+    # Steps of the plane (16 rows x 16 s x 64 k) without a blocked coefficient take plain multiply-adds.  OF planes
+    # written by hand: no bit at all, a few scattered bits, a dense corner next to clean steps, and a set bit in the
+    # last word only; K ragged against 64 and 32.  Bit-exact on exactly representable sums, the FP32 bound otherwise.
+    rng = np.random.default_rng(271)
+    for (M, N, K) in [(64, 64, 128), (80, 48, 200), (200, 36, 70), (48, 132, 33)]:
+        A = codes(rng, (M, K), 5, 10); B = codes(rng, (N, K), 5, 10)
+        tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+        for case in range(4):
+            of = np.zeros((M, N, K), dtype=bool)
+            if case == 1:
+                of = rng.random((M, N, K)) < 2e-4
+            elif case == 2:
+                of[16:32, 16:32, :min(K, 64)] = rng.random((16, 16, min(K, 64))) < 0.5
+                of[M - 1, N - 1, K - 1] = True
+            elif case == 3:
+                of[:, :, K - 1] = rng.random((M, N)) < 0.1
+            c = ~of
+            tP = torch.from_numpy(pack_plane(of).view(np.int32)).to(DEV)
+            for exact in (True, False):
+                G = (rng.integers(-8, 9, (M, N)) / 4.0).astype(np.float32) if exact else rng.standard_normal((M, N)).astype(np.float32)
+                tG = torch.from_numpy(G).to(DEV)
+                dX, dW = lb.grad(tG, tA, tB, lb.STE_IMMEDIATE_OF, of_plane=tP)
+                torch.cuda.synchronize()
+                dX, dW = dX.cpu().numpy(), dW.cpu().numpy()
+                wX, wW = gref.grad(G, A, B, None, None, lb.STE_IMMEDIATE_OF, c=c)
+                if exact:
+                    assert np.array_equal(dX, wX.astype(np.float32)), (M, N, K, case, "dX")
+                    assert np.array_equal(dW, wW.astype(np.float32)), (M, N, K, case, "dW")
+                else:
+                    aX, aW = gref.grad_abs(G, A, B, None, None, lb.STE_IMMEDIATE_OF, c=c)
+                    assert (np.abs(dX - wX) <= 2 * (N + 1) * 2.0 ** -24 * aX + 1e-30).all(), (M, N, K, case, "dX")
+                    assert (np.abs(dW - wW) <= 2 * (M + 1) * 2.0 ** -24 * aW + 1e-30).all(), (M, N, K, case, "dW")
+                # the coefficient plane itself (bits taken as they are) gives the same products
+                cX, cW = lb.grad(tG, tA, tB, lb.STE_COEF_PLANE, of_plane=torch.from_numpy(pack_plane(c).view(np.int32)).to(DEV))
+                torch.cuda.synchronize()
+                if exact:
+                    assert np.array_equal(cX.cpu().numpy(), dX) and np.array_equal(cW.cpu().numpy(), dW), (M, N, K, case)
+
 
 def test_coefficient_planes_and_the_recursive_estimator_of_the_chunked_order(ref, gref):
     rng = np.random.default_rng(97)
