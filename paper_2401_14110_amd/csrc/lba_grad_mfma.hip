@@ -239,17 +239,19 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
 // L = L(r, s) >= 0 the terms g(r, s) * value(V[s, k]) for L < k < end of L's k block.  One workgroup per ROWS rows r
 // keeps their K sums each in LDS; a wave takes 64 consecutive s at a time (their L and g in its lanes), then
 // one pair after the other with its lanes along k.  out[r, :] += sums (the dense part is already there).
-// ROWS = 2 (rows contiguous in memory, dW): a lane fetches the two rows' values with one 8-byte load, which
-// halves the sectors touched by the strided walk over s.
+// ROWS = 2 or 16 (rows contiguous in memory, dW): a lane fetches its rows' values with 8- or 16-byte loads; the walk
+// over s is strided by a whole row of G, so with 16 rows (64 bytes per s) every sector fetched is used in full,
+// with 2 an eighth of it.  16 rows where their sums fit in LDS (K <= 768).
 template <bool S_CONTIG, int ROWS>
 __global__ void __launch_bounds__(256) lba_grad_boundary_kernel(const float* __restrict__ G, const uint8_t* __restrict__ V,
-                                                                const int32_t* __restrict__ L,
-                                                                float* __restrict__ out, const DenseDims d) {
-    static_assert(ROWS == 1 || (ROWS == 2 && !S_CONTIG), "two rows only where rows are contiguous");
+                                                                const int32_t* __restrict__ L, float* __restrict__ out,
+                                                                const DenseDims d) {
+    static_assert(ROWS == 1 || ((ROWS == 2 || ROWS == 16) && !S_CONTIG), "several rows only where rows are contiguous");
     extern __shared__ float row[];                             // ROWS x K sums
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = blockIdx.x * ROWS;
-    for (int k = tid; k < ROWS * d.K; k += 256) row[k] = 0.0f;
+    const int nrows = min(ROWS, d.R - r);                      // R % 4 == 0: 16-row groups end on a multiple of 4
+    for (int k = tid; k < nrows * d.K; k += 256) row[k] = 0.0f;
     __syncthreads();
     // grid y cuts s into slices of b_chunk (a multiple of 256) when there are few rows
     const int s_lo = blockIdx.y * d.b_chunk, s_hi = min(d.S, s_lo + d.b_chunk);
@@ -261,7 +263,17 @@ __global__ void __launch_bounds__(256) lba_grad_boundary_kernel(const float* __r
         for (int i = 0; i < ROWS; ++i) { lv[i] = -1; gv[i] = 0.0f; }
         if (s < s_hi) {
             const int64_t off = S_CONTIG ? (int64_t)r * d.ld_g + s : (int64_t)s * d.ld_g + r;
-            if (ROWS == 2) {                                   // r even and ld_g % 4 == 0: 8-byte aligned; R % 4 == 0: both rows exist
+            if constexpr (ROWS == 16) {                        // r % 16 == 0 and ld_g % 4 == 0: 16-byte aligned groups of 4 rows
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (4 * q < nrows) {                       // uniform; a group of 4 rows exists as a whole
+                        const int4 l4 = *reinterpret_cast<const int4*>(L + off + 4 * q);
+                        const float4 g4 = *reinterpret_cast<const float4*>(G + off + 4 * q);
+                        lv[4 * q] = l4.x; lv[4 * q + 1] = l4.y; lv[4 * q + 2] = l4.z; lv[4 * q + 3] = l4.w;
+                        gv[4 * q] = g4.x; gv[4 * q + 1] = g4.y; gv[4 * q + 2] = g4.z; gv[4 * q + 3] = g4.w;
+                    }
+                }
+            } else if constexpr (ROWS == 2) {                  // r even and ld_g % 4 == 0: 8-byte aligned; R % 4 == 0: both rows exist
                 const int2 l2 = *reinterpret_cast<const int2*>(L + off);
                 const float2 g2 = *reinterpret_cast<const float2*>(G + off);
                 lv[0] = l2.x; lv[ROWS - 1] = l2.y; gv[0] = g2.x; gv[ROWS - 1] = g2.y;
@@ -286,7 +298,7 @@ __global__ void __launch_bounds__(256) lba_grad_boundary_kernel(const float* __r
         }
     }
     __syncthreads();
-    for (int k = tid; k < ROWS * d.K; k += 256) {
+    for (int k = tid; k < nrows * d.K; k += 256) {
         const float x = row[k];
         if (x != 0.0f) {                                       // row[i * K + k'] belongs to out[(r + i) * K + k']: the same offset from out + r * K
             if (gridDim.y > 1) unsafeAtomicAdd(out + (int64_t)r * d.K + k, x);
@@ -347,21 +359,22 @@ int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* las
     if (dx) LBA_DENSE(true, true); else LBA_DENSE(false, true);
 #undef LBA_DENSE
     if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
-    // the sliver pass: one workgroup per row, and with few rows also slices of s, to have about 1024 workgroups
-    int64_t slices = d.R >= 2048 ? 1 : (2048 + d.R - 1) / d.R;
+    // the sliver pass: one workgroup per group of rows, and with few groups also slices of s, to have about 2048
+    // workgroups
+    const size_t lds = (size_t)K * sizeof(float);
+    const int rows = dx ? 1 : (16 * lds <= 49152 ? 16 : (2 * lds <= 49152 ? 2 : 1));   // dW: R = N is a multiple of 4
+    const int64_t rgroups = (d.R + rows - 1) / rows;
+    int64_t slices = rgroups >= 2048 ? 1 : (2048 + rgroups - 1) / rgroups;
     const int64_t groups = (d.S + 255) / 256;
     if (slices > groups) slices = groups;
     if (slices > 65535) slices = 65535;
     d.b_chunk = (int32_t)(((groups + slices - 1) / slices) * 256);
     slices = (d.S + d.b_chunk - 1) / d.b_chunk;
-    const size_t lds = (size_t)K * sizeof(float);
-    if (dx) {
-        hipLaunchKernelGGL((lba_grad_boundary_kernel<true, 1>), dim3((unsigned)d.R, (unsigned)slices), dim3(256), lds, st, G, V, last_of, out, d);
-    } else if (2 * lds <= 49152) {                             // dW: R = N is a multiple of 4, rows come in pairs
-        hipLaunchKernelGGL((lba_grad_boundary_kernel<false, 2>), dim3((unsigned)(d.R / 2), (unsigned)slices), dim3(256), 2 * lds, st, G, V, last_of, out, d);
-    } else {
-        hipLaunchKernelGGL((lba_grad_boundary_kernel<false, 1>), dim3((unsigned)d.R, (unsigned)slices), dim3(256), lds, st, G, V, last_of, out, d);
-    }
+    const dim3 bgrid((unsigned)rgroups, (unsigned)slices);
+    if (dx)              hipLaunchKernelGGL((lba_grad_boundary_kernel<true, 1>), bgrid, dim3(256), lds, st, G, V, last_of, out, d);
+    else if (rows == 16) hipLaunchKernelGGL((lba_grad_boundary_kernel<false, 16>), bgrid, dim3(256), 16 * lds, st, G, V, last_of, out, d);
+    else if (rows == 2)  hipLaunchKernelGGL((lba_grad_boundary_kernel<false, 2>), bgrid, dim3(256), 2 * lds, st, G, V, last_of, out, d);
+    else                 hipLaunchKernelGGL((lba_grad_boundary_kernel<false, 1>), bgrid, dim3(256), lds, st, G, V, last_of, out, d);
     return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
 }
 
