@@ -239,14 +239,15 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
 // L = L(r, s) >= 0 the terms g(r, s) * value(V[s, k]) for L < k < end of L's k block.  One workgroup per ROWS rows r
 // keeps their K sums each in LDS; a wave takes 64 consecutive s at a time (their L and g in its lanes), then
 // one pair after the other with its lanes along k.  out[r, :] += sums (the dense part is already there).
-// ROWS = 2 or 16 (rows contiguous in memory, dW): a lane fetches its rows' values with 8- or 16-byte loads; the walk
-// over s is strided by a whole row of G, so with 16 rows (64 bytes per s) every sector fetched is used in full,
-// with 2 an eighth of it.  16 rows where their sums fit in LDS (K <= 768).
+// ROWS = 2, 4, 8 or 16 (rows contiguous in memory, dW): a lane fetches its rows' values with 8- or 16-byte loads; the
+// walk over s is strided by a whole row of G, so with 16 rows (64 bytes per s) every sector fetched is used in full,
+// with 2 an eighth of it.  The launcher takes as many rows as have their sums in 48 KB of LDS (16 up to K = 768).
 template <bool S_CONTIG, int ROWS>
 __global__ void __launch_bounds__(256) lba_grad_boundary_kernel(const float* __restrict__ G, const uint8_t* __restrict__ V,
                                                                 const int32_t* __restrict__ L, float* __restrict__ out,
                                                                 const DenseDims d) {
-    static_assert(ROWS == 1 || ((ROWS == 2 || ROWS == 16) && !S_CONTIG), "several rows only where rows are contiguous");
+    static_assert(ROWS == 1 || ((ROWS == 2 || ROWS == 4 || ROWS == 8 || ROWS == 16) && !S_CONTIG),
+                  "several rows only where rows are contiguous");
     extern __shared__ float row[];                             // ROWS x K sums
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int r = blockIdx.x * ROWS;
@@ -263,9 +264,9 @@ __global__ void __launch_bounds__(256) lba_grad_boundary_kernel(const float* __r
         for (int i = 0; i < ROWS; ++i) { lv[i] = -1; gv[i] = 0.0f; }
         if (s < s_hi) {
             const int64_t off = S_CONTIG ? (int64_t)r * d.ld_g + s : (int64_t)s * d.ld_g + r;
-            if constexpr (ROWS == 16) {                        // r % 16 == 0 and ld_g % 4 == 0: 16-byte aligned groups of 4 rows
+            if constexpr (ROWS >= 4) {                         // r % 4 == 0 and ld_g % 4 == 0: 16-byte aligned groups of 4 rows
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
+                for (int q = 0; q < ROWS / 4; ++q) {
                     if (4 * q < nrows) {                       // uniform; a group of 4 rows exists as a whole
                         const int4 l4 = *reinterpret_cast<const int4*>(L + off + 4 * q);
                         const float4 g4 = *reinterpret_cast<const float4*>(G + off + 4 * q);
@@ -362,7 +363,8 @@ int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* las
     // the sliver pass: one workgroup per group of rows, and with few groups also slices of s, to have about 2048
     // workgroups
     const size_t lds = (size_t)K * sizeof(float);
-    const int rows = dx ? 1 : (16 * lds <= 49152 ? 16 : (2 * lds <= 49152 ? 2 : 1));   // dW: R = N is a multiple of 4
+    int rows = 1;                                              // dW: R = N is a multiple of 4
+    if (!dx) for (rows = 16; rows > 1 && (size_t)rows * lds > 49152; rows /= 2) {}
     const int64_t rgroups = (d.R + rows - 1) / rows;
     int64_t slices = rgroups >= 2048 ? 1 : (2048 + rgroups - 1) / rgroups;
     const int64_t groups = (d.S + 255) / 256;
@@ -373,6 +375,8 @@ int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* las
     const dim3 bgrid((unsigned)rgroups, (unsigned)slices);
     if (dx)              hipLaunchKernelGGL((lba_grad_boundary_kernel<true, 1>), bgrid, dim3(256), lds, st, G, V, last_of, out, d);
     else if (rows == 16) hipLaunchKernelGGL((lba_grad_boundary_kernel<false, 16>), bgrid, dim3(256), 16 * lds, st, G, V, last_of, out, d);
+    else if (rows == 8)  hipLaunchKernelGGL((lba_grad_boundary_kernel<false, 8>), bgrid, dim3(256), 8 * lds, st, G, V, last_of, out, d);
+    else if (rows == 4)  hipLaunchKernelGGL((lba_grad_boundary_kernel<false, 4>), bgrid, dim3(256), 4 * lds, st, G, V, last_of, out, d);
     else if (rows == 2)  hipLaunchKernelGGL((lba_grad_boundary_kernel<false, 2>), bgrid, dim3(256), 2 * lds, st, G, V, last_of, out, d);
     else                 hipLaunchKernelGGL((lba_grad_boundary_kernel<false, 1>), bgrid, dim3(256), lds, st, G, V, last_of, out, d);
     return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
