@@ -187,7 +187,7 @@ __device__ __forceinline__ void masked_fmac4_lanes(float& acc, uint32_t w0, uint
         : [w0] "v"(w0), [w1] "v"(w1), [w2] "v"(w2), [w3] "v"(w3),
           [a0] "n"(L0), [b0] "n"(L0 + 32), [a1] "n"(L1), [b1] "n"(L1 + 32),
           [a2] "n"(L2), [b2] "n"(L2 + 32), [a3] "n"(L3), [b3] "n"(L3 + 32),
-          [g0] "s"(g[0]), [g1] "s"(g[1]), [g2] "s"(g[2]), [g3] "s"(g[3]),
+          [g0] "v"(g[0]), [g1] "v"(g[1]), [g2] "v"(g[2]), [g3] "v"(g[3]),
           [v0] "v"(v[0]), [v1] "v"(v[1]), [v2] "v"(v[2]), [v3] "v"(v[3])
         : "s94", "s95");
 }
@@ -207,51 +207,67 @@ __device__ __forceinline__ void lanes_row(float& acc, const uint32_t (&w)[8], co
     }
 }
 
-// gp[i]: where the 16 contiguous scalars g of line i of the super-step start (a row r0 + i when g is contiguous
-// along s, a column s + i when it is contiguous along r); block (IB, UB) takes four 16-byte scalar loads at
-// constant offsets from four of them (computing each address from r, s and the strides cost four scalar
-// instructions per load).
-// The 4 x 4 scalars g of block (IB, UB): four 16-byte scalar loads at constant offsets from four of the lines.
+// The 16 x 16 values g of a super-step reach the multiply-adds through LDS: the wave loads the tile with one 16-byte
+// vector load per lane, a whole super-step ahead, and stores it in its own 1 KB of LDS (line p = lane / 4 holds 16
+// values that are contiguous in memory: a row r0 + p when g is contiguous along s, a column s + p otherwise).  Block
+// (IB, UB) then reads its 4 x 4 values with four 16-byte LDS reads in which every lane reads the same address (a
+// broadcast): the value sits in a vector register of every lane, whatever the execution mask does afterwards.
+// (Scalar loads delivered g before: each fed one instruction and was requested one block ahead, and their latency,
+// sixteen times per super-step, was what bounded the kernel.)
+template <bool S_CONTIG>
+__device__ __forceinline__ float4 fetch_g_tile(const float* __restrict__ G, int r0, int s, int lane, const GradDims& d) {
+    const int p = lane >> 2, c4 = (lane & 3) * 4;
+    const uint32_t off = S_CONTIG ? (uint32_t)(r0 + p) * (uint32_t)d.stride_r + (uint32_t)(s + c4)
+                                  : (uint32_t)(s + p) * (uint32_t)d.stride_s + (uint32_t)(r0 + c4);
+    return *reinterpret_cast<const float4*>(G + off);
+}
+
+__device__ __forceinline__ void store_g_tile(float* tile, float4 g4, int lane) {
+    *reinterpret_cast<float4*>(tile + (lane >> 2) * 16 + (lane & 3) * 4) = g4;
+}
+
 template <bool S_CONTIG, int IB, int UB>
-__device__ __forceinline__ void load_g_block(float (&g)[4][4], const float* const (&gp)[16]) {
+__device__ __forceinline__ void load_g_block(float (&g)[4][4], const float* tile) {
 #pragma unroll
     for (int a = 0; a < 4; ++a) {
-        const float4 gv = S_CONTIG ? *reinterpret_cast<const float4*>(gp[4 * IB + a] + 4 * UB)
-                                   : *reinterpret_cast<const float4*>(gp[4 * UB + a] + 4 * IB);
+        const float4 gv = S_CONTIG ? *reinterpret_cast<const float4*>(tile + (4 * IB + a) * 16 + 4 * UB)
+                                   : *reinterpret_cast<const float4*>(tile + (4 * UB + a) * 16 + 4 * IB);
         const float ga[4] = {gv.x, gv.y, gv.z, gv.w};
 #pragma unroll
         for (int b = 0; b < 4; ++b) g[S_CONTIG ? a : b][S_CONTIG ? b : a] = ga[b];
     }
 }
 
-// Block B = 4 * IB + UB of the 16 blocks of a super-step.  The scalars of block B + 1 are requested before block
-// B runs on the ones requested one block earlier (the scheduling barriers pin that order: left alone, the loads
-// sit right in front of their first use and every block waits for memory).
+// Block B = 4 * IB + UB of the 16 blocks of a super-step.  The values of block B + 1 are read from LDS before block
+// B runs on the ones read one block earlier (the scheduling barriers pin that order: left alone, the reads
+// sit right in front of their first use and every block waits for them).
+// Overflows are rare where the formats fit the data: a block whose 16 word pairs hold no blocked coefficient (lanes
+// beyond K carry the value +0, so their bits do not matter) takes plain multiply-adds, one instruction per 64 terms
+// without the lane-mask traffic, in the same order.  dirty_lo / dirty_hi: the lanes whose words in w[0..3] / w[4..7]
+// are not all ones; the block's words sit in eight fixed lanes of one of the two register groups.
 template <bool S_CONTIG, int B>
-__device__ __forceinline__ void lanes_block(float (&acc)[16], const float (&v)[16], const float* const (&gp)[16],
-                                            const uint32_t (&w)[8], const float (&g)[4][4], float (&g_next)[4][4]) {
-    constexpr int IB = B / 4, UB = B % 4, NB = (B + 1) % 16;
-    if (B < 15) load_g_block<S_CONTIG, NB / 4, NB % 4>(g_next, gp);
-    __builtin_amdgcn_sched_barrier(0);
-    const float vv[4] = {v[4 * UB + 0], v[4 * UB + 1], v[4 * UB + 2], v[4 * UB + 3]};
-    lanes_row<S_CONTIG, 4 * IB + 0, UB>(acc[4 * IB + 0], w, g[0], vv);
-    lanes_row<S_CONTIG, 4 * IB + 1, UB>(acc[4 * IB + 1], w, g[1], vv);
-    lanes_row<S_CONTIG, 4 * IB + 2, UB>(acc[4 * IB + 2], w, g[2], vv);
-    lanes_row<S_CONTIG, 4 * IB + 3, UB>(acc[4 * IB + 3], w, g[3], vv);
-    __builtin_amdgcn_sched_barrier(0);
-}
-
-// The same block with every coefficient 1: plain multiply-adds, in the same order as the masked ones.
-template <bool S_CONTIG, int B>
-__device__ __forceinline__ void plain_block(float (&acc)[16], const float (&v)[16], const float* const (&gp)[16],
+__device__ __forceinline__ void lanes_block(float (&acc)[16], const float (&v)[16], const float* tile,
+                                            const uint32_t (&w)[8], uint64_t dirty_lo, uint64_t dirty_hi,
                                             const float (&g)[4][4], float (&g_next)[4][4]) {
     constexpr int IB = B / 4, UB = B % 4, NB = (B + 1) % 16;
-    if (B < 15) load_g_block<S_CONTIG, NB / 4, NB % 4>(g_next, gp);
+    // word (i, u) of slab h: lane h*32 + a*2 + (b >> 3), register w[b & 7], (a, b) = (i, u) or (u, i) (see lanes_row)
+    constexpr int AB = S_CONTIG ? IB : UB, BB = S_CONTIG ? UB : IB;            // block index along a and along b
+    constexpr uint64_t lanes32 = (uint64_t)0x55u << (8 * AB + (BB >> 1));     // a = 4 AB .. 4 AB + 3, lane a*2 + (BB >> 1)
+    constexpr uint64_t lanes = lanes32 | (lanes32 << 32);
+    if (B < 15) load_g_block<S_CONTIG, NB / 4, NB % 4>(g_next, tile);
     __builtin_amdgcn_sched_barrier(0);
+    if ((((BB & 1) ? dirty_hi : dirty_lo) & lanes) == 0) {     // uniform
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+        for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) acc[4 * IB + a] = __builtin_fmaf(g[a][b], v[4 * UB + b], acc[4 * IB + a]);
+            for (int b = 0; b < 4; ++b) acc[4 * IB + a] = __builtin_fmaf(g[a][b], v[4 * UB + b], acc[4 * IB + a]);
+    } else {
+        const float vv[4] = {v[4 * UB + 0], v[4 * UB + 1], v[4 * UB + 2], v[4 * UB + 3]};
+        lanes_row<S_CONTIG, 4 * IB + 0, UB>(acc[4 * IB + 0], w, g[0], vv);
+        lanes_row<S_CONTIG, 4 * IB + 1, UB>(acc[4 * IB + 1], w, g[1], vv);
+        lanes_row<S_CONTIG, 4 * IB + 2, UB>(acc[4 * IB + 2], w, g[2], vv);
+        lanes_row<S_CONTIG, 4 * IB + 3, UB>(acc[4 * IB + 3], w, g[3], vv);
+    }
     __builtin_amdgcn_sched_barrier(0);
 }
 
@@ -260,7 +276,7 @@ __device__ __forceinline__ void plain_block(float (&acc)[16], const float (&v)[1
 // the scalar-load path cannot sustain), turned into coefficients, and handed out lane by lane.
 template <bool S_CONTIG>
 __device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, int s, int k, int lane,
-                                                    const uint8_t* __restrict__ V, const float* __restrict__ G,
+                                                    const uint8_t* __restrict__ V, const float* tile,
                                                     const uint32_t* __restrict__ P0, const uint32_t* __restrict__ P1,
                                                     const GradDims& d) {
     const int q = lane & 31, a = q >> 1, half8 = (q & 1) * 8;
@@ -277,36 +293,18 @@ __device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, in
         const uint32_t code = (k < d.K) ? V[(int64_t)(s + u) * d.K + k] : 0u;
         v[u] = decode_e4m3(code);
     }
-    const float* gp[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i)
-        gp[i] = S_CONTIG ? G + ((uint32_t)(r0 + i) * (uint32_t)d.stride_r + (uint32_t)s)
-                         : G + ((uint32_t)(s + i) * (uint32_t)d.stride_s + (uint32_t)r0);
     float ga[4][4], gb[4][4];
-    load_g_block<S_CONTIG, 0, 0>(ga, gp);
-    // Overflows are rare where the formats fit the data: a step whose 512 words hold no blocked coefficient at all
-    // (lanes beyond K carry the value +0, so their bits do not matter) is a plain product, one multiply-add per 64
-    // terms without the lane-mask traffic
-    const uint32_t every = w[0] & w[1] & w[2] & w[3] & w[4] & w[5] & w[6] & w[7];
-    if (__builtin_amdgcn_ballot_w64(every != 0xFFFFFFFFu) == 0) {                      // uniform
-        plain_block<S_CONTIG, 0>(acc, v, gp, ga, gb);   plain_block<S_CONTIG, 1>(acc, v, gp, gb, ga);
-        plain_block<S_CONTIG, 2>(acc, v, gp, ga, gb);   plain_block<S_CONTIG, 3>(acc, v, gp, gb, ga);
-        plain_block<S_CONTIG, 4>(acc, v, gp, ga, gb);   plain_block<S_CONTIG, 5>(acc, v, gp, gb, ga);
-        plain_block<S_CONTIG, 6>(acc, v, gp, ga, gb);   plain_block<S_CONTIG, 7>(acc, v, gp, gb, ga);
-        plain_block<S_CONTIG, 8>(acc, v, gp, ga, gb);   plain_block<S_CONTIG, 9>(acc, v, gp, gb, ga);
-        plain_block<S_CONTIG, 10>(acc, v, gp, ga, gb);  plain_block<S_CONTIG, 11>(acc, v, gp, gb, ga);
-        plain_block<S_CONTIG, 12>(acc, v, gp, ga, gb);  plain_block<S_CONTIG, 13>(acc, v, gp, gb, ga);
-        plain_block<S_CONTIG, 14>(acc, v, gp, ga, gb);  plain_block<S_CONTIG, 15>(acc, v, gp, gb, ga);
-        return;
-    }
-    lanes_block<S_CONTIG, 0>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 1>(acc, v, gp, w, gb, ga);
-    lanes_block<S_CONTIG, 2>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 3>(acc, v, gp, w, gb, ga);
-    lanes_block<S_CONTIG, 4>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 5>(acc, v, gp, w, gb, ga);
-    lanes_block<S_CONTIG, 6>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 7>(acc, v, gp, w, gb, ga);
-    lanes_block<S_CONTIG, 8>(acc, v, gp, w, ga, gb);   lanes_block<S_CONTIG, 9>(acc, v, gp, w, gb, ga);
-    lanes_block<S_CONTIG, 10>(acc, v, gp, w, ga, gb);  lanes_block<S_CONTIG, 11>(acc, v, gp, w, gb, ga);
-    lanes_block<S_CONTIG, 12>(acc, v, gp, w, ga, gb);  lanes_block<S_CONTIG, 13>(acc, v, gp, w, gb, ga);
-    lanes_block<S_CONTIG, 14>(acc, v, gp, w, ga, gb);  lanes_block<S_CONTIG, 15>(acc, v, gp, w, gb, ga);
+    load_g_block<S_CONTIG, 0, 0>(ga, tile);
+    const uint64_t dlo = __builtin_amdgcn_ballot_w64((w[0] & w[1] & w[2] & w[3]) != 0xFFFFFFFFu);
+    const uint64_t dhi = __builtin_amdgcn_ballot_w64((w[4] & w[5] & w[6] & w[7]) != 0xFFFFFFFFu);
+    lanes_block<S_CONTIG, 0>(acc, v, tile, w, dlo, dhi, ga, gb);   lanes_block<S_CONTIG, 1>(acc, v, tile, w, dlo, dhi, gb, ga);
+    lanes_block<S_CONTIG, 2>(acc, v, tile, w, dlo, dhi, ga, gb);   lanes_block<S_CONTIG, 3>(acc, v, tile, w, dlo, dhi, gb, ga);
+    lanes_block<S_CONTIG, 4>(acc, v, tile, w, dlo, dhi, ga, gb);   lanes_block<S_CONTIG, 5>(acc, v, tile, w, dlo, dhi, gb, ga);
+    lanes_block<S_CONTIG, 6>(acc, v, tile, w, dlo, dhi, ga, gb);   lanes_block<S_CONTIG, 7>(acc, v, tile, w, dlo, dhi, gb, ga);
+    lanes_block<S_CONTIG, 8>(acc, v, tile, w, dlo, dhi, ga, gb);   lanes_block<S_CONTIG, 9>(acc, v, tile, w, dlo, dhi, gb, ga);
+    lanes_block<S_CONTIG, 10>(acc, v, tile, w, dlo, dhi, ga, gb);  lanes_block<S_CONTIG, 11>(acc, v, tile, w, dlo, dhi, gb, ga);
+    lanes_block<S_CONTIG, 12>(acc, v, tile, w, dlo, dhi, ga, gb);  lanes_block<S_CONTIG, 13>(acc, v, tile, w, dlo, dhi, gb, ga);
+    lanes_block<S_CONTIG, 14>(acc, v, tile, w, dlo, dhi, ga, gb);  lanes_block<S_CONTIG, 15>(acc, v, tile, w, dlo, dhi, gb, ga);
 }
 
 template <int MODE, bool S_CONTIG>
@@ -332,8 +330,19 @@ __global__ void __launch_bounds__(256) lba_grad_kernel(const float* __restrict__
     for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
 
     int s = s_begin;
-    if (MODE == LBA_STE_IMMEDIATE_OF && rows_fast) {
-        for (; s + 16 <= s_end; s += 16) immediate_superstep<S_CONTIG>(acc, r0, s, k, lane, V, G, P0, P1, d);
+    if (MODE == LBA_STE_IMMEDIATE_OF && rows_fast && s + 16 <= s_end) {
+        __shared__ __attribute__((aligned(16))) float gtiles[4][256];      // one 16 x 16 tile of g per wave
+        float* tile = gtiles[wave];
+        float4 g4 = fetch_g_tile<S_CONTIG>(G, r0, s, lane, d);
+        for (; s + 16 <= s_end; s += 16) {
+            // LDS operations of a wave complete in order: the tile is overwritten after the last reads of the step
+            // before, and read after it is written; the wave barriers keep the compiler from moving them
+            __builtin_amdgcn_wave_barrier();
+            store_g_tile(tile, g4, lane);
+            __builtin_amdgcn_wave_barrier();
+            if (s + 32 <= s_end) g4 = fetch_g_tile<S_CONTIG>(G, r0, s + 16, lane, d);   // a whole step ahead
+            immediate_superstep<S_CONTIG>(acc, r0, s, k, lane, V, tile, P0, P1, d);
+        }
     }
     for (; s < s_end; s += 4) {
         float v[4];
