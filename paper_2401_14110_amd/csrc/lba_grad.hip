@@ -238,23 +238,22 @@ __device__ __forceinline__ void load_g_block(float (&g)[4][4], const float* tile
     }
 }
 
-// Block B = 4 * IB + UB of the 16 blocks of a super-step.  The values of block B + 1 are read from LDS before block
-// B runs on the ones read one block earlier (the scheduling barriers pin that order: left alone, the reads
-// sit right in front of their first use and every block waits for them).
+// Block B = 4 * IB + UB of the 16 blocks of a super-step: reads its 4 x 4 values g from LDS (the other waves of the
+// SIMD cover that latency: reading a block ahead cost 20 registers and a wave per SIMD, and measured slower) and runs.
 // Overflows are rare where the formats fit the data: a block whose 16 word pairs hold no blocked coefficient (lanes
 // beyond K carry the value +0, so their bits do not matter) takes plain multiply-adds, one instruction per 64 terms
 // without the lane-mask traffic, in the same order.  dirty_lo / dirty_hi: the lanes whose words in w[0..3] / w[4..7]
 // are not all ones; the block's words sit in eight fixed lanes of one of the two register groups.
 template <bool S_CONTIG, int B>
 __device__ __forceinline__ void lanes_block(float (&acc)[16], const float (&v)[16], const float* tile,
-                                            const uint32_t (&w)[8], uint64_t dirty_lo, uint64_t dirty_hi,
-                                            const float (&g)[4][4], float (&g_next)[4][4]) {
-    constexpr int IB = B / 4, UB = B % 4, NB = (B + 1) % 16;
+                                            const uint32_t (&w)[8], uint64_t dirty_lo, uint64_t dirty_hi) {
+    constexpr int IB = B / 4, UB = B % 4;
     // word (i, u) of slab h: lane h*32 + a*2 + (b >> 3), register w[b & 7], (a, b) = (i, u) or (u, i) (see lanes_row)
     constexpr int AB = S_CONTIG ? IB : UB, BB = S_CONTIG ? UB : IB;            // block index along a and along b
     constexpr uint64_t lanes32 = (uint64_t)0x55u << (8 * AB + (BB >> 1));     // a = 4 AB .. 4 AB + 3, lane a*2 + (BB >> 1)
     constexpr uint64_t lanes = lanes32 | (lanes32 << 32);
-    if (B < 15) load_g_block<S_CONTIG, NB / 4, NB % 4>(g_next, tile);
+    float g[4][4];
+    load_g_block<S_CONTIG, IB, UB>(g, tile);
     __builtin_amdgcn_sched_barrier(0);
     if ((((BB & 1) ? dirty_hi : dirty_lo) & lanes) == 0) {     // uniform
 #pragma unroll
@@ -293,18 +292,16 @@ __device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, in
         const uint32_t code = (k < d.K) ? V[(int64_t)(s + u) * d.K + k] : 0u;
         v[u] = decode_e4m3(code);
     }
-    float ga[4][4], gb[4][4];
-    load_g_block<S_CONTIG, 0, 0>(ga, tile);
     const uint64_t dlo = __builtin_amdgcn_ballot_w64((w[0] & w[1] & w[2] & w[3]) != 0xFFFFFFFFu);
     const uint64_t dhi = __builtin_amdgcn_ballot_w64((w[4] & w[5] & w[6] & w[7]) != 0xFFFFFFFFu);
-    lanes_block<S_CONTIG, 0>(acc, v, tile, w, dlo, dhi, ga, gb);   lanes_block<S_CONTIG, 1>(acc, v, tile, w, dlo, dhi, gb, ga);
-    lanes_block<S_CONTIG, 2>(acc, v, tile, w, dlo, dhi, ga, gb);   lanes_block<S_CONTIG, 3>(acc, v, tile, w, dlo, dhi, gb, ga);
-    lanes_block<S_CONTIG, 4>(acc, v, tile, w, dlo, dhi, ga, gb);   lanes_block<S_CONTIG, 5>(acc, v, tile, w, dlo, dhi, gb, ga);
-    lanes_block<S_CONTIG, 6>(acc, v, tile, w, dlo, dhi, ga, gb);   lanes_block<S_CONTIG, 7>(acc, v, tile, w, dlo, dhi, gb, ga);
-    lanes_block<S_CONTIG, 8>(acc, v, tile, w, dlo, dhi, ga, gb);   lanes_block<S_CONTIG, 9>(acc, v, tile, w, dlo, dhi, gb, ga);
-    lanes_block<S_CONTIG, 10>(acc, v, tile, w, dlo, dhi, ga, gb);  lanes_block<S_CONTIG, 11>(acc, v, tile, w, dlo, dhi, gb, ga);
-    lanes_block<S_CONTIG, 12>(acc, v, tile, w, dlo, dhi, ga, gb);  lanes_block<S_CONTIG, 13>(acc, v, tile, w, dlo, dhi, gb, ga);
-    lanes_block<S_CONTIG, 14>(acc, v, tile, w, dlo, dhi, ga, gb);  lanes_block<S_CONTIG, 15>(acc, v, tile, w, dlo, dhi, gb, ga);
+    lanes_block<S_CONTIG, 0>(acc, v, tile, w, dlo, dhi);   lanes_block<S_CONTIG, 1>(acc, v, tile, w, dlo, dhi);
+    lanes_block<S_CONTIG, 2>(acc, v, tile, w, dlo, dhi);   lanes_block<S_CONTIG, 3>(acc, v, tile, w, dlo, dhi);
+    lanes_block<S_CONTIG, 4>(acc, v, tile, w, dlo, dhi);   lanes_block<S_CONTIG, 5>(acc, v, tile, w, dlo, dhi);
+    lanes_block<S_CONTIG, 6>(acc, v, tile, w, dlo, dhi);   lanes_block<S_CONTIG, 7>(acc, v, tile, w, dlo, dhi);
+    lanes_block<S_CONTIG, 8>(acc, v, tile, w, dlo, dhi);   lanes_block<S_CONTIG, 9>(acc, v, tile, w, dlo, dhi);
+    lanes_block<S_CONTIG, 10>(acc, v, tile, w, dlo, dhi);  lanes_block<S_CONTIG, 11>(acc, v, tile, w, dlo, dhi);
+    lanes_block<S_CONTIG, 12>(acc, v, tile, w, dlo, dhi);  lanes_block<S_CONTIG, 13>(acc, v, tile, w, dlo, dhi);
+    lanes_block<S_CONTIG, 14>(acc, v, tile, w, dlo, dhi);  lanes_block<S_CONTIG, 15>(acc, v, tile, w, dlo, dhi);
 }
 
 template <int MODE, bool S_CONTIG>
