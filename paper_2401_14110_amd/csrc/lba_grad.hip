@@ -43,6 +43,7 @@ struct GradDims {
     int32_t atomic;            // 1: gridDim.z > 1, combine with atomic adds
     int32_t vec_ok;            // 1: G, the plane and last_of are 16-byte aligned and N % 4 == 0 (wide scalar loads)
     uint32_t plane_xor;        // 0xFFFFFFFF: the plane holds OF bits (c = 1 - bit); 0: it holds the coefficients
+    int32_t v16;               // 1: rows of codes are 16-byte aligned (V % 16 == 0, K % 16 == 0)
 };
 
 __device__ __forceinline__ float decode_e4m3(uint32_t code) {
@@ -222,6 +223,21 @@ __device__ __forceinline__ float4 fetch_g_tile(const float* __restrict__ G, int 
     return *reinterpret_cast<const float4*>(G + off);
 }
 
+// The 16 x 64 codes of a step (16 values of s, the wave's 64 k): one 16-byte load per lane (row lane / 4, bytes
+// 16 * (lane % 4) ..), stored row-major in the wave's LDS; lane k then reads byte k of every row.  (One byte load per
+// lane and row, sixteen per step, took a quarter of the kernel's time.)  Needs 16-byte aligned rows of codes; a piece
+// that starts at or beyond K is +0.
+__device__ __forceinline__ uint4 fetch_v_tile(const uint8_t* __restrict__ V, int s, int k0, int lane, const GradDims& d) {
+    const int kq = k0 + (lane & 3) * 16;
+    uint4 c = make_uint4(0u, 0u, 0u, 0u);
+    if (kq < d.K) c = *reinterpret_cast<const uint4*>(V + (int64_t)(s + (lane >> 2)) * d.K + kq);
+    return c;
+}
+
+__device__ __forceinline__ void store_v_tile(uint8_t* vtile, uint4 c, int lane) {
+    *reinterpret_cast<uint4*>(vtile + (lane >> 2) * 64 + (lane & 3) * 16) = c;
+}
+
 __device__ __forceinline__ void store_g_tile(float* tile, float4 g4, int lane) {
     *reinterpret_cast<float4*>(tile + (lane >> 2) * 16 + (lane & 3) * 4) = g4;
 }
@@ -275,7 +291,7 @@ __device__ __forceinline__ void lanes_block(float (&acc)[16], const float (&v)[1
 // the scalar-load path cannot sustain), turned into coefficients, and handed out lane by lane.
 template <bool S_CONTIG>
 __device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, int s, int k, int lane,
-                                                    const uint8_t* __restrict__ V, const float* tile,
+                                                    const uint8_t* __restrict__ V, const float* tile, const uint8_t* vtile,
                                                     const uint32_t* __restrict__ P0, const uint32_t* __restrict__ P1,
                                                     const GradDims& d) {
     const int q = lane & 31, a = q >> 1, half8 = (q & 1) * 8;
@@ -287,10 +303,15 @@ __device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, in
     const uint32_t f = d.plane_xor;                            // OF plane: c = 1 - OF
     const uint32_t w[8] = {x.x ^ f, x.y ^ f, x.z ^ f, x.w ^ f, y.x ^ f, y.y ^ f, y.z ^ f, y.w ^ f};
     float v[16];
+    if (d.v16) {                                               // uniform: the codes are in the wave's LDS tile
 #pragma unroll
-    for (int u = 0; u < 16; ++u) {
-        const uint32_t code = (k < d.K) ? V[(int64_t)(s + u) * d.K + k] : 0u;
-        v[u] = decode_e4m3(code);
+        for (int u = 0; u < 16; ++u) v[u] = decode_e4m3(vtile[u * 64 + lane]);
+    } else {
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const uint32_t code = (k < d.K) ? V[(int64_t)(s + u) * d.K + k] : 0u;
+            v[u] = decode_e4m3(code);
+        }
     }
     const uint64_t dlo = __builtin_amdgcn_ballot_w64((w[0] & w[1] & w[2] & w[3]) != 0xFFFFFFFFu);
     const uint64_t dhi = __builtin_amdgcn_ballot_w64((w[4] & w[5] & w[6] & w[7]) != 0xFFFFFFFFu);
@@ -329,16 +350,23 @@ __global__ void __launch_bounds__(256) lba_grad_kernel(const float* __restrict__
     int s = s_begin;
     if (MODE == LBA_STE_IMMEDIATE_OF && rows_fast && s + 16 <= s_end) {
         __shared__ __attribute__((aligned(16))) float gtiles[4][256];      // one 16 x 16 tile of g per wave
+        __shared__ __attribute__((aligned(16))) uint8_t vtiles[4][1024];    // and one 16 x 64 tile of codes
         float* tile = gtiles[wave];
+        uint8_t* vtile = vtiles[wave];
         float4 g4 = fetch_g_tile<S_CONTIG>(G, r0, s, lane, d);
         for (; s + 16 <= s_end; s += 16) {
-            // LDS operations of a wave complete in order: the tile is overwritten after the last reads of the step
-            // before, and read after it is written; the wave barriers keep the compiler from moving them
+            // LDS operations of a wave complete in order: the tiles are overwritten after the last reads of the step
+            // before, and read after they are written; the wave barriers keep the compiler from moving them.
+            // g was requested a whole step ahead; the codes (L2-resident, re-read by every row block) are requested
+            // here, which keeps their four registers free during the step
+            uint4 c4 = make_uint4(0u, 0u, 0u, 0u);
+            if (d.v16) c4 = fetch_v_tile(V, s, k0, lane, d);
             __builtin_amdgcn_wave_barrier();
             store_g_tile(tile, g4, lane);
+            if (d.v16) store_v_tile(vtile, c4, lane);
             __builtin_amdgcn_wave_barrier();
-            if (s + 32 <= s_end) g4 = fetch_g_tile<S_CONTIG>(G, r0, s + 16, lane, d);   // a whole step ahead
-            immediate_superstep<S_CONTIG>(acc, r0, s, k, lane, V, tile, P0, P1, d);
+            if (s + 32 <= s_end) g4 = fetch_g_tile<S_CONTIG>(G, r0, s + 16, lane, d);
+            immediate_superstep<S_CONTIG>(acc, r0, s, k, lane, V, tile, vtile, P0, P1, d);
         }
     }
     for (; s < s_end; s += 4) {
@@ -476,6 +504,7 @@ static int run_grad_side(bool dx, const float* G, const uint8_t* V, const uint32
     gp.atomic = split > 1 ? 1 : 0;
     const uintptr_t al = (uintptr_t)G | (uintptr_t)plane | (uintptr_t)last_of;
     gp.vec_ok = ((al % 16) == 0 && (N % 4) == 0) ? 1 : 0;
+    gp.v16 = (((uintptr_t)V % 16) == 0 && (K % 16) == 0) ? 1 : 0;
     if (gp.atomic) {
         const int64_t n = (int64_t)gp.R * K;
         hipLaunchKernelGGL(lba_grad_zero_kernel, zero_grid(n), dim3(256), 0, st, out, n);
