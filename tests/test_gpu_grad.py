@@ -221,7 +221,8 @@ def test_immediate_estimator_on_clean_and_nearly_clean_planes(ref, gref):
     # written by hand: no bit at all, a few scattered bits, a dense corner next to clean steps, and a set bit in the
     # last word only; K ragged against 64 and 32.  Bit-exact on exactly representable sums, the FP32 bound otherwise.
     rng = np.random.default_rng(271)
-    for (M, N, K) in [(64, 64, 128), (80, 48, 200), (200, 36, 70), (48, 132, 33)]:
+    # K = 80 and 208: rows of codes 16-byte aligned (the codes of a step go through LDS) with a ragged last k block
+    for (M, N, K) in [(64, 64, 128), (80, 48, 200), (200, 36, 70), (48, 132, 33), (72, 64, 80), (40, 48, 208)]:
         A = codes(rng, (M, K), 5, 10); B = codes(rng, (N, K), 5, 10)
         tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
         for case in range(4):
