@@ -146,12 +146,14 @@ def main():
         dWbuf = torch.empty(max(l["N"] * l["K"] for l in layers), dtype=torch.float32, device=dev)
         for l in layers:
             l["macs"] *= 2                                     # dX and dW
-            # VALU issue slots per masked MAC (one wave instruction = 64 MACs; half-rate forms count 2):
-            # v_fmac with a scalar operand 2; + two v_readlane (immediate) or one v_cmp (recursive)
-            l["plan"] = dict(l["plan"], kernel=2, prod_mode=ste, valu_per_mac_x100=(200, 600, 400)[ste])
+            # VALU issue slots per masked MAC (one wave instruction = 64 MACs; half-rate forms count 2).  Vector
+            # kernel, identity / recursive: v_fmac with a scalar operand 2 (+ one v_cmp, recursive).  Immediate: priced
+            # at its floor, one full-rate v_fmac per 64 terms (a block without a blocked coefficient); blocks with
+            # blocked coefficients add two v_readlane per instruction, which this count leaves out
+            l["plan"] = dict(l["plan"], kernel=2, prod_mode=ste, valu_per_mac_x100=(200, 100, 400)[ste])
             # identity and (sequential) recursive coefficients are constant inside a k tile: lba_grad runs them as a
-            # dense product on the matrix cores when rows of G and groups of codes are aligned
-            if ste != 1 and l["N"] % 4 == 0 and l["K"] % 4 == 0 and (ste == 0 or l["K"] <= 12288):
+            # dense product on the matrix cores when rows of G are aligned
+            if ste != 1 and l["N"] % 4 == 0 and (ste == 0 or l["K"] <= 12288):
                 l["plan"] = dict(l["plan"], kernel=3, valu_per_mac_x100=0)
             l["of"] = l["last"] = None
             if ste:
