@@ -289,17 +289,26 @@ __device__ __forceinline__ void lanes_block(float (&acc)[16], const float (&v)[1
 // 16 rows x 16 s of the immediate estimator.  The 512 plane words of the step (two slabs) are fetched with
 // two 16-byte vector loads per lane (many in flight: the plane is streamed once and never reused, which
 // the scalar-load path cannot sustain), turned into coefficients, and handed out lane by lane.
+struct PlaneWords { uint4 x, y; };
+
 template <bool S_CONTIG>
-__device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, int s, int k, int lane,
-                                                    const uint8_t* __restrict__ V, const float* tile, const uint8_t* vtile,
-                                                    const uint32_t* __restrict__ P0, const uint32_t* __restrict__ P1,
-                                                    const GradDims& d) {
+__device__ __forceinline__ PlaneWords fetch_plane_words(int r0, int s, int lane, const uint32_t* __restrict__ P0,
+                                                        const uint32_t* __restrict__ P1, const GradDims& d) {
     const int q = lane & 31, a = q >> 1, half8 = (q & 1) * 8;
     const uint32_t* __restrict__ P = (lane & 32) ? P1 : P0;
     const uint32_t off = S_CONTIG ? (uint32_t)(r0 + a) * (uint32_t)d.stride_r + (uint32_t)(s + half8)
                                   : (uint32_t)(s + a) * (uint32_t)d.stride_s + (uint32_t)(r0 + half8);
-    const uint4 x = *reinterpret_cast<const uint4*>(P + off);
-    const uint4 y = *reinterpret_cast<const uint4*>(P + off + 4);
+    PlaneWords p;
+    p.x = *reinterpret_cast<const uint4*>(P + off);
+    p.y = *reinterpret_cast<const uint4*>(P + off + 4);
+    return p;
+}
+
+template <bool S_CONTIG>
+__device__ __forceinline__ void immediate_superstep(float (&acc)[16], int r0, int s, int k, int lane,
+                                                    const uint8_t* __restrict__ V, const float* tile, const uint8_t* vtile,
+                                                    const PlaneWords& pw, const GradDims& d) {
+    const uint4 x = pw.x, y = pw.y;
     const uint32_t f = d.plane_xor;                            // OF plane: c = 1 - OF
     const uint32_t w[8] = {x.x ^ f, x.y ^ f, x.z ^ f, x.w ^ f, y.x ^ f, y.y ^ f, y.z ^ f, y.w ^ f};
     float v[16];
@@ -354,20 +363,31 @@ __global__ void __launch_bounds__(256) lba_grad_kernel(const float* __restrict__
         float* tile = gtiles[wave];
         uint8_t* vtile = vtiles[wave];
         float4 g4 = fetch_g_tile<S_CONTIG>(G, r0, s, lane, d);
-        for (; s + 16 <= s_end; s += 16) {
+        auto step = [&](int ss, const PlaneWords& pw) {
             // LDS operations of a wave complete in order: the tiles are overwritten after the last reads of the step
             // before, and read after they are written; the wave barriers keep the compiler from moving them.
             // g was requested a whole step ahead; the codes (L2-resident, re-read by every row block) are requested
             // here, which keeps their four registers free during the step
             uint4 c4 = make_uint4(0u, 0u, 0u, 0u);
-            if (d.v16) c4 = fetch_v_tile(V, s, k0, lane, d);
+            if (d.v16) c4 = fetch_v_tile(V, ss, k0, lane, d);
             __builtin_amdgcn_wave_barrier();
             store_g_tile(tile, g4, lane);
             if (d.v16) store_v_tile(vtile, c4, lane);
             __builtin_amdgcn_wave_barrier();
-            if (s + 32 <= s_end) g4 = fetch_g_tile<S_CONTIG>(G, r0, s + 16, lane, d);
-            immediate_superstep<S_CONTIG>(acc, r0, s, k, lane, V, tile, vtile, P0, P1, d);
+            if (ss + 32 <= s_end) g4 = fetch_g_tile<S_CONTIG>(G, r0, ss + 16, lane, d);
+            immediate_superstep<S_CONTIG>(acc, r0, ss, k, lane, V, tile, vtile, pw, d);
+        };
+        if (S_CONTIG) {
+            // two steps share the 128-byte lines of the plane's rows: both halves are requested together (a step
+            // later the line has often left L2 again: the plane streams through it once)
+            for (; s + 32 <= s_end; s += 32) {
+                const PlaneWords pa = fetch_plane_words<S_CONTIG>(r0, s, lane, P0, P1, d);
+                const PlaneWords pb = fetch_plane_words<S_CONTIG>(r0, s + 16, lane, P0, P1, d);
+                step(s, pa);
+                step(s + 16, pb);
+            }
         }
+        for (; s + 16 <= s_end; s += 16) step(s, fetch_plane_words<S_CONTIG>(r0, s, lane, P0, P1, d));
     }
     for (; s < s_end; s += 4) {
         float v[4];
