@@ -146,7 +146,8 @@ int lba_gemm_batched(const uint8_t* A, const uint8_t* B, float* C, int64_t batch
  * Each plane holds lba_mask_words(M, N, K) uint32 words: word index ((k / 32) * M + m) * N + n,
  * bit k % 32; bits for k >= K are zero.  C may be NULL (then only the planes are written); either
  * plane may be NULL but not both.  C, when given, equals lba_gemm's bit for bit.
- * LBA_ORDER_SEQ only. */
+ * LBA_ORDER_SEQ only (LBA_ERR_UNSUPPORTED otherwise: the chunked order has second-level planes too and is
+ * served by lba_gemm_bwd_chunked below). */
 int lba_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C,
                  uint32_t* of_mask, uint32_t* uf_mask,
                  int64_t M, int64_t N, int64_t K,
@@ -175,8 +176,29 @@ int lba_gemm_bwd_diff_in(const uint8_t* A, const uint8_t* B, float* C, uint32_t*
                          int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,
                          lba_qfmt qprod, lba_qfmt qacc, int32_t order, float eps2, void* hip_stream);
 
-/* Number of uint32 words in one event plane: ceil(K / 32) * M * N (0 if any size is <= 0). */
+/* The same re-run for the chunked order (Sec. 3: chunks of 16, Fig. 1 right; App. D, last paragraph: the
+ * recompute follows the same tree).  First-level planes of_mask / uf_mask: as for lba_gemm_bwd, with S_k the
+ * partial sum of k's own chunk (a chain that starts from 0 at every multiple of 16).  Second-level planes
+ * of_mask2 / uf_mask2, lba_mask_words_level2(M, N, K) words each: for chunk j = 0 .. ceil(K / 16) - 1, with
+ * T_0 = 0 and T_{j+1} = Q_acc(T_j + chunk_j), bit j % 32 of word ((j / 32) * M + m) * N + n is
+ *   OF2_j = [ |T_j + chunk_j| >= R_OF of Q_acc ]
+ *   UF2_j = [ T_j + chunk_j != 0 and |T_j + chunk_j| < R_UF of Q_acc ]    (no Q_prod at the second level)
+ * and bits for j >= ceil(K / 16) are zero.  C may be NULL; any of the four planes may be NULL, but not all
+ * of them (unless K == 0, when the planes have no words).  C, when given, equals lba_gemm's with
+ * LBA_ORDER_CHUNK16 bit for bit.  The second-level OF plane is what lba_ste_plane needs for the recursive
+ * estimator under this order.  Errors as for lba_gemm_bwd. */
+int lba_gemm_bwd_chunked(const uint8_t* A, const uint8_t* B, float* C,
+                         uint32_t* of_mask, uint32_t* uf_mask, uint32_t* of_mask2, uint32_t* uf_mask2,
+                         int64_t M, int64_t N, int64_t K,
+                         lba_qfmt qprod, lba_qfmt qacc, void* hip_stream);
+
+/* Number of uint32 words in one event plane: ceil(K / 32) * M * N (0 if any size is <= 0; SIZE_MAX if the
+ * count does not fit in size_t, which no shape inside the limits of the calls above reaches). */
 size_t lba_mask_words(int64_t M, int64_t N, int64_t K);
+
+/* Number of uint32 words in one second-level plane of lba_gemm_bwd_chunked: ceil(ceil(K / 16) / 32) * M * N
+ * (one bit per chunk of 16 steps, Sec. 3; 0 if any size is <= 0, SIZE_MAX on overflow of size_t). */
+size_t lba_mask_words_level2(int64_t M, int64_t N, int64_t K);
 
 /* ---- gradient side: the fine-grained straight-through estimators of Sec. 4 and App. D ---------
  *
@@ -262,6 +284,13 @@ typedef struct {
  * 3 lba_gemm_bwd with the overflow plane alone (uf_mask == NULL). */
 int lba_plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc,
                    int32_t order, int32_t with_masks, lba_plan_info* out);
+
+/* The kernel the same call would launch, named as a profiler prints its template instantiation without the
+ * namespace and the argument list (e.g. "lba_fast_mixed_kernel<32, 1, 0, 0>"), written to buf (NUL-terminated,
+ * truncated to buf_len).  For benchmark reports that look up profiler records of the kernel that ran; host
+ * only.  Returns LBA_OK, LBA_ERR_NULL or the status lba_plan_query would return. */
+int lba_plan_kernel_name(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc,
+                         int32_t order, int32_t with_masks, char* buf, size_t buf_len);
 
 /* lba_plan_query for the operand formats of lba_gemm_in (the biases are folded as that call folds them). */
 int lba_plan_query_in(int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,

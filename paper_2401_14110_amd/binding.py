@@ -9,8 +9,7 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-# LBA_HIP_LIB names another build of the same library (A/B measurements); the default is the in-tree one
-_LIBPATH = os.environ.get("LBA_HIP_LIB") or os.path.join(_HERE, "liblba_hip.so")
+_LIBPATH = os.path.join(_HERE, "liblba_hip.so")
 
 ROUND_FLOOR, ROUND_RNE = 0, 1
 STE_IDENTITY, STE_IMMEDIATE_OF, STE_RECURSIVE_OF, STE_COEF_PLANE = 0, 1, 2, 3
@@ -50,14 +49,16 @@ class LbaError(RuntimeError):
 _lib = None
 
 
-def lib():
-    """Load paper_2401_14110_amd/liblba_hip.so (built by __graft_entry__.build())."""
+def lib(path=None):
+    """Load paper_2401_14110_amd/liblba_hip.so (built by __graft_entry__.build()).  `path`: another build of
+    the same library, honoured only on the first call of a process (A/B measurements)."""
     global _lib
     if _lib is None:
-        if not os.path.exists(_LIBPATH):
+        libpath = path or _LIBPATH
+        if not os.path.exists(libpath):
             raise RuntimeError("HIP library %s is missing: run `python __graft_entry__.py` "
-                               "(there is no fallback path)" % _LIBPATH)
-        L = ctypes.CDLL(_LIBPATH)
+                               "(there is no fallback path)" % libpath)
+        L = ctypes.CDLL(libpath)
         vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32
         L.lba_gemm.restype = ctypes.c_int
         L.lba_gemm.argtypes = [vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, i32, vp]
@@ -97,6 +98,8 @@ def lib():
         L.lba_mask_words.argtypes = [i64, i64, i64]
         L.lba_strerror.restype = ctypes.c_char_p
         L.lba_strerror.argtypes = [ctypes.c_int]
+        L.lba_plan_kernel_name.restype = ctypes.c_int
+        L.lba_plan_kernel_name.argtypes = [i64, i64, i64, lba_qfmt, lba_qfmt, i32, i32, ctypes.c_char_p, ctypes.c_size_t]
         L.lba_plan_query.restype = ctypes.c_int
         L.lba_plan_query.argtypes = [i64, i64, i64, lba_qfmt, lba_qfmt, i32, i32,
                                      ctypes.POINTER(lba_plan_info)]
@@ -230,6 +233,12 @@ def lba_plan_query(M, N, K, qprod, qacc, order=ORDER_SEQ, with_masks=0):
     return {n: getattr(info, n) for n, _ in lba_plan_info._fields_}
 
 
+def lba_plan_kernel_name(M, N, K, qprod, qacc, order=ORDER_SEQ, with_masks=0):
+    buf = ctypes.create_string_buffer(128)
+    _check(lib().lba_plan_kernel_name(M, N, K, qfmt(qprod), qfmt(qacc), order, with_masks, buf, len(buf)))
+    return buf.value.decode()
+
+
 # ---- tensor conveniences --------------------------------------------------------------------
 
 def _ops(A, B):
@@ -325,8 +334,18 @@ def gemm_bwd_chunked(A, B, qprod, qacc, want_c=True, stream=None, want_uf=True):
     return (C, *planes)
 
 
+def _plane(t, K, M=None, N=None, what="plane"):
+    """An event / coefficient plane as the library reads it: int32 [ceil(K/32), M, N], contiguous, on the device."""
+    if t.dtype not in (torch.int32, torch.uint32) or not t.is_cuda or t.dim() != 3:
+        raise ValueError("%s must be a 3-d int32 device tensor [ceil(K/32), M, N]" % what)
+    if t.shape[0] != (K + 31) // 32 or (M is not None and tuple(t.shape[1:]) != (M, N)):
+        raise ValueError("%s has shape %s, expected [%d, M, N]" % (what, tuple(t.shape), (K + 31) // 32))
+    return t.contiguous()
+
+
 def last_overflow(of_plane, K, stream=None):
     """int32 [M, N] index of the last overflowing step of every chain (-1: none) from an OF plane."""
+    of_plane = _plane(of_plane, K, what="of_plane")
     W, M, N = of_plane.shape
     out = torch.empty((M, N), dtype=torch.int32, device=of_plane.device)
     _check(lib().lba_last_overflow(of_plane.data_ptr() or None, out.data_ptr() or None, M, N, K, _stream(stream)))
@@ -341,6 +360,12 @@ def grad(G, A, B, ste, of_plane=None, last_of=None, want_dx=True, want_dw=True, 
     if G.dtype != torch.float32 or tuple(G.shape) != (M, N) or not G.is_cuda:
         raise ValueError("G must be a float32 device tensor [M, N]")
     G = G.contiguous()
+    if of_plane is not None:
+        of_plane = _plane(of_plane, K, M, N, "of_plane")
+    if last_of is not None:
+        if last_of.dtype != torch.int32 or tuple(last_of.shape) != (M, N) or not last_of.is_cuda:
+            raise ValueError("last_of must be an int32 device tensor [M, N]")
+        last_of = last_of.contiguous()
     dX = torch.empty((M, K), dtype=torch.float32, device=A.device) if want_dx else None
     dW = torch.empty((N, K), dtype=torch.float32, device=A.device) if want_dw else None
     ptr = lambda t: (t.data_ptr() or None) if t is not None else None
@@ -351,7 +376,13 @@ def grad(G, A, B, ste, of_plane=None, last_of=None, want_dx=True, want_dw=True, 
 
 def ste_plane(of_plane, K, ste, order=ORDER_SEQ, of_plane2=None, stream=None):
     """Coefficient plane (int32 [ceil(K/32), M, N], bit = 1: passes) of an estimator from the OF plane(s)."""
+    of_plane = _plane(of_plane, K, what="of_plane")
     W, M, N = of_plane.shape
+    if of_plane2 is not None:
+        if of_plane2.dtype not in (torch.int32, torch.uint32) or not of_plane2.is_cuda or \
+                tuple(of_plane2.shape) != (((K + 15) // 16 + 31) // 32, M, N):
+            raise ValueError("of_plane2 must be an int32 device tensor [ceil(ceil(K/16)/32), M, N]")
+        of_plane2 = of_plane2.contiguous()
     out = torch.empty_like(of_plane)
     _check(lib().lba_ste_plane(of_plane.data_ptr() or None,
                                (of_plane2.data_ptr() or None) if of_plane2 is not None else None,

@@ -598,13 +598,12 @@ int lba_grad(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t*
     if (!G) return LBA_ERR_NULL;
     if ((ste == LBA_STE_IMMEDIATE_OF || ste == LBA_STE_COEF_PLANE) && !of_mask) return LBA_ERR_NULL;
     if (ste == LBA_STE_RECURSIVE_OF && !last_of) return LBA_ERR_NULL;
+    if ((dX && !B) || (dW && !A)) return LBA_ERR_NULL;         // every check before the first launch
     if (dX) {
-        if (!B) return LBA_ERR_NULL;
         rc = lba::run_grad_side(true, G, B, of_mask, last_of, dX, M, N, K, ste, st);
         if (rc != LBA_OK) return rc;
     }
     if (dW) {
-        if (!A) return LBA_ERR_NULL;
         rc = lba::run_grad_side(false, G, A, of_mask, last_of, dW, M, N, K, ste, st);
         if (rc != LBA_OK) return rc;
     }

@@ -2,6 +2,7 @@
 // The device code is in lba_device.h; its instantiations are in lba_fast_*.hip, lba_bwd.hip, lba_gen.hip.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdio.h>
 
 #include "lba_internal.h"
 #include "lba_launch.h"
@@ -26,6 +27,34 @@ static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
         return launch_fast_44(pl, st);
     }
     return launch_gen(pl, st);
+}
+
+// The kernel launch_plan starts for a plan, named as a profiler prints the template instantiation
+// ("lba_fast_mixed_kernel<32, 1, 0, 0>"): benchmark reports use it to find the counter records of the kernel
+// that actually ran.  uf: the call asks for an underflow plane.  Mirrors launch_plan and the launchers.
+static void plan_kernel_name(const Plan& pl, bool uf, char* buf, size_t n) {
+    const int pm = pl.prod_mode, ord = pl.order;
+    const char* b = uf ? "true" : "false";
+    if (pl.kernel == KERNEL_GEN) {
+        snprintf(buf, n, "lba_gen_kernel<%d, %s, %d, %s>", pl.round, pl.events == 1 ? "true" : "false", ord,
+                 pl.events == 2 ? "true" : "false");
+        return;
+    }
+    if (pl.events == 2) {
+        snprintf(buf, n, pl.mix_tail > 0 ? "lba_fast_diff_mixed_kernel<%d, %d>" : "lba_fast_diff_kernel<%d, %d>", pm, ord);
+    } else if (pl.events) {
+        if (pl.amode)             snprintf(buf, n, "lba_fast_bwd_kernel<%d, 0, %s, 1>", pm, b);
+        else if (pl.mix_tail > 0) snprintf(buf, n, "lba_fast_bwd_mixed_kernel<%d, %s>", pm, b);
+        else                      snprintf(buf, n, "lba_fast_bwd_kernel<%d, %d, %s, 0>", pm, ord, b);
+    } else if (pl.rne_odd) {
+        snprintf(buf, n, "lba_fast_kernel<4, 4, %d, %d, 3, %d, 0>", pl.bk, pm, ord);
+    } else {
+        // rounding code of the instantiation: 0 floor, 1 nearest-even by bfe / add3 / and, 2 by the bfloat16 conversion (M = 7)
+        const int rnd = pl.round == LBA_ROUND_FLOOR ? 0 : ((pl.kp.sh_a == 16 && !pl.amode) ? 2 : 1);
+        if (pl.amode)             snprintf(buf, n, "lba_fast_kernel<4, 4, %d, %d, %d, %d, 1>", pl.bk, pm, rnd, ord);
+        else if (pl.mix_tail > 0) snprintf(buf, n, "lba_fast_mixed_kernel<%d, %d, %d, %d>", pl.bk, pm, rnd, ord);
+        else                      snprintf(buf, n, "lba_fast_kernel<%d, %d, %d, %d, %d, %d, 0>", pl.tm, pl.tn, pl.bk, pm, rnd, ord);
+    }
 }
 
 static int gcd_align(const void* ptr, int64_t K) {
@@ -128,7 +157,7 @@ int lba_gemm_bwd_diff(const uint8_t* A, const uint8_t* B, float* C, uint32_t* di
     const int rc = lba::make_plan(M, N, K, qprod, qacc, order, 2, &pl);
     if (rc != LBA_OK) return rc;
     if (!diff_eps_ok(eps2)) return LBA_ERR_FORMAT;
-    if (!diff_mask && M * N * K > 0) return LBA_ERR_NULL;
+    if (!diff_mask && M > 0 && N > 0 && K > 0) return LBA_ERR_NULL;
     return lba::run(A, B, C, diff_mask, nullptr, M, N, K, qprod, qacc, order, 2, hip_stream,
                     1, 0, 0, 0, nullptr, nullptr, nullptr, nullptr, 0, 0, eps2);
 }
@@ -220,14 +249,23 @@ int lba_gemm_batched(const uint8_t* A, const uint8_t* B, float* C, int64_t batch
                     batch, stride_a, stride_b, stride_c);
 }
 
+// groups * M * N, saturated at SIZE_MAX (a caller sizing a buffer from a wrapped count would under-allocate)
+static size_t plane_words(int64_t groups, int64_t M, int64_t N) {
+    size_t mn = 0, words = 0;
+    if (__builtin_mul_overflow((size_t)M, (size_t)N, &mn) || __builtin_mul_overflow(mn, (size_t)groups, &words))
+        return SIZE_MAX;
+    return words;
+}
+
 size_t lba_mask_words(int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
-    return (size_t)((K + 31) / 32) * (size_t)M * (size_t)N;
+    return plane_words(K / 32 + (K % 32 != 0), M, N);
 }
 
 size_t lba_mask_words_level2(int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0) return 0;
-    return (size_t)(((K + 15) / 16 + 31) / 32) * (size_t)M * (size_t)N;
+    const int64_t chunks = K / 16 + (K % 16 != 0);
+    return plane_words(chunks / 32 + (chunks % 32 != 0), M, N);
 }
 
 const char* lba_strerror(int code) {
@@ -261,6 +299,16 @@ static int plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt 
 int lba_plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
                    int32_t with_masks, lba_plan_info* out) {
     return plan_query(M, N, K, qprod, qacc, order, with_masks, nullptr, out);
+}
+
+int lba_plan_kernel_name(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc, int32_t order,
+                         int32_t with_masks, char* buf, size_t buf_len) {
+    if (!buf || buf_len == 0) return LBA_ERR_NULL;
+    lba::Plan pl;
+    const int rc = lba::make_plan(M, N, K, qprod, qacc, order, with_masks, &pl);
+    if (rc != LBA_OK) return rc;
+    lba::plan_kernel_name(pl, with_masks == 1, buf, buf_len);
+    return LBA_OK;
 }
 
 int lba_plan_query_in(int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,

@@ -259,6 +259,16 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         if (!rne_odd) fast = false;
     }
     if (fast && (flush || clamp) && std::abs(c_a_dom - c_p_dom) > 120) fast = false;   // kc must be an FP32 normal
+    // the fixed domain of the no-underflow flag must keep R_OF of Q_acc an FP32 normal there (a top exponent
+    // below -66 would put it among the flushed denormals and every chain would clamp to 0)
+    if (fast && nouf_a && top_exp(qa) + c_a_dom < -126) fast = false;
+    // ... and every non-zero sum: sums are multiples of the products' unit, 2^min_lsb, or, where Q_prod can
+    // saturate, of the unit of its R_OF; if even the smallest product saturates they are multiples of R_OF itself
+    if (fast && nouf_a) {
+        int low = in.min_lsb;
+        if (clamp) low = (top_exp(qp) + 1 <= in.min_lsb) ? top_exp(qp) : std::min(in.min_lsb, top_exp(qp) - qp.man_bits);
+        if (low + c_a_dom < -126) fast = false;
+    }
     // the recompute kernel also forms p * kc * 2^60 and S * 2^60
     if (fast && events && (std::abs(c_a_dom - c_p_dom) > 60 || top_exp(qa) + c_a_dom + 61 > 126)) fast = false;
     // the DIFF plane's scaled-domain kernel: E4M3 operands, Q_prod without mantissa rounding

@@ -3,6 +3,7 @@ header declares, validates arguments before touching the device, and plans kerne
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -31,6 +32,52 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(L, n), n
         # the Python binding carries the same names
         assert hasattr(lb, n), n
+
+
+def exported_functions():
+    out = subprocess.run(["nm", "-D", "--defined-only", os.path.join(ROOT, "paper_2401_14110_amd", "liblba_hip.so")],
+                         check=True, capture_output=True, text=True).stdout
+    return {f[2] for f in (line.split() for line in out.splitlines()) if len(f) == 3 and f[1] in "TW" and f[2].startswith("lba_")}
+
+
+def test_header_declares_every_exported_symbol():
+    # the other direction: an exported entry point that the header does not declare cannot be reached from C
+    exported = exported_functions()
+    assert {"lba_gemm", "lba_gemm_bwd_chunked", "lba_mask_words_level2"} <= exported
+    assert exported <= declared_functions(), exported - declared_functions()
+    for n in exported:
+        assert hasattr(lb, n), n
+
+
+def test_a_c99_caller_compiles_against_the_header_and_links(tmp_path):
+    exe = str(tmp_path / "c_caller")
+    libdir = os.path.join(ROOT, "paper_2401_14110_amd")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    os.path.join(ROOT, "tests", "c_caller.c"), "-o", exe, "-L", libdir, "-llba_hip",
+                    "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    run = subprocess.run([exe], capture_output=True, text=True)
+    assert run.returncode == 0, (run.returncode, run.stdout, run.stderr)
+    assert "c caller ok" in run.stdout
+
+
+def test_mask_word_counts_saturate_instead_of_wrapping():
+    big = (1 << 62)
+    assert lb.lba_mask_words(big, big, 64) == (1 << 64) - 1
+    assert lb.lba_mask_words_level2(big, big, 1 << 40) == (1 << 64) - 1
+    assert lb.lba_mask_words((1 << 30) - 64, 1 << 21, (1 << 31) - 64) == (1 << 64) - 1   # the largest admitted shape: 2^77 words
+    assert lb.lba_mask_words(1 << 20, 1 << 20, (1 << 20) + 1) == ((1 << 15) + 1) << 40
+    # a NULL plane with sizes whose product would overflow 64 bits is still a NULL error, not undefined behaviour
+    A = ctypes.c_void_p(0x1000)
+    assert lb.lba_gemm_bwd_diff(A, A, A, None, (1 << 30) - 64, 1 << 21, (1 << 31) - 64, GOOD_P, GOOD_A, 0, 0.5) == lb.ERR_NULL
+
+
+def test_gradient_call_checks_every_pointer_before_launching():
+    G = A = B = P = O = ctypes.c_void_p(0x1000)
+    # dX and dW asked for, A missing: refused although the dX side alone would have been fine
+    assert lb.lba_grad(G, None, B, P, None, O, O, 8, 8, 8, 1) == lb.ERR_NULL
+    assert lb.lba_grad(G, A, None, P, None, O, O, 8, 8, 8, 1) == lb.ERR_NULL
+    assert lb.lba_grad(G, A, B, None, None, O, O, 8, 8, 8, 1) == lb.ERR_NULL
+    assert lb.lba_grad(G, A, B, P, None, O, O, 8, 8, 8, 2) == lb.ERR_NULL
 
 
 def test_status_texts():
@@ -153,6 +200,16 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     # no-underflow flag: still the scaled kernel; a flagged Q_prod that cannot saturate is the identity
     assert q(64, 64, 64, (5, 7, -1, 0x100), (4, 7, -9, 0x100))["prod_mode"] == 0
     assert q(64, 64, 64, (5, 7, 15, 0x101), (4, 7, 7, 0x101))["kernel"] == 0
+    # ... unless R_OF of the accumulator would be a denormal in the flag's fixed domain (2^-60): general kernel
+    assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 90, 0x100))["kernel"] == 1
+    assert q(64, 64, 64, (5, 7, 15, 0), (2, 7, 126, 0x100))["kernel"] == 1
+    assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 90, 0x101), order=1)["kernel"] == 1
+    assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 81, 0x100))["kernel"] == 0      # top exponent -66: still a normal there
+    assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 82, 0x100))["kernel"] == 1
+    # ... or a Q_prod that saturates every product at a value below 2^-66 would put the sums among them
+    assert q(64, 64, 64, (4, 3, 101, 1), (4, 8, -57, 0x101), order=1)["kernel"] == 1
+    assert q(64, 64, 64, (4, 3, 81, 0), (4, 8, -57, 0x100))["kernel"] == 0      # R_OF of Q_prod about 2^-65: fine
+    assert q(64, 64, 64, (4, 3, 82, 0), (4, 8, -57, 0x100))["kernel"] == 1
     # recompute call: scaled-domain kernel for floor when Q_prod can underflow, else the general one
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), with_masks=1)["kernel"] == 1

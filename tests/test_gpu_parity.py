@@ -371,6 +371,49 @@ def test_random_formats(ref):
     assert {(0, 0, False), (0, 1, False), (0, 1, True), (1, 1, False)} <= picked, picked
 
 
+def test_no_underflow_accumulators_with_a_tiny_range(ref):
+    # the no-underflow flag on an accumulator whose R_OF lies far below every product (top exponent -75 and
+    # -123): every non-zero step saturates at +-R_OF, whichever kernel runs it
+    rng = np.random.default_rng(2025)
+    A = rand_codes(rng, (40, 70)); B = rand_codes(rng, (36, 70))
+    for qa in ((4, 7, 90, 0x100), (2, 7, 126, 0x100), (4, 7, 81, 0x100), (4, 7, 82, 0x101), (3, 3, 100, 0x100)):
+        for order in (0, 1):
+            got = check(ref, A, B, (5, 7, 15, qa[3] & 1), qa, "tiny no-underflow accumulator", order=order)
+            top = (1 << qa[0]) - qa[2] - 1
+            rof = 2.0 ** top * (2 - 2.0 ** -qa[1])
+            assert set(np.unique(np.abs(got)).tolist()) <= {0.0, rof}
+            assert (np.abs(got) == rof).any()
+
+
+def test_random_formats_over_the_whole_bias_range(ref):
+    # the same sweep with the biases drawn from the whole documented range (2^E - b - 1 <= 127, b <= 126): most
+    # of these formats flush or saturate everything, which is where a domain of the scaled kernel can run out of
+    # FP32's own exponent range
+    pyr = random.Random(77)
+    rng = np.random.default_rng(77)
+    A = rand_codes(rng, (40, 70)); B = rand_codes(rng, (36, 70))
+    done = 0
+    kernels = set()
+    while done < 80:
+        fmts = []
+        for _ in range(2):
+            E = pyr.randint(2, 7); M = pyr.choice([1, 3, 5, 7, 8, 10, 12, 20, 23])
+            b = pyr.randint((1 << E) - 128, 126)
+            if done % 2:                                       # every other case: near the operands' own range
+                b = pyr.randint(max((1 << E) - 128, -30), 60)
+            fmts.append((E, M, b))
+        rnd = pyr.randint(0, 1)
+        qpf, qaf = fmts[0] + (rnd | pyr.choice([0, 0, 0x100]),), fmts[1] + (rnd | pyr.choice([0, 0, 0x100]),)
+        order = pyr.randint(0, 1)
+        if ref.carrier_bits(fm(ref, qpf), fm(ref, qaf)) == 0:
+            continue
+        plan = lb.lba_plan_query(40, 36, 70, qpf, qaf, order)
+        kernels.add(plan["kernel"])
+        check(ref, A, B, qpf, qaf, "random format (full bias range) %d" % done, order=order)
+        done += 1
+    assert kernels == {0, 1}
+
+
 def test_event_planes_of_the_chunked_order(ref):
     # first-level planes (bit k: step k of its own chunk's chain) and second-level planes (bit j: the add
     # of chunk j) for K below, at and across chunk, tile and second-level-word (512) boundaries; scaled

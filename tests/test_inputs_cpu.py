@@ -74,6 +74,11 @@ def test_checksum_function_and_golden_file():
     for line in open(path):
         t = line.split()
         if t and not line.startswith("#"):
-            assert len(t) == 11 and all(len(v) == 16 for v in t[8:])
+            assert len(t) in (11, 13, 15) and all(len(v) == 16 for v in t[8:11])
+            assert [v.split("=")[0] for v in t[11:]] == ["of", "uf", "of2", "uf2"][:len(t) - 11]
+            assert all(len(v.split("=")[1]) == 16 for v in t[11:])
+            assert (len(t) == 15) == (t[7] == "1" and len(t) > 11)         # chunked order with planes: four of them
             rows[t[0]] = rows.get(t[0], 0) + 1
-    assert rows == {"conv": 2, "bert": 4, "gemm4096": 1, "resnet50": 54}
+    # conv: floor (with planes) and nearest-even; bert: floor / sequential and the paper's biases / chunked, with
+    # planes; ResNet-50: floor, nearest-even and the paper's biases under the chunked order
+    assert rows == {"conv": 2, "bert": 8, "gemm4096": 1, "resnet50": 162}

@@ -159,3 +159,74 @@ def test_immediate_diff_coefficients_against_fraction_model(ref, gref):
         for n in range(2):
             for k in range(K):
                 assert dW[n, k] == sum(G[m, n] * tab[A[m, k]] * c[m, n, k] for m in range(3))
+
+
+def test_sum_of_magnitudes_that_scales_the_fp32_tolerance(ref, gref):
+    """grad_abs (sum over the kept terms of |g| * |value|) sets the tolerance of every floating-point gradient
+    parity test, so it is pinned like the sums themselves: hand-worked single chains from the coefficient
+    patterns above, a library matmul of magnitudes for the identity estimator, the Fraction model on a case
+    with overflows, and the inequalities that any sum of magnitudes satisfies."""
+    P, N448, ONE, Z = 0x7E, 0xFE, 0x38, 0x00          # +448, -448, 1.0, 0
+    qp, qa = ref.QFmt(5, 7, 15, 0), ref.QFmt(4, 7, 7, 0)
+    # (a codes, b codes, immediate c, recursive c): the patterns of test_hand_worked_coefficient_patterns
+    cases = [([P, N448, ONE], [P, ONE, ONE], [0, 1, 1], [0, 1, 1]),
+             ([ONE, P, N448], [ONE, P, ONE], [1, 0, 1], [0, 0, 1]),
+             ([ONE, ONE, P], [ONE, ONE, P], [1, 1, 0], [0, 0, 0])]
+    val = {P: 448.0, N448: 448.0, ONE: 1.0, Z: 0.0}    # magnitudes, typed by hand
+    for a, b, c_imm, c_rec in cases:
+        A = np.array([a], dtype=np.uint8); B = np.array([b], dtype=np.uint8)
+        for g in (0.75, -0.75):
+            for ste, c in ((gref.STE_IMMEDIATE_OF, c_imm), (gref.STE_RECURSIVE_OF, c_rec), (gref.STE_IDENTITY, [1, 1, 1])):
+                aX, aW = gref.grad_abs(np.array([[g]]), A, B, qp, qa, ste)
+                assert aX.shape == (1, 3) and aW.shape == (1, 3)
+                assert aX[0].tolist() == [0.75 * val[b[k]] * c[k] for k in range(3)]
+                assert aW[0].tolist() == [0.75 * val[a[k]] * c[k] for k in range(3)]
+    # identity estimator: |G| times the matrix of magnitudes (library matmul)
+    rng = np.random.default_rng(21)
+    A = _codes(rng, (9, 40)); B = _codes(rng, (7, 40))
+    G = rng.standard_normal((9, 7))
+    tab = np.array([abs(ref.decode(c)) for c in range(256)])
+    aX, aW = gref.grad_abs(G, A, B, qp, qa, gref.STE_IDENTITY)
+    assert np.allclose(aX, np.abs(G) @ tab[B], rtol=1e-13, atol=0) and np.allclose(aW, np.abs(G).T @ tab[A], rtol=1e-13, atol=0)
+    # with overflows, both orders: exact rational sums of magnitudes from the Fraction model's events
+    # (all-positive gradients and operands make the plain sums of _frac_grad sums of magnitudes)
+    for chunked in (False, True):
+        order = ref.ORDER_CHUNK16 if chunked else ref.ORDER_SEQ
+        K = 37
+        A = _codes(rng, (3, K), 3, 12); B = _codes(rng, (2, K), 3, 12)
+        G = rng.integers(-8, 9, (3, 2)) / 4.0
+        for ste in (0, 1, 2):
+            aX, aW = gref.grad_abs(G, A, B, qp, qa, ste, order)
+            dX, dW = gref.grad(G, A, B, qp, qa, ste, order)
+            assert (aX >= np.abs(dX)).all() and (aW >= np.abs(dW)).all()            # triangle inequality
+            # same events (they depend on the signed operands), magnitudes summed exactly
+            M_, N_ = 3, 2
+            wX = [[Fraction(0)] * K for _ in range(M_)]; wW = [[Fraction(0)] * K for _ in range(N_)]
+            for m in range(M_):
+                for n in range(N_):
+                    a = [int(c) for c in A[m]]; b = [int(c) for c in B[n]]
+                    if chunked:
+                        _, ev1, ev2 = FM.chain_chunk16(a, b, (5, 7, 15, 0), (4, 7, 7, 0), with_events=True)
+                    else:
+                        _, ev1 = FM.chain(a, b, (5, 7, 15, 0), (4, 7, 7, 0)); ev2 = []
+                    for k in range(K):
+                        if ste == 0:
+                            c = 1
+                        elif ste == 1:
+                            c = 0 if ev1[k][0] else 1
+                        else:
+                            j = k // 16
+                            path = ([ev1[i][0] for i in range(k, min(K, 16 * j + 16))] + [ev2[jj][0] for jj in range(j, len(ev2))]
+                                    if chunked else [ev1[i][0] for i in range(k, K)])
+                            c = 0 if any(path) else 1
+                        g = abs(Fraction(float(G[m, n])))
+                        wX[m][k] += g * abs(FM.e4m3_value(b[k])) * c
+                        wW[n][k] += g * abs(FM.e4m3_value(a[k])) * c
+            assert all(Fraction(float(aX[m, k])) == wX[m][k] for m in range(M_) for k in range(K))
+            assert all(Fraction(float(aW[n, k])) == wW[n][k] for n in range(N_) for k in range(K))
+    # a sign flip of g or of an operand column that leaves the events alone leaves the magnitudes alone:
+    # identity estimator, any signs
+    aX2, aW2 = gref.grad_abs(-G, A, B, qp, qa, gref.STE_IDENTITY)
+    aX1, aW1 = gref.grad_abs(G, A, B, qp, qa, gref.STE_IDENTITY)
+    assert np.array_equal(aX1, aX2) and np.array_equal(aW1, aW2)
+    assert np.array_equal(gref.grad_abs(G, A ^ 0x80, B, qp, qa, gref.STE_IDENTITY)[1], aW1)
