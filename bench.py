@@ -25,15 +25,27 @@ if ROOT not in sys.path:
 # 256 CUs x 4 SIMDs x 32 lanes per clock x 2.4 GHz = 78.6e12 full-rate VALU lane-ops per second: the
 # rate behind the published 157.3 TFLOP/s FP32 vector peak (an FMA counts two flops).
 PEAK_LANE_OPS = 256 * 4 * 32 * 2.4e9
-# what the issue-rate probe sustains with the inner loop's own mix (mul | fma | and, phased, 4 waves per SIMD):
-# 114.5 of the 128 lane-ops per clock per CU (profiles/valu_issue_rates_gfx950.md)
-MEASURED_LANE_OPS = 256 * 114.5 * 2.4e9
-# HBM bytes per launch of the dominant kernel of the default workload (the 42 launches of the mixed-grid
-# kernel), from the calibrated rocprofv3 FETCH_SIZE / WRITE_SIZE runs summarised in
-# profiles/lba_fast_kernel_resnet50_sweep.md: FETCH_SIZE 875129.9 KiB x 2.000 + WRITE_SIZE 1173244.3 KiB.
-RESNET50_TRAFFIC_BYTES_PER_LAUNCH = (2.0 * 875129.9375 + 1173244.25) * 1024 / 42
+# Counter-derived figures (HBM bytes per launch from calibrated FETCH_SIZE / WRITE_SIZE runs, VALU instructions
+# issued per MAC from SQ_INSTS_VALU, the rate the issue-rate probe sustains with a kernel's own instruction mix)
+# are not measured by this script: they come from profiles/roofline_counters.json, written by
+# paper_2401_14110_amd/rocprof_record.py from rocprofv3 runs of this script, and are reported only when the
+# record's workload and kernel name are the ones that ran here; otherwise the fields are null.
+COUNTER_RECORDS = os.path.join(ROOT, "profiles", "roofline_counters.json")
 PROD_FMT = (5, 7, 15)
 ACC_FMT = (4, 7, 7)
+
+
+def counter_record(workload_key, kernel_name):
+    """The record of rocprof_record.py for this workload and kernel, or None."""
+    try:
+        with open(COUNTER_RECORDS) as f:
+            data = json.load(f)
+    except (OSError, ValueError):
+        return None
+    for rec in data.get("records", []):
+        if rec.get("workload_key") == workload_key and kernel_name in rec.get("kernels", {}):
+            return dict(rec["kernels"][kernel_name], commit=rec.get("commit"), probe=data.get("valu_probe", {}))
+    return None
 
 
 def cpu_baseline(layer, qp, qa, C_gpu, order=0, threads=None, budget_macs=2.0e9):
@@ -56,9 +68,20 @@ def cpu_baseline(layer, qp, qa, C_gpu, order=0, threads=None, budget_macs=2.0e9)
     got = C_gpu[:rows].cpu().numpy()
     parity = bool(np.array_equal(got.view(np.uint32), want.view(np.uint32)))
     macs = rows * layer["N"] * layer["K"]
+    # the same oracle on one thread, on a sixteenth of the slab
+    rows1 = max(1, rows // 16)
+    t0 = time.perf_counter()
+    if "fa" in layer:
+        lba_ref.gemm_in(A[:rows1], B, lba_ref.InFmt(*layer["fa"]), lba_ref.InFmt(*layer["fb"]), lba_ref.QFmt(*qp),
+                        lba_ref.QFmt(*qa), order=order, nthreads=1)
+    else:
+        lba_ref.gemm(A[:rows1], B, lba_ref.QFmt(*qp), lba_ref.QFmt(*qa), order=order, nthreads=1)
+    dt1 = time.perf_counter() - t0
     return {"value": macs / dt, "unit": "LBA-MAC/s", "cores": threads, "kind": "oracle",
             "sample": "first %d rows of %s (M=%d,N=%d,K=%d), %.3g MACs, %.1f s" %
                       (rows, layer["name"], layer["M"], layer["N"], layer["K"], macs, dt),
+            "value_1_thread": rows1 * layer["N"] * layer["K"] / dt1,
+            "sample_1_thread": "first %d rows, %.1f s" % (rows1, dt1),
             "bit_exact_vs_gpu": parity}
 
 
@@ -90,6 +113,13 @@ def main():
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="after the steps, run a 1 GiB fill and a 1 GiB add (references for rocprofv3 FETCH_SIZE/WRITE_SIZE)")
+    ap.add_argument("--results", default=None, metavar="FILE",
+                    help="append one JSON line per GEMM of the workload (shape, formats, rounding, order, kernel, time, MAC/s, "
+                         "checksum of the complete output and its verdict against the offline oracle checksum of "
+                         "tests/golden/full_digests.txt); forward call on E4M3 operands only")
+    ap.add_argument("--dump-kernels", default=None, metavar="FILE",
+                    help="write the kernels of one step (name, launches, MACs, algorithmic bytes, issue slots per MAC) as "
+                         "JSON: the input rocprof_record.py pairs with the profiler's per-kernel counters")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU (every output chain is independent; "
@@ -131,6 +161,7 @@ def main():
         else:
             l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], PROD_FMT, acc_fmt, rnd)
             l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, with_masks)
+            l["kname"] = lb.lba_plan_kernel_name(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, with_masks)
             if args.bwd and args.of_only and order == 0:
                 # priced like the forward call: k-tiles that cannot overflow run the forward tile (3 slots per MAC);
                 # tiles that can add a clamp, a compare and a carry-in add per MAC, which this count leaves out
@@ -249,16 +280,26 @@ def main():
     ms_per_step = wall * 1e3 / args.steps
     value = total_macs * args.steps / wall
 
-    # per-launch durations (HIP events on the launch stream), grouped by kernel variant
+    # per-launch durations (HIP events on the launch stream: torch's current stream is the one every call is given),
+    # grouped by the kernel that ran
+    def synthetic_name(p):
+        fam = ("fast_diff" if args.diff is not None else "fast_bwd" if args.bwd else "fast") if p["kernel"] == 0 else "gen"
+        return "lba_%s%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (fam, "_mixed" if p.get("tail_blocks", 0) > 0 else "", p["thread_m"],
+                                                                 p["thread_n"], p["tile_k"], p["prod_mode"], "rne" if p["round"] else "floor")
+
     groups = {}
     per_layer_ms = [0.0] * len(layers)
+    step_ms = [0.0] * args.steps
     for s in range(args.steps):
         for i, l in enumerate(layers):
             ms = ev[s][i][0].elapsed_time(ev[s][i][1])
             per_layer_ms[i] += ms / args.steps
+            step_ms[s] += ms
             p = l["plan"]
-            key = (p["kernel"], p["prod_mode"], p["round"], p["thread_m"], p["thread_n"], p["tile_k"], p.get("tail_blocks", 0) > 0)
-            g = groups.setdefault(key, dict(ms=0.0, macs=0, launches=0, bytes=0, ops=p["valu_per_mac_x100"] / 100.0))
+            key = ("lba_grad_kernel<%s>" % args.grad) if args.grad else l.get("kname") or synthetic_name(p)
+            if args.grad:
+                key = (key, p["kernel"])
+            g = groups.setdefault(key, dict(ms=0.0, macs=0, launches=0, bytes=0, ops=p["valu_per_mac_x100"] / 100.0, plan_kernel=p["kernel"]))
             g["ms"] += ms
             g["macs"] += l["macs"]
             if args.grad:     # g (and the plane or the last-overflow indices) once per product, codes once, outputs once
@@ -267,25 +308,49 @@ def main():
                 g["bytes"] += 2 * per_prod + 5 * (l["M"] * l["K"] + l["N"] * l["K"])
             else:
                 g["bytes"] += l["M"] * l["K"] + l["N"] * l["K"] + 4 * l["M"] * l["N"]   # A, B once, C once
+                if args.bwd:                                                         # + one bit per MAC and plane
+                    planes = 1 if (args.diff is not None or args.of_only) else 2
+                    g["bytes"] += 4 * planes * lb.lba_mask_words(l["M"], l["N"], l["K"])
+                    if order == 1:
+                        g["bytes"] += 4 * 2 * lb.lba_mask_words_level2(l["M"], l["N"], l["K"])
             g["launches"] += 1
+    step_ms.sort()
+    median_ms = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else 0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
     dom_key = max(groups, key=lambda k: groups[k]["ms"])
     dom = groups[dom_key]
+    dom_name = dom_key[0] if isinstance(dom_key, tuple) else dom_key
     achieved = dom["macs"] * dom["ops"] / (dom["ms"] * 1e-3)
+    workload_key = "%s:%s:%s:%s:acc=%d,%d" % (
+        args.workload, ("grad-" + args.grad) if args.grad else ("diff" if args.diff is not None else ("bwd-of" if args.of_only else "bwd")) if args.bwd else "fwd",
+        args.round, args.order, acc_fmt[0], acc_fmt[1]) + (":in=%d,%d" % in_fmt if in_fmt else "") + (":implicit" if args.implicit else "")
+    rec = counter_record(workload_key, dom_name)
+    probe_rate = None
+    if rec and rec.get("probe_mix"):
+        probe_rate = rec["probe"].get(rec["probe_mix"], {}).get("lane_ops_per_s")
     roofline = {
         "bound": "alu", "achieved": achieved / 1e12, "peak": PEAK_LANE_OPS / 1e12, "unit": "Tlane-op/s",
         "frac": achieved / PEAK_LANE_OPS,
-        "peak_measured": MEASURED_LANE_OPS / 1e12, "frac_of_measured": achieved / MEASURED_LANE_OPS,
-        "traffic": RESNET50_TRAFFIC_BYTES_PER_LAUNCH if (args.workload == "resnet50" and rnd == 0 and order == 0 and not args.bwd and not args.grad) else None,
-        "kernel": ("lba_grad_kernel<%s>" % args.grad) if args.grad else "lba_%s_kernel<%dx%d,bk%d,prod_mode=%d,%s>" % (
-            (("fast_diff_mixed" if dom_key[6] else "fast_diff") if args.diff is not None else ("fast_bwd_mixed" if dom_key[6] else "fast_bwd") if args.bwd else ("fast_mixed" if dom_key[6] else "fast")) if dom_key[0] == 0 else "gen", dom_key[3], dom_key[4], dom_key[5], dom_key[1],
-            "rne" if dom_key[2] else "floor"),
+        "peak_measured": probe_rate / 1e12 if probe_rate else None,
+        "frac_of_measured": achieved / probe_rate if probe_rate else None,
+        "traffic": rec.get("traffic_bytes_per_launch") if rec else None,
+        "kernel": dom_name,
         "algorithmic_bytes": dom["bytes"] / dom["launches"],
-        "valu_slots_per_mac": dom["ops"], "avg_launch_ms": dom["ms"] / dom["launches"],
+        "valu_slots_per_mac": dom["ops"],
+        "issued_valu_per_mac": rec.get("issued_valu_per_mac") if rec else None,
+        "counters_from": ("profiles/roofline_counters.json @ %s" % rec.get("commit")) if rec else None,
+        "avg_launch_ms": dom["ms"] / dom["launches"],
         "launches": dom["launches"], "mac_per_s": dom["macs"] / (dom["ms"] * 1e-3),
         "time_share": dom["ms"] / sum(g["ms"] for g in groups.values()),
     }
+    if args.dump_kernels:
+        with open(args.dump_kernels, "w") as f:
+            json.dump({"workload_key": workload_key, "steps": args.steps, "warmup": args.warmup,
+                       "kernels": {(k[0] if isinstance(k, tuple) else k): dict(
+                           launches_per_step=g["launches"] // args.steps, macs_per_step=g["macs"] // args.steps,
+                           algorithmic_bytes_per_step=g["bytes"] // args.steps, slots_per_mac=g["ops"],
+                           avg_launch_ms_events=g["ms"] / g["launches"]) for k, g in groups.items()}}, f, indent=1)
 
-    if args.grad and dom_key[0] == 3:
+    if args.grad and dom["plan_kernel"] == 3:
         # three bfloat16 MFMA passes per FP32 x FP8 product (g is split exactly into three bfloat16 pieces):
         # issued flops = 3 x 2 per masked MAC, against the dense bfloat16 peak of the matrix cores
         issued = dom["macs"] * 6 / (dom["ms"] * 1e-3)
@@ -293,6 +358,31 @@ def main():
                          "kernel": "lba_grad_dense_kernel<%s> (v_mfma_f32_32x32x16_bf16, 3 passes)" % args.grad,
                          "algorithmic_tflops": dom["macs"] * 2 / (dom["ms"] * 1e-3) / 1e12, "valu_slots_per_mac": None,
                          "peak_measured": None, "frac_of_measured": None})
+
+    if args.results and not (args.bwd or args.grad or in_fmt or args.implicit):
+        from paper_2401_14110_amd.digest import digest
+        gold = {}
+        for line in open(os.path.join(ROOT, "tests", "golden", "full_digests.txt")):
+            f = line.split()
+            if f and not line.startswith("#"):
+                gold[(f[0], int(f[1]), f[5], f[6], int(f[7]))] = (int(f[8], 16), int(f[9], 16), int(f[10], 16))
+        with open(args.results, "a") as out_f:
+            for i, l in enumerate(layers):
+                launch(l)
+                torch.cuda.synchronize()
+                d = digest(l["C"])
+                want = gold.get((args.workload, i, ",".join(map(str, l["qp"])), ",".join(map(str, l["qa"])), order))
+                if want is None:
+                    verdict = "no offline oracle checksum for this case"
+                elif (digest(l["A"]), digest(l["B"])) != want[:2]:
+                    verdict = "inputs differ from the ones the oracle checksum was made from"
+                else:
+                    verdict = "bit-exact (complete output)" if d == want[2] else "MISMATCH"
+                out_f.write(json.dumps({"workload": args.workload, "layer": i, "name": l["name"], "M": l["M"], "N": l["N"], "K": l["K"],
+                                        "qprod": l["qp"], "qacc": l["qa"], "round": args.round, "order": args.order,
+                                        "kernel": l.get("kname"), "slots_per_mac": l["plan"]["valu_per_mac_x100"] / 100.0,
+                                        "ms": per_layer_ms[i], "mac_per_s": l["macs"] / (per_layer_ms[i] * 1e-3),
+                                        "digest_C": "%016x" % d, "parity": verdict}) + "\n")
 
     if args.per_layer:
         for i, l in enumerate(layers):
@@ -304,6 +394,7 @@ def main():
     out = {
         "metric": "simulated LBA-MACs/sec on one MI355X", "value": value, "unit": "LBA-MAC/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "ms_per_step_median_events": median_ms, "value_median_events": total_macs / (median_ms * 1e-3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32-carrier/fp8-in",
         "data": "synthetic",
         "config": {"workload": {"resnet50": "ResNet-50 forward, batch 64, 224x224: 53 convs (im2col) + FC as 54 LBA GEMMs",

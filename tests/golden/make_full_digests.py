@@ -1,4 +1,4 @@
-"""Writes tests/golden/full_digests.txt: checksums (tests/digest.py) of the complete oracle outputs of the
+"""Writes tests/golden/full_digests.txt: checksums (paper_2401_14110_amd/digest.py) of the complete oracle outputs of the
 benchmark configurations, with the checksums of the input codes they were computed from.  Calls only the
 input generators and oracle/ (never the HIP library).  Run from the repository root:
 
@@ -20,7 +20,7 @@ sys.path.insert(0, os.path.dirname(HERE))
 
 import torch  # noqa: E402
 
-from digest import digest  # noqa: E402
+from paper_2401_14110_amd.digest import digest  # noqa: E402
 from oracle import lba_ref  # noqa: E402
 from paper_2401_14110_amd import inputs  # noqa: E402
 

@@ -11,7 +11,7 @@ import os
 import pytest
 import torch
 
-from digest import digest
+from paper_2401_14110_amd.digest import digest
 from paper_2401_14110_amd import binding as lb
 from paper_2401_14110_amd import inputs
 

@@ -55,11 +55,11 @@ def test_layer_lists():
 
 
 def test_checksum_function_and_golden_file():
-    """tests/digest.py (the checksum the full-size GPU checks use) on the CPU: position-sensitive, independent of
+    """paper_2401_14110_amd/digest.py (the checksum the full-size GPU checks use) on the CPU: position-sensitive, independent of
     the chunking; the golden file holds one row per GEMM of the benchmark configurations."""
     import os
     import torch
-    from digest import digest
+    from paper_2401_14110_amd.digest import digest
     g = torch.Generator().manual_seed(5)
     x = torch.randint(0, 256, (70001,), dtype=torch.uint8, generator=g)
     f = torch.randn((333, 77), generator=g)
