@@ -1,44 +1,10 @@
-// lba_bwd.hip -- instantiations of lba_fast_bwd_kernel (the recompute call in the scaled domain).
-#include "lba_device.h"
-#include "lba_launch.h"
+// lba_bwd.hip -- instantiations of lba_fast_bwd_kernel (the recompute call in the scaled domain) for floor
+// rounding; the nearest-even ones are in lba_bwd_rne.hip.
+#include "lba_launch_bwd.h"
 
 namespace lba {
 hipError_t launch_fast_bwd(const Plan& pl, hipStream_t st) {
-    const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
-    const bool uf = pl.kp.uf_mask != nullptr || pl.kp.uf_mask2 != nullptr;
-    if (pl.amode) {                                        // im2col rows / other operand formats: sequential order only
-#define LBA_BWD1(PM, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, LBA_ORDER_SEQ, UF, 1>), grid, block, 0, st, pl.kp)
-        if (pl.order != LBA_ORDER_SEQ) return hipErrorInvalidValue;
-        switch (pl.prod_mode) {
-            case PM_FLUSH:       if (uf) LBA_BWD1(PM_FLUSH, true); else LBA_BWD1(PM_FLUSH, false); break;
-            case PM_FLUSH_CLAMP: if (uf) LBA_BWD1(PM_FLUSH_CLAMP, true); else LBA_BWD1(PM_FLUSH_CLAMP, false); break;
-            case PM_TRUNC:       if (uf) LBA_BWD1(PM_TRUNC, true); else LBA_BWD1(PM_TRUNC, false); break;
-            case PM_TRUNC_CLAMP: if (uf) LBA_BWD1(PM_TRUNC_CLAMP, true); else LBA_BWD1(PM_TRUNC_CLAMP, false); break;
-            default: return hipErrorInvalidValue;
-        }
-#undef LBA_BWD1
-        return hipGetLastError();
-    }
-    if (pl.mix_tail > 0) {                                 // sequential order: mixed grid
-        if (pl.order != LBA_ORDER_SEQ) return hipErrorInvalidValue;
-        const dim3 mgrid(pl.grid_x, 1, 1);
-#define LBA_BWDM(PM) do { if (uf) hipLaunchKernelGGL((lba_fast_bwd_mixed_kernel<PM, true>), mgrid, block, 0, st, pl.kp); \
-                          else    hipLaunchKernelGGL((lba_fast_bwd_mixed_kernel<PM, false>), mgrid, block, 0, st, pl.kp); } while (0)
-        if (pl.prod_mode == PM_FLUSH)            LBA_BWDM(PM_FLUSH);
-        else if (pl.prod_mode == PM_FLUSH_CLAMP) LBA_BWDM(PM_FLUSH_CLAMP);
-        else return hipErrorInvalidValue;
-#undef LBA_BWDM
-        return hipGetLastError();
-    }
-#define LBA_BWD(PM, ORDER, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, ORDER, UF>), grid, block, 0, st, pl.kp)
-    if (pl.order == LBA_ORDER_CHUNK16) {
-        if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD(PM_FLUSH, LBA_ORDER_CHUNK16, true); else LBA_BWD(PM_FLUSH, LBA_ORDER_CHUNK16, false); }
-        else                          { if (uf) LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_CHUNK16, true); else LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_CHUNK16, false); }
-    } else {
-        if (pl.prod_mode == PM_FLUSH) { if (uf) LBA_BWD(PM_FLUSH, LBA_ORDER_SEQ, true); else LBA_BWD(PM_FLUSH, LBA_ORDER_SEQ, false); }
-        else                          { if (uf) LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_SEQ, true); else LBA_BWD(PM_FLUSH_CLAMP, LBA_ORDER_SEQ, false); }
-    }
-#undef LBA_BWD
-    return hipGetLastError();
+    if (pl.round != LBA_ROUND_FLOOR) return launch_fast_bwd_rne(pl, st);
+    return launch_fast_bwd_rounding<LBA_ROUND_FLOOR>(pl, st);
 }
 }  // namespace lba

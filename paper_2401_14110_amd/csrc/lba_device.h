@@ -40,6 +40,7 @@ __device__ __forceinline__ void set_round_ninf()    { asm volatile("s_setreg_imm
 __device__ __forceinline__ void set_round_zero()    { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 3\n\ts_nop 1" ::: "memory"); }
 // the same two without the memory clobber, for inner loops whose mode-dependent operations are all
 // volatile assembly themselves (volatile statements keep their order; loads may still move across)
+__device__ __forceinline__ void set_round_nearest_nm() { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 0\n\ts_nop 1"); }
 __device__ __forceinline__ void set_round_pinf_nm() { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 1\n\ts_nop 1"); }
 __device__ __forceinline__ void set_round_ninf_nm() { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 2\n\ts_nop 1"); }
 __device__ __forceinline__ void set_round_zero_nm() { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 3\n\ts_nop 1"); }
@@ -768,24 +769,174 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_mixed_kernel
 }
 
 // ---------------------------------------------------------------------------------------------
-// fast recompute kernel: forward chain + event planes (floor, sequential order, Q_prod can flush)
+// fast recompute kernel: forward chain + event planes (Q_prod can flush; floor or nearest-even)
 // ---------------------------------------------------------------------------------------------
-// Same scaled domain as lba_fast_kernel, so both underflows are hardware flushes, and every decision
-// is exact under the toward-zero mode:
-//   OF_k  <=>  |t| >= R_OF  <=>  the clamped, truncated sum has magnitude exactly R_OF
-//   product underflow  <=>  the flushed product is 0 although both operands are non-zero
-//   accumulator underflow  <=>  the flushed sum is 0, the product is not, and the exact sum is not
-//       zero; the exact sum is zero only if p*kc == -S with S != 0, and then p*kc is a normal number
-//       that a plain multiply reproduces exactly
+// Same scaled domain as lba_fast_kernel.  The wave runs with FP32 denormals flushed on INPUT but kept on OUTPUT
+// (MODE.FP_DENORM = 2): a sum below the accumulator's R_UF (2^-126 here) comes out of the fused multiply-add as a
+// denormal number, which is exactly the accumulator-underflow event (t != 0 and |t| < R_UF: an exact zero sum is
+// not a denormal), and the next instruction that reads it takes it as zero, which is the flush.  Every non-zero
+// sum below 2^-126 is representable there: with S != 0 a sum of an (M+1)-bit and a product's <= 12-bit value is
+// zero or at least 2^-126-23 in magnitude, and with S = 0 it is the product itself, at least 2^-126 in the
+// product's domain, i.e. 2^(c_a - c_p - 126) here (the planner admits c_p - c_a <= 23).
+//   OF_k  <=>  |t| >= R_OF.  Floor: the clamped, truncated sum has magnitude exactly R_OF.  Nearest-even: decided
+//         on a second sum rounded toward zero (a sum just below R_OF may round up to it without being an overflow).
+//   product underflow  <=>  the product reads as zero although both operands are non-zero
+//   accumulator underflow  <=>  the sum is a denormal number
+// Nearest-even: the sum is rounded once to 24 bits and then to M+1 bits by bit manipulation (the planner admits
+// the formats for which that equals one rounding); a denormal sum is flushed by one multiply by 1 first.
 // One 32-bit word per chain and k-tile: bits are shifted in (first k highest) and reversed at the end.
+// A k-tile that starts with every |S| of the wave below R_OF - BK * max|p| cannot overflow: it skips the clamp
+// and the overflow test (its OF words are zero), and with no underflow plane asked for it is the forward tile.
 // Chunked order: after the 16th step of a chunk the chunk sum S joins the second-level sum,
-// T <- Q_acc(T + S) with its own two event bits, and S restarts from 0.  T and S are values of Q_acc's
-// grid (zero or normal numbers), so T + S is exactly zero iff S == -T.  The extra registers (T and the
-// second-level words) are paid for with two instead of four waves per SIMD.
-// UF = false (no underflow plane asked for): the underflow tests are dropped, and under the sequential
-// order a k-tile that starts with every |S| of the wave below R_OF - BK * max|p| cannot overflow at all:
-// it runs the forward kernel's clamp-free tile and its OF words are zero.
-template <int TM, int TN, int PM, int ORDER, bool UF, int AMODE>
+// T <- Q_acc(T + S) with its own two event bits, and S restarts from 0; the test above is made on T.
+__device__ __forceinline__ void set_denorm_out_f32() { asm volatile("s_setreg_imm32_b32 hwreg(HW_REG_MODE, 4, 2), 2\n\ts_nop 1" ::: "memory"); }
+
+// lane mask of the lanes whose word is a denormal number (the bit pattern is tested, whatever the wave's mode)
+__device__ __forceinline__ uint64_t ballot_denormal(float x, uint32_t cls) {
+    uint64_t m;
+    asm("v_cmp_class_f32 %0, %1, %2" : "=s"(m) : "v"(x), "v"(cls));
+    return m;
+}
+
+struct BwdConst {
+    float kc, rof, rofp, one;
+    uint32_t mask, maskp, half, cls;
+    int sh;
+};
+
+// nearest-even at M+1 bits of a 24-bit sum that may be a denormal number (flushed first: one multiply by 1)
+// (FLUSHED: the wave flushes denormal results itself, nothing to do)
+__device__ __forceinline__ float bwd_round(float td, const BwdConst& c, int RND, bool FLUSHED) {
+    if (RND == LBA_ROUND_FLOOR) return __uint_as_float(__float_as_uint(td) & c.mask);
+    float tf = td;
+    if (!FLUSHED) asm("v_mul_f32 %0, %1, %2" : "=v"(tf) : "v"(td), "v"(c.one));
+    const uint32_t u = __float_as_uint(tf);
+    return __uint_as_float((u + c.half + ((u >> c.sh) & 1u)) & c.mask);
+}
+
+// One k-tile with event bits.  QUIET: no sum of the tile can reach R_OF (no clamp, no overflow test).
+template <int TM, int TN, int PM, int RND, int ORDER, bool UF, bool QUIET, int BM, int BN>
+__device__ __forceinline__ void bwd_tile(float (&acc)[TM][TN], float (&top)[TM][TN], uint32_t (&wof)[TM][TN], uint32_t (&wuf)[TM][TN],
+                                         uint32_t (&wof2)[TM][TN], uint32_t (&wuf2)[TM][TN], const float* As, const float* Bs,
+                                         int tx, int ty, const BwdConst& c) {
+    constexpr bool DIRECTED = (RND != LBA_ROUND_FLOOR) && !QUIET;      // a second, toward-zero sum decides the overflow
+#pragma unroll 4
+    for (int k = 0; k < 32; ++k) {
+        float a[TM], b[TN];
+        read_operands<TM, TN, BM, BN>(As, Bs, k, tx, ty, a, b);
+        // all tests produce 64-bit lane masks; the event logic runs on the scalar unit
+        uint64_t nza[TM], nzb[TN];
+        if (UF) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) nza[i] = __builtin_amdgcn_ballot_w64(a[i] != 0.0f);
+#pragma unroll
+            for (int j = 0; j < TN; ++j) nzb[j] = __builtin_amdgcn_ballot_w64(b[j] != 0.0f);
+        }
+        // the chains advance in groups of NI rows (8 chains for the 4 x 4 lane block): enough independent work per
+        // phase, half the temporaries
+        constexpr int NI = TM >= 2 ? 2 : 1;
+#pragma unroll
+        for (int i0 = 0; i0 < TM; i0 += NI) {
+            float q[NI][TN], td[NI][TN], tz[NI][TN];
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) q[i][j] = a[i0 + i] * b[j];   // below Q_prod's R_UF: a denormal, read as zero from here on
+            if (PM == PM_TRUNC || PM == PM_TRUNC_CLAMP) {                  // Q_prod's mantissa, by truncation
+#pragma unroll
+                for (int i = 0; i < NI; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) q[i][j] = __uint_as_float(__float_as_uint(q[i][j]) & c.maskp);
+            }
+            if (PM == PM_FLUSH_CLAMP || PM == PM_TRUNC_CLAMP) {
+#pragma unroll
+                for (int i = 0; i < NI; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) q[i][j] = med3(q[i][j], -c.rofp, c.rofp);
+            }
+            if (DIRECTED) {
+                set_round_zero_nm();
+#pragma unroll
+                for (int i = 0; i < NI; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(tz[i][j]) : "v"(q[i][j]), "v"(c.kc), "v"(acc[i0 + i][j]));
+                set_round_nearest_nm();
+#pragma unroll
+                for (int i = 0; i < NI; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(td[i][j]) : "v"(q[i][j]), "v"(c.kc), "v"(acc[i0 + i][j]));
+            } else {
+                // the wave's rounding mode never changes in this copy of the loop: toward zero (floor) or nearest
+#pragma unroll
+                for (int i = 0; i < NI; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) asm("v_fma_f32 %0, %1, %2, %3" : "=v"(td[i][j]) : "v"(q[i][j]), "v"(c.kc), "v"(acc[i0 + i][j]));
+            }
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    uint64_t uf = 0;
+                    if (UF) {
+                        const uint64_t zq = __builtin_amdgcn_ballot_w64(q[i][j] == 0.0f);
+                        uf = (zq & nza[i0 + i] & nzb[j]) | ballot_denormal(td[i][j], c.cls);
+                    }
+                    float tsum = bwd_round(td[i][j], c, RND, !UF);
+                    if (!QUIET) {
+                        tsum = med3(tsum, -c.rof, c.rof);
+                        const uint64_t of = DIRECTED ? __builtin_amdgcn_ballot_w64(__builtin_fabsf(tz[i][j]) >= c.rof)
+                                                     : __builtin_amdgcn_ballot_w64(__builtin_fabsf(tsum) == c.rof);
+                        // word <- 2 * word + (this lane's bit of the mask): add with the mask as carry-in
+                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof[i0 + i][j]) : "s"(of) : "vcc");
+                    }
+                    if (UF) asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wuf[i0 + i][j]) : "s"(uf) : "vcc");
+                    acc[i0 + i][j] = tsum;
+                }
+        }
+        if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
+            float ud[TM][TN], uz[TM][TN];
+            if (DIRECTED) {
+                set_round_zero_nm();
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) asm volatile("v_add_f32 %0, %1, %2" : "=v"(uz[i][j]) : "v"(top[i][j]), "v"(acc[i][j]));
+                set_round_nearest_nm();
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) asm volatile("v_add_f32 %0, %1, %2" : "=v"(ud[i][j]) : "v"(top[i][j]), "v"(acc[i][j]));
+            } else {
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) asm("v_add_f32 %0, %1, %2" : "=v"(ud[i][j]) : "v"(top[i][j]), "v"(acc[i][j]));
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    float u = bwd_round(ud[i][j], c, RND, !UF);
+                    if (!QUIET) {
+                        u = med3(u, -c.rof, c.rof);
+                        const uint64_t of = DIRECTED ? __builtin_amdgcn_ballot_w64(__builtin_fabsf(uz[i][j]) >= c.rof)
+                                                     : __builtin_amdgcn_ballot_w64(__builtin_fabsf(u) == c.rof);
+                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof2[i][j]) : "s"(of) : "vcc");
+                    } else {
+                        wof2[i][j] <<= 1;                                   // the chunk's (zero) bit
+                    }
+                    if (UF) {
+                        const uint64_t uf = ballot_denormal(ud[i][j], c.cls);
+                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wuf2[i][j]) : "s"(uf) : "vcc");
+                    }
+                    top[i][j] = u;
+                    acc[i][j] = 0.0f;
+                }
+        }
+    }
+}
+
+template <int TM, int TN, int PM, int RND, int ORDER, bool UF, int AMODE>
 __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, const int m0, const int n0) {
     constexpr int BK = 32, BM = 16 * TM, BN = 16 * TN;
     constexpr int STAGE = BK * (BM + BN);
@@ -799,16 +950,18 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
     float* pC = p.C ? p.C + (int64_t)blockIdx.z * p.stride_c : nullptr;
 
     const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
-    set_flush_f32();
+    if (UF) set_denorm_out_f32();                              // without an underflow plane: plain flushing, as the forward kernel
+    else    set_flush_f32();
     if (AMODE) set_denorm_f16();
-    set_round_zero();
+    if (RND == LBA_ROUND_FLOOR) set_round_zero();
 
-    // kc_up / up: the same product and accumulator moved up by 2^60, where neither can flush
-    float kc = p.kc, rof = p.rof_a, rofp = p.rof_p, kc_up = p.kc * 0x1p60f, up = 0x1p60f;
-    uint32_t mask = p.mask_a, maskp = p.mask_p;
-    asm volatile("" : "+v"(kc), "+v"(rof), "+v"(rofp), "+v"(mask), "+v"(maskp), "+v"(kc_up), "+v"(up));
+    BwdConst c;
+    c.kc = p.kc; c.rof = p.rof_a; c.rofp = p.rof_p; c.one = 1.0f; c.mask = p.mask_a; c.maskp = p.mask_p; c.half = p.half_a;
+    c.cls = 0x90u;                                             // -denormal | +denormal
+    c.sh = p.sh_a;
+    asm volatile("" : "+v"(c.kc), "+v"(c.rof), "+v"(c.rofp), "+v"(c.one), "+v"(c.mask), "+v"(c.maskp), "+v"(c.half), "+v"(c.cls));
     FastConst fc;
-    fc.kc = kc; fc.rof = rof; fc.rofp = rofp; fc.mask = mask; fc.half = 0u; fc.sh = p.sh_a; fc.maskp = maskp; fc.halfp = p.half_p; fc.shp = p.sh_p;
+    fc.kc = c.kc; fc.rof = c.rof; fc.rofp = c.rofp; fc.mask = c.mask; fc.half = c.half; fc.sh = p.sh_a; fc.maskp = c.maskp; fc.halfp = p.half_p; fc.shp = p.sh_p;
     float thresh = p.fast_thresh;
     asm volatile("" : "+v"(thresh));
 
@@ -841,133 +994,30 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
             else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
             fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
-        bool quiet = false;                                    // no sum of this tile can reach R_OF
-        if (!UF && ORDER == LBA_ORDER_SEQ) {
-            float mx = 0.0f;
+        // no sum of this tile can reach R_OF (chunked order: the test is on the second-level sums; a first-level
+        // sum starts from 0 and is covered by the same bound)
+        float mx = 0.0f;
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; j += 2)
-                    mx = __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(acc[i][j]), __builtin_fabsf(acc[i][j + 1])));
-            quiet = __all(mx < thresh);
-        }
-        if (quiet) {
-            fast_tile<PM, LBA_ROUND_FLOOR, LBA_ORDER_SEQ, false, TM, TN, BK, BM, BN>(acc, top, As, Bs, tx, ty, fc);
-        } else if (!UF) {
-#pragma unroll 4
-            for (int k = 0; k < BK; ++k) {
-                float a[TM], b[TN];
-                read_operands<TM, TN, BM, BN>(As, Bs, k, tx, ty, a, b);
-                float q[TM][TN];
+            for (int j = 0; j < TN; j += 2)
+                mx = (ORDER == LBA_ORDER_CHUNK16)
+                         ? __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(top[i][j]), __builtin_fabsf(top[i][j + 1])))
+                         : __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(acc[i][j]), __builtin_fabsf(acc[i][j + 1])));
+        const bool quiet = __all(mx < thresh);
+        if (quiet && !UF) {
+            constexpr int FRND = RND == LBA_ROUND_FLOOR ? LBA_ROUND_FLOOR : LBA_ROUND_RNE;
+            fast_tile<PM, FRND, ORDER, false, TM, TN, BK, BM, BN>(acc, top, As, Bs, tx, ty, fc);
+            if (ORDER == LBA_ORDER_CHUNK16) {
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) q[i][j] = a[i] * b[j];
-                if (PM == PM_TRUNC || PM == PM_TRUNC_CLAMP) {          // Q_prod's mantissa, by truncation
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) q[i][j] = __uint_as_float(__float_as_uint(q[i][j]) & maskp);
-                }
-                if (PM == PM_FLUSH_CLAMP || PM == PM_TRUNC_CLAMP) {
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) q[i][j] = med3(q[i][j], -rofp, rofp);
-                }
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        float tsum = __builtin_fmaf(q[i][j], kc, acc[i][j]);
-                        tsum = __uint_as_float(__float_as_uint(tsum) & mask);
-                        tsum = med3(tsum, -rof, rof);
-                        const uint64_t of = __builtin_amdgcn_ballot_w64(__builtin_fabsf(tsum) == rof);
-                        acc[i][j] = tsum;
-                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof[i][j]) : "s"(of) : "vcc");
-                    }
-                if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int j = 0; j < TN; ++j) {
-                            float u = top[i][j] + acc[i][j];
-                            u = __uint_as_float(__float_as_uint(u) & mask);
-                            u = med3(u, -rof, rof);
-                            const uint64_t of = __builtin_amdgcn_ballot_w64(__builtin_fabsf(u) == rof);
-                            top[i][j] = u;
-                            acc[i][j] = 0.0f;
-                            asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof2[i][j]) : "s"(of) : "vcc");
-                        }
-                }
+                    for (int j = 0; j < TN; ++j) wof2[i][j] <<= 2;         // the two chunks' (zero) bits
             }
-        } else
-#pragma unroll 4
-        for (int k = 0; k < BK; ++k) {
-            float a[TM], b[TN];
-            read_operands<TM, TN, BM, BN>(As, Bs, k, tx, ty, a, b);
-            // all tests produce 64-bit lane masks; the event logic runs on the scalar unit
-            uint64_t nza[TM], nzb[TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) nza[i] = __builtin_amdgcn_ballot_w64(a[i] != 0.0f);
-#pragma unroll
-            for (int j = 0; j < TN; ++j) nzb[j] = __builtin_amdgcn_ballot_w64(b[j] != 0.0f);
-            float q[TM][TN], w[TM][TN], su[TM][TN];
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) q[i][j] = a[i] * b[j];            // flushed below Q_prod's R_UF
-            if (PM == PM_TRUNC || PM == PM_TRUNC_CLAMP) {              // a non-zero product stays non-zero
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) q[i][j] = __uint_as_float(__float_as_uint(q[i][j]) & maskp);
-            }
-            if (PM == PM_FLUSH_CLAMP || PM == PM_TRUNC_CLAMP) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) q[i][j] = med3(q[i][j], -rofp, rofp);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) { w[i][j] = q[i][j] * kc_up; su[i][j] = acc[i][j] * up; }   // exact, never flushed
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) {
-                    const uint64_t cancel = __builtin_amdgcn_ballot_w64(w[i][j] == -su[i][j]);   // exact sum is zero (or p = S = 0)
-                    float tsum = __builtin_fmaf(q[i][j], kc, acc[i][j]);       // truncated, flushed exact sum
-                    tsum = __uint_as_float(__float_as_uint(tsum) & mask);
-                    tsum = med3(tsum, -rof, rof);
-                    const uint64_t zq = __builtin_amdgcn_ballot_w64(q[i][j] == 0.0f);
-                    const uint64_t zt = __builtin_amdgcn_ballot_w64(tsum == 0.0f);
-                    const uint64_t of = __builtin_amdgcn_ballot_w64(__builtin_fabsf(tsum) == rof);
-                    const uint64_t uf = (zq & nza[i] & nzb[j]) | (zt & ~zq & ~cancel);
-                    acc[i][j] = tsum;
-                    // word <- 2 * word + (this lane's bit of the mask): add with the mask as carry-in
-                    asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof[i][j]) : "s"(of) : "vcc");
-                    asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wuf[i][j]) : "s"(uf) : "vcc");
-                }
-            if (ORDER == LBA_ORDER_CHUNK16 && (k & 15) == 15) {
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) {
-                        const uint64_t cancel = __builtin_amdgcn_ballot_w64(acc[i][j] == -top[i][j]);
-                        float u = top[i][j] + acc[i][j];                        // truncated, flushed exact sum
-                        u = __uint_as_float(__float_as_uint(u) & mask);
-                        u = med3(u, -rof, rof);
-                        const uint64_t zu = __builtin_amdgcn_ballot_w64(u == 0.0f);
-                        const uint64_t of = __builtin_amdgcn_ballot_w64(__builtin_fabsf(u) == rof);
-                        const uint64_t uf = zu & ~cancel;
-                        top[i][j] = u;
-                        acc[i][j] = 0.0f;
-                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wof2[i][j]) : "s"(of) : "vcc");
-                        asm volatile("v_addc_co_u32 %0, vcc, %0, %0, %1" : "+v"(wuf2[i][j]) : "s"(uf) : "vcc");
-                    }
-            }
+        } else if (quiet) {
+            bwd_tile<TM, TN, PM, RND, ORDER, UF, true, BM, BN>(acc, top, wof, wuf, wof2, wuf2, As, Bs, tx, ty, c);
+        } else {
+            bwd_tile<TM, TN, PM, RND, ORDER, UF, false, BM, BN>(acc, top, wof, wuf, wof2, wuf2, As, Bs, tx, ty, c);
         }
         store_event_words(p.of_mask, UF ? p.uf_mask : nullptr, t, 32, p.K - t * BK, wof, wuf, m0, n0, tx, ty, p);
         if (ORDER == LBA_ORDER_CHUNK16 && ((t & 15) == 15 || !more)) {
@@ -983,7 +1033,8 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
         }
         __syncthreads();
     }
-    set_round_nearest();
+    if (RND == LBA_ROUND_FLOOR) set_round_nearest();
+    set_flush_f32();
 
     if (pC) {
 #pragma unroll
@@ -995,7 +1046,7 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 const float s = (ORDER == LBA_ORDER_CHUNK16) ? top[i][j] : acc[i][j];
-                v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);
+                v[j] = (s == 0.0f) ? 0.0f : __builtin_ldexpf(s, p.out_exp);   // a denormal sum reads as zero here
             }
             float* dst = pC + (int64_t)m * p.N + n;
             if (p.c_vec && n + TN - 1 < p.N) {
@@ -1010,25 +1061,25 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
     }
 }
 
-template <int PM, int ORDER, bool UF, int AMODE = 0>
+template <int PM, int RND, int ORDER, bool UF, int AMODE = 0>
 __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_fast_bwd_kernel(const KParams p) {
     __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
-    fast_bwd_body<4, 4, PM, ORDER, UF, AMODE>(p, smem, blockIdx.x * 64, blockIdx.y * 64);
+    fast_bwd_body<4, 4, PM, RND, ORDER, UF, AMODE>(p, smem, blockIdx.x * 64, blockIdx.y * 64);
 }
 
 // The sequential order on E4M3 matrices on the mixed grid of lba_fast_mixed_kernel: 64 x 64 workgroups for the
 // full rounds, 32 x 32 ones on the last rows.
-template <int PM, bool UF>
+template <int PM, int RND, bool UF>
 __global__ void __launch_bounds__(256, 4) lba_fast_bwd_mixed_kernel(const KParams p) {
     __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
     const int b = blockIdx.x;
     if (b < p.mix_main) {                                      // uniform
         const int by = b / p.mix_gx_main, bx = b - by * p.mix_gx_main;
-        fast_bwd_body<4, 4, PM, LBA_ORDER_SEQ, UF, 0>(p, smem, bx * 64, by * 64);
+        fast_bwd_body<4, 4, PM, RND, LBA_ORDER_SEQ, UF, 0>(p, smem, bx * 64, by * 64);
     } else {
         const int t = b - p.mix_main;
         const int by = t / p.mix_gx_tail, bx = t - by * p.mix_gx_tail;
-        fast_bwd_body<2, 2, PM, LBA_ORDER_SEQ, UF, 0>(p, smem, p.mix_m_main + bx * 32, by * 32);
+        fast_bwd_body<2, 2, PM, RND, LBA_ORDER_SEQ, UF, 0>(p, smem, p.mix_m_main + bx * 32, by * 32);
     }
 }
 

@@ -43,9 +43,9 @@ static void plan_kernel_name(const Plan& pl, bool uf, char* buf, size_t n) {
     if (pl.events == 2) {
         snprintf(buf, n, pl.mix_tail > 0 ? "lba_fast_diff_mixed_kernel<%d, %d>" : "lba_fast_diff_kernel<%d, %d>", pm, ord);
     } else if (pl.events) {
-        if (pl.amode)             snprintf(buf, n, "lba_fast_bwd_kernel<%d, 0, %s, 1>", pm, b);
-        else if (pl.mix_tail > 0) snprintf(buf, n, "lba_fast_bwd_mixed_kernel<%d, %s>", pm, b);
-        else                      snprintf(buf, n, "lba_fast_bwd_kernel<%d, %d, %s, 0>", pm, ord, b);
+        if (pl.amode)             snprintf(buf, n, "lba_fast_bwd_kernel<%d, 0, 0, %s, 1>", pm, b);
+        else if (pl.mix_tail > 0) snprintf(buf, n, "lba_fast_bwd_mixed_kernel<%d, %d, %s>", pm, pl.round, b);
+        else                      snprintf(buf, n, "lba_fast_bwd_kernel<%d, %d, %d, %s, 0>", pm, pl.round, ord, b);
     } else if (pl.rne_odd) {
         snprintf(buf, n, "lba_fast_kernel<4, 4, %d, %d, 3, %d, 0>", pl.bk, pm, ord);
     } else {

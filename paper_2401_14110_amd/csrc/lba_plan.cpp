@@ -249,9 +249,11 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     // a narrower product mantissa is one bit mask (truncation) or bfe / add3 / and (nearest-even) on the
     // exact FP32 product (the recompute call: truncation only)
     bool fast = !prod_round || !events || (qp.round == LBA_ROUND_FLOOR && order == LBA_ORDER_SEQ);
-    // the recompute call has a scaled-domain kernel for floor rounding when Q_prod can underflow
-    // (its product-underflow test is the multiply's flush); anything else takes the general kernel
-    if (events && (qa.round != LBA_ROUND_FLOOR || !flush)) fast = false;
+    // the recompute call has a scaled-domain kernel when Q_prod can underflow (its product-underflow test is
+    // the multiply's flush); nearest-even accumulators on E4M3 matrices whose products Q_prod does not round
+    // (and only where rounding twice is exact, below); anything else takes the general kernel
+    if (events && !flush) fast = false;
+    if (events && qa.round != LBA_ROUND_FLOOR && (events == 2 || prod_round || conv || in.ea != 4 || in.eb != 4)) fast = false;
     bool rne_odd = false;
     if (fast && qa.round == LBA_ROUND_RNE && !rne_fast_ok(qp, qa, clamp, flush, nouf_a, in)) {
         // E4M3 matrices, Q_prod without mantissa rounding, forward call: the round-to-odd variant
@@ -269,8 +271,11 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         if (clamp) low = (top_exp(qp) + 1 <= in.min_lsb) ? top_exp(qp) : std::min(in.min_lsb, top_exp(qp) - qp.man_bits);
         if (low + c_a_dom < -126) fast = false;
     }
-    // the recompute kernel also forms p * kc * 2^60 and S * 2^60
-    if (fast && events && (std::abs(c_a_dom - c_p_dom) > 60 || top_exp(qa) + c_a_dom + 61 > 126)) fast = false;
+    // the DIFF kernel also forms p * kc * 2^60 and S * 2^60
+    if (fast && events == 2 && (std::abs(c_a_dom - c_p_dom) > 60 || top_exp(qa) + c_a_dom + 61 > 126)) fast = false;
+    // the recompute kernel reads an accumulator underflow off a denormal sum: with S = 0 the sum is the product,
+    // at least 2^-126 in its own domain, which must not fall below the smallest denormal in the accumulator's
+    if (fast && events && events != 2 && c_p_dom - c_a_dom > 23) fast = false;
     // the DIFF plane's scaled-domain kernel: E4M3 operands, Q_prod without mantissa rounding
     if (events == 2 && (prod_round || nouf_a || conv || in.ea != 4 || in.eb != 4)) fast = false;
 
@@ -296,12 +301,18 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         if (qa.round == LBA_ROUND_RNE) slots += (qa.man_bits == 7 && !rne_odd) ? 1 : 4;   // M = 7: cvt to bfloat16 replaces and; else bfe, add3
         if (rne_odd) slots += 4;                                  // second fma, bfe, bfi
         p.valu_per_mac_x100 = slots * 100;
-        if (events)                                              // 5 full-rate + 7 half-rate instructions, + operand tests
-            p.valu_per_mac_x100 = 1950 + (p.prod_mode == PM_FLUSH_CLAMP ? 200 : 0);
+        if (events) {
+            // both planes, a k-tile that cannot overflow: mul, fma, and at full rate; zero test of the product, class
+            // test of the sum, carry-in add at half rate; the operand tests (8 per 16 chains); nearest-even adds the
+            // flushing multiply, bfe, add3.  (A tile that can overflow adds med3, a compare and a carry-in add: 6.)
+            p.valu_per_mac_x100 = 1000 + (qa.round == LBA_ROUND_RNE ? 500 : 0);
+            if (p.prod_mode == PM_FLUSH_CLAMP || p.prod_mode == PM_TRUNC_CLAMP) p.valu_per_mac_x100 += 200;
+            if (p.prod_mode == PM_TRUNC || p.prod_mode == PM_TRUNC_CLAMP) p.valu_per_mac_x100 += 100;
+        }
         if (events == 2)                                         // mul, fma, and, mul, max, min, mul, sub, cmp; med3, addc at half rate
             p.valu_per_mac_x100 = 1300 + (p.prod_mode == PM_FLUSH_CLAMP ? 200 : 0);
         if (order == LBA_ORDER_CHUNK16)                          // add, and [, bfe, add3], zero per 16 steps
-            p.valu_per_mac_x100 += (events ? 1300 : (qa.round == LBA_ROUND_RNE ? 700 : 300)) / 16;
+            p.valu_per_mac_x100 += (events == 2 ? 1300 : events ? 900 : (qa.round == LBA_ROUND_RNE ? 700 : 300)) / 16;
     } else {
         p.kernel = KERNEL_GEN;
         p.prod_mode = PM_FLUSH_CLAMP;

@@ -212,13 +212,18 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     assert q(64, 64, 64, (4, 3, 82, 0), (4, 8, -57, 0x100))["kernel"] == 1
     # recompute call: scaled-domain kernel for floor when Q_prod can underflow, else the general one
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 0
-    assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), with_masks=1)["kernel"] == 1
+    assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), with_masks=1)["kernel"] == 0      # nearest-even: where rounding twice is exact
+    assert q(64, 64, 64, (5, 7, 15, 1), (4, 11, 7, 1), with_masks=1)["kernel"] == 1     # ... not beyond 10 mantissa bits
+    assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), with_masks=2)["kernel"] == 1      # the DIFF plane: floor only
+    assert q(64, 64, 64, (5, 7, 17, 0), (4, 7, -7, 0), with_masks=1)["kernel"] == 1     # products up to 2^24 below R_UF of Q_acc
+    assert q(64, 64, 64, (5, 7, 17, 0), (4, 7, -6, 0), with_masks=1)["kernel"] == 0
     assert q(64, 64, 64, (6, 7, 20, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 1
     # chunked order, forward and recompute
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=1)["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 1), (5, 3, 15, 1), order=1)["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=1, with_masks=1)["kernel"] == 0
-    assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), order=1, with_masks=1)["kernel"] == 1
+    assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), order=1, with_masks=1)["kernel"] == 0
+    assert q(64, 64, 64, (5, 7, 15, 1), (5, 3, 15, 1), order=1, with_masks=1)["kernel"] == 1
     # nearest-even below 7 mantissa bits: scaled kernel only when every inexact FP32 sum overflows
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 3, 7, 1))["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 6, 7, 1))["kernel"] == 0

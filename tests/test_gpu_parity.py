@@ -468,6 +468,50 @@ def test_event_planes_of_the_chunked_order(ref):
                            (5, 7, 15, 0), (4, 7, 7, 0), order=1) == lb.ERR_UNSUPPORTED
 
 
+def test_random_formats_event_planes(ref):
+    # a seeded sweep of the recompute call over formats (both roundings, both orders, with and without the
+    # underflow plane) whose ranges lie near the operands' own, so that overflows, product underflows and
+    # accumulator underflows all occur; operands quiet at the start of the chains and loud at the end, so that
+    # k-tiles with and without a possible overflow both run.  Whichever kernel the planner picks must give the
+    # oracle's C and planes.
+    pyr = random.Random(4242)
+    rng = np.random.default_rng(4242)
+    A = rand_codes(rng, (70, 150), 2, 9); B = rand_codes(rng, (40, 150), 2, 9)
+    A[:, 96:] = rand_codes(rng, (70, 54), 6, 14)
+    tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    picked, events = set(), [0, 0, 0]
+    done = 0
+    while done < 70:
+        Ep, Ea = pyr.randint(3, 6), pyr.choice([3, 3, 4, 4, 4, 5, 6])
+        Mp, Ma = pyr.choice([7, 7, 8, 10, 12]), pyr.choice([3, 5, 7, 7, 8, 10, 11, 16, 23])
+        ba = pyr.randint(-6, 12)
+        bp = ba + pyr.choice([-3, 0, 2, 2, 5, 8, 8, 12, 20, 23, 24, 30])
+        if bp > 126 or (1 << Ep) - bp - 1 > 127 or (1 << Ea) - ba - 1 > 127:
+            continue
+        rnd, order, want_uf = pyr.randint(0, 1), pyr.randint(0, 1), pyr.random() < 0.75
+        qpf, qaf = (Ep, Mp, bp, rnd), (Ea, Ma, ba, rnd)
+        plan = lb.lba_plan_query(70, 40, 150, qpf, qaf, order, 1 if want_uf else 3)
+        picked.add((plan["kernel"], rnd, order))
+        what = (qpf, qaf, order, want_uf, plan["kernel"])
+        if order == 1:
+            got = lb.gemm_bwd_chunked(tA, tB, qpf, qaf, want_uf=want_uf)
+            want = ref.gemm_bwd(A, B, fm(ref, qpf), fm(ref, qaf), order=ref.ORDER_CHUNK16, level2=True)
+        else:
+            got = lb.gemm_bwd(tA, tB, qpf, qaf, want_uf=want_uf)
+            want = ref.gemm_bwd(A, B, fm(ref, qpf), fm(ref, qaf))
+        torch.cuda.synchronize()
+        assert np.array_equal(bits(got[0].cpu().numpy()), bits(want[0])), what + ("C",)
+        for i in range(1, len(want)):
+            if got[i] is None:
+                assert not want_uf and i % 2 == 0
+                continue
+            assert np.array_equal(got[i].cpu().numpy().view(np.uint32), want[i]), what + ("plane %d" % i,)
+        events[0] += int(want[1].any()); events[1] += int(want[2].any()); events[2] += int((want[1] == 0).all(axis=(1, 2)).any())
+        done += 1
+    assert {(0, 0, 0), (0, 0, 1), (0, 1, 0), (0, 1, 1), (1, 1, 0)} <= picked, picked
+    assert events[0] > 15 and events[1] > 20 and events[2] > 10, events
+
+
 def test_overflow_plane_alone(ref):
     # without an underflow plane the recompute call runs its overflow-only variant; under the sequential
     # order k-tiles that cannot overflow take the forward kernel's tile.  Small operands (no event at all),
