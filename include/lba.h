@@ -274,7 +274,9 @@ typedef struct {
     int32_t grid_x, grid_y;           /* workgroups launched                                      */
     int32_t valu_per_mac_x100;        /* kernel 0: full-rate VALU issue slots per MAC of the inner
                                          loop without the accumulator clamp, times 100 (a half-rate
-                                         instruction counts as 2 slots); kernel 1: 0 (not modelled) */
+                                         instruction counts as 2 slots); kernel 1: the budget of a plain
+                                         FMAq step (10 floor, 12 nearest-even, 4 more with event bits), which
+                                         is less than its loop issues */
     int32_t tail_blocks;              /* > 0: mixed grid: grid_x counts grid_x - tail_blocks workgroups of
                                          tile_m x tile_n plus tail_blocks workgroups of 32 x 32 (2 x 2 outputs
                                          per lane) on the last rows; grid_y is 1                            */

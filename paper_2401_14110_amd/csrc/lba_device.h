@@ -1084,7 +1084,7 @@ __global__ void __launch_bounds__(256, 4) lba_fast_bwd_mixed_kernel(const KParam
 }
 
 // Recompute call for the DIFF plane (Sec. 4 "Immediate / DIFF", App. D, eps1 -> 0+) in the scaled domain:
-// floor rounding, E4M3 operands, Q_prod without mantissa rounding, flush kept.  Per step:
+// floor or (where rounding twice is exact) nearest-even rounding, E4M3 operands, Q_prod without mantissa rounding, flush kept.  Per step:
 //   DIFF = [ |S' - S| <= eps2 * |x w| ],  both sides formed 2^60 above the accumulator's domain, where
 // neither can be flushed; eps2 * |x w| has at most 12 + 8 significant bits (exact).  A product that Q_prod
 // flushes leaves S' = S, so the flushed multiply (zero) gives the right bit too.
@@ -1093,7 +1093,7 @@ __global__ void __launch_bounds__(256, 4) lba_fast_bwd_mixed_kernel(const KParam
 // the accumulator's width.  The mode-dependent operations of a step (product, sum, subtraction) are
 // volatile assembly, which keeps them on their side of the two mode writes; everything else is exact.
 // Writes the plane through p.of_mask.
-template <int TM, int TN, int PM, int ORDER>
+template <int TM, int TN, int PM, int RND, int ORDER>
 __device__ __forceinline__ void fast_diff_body(const KParams& p, float* smem, const int m0, const int n0) {
     constexpr int BK = 32, BM = 16 * TM, BN = 16 * TN;
     constexpr int STAGE = BK * (BM + BN);
@@ -1107,11 +1107,19 @@ __device__ __forceinline__ void fast_diff_body(const KParams& p, float* smem, co
 
     const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
     set_flush_f32();
-    set_round_zero();
+    if (RND == LBA_ROUND_FLOOR) set_round_zero();
 
     float kc = p.kc, rof = p.rof_a, rofp = p.rof_p, up = 0x1p60f, ce = p.kc * 0x1p60f * p.diff_eps;
-    uint32_t mask = p.mask_a;
-    asm volatile("" : "+v"(kc), "+v"(rof), "+v"(rofp), "+v"(mask), "+v"(up), "+v"(ce));
+    uint32_t mask = p.mask_a, half = p.half_a;
+    const int sh = p.sh_a;
+    asm volatile("" : "+v"(kc), "+v"(rof), "+v"(rofp), "+v"(mask), "+v"(half), "+v"(up), "+v"(ce));
+    // mantissa rounding of a sum: a bit mask under the toward-zero mode (floor); nearest-even of the 24-bit
+    // nearest-even sum by bit manipulation (the planner admits the formats for which that is one rounding)
+    auto round_sum = [&](float t) -> float {
+        const uint32_t u = __float_as_uint(t);
+        if (RND == LBA_ROUND_FLOOR) return __uint_as_float(u & mask);
+        return __uint_as_float((u + half + ((u >> sh) & 1u)) & mask);
+    };
 
     float acc[TM][TN], accu[TM][TN], top[TM][TN];              // accu = acc * 2^60
     uint32_t wdf[TM][TN], unused[TM][TN];
@@ -1146,12 +1154,12 @@ __device__ __forceinline__ void fast_diff_body(const KParams& p, float* smem, co
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int j = 0; j < TN; ++j) {                          // toward zero
+                    for (int j = 0; j < TN; ++j) {                          // the wave's own mode: toward zero, or nearest
                         float q0, tsum;
                         asm volatile("v_mul_f32 %0, %1, %2" : "=v"(q0) : "v"(a[i]), "v"(b[j]));
                         const float q = (PM == PM_FLUSH_CLAMP) ? med3(q0, -rofp, rofp) : q0;
                         asm volatile("v_fma_f32 %0, %1, %2, %3" : "=v"(tsum) : "v"(q), "v"(kc), "v"(acc[i][j]));
-                        tsum = __uint_as_float(__float_as_uint(tsum) & mask);
+                        tsum = round_sum(tsum);
                         tsum = med3(tsum, -rof, rof);
                         const float su = tsum * up;                         // exact
                         hi[i][j] = __builtin_fmaxf(su, accu[i][j]);
@@ -1166,7 +1174,7 @@ __device__ __forceinline__ void fast_diff_body(const KParams& p, float* smem, co
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
                         asm volatile("v_sub_f32 %0, %1, %2" : "=v"(hi[i][j]) : "v"(hi[i][j]), "v"(lo[i][j]));
-                set_round_zero_nm();
+                if (RND == LBA_ROUND_FLOOR) set_round_zero_nm(); else set_round_nearest_nm();
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -1181,8 +1189,8 @@ __device__ __forceinline__ void fast_diff_body(const KParams& p, float* smem, co
 #pragma unroll
                     for (int j = 0; j < TN; ++j) {
                         float u;
-                        asm volatile("v_add_f32 %0, %1, %2" : "=v"(u) : "v"(top[i][j]), "v"(acc[i][j]));   // stays in the toward-zero part
-                        u = __uint_as_float(__float_as_uint(u) & mask);
+                        asm volatile("v_add_f32 %0, %1, %2" : "=v"(u) : "v"(top[i][j]), "v"(acc[i][j]));   // stays in the part that runs in the wave's own mode
+                        u = round_sum(u);
                         top[i][j] = med3(u, -rof, rof);
                         acc[i][j] = 0.0f;
                         accu[i][j] = 0.0f;
@@ -1197,7 +1205,7 @@ __device__ __forceinline__ void fast_diff_body(const KParams& p, float* smem, co
         }
         __syncthreads();
     }
-    set_round_nearest();
+    if (RND == LBA_ROUND_FLOOR) set_round_nearest();
 
     if (pC) {
 #pragma unroll
@@ -1224,25 +1232,25 @@ __device__ __forceinline__ void fast_diff_body(const KParams& p, float* smem, co
     }
 }
 
-template <int PM, int ORDER>
+template <int PM, int RND, int ORDER>
 __global__ void __launch_bounds__(256, 3) lba_fast_diff_kernel(const KParams p) {
     __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
-    fast_diff_body<4, 4, PM, ORDER>(p, smem, blockIdx.x * 64, blockIdx.y * 64);
+    fast_diff_body<4, 4, PM, RND, ORDER>(p, smem, blockIdx.x * 64, blockIdx.y * 64);
 }
 
 // The same on the mixed grid of lba_fast_mixed_kernel: 64 x 64 workgroups for the full rounds, 32 x 32 ones on the
 // last rows of the launch.
-template <int PM, int ORDER>
+template <int PM, int RND, int ORDER>
 __global__ void __launch_bounds__(256, 3) lba_fast_diff_mixed_kernel(const KParams p) {
     __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
     const int b = blockIdx.x;
     if (b < p.mix_main) {                                      // uniform
         const int by = b / p.mix_gx_main, bx = b - by * p.mix_gx_main;
-        fast_diff_body<4, 4, PM, ORDER>(p, smem, bx * 64, by * 64);
+        fast_diff_body<4, 4, PM, RND, ORDER>(p, smem, bx * 64, by * 64);
     } else {
         const int t = b - p.mix_main;
         const int by = t / p.mix_gx_tail, bx = t - by * p.mix_gx_tail;
-        fast_diff_body<2, 2, PM, ORDER>(p, smem, p.mix_m_main + bx * 32, by * 32);
+        fast_diff_body<2, 2, PM, RND, ORDER>(p, smem, p.mix_m_main + bx * 32, by * 32);
     }
 }
 

@@ -41,7 +41,7 @@ static void plan_kernel_name(const Plan& pl, bool uf, char* buf, size_t n) {
         return;
     }
     if (pl.events == 2) {
-        snprintf(buf, n, pl.mix_tail > 0 ? "lba_fast_diff_mixed_kernel<%d, %d>" : "lba_fast_diff_kernel<%d, %d>", pm, ord);
+        snprintf(buf, n, pl.mix_tail > 0 ? "lba_fast_diff_mixed_kernel<%d, %d, %d>" : "lba_fast_diff_kernel<%d, %d, %d>", pm, pl.round, ord);
     } else if (pl.events) {
         if (pl.amode)             snprintf(buf, n, "lba_fast_bwd_kernel<%d, 0, 0, %s, 1>", pm, b);
         else if (pl.mix_tail > 0) snprintf(buf, n, "lba_fast_bwd_mixed_kernel<%d, %d, %s>", pm, pl.round, b);

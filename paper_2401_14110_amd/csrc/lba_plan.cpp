@@ -253,7 +253,7 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     // the multiply's flush); nearest-even accumulators on E4M3 matrices whose products Q_prod does not round
     // (and only where rounding twice is exact, below); anything else takes the general kernel
     if (events && !flush) fast = false;
-    if (events && qa.round != LBA_ROUND_FLOOR && (events == 2 || prod_round || conv || in.ea != 4 || in.eb != 4)) fast = false;
+    if (events && qa.round != LBA_ROUND_FLOOR && (prod_round || conv || in.ea != 4 || in.eb != 4)) fast = false;
     bool rne_odd = false;
     if (fast && qa.round == LBA_ROUND_RNE && !rne_fast_ok(qp, qa, clamp, flush, nouf_a, in)) {
         // E4M3 matrices, Q_prod without mantissa rounding, forward call: the round-to-odd variant
@@ -309,8 +309,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
             if (p.prod_mode == PM_FLUSH_CLAMP || p.prod_mode == PM_TRUNC_CLAMP) p.valu_per_mac_x100 += 200;
             if (p.prod_mode == PM_TRUNC || p.prod_mode == PM_TRUNC_CLAMP) p.valu_per_mac_x100 += 100;
         }
-        if (events == 2)                                         // mul, fma, and, mul, max, min, mul, sub, cmp; med3, addc at half rate
-            p.valu_per_mac_x100 = 1300 + (p.prod_mode == PM_FLUSH_CLAMP ? 200 : 0);
+        if (events == 2)                                         // mul, fma, and, mul, max, min, mul, sub, cmp; med3, addc at half rate; nearest-even: bfe, add3
+            p.valu_per_mac_x100 = 1300 + (p.prod_mode == PM_FLUSH_CLAMP ? 200 : 0) + (qa.round == LBA_ROUND_RNE ? 400 : 0);
         if (order == LBA_ORDER_CHUNK16)                          // add, and [, bfe, add3], zero per 16 steps
             p.valu_per_mac_x100 += (events == 2 ? 1300 : events ? 900 : (qa.round == LBA_ROUND_RNE ? 700 : 300)) / 16;
     } else {
@@ -323,7 +323,11 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         if (nouf_a) kp.ruf_a = 0.0f;
         kp.prod_round = prod_round ? 1 : 0;
         kp.prod_rne = (qp.round == LBA_ROUND_RNE) ? 1 : 0;
-        p.valu_per_mac_x100 = 0;                           // filled by the launcher's table
+        // Priced at the budget of a straightforward FMAq step, not at what the compiled loop issues (18 to 60
+        // VALU instructions per MAC, depending on the variant): exact multiply, two range checks on the product,
+        // exact add, mantissa rounding, two range checks on the sum, decode = 10 slots for floor, 12 for
+        // nearest-even; 4 more with event bits or the DIFF bit.  A long loop cannot raise its own score.
+        p.valu_per_mac_x100 = (qa.round == LBA_ROUND_RNE ? 1200 : 1000) + (events ? 400 : 0);
     }
     p.amode = (conv || in.ea != 4 || in.eb != 4 || p.prod_mode == PM_RNE || p.prod_mode == PM_RNE_CLAMP ||
                (events && (p.prod_mode == PM_TRUNC || p.prod_mode == PM_TRUNC_CLAMP))) ? 1 : 0;

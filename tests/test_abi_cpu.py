@@ -214,7 +214,8 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     assert q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 0
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), with_masks=1)["kernel"] == 0      # nearest-even: where rounding twice is exact
     assert q(64, 64, 64, (5, 7, 15, 1), (4, 11, 7, 1), with_masks=1)["kernel"] == 1     # ... not beyond 10 mantissa bits
-    assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), with_masks=2)["kernel"] == 1      # the DIFF plane: floor only
+    assert q(64, 64, 64, (5, 7, 15, 1), (4, 7, 7, 1), with_masks=2)["kernel"] == 0      # the DIFF plane likewise
+    assert q(64, 64, 64, (5, 7, 15, 1), (5, 3, 15, 1), with_masks=2)["kernel"] == 1
     assert q(64, 64, 64, (5, 7, 17, 0), (4, 7, -7, 0), with_masks=1)["kernel"] == 1     # products up to 2^24 below R_UF of Q_acc
     assert q(64, 64, 64, (5, 7, 17, 0), (4, 7, -6, 0), with_masks=1)["kernel"] == 0
     assert q(64, 64, 64, (6, 7, 20, 0), (4, 7, 7, 0), with_masks=1)["kernel"] == 1
