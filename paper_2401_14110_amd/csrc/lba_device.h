@@ -273,7 +273,7 @@ template <int ROWS, int BK>
 struct Stage {
     static constexpr int kChunks = ROWS * BK / 16;                         // 16-byte pieces per tile
     static constexpr int kPerLane = (kChunks + 255) / 256;
-    static constexpr int kRowShift = ROWS == 16 ? 4 : ROWS == 32 ? 5 : ROWS == 64 ? 6 : ROWS == 128 ? 7 : 8;
+    static constexpr int kRowShift = ROWS == 8 ? 3 : ROWS == 16 ? 4 : ROWS == 32 ? 5 : ROWS == 64 ? 6 : ROWS == 128 ? 7 : 8;
     static_assert((1 << kRowShift) == ROWS, "tile rows must be a power of two");
     // lanes that take B's pieces: the highest-numbered ones, so that A and B share the work
     static constexpr int kTailShift = kChunks < 256 ? 256 - kChunks : 0;
@@ -411,7 +411,9 @@ __device__ __forceinline__ void store_tile(float* __restrict__ dst /* [BK][ROWS]
 // value(code) * 2^(bias - 15), subnormals included, so the hardware FP16 -> FP32 conversion and one exact
 // multiply by 2^(15 - bias + scale_exp) decode it.  E = 5 would put e = 31 on FP16's inf / NaN codes and is
 // decoded arithmetically (integer significand times a power of two).
-template <int ROWS, int BK>
+// PAD: floats inserted after every 16 k (the K-parallel kernel reads several 16-k pieces at once and keeps them
+// on different banks that way).
+template <int ROWS, int BK, int PAD = 0>
 __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][ROWS] */, float scale,
                                                int tid, const uint4 (&regs)[Stage<ROWS, BK>::kPerLane],
                                                int E = 4, int M = 3, int scale_exp = 0) {
@@ -431,13 +433,13 @@ __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][R
                     for (int j = 0; j < 16; ++j) {
                         const uint32_t code = (w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
                         const uint16_t h = (uint16_t)(((code & 0x80u) << 8) | ((code & 0x7Fu) << up));
-                        dst[(kq * 16 + j) * ROWS + row] = (float)__builtin_bit_cast(_Float16, h) * sc16;
+                        dst[(kq * 16 + j) * ROWS + row + kq * PAD] = (float)__builtin_bit_cast(_Float16, h) * sc16;
                     }
                 } else {
 #pragma unroll
                     for (int j = 0; j < 16; ++j) {
                         const int code = (int)((w[j >> 2] >> (8 * (j & 3))) & 0xFFu);
-                        dst[(kq * 16 + j) * ROWS + row] = decode_entry(code, scale_exp, E, M);
+                        dst[(kq * 16 + j) * ROWS + row + kq * PAD] = decode_entry(code, scale_exp, E, M);
                     }
                 }
             }
@@ -469,7 +471,7 @@ __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][R
                 }
             }
 #pragma unroll
-            for (int j = 0; j < 16; ++j) dst[(kq * 16 + j) * ROWS + row] = f[j];
+            for (int j = 0; j < 16; ++j) dst[(kq * 16 + j) * ROWS + row + kq * PAD] = f[j];
         }
     }
 }
@@ -765,6 +767,165 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_mixed_kernel
         const int t = b - p.mix_main;
         const int by = t / p.mix_gx_tail, bx = t - by * p.mix_gx_tail;
         fast_body<2, 2, BK, PM, RND, ORDER, 0>(p, smem, p.mix_m_main + bx * 32, by * 32);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// K-parallel kernel for the chunked order (forward call, launches with too few outputs to fill the chip)
+// ---------------------------------------------------------------------------------------------
+// Under the chunked order (Sec. 3, Fig. 1 right) the chunks of 16 products are independent chains from 0; only
+// the second level, T <- Q_acc(T + chunk sum) over the chunks in order, is sequential.  When a product has too
+// few outputs for one lane per 4 x 4 block of them to fill the chip, a workgroup takes a small tile of outputs and
+// runs CF = 4 * CPW chunks of it side by side: wave w and, inside a wave, lane group cw own chunk w * CPW + cw of
+// the current k-tile (16 * CF steps deep); every lane still advances TM x TN chains.  After the 16 steps the chunk
+// sums go through LDS to the lanes that own the outputs' second-level sums, which add them in chunk order.
+// The result is the chunked order's, bit for bit: the first level is the same chain per chunk, the second level
+// the same ordered chain.
+//   CPW = 1: 64 lane blocks of 4 x 4 per wave, tile 32 x 32, 4 chunks in flight (k-tile 64)
+//   CPW = 4: 16 lane blocks of 2 x 4 per wave, tile 8 x 16, 16 chunks in flight (k-tile 256)
+// One LDS stage (the next tile's global loads are in flight during the steps and are decoded into LDS while the
+// second level runs), two barriers per k-tile.
+template <int RND>
+__device__ __forceinline__ float level2_scalar(float T, float cs, const FastConst& c) {
+    float u = T + cs;                                          // both on Q_acc's grid: one rounding of the exact sum
+    if (RND == RND_RNE_BF16) {
+        u = rne_to_8_bits(u);
+    } else {
+        uint32_t w = __float_as_uint(u);
+        if (RND == LBA_ROUND_RNE) w = w + c.half + ((w >> c.sh) & 1u);
+        u = __uint_as_float(w & c.mask);
+    }
+    return med3(u, -c.rof, c.rof);
+}
+
+template <int TM, int TN, int CPW, int PM, int RND>
+__global__ void __launch_bounds__(256, (CPW == 4 && TM == 4) ? 3 : 4) lba_kpar_kernel(const KParams p) {
+    constexpr int SUB = 64 / CPW;                              // lane blocks per wave
+    constexpr int SX = CPW == 1 ? 8 : 4, SY = SUB / SX;        // ... arranged SY x SX
+    constexpr int BM = SY * TM, BN = SX * TN;                  // outputs of the workgroup
+    constexpr int CF = 4 * CPW, BKT = 16 * CF;                 // chunks in flight, depth of a k-tile
+    constexpr int PAD_A = CPW == 1 ? 0 : (BM >= 16 ? 16 : 8), PAD_B = CPW == 1 ? 0 : 16;
+    constexpr int A_FLOATS = BKT * BM + CF * PAD_A, B_FLOATS = BKT * BN + CF * PAD_B;
+    constexpr int OUT = BM * BN, OPL = (OUT + 255) / 256;      // outputs, second-level sums per lane
+    __shared__ __attribute__((aligned(16))) float smem[A_FLOATS + B_FLOATS + CF * OUT];
+    float* As = smem;
+    float* Bs = smem + A_FLOATS;
+    float* xs = Bs + B_FLOATS;                                 // [chunk][output]
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, l = tid & 63;
+    const int cw = l / SUB, st = l % SUB;
+    const int ty = st / SX, tx = st % SX;
+    const int chunk = wave * CPW + cw;                         // this lane's chunk of a k-tile
+    const int m0 = blockIdx.x * BM, n0 = blockIdx.y * BN;
+    const int tidb = tid - Stage<BN, BKT>::kTailShift;
+
+    const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
+    set_flush_f32();
+    if (RND == LBA_ROUND_FLOOR) set_round_zero();
+
+    FastConst c;
+    c.kc = p.kc; c.rof = p.rof_a; c.rofp = p.rof_p; c.mask = p.mask_a; c.half = p.half_a; c.sh = p.sh_a; c.maskp = p.mask_p; c.halfp = p.half_p; c.shp = p.sh_p;
+    asm volatile("" : "+v"(c.kc), "+v"(c.rof), "+v"(c.rofp), "+v"(c.mask), "+v"(c.half), "+v"(c.maskp), "+v"(c.halfp));
+    // a first-level sum starts from 0 and takes 16 steps: if 32 steps from 0 cannot reach R_OF (the bound the other
+    // kernels test per k-tile), the clamp is a no-op
+    const bool noclamp = p.fast_thresh > 0.0f;                 // uniform
+
+    float T[OPL];
+#pragma unroll
+    for (int r = 0; r < OPL; ++r) T[r] = 0.0f;
+
+    // two register sets for operand pieces in flight: the loads of tile t + 2 are issued at the start of tile t and
+    // decoded into LDS during tile t + 1, so that a whole tile period covers their latency (a k-tile of this kernel
+    // is short: 16 steps)
+    uint4 ra0[Stage<BM, BKT>::kPerLane], rb0[Stage<BN, BKT>::kPerLane], ra1[Stage<BM, BKT>::kPerLane], rb1[Stage<BN, BKT>::kPerLane];
+    const int ntiles = (p.K + BKT - 1) / BKT;
+
+    fetch_tile<BM, BKT>(p.A, p.M, p.K, m0, 0, p.ld_align, tid, ra0);
+    fetch_tile<BN, BKT>(p.B, p.N, p.K, n0, 0, p.ld_align, tidb, rb0);
+    if (ntiles > 1) {
+        fetch_tile<BM, BKT>(p.A, p.M, p.K, m0, BKT, p.ld_align, tid, ra1);
+        fetch_tile<BN, BKT>(p.B, p.N, p.K, n0, BKT, p.ld_align, tidb, rb1);
+    }
+    store_tile_cvt<BM, BKT, PAD_A>(As, sc_a, tid, ra0);
+    store_tile_cvt<BN, BKT, PAD_B>(Bs, sc_b, tidb, rb0);
+    __syncthreads();
+
+    const float* Ac = As + chunk * PAD_A;
+    const float* Bc = Bs + chunk * PAD_B;
+    // one k-tile: `next` holds the pieces of tile t + 1 (to be decoded into LDS), `free` takes those of tile t + 2
+    auto tile = [&](int t, uint4 (&next_a)[Stage<BM, BKT>::kPerLane], uint4 (&next_b)[Stage<BN, BKT>::kPerLane],
+                    uint4 (&free_a)[Stage<BM, BKT>::kPerLane], uint4 (&free_b)[Stage<BN, BKT>::kPerLane]) {
+        const bool more = (t + 1) < ntiles;
+        // first level: this lane's chunk, 16 steps from 0 (a chunk beyond K reads zeros and sums to 0)
+        float acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = 0.0f;
+        if (noclamp) {
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                float a[TM], b[TN];
+                read_operands<TM, TN, BM, BN>(Ac, Bc, chunk * 16 + s, tx, ty, a, b);
+                fast_group<PM, RND, false, 0, TM, TM, TN>(acc, a, b, c);
+            }
+        } else {
+#pragma unroll
+            for (int s = 0; s < 16; ++s) {
+                float a[TM], b[TN];
+                read_operands<TM, TN, BM, BN>(Ac, Bc, chunk * 16 + s, tx, ty, a, b);
+                fast_group<PM, RND, true, 0, TM, TM, TN>(acc, a, b, c);
+            }
+        }
+        // chunk sums to the owners of the outputs
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            float* dst = xs + chunk * OUT + (ty * TM + i) * BN + tx * TN;
+            if (TN == 4) *reinterpret_cast<float4*>(dst) = make_float4(acc[i][0], acc[i][1], acc[i][TN - 2], acc[i][TN - 1]);
+            else         *reinterpret_cast<float2*>(dst) = make_float2(acc[i][0], acc[i][1]);
+        }
+        __syncthreads();                                       // chunk sums visible; every lane is done with the operand tiles
+        if (more) {
+            store_tile_cvt<BM, BKT, PAD_A>(As, sc_a, tid, next_a);
+            store_tile_cvt<BN, BKT, PAD_B>(Bs, sc_b, tidb, next_b);
+        }
+        if (t + 3 < ntiles) {                                  // `next` is free again: tile t + 3 (tile t + 2 is in `free`)
+            fetch_tile<BM, BKT>(p.A, p.M, p.K, m0, (t + 3) * BKT, p.ld_align, tid, next_a);
+            fetch_tile<BN, BKT>(p.B, p.N, p.K, n0, (t + 3) * BKT, p.ld_align, tidb, next_b);
+        }
+        (void)free_a; (void)free_b;
+        // second level, in chunk order (Sec. 3: no Q_prod here); the owners are the last lanes of the workgroup (the
+        // first ones have more operand pieces to decode)
+#pragma unroll
+        for (int r = 0; r < OPL; ++r) {
+            const int o = OUT >= 256 ? tid + 256 * r : tid - (256 - OUT);
+            if (OUT >= 256 || o >= 0) {
+#pragma unroll
+                for (int cc = 0; cc < CF; ++cc) T[r] = level2_scalar<RND>(T[r], xs[cc * OUT + o], c);
+            }
+        }
+        __syncthreads();                                       // next operand tiles visible; chunk sums consumed
+    };
+    // at the start of tile t: set 1 holds tile t + 1 (t even) / set 0 (t odd); tile 2 goes to set 0 once it is decoded
+    if (ntiles > 2) {
+        // set 0 was decoded above: reuse it for tile 2 right away
+        fetch_tile<BM, BKT>(p.A, p.M, p.K, m0, 2 * BKT, p.ld_align, tid, ra0);
+        fetch_tile<BN, BKT>(p.B, p.N, p.K, n0, 2 * BKT, p.ld_align, tidb, rb0);
+    }
+    for (int t = 0; t < ntiles; t += 2) {
+        tile(t, ra1, rb1, ra0, rb0);
+        if (t + 1 < ntiles) tile(t + 1, ra0, rb0, ra1, rb1);
+    }
+    if (RND == LBA_ROUND_FLOOR) set_round_nearest();
+
+#pragma unroll
+    for (int r = 0; r < OPL; ++r) {
+        const int o = OUT >= 256 ? tid + 256 * r : tid - (256 - OUT);
+        if (OUT >= 256 || o >= 0) {
+            const int m = m0 + o / BN, n = n0 + o % BN;
+            if (m < p.M && n < p.N) p.C[(int64_t)m * p.N + n] = (T[r] == 0.0f) ? 0.0f : __builtin_ldexpf(T[r], p.out_exp);
+        }
     }
 }
 

@@ -16,6 +16,7 @@ __global__ void lba_fill_zero_kernel(float* C, int64_t n) {
 }
 
 static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
+    if (pl.kernel == KERNEL_FAST && pl.kpar > 0) return launch_kpar(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.events == 2) return launch_fast_diff(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.events) return launch_fast_bwd(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.rne_odd) return launch_fast_odd(pl, st);
@@ -40,7 +41,10 @@ static void plan_kernel_name(const Plan& pl, bool uf, char* buf, size_t n) {
                  pl.events == 2 ? "true" : "false");
         return;
     }
-    if (pl.events == 2) {
+    if (pl.kpar > 0) {
+        const int rnd = pl.round == LBA_ROUND_FLOOR ? 0 : (pl.kp.sh_a == 16 ? 2 : 1);
+        snprintf(buf, n, "lba_kpar_kernel<%d, 4, %d, %d, %d>", pl.kpar == 3 ? 2 : 4, pl.kpar == 1 ? 1 : 4, pm, rnd);
+    } else if (pl.events == 2) {
         snprintf(buf, n, pl.mix_tail > 0 ? "lba_fast_diff_mixed_kernel<%d, %d, %d>" : "lba_fast_diff_kernel<%d, %d, %d>", pm, pl.round, ord);
     } else if (pl.events) {
         if (pl.amode)             snprintf(buf, n, "lba_fast_bwd_kernel<%d, 0, 0, %s, 1>", pm, b);
@@ -289,6 +293,11 @@ static int plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt 
     if (rc != LBA_OK) return rc;
     out->kernel = pl.kernel; out->prod_mode = pl.prod_mode; out->round = pl.round;
     out->tile_m = 16 * pl.tm; out->tile_n = 16 * pl.tn; out->tile_k = pl.bk;
+    if (pl.kpar > 0) {                                         // outputs per workgroup and depth of a k-tile (chunks in flight x 16)
+        out->tile_m = pl.kpar == 1 ? 32 : 8;
+        out->tile_n = pl.kpar == 1 ? 32 : 16;
+        out->tile_k = pl.kpar == 1 ? 64 : 256;
+    }
     out->thread_m = pl.tm; out->thread_n = pl.tn;
     out->grid_x = pl.grid_x; out->grid_y = pl.grid_y;
     out->valu_per_mac_x100 = pl.valu_per_mac_x100;

@@ -17,6 +17,8 @@ hipError_t launch_fast_22(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_amode(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_mixed(const Plan& pl, hipStream_t st);   // plans with mix_tail > 0
 hipError_t launch_fast_odd(const Plan& pl, hipStream_t st);     // plans with rne_odd
+// forward, chunked order, several chunks of an output side by side (plans with kpar > 0)
+hipError_t launch_kpar(const Plan& pl, hipStream_t st);
 // recompute call, scaled-domain kernel (launch_fast_bwd hands nearest-even plans to launch_fast_bwd_rne)
 hipError_t launch_fast_bwd(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_bwd_rne(const Plan& pl, hipStream_t st);

@@ -357,7 +357,24 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     const int64_t bm = 16 * p.tm, bn = 16 * p.tn;
     p.grid_x = (int)((M + bm - 1) / bm);
     p.grid_y = (int)((N + bn - 1) / bn);
-    plan_mixed_grid(M, N, batch, &p);
+    // Chunked order, forward call, fewer than 512 workgroups even of 32 x 32 outputs (less than two waves on every
+    // SIMD whatever the lane block): the chunks of an output are independent first-level chains, so a workgroup
+    // takes 8 x 16 outputs and runs 16 chunks of them side by side (lba_kpar_kernel); chains shorter than 128 steps
+    // take 32 x 32 outputs and 4 chunks.  Measured: 64 x 1000 x 2048 1.4 -> 6.4e12 MAC/s, 256 x 256 x 4096
+    // 1.5 -> 7.3e12; from 512 workgroups of 32 x 32 on it no longer pays.
+    p.kpar = 0;
+    if (p.kernel == KERNEL_FAST && order == LBA_ORDER_CHUNK16 && !events && !p.amode && !p.rne_odd && batch == 1 && K > 16 &&
+        (p.prod_mode == PM_IDENT || p.prod_mode == PM_FLUSH || p.prod_mode == PM_FLUSH_CLAMP)) {
+        const int64_t b32 = ((M + 31) / 32) * ((N + 31) / 32);
+        if (b32 < 512 && (N + 15) / 16 <= 65535) {
+            p.kpar = K < 128 ? 1 : 3;
+            const int64_t tm = p.kpar == 1 ? 32 : 8, tn = p.kpar == 1 ? 32 : 16;
+            p.tm = p.kpar == 3 ? 2 : 4; p.tn = 4;
+            p.grid_x = (int)((M + tm - 1) / tm);
+            p.grid_y = (int)((N + tn - 1) / tn);
+        }
+    }
+    if (p.kpar == 0) plan_mixed_grid(M, N, batch, &p);
     *out = p;
     return LBA_OK;
 }

@@ -202,6 +202,12 @@ static void sweep_planner() {
                                             CHECK((int64_t)kp.mix_gx_tail * 32 >= M - kp.mix_m_main, "tail rows cover M");
                                             CHECK(pl.mix_tail == kp.mix_gx_tail * ((N + 31) / 32), "tail count");
                                             CHECK(pl.grid_x == kp.mix_main + pl.mix_tail && pl.grid_y == 1, "mixed grid");
+                                        } else if (pl.kpar > 0) {
+                                            const int64_t tm = pl.kpar == 1 ? 32 : 8, tn = pl.kpar == 1 ? 32 : 16;
+                                            CHECK(pl.kpar == 1 || pl.kpar == 3, "kpar %d", pl.kpar);
+                                            CHECK(order == LBA_ORDER_CHUNK16 && events == 0 && pl.kernel == lba::KERNEL_FAST, "kpar plan");
+                                            CHECK(pl.grid_x * tm >= M && pl.grid_y * tn >= N && (pl.grid_x - 1) * tm < M && (pl.grid_y - 1) * tn < N, "kpar grid");
+                                            CHECK(pl.grid_y <= 65535 && (int64_t)pl.grid_x * pl.grid_y >= 1, "kpar grid limits");
                                         } else {
                                             CHECK((int64_t)pl.grid_x * 16 * pl.tm >= M && (int64_t)pl.grid_y * 16 * pl.tn >= N, "grid covers the outputs");
                                             CHECK((int64_t)(pl.grid_x - 1) * 16 * pl.tm < M || M == 0, "no empty tile row");

@@ -167,6 +167,33 @@ def test_chunked_order(ref, rnd):
         assert np.count_nonzero(got) > got.size // 2
 
 
+def test_chunked_order_with_chunks_side_by_side(ref):
+    # launches with few outputs run several chunks of an output side by side (first-level chains are independent;
+    # the second level stays an ordered chain): ragged K below, at and across the depth of a k-tile of each shape of
+    # that kernel (64 and 256), ragged M and N, both workgroup shapes, clamped and clamp-free first levels,
+    # both roundings and the bfloat16 shortcut (M = 7), every product mode.  Bit for bit the oracle's chunked order.
+    rng = np.random.default_rng(161)
+    shapes = [(70, 66), (5, 3), (33, 130), (300, 200), (1100, 530), (17, 1000)]
+    seen = set()
+    for (M, N) in shapes:
+        for K in (17, 147, 530, 64, 127, 256, 1100):
+            if M * N * K > 4e8:
+                continue
+            A = rand_codes(rng, (M, K), 2, 13); B = rand_codes(rng, (N, K), 2, 13)
+            for qp, qa in [((5, 7, 15), (4, 7, 7)), ((4, 7, 12), (4, 7, 10)), ((6, 7, 20), (6, 7, 31)), ((5, 7, 15), (5, 10, 15)),
+                           ((6, 7, 20), (4, 5, 7)), ((5, 7, -1), (4, 7, -9))]:
+                for rnd in (0, 1):
+                    qpf, qaf = qp + (rnd,), qa + (rnd,)
+                    name = lb.lba_plan_kernel_name(M, N, K, qpf, qaf, 1, 0)
+                    if "kpar" not in name:
+                        continue
+                    seen.add(name)
+                    check(ref, A, B, qpf, qaf, "chunks side by side %s" % name, order=1)
+    shapes_seen = {n.split("<")[1].split(",")[0] + n.split(",")[2] for n in seen}
+    assert shapes_seen == {"4 1", "2 4"}, seen
+    assert {n.rstrip(">").split(", ")[3] for n in seen} == {"0", "1", "2"} and {n.rstrip(">").split(", ")[4] for n in seen} == {"0", "1", "2"}, seen
+
+
 def test_no_underflow_flag(ref):
     # FMAq "excluding underflow events" (Sec. 3): the flag on either quantizer or both, all kernels
     NOUF = 0x100
