@@ -184,7 +184,10 @@ def main():
             l["plan"] = dict(l["plan"], kernel=2, prod_mode=ste, valu_per_mac_x100=(200, 100, 400)[ste])
             # identity and (sequential) recursive coefficients are constant inside a k tile: lba_grad runs them as a
             # dense product on the matrix cores when rows of G are aligned
-            if ste != 1 and l["N"] % 4 == 0 and (ste == 0 or l["K"] <= 12288):
+            # ... and so are the bricks of the immediate estimator that hold no overflow (lba_grad_ws; on this workload,
+            # whose formats fit the data, that is every brick; the pass over the plane that finds them is inside the
+            # timed call)
+            if l["N"] % 4 == 0 and (ste == 0 or ste == 1 or l["K"] <= 12288):
                 l["plan"] = dict(l["plan"], kernel=3, valu_per_mac_x100=0)
             l["of"] = l["last"] = None
             if ste:
@@ -192,13 +195,18 @@ def main():
             if ste == 2:
                 l["last"] = lb.last_overflow(l["of"], l["K"])
                 l["of"] = None
+        wsbuf = torch.empty(max(256, max(lb.lba_grad_workspace_bytes(l["M"], l["N"], l["K"]) for l in layers)), dtype=torch.uint8, device=dev)
         torch.cuda.synchronize()
 
         def launch(l):
-            rc = lb.lba_grad(Gbuf.data_ptr(), l["A"].data_ptr(), l["B"].data_ptr(),
-                             l["of"].data_ptr() if l["of"] is not None else None,
-                             l["last"].data_ptr() if l["last"] is not None else None,
-                             dXbuf.data_ptr(), dWbuf.data_ptr(), l["M"], l["N"], l["K"], ste, stream)
+            if ste == 1:
+                rc = lb.lba_grad_ws(Gbuf.data_ptr(), l["A"].data_ptr(), l["B"].data_ptr(), l["of"].data_ptr(), None,
+                                    dXbuf.data_ptr(), dWbuf.data_ptr(), l["M"], l["N"], l["K"], ste, wsbuf.data_ptr(), wsbuf.numel(), stream)
+            else:
+                rc = lb.lba_grad(Gbuf.data_ptr(), l["A"].data_ptr(), l["B"].data_ptr(),
+                                 l["of"].data_ptr() if l["of"] is not None else None,
+                                 l["last"].data_ptr() if l["last"] is not None else None,
+                                 dXbuf.data_ptr(), dWbuf.data_ptr(), l["M"], l["N"], l["K"], ste, stream)
             if rc != 0:
                 raise RuntimeError(lb.lba_strerror(rc))
     total_macs = sum(l["macs"] for l in layers)
@@ -355,7 +363,8 @@ def main():
         # issued flops = 3 x 2 per masked MAC, against the dense bfloat16 peak of the matrix cores
         issued = dom["macs"] * 6 / (dom["ms"] * 1e-3)
         roofline.update({"bound": "mfma", "achieved": issued / 1e12, "peak": 2500.0, "unit": "TFLOP/s", "frac": issued / 2.5e15,
-                         "kernel": "lba_grad_dense_kernel<%s> (v_mfma_f32_32x32x16_bf16, 3 passes)" % args.grad,
+                         "kernel": "lba_grad_dense_kernel<%s> (v_mfma_f32_32x32x16_bf16, 3 passes%s)" % (
+                             args.grad, "; lba_grad_ws: the whole call, with the pass over the plane and the vector kernel's bricks" if args.grad == "immediate" else ""),
                          "algorithmic_tflops": dom["macs"] * 2 / (dom["ms"] * 1e-3) / 1e12, "valu_slots_per_mac": None,
                          "peak_measured": None, "frac_of_measured": None})
 
@@ -402,7 +411,7 @@ def main():
                                 "bert": "BERT-base linears, 4096 tokens", "gemm4096": "4096^3 GEMM",
                                 "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}[args.workload],
                    "macs_per_step": total_macs, "qprod": "M7E5 b=15", "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
-                   "call": ("lba_grad, %s estimator: dX and dW (2 masked MACs per forward MAC)" % args.grad) if args.grad else ("lba_gemm_bwd_diff (C + DIFF plane, eps2 = %g)" % args.diff) if args.diff is not None else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else ("lba_gemm_bwd (C + OF plane)" if args.of_only else "lba_gemm_bwd (C + OF and UF planes)")) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
+                   "call": ("%s, %s estimator: dX and dW (2 masked MACs per forward MAC)" % ("lba_grad_ws" if args.grad == "immediate" else "lba_grad", args.grad)) if args.grad else ("lba_gemm_bwd_diff (C + DIFF plane, eps2 = %g)" % args.diff) if args.diff is not None else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else ("lba_gemm_bwd (C + OF plane)" if args.of_only else "lba_gemm_bwd (C + OF and UF planes)")) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
                    "conv": "implicit im2col from NHWC activations (lba_conv2d)" if args.implicit else "operand A is the written-out im2col matrix",
                    "operands": ("E%dM%d codes with per-tensor flex bias (lba_gemm_in)" % in_fmt) if in_fmt else "E4M3"},
         "roofline": roofline,

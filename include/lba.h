@@ -259,6 +259,25 @@ int lba_grad(const float* G, const uint8_t* A, const uint8_t* B,
              const uint32_t* of_mask, const int32_t* last_of,
              float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* hip_stream);
 
+/* lba_grad with a workspace (Sec. 4, App. D: the immediate estimator is the plain backward product wherever no
+ * step of a region overflowed).  Same arguments, results and error bound as lba_grad; with ste =
+ * LBA_STE_IMMEDIATE_OF or LBA_STE_COEF_PLANE (and G 16-byte aligned, N % 4 == 0) the work is split by bricks of
+ * 128 rows x 32 summed indices x 256 k: one pass over the plane marks, in the workspace, the bricks that hold a
+ * blocked coefficient; all other bricks are dense products and run on the matrix cores, the marked ones in the
+ * kernel that applies the plane bit by bit.  Where the accumulator format fits the data (few or no overflows)
+ * this is close to the cost of the identity estimator plus one read of the plane.  Other estimators ignore the
+ * workspace.  workspace: device memory owned by the caller, 256-byte aligned (else LBA_ERR_ALIGN), at least
+ * lba_grad_workspace_bytes(M, N, K) bytes (else LBA_ERR_SHAPE), NULL is LBA_ERR_NULL; its contents on return are
+ * unspecified, and calls that share a workspace must not overlap. */
+int lba_grad_ws(const float* G, const uint8_t* A, const uint8_t* B,
+                const uint32_t* of_mask, const int32_t* last_of,
+                float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste,
+                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Bytes of workspace lba_grad_ws needs for a shape (two brick maps: about M * N * K / 2^19 bytes; 0 for an empty
+ * or invalid shape). */
+size_t lba_grad_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
 /* Static, human-readable text for a status code (never NULL). */
 const char* lba_strerror(int code);
 

@@ -94,6 +94,10 @@ def lib(path=None):
         L.lba_ste_plane.argtypes = [vp, vp, vp, i64, i64, i64, i32, i32, vp]
         L.lba_grad.restype = ctypes.c_int
         L.lba_grad.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
+        L.lba_grad_ws.restype = ctypes.c_int
+        L.lba_grad_ws.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
+        L.lba_grad_workspace_bytes.restype = ctypes.c_size_t
+        L.lba_grad_workspace_bytes.argtypes = [i64, i64, i64]
         L.lba_mask_words.restype = ctypes.c_size_t
         L.lba_mask_words.argtypes = [i64, i64, i64]
         L.lba_strerror.restype = ctypes.c_char_p
@@ -210,6 +214,15 @@ def lba_ste_plane(of_mask, of_mask2, coef, M, N, K, ste, order, hip_stream=None)
 def lba_grad(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, hip_stream=None):
     return lib().lba_grad(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste,
                           ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_grad_ws(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, workspace, workspace_bytes, hip_stream=None):
+    return lib().lba_grad_ws(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, workspace, workspace_bytes,
+                             ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_grad_workspace_bytes(M, N, K):
+    return int(lib().lba_grad_workspace_bytes(M, N, K))
 
 
 def lba_mask_words(M, N, K):
@@ -352,8 +365,9 @@ def last_overflow(of_plane, K, stream=None):
     return out
 
 
-def grad(G, A, B, ste, of_plane=None, last_of=None, want_dx=True, want_dw=True, stream=None):
-    """Masked gradient products: returns (dX [M, K] or None, dW [N, K] or None), float32 device tensors."""
+def grad(G, A, B, ste, of_plane=None, last_of=None, want_dx=True, want_dw=True, stream=None, workspace=None):
+    """Masked gradient products: returns (dX [M, K] or None, dW [N, K] or None), float32 device tensors.
+    workspace: a uint8 device tensor of at least lba_grad_workspace_bytes(M, N, K) bytes: lba_grad_ws."""
     A, B = _ops(A, B)
     M, K = A.shape
     N = B.shape[0]
@@ -369,6 +383,12 @@ def grad(G, A, B, ste, of_plane=None, last_of=None, want_dx=True, want_dw=True, 
     dX = torch.empty((M, K), dtype=torch.float32, device=A.device) if want_dx else None
     dW = torch.empty((N, K), dtype=torch.float32, device=A.device) if want_dw else None
     ptr = lambda t: (t.data_ptr() or None) if t is not None else None
+    if workspace is not None:
+        if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+            raise ValueError("workspace must be a contiguous uint8 device tensor")
+        _check(lib().lba_grad_ws(ptr(G), ptr(A), ptr(B), ptr(of_plane), ptr(last_of), ptr(dX), ptr(dW), M, N, K, ste,
+                                 ptr(workspace), workspace.numel(), _stream(stream)))
+        return dX, dW
     _check(lib().lba_grad(ptr(G), ptr(A), ptr(B), ptr(of_plane), ptr(last_of), ptr(dX), ptr(dW), M, N, K, ste,
                           _stream(stream)))
     return dX, dW

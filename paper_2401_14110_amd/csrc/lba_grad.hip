@@ -31,7 +31,7 @@ namespace lba {
 // lba_grad_mfma.hip: the identity estimator as a dense contraction on the matrix cores
 bool grad_dense_ok(const float* G, const uint8_t* V, const int32_t* last_of, int64_t M, int64_t N, int64_t K);
 int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* last_of, float* out,
-                   int64_t M, int64_t N, int64_t K, hipStream_t st);
+                   int64_t M, int64_t N, int64_t K, hipStream_t st, const uint8_t* bricks = nullptr);
 
 // Sizes of one launch; the pointers are separate kernel arguments so that they can be declared
 // non-aliasing, which is what lets the compiler fetch the wave-uniform values with scalar loads.
@@ -44,6 +44,11 @@ struct GradDims {
     int32_t vec_ok;            // 1: G, the plane and last_of are 16-byte aligned and N % 4 == 0 (wide scalar loads)
     uint32_t plane_xor;        // 0xFFFFFFFF: the plane holds OF bits (c = 1 - bit); 0: it holds the coefficients
     int32_t v16;               // 1: rows of codes are 16-byte aligned (V % 16 == 0, K % 16 == 0)
+    // brick map (immediate estimator with a workspace): byte ((k / 256) * brick_rb + r / 128) * brick_sb + s / 32 is
+    // non-zero where some coefficient of that brick is 0; this kernel then takes those bricks only (the matrix-core
+    // kernel adds the others).  NULL: every brick.
+    const uint8_t* bricks;
+    int32_t brick_rb, brick_sb;
 };
 
 __device__ __forceinline__ float decode_e4m3(uint32_t code) {
@@ -362,8 +367,24 @@ __global__ void __launch_bounds__(256) lba_grad_kernel(const float* __restrict__
         __shared__ __attribute__((aligned(16))) uint8_t vtiles[4][1024];    // and one 16 x 64 tile of codes
         float* tile = gtiles[wave];
         uint8_t* vtile = vtiles[wave];
+        const uint8_t* __restrict__ brick_row = d.bricks ? d.bricks + ((int64_t)(k0 >> 8) * d.brick_rb + (r0 >> 7)) * d.brick_sb : nullptr;
+        auto dirty = [&](int ss) { return !brick_row || brick_row[ss >> 5] != 0; };   // uniform
+        // fast-forward over clean bricks, eight (256 values of s) per round of loads (s is a multiple of 32 here:
+        // the slices of s start on brick boundaries)
+        auto skip_clean = [&](int ss) {
+            if (brick_row && (ss & 31) == 0) {
+                while (ss + 256 <= s_end) {
+                    const uint8_t* b8 = brick_row + (ss >> 5);
+                    if ((uint32_t)b8[0] | b8[1] | b8[2] | b8[3] | b8[4] | b8[5] | b8[6] | b8[7]) break;
+                    ss += 256;
+                }
+            }
+            return ss;
+        };
+        int g4_for = s;                                                    // the step g4 was fetched for
         float4 g4 = fetch_g_tile<S_CONTIG>(G, r0, s, lane, d);
         auto step = [&](int ss, const PlaneWords& pw) {
+            if (g4_for != ss) g4 = fetch_g_tile<S_CONTIG>(G, r0, ss, lane, d);   // the step before was skipped (clean brick)
             // LDS operations of a wave complete in order: the tiles are overwritten after the last reads of the step
             // before, and read after they are written; the wave barriers keep the compiler from moving them.
             // g was requested a whole step ahead; the codes (L2-resident, re-read by every row block) are requested
@@ -374,22 +395,31 @@ __global__ void __launch_bounds__(256) lba_grad_kernel(const float* __restrict__
             store_g_tile(tile, g4, lane);
             if (d.v16) store_v_tile(vtile, c4, lane);
             __builtin_amdgcn_wave_barrier();
-            if (ss + 32 <= s_end) g4 = fetch_g_tile<S_CONTIG>(G, r0, ss + 16, lane, d);
+            if (ss + 32 <= s_end) { g4 = fetch_g_tile<S_CONTIG>(G, r0, ss + 16, lane, d); g4_for = ss + 16; }
             immediate_superstep<S_CONTIG>(acc, r0, ss, k, lane, V, tile, vtile, pw, d);
         };
         if (S_CONTIG) {
             // two steps share the 128-byte lines of the plane's rows: both halves are requested together (a step
             // later the line has often left L2 again: the plane streams through it once)
             for (; s + 32 <= s_end; s += 32) {
+                s = skip_clean(s);
+                if (s + 32 > s_end) break;
+                if (!dirty(s) && !dirty(s + 16)) continue;
                 const PlaneWords pa = fetch_plane_words<S_CONTIG>(r0, s, lane, P0, P1, d);
                 const PlaneWords pb = fetch_plane_words<S_CONTIG>(r0, s + 16, lane, P0, P1, d);
-                step(s, pa);
-                step(s + 16, pb);
+                if (dirty(s)) step(s, pa);
+                if (dirty(s + 16)) step(s + 16, pb);
             }
         }
-        for (; s + 16 <= s_end; s += 16) step(s, fetch_plane_words<S_CONTIG>(r0, s, lane, P0, P1, d));
+        for (; s + 16 <= s_end; s += 16) {
+            s = skip_clean(s);
+            if (s + 16 > s_end) break;
+            if (dirty(s)) step(s, fetch_plane_words<S_CONTIG>(r0, s, lane, P0, P1, d));
+        }
     }
     for (; s < s_end; s += 4) {
+        if (MODE == LBA_STE_IMMEDIATE_OF && d.bricks &&
+            d.bricks[((int64_t)(k0 >> 8) * d.brick_rb + (r0 >> 7)) * d.brick_sb + (s >> 5)] == 0) continue;   // uniform: a clean brick
         float v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -413,11 +443,72 @@ __global__ void __launch_bounds__(256) lba_grad_kernel(const float* __restrict__
         for (int i = 0; i < 16; ++i) {
             if (r0 + i < d.R) {
                 float* dst = out + (int64_t)(r0 + i) * d.K + k;
-                if (d.atomic) unsafeAtomicAdd(dst, acc[i]);
+                // (with a brick map the output already holds the matrix-core kernel's part: zeros are not added)
+                if (d.atomic) { if (!d.bricks || acc[i] != 0.0f) unsafeAtomicAdd(dst, acc[i]); }
                 else          *dst = acc[i];
             }
         }
     }
+}
+
+// Brick maps of the immediate estimator from a plane, one pass: a brick is 128 rows x 32 s x 256 k of a product
+// (dX: rows m, s = n; dW: rows n, s = m); its byte becomes non-zero if some coefficient in it is 0 (flip = all ones: the
+// plane holds OF bits, a set bit blocks; flip = 0: it holds coefficients, a clear bit among the K valid ones blocks).
+// The maps are zeroed beforehand.  One workgroup per group of rows of the [words * M][N] matrix of plane words.
+struct BrickDims {
+    int64_t quads;             // words * M * N / 4: 16-byte groups of plane words (N % 4 == 0: a group lies in one row)
+    int32_t M, N, K, qpr;      // qpr = N / 4
+    int32_t rbx, sbx, rbw, sbw;
+    uint32_t flip;
+};
+
+constexpr int kBrickQuadsPerWg = 4096;                         // 64 KB of the plane per workgroup
+
+__global__ void __launch_bounds__(256) lba_brick_map_kernel(const uint32_t* __restrict__ plane, uint8_t* __restrict__ map_dx,
+                                                            uint8_t* __restrict__ map_dw, const BrickDims d) {
+    const int words = (d.K + 31) >> 5;
+    // the workgroup's first group: row (w, m) of the [words * M][N] matrix and position in it, computed once
+    const int64_t q0 = (int64_t)blockIdx.x * kBrickQuadsPerWg;
+    const int64_t row0 = q0 / d.qpr;
+    const int rem0 = (int)(q0 - row0 * d.qpr);
+    const int w0 = (int)(row0 / d.M);
+    const int m0 = (int)(row0 - (int64_t)w0 * d.M);
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    const u32x4* __restrict__ src = reinterpret_cast<const u32x4*>(plane) + q0;
+    constexpr int BATCH = 8;                                   // loads in flight per lane: the pass is bound by memory
+    for (int i0 = 0; i0 < kBrickQuadsPerWg / 256; i0 += BATCH) {
+        u32x4 xs[BATCH];
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j) {
+            const int l = (i0 + j) * 256 + (int)threadIdx.x;
+            xs[j] = (q0 + l < d.quads) ? __builtin_nontemporal_load(src + l) : u32x4{d.flip, d.flip, d.flip, d.flip};
+        }
+#pragma unroll
+        for (int j = 0; j < BATCH; ++j) {
+            const u32x4 x = xs[j];
+            const uint32_t raw = (x.x ^ d.flip) | (x.y ^ d.flip) | (x.z ^ d.flip) | (x.w ^ d.flip);
+            if (raw == 0u) continue;                           // the usual case: nothing blocked in these 128 steps
+            const int l = (i0 + j) * 256 + (int)threadIdx.x;
+            const int t = rem0 + l;
+            const int dr = t / d.qpr;
+            const int n = (t - dr * d.qpr) * 4;
+            int w = w0, m = m0 + dr;
+            while (m >= d.M) { m -= d.M; ++w; }
+            const int valid = d.K - 32 * w;
+            const uint32_t vmask = (w == words - 1 && valid < 32) ? ((1u << valid) - 1u) : 0xFFFFFFFFu;
+            if (raw & vmask) {                                 // the four words share every brick index (n / 32, n / 128)
+                uint8_t* bx = map_dx + ((int64_t)(w >> 3) * d.rbx + (m >> 7)) * d.sbx + (n >> 5);
+                uint8_t* bw = map_dw + ((int64_t)(w >> 3) * d.rbw + (n >> 7)) * d.sbw + (m >> 5);
+                if (!*bx) *bx = 1;                             // racing stores write the same value
+                if (!*bw) *bw = 1;
+            }
+        }
+    }
+}
+
+__global__ void lba_grad_zero_words_kernel(uint32_t* x, int64_t n) {
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += step) x[i] = 0u;
 }
 
 // x[0..n) = 0 with a grid-stride loop (the launch caps the grid: a grid dimension holds fewer than 2^32 lanes)
@@ -504,14 +595,24 @@ static hipError_t launch_grad(int ste, const float* G, const uint8_t* V, const u
 }
 
 // One of the two products.  Splits s over grid z when the (r, k) grid alone would leave the chip idle.
+// bricks: this side's brick map (immediate estimator / coefficient plane with a workspace), or NULL
 static int run_grad_side(bool dx, const float* G, const uint8_t* V, const uint32_t* plane, const int32_t* last_of,
-                         float* out, int64_t M, int64_t N, int64_t K, int ste, hipStream_t st) {
+                         float* out, int64_t M, int64_t N, int64_t K, int ste, hipStream_t st, const uint8_t* bricks = nullptr) {
     // coefficients that are constant inside a k tile: the matrix-core path (identity; recursive, with a sliver pass)
     if (ste == LBA_STE_IDENTITY && grad_dense_ok(G, V, nullptr, M, N, K))
         return run_grad_dense(dx, G, V, nullptr, out, M, N, K, st);
     if (ste == LBA_STE_RECURSIVE_OF && grad_dense_ok(G, V, last_of, M, N, K))
         return run_grad_dense(dx, G, V, last_of, out, M, N, K, st);
+    if (bricks) {
+        // the bricks whose coefficients are all 1 on the matrix cores (the output is overwritten, or zeroed and
+        // added to); the vector kernel below then adds the other bricks
+        const int rc = run_grad_dense(dx, G, V, nullptr, out, M, N, K, st, bricks);
+        if (rc != LBA_OK) return rc;
+    }
     GradDims gp;
+    gp.bricks = bricks;
+    gp.brick_rb = (int32_t)(((dx ? M : N) + 127) / 128);
+    gp.brick_sb = (int32_t)(((dx ? N : M) + 31) / 32);
     gp.plane_xor = (ste == LBA_STE_COEF_PLANE) ? 0u : 0xFFFFFFFFu;
     if (ste == LBA_STE_COEF_PLANE) ste = LBA_STE_IMMEDIATE_OF;   // same kernel, bits taken as they are
     gp.K = (int32_t)K;
@@ -521,11 +622,15 @@ static int run_grad_side(bool dx, const float* G, const uint8_t* V, const uint32
     const int64_t gx = (gp.R + 63) / 64, gy = (K + 63) / 64;      // row blocks on x (no 65535 limit there)
     int split = 1;
     plan_grad_split(gx * gy, gp.S, &split, &gp.s_chunk);
-    gp.atomic = split > 1 ? 1 : 0;
+    if (bricks) {                                              // slices of s on brick boundaries
+        gp.s_chunk = (gp.s_chunk + 31) / 32 * 32;
+        split = (int)((gp.S + gp.s_chunk - 1) / gp.s_chunk);
+    }
+    gp.atomic = (split > 1 || bricks) ? 1 : 0;
     const uintptr_t al = (uintptr_t)G | (uintptr_t)plane | (uintptr_t)last_of;
     gp.vec_ok = ((al % 16) == 0 && (N % 4) == 0) ? 1 : 0;
     gp.v16 = (((uintptr_t)V % 16) == 0 && (K % 16) == 0) ? 1 : 0;
-    if (gp.atomic) {
+    if (gp.atomic && !bricks) {
         const int64_t n = (int64_t)gp.R * K;
         hipLaunchKernelGGL(lba_grad_zero_kernel, zero_grid(n), dim3(256), 0, st, out, n);
         if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
@@ -575,8 +680,44 @@ int lba_ste_plane(const uint32_t* of_mask, const uint32_t* of_mask2, uint32_t* c
     return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
 }
 
+// bytes of the two brick maps (dX side first), each padded to a multiple of 256
+static void brick_bytes(int64_t M, int64_t N, int64_t K, size_t* dx_bytes, size_t* dw_bytes) {
+    const size_t kb = (size_t)((K + 255) / 256);
+    const size_t bx = kb * (size_t)((M + 127) / 128) * (size_t)((N + 31) / 32), bw = kb * (size_t)((N + 127) / 128) * (size_t)((M + 31) / 32);
+    *dx_bytes = (bx + 255) / 256 * 256;
+    *dw_bytes = (bw + 255) / 256 * 256;
+}
+
+size_t lba_grad_workspace_bytes(int64_t M, int64_t N, int64_t K) {
+    if (M <= 0 || N <= 0 || K <= 0 || lba::validate_shapes(M, N, K) != LBA_OK || M * N > ((int64_t)1 << 30)) return 0;
+    size_t a, b;
+    brick_bytes(M, N, K, &a, &b);
+    return a + b;
+}
+
+static int grad_impl(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
+                     float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* workspace, void* hip_stream);
+
 int lba_grad(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
              float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* hip_stream) {
+    return grad_impl(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, nullptr, hip_stream);
+}
+
+int lba_grad_ws(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
+                float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste,
+                void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const int rc = lba::validate_shapes(M, N, K);
+    if (rc != LBA_OK) return rc;
+    if (M > 0 && N > 0 && K > 0 && M * N <= ((int64_t)1 << 30)) {
+        if (!workspace) return LBA_ERR_NULL;
+        if (((uintptr_t)workspace % 256) != 0) return LBA_ERR_ALIGN;
+        if (workspace_bytes < lba_grad_workspace_bytes(M, N, K)) return LBA_ERR_SHAPE;
+    }
+    return grad_impl(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, workspace, hip_stream);
+}
+
+static int grad_impl(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
+                     float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* workspace, void* hip_stream) {
     int rc = lba::validate_shapes(M, N, K);
     if (rc != LBA_OK) return rc;
     if (ste != LBA_STE_IDENTITY && ste != LBA_STE_IMMEDIATE_OF && ste != LBA_STE_RECURSIVE_OF &&
@@ -599,12 +740,40 @@ int lba_grad(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t*
     if ((ste == LBA_STE_IMMEDIATE_OF || ste == LBA_STE_COEF_PLANE) && !of_mask) return LBA_ERR_NULL;
     if (ste == LBA_STE_RECURSIVE_OF && !last_of) return LBA_ERR_NULL;
     if ((dX && !B) || (dW && !A)) return LBA_ERR_NULL;         // every check before the first launch
+    // With a workspace, the immediate estimator (and a coefficient plane) splits the work by bricks: one pass over
+    // the plane marks the bricks that hold a blocked coefficient; the others are plain dense products and run on
+    // the matrix cores, the marked ones in the vector kernel that applies the plane bit by bit.  Every term is
+    // added by exactly one of the two kernels.
+    const uint8_t* bricks_dx = nullptr;
+    const uint8_t* bricks_dw = nullptr;
+    if (workspace && (ste == LBA_STE_IMMEDIATE_OF || ste == LBA_STE_COEF_PLANE) &&
+        lba::grad_dense_ok(G, nullptr, nullptr, M, N, K) && ((uintptr_t)of_mask % 16) == 0) {
+        size_t bx, bw;
+        brick_bytes(M, N, K, &bx, &bw);
+        uint8_t* map_dx = (uint8_t*)workspace;
+        uint8_t* map_dw = map_dx + bx;
+        const int64_t words4 = (int64_t)((bx + bw) / 4);
+        hipLaunchKernelGGL(lba::lba_grad_zero_words_kernel, lba::zero_grid(words4), dim3(256), 0, st, (uint32_t*)workspace, words4);
+        if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
+        lba::BrickDims bd;
+        bd.quads = ((K + 31) / 32) * M * (N / 4);
+        bd.M = (int32_t)M; bd.N = (int32_t)N; bd.K = (int32_t)K; bd.qpr = (int32_t)(N / 4);
+        bd.rbx = (int32_t)((M + 127) / 128); bd.sbx = (int32_t)((N + 31) / 32);
+        bd.rbw = (int32_t)((N + 127) / 128); bd.sbw = (int32_t)((M + 31) / 32);
+        bd.flip = (ste == LBA_STE_COEF_PLANE) ? 0xFFFFFFFFu : 0u;   // a coefficient plane blocks where a bit is clear
+        const int64_t wgs = (bd.quads + lba::kBrickQuadsPerWg - 1) / lba::kBrickQuadsPerWg;
+        if (wgs > 2147483647LL) return LBA_ERR_SHAPE;
+        hipLaunchKernelGGL(lba::lba_brick_map_kernel, dim3((unsigned)wgs), dim3(256), 0, st, of_mask, map_dx, map_dw, bd);
+        if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
+        bricks_dx = map_dx;
+        bricks_dw = map_dw;
+    }
     if (dX) {
-        rc = lba::run_grad_side(true, G, B, of_mask, last_of, dX, M, N, K, ste, st);
+        rc = lba::run_grad_side(true, G, B, of_mask, last_of, dX, M, N, K, ste, st, bricks_dx);
         if (rc != LBA_OK) return rc;
     }
     if (dW) {
-        rc = lba::run_grad_side(false, G, A, of_mask, last_of, dW, M, N, K, ste, st);
+        rc = lba::run_grad_side(false, G, A, of_mask, last_of, dW, M, N, K, ste, st, bricks_dw);
         if (rc != LBA_OK) return rc;
     }
     return LBA_OK;

@@ -45,6 +45,7 @@ struct DenseDims {
     int32_t b_chunk;           // sliver pass: s values per grid y (a multiple of 256)
     int32_t k_shift;           // log2 of the k tile of the dense pass (the sliver pass cuts k into the same blocks)
     int32_t v_vec;             // 1: every row of codes starts 4-byte aligned (V % 4 == 0, K % 4 == 0)
+    int32_t brick_rb, brick_sb; // brick map of the immediate estimator: byte ((k / 256) * brick_rb + r / 128) * brick_sb + s / 32
 };
 
 // DTK (a template argument): 128 or 256 columns k per workgroup; the wider tile splits G half as often and is
@@ -87,7 +88,8 @@ __device__ __forceinline__ void decode4(uint32_t w, float (&v)[4]) {
 template <bool S_CONTIG, bool MASKED, int DTK>
 __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __restrict__ G, const uint8_t* __restrict__ V,
                                                                 const int32_t* __restrict__ L,
-                                                                float* __restrict__ out, const DenseDims d) {
+                                                                float* __restrict__ out, const DenseDims d,
+                                                                const uint8_t* __restrict__ bricks) {
     constexpr int DNBJ = DTK / 64;                             // MFMA column blocks per wave (two waves side by side)
     __shared__ __attribute__((aligned(16))) uint16_t sA[3][DTR * DPITCH];
     __shared__ __attribute__((aligned(16))) uint16_t sB[DTK * DPITCH];
@@ -156,8 +158,15 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
 #pragma unroll
             for (int t = 0; t < 16; ++t) acc[i][j][t] = 0.0f;
 
+    // Immediate estimator: a brick (128 rows x 32 s x 256 k) in which some coefficient is 0 is left to the vector
+    // kernel, which applies the coefficients bit by bit; this kernel adds the bricks whose coefficients are all 1.
+    const uint8_t* __restrict__ brick_row = bricks ? bricks + ((int64_t)(k0 >> 8) * d.brick_rb + (r0 >> 7)) * d.brick_sb : nullptr;
     fetch(s_begin);
     for (int sb = s_begin; sb < s_end; sb += DBS) {
+        if (brick_row && brick_row[sb >> 5]) {                 // uniform over the workgroup
+            if (sb + DBS < s_end) fetch(sb + DBS);
+            continue;
+        }
         // split / decode this step's patches into LDS
         {
             float g[4][4];                                     // [row a][s b]
@@ -327,8 +336,10 @@ bool grad_dense_ok(const float* G, const uint8_t* V, const int32_t* last_of, int
 // One of the two products with the identity coefficients (last_of == NULL) or the recursive ones.
 // LBA_OK or LBA_ERR_LAUNCH.
 int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* last_of, float* out,
-                   int64_t M, int64_t N, int64_t K, hipStream_t st) {
+                   int64_t M, int64_t N, int64_t K, hipStream_t st, const uint8_t* bricks) {
     DenseDims d;
+    d.brick_rb = (int32_t)(((dx ? M : N) + 127) / 128);
+    d.brick_sb = (int32_t)(((dx ? N : M) + 31) / 32);
     d.R = (int32_t)(dx ? M : N); d.S = (int32_t)(dx ? N : M); d.K = (int32_t)K; d.ld_g = (int32_t)N;
     d.b_chunk = d.S;
     d.v_vec = (((uintptr_t)V % 4) == 0 && (K % 4) == 0) ? 1 : 0;
@@ -351,8 +362,8 @@ int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* las
         if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
     }
     const dim3 grid((unsigned)gx, (unsigned)gy, (unsigned)split);
-#define LBA_DENSE(SC, MK) do { if (wide) hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 256>), grid, dim3(256), 0, st, G, V, last_of, out, d); \
-                               else      hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 128>), grid, dim3(256), 0, st, G, V, last_of, out, d); } while (0)
+#define LBA_DENSE(SC, MK) do { if (wide) hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 256>), grid, dim3(256), 0, st, G, V, last_of, out, d, bricks); \
+                               else      hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 128>), grid, dim3(256), 0, st, G, V, last_of, out, d, bricks); } while (0)
     if (!last_of) {
         if (dx) LBA_DENSE(true, false); else LBA_DENSE(false, false);
         return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;

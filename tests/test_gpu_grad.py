@@ -290,3 +290,75 @@ def test_coefficient_planes_and_the_recursive_estimator_of_the_chunked_order(ref
     assert lb.lba_ste_plane(of.data_ptr(), None, of.data_ptr(), M, N, K, lb.STE_RECURSIVE_OF, 1) == lb.ERR_NULL
     assert lb.lba_ste_plane(of.data_ptr(), None, of.data_ptr(), M, N, K, lb.STE_IDENTITY, 0) == lb.ERR_UNSUPPORTED
     assert lb.lba_ste_plane(None, None, of.data_ptr(), M, N, K, lb.STE_IMMEDIATE_OF, 0) == lb.ERR_NULL
+
+
+def test_immediate_estimator_split_by_bricks(ref, gref):
+    # lba_grad_ws: bricks (128 rows x 32 summed indices x 256 k) without a blocked coefficient run on the matrix
+    # cores, the others in the vector kernel; every term is added by exactly one of them.  Planes without any
+    # overflow, with overflows in the last part of the chains only (clean and marked bricks side by side, in both
+    # directions), and with overflows everywhere; shapes ragged against the bricks, several k bricks, sums split over
+    # workgroups, the general path (N % 4 != 0: no bricks); a coefficient plane (recursive estimator of the chunked
+    # order).  Bit-exact on exactly representable sums, then the FP32 bound on general data; the workspace is filled
+    # with garbage first and is shared by consecutive calls.
+    rng = np.random.default_rng(777)
+    QPb, QAb = (4, 7, 12, 0), (4, 7, 10, 0)                        # R_OF = 63.75
+    ws = torch.full((1 << 20,), 0xA5, dtype=torch.uint8, device=DEV)
+    kinds = set()
+    for (M, N, K), loud in [((300, 200, 600), "tail"), ((130, 68, 260), "none"), ((260, 132, 515), "all"), ((64, 516, 640), "tail"),
+                            ((3000, 24, 300), "tail"), ((40, 2100, 72), "all"), ((257, 36, 1028), "tail"), ((70, 66, 100), "tail"),
+                            ((33, 130, 65), "all"), ((1500, 64, 147), "rows")]:
+        assert lb.lba_grad_workspace_bytes(M, N, K) <= ws.numel()
+        A = codes(rng, (M, K), 2, 5); B = codes(rng, (N, K), 2, 5)           # products below 2^-5: no sum reaches R_OF
+        if loud == "tail":
+            A[:, K - K // 3:] = codes(rng, (M, K // 3), 6, 10); B[:, K - K // 3:] = codes(rng, (N, K // 3), 6, 10)
+        elif loud == "all":
+            A = codes(rng, (M, K), 5, 10); B = codes(rng, (N, K), 5, 10)
+        elif loud == "rows":
+            A[M // 2: M // 2 + 40] = codes(rng, (40, K), 7, 10); B[:, :] = codes(rng, (N, K), 5, 8)
+        tA, tB, of = gpu_inputs(ref, A, B, QPb, QAb)
+        ofn = of.cpu().numpy()
+        kinds.add("clean" if not ofn.any() else ("mixed" if (ofn == 0).all(axis=(1, 2)).any() or loud == "rows" else "dirty"))
+        for exact in (True, False):
+            G = (rng.integers(-8, 9, (M, N)) / 4.0).astype(np.float32) if exact else rng.standard_normal((M, N)).astype(np.float32)
+            if not exact:                                                    # general data: full-range operands in the loud part
+                pass
+            tG = torch.from_numpy(G).to(DEV)
+            dX, dW = lb.grad(tG, tA, tB, lb.STE_IMMEDIATE_OF, of_plane=of, workspace=ws)
+            torch.cuda.synchronize()
+            dX, dW = dX.cpu().numpy(), dW.cpu().numpy()
+            wX, wW = gref.grad(G, A, B, ref.QFmt(*QPb), ref.QFmt(*QAb), 1)
+            if exact:
+                assert np.array_equal(dX, wX.astype(np.float32)), (M, N, K, loud, "dX", np.abs(dX - wX).max())
+                assert np.array_equal(dW, wW.astype(np.float32)), (M, N, K, loud, "dW", np.abs(dW - wW).max())
+            else:
+                aX, aW = gref.grad_abs(G, A, B, ref.QFmt(*QPb), ref.QFmt(*QAb), 1)
+                assert (np.abs(dX - wX) <= 2 * (N + 1) * 2.0 ** -24 * aX + 1e-30).all(), (M, N, K, loud, "dX")
+                assert (np.abs(dW - wW) <= 2 * (M + 1) * 2.0 ** -24 * aW + 1e-30).all(), (M, N, K, loud, "dW")
+            # the same call without the workspace agrees within the same bound (bit for bit on exact data)
+            pX, pW = lb.grad(tG, tA, tB, lb.STE_IMMEDIATE_OF, of_plane=of)
+            torch.cuda.synchronize()
+            if exact:
+                assert np.array_equal(pX.cpu().numpy(), dX) and np.array_equal(pW.cpu().numpy(), dW)
+    assert kinds == {"clean", "mixed", "dirty"}, kinds
+    # a coefficient plane: the recursive estimator of the chunked order
+    M, N, K = 260, 132, 515
+    A = codes(rng, (M, K), 2, 5); B = codes(rng, (N, K), 2, 5)
+    A[:, 300:400] = codes(rng, (M, 100), 6, 10); B[:, 300:400] = codes(rng, (N, 100), 6, 10)
+    tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    _, of, _, of2, _ = lb.gemm_bwd_chunked(tA, tB, QPb, QAb, want_c=False)
+    coef = lb.ste_plane(of, K, lb.STE_RECURSIVE_OF, order=1, of_plane2=of2)
+    G = (rng.integers(-8, 9, (M, N)) / 4.0).astype(np.float32)
+    dX, dW = lb.grad(torch.from_numpy(G).to(DEV), tA, tB, lb.STE_COEF_PLANE, of_plane=coef, workspace=ws)
+    torch.cuda.synchronize()
+    wX, wW = gref.grad(G, A, B, ref.QFmt(*QPb), ref.QFmt(*QAb), 2, 1)
+    assert np.array_equal(dX.cpu().numpy(), wX.astype(np.float32)) and np.array_equal(dW.cpu().numpy(), wW.astype(np.float32))
+    c = gref.coefficients(A, B, ref.QFmt(*QPb), ref.QFmt(*QAb), 2, 1)
+    assert 0 < c.sum() < c.size
+    # argument errors: nothing is enqueued
+    ptr = lambda t: t.data_ptr()
+    args = (ptr(torch.from_numpy(G).to(DEV)), ptr(tA), ptr(tB), ptr(coef), None, ptr(dX), ptr(dW), M, N, K, lb.STE_COEF_PLANE)
+    assert lb.lba_grad_ws(*args, None, 1 << 20) == lb.ERR_NULL
+    assert lb.lba_grad_ws(*args, ptr(ws) + 4, 1 << 19) == lb.ERR_ALIGN
+    assert lb.lba_grad_ws(*args, ptr(ws), lb.lba_grad_workspace_bytes(M, N, K) - 1) == lb.ERR_SHAPE
+    assert lb.lba_grad_ws(*args, ptr(ws), lb.lba_grad_workspace_bytes(M, N, K)) == lb.OK
+    torch.cuda.synchronize()
