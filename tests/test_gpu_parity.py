@@ -395,7 +395,7 @@ def test_random_formats(ref):
         picked.add((plan["kernel"], rnd, plan["valu_per_mac_x100"] >= 1000))
         check(ref, A, B, qpf, qaf, "random format %d" % done, order=order)
         done += 1
-    assert {(0, 0, False), (0, 1, False), (0, 1, True), (1, 1, False)} <= picked, picked
+    assert {(0, 0, False), (0, 1, False), (0, 1, True), (1, 1, True)} <= picked, picked
 
 
 def test_no_underflow_accumulators_with_a_tiny_range(ref):
