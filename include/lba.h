@@ -274,6 +274,17 @@ int lba_grad_ws(const float* G, const uint8_t* A, const uint8_t* B,
                 float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* lba_grad_ws for callers that cannot allocate device memory (code under HIP graph capture, serving loops,
+ * harnesses that forbid hipMalloc): the brick maps live in 1 MiB of device memory that belongs to the library
+ * itself (one copy per GPU, held until the process ends), so the call takes no workspace and allocates nothing.
+ * Shapes whose maps would not fit, lba_grad_workspace_bytes(M, N, K) > 2^20 (about M * N * K > 5 * 10^11), are
+ * refused with LBA_ERR_SHAPE: use lba_grad_ws.  Results and every other error as lba_grad_ws.  All calls on one GPU
+ * share that memory (it is cleared by each call that uses it): calls of lba_grad_static that overlap on one GPU,
+ * from several streams or threads, race; calls on one stream, or otherwise ordered, are fine. */
+int lba_grad_static(const float* G, const uint8_t* A, const uint8_t* B,
+                    const uint32_t* of_mask, const int32_t* last_of,
+                    float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* hip_stream);
+
 /* Bytes of workspace lba_grad_ws needs for a shape (two brick maps: about M * N * K / 2^19 bytes; 0 for an empty
  * or invalid shape). */
 size_t lba_grad_workspace_bytes(int64_t M, int64_t N, int64_t K);

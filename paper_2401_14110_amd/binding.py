@@ -96,6 +96,8 @@ def lib(path=None):
         L.lba_grad.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
         L.lba_grad_ws.restype = ctypes.c_int
         L.lba_grad_ws.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
+        L.lba_grad_static.restype = ctypes.c_int
+        L.lba_grad_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
         L.lba_grad_workspace_bytes.restype = ctypes.c_size_t
         L.lba_grad_workspace_bytes.argtypes = [i64, i64, i64]
         L.lba_mask_words.restype = ctypes.c_size_t
@@ -219,6 +221,11 @@ def lba_grad(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, hip_stream=None):
 def lba_grad_ws(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, workspace, workspace_bytes, hip_stream=None):
     return lib().lba_grad_ws(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, workspace, workspace_bytes,
                              ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_grad_static(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, hip_stream=None):
+    return lib().lba_grad_static(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste,
+                                 ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
 
 
 def lba_grad_workspace_bytes(M, N, K):

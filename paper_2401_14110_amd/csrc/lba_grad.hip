@@ -23,6 +23,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "lba.h"
 #include "lba_internal.h"
 
@@ -714,6 +716,39 @@ int lba_grad_ws(const float* G, const uint8_t* A, const uint8_t* B, const uint32
         if (workspace_bytes < lba_grad_workspace_bytes(M, N, K)) return LBA_ERR_SHAPE;
     }
     return grad_impl(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, workspace, hip_stream);
+}
+
+// The brick maps of lba_grad_static: device memory that belongs to the library (every GPU the library runs on holds
+// its own copy until the process ends).  In host code the array's name is only a handle: its device address is asked
+// for once per device and kept.
+#define LBA_GRAD_STATIC_BYTES (1 << 20)
+static __device__ __align__(256) unsigned char scratch[LBA_GRAD_STATIC_BYTES];
+
+static int static_scratch(void** out) {
+    static std::mutex mu;
+    static void* addr[64] = {nullptr};                         // per device
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return LBA_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!addr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return LBA_ERR_LAUNCH;
+        addr[dev] = p;
+    }
+    *out = addr[dev];
+    return LBA_OK;
+}
+
+int lba_grad_static(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
+                    float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* hip_stream) {
+    const int rc = lba::validate_shapes(M, N, K);
+    if (rc != LBA_OK) return rc;
+    if (M > 0 && N > 0 && K > 0 && M * N <= ((int64_t)1 << 30) && lba_grad_workspace_bytes(M, N, K) > (size_t)LBA_GRAD_STATIC_BYTES)
+        return LBA_ERR_SHAPE;                                  // beyond the library's own scratch memory: use lba_grad_ws
+    void* ws = nullptr;
+    const int rs = static_scratch(&ws);
+    if (rs != LBA_OK) return rs;
+    return grad_impl(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, ws, hip_stream);
 }
 
 static int grad_impl(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
