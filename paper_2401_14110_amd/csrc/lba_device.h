@@ -413,10 +413,11 @@ __device__ __forceinline__ void store_tile(float* __restrict__ dst /* [BK][ROWS]
 // decoded arithmetically (integer significand times a power of two).
 // PAD: floats inserted after every 16 k (the K-parallel kernel reads several 16-k pieces at once and keeps them
 // on different banks that way).
+// lane_max (E4M3 path only): if not null, raised to the largest magnitude this lane stored.
 template <int ROWS, int BK, int PAD = 0>
 __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][ROWS] */, float scale,
                                                int tid, const uint4 (&regs)[Stage<ROWS, BK>::kPerLane],
-                                               int E = 4, int M = 3, int scale_exp = 0) {
+                                               int E = 4, int M = 3, int scale_exp = 0, float* lane_max = nullptr) {
     typedef float v2f __attribute__((ext_vector_type(2)));
     if (E != 4) {                                              // uniform
 #pragma unroll
@@ -472,8 +473,32 @@ __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][R
             }
 #pragma unroll
             for (int j = 0; j < 16; ++j) dst[(kq * 16 + j) * ROWS + row + kq * PAD] = f[j];
+            if (lane_max) {
+                float m = *lane_max;
+#pragma unroll
+                for (int j = 0; j < 16; j += 2) m = __builtin_fmaxf(m, __builtin_fmaxf(__builtin_fabsf(f[j]), __builtin_fabsf(f[j + 1])));
+                *lane_max = m;
+            }
         }
     }
+}
+
+// Largest magnitudes of the operand tiles a workgroup has just staged, for a bound on the tile's products that
+// follows the data: every lane hands in the largest magnitude it stored (0 if it stored nothing); lanes 0..127
+// stage A, lanes 128..255 stage B.  slot: 4 floats of LDS, published by the next barrier.
+__device__ __forceinline__ void publish_tile_max(float* slot, float lane_max, int tid) {
+    float m = lane_max;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = __builtin_fmaxf(m, __shfl_xor(m, o, 64));
+    if ((tid & 63) == 0) slot[tid >> 6] = m;
+}
+
+// R_OF (shrunk by the growth of nearest-even rounding over the tile) minus 32 products of the largest operands
+// of the tile: sums that start the tile below it cannot reach R_OF inside it.  The factor covers the roundings
+// of this expression itself.
+__device__ __forceinline__ float tile_threshold(const float* slot, float rof_grow1, float kc) {
+    const float amax = __builtin_fmaxf(slot[0], slot[1]), bmax = __builtin_fmaxf(slot[2], slot[3]);
+    return rof_grow1 - 32.0f * 1.001f * (amax * bmax) * kc;
 }
 
 // Reads the TM + TN operand values of one k from an LDS stage (TM, TN in {2, 4}): the lane's
@@ -629,11 +654,25 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
     uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
     const int ntiles = (p.K + BK - 1) / BK;                    // K > 0 here; division by a constant
 
+    // Formats whose R_OF is within a few maximal products of zero (the planner's flag: the fixed bounds below fail
+    // for four tiles at once) also get a bound per tile from the operands actually staged.
+    __shared__ float tile_max[2][4];
+    const bool dyn = !AMODE && p.dyn_bound != 0;               // uniform
+    auto stage_tiles = [&](float* Ad, int st) {
+        if (dyn) {
+            float lm = 0.0f;
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, 4, 3, 0, &lm);
+            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, 4, 3, 0, &lm);
+            publish_tile_max(tile_max[st], lm, tid);
+        } else {
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
+            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
+        }
+    };
     if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
     else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
     fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
-    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
-    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
+    stage_tiles(smem, 0);
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
@@ -661,6 +700,7 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
                              ? __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(top[i][j]), __builtin_fabsf(top[i][j + 1])))
                              : __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(acc[i][j]), __builtin_fabsf(acc[i][j + 1])));
             safe_tiles = __all(mx < thresh4) ? 4 : (__all(mx < thresh) ? 1 : 0);
+            if (dyn && safe_tiles == 0 && __all(mx < tile_threshold(tile_max[t & 1], p.rof_grow1, c.kc))) safe_tiles = 1;
         }
         if (safe_tiles > 0) {
             --safe_tiles;
@@ -668,11 +708,7 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
         } else {
             fast_tile<PM, RND, ORDER, true, TM, TN, BK, BM, BN>(acc, top, As, Bs, tx, ty, c);
         }
-        if (more) {
-            float* Ad = smem + ((t + 1) & 1) * STAGE;
-            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
-            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
-        }
+        if (more) stage_tiles(smem + ((t + 1) & 1) * STAGE, (t + 1) & 1);
         __syncthreads();
     }
     if (RND == LBA_ROUND_FLOOR || RND == RND_RNE_ODD) set_round_nearest();
@@ -1139,11 +1175,24 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
     uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
     const int ntiles = (p.K + BK - 1) / BK;
 
+    // (the bound per tile from the operands actually staged: see fast_body)
+    __shared__ float tile_max[2][4];
+    const bool dyn = !AMODE && p.dyn_bound != 0;               // uniform
+    auto stage_tiles = [&](float* Ad, int st) {
+        if (dyn) {
+            float lm = 0.0f;
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, 4, 3, 0, &lm);
+            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, 4, 3, 0, &lm);
+            publish_tile_max(tile_max[st], lm, tid);
+        } else {
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
+            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
+        }
+    };
     if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
     else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
     fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
-    store_tile_cvt<BM, BK>(smem, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
-    store_tile_cvt<BN, BK>(smem + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
+    stage_tiles(smem, 0);
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
@@ -1165,7 +1214,7 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
                 mx = (ORDER == LBA_ORDER_CHUNK16)
                          ? __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(top[i][j]), __builtin_fabsf(top[i][j + 1])))
                          : __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(acc[i][j]), __builtin_fabsf(acc[i][j + 1])));
-        const bool quiet = __all(mx < thresh);
+        const bool quiet = __all(mx < thresh) || (dyn && __all(mx < tile_threshold(tile_max[t & 1], p.rof_grow1, c.kc)));
         if (quiet && !UF) {
             constexpr int FRND = RND == LBA_ROUND_FLOOR ? LBA_ROUND_FLOOR : LBA_ROUND_RNE;
             fast_tile<PM, FRND, ORDER, false, TM, TN, BK, BM, BN>(acc, top, As, Bs, tx, ty, fc);
@@ -1187,11 +1236,7 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
             store_event_words(p.of_mask2, UF ? p.uf_mask2 : nullptr, t >> 4, 2 * ((t & 15) + 1), chunks - 32 * (t >> 4),
                               wof2, wuf2, m0, n0, tx, ty, p);
         }
-        if (more) {
-            float* Ad = smem + ((t + 1) & 1) * STAGE;
-            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
-            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
-        }
+        if (more) stage_tiles(smem + ((t + 1) & 1) * STAGE, (t + 1) & 1);
         __syncthreads();
     }
     if (RND == LBA_ROUND_FLOOR) set_round_nearest();

@@ -34,6 +34,9 @@ struct KParams {
     float kc;                // FAST with an explicit product: t = p * kc + S
     float fast_thresh;       // FAST: a k-tile needs no clamp if every |S| is below this at its start
     float fast_thresh4;      // FAST: same for four consecutive k-tiles
+    int32_t dyn_bound;       // FAST: 1: the four-tile bound fails (R_OF within 128 maximal products of zero): also test, per
+                             // k-tile, R_OF against 32 products of the largest operands actually staged
+    float rof_grow1;         // FAST: R_OF divided by the growth nearest-even rounding can add over one k-tile (rounded down)
     // accumulator quantizer, in the kernel's (possibly scaled) domain
     uint32_t mask_a; uint32_t half_a; int32_t sh_a; float rof_a; float ruf_a;
     // product quantizer

@@ -353,6 +353,14 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
             if ((double)thf > th) thf = std::nextafterf(thf, -INFINITY);
             if (th > 0.0 && thf > 0.0f) (n == 1 ? kp.fast_thresh : kp.fast_thresh4) = thf;
         }
+        // the bound that follows the data (kernels for E4M3 matrices only): wanted where the fixed one is weak
+        double g1 = (double)kp.rof_a;
+        if (qa.round == LBA_ROUND_RNE)
+            g1 /= std::pow((1.0 + std::ldexp(1.0, -qa.man_bits - 1)) * (1.0 + std::ldexp(1.0, -24)), p.bk);
+        float g1f = (float)g1;
+        if ((double)g1f > g1) g1f = std::nextafterf(g1f, -INFINITY);
+        kp.rof_grow1 = g1f;
+        kp.dyn_bound = (!p.amode && !p.rne_odd && kp.fast_thresh4 <= 0.0f) ? 1 : 0;
     }
     const int64_t bm = 16 * p.tm, bn = 16 * p.tn;
     p.grid_x = (int)((M + bm - 1) / bm);
