@@ -280,7 +280,9 @@ int lba_grad_ws(const float* G, const uint8_t* A, const uint8_t* B,
  * Shapes whose maps would not fit, lba_grad_workspace_bytes(M, N, K) > 2^20 (about M * N * K > 5 * 10^11), are
  * refused with LBA_ERR_SHAPE: use lba_grad_ws.  Results and every other error as lba_grad_ws.  All calls on one GPU
  * share that memory (it is cleared by each call that uses it): calls of lba_grad_static that overlap on one GPU,
- * from several streams or threads, race; calls on one stream, or otherwise ordered, are fine. */
+ * from several streams or threads, race; calls on one stream, or otherwise ordered, are fine.  The first call on
+ * a device looks the memory's address up (no allocation, but a runtime query): make it before a stream capture
+ * starts. */
 int lba_grad_static(const float* G, const uint8_t* A, const uint8_t* B,
                     const uint32_t* of_mask, const int32_t* last_of,
                     float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* hip_stream);
