@@ -85,7 +85,7 @@ def cpu_baseline(layer, qp, qa, C_gpu, order=0, threads=None, budget_macs=2.0e9)
             "bit_exact_vs_gpu": parity}
 
 
-def main():
+def make_parser():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
@@ -120,7 +120,16 @@ def main():
     ap.add_argument("--dump-kernels", default=None, metavar="FILE",
                     help="write the kernels of one step (name, launches, MACs, algorithmic bytes, issue slots per MAC) as "
                          "JSON: the input rocprof_record.py pairs with the profiler's per-kernel counters")
-    args = ap.parse_args()
+    ap.add_argument("--paper-biases", action="store_true",
+                    help="Q_prod = M7E4 b=12, Q_acc = M7E4 b=10: the paper's own bias pair (Sec. 3.1) instead of M7E5 b=15 / M7E4 b=7")
+    ap.add_argument("--suite", default=None, metavar="OUT.md",
+                    help="run every configuration of the summary table (SUITE below) one after the other and write the table "
+                         "to OUT.md and the JSON lines to OUT.jsonl")
+    return ap
+
+
+def run(args):
+    """One benchmark configuration; returns the dictionary of the JSON line."""
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs on ONE GPU (every output chain is independent; "
                          "rows of A and of C would shard across GPUs with B replicated and nothing exchanged). Use --gpus 1.")
@@ -136,6 +145,9 @@ def main():
     order = 0 if args.order == "seq" else 1
 
     acc_fmt = ACC_FMT
+    prod_fmt = PROD_FMT
+    if args.paper_biases:
+        prod_fmt, acc_fmt = (4, 7, 12), (4, 7, 10)
     if args.acc:
         e, m = (int(v) for v in args.acc.split(","))
         acc_fmt = (e, m, 2 ** (e - 1) - 1)
@@ -152,14 +164,14 @@ def main():
     Cbuf = torch.empty(cmax, dtype=torch.float32, device=dev)
     for l in layers:
         if in_fmt:                                          # biases stay in real units: the library folds the flex biases
-            l["qp"], l["qa"] = PROD_FMT + (rnd,), acc_fmt + (rnd,)
+            l["qp"], l["qa"] = prod_fmt + (rnd,), acc_fmt + (rnd,)
             l["fa"], l["fb"] = in_fmt + (l["ta"],), in_fmt + (l["tb"],)
             l["plan"] = lb.lba_plan_query_in(l["M"], l["N"], l["K"], l["fa"], l["fb"], l["qp"], l["qa"], order, 1 if args.bwd else 0)
             if args.bwd and args.of_only:
                 fwd = lb.lba_plan_query_in(l["M"], l["N"], l["K"], l["fa"], l["fb"], l["qp"], l["qa"], order, 0)
                 l["plan"] = dict(l["plan"], valu_per_mac_x100=fwd["valu_per_mac_x100"])
         else:
-            l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], PROD_FMT, acc_fmt, rnd)
+            l["qp"], l["qa"], _ = inputs.folded_formats(l["ta"], l["tb"], prod_fmt, acc_fmt, rnd)
             l["plan"] = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, with_masks)
             l["kname"] = lb.lba_plan_kernel_name(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, with_masks)
             if args.bwd and args.of_only and order == 0:
@@ -330,7 +342,8 @@ def main():
     achieved = dom["macs"] * dom["ops"] / (dom["ms"] * 1e-3)
     workload_key = "%s:%s:%s:%s:acc=%d,%d" % (
         args.workload, ("grad-" + args.grad) if args.grad else ("diff" if args.diff is not None else ("bwd-of" if args.of_only else "bwd")) if args.bwd else "fwd",
-        args.round, args.order, acc_fmt[0], acc_fmt[1]) + (":in=%d,%d" % in_fmt if in_fmt else "") + (":implicit" if args.implicit else "")
+        args.round, args.order, acc_fmt[0], acc_fmt[1]) + (":in=%d,%d" % in_fmt if in_fmt else "") + (":implicit" if args.implicit else "") + (
+        ":paper-biases" if args.paper_biases else "")
     rec = counter_record(workload_key, dom_name)
     probe_rate = None
     if rec and rec.get("probe_mix"):
@@ -410,7 +423,7 @@ def main():
                                 "conv": "ResNet-18 3x3 conv 64->64, batch 32, 56x56 (M=100352,N=64,K=576)",
                                 "bert": "BERT-base linears, 4096 tokens", "gemm4096": "4096^3 GEMM",
                                 "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}[args.workload],
-                   "macs_per_step": total_macs, "qprod": "M7E5 b=15", "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
+                   "macs_per_step": total_macs, "qprod": "M%dE%d b=%d" % (prod_fmt[1], prod_fmt[0], prod_fmt[2]), "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
                    "call": ("%s, %s estimator: dX and dW (2 masked MACs per forward MAC)" % ("lba_grad_ws" if args.grad == "immediate" else "lba_grad", args.grad)) if args.grad else ("lba_gemm_bwd_diff (C + DIFF plane, eps2 = %g)" % args.diff) if args.diff is not None else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else ("lba_gemm_bwd (C + OF plane)" if args.of_only else "lba_gemm_bwd (C + OF and UF planes)")) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
                    "conv": "implicit im2col from NHWC activations (lba_conv2d)" if args.implicit else "operand A is the written-out im2col matrix",
                    "operands": ("E%dM%d codes with per-tensor flex bias (lba_gemm_in)" % in_fmt) if in_fmt else "E4M3"},
@@ -423,7 +436,129 @@ def main():
         launch(l)
         torch.cuda.synchronize()
         out["cpu_baseline"] = cpu_baseline(l, l["qp"], l["qa"], l["C"], order, args.cpu_threads)
-    print(json.dumps(out))
+    return out
+
+
+# The configurations of profiles/all_configs_summary.md: (section, label, flags).
+SUITE = [
+    ("main", "1: 64x64x256, nearest-even (launch latency)", "--workload config1 --round rne --steps 200 --warmup 20"),
+    ("main", "1: same, chunks of 16 (K-parallel kernel)", "--workload config1 --round rne --order chunk16 --steps 200 --warmup 20"),
+    ("main", "2: ResNet-18 conv 100352x64x576, floor", "--workload conv --steps 20"),
+    ("main", "2: same, nearest-even", "--workload conv --round rne --steps 20"),
+    ("main", "3: ResNet-50 sweep, 54 GEMMs, floor (headline)", ""),
+    ("main", "3: same, nearest-even", "--round rne"),
+    ("main", "3: same, chunks of 16", "--order chunk16"),
+    ("main", "3: same, chunks of 16, the paper's biases (10, 12)", "--order chunk16 --paper-biases"),
+    ("main", "4: BERT-base linears, floor", "--workload bert --steps 10"),
+    ("main", "4: same, nearest-even", "--workload bert --round rne --steps 10"),
+    ("main", "2: lba_gemm_bwd (C + 2 planes)", "--workload conv --bwd --steps 3 --warmup 1"),
+    ("main", "3: lba_gemm_bwd (C + 2 planes), ResNet-50 sweep", "--bwd --steps 3 --warmup 1"),
+    ("main", "3: same, nearest-even", "--bwd --round rne --steps 3 --warmup 1"),
+    ("main", "4: lba_gemm_bwd (C + 2 planes)", "--workload bert --bwd --steps 3 --warmup 1"),
+    ("main", "5: 4096^3 lba_gemm_bwd, Q_acc M3E4", "--workload gemm4096 --acc 4,3 --bwd --steps 3 --warmup 1"),
+    ("main", "5: 4096^3 lba_gemm_bwd, Q_acc M7E4", "--workload gemm4096 --acc 4,7 --bwd --steps 3 --warmup 1"),
+    ("main", "5: same, nearest-even", "--workload gemm4096 --acc 4,7 --round rne --bwd --steps 3 --warmup 1"),
+    ("main", "5: 4096^3 lba_gemm_bwd, Q_acc M10E6", "--workload gemm4096 --acc 6,10 --bwd --steps 3 --warmup 1"),
+    ("wide", "lba_gemm_bwd, OF plane only, ResNet-50 sweep", "--bwd --of-only --steps 5"),
+    ("wide", "same, BERT-base linears", "--workload bert --bwd --of-only --steps 5"),
+    ("wide", "same, ResNet-18 conv", "--workload conv --bwd --of-only --steps 10"),
+    ("wide", "same, 4096^3, Q_acc M7E4", "--workload gemm4096 --acc 4,7 --bwd --of-only --steps 3 --warmup 1"),
+    ("wide", "same, 4096^3, Q_acc M7E5", "--workload gemm4096 --acc 5,7 --bwd --of-only --steps 3 --warmup 1"),
+    ("wide", "lba_gemm_bwd_diff (C + DIFF plane, eps2 = 0.25), 4096^3, Q_acc M7E4", "--workload gemm4096 --acc 4,7 --bwd --diff 0.25 --steps 3 --warmup 1"),
+    ("wide", "same, nearest-even", "--workload gemm4096 --acc 4,7 --round rne --bwd --diff 0.25 --steps 3 --warmup 1"),
+    ("wide", "same, chunks of 16", "--workload gemm4096 --acc 4,7 --bwd --diff 0.25 --order chunk16 --steps 3 --warmup 1"),
+    ("wide", "same, Q_acc M7E5, nearest-even", "--workload gemm4096 --acc 5,7 --round rne --bwd --diff 0.25 --steps 3 --warmup 1"),
+    ("wide", "same, BERT-base linears, M7E4", "--workload bert --bwd --diff 0.25 --steps 3 --warmup 1"),
+    ("wide", "same, ResNet-50 sweep, M7E4", "--bwd --diff 0.25 --steps 3 --warmup 1"),
+    ("wide", "lba_gemm_bwd_chunked (C + 4 planes), 4096^3", "--workload gemm4096 --acc 4,7 --bwd --order chunk16 --steps 3 --warmup 1"),
+    ("wide", "same, BERT-base linears", "--workload bert --bwd --order chunk16 --steps 3 --warmup 1"),
+    ("wide", "lba_gemm_in, M4E3 flex-bias operands, ResNet-50 sweep, floor", "--in-fmt 3,4"),
+    ("wide", "same, chunks of 16", "--in-fmt 3,4 --order chunk16"),
+    ("wide", "same, BERT-base linears", "--in-fmt 3,4 --workload bert --steps 10"),
+    ("wide", "same, ResNet-50 sweep, nearest-even (Q_prod rounds the 10-bit products to nearest)", "--in-fmt 3,4 --round rne --steps 5 --warmup 1"),
+    ("wide", "lba_gemm_bwd_in, M4E3 operands, OF plane only, ResNet-50 sweep", "--in-fmt 3,4 --bwd --of-only --steps 5"),
+    ("wide", "same, both planes, BERT-base linears", "--in-fmt 3,4 --workload bert --bwd --steps 3 --warmup 1"),
+    ("wide", "lba_conv2d from NHWC activations, ResNet-50 sweep", "--implicit"),
+    ("wide", "same, ResNet-18 conv", "--implicit --workload conv --steps 20"),
+    ("grad", "lba_grad, identity estimator, ResNet-50 sweep (dX and dW)", "--grad identity --steps 3 --warmup 1"),
+    ("grad", "lba_grad, recursive estimator", "--grad recursive --steps 3 --warmup 1"),
+    ("grad", "lba_grad_ws, immediate estimator (pass over the plane + matrix cores + vector kernel)", "--grad immediate --steps 3 --warmup 1"),
+    ("grad", "lba_grad, identity estimator, 4096^3", "--workload gemm4096 --grad identity --steps 3 --warmup 1"),
+    ("grad", "lba_grad, recursive estimator, 4096^3", "--workload gemm4096 --grad recursive --steps 3 --warmup 1"),
+    ("grad", "lba_grad_ws, immediate estimator, 4096^3", "--workload gemm4096 --grad immediate --steps 3 --warmup 1"),
+] + [("sweep", "%s E%d M%d" % (r, e, m), "--workload gemm4096 --acc %d,%d --round %s --steps 5 --warmup 1" % (e, m, r))
+     for r in ("floor", "rne") for e in (4, 5, 6) for m in range(3, 11)]
+
+
+def run_suite(path):
+    """Every configuration of SUITE in this process; writes the summary table and the JSON lines."""
+    import gc
+    import torch
+    ap = make_parser()
+    rows = []
+    with open(os.path.splitext(path)[0] + ".jsonl", "w") as jl:
+        for section, label, flags in SUITE:
+            a = ap.parse_args(flags.split() + ["--no-cpu-baseline"])
+            out = run(a)
+            out["suite"] = {"section": section, "label": label, "flags": flags}
+            jl.write(json.dumps(out) + "\n")
+            jl.flush()
+            rows.append((section, label, flags, out))
+            sys.stderr.write("%-80s %8.3f TMAC/s\n" % (label[:80], out["value"] / 1e12))
+            gc.collect()
+            torch.cuda.empty_cache()
+
+    def line(label, flags, d):
+        r = d["roofline"]
+        return "| %s | `%s` | %.3f | %.4f | %s | %s | %.3f |" % (
+            label, flags or "(none)", d["value"] / 1e12, d["ms_per_step"], r["kernel"].split(" (")[0],
+            ("%.1f" % r["valu_slots_per_mac"]) if r.get("valu_slots_per_mac") else "mfma", r["frac"])
+
+    w = []
+    w.append("# All five configurations on one MI355X: throughput of the library calls\n")
+    w.append("Written by `python bench.py --suite profiles/all_configs_summary.md` (one process, one box; every row is one")
+    w.append("configuration of `bench.py` with the flags shown, inputs resident in HBM, HIP events per launch, wall time over the")
+    w.append("steps for the rate; the JSON lines are in `all_configs_summary.jsonl`).  `frac` is the dominant kernel's VALU issue")
+    w.append("slots per second over the 78.64e12 peak, with the slot count per MAC the planner states for the loop without the")
+    w.append("accumulator clamp and without the overflow test (k-tiles in which a sum can reach R_OF add 2 slots per MAC, or 6")
+    w.append("with event planes, which the count leaves out: their `frac` under-reports); `mfma`: issued bfloat16 flops over the")
+    w.append("2.5e15 peak of the matrix cores.  Parity of all of these configurations is what the GPU tests check.\n")
+    for section, title in (("main", "The five configurations"), ("wide", "Widened rows"), ("grad", "Gradient products (2 masked MACs per forward MAC)")):
+        w.append("## %s\n" % title)
+        w.append("| configuration | bench.py flags | 1e12 MAC/s | ms/step | dominant kernel | slots/MAC | frac |")
+        w.append("|---|---|---|---|---|---|---|")
+        for sec, label, flags, d in rows:
+            if sec == section:
+                w.append(line(label, flags, d))
+        w.append("")
+    w.append("## Configuration 5: accumulator-width sweep on 4096^3 (68.7e9 MACs per call)\n")
+    w.append("`python bench.py --workload gemm4096 --acc E,M [--round rne] --steps 5 --warmup 1`, b = 2^(E-1)-1, Q_prod = M7E5 b=15,")
+    w.append("biases folded by the operand scales.  Entries: 1e12 LBA-MAC/s (ms per call); `o`: the round-to-odd variant of the")
+    w.append("scaled kernel, `g`: the general kernel.\n")
+    cells = {l: d for sec, l, f, d in rows if sec == "sweep"}
+    for r, title in (("floor", "Floor (the paper's LBA rounding)"), ("rne", "Nearest-even")):
+        w.append("%s:\n" % title)
+        w.append("| E \\ M | 3 | 4 | 5 | 6 | 7 | 8 | 9 | 10 |")
+        w.append("|---|---|---|---|---|---|---|---|---|")
+        for e in (4, 5, 6):
+            cs = []
+            for m in range(3, 11):
+                d = cells["%s E%d M%d" % (r, e, m)]
+                k = d["roofline"]["kernel"]
+                tag = "g" if "gen_kernel" in k else ("o" if k.startswith("lba_fast_kernel") and k.rstrip(">").split(", ")[4] == "3" else "")
+                cs.append("%.2f%s (%.2f)" % (d["value"] / 1e12, tag, d["ms_per_step"]))
+            w.append("| %d | %s |" % (e, " | ".join(cs)))
+        w.append("")
+    with open(path, "w") as f:
+        f.write("\n".join(w))
+
+
+def main():
+    args = make_parser().parse_args()
+    if args.suite:
+        run_suite(args.suite)
+        return
+    print(json.dumps(run(args)))
 
 
 if __name__ == "__main__":

@@ -113,14 +113,17 @@ def main():
     ap.add_argument("--probe", help="text printed by valu_rate_probe")
     ap.add_argument("--probe-mix", default=None, help="the probe's instruction mix that matches the kernels' inner loop")
     ap.add_argument("--bench-flags", default="", help="the flags bench.py was run with (recorded)")
+    ap.add_argument("--commit", default=None, help="commit the runs were made from (default: git rev-parse of this checkout)")
     ap.add_argument("-o", "--out", default=OUT)
     args = ap.parse_args()
 
     dump = json.load(open(args.kernels))
-    try:
-        commit = subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], capture_output=True, text=True).stdout.strip()
-    except OSError:
-        commit = ""
+    commit = args.commit or ""
+    if not commit:
+        try:
+            commit = subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], capture_output=True, text=True).stdout.strip()
+        except OSError:
+            commit = ""
     rec = {"workload_key": dump["workload_key"], "bench_flags": args.bench_flags, "commit": commit or None, "kernels": {}}
     stats = kernel_stats(args.kt) if args.kt else {}
     sq, sq_n, _ = counters(args.sq) if args.sq else ({}, {}, [])
