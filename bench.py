@@ -10,7 +10,8 @@ before the timed region.  Prints ONE JSON line.
 
 Other workloads (for profiling, not the headline): --workload conv (ResNet-18 3x3 conv 64->64 at
 batch 32), bert (BERT-base linears at 4096 tokens), gemm4096 (4096^3; --acc E,M sweeps the accumulator
-format), config1 (one 64x64x256 GEMM: launch latency).
+format), config1 (one 64x64x256 GEMM: launch latency), layer:MxNxK (one GEMM of that shape with the ResNet-50
+data recipe: per-shape profiles).
 """
 import argparse
 import json
@@ -422,7 +423,8 @@ def run(args):
         "config": {"workload": {"resnet50": "ResNet-50 forward, batch 64, 224x224: 53 convs (im2col) + FC as 54 LBA GEMMs",
                                 "conv": "ResNet-18 3x3 conv 64->64, batch 32, 56x56 (M=100352,N=64,K=576)",
                                 "bert": "BERT-base linears, 4096 tokens", "gemm4096": "4096^3 GEMM",
-                                "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}[args.workload],
+                                "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}.get(
+                                    args.workload, "single GEMM %s, ReLU activations, He weights" % args.workload),
                    "macs_per_step": total_macs, "qprod": "M%dE%d b=%d" % (prod_fmt[1], prod_fmt[0], prod_fmt[2]), "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
                    "call": ("%s, %s estimator: dX and dW (2 masked MACs per forward MAC)" % ("lba_grad_ws" if args.grad == "immediate" else "lba_grad", args.grad)) if args.grad else ("lba_gemm_bwd_diff (C + DIFF plane, eps2 = %g)" % args.diff) if args.diff is not None else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else ("lba_gemm_bwd (C + OF plane)" if args.of_only else "lba_gemm_bwd (C + OF and UF planes)")) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
                    "conv": "implicit im2col from NHWC activations (lba_conv2d)" if args.implicit else "operand A is the written-out im2col matrix",
@@ -486,6 +488,8 @@ SUITE = [
     ("grad", "lba_grad, identity estimator, 4096^3", "--workload gemm4096 --grad identity --steps 3 --warmup 1"),
     ("grad", "lba_grad, recursive estimator, 4096^3", "--workload gemm4096 --grad recursive --steps 3 --warmup 1"),
     ("grad", "lba_grad_ws, immediate estimator, 4096^3", "--workload gemm4096 --grad immediate --steps 3 --warmup 1"),
+] + [("grad", "%s, %s estimator, %s" % ("lba_grad_ws" if e == "immediate" else "lba_grad", e, n), "--workload %s --grad %s --steps 5 --warmup 2" % (w, e))
+     for w, n in (("bert", "BERT-base linears"), ("conv", "ResNet-18 conv")) for e in ("identity", "recursive", "immediate")
 ] + [("sweep", "%s E%d M%d" % (r, e, m), "--workload gemm4096 --acc %d,%d --round %s --steps 5 --warmup 1" % (e, m, r))
      for r in ("floor", "rne") for e in (4, 5, 6) for m in range(3, 11)]
 

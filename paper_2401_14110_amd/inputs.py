@@ -270,7 +270,8 @@ def make_workload(name, device="cpu", in_fmt=None):
     operand shape share data.  Workloads: 'resnet50' (ResNet-50 forward, batch 64, 224x224: 54 GEMMs),
     'conv' (ResNet-18 3x3 conv 64->64 at batch 32), 'bert' (BERT-base linears, 4096 tokens),
     'gemm4096' (4096^3, N(0,1) operands), 'config1' (M=N=64, K=256, N(0,1) operands scaled to
-    max|x| = 448, seed 0).  With in_fmt = (E, M) the codes are of that 8-bit format and ta / tb are the
+    max|x| = 448, seed 0), 'layer:MxNxK' (one GEMM of that shape with the ResNet-50 recipe: ReLU activations,
+    He weights; for per-shape profiles).  With in_fmt = (E, M) the codes are of that 8-bit format and ta / tb are the
     per-tensor flex biases (for lba_gemm_in, with the quantizers' biases in real units)."""
     if name == "resnet50":
         layers = resnet50_gemms(batch=64, image=224)
@@ -287,6 +288,10 @@ def make_workload(name, device="cpu", in_fmt=None):
     elif name == "config1":
         layers = [("gemm64", 64, 64, 256)]
         seed = 0
+    elif name.startswith("layer:"):
+        M, N, K = (int(v) for v in name[6:].split("x"))
+        layers = [(name, M, N, K)]
+        seed = 3
     else:
         raise ValueError("unknown workload %r" % name)
     # one operand tensor per distinct (rows, K) and role: layers of equal shape share data
@@ -296,14 +301,14 @@ def make_workload(name, device="cpu", in_fmt=None):
         if (M, K) not in cache_a:
             if name == "resnet50":
                 kind = "normal" if lname == "conv1" else "relu"
-            elif name == "conv":
+            elif name == "conv" or name.startswith("layer:"):
                 kind = "relu"
             else:
                 kind = "normal"
             cache_a[(M, K)] = make_operand(kind, M, K, seed, 2 * len(cache_a), device=device,
                                            scale_mode=mode, in_fmt=in_fmt)
         if (N, K) not in cache_b:
-            if name in ("resnet50", "conv"):
+            if name in ("resnet50", "conv") or name.startswith("layer:"):
                 std = (2.0 / K) ** 0.5
             elif name == "bert":
                 std = 0.02
