@@ -309,9 +309,12 @@ typedef struct {
                                          instruction counts as 2 slots); kernel 1: the budget of a plain
                                          FMAq step (10 floor, 12 nearest-even, 4 more with event bits), which
                                          is less than its loop issues */
-    int32_t tail_blocks;              /* > 0: mixed grid: grid_x counts grid_x - tail_blocks workgroups of
-                                         tile_m x tile_n plus tail_blocks workgroups of 32 x 32 (2 x 2 outputs
-                                         per lane) on the last rows; grid_y is 1                            */
+    int32_t tail_blocks;              /* tail_blocks + mid_blocks > 0: mixed grid: grid_x counts, in this order,
+                                         grid_x - mid_blocks - tail_blocks workgroups of tile_m x tile_n,
+                                         mid_blocks workgroups of 48 x 64 (3 x 4 outputs per lane) on the rows
+                                         after them and tail_blocks workgroups of 32 x 32 (2 x 2 per lane) on
+                                         the last rows; grid_y is 1                                          */
+    int32_t mid_blocks;
 } lba_plan_info;
 
 /* with_masks: 0 the forward call, 1 the recompute call with event planes, 2 lba_gemm_bwd_diff,

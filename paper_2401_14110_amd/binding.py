@@ -37,7 +37,7 @@ class lba_conv2d_desc(ctypes.Structure):
 class lba_plan_info(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "kernel", "prod_mode", "round", "tile_m", "tile_n", "tile_k", "thread_m", "thread_n",
-        "grid_x", "grid_y", "valu_per_mac_x100", "tail_blocks")]
+        "grid_x", "grid_y", "valu_per_mac_x100", "tail_blocks", "mid_blocks")]
 
 
 class LbaError(RuntimeError):

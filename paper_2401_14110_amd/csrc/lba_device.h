@@ -273,8 +273,11 @@ template <int ROWS, int BK>
 struct Stage {
     static constexpr int kChunks = ROWS * BK / 16;                         // 16-byte pieces per tile
     static constexpr int kPerLane = (kChunks + 255) / 256;
-    static constexpr int kRowShift = ROWS == 8 ? 3 : ROWS == 16 ? 4 : ROWS == 32 ? 5 : ROWS == 64 ? 6 : ROWS == 128 ? 7 : 8;
-    static_assert((1 << kRowShift) == ROWS, "tile rows must be a power of two");
+    static_assert(ROWS == 48 || (ROWS & (ROWS - 1)) == 0, "tile rows: a power of two, or 48");
+    // k-major LDS tile: floats per k.  A 48-row tile (3 rows per lane) keeps the 64-row pitch, each lane's three
+    // rows in the first three of its four slots, so that a lane still reads its operands with one 16-byte read.
+    static constexpr int kPitch = ROWS == 48 ? 64 : ROWS;
+    static __device__ __forceinline__ int slot(int row) { return ROWS == 48 ? row + row / 3 : row; }
     // lanes that take B's pieces: the highest-numbered ones, so that A and B share the work
     static constexpr int kTailShift = kChunks < 256 ? 256 - kChunks : 0;
 };
@@ -292,8 +295,8 @@ __device__ __forceinline__ void fetch_tile(const uint8_t* __restrict__ G, int ro
         const int c = tid + i * 256;
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
-            const int row = c & (ROWS - 1);
-            const int kq = c >> Stage<ROWS, BK>::kRowShift;                 // ROWS is a power of two
+            const int row = c % ROWS;                                       // division by a constant
+            const int kq = c / ROWS;
             const int r = r0 + row, k = k0 + kq * 16;
             if (r < rows && k < K) {
                 const uint8_t* src = G + (int64_t)r * K + k;
@@ -342,8 +345,8 @@ __device__ __forceinline__ void fetch_tile_conv(const uint8_t* __restrict__ X, c
         const int c = tid + i * 256;
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
         if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
-            const int row = c & (ROWS - 1);
-            const int kq = c >> Stage<ROWS, BK>::kRowShift;
+            const int row = c % ROWS;
+            const int kq = c / ROWS;
             const int r = r0 + row, k = k0 + kq * 16;
             if (r < p.M && k < p.K) {
                 const int ow = r % p.cv_ow, t = r / p.cv_ow;            // the lane's row never changes: hoisted
@@ -392,13 +395,13 @@ __device__ __forceinline__ void store_tile(float* __restrict__ dst /* [BK][ROWS]
     for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
         const int c = tid + i * 256;
         if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
-            const int row = c & (ROWS - 1);
-            const int kq = c >> Stage<ROWS, BK>::kRowShift;
+            const int row = Stage<ROWS, BK>::slot(c % ROWS);
+            const int kq = c / ROWS;
             const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 const uint32_t code = (w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
-                dst[(kq * 16 + j) * ROWS + row] = lut[code];
+                dst[(kq * 16 + j) * Stage<ROWS, BK>::kPitch + row] = lut[code];
             }
         }
     }
@@ -424,8 +427,8 @@ __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][R
         for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
             const int c = tid + i * 256;
             if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
-                const int row = c & (ROWS - 1);
-                const int kq = c >> Stage<ROWS, BK>::kRowShift;
+                const int row = Stage<ROWS, BK>::slot(c % ROWS);
+                const int kq = c / ROWS;
                 const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
                 const float sc16 = __builtin_ldexpf(1.0f, 15 - ((1 << (E - 1)) - 1) + scale_exp);
                 const int up = 10 - M;
@@ -434,13 +437,13 @@ __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][R
                     for (int j = 0; j < 16; ++j) {
                         const uint32_t code = (w[j >> 2] >> (8 * (j & 3))) & 0xFFu;
                         const uint16_t h = (uint16_t)(((code & 0x80u) << 8) | ((code & 0x7Fu) << up));
-                        dst[(kq * 16 + j) * ROWS + row + kq * PAD] = (float)__builtin_bit_cast(_Float16, h) * sc16;
+                        dst[(kq * 16 + j) * Stage<ROWS, BK>::kPitch + row + kq * PAD] = (float)__builtin_bit_cast(_Float16, h) * sc16;
                     }
                 } else {
 #pragma unroll
                     for (int j = 0; j < 16; ++j) {
                         const int code = (int)((w[j >> 2] >> (8 * (j & 3))) & 0xFFu);
-                        dst[(kq * 16 + j) * ROWS + row + kq * PAD] = decode_entry(code, scale_exp, E, M);
+                        dst[(kq * 16 + j) * Stage<ROWS, BK>::kPitch + row + kq * PAD] = decode_entry(code, scale_exp, E, M);
                     }
                 }
             }
@@ -451,8 +454,8 @@ __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][R
     for (int i = 0; i < Stage<ROWS, BK>::kPerLane; ++i) {
         const int c = tid + i * 256;
         if (c >= 0 && c < Stage<ROWS, BK>::kChunks) {
-            const int row = c & (ROWS - 1);
-            const int kq = c >> Stage<ROWS, BK>::kRowShift;
+            const int row = Stage<ROWS, BK>::slot(c % ROWS);
+            const int kq = c / ROWS;
             const uint32_t w[4] = {regs[i].x, regs[i].y, regs[i].z, regs[i].w};
             float f[16];
             uint32_t nan_any = 0u;
@@ -472,7 +475,7 @@ __device__ __forceinline__ void store_tile_cvt(float* __restrict__ dst /* [BK][R
                 }
             }
 #pragma unroll
-            for (int j = 0; j < 16; ++j) dst[(kq * 16 + j) * ROWS + row + kq * PAD] = f[j];
+            for (int j = 0; j < 16; ++j) dst[(kq * 16 + j) * Stage<ROWS, BK>::kPitch + row + kq * PAD] = f[j];
             if (lane_max) {
                 float m = *lane_max;
 #pragma unroll
@@ -501,15 +504,19 @@ __device__ __forceinline__ float tile_threshold(const float* slot, float rof_gro
     return rof_grow1 - 32.0f * 1.001f * (amax * bmax) * kc;
 }
 
-// Reads the TM + TN operand values of one k from an LDS stage (TM, TN in {2, 4}): the lane's
-// rows ty*TM .. and columns tx*TN .. are contiguous in the k-major tiles.
+// Reads the TM + TN operand values of one k from an LDS stage (TM in {2, 3, 4}, TN in {2, 4}): the lane's
+// rows ty*TM .. and columns tx*TN .. are contiguous in the k-major tiles (BM, BN: floats per k; three rows
+// per lane sit in slots of four, see Stage).
 template <int TM, int TN, int BM, int BN>
 __device__ __forceinline__ void read_operands(const float* As, const float* Bs, int k, int tx, int ty,
                                               float (&a)[TM], float (&b)[TN]) {
-    static_assert((TM == 2 || TM == 4) && (TN == 2 || TN == 4), "lane block");
+    static_assert((TM == 2 || TM == 3 || TM == 4) && (TN == 2 || TN == 4), "lane block");
     if (TM == 4) {
         const float4 v = *reinterpret_cast<const float4*>(As + k * BM + ty * 4);
         a[0] = v.x; a[1] = v.y; a[TM - 2] = v.z; a[TM - 1] = v.w;
+    } else if (TM == 3) {
+        const float4 v = *reinterpret_cast<const float4*>(As + k * BM + ty * 4);
+        a[0] = v.x; a[1] = v.y; a[TM - 1] = v.z;
     } else {
         const float2 v = *reinterpret_cast<const float2*>(As + k * BM + ty * 2);
         a[0] = v.x; a[1] = v.y;
@@ -624,7 +631,8 @@ template <int TM, int TN, int BK, int PM, int RND, int ORDER, int AMODE>
 __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ smem, int m0, int n0) {
     static_assert(BK % 16 == 0, "chunk boundaries must fall on fixed positions of a k-tile");
     constexpr int BM = 16 * TM, BN = 16 * TN;
-    constexpr int STAGE = BK * (BM + BN);
+    constexpr int BMP = Stage<BM, BK>::kPitch;                // floats per k of the A tile in LDS
+    constexpr int STAGE = BK * (BMP + BN);
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
@@ -662,11 +670,11 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
         if (dyn) {
             float lm = 0.0f;
             store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, 4, 3, 0, &lm);
-            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, 4, 3, 0, &lm);
+            store_tile_cvt<BN, BK>(Ad + BK * BMP, sc_b, tidb, rb, 4, 3, 0, &lm);
             publish_tile_max(tile_max[st], lm, tid);
         } else {
             store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
-            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
+            store_tile_cvt<BN, BK>(Ad + BK * BMP, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
         }
     };
     if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
@@ -677,7 +685,7 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
 
     for (int t = 0; t < ntiles; ++t) {
         const float* As = smem + (t & 1) * STAGE;
-        const float* Bs = As + BK * BM;
+        const float* Bs = As + BK * BMP;
         const bool more = (t + 1) < ntiles;
         if (more) {
             if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
@@ -704,9 +712,9 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
         }
         if (safe_tiles > 0) {
             --safe_tiles;
-            fast_tile<PM, RND, ORDER, false, TM, TN, BK, BM, BN>(acc, top, As, Bs, tx, ty, c);
+            fast_tile<PM, RND, ORDER, false, TM, TN, BK, BMP, BN>(acc, top, As, Bs, tx, ty, c);
         } else {
-            fast_tile<PM, RND, ORDER, true, TM, TN, BK, BM, BN>(acc, top, As, Bs, tx, ty, c);
+            fast_tile<PM, RND, ORDER, true, TM, TN, BK, BMP, BN>(acc, top, As, Bs, tx, ty, c);
         }
         if (more) stage_tiles(smem + ((t + 1) & 1) * STAGE, (t + 1) & 1);
         __syncthreads();
@@ -788,10 +796,11 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
     fast_body<TM, TN, BK, PM, RND, ORDER, AMODE>(p, smem, blockIdx.x * 16 * TM, blockIdx.y * 16 * TN);
 }
 
-// Mixed grid for launches that would leave the last round of 64 x 64 workgroups half empty: the first
-// mix_main workgroups (rows below mix_m_main) take 64 x 64 tiles with 4 x 4 outputs per lane, the rest
-// covers the remaining rows with 32 x 32 tiles (2 x 2 per lane), a quarter of the work each, so that the
-// tail of the launch is cut four times finer.  Workgroups are numbered rows-first in both regions.
+// Mixed grid for launches that would leave the last round of 64 x 64 workgroups half empty, or a CU with an odd
+// number of workgroups: the first mix_main workgroups (rows below mix_m_main) take 64 x 64 tiles with 4 x 4 outputs
+// per lane, the next mix_half (rows below mix_m_half) 48 x 64 tiles with 3 x 4 per lane, three quarters of the work
+// each, and the rest covers the remaining rows with 32 x 32 tiles (2 x 2 per lane), a quarter of the work each, so
+// that the tail of the launch is cut four times finer.  Workgroups are numbered rows-first in every region.
 template <int BK, int PM, int RND, int ORDER>
 __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_mixed_kernel(const KParams p) {
     __shared__ __attribute__((aligned(16))) float smem[2 * BK * 16 * 8];
@@ -799,10 +808,14 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_mixed_kernel
     if (b < p.mix_main) {                                      // uniform
         const int by = b / p.mix_gx_main, bx = b - by * p.mix_gx_main;
         fast_body<4, 4, BK, PM, RND, ORDER, 0>(p, smem, bx * 64, by * 64);
-    } else {
+    } else if (b < p.mix_main + p.mix_half) {
         const int t = b - p.mix_main;
+        const int by = t / p.mix_gx_half, bx = t - by * p.mix_gx_half;
+        fast_body<3, 4, BK, PM, RND, ORDER, 0>(p, smem, p.mix_m_main + bx * 48, by * 64);
+    } else {
+        const int t = b - p.mix_main - p.mix_half;
         const int by = t / p.mix_gx_tail, bx = t - by * p.mix_gx_tail;
-        fast_body<2, 2, BK, PM, RND, ORDER, 0>(p, smem, p.mix_m_main + bx * 32, by * 32);
+        fast_body<2, 2, BK, PM, RND, ORDER, 0>(p, smem, p.mix_m_half + bx * 32, by * 32);
     }
 }
 

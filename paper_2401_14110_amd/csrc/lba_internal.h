@@ -50,8 +50,10 @@ struct KParams {
     int32_t cv_h, cv_w, cv_c, cv_kw, cv_stride, cv_pad, cv_oh, cv_ow;
     uint64_t cv_magic_c, cv_magic_kw;   // ceil(2^40 / d): x / d == (x * magic) >> 40 for x < 2^24, d < 2^14
     // mixed grid (lba_fast_mixed_kernel): workgroups below mix_main take 64 x 64 tiles of the rows below
-    // mix_m_main (mix_gx_main of them per tile column), the rest 32 x 32 tiles of the remaining rows
+    // mix_m_main (mix_gx_main of them per tile column), the next mix_half take 48 x 64 tiles (3 x 4 outputs per lane) of the rows below
+    // mix_m_half (mix_gx_half per tile column; the forward kernel only), the rest 32 x 32 tiles of the remaining rows
     int32_t mix_main, mix_gx_main, mix_gx_tail, mix_m_main;
+    int32_t mix_half, mix_gx_half, mix_m_half;
     int32_t prod_round;      // GEN: product mantissa narrower than a product of two operands
     int32_t prod_rne;        // GEN: its rounding
     float diff_eps;          // DIFF plane (written through of_mask): the threshold eps2, exact

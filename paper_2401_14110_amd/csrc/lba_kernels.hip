@@ -301,7 +301,8 @@ static int plan_query(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt 
     out->thread_m = pl.tm; out->thread_n = pl.tn;
     out->grid_x = pl.grid_x; out->grid_y = pl.grid_y;
     out->valu_per_mac_x100 = pl.valu_per_mac_x100;
-    out->tail_blocks = pl.mix_tail;
+    out->tail_blocks = pl.mix_tail > 0 ? pl.mix_tail - pl.kp.mix_half : 0;
+    out->mid_blocks = pl.mix_tail > 0 ? pl.kp.mix_half : 0;
     return LBA_OK;
 }
 

@@ -38,6 +38,8 @@
 
 #include <cmath>
 #include <cstring>
+#include <cstdlib>
+#include <cstdio>
 
 #include <algorithm>
 
@@ -180,6 +182,29 @@ static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int event
 // run side by side, but they share the CU's issue slots); when the last round is mostly empty, the rows
 // of that round are cut into 32 x 32 tiles instead (a quarter of the work each, at about 0.8 of the
 // efficiency), which the launch then finishes in quarter rounds.  Used when the model says 3 % or more.
+// Fills in a mixed grid: gx_main tile rows of 64 x 64 workgroups, then gx_half tile rows of 48 x 64 ones, then
+// 32 x 32 workgroups on whatever rows are left.  False when the counts do not fit a launch.
+static bool set_mixed_grid(int64_t M, int64_t N, int64_t gx_main, int64_t gx_half, Plan* p) {
+    const int64_t gy = (N + 63) / 64, gy_tail = (N + 31) / 32;
+    const int64_t m_main = gx_main * 64, m_half = m_main + gx_half * 48;
+    if (gx_main < 0 || gx_half < 0 || m_half > M) return false;
+    const int64_t gx_tail = m_half < M ? (M - m_half + 31) / 32 : 0, tail = gx_tail * gy_tail;
+    const int64_t total = (gx_main + gx_half) * gy + tail;
+    if (total > 2147483647LL || gx_half * gy + tail < 1) return false;
+    p->mix_tail = (int)(gx_half * gy + tail);
+    p->tm = 4; p->tn = 4;
+    p->kp.mix_main = (int32_t)(gx_main * gy);
+    p->kp.mix_gx_main = (int32_t)(gx_main > 0 ? gx_main : 1);
+    p->kp.mix_m_main = (int32_t)m_main;
+    p->kp.mix_half = (int32_t)(gx_half * gy);
+    p->kp.mix_gx_half = (int32_t)(gx_half > 0 ? gx_half : 1);
+    p->kp.mix_m_half = (int32_t)m_half;
+    p->kp.mix_gx_tail = (int32_t)(gx_tail > 0 ? gx_tail : 1);
+    p->grid_x = (int)total;
+    p->grid_y = 1;
+    return true;
+}
+
 static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
     p->mix_tail = 0;
     if (p->kernel != KERNEL_FAST || p->amode || p->rne_odd || batch != 1) return;
@@ -187,7 +212,37 @@ static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
     if (p->events == 1 && p->order != LBA_ORDER_SEQ) return;
     if (p->prod_mode != PM_IDENT && p->prod_mode != PM_FLUSH && p->prod_mode != PM_FLUSH_CLAMP) return;
     const int64_t gx = (M + 63) / 64, gy = (N + 63) / 64, blocks = gx * gy;
-    if (blocks <= 384 || blocks > 256 * 16) return;
+#ifdef LBA_EXPERIMENT
+    if (const char* e = getenv("LBA_MIX")) {
+        long a = 0, b = 0;
+        if (sscanf(e, "%ld,%ld", &a, &b) == 2 && p->events == 0) { if (a >= 0) set_mixed_grid(M, N, a, b, p); return; }
+    }
+#endif
+    if (blocks > 256 * 16) return;
+    // Rounds of 48 x 64 workgroups (forward call only; measured on M sweeps at N = 256 and 512, whose rates depend on
+    // blocks / 256 alone): a CU that holds three 64 x 64 workgroups, or one, issues well below one that holds four or
+    // two, and a launch just above a whole number of rounds pays a nearly empty round.  Whole rounds of the
+    // three-quarter tile put 2 or 4 equal workgroups on every CU where the 64 x 64 tile gives 1.5 or 3, and one such
+    // round after the full rounds of 64 x 64 replaces a last round that would be 60-77 % full.
+    const int64_t gy32 = (N + 31) / 32;
+    if (p->events == 0 && blocks > 256 && gy <= 256) {
+        const int64_t b = (M / 48) * gy / 256;                 // whole rounds of 48 x 64 workgroups
+        if (b >= 1 && b <= 4) {
+            const int64_t gx_half = b * 256 / gy;
+            const int64_t rows_left = M - gx_half * 48;
+            const int64_t nq = (rows_left + 31) / 32 * gy32;   // 32 x 32 workgroups after them
+            const bool take = (b == 1 && blocks >= 282) || (b == 2 && nq <= 256) || (b == 3 && nq <= 256 && blocks >= 600) ||
+                              (b == 4 && nq <= 256 && blocks >= 780);
+            if (take && rows_left >= 0 && set_mixed_grid(M, N, 0, gx_half, p)) return;
+        }
+        const int64_t a = blocks / 256;                        // full rounds of 64 x 64, then one round of 48 x 64
+        if (a >= 3 && a <= 8) {
+            const int64_t gx_main = a * 256 / gy;
+            const int64_t mids = (M - gx_main * 64) / 48;
+            if (gx_main >= 1 && mids * gy >= 205 && mids * gy <= 256 && set_mixed_grid(M, N, gx_main, mids, p)) return;
+        }
+    }
+    if (blocks <= 384) return;
     const int64_t rounds = blocks / 256;
     const int64_t gx_main = (rounds * 256) / gy;               // whole tile rows inside the full rounds
     if (gx_main < 1 || gx_main >= gx) return;
@@ -198,14 +253,7 @@ static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
     if (p->tm == 2 && p->tn == 4) plain = 0.5 * (double)((2 * blocks + 255) / 256) / 0.95;   // the 32 x 64 choice
     const double mixed = (double)(gx_main * gy) / 256.0 + (double)((tail + 255) / 256) * 0.25 / 0.8;
     if (mixed > 0.97 * plain) return;
-    p->mix_tail = (int)tail;
-    p->tm = 4; p->tn = 4;
-    p->kp.mix_main = (int32_t)(gx_main * gy);
-    p->kp.mix_gx_main = (int32_t)gx_main;
-    p->kp.mix_gx_tail = (int32_t)gx_tail;
-    p->kp.mix_m_main = (int32_t)m_main;
-    p->grid_x = (int)(gx_main * gy + tail);
-    p->grid_y = 1;
+    set_mixed_grid(M, N, gx_main, 0, p);
 }
 
 int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_qfmt& qa_in,

@@ -197,10 +197,18 @@ static void sweep_planner() {
                                         if (pl.mix_tail > 0) {
                                             ++mixed;
                                             const lba::KParams& kp = pl.kp;
-                                            CHECK(kp.mix_m_main == kp.mix_gx_main * 64 && kp.mix_m_main < M, "mixed rows");
-                                            CHECK(kp.mix_main == kp.mix_gx_main * ((N + 63) / 64), "mixed main count");
-                                            CHECK((int64_t)kp.mix_gx_tail * 32 >= M - kp.mix_m_main, "tail rows cover M");
-                                            CHECK(pl.mix_tail == kp.mix_gx_tail * ((N + 31) / 32), "tail count");
+                                            const int64_t gy64 = (N + 63) / 64, gy32 = (N + 31) / 32;
+                                            CHECK(kp.mix_m_main % 64 == 0 && kp.mix_m_main <= M && kp.mix_main == kp.mix_m_main / 64 * gy64, "64-row region");
+                                            CHECK(kp.mix_main == 0 || kp.mix_m_main == (int64_t)kp.mix_gx_main * 64, "64-row region width");
+                                            CHECK(kp.mix_m_half >= kp.mix_m_main && kp.mix_m_half <= M && (kp.mix_m_half - kp.mix_m_main) % 48 == 0, "48-row region");
+                                            CHECK(kp.mix_half == (kp.mix_m_half - kp.mix_m_main) / 48 * gy64, "48-row count");
+                                            CHECK(kp.mix_half == 0 || kp.mix_m_half - kp.mix_m_main == (int64_t)kp.mix_gx_half * 48, "48-row region width");
+                                            CHECK(kp.mix_half == 0 || events == 0, "48-row tiles are the forward kernel's");
+                                            const int64_t quarters = pl.mix_tail - kp.mix_half;
+                                            CHECK(quarters >= 0 && (quarters == 0) == (kp.mix_m_half >= M), "32-row region present iff rows are left");
+                                            CHECK(quarters == 0 || ((int64_t)kp.mix_gx_tail * 32 >= M - kp.mix_m_half && (int64_t)(kp.mix_gx_tail - 1) * 32 < M - kp.mix_m_half), "tail rows cover M");
+                                            CHECK(quarters == 0 || quarters == kp.mix_gx_tail * gy32, "tail count");
+                                            CHECK(kp.mix_gx_main >= 1 && kp.mix_gx_half >= 1 && kp.mix_gx_tail >= 1, "divisors");
                                             CHECK(pl.grid_x == kp.mix_main + pl.mix_tail && pl.grid_y == 1, "mixed grid");
                                         } else if (pl.kpar > 0) {
                                             const int64_t tm = pl.kpar == 1 ? 32 : 8, tn = pl.kpar == 1 ? 32 : 16;

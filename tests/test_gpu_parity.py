@@ -682,16 +682,28 @@ def test_mixed_grid(ref):
             qpf, qaf = qp + (rnd,), qa + (rnd,)
             plan = lb.lba_plan_query(M, N, K, qpf, qaf, order)
             two_sums = rnd == 1 and plan["valu_per_mac_x100"] >= 1000      # the round-to-odd variant has no mixed grid
-            assert plan["kernel"] == 1 or two_sums or (plan["tail_blocks"] > 0 and plan["grid_y"] == 1), plan
-            mixed += plan["tail_blocks"] > 0
+            assert plan["kernel"] == 1 or two_sums or (plan["tail_blocks"] + plan["mid_blocks"] > 0 and plan["grid_y"] == 1), plan
+            mixed += plan["tail_blocks"] + plan["mid_blocks"] > 0
             check(ref, A, B, qpf, qaf, "mixed grid", order=order)
     assert mixed >= 36
+    # whole rounds of 48 x 64 workgroups (3 x 4 outputs per lane; the forward call): one, two and four rounds of them
+    # in front of the 32 x 32 tail, and one round of them behind three rounds of 64 x 64
+    for (M, N, K), main in [((64 * 300 + 5, 64, 40), False), ((64 * 392, 64, 40), False), ((12544, 256, 40), False), ((64 * 947 + 17, 64, 40), True)]:
+        A = rand_codes(rng, (M, K), 3, 12); B = rand_codes(rng, (N, K), 3, 12)
+        for (qp, qa), rnd, order in itertools.product([FMT_PAPER[0], FMT_SWEEP[4]], (0, 1), (0, 1)):
+            qpf, qaf = qp + (rnd,), qa + (rnd,)
+            plan = lb.lba_plan_query(M, N, K, qpf, qaf, order)
+            if plan["kernel"] == 0 and plan["valu_per_mac_x100"] < 1000:
+                assert plan["mid_blocks"] > 0 and (205 <= plan["mid_blocks"] <= 256 if main else plan["mid_blocks"] % 256 == 0), plan
+                assert (plan["grid_x"] - plan["mid_blocks"] - plan["tail_blocks"] > 0) == main, plan
+            check(ref, A, B, qpf, qaf, "48-row rounds", order=order)
+        assert lb.lba_plan_query(M, N, K, FMT_PAPER[0][0] + (0,), FMT_PAPER[0][1] + (0,), 0, 1)["mid_blocks"] == 0   # recompute: none
     # not used where it cannot help: exact multiples of a round, tiny and huge grids (for the recompute call too)
     assert lb.lba_plan_query(64 * 256, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
     assert lb.lba_plan_query(64 * 40, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
     # up to 384 workgroups of 64 x 64 a CU would run a single wave per SIMD (half rate): finer plain tiles instead
-    small = lb.lba_plan_query(64 * 300, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))
-    assert small["tail_blocks"] == 0 and (small["thread_m"], small["thread_n"]) == (2, 4)
+    small = lb.lba_plan_query(64 * 270, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))
+    assert small["tail_blocks"] + small["mid_blocks"] == 0 and (small["thread_m"], small["thread_n"]) == (2, 4)
     assert lb.lba_plan_query(64 * 100, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["thread_n"] == 2
     assert lb.lba_plan_query(64 * 12544, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0))["tail_blocks"] == 0
     assert lb.lba_plan_query(64 * 300, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), 0, 1)["tail_blocks"] == 0
