@@ -106,9 +106,12 @@ def make_parser():
     ap.add_argument("--of-only", action="store_true", help="with --bwd: ask for the overflow plane only")
     ap.add_argument("--diff", type=float, default=None, metavar="EPS2",
                     help="with --bwd: time lba_gemm_bwd_diff (C + the DIFF plane for that threshold) instead")
-    ap.add_argument("--grad", default=None, choices=["identity", "immediate", "recursive"],
+    ap.add_argument("--grad", default=None, choices=["identity", "immediate", "recursive", "premapped"],
                     help="time lba_grad (dX and dW with that estimator's coefficients; the OF planes / last-overflow "
-                         "indices are computed before the timed region) instead of lba_gemm; 2 MACs per forward MAC")
+                         "indices are computed before the timed region) instead of lba_gemm; 2 MACs per forward MAC; "
+                         "premapped: the immediate estimator through lba_grad_premapped, with the brick maps left by "
+                         "lba_gemm_bwd_ws before the timed region")
+    ap.add_argument("--maps", action="store_true", help="with --bwd: time lba_gemm_bwd_ws (also leaves the brick maps) instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=0, help="threads of the oracle leg (default: min(16, cores))")
     ap.add_argument("--per-layer", action="store_true", help="also print a per-layer table to stderr")
@@ -183,7 +186,8 @@ def run(args):
         l["C"] = Cbuf[: l["M"] * l["N"]].view(l["M"], l["N"])
         l["macs"] = l["M"] * l["N"] * l["K"]
     if args.grad:
-        ste = {"identity": 0, "immediate": 1, "recursive": 2}[args.grad]
+        ste = {"identity": 0, "immediate": 1, "recursive": 2, "premapped": 1}[args.grad]
+        premapped = args.grad == "premapped"
         stream = torch.cuda.current_stream().cuda_stream
         Gbuf = torch.randn(cmax, dtype=torch.float32, device=dev)
         dXbuf = torch.empty(max(l["M"] * l["K"] for l in layers), dtype=torch.float32, device=dev)
@@ -203,7 +207,9 @@ def run(args):
             if l["N"] % 4 == 0 and (ste == 0 or ste == 1 or l["K"] <= 12288):
                 l["plan"] = dict(l["plan"], kernel=3, valu_per_mac_x100=0)
             l["of"] = l["last"] = None
-            if ste:
+            if premapped:
+                _, l["of"], _, l["ws"] = lb.gemm_bwd_ws(l["A"], l["B"], l["qp"], l["qa"], want_c=False, want_uf=False)
+            elif ste:
                 _, l["of"], _ = lb.gemm_bwd(l["A"], l["B"], l["qp"], l["qa"], want_c=False)
             if ste == 2:
                 l["last"] = lb.last_overflow(l["of"], l["K"])
@@ -212,7 +218,10 @@ def run(args):
         torch.cuda.synchronize()
 
         def launch(l):
-            if ste == 1:
+            if premapped:
+                rc = lb.lba_grad_premapped(Gbuf.data_ptr(), l["A"].data_ptr(), l["B"].data_ptr(), l["of"].data_ptr(),
+                                           dXbuf.data_ptr(), dWbuf.data_ptr(), l["M"], l["N"], l["K"], l["ws"].data_ptr(), l["ws"].numel(), stream)
+            elif ste == 1:
                 rc = lb.lba_grad_ws(Gbuf.data_ptr(), l["A"].data_ptr(), l["B"].data_ptr(), l["of"].data_ptr(), None,
                                     dXbuf.data_ptr(), dWbuf.data_ptr(), l["M"], l["N"], l["K"], ste, wsbuf.data_ptr(), wsbuf.numel(), stream)
             else:
@@ -230,6 +239,8 @@ def run(args):
         of_buf = torch.empty(wmax, dtype=torch.int32, device=dev)
         uf_buf = torch.empty(wmax, dtype=torch.int32, device=dev)
         stream = torch.cuda.current_stream().cuda_stream
+        if args.maps:
+            ws_buf = torch.empty(max(256, max(lb.lba_grad_workspace_bytes(l["M"], l["N"], l["K"]) for l in layers)), dtype=torch.uint8, device=dev)
 
         if order == 1:
             w2max = max(lb.lba_mask_words_level2(l["M"], l["N"], l["K"]) for l in layers)
@@ -248,6 +259,10 @@ def run(args):
                 rc = lb.lba_gemm_bwd_chunked(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
                                              uf_buf.data_ptr(), of2_buf.data_ptr(), uf2_buf.data_ptr(),
                                              l["M"], l["N"], l["K"], l["qp"], l["qa"], stream)
+            elif args.maps:
+                rc = lb.lba_gemm_bwd_ws(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
+                                        None if args.of_only else uf_buf.data_ptr(), l["M"], l["N"], l["K"], l["qp"], l["qa"],
+                                        ws_buf.data_ptr(), ws_buf.numel(), stream)
             else:
                 rc = lb.lba_gemm_bwd(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
                                      None if args.of_only else uf_buf.data_ptr(), l["M"], l["N"], l["K"], l["qp"], l["qa"], order, stream)
@@ -325,6 +340,7 @@ def run(args):
             g["macs"] += l["macs"]
             if args.grad:     # g (and the plane or the last-overflow indices) once per product, codes once, outputs once
                 per_prod = 4 * l["M"] * l["N"] + {"identity": 0, "immediate": l["M"] * l["N"] * ((l["K"] + 31) // 32) * 4,
+                                                  "premapped": 0,     # the plane is read only inside marked bricks
                                                   "recursive": 4 * l["M"] * l["N"]}[args.grad]
                 g["bytes"] += 2 * per_prod + 5 * (l["M"] * l["K"] + l["N"] * l["K"])
             else:
@@ -344,7 +360,7 @@ def run(args):
     workload_key = "%s:%s:%s:%s:acc=%d,%d" % (
         args.workload, ("grad-" + args.grad) if args.grad else ("diff" if args.diff is not None else ("bwd-of" if args.of_only else "bwd")) if args.bwd else "fwd",
         args.round, args.order, acc_fmt[0], acc_fmt[1]) + (":in=%d,%d" % in_fmt if in_fmt else "") + (":implicit" if args.implicit else "") + (
-        ":paper-biases" if args.paper_biases else "")
+        ":paper-biases" if args.paper_biases else "") + (":maps" if args.maps else "")
     rec = counter_record(workload_key, dom_name)
     probe_rate = None
     if rec and rec.get("probe_mix"):
@@ -378,7 +394,8 @@ def run(args):
         issued = dom["macs"] * 6 / (dom["ms"] * 1e-3)
         roofline.update({"bound": "mfma", "achieved": issued / 1e12, "peak": 2500.0, "unit": "TFLOP/s", "frac": issued / 2.5e15,
                          "kernel": "lba_grad_dense_kernel<%s> (v_mfma_f32_32x32x16_bf16, 3 passes%s)" % (
-                             args.grad, "; lba_grad_ws: the whole call, with the pass over the plane and the vector kernel's bricks" if args.grad == "immediate" else ""),
+                             args.grad, "; lba_grad_ws: the whole call, with the pass over the plane and the vector kernel's bricks" if args.grad == "immediate" else
+                             "; lba_grad_premapped: the whole call, with the vector kernel's bricks" if args.grad == "premapped" else ""),
                          "algorithmic_tflops": dom["macs"] * 2 / (dom["ms"] * 1e-3) / 1e12, "valu_slots_per_mac": None,
                          "peak_measured": None, "frac_of_measured": None})
 
@@ -426,7 +443,7 @@ def run(args):
                                 "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}.get(
                                     args.workload, "single GEMM %s, ReLU activations, He weights" % args.workload),
                    "macs_per_step": total_macs, "qprod": "M%dE%d b=%d" % (prod_fmt[1], prod_fmt[0], prod_fmt[2]), "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
-                   "call": ("%s, %s estimator: dX and dW (2 masked MACs per forward MAC)" % ("lba_grad_ws" if args.grad == "immediate" else "lba_grad", args.grad)) if args.grad else ("lba_gemm_bwd_diff (C + DIFF plane, eps2 = %g)" % args.diff) if args.diff is not None else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else ("lba_gemm_bwd (C + OF plane)" if args.of_only else "lba_gemm_bwd (C + OF and UF planes)")) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
+                   "call": ("%s, %s estimator: dX and dW (2 masked MACs per forward MAC)" % ({"immediate": "lba_grad_ws", "premapped": "lba_grad_premapped"}.get(args.grad, "lba_grad"), "immediate" if args.grad == "premapped" else args.grad)) if args.grad else ("lba_gemm_bwd_diff (C + DIFF plane, eps2 = %g)" % args.diff) if args.diff is not None else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else (("lba_gemm_bwd_ws" if args.maps else "lba_gemm_bwd") + (" (C + OF plane)" if args.of_only else " (C + OF and UF planes)"))) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
                    "conv": "implicit im2col from NHWC activations (lba_conv2d)" if args.implicit else "operand A is the written-out im2col matrix",
                    "operands": ("E%dM%d codes with per-tensor flex bias (lba_gemm_in)" % in_fmt) if in_fmt else "E4M3"},
         "roofline": roofline,
@@ -488,6 +505,11 @@ SUITE = [
     ("grad", "lba_grad, identity estimator, 4096^3", "--workload gemm4096 --grad identity --steps 3 --warmup 1"),
     ("grad", "lba_grad, recursive estimator, 4096^3", "--workload gemm4096 --grad recursive --steps 3 --warmup 1"),
     ("grad", "lba_grad_ws, immediate estimator, 4096^3", "--workload gemm4096 --grad immediate --steps 3 --warmup 1"),
+    ("grad", "lba_grad_premapped (maps left by lba_gemm_bwd_ws), immediate estimator, ResNet-50 sweep", "--grad premapped --steps 3 --warmup 1"),
+    ("grad", "same, 4096^3", "--workload gemm4096 --grad premapped --steps 3 --warmup 1"),
+    ("grad", "same, BERT-base linears", "--workload bert --grad premapped --steps 5 --warmup 2"),
+    ("main", "3: lba_gemm_bwd_ws (C + 2 planes + brick maps), ResNet-50 sweep", "--bwd --maps --steps 3 --warmup 1"),
+    ("main", "5: same, 4096^3, Q_acc M7E4", "--workload gemm4096 --acc 4,7 --bwd --maps --steps 3 --warmup 1"),
 ] + [("grad", "%s, %s estimator, %s" % ("lba_grad_ws" if e == "immediate" else "lba_grad", e, n), "--workload %s --grad %s --steps 5 --warmup 2" % (w, e))
      for w, n in (("bert", "BERT-base linears"), ("conv", "ResNet-18 conv")) for e in ("identity", "recursive", "immediate")
 ] + [("sweep", "%s E%d M%d" % (r, e, m), "--workload gemm4096 --acc %d,%d --round %s --steps 5 --warmup 1" % (e, m, r))

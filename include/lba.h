@@ -274,6 +274,26 @@ int lba_grad_ws(const float* G, const uint8_t* A, const uint8_t* B,
                 float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste,
                 void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* The recompute call and the immediate estimator as a pair that reads the overflow plane once less (Sec. 4
+ * "Immediate / OF", App. C.3: the planes are written by the recompute and read by the backward products).
+ * lba_gemm_bwd_ws is lba_gemm_bwd under the sequential order (same C and planes, same errors) and also leaves in
+ * `workspace` the brick maps of the overflow plane it wrote, which lba_grad_ws would otherwise build with a pass of
+ * its own over that plane: the recompute kernel knows which words it stores are non-zero.  of_mask must not be NULL
+ * (LBA_ERR_NULL); workspace: device memory, 256-byte aligned (LBA_ERR_ALIGN), at least
+ * lba_grad_workspace_bytes(M, N, K) bytes (LBA_ERR_SHAPE; also for shapes beyond lba_grad's limits, for which that
+ * count is 0 although M, N, K > 0); its layout is the library's own.
+ * lba_grad_premapped is lba_grad_ws with ste = LBA_STE_IMMEDIATE_OF for exactly that plane and that workspace,
+ * both unchanged since lba_gemm_bwd_ws wrote them (same shape; any stream order that makes the recompute call
+ * complete first): it skips the pass over the plane.  A workspace that does not describe the plane gives wrong
+ * gradients without an error.  Results (FP32 sums, order unspecified) and errors as lba_grad_ws. */
+int lba_gemm_bwd_ws(const uint8_t* A, const uint8_t* B, float* C,
+                    uint32_t* of_mask, uint32_t* uf_mask,
+                    int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+int lba_grad_premapped(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask,
+                       float* dX, float* dW, int64_t M, int64_t N, int64_t K,
+                       const void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* lba_grad_ws for callers that cannot allocate device memory (code under HIP graph capture, serving loops,
  * harnesses that forbid hipMalloc): the brick maps live in 1 MiB of device memory that belongs to the library
  * itself (one copy per GPU, held until the process ends), so the call takes no workspace and allocates nothing.

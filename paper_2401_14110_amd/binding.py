@@ -96,6 +96,10 @@ def lib(path=None):
         L.lba_grad.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
         L.lba_grad_ws.restype = ctypes.c_int
         L.lba_grad_ws.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, ctypes.c_size_t, vp]
+        L.lba_gemm_bwd_ws.restype = ctypes.c_int
+        L.lba_gemm_bwd_ws.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, lba_qfmt, lba_qfmt, vp, ctypes.c_size_t, vp]
+        L.lba_grad_premapped.restype = ctypes.c_int
+        L.lba_grad_premapped.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, ctypes.c_size_t, vp]
         L.lba_grad_static.restype = ctypes.c_int
         L.lba_grad_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
         L.lba_grad_workspace_bytes.restype = ctypes.c_size_t
@@ -228,6 +232,16 @@ def lba_grad_static(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, hip_stream=
                                  ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
 
 
+def lba_gemm_bwd_ws(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, workspace, workspace_bytes, hip_stream=None):
+    return lib().lba_gemm_bwd_ws(A, B, C, of_mask, uf_mask, M, N, K, qfmt(qprod), qfmt(qacc), workspace, workspace_bytes,
+                                 ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
+def lba_grad_premapped(G, A, B, of_mask, dX, dW, M, N, K, workspace, workspace_bytes, hip_stream=None):
+    return lib().lba_grad_premapped(G, A, B, of_mask, dX, dW, M, N, K, workspace, workspace_bytes,
+                                    ctypes.c_void_p(hip_stream) if isinstance(hip_stream, int) else hip_stream)
+
+
 def lba_grad_workspace_bytes(M, N, K):
     return int(lib().lba_grad_workspace_bytes(M, N, K))
 
@@ -314,6 +328,52 @@ def gemm_bwd(A, B, qprod, qacc, order=ORDER_SEQ, want_c=True, stream=None, want_
                               of.data_ptr() or None, (uf.data_ptr() or None) if want_uf else None,
                               M, N, K, qfmt(qprod), qfmt(qacc), order, _stream(stream)))
     return C, of, uf
+
+
+def _workspace(workspace):
+    if workspace.dtype != torch.uint8 or not workspace.is_cuda or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous uint8 device tensor")
+    return workspace
+
+
+def gemm_bwd_ws(A, B, qprod, qacc, workspace=None, want_c=True, stream=None, want_uf=True):
+    """lba_gemm_bwd_ws: as gemm_bwd (sequential order), and `workspace` (allocated here if None: a uint8 device tensor
+    of lba_grad_workspace_bytes(M, N, K) bytes) receives the brick maps of the OF plane for grad_premapped.
+    Returns (C or None, OF plane, UF plane or None, workspace)."""
+    A, B = _ops(A, B)
+    M, K = A.shape
+    N = B.shape[0]
+    W = (K + 31) // 32
+    if workspace is None:
+        workspace = torch.empty(max(256, lba_grad_workspace_bytes(M, N, K)), dtype=torch.uint8, device=A.device)
+    workspace = _workspace(workspace)
+    C = torch.empty((M, N), dtype=torch.float32, device=A.device) if want_c else None
+    of = torch.empty((W, M, N), dtype=torch.int32, device=A.device)
+    uf = torch.empty((W, M, N), dtype=torch.int32, device=A.device) if want_uf else None
+    _check(lib().lba_gemm_bwd_ws(A.data_ptr() or None, B.data_ptr() or None,
+                                 (C.data_ptr() or None) if want_c else None,
+                                 of.data_ptr() or None, (uf.data_ptr() or None) if want_uf else None,
+                                 M, N, K, qfmt(qprod), qfmt(qacc), workspace.data_ptr() or None, workspace.numel(),
+                                 _stream(stream)))
+    return C, of, uf, workspace
+
+
+def grad_premapped(G, A, B, of_plane, workspace, want_dx=True, want_dw=True, stream=None):
+    """lba_grad_premapped: the immediate estimator's dX, dW from the OF plane and the workspace of gemm_bwd_ws."""
+    A, B = _ops(A, B)
+    M, K = A.shape
+    N = B.shape[0]
+    if G.dtype != torch.float32 or tuple(G.shape) != (M, N) or not G.is_cuda:
+        raise ValueError("G must be a float32 device tensor [M, N]")
+    G = G.contiguous()
+    of_plane = _plane(of_plane, K, M, N, "of_plane")
+    workspace = _workspace(workspace)
+    dX = torch.empty((M, K), dtype=torch.float32, device=A.device) if want_dx else None
+    dW = torch.empty((N, K), dtype=torch.float32, device=A.device) if want_dw else None
+    ptr = lambda t: (t.data_ptr() or None) if t is not None else None
+    _check(lib().lba_grad_premapped(ptr(G), ptr(A), ptr(B), ptr(of_plane), ptr(dX), ptr(dW), M, N, K,
+                                    ptr(workspace), workspace.numel(), _stream(stream)))
+    return dX, dW
 
 
 def gemm_bwd_diff(A, B, qprod, qacc, eps2, order=ORDER_SEQ, want_c=True, stream=None, fmt_a=None, fmt_b=None):

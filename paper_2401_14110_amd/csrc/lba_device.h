@@ -1146,6 +1146,36 @@ __device__ __forceinline__ void bwd_tile(float (&acc)[TM][TN], float (&top)[TM][
     }
 }
 
+// Brick maps of the overflow plane as a by-product of the recompute (the gradient side's split of the immediate
+// estimator): a brick is 128 rows x 32 s x 256 k of a gradient product (dX: rows m, s = n; dW: rows n, s = m) and its
+// byte is set when one of its steps overflows.  Called after a k-tile that was not provably quiet, before its words
+// are stored: wof holds the tile's bits, first step highest; `valid` steps of the tile lie below K.  A wave's
+// outputs are 4 TM rows (inside one group of 32 rows) by 16 TN columns (one group of 32 columns, or two when
+// TN = 4: lanes with tx < 8 and the others); tiles start at multiples of 16 TM and 16 TN, so no brick is straddled.
+template <int TM, int TN>
+__device__ __forceinline__ void mark_bricks(const uint32_t (&wof)[TM][TN], int m0, int n0, int t, int valid, int tx, int ty,
+                                            const KParams& p) {
+    uint32_t any = 0u;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            if (m0 + ty * TM + i < p.M && n0 + tx * TN + j < p.N) any |= wof[i][j];
+    if (valid < 32) any &= ~((1u << (32 - valid)) - 1u);       // steps at and beyond K
+    const uint64_t dirty = __builtin_amdgcn_ballot_w64(any != 0u);
+    if (dirty == 0) return;                                    // uniform; the usual case
+    if ((threadIdx.x & 63) == 0) {                             // this lane's first row is the wave's (tx = 0)
+        const int64_t kb = t >> 3;
+        const int m = m0 + ty * TM;
+        uint8_t* bw = p.map_dw + (kb * p.map_rbw + (n0 >> 7)) * p.map_sbw + (m >> 5);
+        if (!*bw) *bw = 1;                                     // racing stores write the same value
+        uint8_t* bx = p.map_dx + (kb * p.map_rbx + (m >> 7)) * p.map_sbx + (n0 >> 5);
+        const uint64_t low = TN == 4 ? 0x00FF00FF00FF00FFull : ~0ull;   // lanes whose columns lie in the first group
+        if ((dirty & low) && !*bx) *bx = 1;
+        if (TN == 4 && (dirty & ~low) && !bx[1]) bx[1] = 1;
+    }
+}
+
 template <int TM, int TN, int PM, int RND, int ORDER, bool UF, int AMODE>
 __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, const int m0, const int n0) {
     constexpr int BK = 32, BM = 16 * TM, BN = 16 * TN;
@@ -1241,6 +1271,7 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
             bwd_tile<TM, TN, PM, RND, ORDER, UF, true, BM, BN>(acc, top, wof, wuf, wof2, wuf2, As, Bs, tx, ty, c);
         } else {
             bwd_tile<TM, TN, PM, RND, ORDER, UF, false, BM, BN>(acc, top, wof, wuf, wof2, wuf2, As, Bs, tx, ty, c);
+            if (ORDER == LBA_ORDER_SEQ && p.map_dx) mark_bricks<TM, TN>(wof, m0, n0, t, p.K - t * BK, tx, ty, p);
         }
         store_event_words(p.of_mask, UF ? p.uf_mask : nullptr, t, 32, p.K - t * BK, wof, wuf, m0, n0, tx, ty, p);
         if (ORDER == LBA_ORDER_CHUNK16 && ((t & 15) == 15 || !more)) {

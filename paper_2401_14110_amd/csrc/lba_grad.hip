@@ -27,6 +27,7 @@
 
 #include "lba.h"
 #include "lba_internal.h"
+#include "lba_launch.h"
 
 namespace lba {
 
@@ -508,9 +509,9 @@ __global__ void __launch_bounds__(256) lba_brick_map_kernel(const uint32_t* __re
     }
 }
 
-__global__ void lba_grad_zero_words_kernel(uint32_t* x, int64_t n) {
+__global__ void lba_grad_fill_words_kernel(uint32_t* x, int64_t n, uint32_t v) {
     const int64_t step = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += step) x[i] = 0u;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += step) x[i] = v;
 }
 
 // x[0..n) = 0 with a grid-stride loop (the launch caps the grid: a grid dimension holds fewer than 2^32 lanes)
@@ -643,6 +644,50 @@ static int run_grad_side(bool dx, const float* G, const uint8_t* V, const uint32
     return e == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
 }
 
+// bytes of the two brick maps (dX side first), each padded to a multiple of 256
+void brick_bytes(int64_t M, int64_t N, int64_t K, size_t* dx_bytes, size_t* dw_bytes) {
+    const size_t kb = (size_t)((K + 255) / 256);
+    const size_t bx = kb * (size_t)((M + 127) / 128) * (size_t)((N + 31) / 32), bw = kb * (size_t)((N + 127) / 128) * (size_t)((M + 31) / 32);
+    *dx_bytes = (bx + 255) / 256 * 256;
+    *dw_bytes = (bw + 255) / 256 * 256;
+}
+
+int brick_maps_fill(void* workspace, int64_t M, int64_t N, int64_t K, bool dirty, hipStream_t st) {
+    size_t bx, bw;
+    brick_bytes(M, N, K, &bx, &bw);
+    const int64_t words4 = (int64_t)((bx + bw) / 4);
+    hipLaunchKernelGGL(lba_grad_fill_words_kernel, zero_grid(words4), dim3(256), 0, st, (uint32_t*)workspace, words4, dirty ? 0x01010101u : 0u);
+    return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
+}
+
+int brick_maps_scan(const uint32_t* plane, void* workspace, int64_t M, int64_t N, int64_t K, uint32_t flip, hipStream_t st) {
+    const int rc = brick_maps_fill(workspace, M, N, K, false, st);
+    if (rc != LBA_OK) return rc;
+    size_t bx, bw;
+    brick_bytes(M, N, K, &bx, &bw);
+    uint8_t* map_dx = (uint8_t*)workspace;
+    uint8_t* map_dw = map_dx + bx;
+    BrickDims bd;
+    bd.quads = ((K + 31) / 32) * M * (N / 4);
+    bd.M = (int32_t)M; bd.N = (int32_t)N; bd.K = (int32_t)K; bd.qpr = (int32_t)(N / 4);
+    bd.rbx = (int32_t)((M + 127) / 128); bd.sbx = (int32_t)((N + 31) / 32);
+    bd.rbw = (int32_t)((N + 127) / 128); bd.sbw = (int32_t)((M + 31) / 32);
+    bd.flip = flip;
+    const int64_t wgs = (bd.quads + kBrickQuadsPerWg - 1) / kBrickQuadsPerWg;
+    if (wgs > 2147483647LL) return LBA_ERR_SHAPE;
+    hipLaunchKernelGGL(lba_brick_map_kernel, dim3((unsigned)wgs), dim3(256), 0, st, plane, map_dx, map_dw, bd);
+    return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
+}
+
+void brick_map_params(void* workspace, int64_t M, int64_t N, int64_t K, KParams* kp) {
+    size_t bx, bw;
+    brick_bytes(M, N, K, &bx, &bw);
+    kp->map_dx = (uint8_t*)workspace;
+    kp->map_dw = kp->map_dx + bx;
+    kp->map_rbx = (int32_t)((M + 127) / 128); kp->map_sbx = (int32_t)((N + 31) / 32);
+    kp->map_rbw = (int32_t)((N + 127) / 128); kp->map_sbw = (int32_t)((M + 31) / 32);
+}
+
 }  // namespace lba
 
 extern "C" {
@@ -682,23 +727,16 @@ int lba_ste_plane(const uint32_t* of_mask, const uint32_t* of_mask2, uint32_t* c
     return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
 }
 
-// bytes of the two brick maps (dX side first), each padded to a multiple of 256
-static void brick_bytes(int64_t M, int64_t N, int64_t K, size_t* dx_bytes, size_t* dw_bytes) {
-    const size_t kb = (size_t)((K + 255) / 256);
-    const size_t bx = kb * (size_t)((M + 127) / 128) * (size_t)((N + 31) / 32), bw = kb * (size_t)((N + 127) / 128) * (size_t)((M + 31) / 32);
-    *dx_bytes = (bx + 255) / 256 * 256;
-    *dw_bytes = (bw + 255) / 256 * 256;
-}
-
 size_t lba_grad_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     if (M <= 0 || N <= 0 || K <= 0 || lba::validate_shapes(M, N, K) != LBA_OK || M * N > ((int64_t)1 << 30)) return 0;
     size_t a, b;
-    brick_bytes(M, N, K, &a, &b);
+    lba::brick_bytes(M, N, K, &a, &b);
     return a + b;
 }
 
 static int grad_impl(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
-                     float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* workspace, void* hip_stream);
+                     float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* workspace, void* hip_stream,
+                     bool maps_ready = false);
 
 int lba_grad(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
              float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* hip_stream) {
@@ -739,6 +777,19 @@ static int static_scratch(void** out) {
     return LBA_OK;
 }
 
+int lba_grad_premapped(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask,
+                       float* dX, float* dW, int64_t M, int64_t N, int64_t K,
+                       const void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const int rc = lba::validate_shapes(M, N, K);
+    if (rc != LBA_OK) return rc;
+    if (M > 0 && N > 0 && K > 0 && M * N <= ((int64_t)1 << 30)) {
+        if (!workspace) return LBA_ERR_NULL;
+        if (((uintptr_t)workspace % 256) != 0) return LBA_ERR_ALIGN;
+        if (workspace_bytes < lba_grad_workspace_bytes(M, N, K)) return LBA_ERR_SHAPE;
+    }
+    return grad_impl(G, A, B, of_mask, nullptr, dX, dW, M, N, K, LBA_STE_IMMEDIATE_OF, const_cast<void*>(workspace), hip_stream, true);
+}
+
 int lba_grad_static(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
                     float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* hip_stream) {
     const int rc = lba::validate_shapes(M, N, K);
@@ -752,7 +803,8 @@ int lba_grad_static(const float* G, const uint8_t* A, const uint8_t* B, const ui
 }
 
 static int grad_impl(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
-                     float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* workspace, void* hip_stream) {
+                     float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* workspace, void* hip_stream,
+                     bool maps_ready) {
     int rc = lba::validate_shapes(M, N, K);
     if (rc != LBA_OK) return rc;
     if (ste != LBA_STE_IDENTITY && ste != LBA_STE_IMMEDIATE_OF && ste != LBA_STE_RECURSIVE_OF &&
@@ -784,22 +836,13 @@ static int grad_impl(const float* G, const uint8_t* A, const uint8_t* B, const u
     if (workspace && (ste == LBA_STE_IMMEDIATE_OF || ste == LBA_STE_COEF_PLANE) &&
         lba::grad_dense_ok(G, nullptr, nullptr, M, N, K) && ((uintptr_t)of_mask % 16) == 0) {
         size_t bx, bw;
-        brick_bytes(M, N, K, &bx, &bw);
+        lba::brick_bytes(M, N, K, &bx, &bw);
         uint8_t* map_dx = (uint8_t*)workspace;
         uint8_t* map_dw = map_dx + bx;
-        const int64_t words4 = (int64_t)((bx + bw) / 4);
-        hipLaunchKernelGGL(lba::lba_grad_zero_words_kernel, lba::zero_grid(words4), dim3(256), 0, st, (uint32_t*)workspace, words4);
-        if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
-        lba::BrickDims bd;
-        bd.quads = ((K + 31) / 32) * M * (N / 4);
-        bd.M = (int32_t)M; bd.N = (int32_t)N; bd.K = (int32_t)K; bd.qpr = (int32_t)(N / 4);
-        bd.rbx = (int32_t)((M + 127) / 128); bd.sbx = (int32_t)((N + 31) / 32);
-        bd.rbw = (int32_t)((N + 127) / 128); bd.sbw = (int32_t)((M + 31) / 32);
-        bd.flip = (ste == LBA_STE_COEF_PLANE) ? 0xFFFFFFFFu : 0u;   // a coefficient plane blocks where a bit is clear
-        const int64_t wgs = (bd.quads + lba::kBrickQuadsPerWg - 1) / lba::kBrickQuadsPerWg;
-        if (wgs > 2147483647LL) return LBA_ERR_SHAPE;
-        hipLaunchKernelGGL(lba::lba_brick_map_kernel, dim3((unsigned)wgs), dim3(256), 0, st, of_mask, map_dx, map_dw, bd);
-        if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
+        if (!maps_ready) {                                     // (lba_grad_premapped: the recompute call left them there)
+            rc = lba::brick_maps_scan(of_mask, workspace, M, N, K, (ste == LBA_STE_COEF_PLANE) ? 0xFFFFFFFFu : 0u, st);
+            if (rc != LBA_OK) return rc;
+        }
         bricks_dx = map_dx;
         bricks_dw = map_dw;
     }

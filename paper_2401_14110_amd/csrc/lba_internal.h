@@ -54,6 +54,12 @@ struct KParams {
     // mix_m_half (mix_gx_half per tile column; the forward kernel only), the rest 32 x 32 tiles of the remaining rows
     int32_t mix_main, mix_gx_main, mix_gx_tail, mix_m_main;
     int32_t mix_half, mix_gx_half, mix_m_half;
+    // brick maps of the overflow plane as a by-product of the recompute call (lba_gemm_bwd_ws), else null: byte
+    // ((k / 256) * map_rbx + m / 128) * map_sbx + n / 32 of map_dx and ((k / 256) * map_rbw + n / 128) * map_sbw + m / 32
+    // of map_dw are set when a step of that brick overflows (the maps arrive zeroed)
+    uint8_t* map_dx;
+    uint8_t* map_dw;
+    int32_t map_rbx, map_sbx, map_rbw, map_sbw;
     int32_t prod_round;      // GEN: product mantissa narrower than a product of two operands
     int32_t prod_rne;        // GEN: its rounding
     float diff_eps;          // DIFF plane (written through of_mask): the threshold eps2, exact

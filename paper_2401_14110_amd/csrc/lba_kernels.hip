@@ -72,7 +72,8 @@ static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, 
                int order, int events, void* stream,
                int64_t batch = 1, int64_t stride_a = 0, int64_t stride_b = 0, int64_t stride_c = 0,
                uint32_t* of_mask2 = nullptr, uint32_t* uf_mask2 = nullptr, const InSpec* in = nullptr,
-               const lba_conv2d_desc* conv = nullptr, int conv_oh = 0, int conv_ow = 0, float diff_eps = 0.0f) {
+               const lba_conv2d_desc* conv = nullptr, int conv_oh = 0, int conv_ow = 0, float diff_eps = 0.0f,
+               void* brick_ws = nullptr) {
     Plan pl;
     if (batch < 0 || batch > 65535 || stride_a < 0 || stride_b < 0 || stride_c < 0) return LBA_ERR_SHAPE;
     int rc = make_plan(M, N, K, qprod, qacc, order, events, &pl, batch, in, conv != nullptr);
@@ -98,6 +99,7 @@ static int run(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, 
     kp.A = A; kp.B = B; kp.C = C; kp.of_mask = of_mask; kp.uf_mask = uf_mask;
     kp.of_mask2 = of_mask2; kp.uf_mask2 = uf_mask2;
     kp.diff_eps = diff_eps;
+    if (brick_ws) brick_map_params(brick_ws, M, N, K, &kp);    // the recompute kernel marks the bricks it finds dirty
     kp.batch = (int32_t)batch; kp.stride_a = stride_a; kp.stride_b = stride_b; kp.stride_c = stride_c;
     int la = gcd_align(A, K);
     const int lb = gcd_align(B, K);
@@ -142,6 +144,36 @@ int lba_gemm_bwd(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask
     }
     // 3: the overflow plane alone (the planner may then cut the last rows finer)
     return lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, order, (of_mask && !uf_mask) ? 3 : 1, hip_stream);
+}
+
+int lba_gemm_bwd_ws(const uint8_t* A, const uint8_t* B, float* C, uint32_t* of_mask, uint32_t* uf_mask,
+                    int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc,
+                    void* workspace, size_t workspace_bytes, void* hip_stream) {
+    const int events = (of_mask && !uf_mask) ? 3 : 1;
+    lba::Plan pl;
+    int rc = lba::make_plan(M, N, K, qprod, qacc, LBA_ORDER_SEQ, events, &pl);
+    if (rc != LBA_OK) return rc;
+    if (M == 0 || N == 0 || K == 0)                            // no plane words, no bricks
+        return lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, LBA_ORDER_SEQ, events, hip_stream);
+    const size_t need = lba_grad_workspace_bytes(M, N, K);
+    if (need == 0) return LBA_ERR_SHAPE;                       // beyond what lba_grad takes
+    if (!of_mask || !workspace) return LBA_ERR_NULL;           // the maps describe the overflow plane
+    if (((uintptr_t)workspace % 256) != 0) return LBA_ERR_ALIGN;
+    if (workspace_bytes < need) return LBA_ERR_SHAPE;
+    if (!A || !B) return LBA_ERR_NULL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    // the scaled-domain recompute kernel marks the bricks itself; after the general kernel one pass over the plane
+    // does (or, where that pass cannot read the plane in 16-byte groups, every brick is marked)
+    const bool fused = pl.kernel == lba::KERNEL_FAST;
+    if (fused) {
+        rc = lba::brick_maps_fill(workspace, M, N, K, false, st);
+        if (rc != LBA_OK) return rc;
+    }
+    rc = lba::run(A, B, C, of_mask, uf_mask, M, N, K, qprod, qacc, LBA_ORDER_SEQ, events, hip_stream,
+                  1, 0, 0, 0, nullptr, nullptr, nullptr, nullptr, 0, 0, 0.0f, fused ? workspace : nullptr);
+    if (rc != LBA_OK || fused) return rc;
+    if ((N % 4) == 0 && ((uintptr_t)of_mask % 16) == 0) return lba::brick_maps_scan(of_mask, workspace, M, N, K, 0u, st);
+    return lba::brick_maps_fill(workspace, M, N, K, true, st);
 }
 
 // eps2 must make eps2 * |x w| exact in FP32: at most 12 significant bits, and a range that keeps the

@@ -27,5 +27,14 @@ hipError_t launch_fast_diff(const Plan& pl, hipStream_t st);
 // general kernel (forward and recompute)
 hipError_t launch_gen(const Plan& pl, hipStream_t st);
 
+// Brick maps of an overflow plane (lba_grad.hip): two byte maps in a caller-given workspace, the dX side first, each
+// padded to a multiple of 256 bytes.  All return LBA_OK or LBA_ERR_LAUNCH / LBA_ERR_SHAPE.
+void brick_bytes(int64_t M, int64_t N, int64_t K, size_t* dx_bytes, size_t* dw_bytes);
+int brick_maps_fill(void* workspace, int64_t M, int64_t N, int64_t K, bool dirty, hipStream_t st);   // all clean / all dirty
+// zeroes the maps, then marks them in one pass over the plane (N % 4 == 0, plane 16-byte aligned); flip: 0 for a
+// plane of overflow bits, all ones for a plane of coefficients
+int brick_maps_scan(const uint32_t* plane, void* workspace, int64_t M, int64_t N, int64_t K, uint32_t flip, hipStream_t st);
+void brick_map_params(void* workspace, int64_t M, int64_t N, int64_t K, KParams* kp);   // for a kernel that marks them itself
+
 }  // namespace lba
 #endif

@@ -80,6 +80,28 @@ def test_gradient_call_checks_every_pointer_before_launching():
     assert lb.lba_grad(G, A, B, P, None, O, O, 8, 8, 8, 2) == lb.ERR_NULL
 
 
+def test_recompute_with_brick_maps_validates_before_launching():
+    A = ctypes.c_void_p(0x1000)
+    W = ctypes.c_void_p(0x2000)                                # 256-byte aligned
+    need = lb.lba_grad_workspace_bytes(256, 64, 512)
+    assert need >= 512
+    args = (256, 64, 512, GOOD_P, GOOD_A)
+    assert lb.lba_gemm_bwd_ws(A, A, A, None, A, *args, W, need) == lb.ERR_NULL        # the maps describe the OF plane
+    assert lb.lba_gemm_bwd_ws(A, A, A, A, A, *args, None, need) == lb.ERR_NULL
+    assert lb.lba_gemm_bwd_ws(A, A, A, A, A, *args, ctypes.c_void_p(0x2010), need) == lb.ERR_ALIGN
+    assert lb.lba_gemm_bwd_ws(A, A, A, A, A, *args, W, need - 1) == lb.ERR_SHAPE
+    assert lb.lba_gemm_bwd_ws(None, A, A, A, A, *args, W, need) == lb.ERR_NULL
+    assert lb.lba_gemm_bwd_ws(A, A, A, A, A, 1 << 20, 1 << 11, 64, GOOD_P, GOOD_A, W, 1 << 30) == lb.ERR_SHAPE   # beyond lba_grad
+    assert lb.lba_gemm_bwd_ws(A, A, A, A, A, 256, 64, 512, (9, 7, 15, 0), GOOD_A, W, need) == lb.ERR_FORMAT
+    assert lb.lba_gemm_bwd_ws(A, A, A, A, A, 0, 64, 512, GOOD_P, GOOD_A, None, 0) == lb.OK            # nothing to do
+    G = O = A
+    assert lb.lba_grad_premapped(G, A, A, A, O, O, 256, 64, 512, None, need) == lb.ERR_NULL
+    assert lb.lba_grad_premapped(G, A, A, A, O, O, 256, 64, 512, ctypes.c_void_p(0x2010), need) == lb.ERR_ALIGN
+    assert lb.lba_grad_premapped(G, A, A, A, O, O, 256, 64, 512, W, need - 1) == lb.ERR_SHAPE
+    assert lb.lba_grad_premapped(G, A, A, None, O, O, 256, 64, 512, W, need) == lb.ERR_NULL
+    assert lb.lba_grad_premapped(None, A, A, A, O, O, 256, 64, 512, W, need) == lb.ERR_NULL
+
+
 def test_status_texts():
     for code in range(0, 7):
         assert lb.strerror(code)

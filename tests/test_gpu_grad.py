@@ -362,3 +362,80 @@ def test_immediate_estimator_split_by_bricks(ref, gref):
     assert lb.lba_grad_ws(*args, ptr(ws), lb.lba_grad_workspace_bytes(M, N, K) - 1) == lb.ERR_SHAPE
     assert lb.lba_grad_ws(*args, ptr(ws), lb.lba_grad_workspace_bytes(M, N, K)) == lb.OK
     torch.cuda.synchronize()
+
+
+def brick_maps_of(ofn, M, N, K):
+    """The two byte maps as the library lays them out (dX side first, each padded to 256 bytes), from an OF plane."""
+    W = (K + 31) // 32
+    words = ofn.view(np.uint32).copy()
+    if K % 32:
+        words[W - 1] &= np.uint32((1 << (K % 32)) - 1)
+    nz = words != 0                                                          # [W, M, N]
+    kb = (K + 255) // 256
+    dx = np.zeros((kb, (M + 127) // 128, (N + 31) // 32), np.uint8)
+    dw = np.zeros((kb, (N + 127) // 128, (M + 31) // 32), np.uint8)
+    w, m, n = np.nonzero(nz)
+    dx[w // 8, m // 128, n // 32] = 1
+    dw[w // 8, n // 128, m // 32] = 1
+    pad = lambda a: np.concatenate([a.ravel(), np.zeros((-a.size) % 256, np.uint8)])
+    return np.concatenate([pad(dx), pad(dw)])
+
+
+def test_recompute_call_leaves_the_brick_maps(ref, gref):
+    # lba_gemm_bwd_ws + lba_grad_premapped: same C and planes as lba_gemm_bwd; the maps in the workspace are those of
+    # the plane (computed here from the plane itself), whichever kernel wrote it: the scaled-domain kernel that marks
+    # bricks as it goes (floor and nearest-even, both planes or the overflow plane alone, plain and mixed grids), the
+    # general kernel followed by the pass over the plane, and the all-marked maps where that pass cannot run
+    # (N % 4 != 0).  Then the gradients from those maps against the oracle.
+    rng = np.random.default_rng(4242)
+    QPb, QAb = (4, 7, 12), (4, 7, 10)                                        # R_OF = 63.75
+    GEN_P, GEN_A = (5, 3, 12), (4, 7, 10)                                    # Q_prod rounds the mantissa: general kernel with planes
+    ws = torch.full((1 << 20,), 0x5A, dtype=torch.uint8, device=DEV)
+    seen = set()
+    cases = [((300, 200, 600), "tail", 0, True), ((130, 68, 260), "none", 0, True), ((260, 132, 515), "all", 1, True),
+             ((64 * 392, 64, 72), "rows", 0, True), ((64 * 150 + 33, 132, 300), "tail", 0, False), ((257, 36, 1028), "tail", 1, False),
+             ((70, 66, 100), "tail", 0, True), ((33, 130, 65), "all", 1, True), ((1500, 64, 147), "rows", 0, True)]
+    for (M, N, K), loud, rnd, want_uf in cases:
+        need = lb.lba_grad_workspace_bytes(M, N, K)
+        assert 0 < need <= ws.numel()
+        A = codes(rng, (M, K), 2, 5); B = codes(rng, (N, K), 2, 5)
+        if loud == "tail":
+            A[:, K - K // 3:] = codes(rng, (M, K // 3), 6, 10); B[:, K - K // 3:] = codes(rng, (N, K // 3), 6, 10)
+        elif loud == "all":
+            A = codes(rng, (M, K), 5, 10); B = codes(rng, (N, K), 5, 10)
+        elif loud == "rows":
+            A[M // 2: M // 2 + 40] = codes(rng, (40, K), 7, 10); B[:, :] = codes(rng, (N, K), 5, 8)
+        tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+        for qp, qa in ((QPb, QAb), (GEN_P, GEN_A)):
+            qpf, qaf = qp + (rnd,), qa + (rnd,)
+            plan = lb.lba_plan_query(M, N, K, qpf, qaf, 0, 1 if want_uf else 3)
+            C0, of0, uf0 = lb.gemm_bwd(tA, tB, qpf, qaf, want_uf=want_uf)
+            ws.fill_(0x5A)
+            C1, of1, uf1, _ = lb.gemm_bwd_ws(tA, tB, qpf, qaf, workspace=ws, want_uf=want_uf)
+            torch.cuda.synchronize()
+            assert torch.equal(C0.view(torch.int32), C1.view(torch.int32)) and torch.equal(of0, of1)
+            assert (uf0 is None and uf1 is None) or torch.equal(uf0, uf1)
+            got = ws[:need].cpu().numpy()
+            want = brick_maps_of(of1.cpu().numpy(), M, N, K)
+            assert want.size == need
+            if plan["kernel"] == 1 and N % 4 != 0:
+                assert (got == 1).all(), (M, N, K, "all marked")
+                seen.add("all-marked")
+            else:
+                assert np.array_equal(got != 0, want != 0), (M, N, K, qp, rnd, plan["kernel"], int((got != 0).sum()), int(want.sum()))
+                seen.add(("general" if plan["kernel"] == 1 else "fused") + ("+mixed" if plan["tail_blocks"] + plan["mid_blocks"] > 0 else ""))
+                kb = (K + 255) // 256
+                bricks = kb * (((M + 127) // 128) * ((N + 31) // 32) + ((N + 127) // 128) * ((M + 31) // 32))
+                seen.add("clean" if not want.any() else ("dirty" if int(want.sum()) == bricks else "partly"))
+            if qp is GEN_P and (M, N, K) != (300, 200, 600):
+                continue                                                     # gradients: once per shape, and once on the general kernel's plane
+            G = rng.standard_normal((M, N)).astype(np.float32)
+            tG = torch.from_numpy(G).to(DEV)
+            dX, dW = lb.grad_premapped(tG, tA, tB, of1, ws)
+            torch.cuda.synchronize()
+            dX, dW = dX.cpu().numpy(), dW.cpu().numpy()
+            wX, wW = gref.grad(G, A, B, ref.QFmt(*qpf), ref.QFmt(*qaf), 1)
+            aX, aW = gref.grad_abs(G, A, B, ref.QFmt(*qpf), ref.QFmt(*qaf), 1)
+            assert (np.abs(dX - wX) <= 2 * (N + 1) * 2.0 ** -24 * aX + 1e-30).all(), (M, N, K, loud, "dX")
+            assert (np.abs(dW - wW) <= 2 * (M + 1) * 2.0 ** -24 * aW + 1e-30).all(), (M, N, K, loud, "dW")
+    assert {"fused", "fused+mixed", "general", "all-marked", "clean", "dirty", "partly"} <= seen, seen
