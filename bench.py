@@ -544,7 +544,7 @@ def run_suite(path):
     w.append("# All five configurations on one MI355X: throughput of the library calls\n")
     w.append("Written by `python bench.py --suite profiles/all_configs_summary.md` (one process, one box; every row is one")
     w.append("configuration of `bench.py` with the flags shown, inputs resident in HBM, HIP events per launch, wall time over the")
-    w.append("steps for the rate; the JSON lines are in `all_configs_summary.jsonl`).  `frac` is the dominant kernel's VALU issue")
+    w.append("steps for the rate; the JSON lines are written beside it as `.jsonl`).  `frac` is the dominant kernel's VALU issue")
     w.append("slots per second over the 78.64e12 peak, with the slot count per MAC the planner states for the loop without the")
     w.append("accumulator clamp and without the overflow test (k-tiles in which a sum can reach R_OF add 2 slots per MAC, or 6")
     w.append("with event planes, which the count leaves out: their `frac` under-reports); `mfma`: issued bfloat16 flops over the")

@@ -355,6 +355,18 @@ __global__ void __launch_bounds__(256) lba_grad_kernel(const float* __restrict__
     if (r0 >= d.R) return;                                     // whole wave (uniform)
     const int s_begin = blockIdx.z * d.s_chunk;
     const int s_end = min(d.S, s_begin + d.s_chunk);
+    if (MODE == LBA_STE_IMMEDIATE_OF && d.bricks) {
+        // nothing marked along this wave's part of its brick row (the usual case where the formats fit the data):
+        // done before anything is fetched; the matrix-core kernel's sums are already in the output
+        const uint8_t* __restrict__ br = d.bricks + ((int64_t)(k0 >> 8) * d.brick_rb + (r0 >> 7)) * d.brick_sb;
+        const int b_end = (s_end + 31) >> 5;
+        uint32_t any = 0u;
+        int b = s_begin >> 5;
+        for (; b + 8 <= b_end && !any; b += 8)
+            any = (uint32_t)br[b] | br[b + 1] | br[b + 2] | br[b + 3] | br[b + 4] | br[b + 5] | br[b + 6] | br[b + 7];
+        for (; b < b_end && !any; ++b) any = br[b];
+        if (!any) return;                                      // uniform
+    }
     const bool has_hi = k0 + 32 < d.K;                         // does the plane have a second word slab here
     const uint32_t* __restrict__ P0 = plane + (int64_t)(k0 >> 5) * d.slab;    // not dereferenced unless MODE needs it
     const uint32_t* __restrict__ P1 = has_hi ? P0 + d.slab : P0;
