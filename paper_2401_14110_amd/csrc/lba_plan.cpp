@@ -38,8 +38,6 @@
 
 #include <cmath>
 #include <cstring>
-#include <cstdlib>
-#include <cstdio>
 
 #include <algorithm>
 
@@ -212,12 +210,6 @@ static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
     if (p->events == 1 && p->order != LBA_ORDER_SEQ) return;
     if (p->prod_mode != PM_IDENT && p->prod_mode != PM_FLUSH && p->prod_mode != PM_FLUSH_CLAMP) return;
     const int64_t gx = (M + 63) / 64, gy = (N + 63) / 64, blocks = gx * gy;
-#ifdef LBA_EXPERIMENT
-    if (const char* e = getenv("LBA_MIX")) {
-        long a = 0, b = 0;
-        if (sscanf(e, "%ld,%ld", &a, &b) == 2 && p->events == 0) { if (a >= 0) set_mixed_grid(M, N, a, b, p); return; }
-    }
-#endif
     if (blocks > 256 * 16) return;
     // Rounds of 48 x 64 workgroups (forward call only; measured on M sweeps at N = 256 and 512, whose rates depend on
     // blocks / 256 alone): a CU that holds three 64 x 64 workgroups, or one, issues well below one that holds four or
