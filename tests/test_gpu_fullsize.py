@@ -239,3 +239,40 @@ def test_gradient_products_at_benchmark_sizes(ref):
     dX, _ = lb.grad(G, layer["A"], layer["B"], lb.STE_IMMEDIATE_OF, of_plane=of, want_dw=False)
     torch.cuda.synchronize()
     sampled(layer, G, dX, None, lb.STE_IMMEDIATE_OF, qp, qa, "conv")
+
+
+def test_brick_maps_and_premapped_gradients_at_benchmark_sizes(ref):
+    """lba_gemm_bwd_ws / lba_grad_premapped at benchmark sizes: the maps the recompute kernel leaves (plain grid on the
+    BERT linear, mixed grid on the ResNet-18 conv) equal the maps lba_grad_ws builds with its own pass over the same
+    plane, byte for byte, and the gradients of lba_grad_premapped pass the sampled check against the oracle."""
+    from oracle import lba_grad_ref as gref
+
+    cases = []
+    layer = [l for l in inputs.make_workload("bert", DEV) if l["name"] == "attn_out"][0]
+    cases.append((layer, inputs.folded_formats(layer["ta"], layer["tb"], PROD, (4, 7, 16), 0)[:2], "attn_out"))   # overflows now and then
+    layer = inputs.make_workload("conv", DEV)[0]
+    cases.append((layer, inputs.folded_formats(layer["ta"], layer["tb"], PROD, (4, 7, 9), 0)[:2], "conv"))
+    marked = 0
+    for layer, (qp, qa), what in cases:
+        M, N, K = layer["M"], layer["N"], layer["K"]
+        need = lb.lba_grad_workspace_bytes(M, N, K)
+        G = torch.from_numpy(np.random.default_rng(8).standard_normal((M, N)).astype(np.float32)).to(DEV)
+        _, of, _, ws = lb.gemm_bwd_ws(layer["A"], layer["B"], qp, qa, want_c=False, want_uf=False)
+        ws2 = torch.full((need,), 0x77, dtype=torch.uint8, device=DEV)
+        eX, eW = lb.grad(G, layer["A"], layer["B"], lb.STE_IMMEDIATE_OF, of_plane=of, workspace=ws2)
+        dX, dW = lb.grad_premapped(G, layer["A"], layer["B"], of, ws)
+        torch.cuda.synchronize()
+        assert torch.equal(ws[:need] != 0, ws2 != 0), what
+        marked += int((ws[:need] != 0).sum())
+        fp, fa = ref.QFmt(*qp), ref.QFmt(*qa)
+        rows = sample_rows(M, n_random=8)
+        idx = torch.from_numpy(rows).to(DEV)
+        A = layer["A"].index_select(0, idx).cpu().numpy(); Gs = G.index_select(0, idx).cpu().numpy()
+        B = layer["B"].cpu().numpy()
+        c = gref.coefficients(A, B, fp, fa, lb.STE_IMMEDIATE_OF)
+        wX, _ = gref.grad(Gs, A, B, fp, fa, lb.STE_IMMEDIATE_OF, c=c)
+        aX, _ = gref.grad_abs(Gs, A, B, fp, fa, lb.STE_IMMEDIATE_OF, c=c)
+        _grad_check(dX.index_select(0, idx).cpu().numpy(), wX, aX, N, what + " dX rows (premapped)")
+        scale = float(eW.abs().max())
+        assert float((dW - eW).abs().max()) <= 1e-4 * scale, what
+    assert marked > 0

@@ -809,12 +809,15 @@ def test_hip_graph_replays(ref):
         last = lb.last_overflow(of, K)
         dX, dW = lb.grad(tG, tA, tB, lb.STE_RECURSIVE_OF, last_of=last)
         dXi, dWi = lb.grad(tG, tA, tB, lb.STE_IMMEDIATE_OF, of_plane=of)
+        C3, of3, _, ws = lb.gemm_bwd_ws(tA, tB, qp, qa, want_uf=False)         # the recompute call that also leaves the brick maps
+        dXp, dWp = lb.grad_premapped(tG, tA, tB, of3, ws)
     for rep in range(3):
         A = rand_codes(rng, (M, K), 3, 11); B = rand_codes(rng, (N, K), 3, 11)
         G = rng.standard_normal((M, N)).astype(np.float32)
         tA.copy_(torch.from_numpy(A)); tB.copy_(torch.from_numpy(B)); tG.copy_(torch.from_numpy(G))
-        for t in (C, Cc, C2, dX, dW, dXi, dWi):
+        for t in (C, Cc, C2, dX, dW, dXi, dWi, C3, dXp, dWp):
             t.fill_(7.0)                                               # stale values must not survive
+        ws.fill_(1)
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
@@ -828,5 +831,6 @@ def test_hip_graph_replays(ref):
         torch.cuda.synchronize()
         assert torch.equal(last, last0), rep
         scale = float(eX.abs().max()) + float(eW.abs().max())
-        for got, want in ((dX, eX), (dW, eW), (dXi, eXi), (dWi, eWi)):
+        assert torch.equal(of3, of) and np.array_equal(bits(C3.cpu().numpy()), bits(wc)), rep
+        for got, want in ((dX, eX), (dW, eW), (dXi, eXi), (dWi, eWi), (dXp, eXi), (dWp, eWi)):
             assert float((got - want).abs().max()) <= 1e-4 * scale, rep
