@@ -31,8 +31,8 @@ PAPER_PROD, PAPER_ACC = (4, 7, 12), (4, 7, 10)
 CASES = {  # workload -> [(product format, accumulator format, rounding, order, planes)]
     "conv": [(PROD, ACC, 0, 0, True), (PROD, ACC, 1, 0, False)],
     "bert": [(PROD, ACC, 0, 0, True), (PAPER_PROD, PAPER_ACC, 0, 1, True)],
-    "gemm4096": [(PROD, ACC, 0, 0, False)],
-    "resnet50": [(PROD, ACC, 0, 0, False), (PROD, ACC, 1, 0, False), (PAPER_PROD, PAPER_ACC, 0, 1, False)],
+    "gemm4096": [(PROD, ACC, 0, 0, False), (PROD, ACC, 0, 0, True)],
+    "resnet50": [(PROD, ACC, 0, 0, False), (PROD, ACC, 1, 0, False), (PAPER_PROD, PAPER_ACC, 0, 1, False), (PROD, ACC, 0, 0, True)],
 }
 
 
