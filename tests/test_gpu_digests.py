@@ -20,7 +20,7 @@ DEV = "cuda:0"
 GOLD = os.path.join(os.path.dirname(__file__), "golden", "full_digests.txt")
 # (rounding, order, with planes) cases the golden file must hold per workload
 WANT_CASES = {"conv": {(0, 0, True), (1, 0, False)}, "bert": {(0, 0, True), (0, 1, True)}, "gemm4096": {(0, 0, False), (0, 0, True)},
-              "resnet50": {(0, 0, False), (1, 0, False), (0, 1, False)}}
+              "resnet50": {(0, 0, False), (1, 0, False), (0, 1, False), (0, 0, True)}}
 
 
 def golden(name):
