@@ -80,5 +80,6 @@ def test_checksum_function_and_golden_file():
             assert (len(t) == 15) == (t[7] == "1" and len(t) > 11)         # chunked order with planes: four of them
             rows[t[0]] = rows.get(t[0], 0) + 1
     # conv: floor (with planes) and nearest-even; bert: floor / sequential and the paper's biases / chunked, with
-    # planes; ResNet-50: floor, nearest-even and the paper's biases under the chunked order
-    assert rows == {"conv": 2, "bert": 8, "gemm4096": 1, "resnet50": 162}
+    # planes; 4096^3: floor without and with planes; ResNet-50: floor (without and with planes), nearest-even and the
+    # paper's biases under the chunked order
+    assert rows == {"conv": 2, "bert": 8, "gemm4096": 2, "resnet50": 216}
