@@ -161,8 +161,8 @@ def run(args):
     with_masks = 2 if args.diff is not None else ((3 if (args.of_only and order == 0) else 1) if args.bwd else 0)
     if in_fmt and (args.grad or (args.bwd and order == 1)):
         raise SystemExit("bench.py: --in-fmt times lba_gemm_in or lba_gemm_bwd_in (sequential order)")
-    if args.implicit and (in_fmt or args.bwd or args.grad):
-        raise SystemExit("bench.py: --implicit times the forward call on E4M3 operands only")
+    if args.implicit and (in_fmt or args.grad or args.diff is not None or args.maps or (args.bwd and (order == 1 or rnd != 0))):
+        raise SystemExit("bench.py: --implicit times lba_conv2d, or with --bwd lba_conv2d_bwd under floor rounding and the sequential order")
     layers = inputs.make_conv_workload(args.workload, dev) if args.implicit else inputs.make_workload(args.workload, dev, in_fmt=in_fmt)
     cmax = max(l["M"] * l["N"] for l in layers)
     Cbuf = torch.empty(cmax, dtype=torch.float32, device=dev)
@@ -183,6 +183,8 @@ def run(args):
                 # tiles that can add a clamp, a compare and a carry-in add per MAC, which this count leaves out
                 fwd = lb.lba_plan_query(l["M"], l["N"], l["K"], l["qp"], l["qa"], order, 0)
                 l["plan"] = dict(l["plan"], valu_per_mac_x100=fwd["valu_per_mac_x100"])
+            if args.implicit:
+                l["kname"] = conv_kernel_name(l["kname"])
         l["C"] = Cbuf[: l["M"] * l["N"]].view(l["M"], l["N"])
         l["macs"] = l["M"] * l["N"] * l["K"]
     if args.grad:
@@ -251,6 +253,9 @@ def run(args):
             if args.diff is not None:
                 rc = lb.lba_gemm_bwd_diff(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
                                           l["M"], l["N"], l["K"], l["qp"], l["qa"], order, args.diff, stream)
+            elif args.implicit:
+                rc = lb.lba_conv2d_bwd(l["X"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
+                                       None if args.of_only else uf_buf.data_ptr(), l["desc"], l["cout"], l["qp"], l["qa"], order, stream)
             elif in_fmt:
                 rc = lb.lba_gemm_bwd_in(l["A"].data_ptr(), l["B"].data_ptr(), l["C"].data_ptr(), of_buf.data_ptr(),
                                         None if args.of_only else uf_buf.data_ptr(), l["M"], l["N"], l["K"],
@@ -443,7 +448,7 @@ def run(args):
                                 "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}.get(
                                     args.workload, "single GEMM %s, ReLU activations, He weights" % args.workload),
                    "macs_per_step": total_macs, "qprod": "M%dE%d b=%d" % (prod_fmt[1], prod_fmt[0], prod_fmt[2]), "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
-                   "call": ("%s, %s estimator: dX and dW (2 masked MACs per forward MAC)" % ({"immediate": "lba_grad_ws", "premapped": "lba_grad_premapped"}.get(args.grad, "lba_grad"), "immediate" if args.grad == "premapped" else args.grad)) if args.grad else ("lba_gemm_bwd_diff (C + DIFF plane, eps2 = %g)" % args.diff) if args.diff is not None else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else (("lba_gemm_bwd_ws" if args.maps else "lba_gemm_bwd") + (" (C + OF plane)" if args.of_only else " (C + OF and UF planes)"))) if args.bwd else "lba_gemm", "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
+                   "call": ("%s, %s estimator: dX and dW (2 masked MACs per forward MAC)" % ({"immediate": "lba_grad_ws", "premapped": "lba_grad_premapped"}.get(args.grad, "lba_grad"), "immediate" if args.grad == "premapped" else args.grad)) if args.grad else ("lba_gemm_bwd_diff (C + DIFF plane, eps2 = %g)" % args.diff) if args.diff is not None else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else (("lba_gemm_bwd_ws" if args.maps else ("lba_conv2d_bwd" if args.implicit else "lba_gemm_bwd")) + (" (C + OF plane)" if args.of_only else " (C + OF and UF planes)"))) if args.bwd else ("lba_conv2d" if args.implicit else "lba_gemm"), "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
                    "conv": "implicit im2col from NHWC activations (lba_conv2d)" if args.implicit else "operand A is the written-out im2col matrix",
                    "operands": ("E%dM%d codes with per-tensor flex bias (lba_gemm_in)" % in_fmt) if in_fmt else "E4M3"},
         "roofline": roofline,
@@ -577,6 +582,17 @@ def run_suite(path):
         w.append("")
     with open(path, "w") as f:
         f.write("\n".join(w))
+
+
+def conv_kernel_name(name):
+    """The kernel lba_conv2d / lba_conv2d_bwd launch where the row-major call of the same shape and formats launches
+    `name`: E4M3 tensors run the same tiles and grids through the instantiations that gather im2col rows."""
+    for plain, conv in (("lba_fast_mixed_kernel<", "lba_fast_conv_mixed_kernel<"), ("lba_fast_bwd_mixed_kernel<", "lba_fast_bwd_conv_mixed_kernel<")):
+        if name.startswith(plain):
+            return conv + name[len(plain):]
+    if (name.startswith("lba_fast_kernel<") or name.startswith("lba_fast_bwd_kernel<")) and name.endswith(", 0>"):
+        return name[:-4] + ", 2>"
+    return name
 
 
 def main():

@@ -387,6 +387,63 @@ __device__ __forceinline__ void fetch_tile_a(const uint8_t* __restrict__ A, cons
     else        fetch_tile<ROWS, BK>(A, p.M, p.K, r0, k0, p.ld_align, tid, regs);
 }
 
+// The same gather with the part that depends on the lane's row alone taken out of the k loop (kernels that read
+// im2col rows of E4M3 codes: AMODE 2).  With k-tiles of 32 a lane fetches one 16-byte piece per tile, always of the
+// same row: ConvLane keeps that row's image and the input coordinates of tap (0, 0).  The load of a piece is
+// unconditional (a piece outside the image or the matrix reads the first bytes of an image and is zeroed afterwards),
+// so that it can be scheduled like the loads of a row-major matrix.
+struct ConvLane {
+    const uint8_t* img;      // X + n * H * W * C
+    int ih0, iw0;            // input row / column of tap (0, 0)
+    int kq16;                // the lane's k offset inside a tile
+    bool ok;                 // the lane has a piece and its row is inside the matrix
+};
+
+template <int ROWS, int BK>
+__device__ __forceinline__ ConvLane conv_lane(const uint8_t* __restrict__ X, const KParams& p, int r0, int tid) {
+    static_assert(Stage<ROWS, BK>::kPerLane == 1, "one piece per lane and tile");
+    ConvLane L;
+    const int c = tid;
+    const int row = c % ROWS, kq = c / ROWS;
+    const int r = r0 + row;
+    L.ok = c >= 0 && c < Stage<ROWS, BK>::kChunks && r < p.M;
+    const int rr = L.ok ? r : 0;
+    const int ow = rr % p.cv_ow, t = rr / p.cv_ow;
+    const int oh = t % p.cv_oh, n = t / p.cv_oh;
+    L.ih0 = oh * p.cv_stride - p.cv_pad;
+    L.iw0 = ow * p.cv_stride - p.cv_pad;
+    L.img = X + (int64_t)n * p.cv_h * p.cv_w * p.cv_c;
+    L.kq16 = kq * 16;
+    return L;
+}
+
+template <int ROWS, int BK>
+__device__ __forceinline__ void fetch_tile_conv_lane(const ConvLane& L, const KParams& p, int k0,
+                                                     uint4 (&regs)[Stage<ROWS, BK>::kPerLane]) {
+    const int k = k0 + L.kq16;
+    const int tap = (int)div_magic((uint32_t)k, p.cv_magic_c);
+    int ch = k - tap * p.cv_c;
+    int kh = (int)div_magic((uint32_t)tap, p.cv_magic_kw), kw = tap - kh * p.cv_kw;
+    if (p.cv_vec) {                                            // uniform
+        const int ih = L.ih0 + kh, iw = L.iw0 + kw;
+        const bool in = L.ok && k < p.K && (unsigned)ih < (unsigned)p.cv_h && (unsigned)iw < (unsigned)p.cv_w;
+        const int64_t off = in ? ((int64_t)ih * p.cv_w + iw) * p.cv_c + ch : 0;   // (an image holds 16 bytes or more)
+        const uint4 v = *reinterpret_cast<const uint4*>(L.img + off);
+        regs[0] = in ? v : make_uint4(0u, 0u, 0u, 0u);
+    } else {
+        uint32_t w[4] = {0u, 0u, 0u, 0u};
+        if (L.ok) {
+            for (int j = 0; j < 16; ++j) {                     // (kh, kw, ch) step along with k
+                const int ih = L.ih0 + kh, iw = L.iw0 + kw;
+                if (k + j < p.K && (unsigned)ih < (unsigned)p.cv_h && (unsigned)iw < (unsigned)p.cv_w)
+                    w[j >> 2] |= (uint32_t)L.img[((int64_t)ih * p.cv_w + iw) * p.cv_c + ch] << (8 * (j & 3));
+                if (++ch == p.cv_c) { ch = 0; if (++kw == p.cv_kw) { kw = 0; ++kh; } }
+            }
+        }
+        regs[0] = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+}
+
 // Decode the fetched pieces through the table and store them k-major into one LDS stage.
 template <int ROWS, int BK>
 __device__ __forceinline__ void store_tile(float* __restrict__ dst /* [BK][ROWS] */, const float* __restrict__ lut,
@@ -626,6 +683,8 @@ __device__ __forceinline__ void fast_tile(float (&acc)[TM][TN], float (&top)[TM]
 
 // AMODE 0: A is a row-major matrix of E4M3 codes and so is B (the default; no other case costs it anything).
 // AMODE 1: A may be an activation tensor read as im2col rows and either operand may use another code format.
+// AMODE 2: A is an activation tensor of E4M3 codes read as im2col rows, B a matrix of E4M3 codes: AMODE 0 with
+//          the gather of fetch_tile_conv_lane in place of A's row-major fetch.
 // The work of one workgroup: the (16 TM) x (16 TN) tile of C at (m0, n0); smem holds two stages.
 template <int TM, int TN, int BK, int PM, int RND, int ORDER, int AMODE>
 __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ smem, int m0, int n0) {
@@ -644,7 +703,7 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
 
     const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
     set_flush_f32();
-    if (AMODE) set_denorm_f16();
+    if (AMODE == 1) set_denorm_f16();
     if (RND == LBA_ROUND_FLOOR) set_round_zero();
 
     FastConst c;
@@ -665,7 +724,7 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
     // Formats whose R_OF is within a few maximal products of zero (the planner's flag: the fixed bounds below fail
     // for four tiles at once) also get a bound per tile from the operands actually staged.
     __shared__ float tile_max[2][4];
-    const bool dyn = !AMODE && p.dyn_bound != 0;               // uniform
+    const bool dyn = AMODE != 1 && p.dyn_bound != 0;           // uniform
     auto stage_tiles = [&](float* Ad, int st) {
         if (dyn) {
             float lm = 0.0f;
@@ -673,12 +732,18 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
             store_tile_cvt<BN, BK>(Ad + BK * BMP, sc_b, tidb, rb, 4, 3, 0, &lm);
             publish_tile_max(tile_max[st], lm, tid);
         } else {
-            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
-            store_tile_cvt<BN, BK>(Ad + BK * BMP, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE == 1 ? p.in_ea : 4, p.in_ma, p.exp_a);
+            store_tile_cvt<BN, BK>(Ad + BK * BMP, sc_b, tidb, rb, AMODE == 1 ? p.in_eb : 4, p.in_mb, p.exp_b);
         }
     };
-    if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
-    else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
+    ConvLane cl;
+    if (AMODE == 2) cl = conv_lane<BM, BK>(pA, p, m0, tid);
+    auto fetch_a = [&](int k0) {
+        if (AMODE == 2)      fetch_tile_conv_lane<BM, BK>(cl, p, k0, ra);
+        else if (AMODE == 1) fetch_tile_a<BM, BK>(pA, p, m0, k0, tid, ra);
+        else                 fetch_tile<BM, BK>(pA, p.M, p.K, m0, k0, p.ld_align, tid, ra);
+    };
+    fetch_a(0);
     fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
     stage_tiles(smem, 0);
     __syncthreads();
@@ -688,8 +753,7 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
         const float* Bs = As + BK * BMP;
         const bool more = (t + 1) < ntiles;
         if (more) {
-            if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
-            else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
+            fetch_a((t + 1) * BK);
             fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
         // (Chunked order: the test is on the second-level sums; a first-level sum starts from 0 and
@@ -801,22 +865,34 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
 // per lane, the next mix_half (rows below mix_m_half) 48 x 64 tiles with 3 x 4 per lane, three quarters of the work
 // each, and the rest covers the remaining rows with 32 x 32 tiles (2 x 2 per lane), a quarter of the work each, so
 // that the tail of the launch is cut four times finer.  Workgroups are numbered rows-first in every region.
-template <int BK, int PM, int RND, int ORDER>
-__global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_mixed_kernel(const KParams p) {
-    __shared__ __attribute__((aligned(16))) float smem[2 * BK * 16 * 8];
-    const int b = blockIdx.x;
+// b: the workgroup's number in the launch.
+template <int BK, int PM, int RND, int ORDER, int AMODE>
+__device__ __forceinline__ void fast_mixed_body(const KParams& p, float* smem, const int b) {
     if (b < p.mix_main) {                                      // uniform
         const int by = b / p.mix_gx_main, bx = b - by * p.mix_gx_main;
-        fast_body<4, 4, BK, PM, RND, ORDER, 0>(p, smem, bx * 64, by * 64);
+        fast_body<4, 4, BK, PM, RND, ORDER, AMODE>(p, smem, bx * 64, by * 64);
     } else if (b < p.mix_main + p.mix_half) {
         const int t = b - p.mix_main;
         const int by = t / p.mix_gx_half, bx = t - by * p.mix_gx_half;
-        fast_body<3, 4, BK, PM, RND, ORDER, 0>(p, smem, p.mix_m_main + bx * 48, by * 64);
+        fast_body<3, 4, BK, PM, RND, ORDER, AMODE>(p, smem, p.mix_m_main + bx * 48, by * 64);
     } else {
         const int t = b - p.mix_main - p.mix_half;
         const int by = t / p.mix_gx_tail, bx = t - by * p.mix_gx_tail;
-        fast_body<2, 2, BK, PM, RND, ORDER, 0>(p, smem, p.mix_m_half + bx * 32, by * 32);
+        fast_body<2, 2, BK, PM, RND, ORDER, AMODE>(p, smem, p.mix_m_half + bx * 32, by * 32);
     }
+}
+
+template <int BK, int PM, int RND, int ORDER>
+__global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_mixed_kernel(const KParams p) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * BK * 16 * 8];
+    fast_mixed_body<BK, PM, RND, ORDER, 0>(p, smem, blockIdx.x);
+}
+
+// The same with A read as im2col rows of an NHWC tensor (AMODE 2).
+template <int BK, int PM, int RND, int ORDER>
+__global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_conv_mixed_kernel(const KParams p) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * BK * 16 * 8];
+    fast_mixed_body<BK, PM, RND, ORDER, 2>(p, smem, blockIdx.x);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1192,7 +1268,7 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
     const float sc_a = __builtin_ldexpf(1.0f, p.exp_a), sc_b = __builtin_ldexpf(1.0f, p.exp_b);
     if (UF) set_denorm_out_f32();                              // without an underflow plane: plain flushing, as the forward kernel
     else    set_flush_f32();
-    if (AMODE) set_denorm_f16();
+    if (AMODE == 1) set_denorm_f16();
     if (RND == LBA_ROUND_FLOOR) set_round_zero();
 
     BwdConst c;
@@ -1220,7 +1296,7 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
 
     // (the bound per tile from the operands actually staged: see fast_body)
     __shared__ float tile_max[2][4];
-    const bool dyn = !AMODE && p.dyn_bound != 0;               // uniform
+    const bool dyn = AMODE != 1 && p.dyn_bound != 0;           // uniform
     auto stage_tiles = [&](float* Ad, int st) {
         if (dyn) {
             float lm = 0.0f;
@@ -1228,12 +1304,18 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
             store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, 4, 3, 0, &lm);
             publish_tile_max(tile_max[st], lm, tid);
         } else {
-            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE ? p.in_ea : 4, p.in_ma, p.exp_a);
-            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, AMODE ? p.in_eb : 4, p.in_mb, p.exp_b);
+            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE == 1 ? p.in_ea : 4, p.in_ma, p.exp_a);
+            store_tile_cvt<BN, BK>(Ad + BK * BM, sc_b, tidb, rb, AMODE == 1 ? p.in_eb : 4, p.in_mb, p.exp_b);
         }
     };
-    if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, 0, tid, ra);
-    else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, 0, p.ld_align, tid, ra);
+    ConvLane cl;
+    if (AMODE == 2) cl = conv_lane<BM, BK>(pA, p, m0, tid);
+    auto fetch_a = [&](int k0) {
+        if (AMODE == 2)      fetch_tile_conv_lane<BM, BK>(cl, p, k0, ra);
+        else if (AMODE == 1) fetch_tile_a<BM, BK>(pA, p, m0, k0, tid, ra);
+        else                 fetch_tile<BM, BK>(pA, p.M, p.K, m0, k0, p.ld_align, tid, ra);
+    };
+    fetch_a(0);
     fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
     stage_tiles(smem, 0);
     __syncthreads();
@@ -1243,8 +1325,7 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
         const float* Bs = As + BK * BM;
         const bool more = (t + 1) < ntiles;
         if (more) {
-            if (AMODE) fetch_tile_a<BM, BK>(pA, p, m0, (t + 1) * BK, tid, ra);
-            else       fetch_tile<BM, BK>(pA, p.M, p.K, m0, (t + 1) * BK, p.ld_align, tid, ra);
+            fetch_a((t + 1) * BK);
             fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
         }
         // no sum of this tile can reach R_OF (chunked order: the test is on the second-level sums; a first-level
@@ -1319,18 +1400,29 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
 
 // The sequential order on E4M3 matrices on the mixed grid of lba_fast_mixed_kernel: 64 x 64 workgroups for the
 // full rounds, 32 x 32 ones on the last rows.
-template <int PM, int RND, bool UF>
-__global__ void __launch_bounds__(256, 4) lba_fast_bwd_mixed_kernel(const KParams p) {
-    __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
-    const int b = blockIdx.x;
+template <int PM, int RND, bool UF, int AMODE>
+__device__ __forceinline__ void fast_bwd_mixed_body(const KParams& p, float* smem, const int b) {
     if (b < p.mix_main) {                                      // uniform
         const int by = b / p.mix_gx_main, bx = b - by * p.mix_gx_main;
-        fast_bwd_body<4, 4, PM, RND, LBA_ORDER_SEQ, UF, 0>(p, smem, bx * 64, by * 64);
+        fast_bwd_body<4, 4, PM, RND, LBA_ORDER_SEQ, UF, AMODE>(p, smem, bx * 64, by * 64);
     } else {
         const int t = b - p.mix_main;
         const int by = t / p.mix_gx_tail, bx = t - by * p.mix_gx_tail;
-        fast_bwd_body<2, 2, PM, RND, LBA_ORDER_SEQ, UF, 0>(p, smem, p.mix_m_main + bx * 32, by * 32);
+        fast_bwd_body<2, 2, PM, RND, LBA_ORDER_SEQ, UF, AMODE>(p, smem, p.mix_m_main + bx * 32, by * 32);
     }
+}
+
+template <int PM, int RND, bool UF>
+__global__ void __launch_bounds__(256, 4) lba_fast_bwd_mixed_kernel(const KParams p) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
+    fast_bwd_mixed_body<PM, RND, UF, 0>(p, smem, blockIdx.x);
+}
+
+// The same with A read as im2col rows of an NHWC tensor (AMODE 2).
+template <int PM, int RND, bool UF>
+__global__ void __launch_bounds__(256, 4) lba_fast_bwd_conv_mixed_kernel(const KParams p) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
+    fast_bwd_mixed_body<PM, RND, UF, 2>(p, smem, blockIdx.x);
 }
 
 // Recompute call for the DIFF plane (Sec. 4 "Immediate / DIFF", App. D, eps1 -> 0+) in the scaled domain:

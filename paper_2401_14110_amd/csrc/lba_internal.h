@@ -79,7 +79,8 @@ struct Plan {
     int rne_odd;             // 1: nearest-even through two directed sums and round-to-odd (RND_RNE_ODD; 4 x 4 only)
     int kpar;                // > 0 (chunked order, forward): lba_kpar_kernel; 1: 32 x 32 outputs per workgroup and 4 chunks in flight,
                              // 3: 8 x 16 outputs and 16 chunks
-    int amode;               // 1: A is read as im2col rows and / or an operand is not E4M3 (4 x 4 lane block only)
+    int amode;               // 1: A is read as im2col rows and / or an operand is not E4M3 (4 x 4 lane block only);
+                             // 2: A is read as im2col rows, E4M3 operands, forward call (any lane block, mixed grids)
     KParams kp;
 };
 

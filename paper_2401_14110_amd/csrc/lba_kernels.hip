@@ -20,6 +20,7 @@ static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
     if (pl.kernel == KERNEL_FAST && pl.events == 2) return launch_fast_diff(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.events) return launch_fast_bwd(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.rne_odd) return launch_fast_odd(pl, st);
+    if (pl.kernel == KERNEL_FAST && pl.amode == 2) return launch_fast_conv(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.amode) return launch_fast_amode(pl, st);   // the planner keeps these on 4 x 4
     if (pl.kernel == KERNEL_FAST && pl.mix_tail > 0) return launch_fast_mixed(pl, st);
     if (pl.kernel == KERNEL_FAST) {
@@ -47,15 +48,19 @@ static void plan_kernel_name(const Plan& pl, bool uf, char* buf, size_t n) {
     } else if (pl.events == 2) {
         snprintf(buf, n, pl.mix_tail > 0 ? "lba_fast_diff_mixed_kernel<%d, %d, %d>" : "lba_fast_diff_kernel<%d, %d, %d>", pm, pl.round, ord);
     } else if (pl.events) {
-        if (pl.amode)             snprintf(buf, n, "lba_fast_bwd_kernel<%d, 0, 0, %s, 1>", pm, b);
+        if (pl.amode == 2 && pl.mix_tail > 0) snprintf(buf, n, "lba_fast_bwd_conv_mixed_kernel<%d, 0, %s>", pm, b);
+        else if (pl.amode == 2)   snprintf(buf, n, "lba_fast_bwd_kernel<%d, 0, 0, %s, 2>", pm, b);
+        else if (pl.amode)        snprintf(buf, n, "lba_fast_bwd_kernel<%d, 0, 0, %s, 1>", pm, b);
         else if (pl.mix_tail > 0) snprintf(buf, n, "lba_fast_bwd_mixed_kernel<%d, %d, %s>", pm, pl.round, b);
         else                      snprintf(buf, n, "lba_fast_bwd_kernel<%d, %d, %d, %s, 0>", pm, pl.round, ord, b);
     } else if (pl.rne_odd) {
         snprintf(buf, n, "lba_fast_kernel<4, 4, %d, %d, 3, %d, 0>", pl.bk, pm, ord);
     } else {
         // rounding code of the instantiation: 0 floor, 1 nearest-even by bfe / add3 / and, 2 by the bfloat16 conversion (M = 7)
-        const int rnd = pl.round == LBA_ROUND_FLOOR ? 0 : ((pl.kp.sh_a == 16 && !pl.amode) ? 2 : 1);
-        if (pl.amode)             snprintf(buf, n, "lba_fast_kernel<4, 4, %d, %d, %d, %d, 1>", pl.bk, pm, rnd, ord);
+        const int rnd = pl.round == LBA_ROUND_FLOOR ? 0 : ((pl.kp.sh_a == 16 && pl.amode != 1) ? 2 : 1);
+        if (pl.amode == 2 && pl.mix_tail > 0) snprintf(buf, n, "lba_fast_conv_mixed_kernel<%d, %d, %d, %d>", pl.bk, pm, rnd, ord);
+        else if (pl.amode == 2)   snprintf(buf, n, "lba_fast_kernel<%d, %d, %d, %d, %d, %d, 2>", pl.tm, pl.tn, pl.bk, pm, rnd, ord);
+        else if (pl.amode)        snprintf(buf, n, "lba_fast_kernel<4, 4, %d, %d, %d, %d, 1>", pl.bk, pm, rnd, ord);
         else if (pl.mix_tail > 0) snprintf(buf, n, "lba_fast_mixed_kernel<%d, %d, %d, %d>", pl.bk, pm, rnd, ord);
         else                      snprintf(buf, n, "lba_fast_kernel<%d, %d, %d, %d, %d, %d, 0>", pl.tm, pl.tn, pl.bk, pm, rnd, ord);
     }

@@ -16,12 +16,14 @@ hipError_t launch_fast_24(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_22(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_amode(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_mixed(const Plan& pl, hipStream_t st);   // plans with mix_tail > 0
+hipError_t launch_fast_conv(const Plan& pl, hipStream_t st);    // plans with amode == 2 (any lane block, mixed or not)
 hipError_t launch_fast_odd(const Plan& pl, hipStream_t st);     // plans with rne_odd
 // forward, chunked order, several chunks of an output side by side (plans with kpar > 0)
 hipError_t launch_kpar(const Plan& pl, hipStream_t st);
 // recompute call, scaled-domain kernel (launch_fast_bwd hands nearest-even plans to launch_fast_bwd_rne)
 hipError_t launch_fast_bwd(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_bwd_rne(const Plan& pl, hipStream_t st);
+hipError_t launch_fast_bwd_conv(const Plan& pl, hipStream_t st);   // plans with amode == 2
 // the DIFF plane, scaled-domain kernel (plans with events == 2)
 hipError_t launch_fast_diff(const Plan& pl, hipStream_t st);
 // general kernel (forward and recompute)

@@ -12,6 +12,7 @@ template <int RND>
 static hipError_t launch_fast_bwd_rounding(const Plan& pl, hipStream_t st) {
     const dim3 grid(pl.grid_x, pl.grid_y, pl.kp.batch), block(256);
     const bool uf = pl.kp.uf_mask != nullptr || pl.kp.uf_mask2 != nullptr;
+    if (pl.amode == 2) return hipErrorInvalidValue;        // launch_fast_bwd_conv
     if (pl.amode) {                                        // im2col rows / other operand formats: floor, sequential order only
         if constexpr (RND == LBA_ROUND_FLOOR) {
 #define LBA_BWD1(PM, UF) hipLaunchKernelGGL((lba_fast_bwd_kernel<PM, RND, LBA_ORDER_SEQ, UF, 1>), grid, block, 0, st, pl.kp)

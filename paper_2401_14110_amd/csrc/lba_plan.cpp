@@ -205,7 +205,7 @@ static bool set_mixed_grid(int64_t M, int64_t N, int64_t gx_main, int64_t gx_hal
 
 static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
     p->mix_tail = 0;
-    if (p->kernel != KERNEL_FAST || p->amode || p->rne_odd || batch != 1) return;
+    if (p->kernel != KERNEL_FAST || p->amode == 1 || p->rne_odd || batch != 1) return;
     // the recompute call has the mixed grid under the sequential order, and for the DIFF plane under both
     if (p->events == 1 && p->order != LBA_ORDER_SEQ) return;
     if (p->prod_mode != PM_IDENT && p->prod_mode != PM_FLUSH && p->prod_mode != PM_FLUSH_CLAMP) return;
@@ -371,8 +371,15 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
     }
     p.amode = (conv || in.ea != 4 || in.eb != 4 || p.prod_mode == PM_RNE || p.prod_mode == PM_RNE_CLAMP ||
                (events && (p.prod_mode == PM_TRUNC || p.prod_mode == PM_TRUNC_CLAMP))) ? 1 : 0;
+    // im2col rows of E4M3 codes, products that Q_prod does not round, the forward call or the recompute call for the
+    // event planes under floor rounding and the sequential order: the kernels of the row-major case with the gather
+    // in place of A's fetch, on the same tiles and grids
+    if (conv && fast && batch == 1 && in.ea == 4 && in.eb == 4 &&
+        (p.prod_mode == PM_IDENT || p.prod_mode == PM_FLUSH || p.prod_mode == PM_FLUSH_CLAMP) &&
+        (!events || (p.events == 1 && qa.round == LBA_ROUND_FLOOR && order == LBA_ORDER_SEQ && p.prod_mode != PM_IDENT)))
+        p.amode = 2;
     p.rne_odd = (fast && rne_odd) ? 1 : 0;
-    pick_tile(M, N, batch, p.kernel, p.events, p.prod_mode, p.amode, p.rne_odd, &p.tm, &p.tn, &p.bk);
+    pick_tile(M, N, batch, p.kernel, p.events, p.prod_mode, p.amode == 1, p.rne_odd, &p.tm, &p.tn, &p.bk);
     kp.batch = 1;
     kp.fast_thresh = -1.0f;
     kp.fast_thresh4 = -1.0f;
@@ -402,7 +409,7 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         kp.rof_grow1 = g1f;
         // (floor only: under nearest-even the growth allowance eats most of the margin, and the sweep of 4096^3 formats
         // measured no gain there)
-        kp.dyn_bound = (!p.amode && !p.rne_odd && qa.round == LBA_ROUND_FLOOR && kp.fast_thresh4 <= 0.0f) ? 1 : 0;
+        kp.dyn_bound = (p.amode != 1 && !p.rne_odd && qa.round == LBA_ROUND_FLOOR && kp.fast_thresh4 <= 0.0f) ? 1 : 0;
     }
     const int64_t bm = 16 * p.tm, bn = 16 * p.tn;
     p.grid_x = (int)((M + bm - 1) / bm);

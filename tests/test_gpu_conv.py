@@ -70,6 +70,46 @@ def test_conv2d_against_explicit_im2col(ref, rnd):
         assert np.array_equal(of.cpu().numpy().view(np.uint32), wof) and np.array_equal(uf.cpu().numpy().view(np.uint32), wuf)
 
 
+def test_conv2d_on_every_lane_block_and_on_mixed_grids(ref):
+    # E4M3 tensors take the kernels of the row-major product with the gather in place of A's fetch, on the same
+    # tiles and grids: 2 x 4 and 4 x 4 lane blocks, whole rounds of 48 x 64 workgroups with a 32 x 32 tail, and full
+    # rounds of 64 x 64 followed by a round of 48 x 64 and the tail (the small cases above run the 2 x 2 block)
+    rng = np.random.default_rng(126)
+    seen = set()
+    for (n, h, w, c, cout, kh, kw, stride, pad), want_plan in [
+            ((3, 76, 76, 16, 64, 3, 3, 1, 1), "2x4"), ((8, 64, 64, 16, 64, 1, 1, 1, 0), "4x4"),
+            ((5, 23, 167, 16, 64, 3, 3, 1, 1), "mid"), ((4, 112, 112, 16, 256, 3, 3, 2, 1), "mid"),
+            ((1, 625, 97, 16, 64, 3, 3, 1, 1), "main+mid"), ((1, 360, 383, 3, 60, 3, 3, 2, 1), "tail")]:
+        X = codes(rng, (n, h, w, c), 3, 12); W = codes(rng, (cout, kh, kw, c), 3, 12)
+        A = ref.im2col_nhwc(X, kh, kw, stride, pad)
+        B = W.reshape(cout, kh * kw * c)
+        tX, tW = torch.from_numpy(X).to(DEV), torch.from_numpy(W).to(DEV)
+        for rnd, order in ((0, 0), (1, 0), (0, 1), (1, 1)):
+            qpf, qaf = (5, 7, 15, rnd), (4, 7, 7, rnd)
+            plan = lb.lba_plan_query(A.shape[0], cout, A.shape[1], qpf, qaf, order)
+            main = plan["grid_x"] - plan["mid_blocks"] - plan["tail_blocks"]
+            got = ("%dx%d" % (plan["thread_m"], plan["thread_n"]) if plan["mid_blocks"] + plan["tail_blocks"] == 0
+                   else ("main+mid" if main > 0 and plan["mid_blocks"] > 0 else ("mid" if plan["mid_blocks"] > 0 else "tail")))
+            assert plan["kernel"] == 0 and got == want_plan, (A.shape, cout, plan)
+            seen.add(got)
+            Y = lb.conv2d(tX, tW, qpf, qaf, stride=stride, pad=pad, order=order)
+            torch.cuda.synchronize()
+            want = ref.gemm(A, B, ref.QFmt(*qpf), ref.QFmt(*qaf), order=order)
+            assert np.array_equal(bits(Y.cpu().numpy().reshape(want.shape)), bits(want)), ((n, h, w, c, cout, kh, kw, stride, pad), rnd, order)
+        # the recompute call: 4 x 4 workgroups, with the 32 x 32 tail where the forward call's grid has one
+        qpf, qaf = (5, 7, 15, 0), (4, 7, 7, 0)
+        plan = lb.lba_plan_query(A.shape[0], cout, A.shape[1], qpf, qaf, 0, 1)
+        assert plan["kernel"] == 0 and plan["mid_blocks"] == 0
+        seen.add("planes, tail" if plan["tail_blocks"] > 0 else "planes")
+        Y, of, uf = lb.conv2d(tX, tW, qpf, qaf, stride=stride, pad=pad, planes=True)
+        torch.cuda.synchronize()
+        wc, wof, wuf = ref.gemm_bwd(A, B, ref.QFmt(*qpf), ref.QFmt(*qaf))
+        assert np.array_equal(bits(Y.cpu().numpy().reshape(wc.shape)), bits(wc))
+        assert np.array_equal(of.cpu().numpy().view(np.uint32), wof) and np.array_equal(uf.cpu().numpy().view(np.uint32), wuf)
+        assert wof.any() and wuf.any()
+    assert seen == {"2x4", "4x4", "mid", "main+mid", "tail", "planes", "planes, tail"}
+
+
 def test_conv2d_unaligned_tensor_and_status_codes(ref):
     rng = np.random.default_rng(125)
     n, h, w, c, cout = 2, 10, 10, 32, 40
