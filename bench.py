@@ -504,6 +504,7 @@ SUITE = [
     ("wide", "same, both planes, BERT-base linears", "--in-fmt 3,4 --workload bert --bwd --steps 3 --warmup 1"),
     ("wide", "lba_conv2d from NHWC activations, ResNet-50 sweep", "--implicit"),
     ("wide", "same, ResNet-18 conv", "--implicit --workload conv --steps 20"),
+    ("wide", "lba_conv2d_bwd (Y + 2 planes) from NHWC activations, ResNet-50 sweep", "--implicit --bwd --steps 3 --warmup 1"),
     ("grad", "lba_grad, identity estimator, ResNet-50 sweep (dX and dW)", "--grad identity --steps 3 --warmup 1"),
     ("grad", "lba_grad, recursive estimator", "--grad recursive --steps 3 --warmup 1"),
     ("grad", "lba_grad_ws, immediate estimator (pass over the plane + matrix cores + vector kernel)", "--grad immediate --steps 3 --warmup 1"),

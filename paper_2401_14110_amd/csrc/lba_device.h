@@ -431,14 +431,20 @@ __device__ __forceinline__ void fetch_tile_conv_lane(const ConvLane& L, const KP
         const uint4 v = *reinterpret_cast<const uint4*>(L.img + off);
         regs[0] = in ? v : make_uint4(0u, 0u, 0u, 0u);
     } else {
-        uint32_t w[4] = {0u, 0u, 0u, 0u};
-        if (L.ok) {
-            for (int j = 0; j < 16; ++j) {                     // (kh, kw, ch) step along with k
+        uint32_t w[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {                          // four independent byte loads per word
+            uint32_t b[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {                      // (kh, kw, ch) step along with k
                 const int ih = L.ih0 + kh, iw = L.iw0 + kw;
-                if (k + j < p.K && (unsigned)ih < (unsigned)p.cv_h && (unsigned)iw < (unsigned)p.cv_w)
-                    w[j >> 2] |= (uint32_t)L.img[((int64_t)ih * p.cv_w + iw) * p.cv_c + ch] << (8 * (j & 3));
+                const bool in = L.ok && k + 4 * q + j < p.K && (unsigned)ih < (unsigned)p.cv_h && (unsigned)iw < (unsigned)p.cv_w;
+                const int64_t off = in ? ((int64_t)ih * p.cv_w + iw) * p.cv_c + ch : 0;
+                const uint32_t v = L.img[off];
+                b[j] = in ? v : 0u;
                 if (++ch == p.cv_c) { ch = 0; if (++kw == p.cv_kw) { kw = 0; ++kh; } }
             }
+            w[q] = b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24);
         }
         regs[0] = make_uint4(w[0], w[1], w[2], w[3]);
     }
