@@ -156,3 +156,73 @@ def test_resnet18_conv_at_full_size(ref):
     want = ref.gemm(A, Wt.cpu().numpy(), ref.QFmt(*qp), ref.QFmt(*qa))
     assert np.array_equal(bits(Yh[rows]), bits(want))
     assert np.count_nonzero(want) > want.size // 2
+
+
+def im2col_rows(Xh, rows, desc, oh_ow):
+    """The im2col rows `rows` of the NHWC tensor Xh, written out on the host (k = (i*kw + j)*c + ch, +0 outside)."""
+    n, h, w, c, kh, kw, stride, pad = desc
+    oh_n, ow_n = oh_ow
+    A = np.zeros((len(rows), kh * kw * c), dtype=np.uint8)
+    for t, r in enumerate(rows):
+        img, rem = divmod(r, oh_n * ow_n)
+        oh, ow = divmod(rem, ow_n)
+        for i in range(kh):
+            for j in range(kw):
+                ih, iw = oh * stride - pad + i, ow * stride - pad + j
+                if 0 <= ih < h and 0 <= iw < w:
+                    A[t, (i * kw + j) * c:(i * kw + j + 1) * c] = Xh[img, ih, iw]
+    return A
+
+
+def test_resnet50_convolutions_at_full_size(ref):
+    # every distinct convolution of the benchmark's ResNet-50 sweep from its NHWC tensor, in the launch configuration
+    # bench.py --implicit times: sampled output pixels (first and last rows, the rows around the seams of the mixed
+    # grid's regions, random ones) against the oracle on their written-out im2col rows; for three layers (the stem
+    # with its byte-wise gather, a strided 3 x 3 layer, a layer whose recompute grid is mixed) also the recompute call
+    layers = inputs.make_conv_workload("resnet50", DEV)
+    rng = np.random.default_rng(7)
+    seen, with_planes, hosts = set(), 0, {}
+    for l in layers:
+        key = (l["desc"], l["cout"])
+        if key in seen:
+            continue
+        seen.add(key)
+        n, h, w, c, kh, kw, stride, pad = l["desc"]
+        M, N, K = l["M"], l["N"], l["K"]
+        rc, oh, ow = lb.lba_conv2d_out_shape(l["desc"])
+        assert rc == lb.OK and n * oh * ow == M
+        qp, qa, _ = inputs.folded_formats(l["ta"], l["tb"], (5, 7, 15), (4, 7, 7), 0)
+        plan = lb.lba_plan_query(M, N, K, qp, qa, 0)
+        main_rows = 64 * ((plan["grid_x"] - plan["mid_blocks"] - plan["tail_blocks"]) // max(1, (N + 63) // 64))
+        mid_rows = main_rows + 48 * (plan["mid_blocks"] // max(1, (N + 63) // 64))
+        rows = {0, 1, M - 1, M - 2, ow - 1, ow, oh * ow - 1, oh * ow % M}
+        for seam in (main_rows, mid_rows):
+            rows |= {r for r in range(seam - 2, seam + 3) if 0 <= r < M}
+        rows |= set(int(r) for r in rng.integers(0, M, 24))
+        rows = sorted(rows)
+        xk = id(l["X"])
+        if xk not in hosts:
+            hosts = {xk: l["X"].cpu().numpy()}                   # one tensor on the host at a time
+        A = im2col_rows(hosts[xk], rows, l["desc"], (oh, ow))
+        Bh = l["B"].cpu().numpy()
+        Wt = l["B"].view(N, kh, kw, c)
+        planes = l["name"] in ("conv1", "layer2.0.conv2", "layer3.0.conv2")
+        if planes:
+            Y, of, uf = lb.conv2d(l["X"], Wt, qp, qa, stride=stride, pad=pad, planes=True)
+            torch.cuda.synchronize()
+            wc, wof, wuf = ref.gemm_bwd(A, Bh, ref.QFmt(*qp), ref.QFmt(*qa))
+            idx = torch.tensor(rows, device=DEV)
+            assert np.array_equal(of[:, idx, :].cpu().numpy().view(np.uint32), wof), l["name"]
+            assert np.array_equal(uf[:, idx, :].cpu().numpy().view(np.uint32), wuf), l["name"]
+            assert wuf.any()
+            with_planes += 1
+            del of, uf
+        else:
+            Y = lb.conv2d(l["X"], Wt, qp, qa, stride=stride, pad=pad)
+            torch.cuda.synchronize()
+            wc = ref.gemm(A, Bh, ref.QFmt(*qp), ref.QFmt(*qa))
+        got = Y.view(M, N)[torch.tensor(rows, device=DEV)].cpu().numpy()
+        assert np.array_equal(bits(got), bits(wc)), (l["name"], l["desc"])
+        assert np.count_nonzero(wc) > wc.size // 4, l["name"]
+        del Y
+    assert len(seen) >= 20 and with_planes == 3
