@@ -85,12 +85,13 @@ __device__ __forceinline__ void decode4(uint32_t w, float (&v)[4]) {
 
 // S_CONTIG: G(r, s) = G[r * ld + s] (dX); else G(r, s) = G[s * ld + r] (dW).  MASKED: L (same layout as G)
 // holds last-overflow indices and g' = [L < k0] g.
-template <bool S_CONTIG, bool MASKED, int DTK>
+template <bool S_CONTIG, bool MASKED, int DTK, bool BYTES = false>
 __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __restrict__ G, const uint8_t* __restrict__ V,
                                                                 const int32_t* __restrict__ L,
                                                                 float* __restrict__ out, const DenseDims d,
                                                                 const uint8_t* __restrict__ bricks) {
     constexpr int DNBJ = DTK / 64;                             // MFMA column blocks per wave (two waves side by side)
+    static_assert(!BYTES || DTK == 128, "unaligned rows of codes: the narrow tile only");
     __shared__ __attribute__((aligned(16))) uint16_t sA[3][DTR * DPITCH];
     __shared__ __attribute__((aligned(16))) uint16_t sB[DTK * DPITCH];
 
@@ -112,6 +113,7 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
     int4 ll[MASKED ? 4 : 1];                                   // last-overflow indices of the G patch: compared when the
                                                                // patch is staged, so that the loads stay in flight meanwhile
     uint32_t vl[DTK / 128][4];
+    uint32_t vh[BYTES ? 4 : 1] = {};                           // unaligned rows of codes: the second aligned word of a group
     auto fetch = [&](int sb) {
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -137,12 +139,15 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
                 uint32_t w = 0u;                               // four codes along k; code 0 (the value +0) beyond K
                 if (sv < s_end && kv < d.K) {
                     const uint8_t* __restrict__ src = V + (int64_t)sv * d.K + kv;
-                    if (d.v_vec) {                             // rows of codes are 4-byte aligned and K % 4 == 0
+                    if (!BYTES) {                              // rows of codes are 4-byte aligned and K % 4 == 0
                         w = *reinterpret_cast<const uint32_t*>(src);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (kv + e < d.K) w |= (uint32_t)src[e] << (8 * e);
+                    } else {                                   // the two aligned words that hold the group's valid bytes, put
+                        const int nvalid = (d.K - kv) < 4 ? (d.K - kv) : 4;   // together when the patch is staged: the loads stay in flight
+                        const uint32_t lo = (uint32_t)(reinterpret_cast<uintptr_t>(src) & 3u);   // (pointers derived from V stay
+                        const uint8_t* __restrict__ p0 = src - lo;                              // global-memory pointers)
+                        const uint8_t* __restrict__ p1 = p0 + ((lo + (uint32_t)nvalid - 1u) & ~3u);   // the same word or the next
+                        w = *reinterpret_cast<const uint32_t*>(p0);
+                        vh[BYTES ? q : 0] = *reinterpret_cast<const uint32_t*>(p1);
                     }
                 }
                 vl[h][q] = w;
@@ -192,6 +197,16 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
                 *reinterpret_cast<uint2*>(&sA[0][off]) = make_uint2(pack_hi(h[0], h[1]), pack_hi(h[2], h[3]));
                 *reinterpret_cast<uint2*>(&sA[1][off]) = make_uint2(pack_hi(m[0], m[1]), pack_hi(m[2], m[3]));
                 *reinterpret_cast<uint2*>(&sA[2][off]) = make_uint2(pack_hi(l[0], l[1]), pack_hi(l[2], l[3]));
+            }
+            if (BYTES) {                                       // shift the groups' bytes out of their two words
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int sv = sb + 4 * b_ps + b, kv = k0 + 4 * b_pk;
+                    const uint32_t sh = (uint32_t)((reinterpret_cast<uintptr_t>(V) + (uintptr_t)((int64_t)sv * d.K + kv)) & 3u) * 8u;
+                    const uint32_t w = __builtin_amdgcn_alignbit(vh[BYTES ? b : 0], vl[0][b], sh);   // ({second, first} >> shift)[31:0]
+                    const int left = d.K - kv;
+                    vl[0][b] = (sv < s_end && left > 0) ? (left < 4 ? (w & ((1u << (8 * left)) - 1u)) : w) : 0u;
+                }
             }
 #pragma unroll
             for (int h = 0; h < DTK / 128; ++h) {
@@ -323,8 +338,8 @@ __global__ void lba_grad_dense_zero_kernel(float* x, int64_t n) {
 }
 
 // Can the matrix-core path take this product?  16-byte rows of G (and of last_of) in both directions; with last_of
-// also a row of K sums within 48 KB of LDS.  (Codes are read in 4-byte groups when their rows are aligned, byte by
-// byte otherwise.)
+// also a row of K sums within 48 KB of LDS.  (Codes are read in 4-byte groups: one load when their rows are aligned,
+// else the two aligned words around the group.)
 bool grad_dense_ok(const float* G, const uint8_t* V, const int32_t* last_of, int64_t M, int64_t N, int64_t K) {
     (void)V;
     if (((uintptr_t)G % 16) != 0 || (N % 4) != 0 || (K + 127) / 128 > 65535)
@@ -344,7 +359,9 @@ int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* las
     d.b_chunk = d.S;
     d.v_vec = (((uintptr_t)V % 4) == 0 && (K % 4) == 0) ? 1 : 0;
     const int64_t gx = (d.R + DTR - 1) / DTR;
-    const bool wide = gx * ((K + 255) / 256) >= 512;           // 128 x 256 tiles still give two workgroups per CU
+    // 128 x 256 tiles where they still give two workgroups per CU (K <= 128 would leave half of such a tile empty;
+    // rows of codes that are not 4-byte aligned are read by the narrow kernel only)
+    const bool wide = K > 128 && d.v_vec && gx * ((K + 255) / 256) >= 512;
     const int dtk = wide ? 256 : 128;
     d.k_shift = wide ? 8 : 7;
     const int64_t gy = (K + dtk - 1) / dtk;
@@ -362,8 +379,9 @@ int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* las
         if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
     }
     const dim3 grid((unsigned)gx, (unsigned)gy, (unsigned)split);
-#define LBA_DENSE(SC, MK) do { if (wide) hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 256>), grid, dim3(256), 0, st, G, V, last_of, out, d, bricks); \
-                               else      hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 128>), grid, dim3(256), 0, st, G, V, last_of, out, d, bricks); } while (0)
+#define LBA_DENSE(SC, MK) do { if (wide)          hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 256>), grid, dim3(256), 0, st, G, V, last_of, out, d, bricks); \
+                               else if (d.v_vec) hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 128>), grid, dim3(256), 0, st, G, V, last_of, out, d, bricks); \
+                               else              hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 128, true>), grid, dim3(256), 0, st, G, V, last_of, out, d, bricks); } while (0)
     if (!last_of) {
         if (dx) LBA_DENSE(true, false); else LBA_DENSE(false, false);
         return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;

@@ -117,7 +117,7 @@ def test_immediate_estimator_with_the_diff_plane(ref, gref):
 
 
 def test_matrix_core_path_identity_and_recursive(ref, gref):
-    # Shapes the dense (matrix-core) path takes (N % 4 == 0; K odd: rows of codes read byte by byte): ragged against its 128 x 128 tiles and
+    # Shapes the dense (matrix-core) path takes (N % 4 == 0; K odd: groups of codes read out of two aligned words): ragged against its 128 x 128 tiles and
     # 32-deep steps, several k blocks, sums split over workgroups.  The recursive estimator gets last-overflow
     # indices written by hand: every position relative to the 128-blocks (first and last k of a block, K - 1,
     # none), so that the masked dense part and the sliver pass must meet exactly.  Bit-exact on data whose
@@ -152,6 +152,20 @@ def test_matrix_core_path_identity_and_recursive(ref, gref):
                     aX, aW = gref.grad_abs(G, A, B, None, None, ste, c=cc)
                     assert (np.abs(dX - wX) <= 2 * (N + 1) * 2.0 ** -24 * aX + 1e-30).all(), (M, N, K, ste, "dX")
                     assert (np.abs(dW - wW) <= 2 * (M + 1) * 2.0 ** -24 * aW + 1e-30).all(), (M, N, K, ste, "dW")
+    # code matrices that start 1, 2 and 3 bytes off a 4-byte boundary (rows then start anywhere, also with K % 4 == 0):
+    # the groups of four codes come out of the two aligned words around them; the last group of the last row ends
+    # with the buffer
+    for off, (M, N, K) in ((1, (140, 36, 260)), (2, (70, 132, 147)), (3, (300, 8, 129))):
+        A = codes(rng, (M, K), 5, 10); B = codes(rng, (N, K), 5, 10)
+        bufA = torch.zeros(M * K + off, dtype=torch.uint8, device=DEV); bufA[off:] = torch.from_numpy(A).to(DEV).reshape(-1)
+        bufB = torch.zeros(N * K + off, dtype=torch.uint8, device=DEV); bufB[off:] = torch.from_numpy(B).to(DEV).reshape(-1)
+        tA, tB = bufA[off:].view(M, K), bufB[off:].view(N, K)
+        assert tA.data_ptr() % 4 == off and tB.data_ptr() % 4 == off
+        G = (rng.integers(-8, 9, (M, N)) / 4.0).astype(np.float32)
+        dX, dW = lb.grad(torch.from_numpy(G).to(DEV), tA, tB, lb.STE_IDENTITY)
+        torch.cuda.synchronize()
+        wX, wW = gref.grad(G, A, B, None, None, lb.STE_IDENTITY, c=np.ones((M, N, K), dtype=bool))
+        assert np.array_equal(dX.cpu().numpy(), wX.astype(np.float32)) and np.array_equal(dW.cpu().numpy(), wW.astype(np.float32)), (off, M, N, K)
     # the split of an FP32 factor into three bfloat16 pieces is exact (as long as the pieces and the products stay
     # FP32 normals): one term per sum, so the product itself must come back
     g = np.array([[1.0 + 2.0 ** -23, -3.1415927, 2.0 ** -80 * 1.6180339, 2.0 ** -60 * (1 + 2.0 ** -12)],
