@@ -111,6 +111,8 @@ def make_parser():
                          "indices are computed before the timed region) instead of lba_gemm; 2 MACs per forward MAC; "
                          "premapped: the immediate estimator through lba_grad_premapped, with the brick maps left by "
                          "lba_gemm_bwd_ws before the timed region")
+    ap.add_argument("--ws", action="store_true",
+                    help="with --grad identity / recursive: time lba_grad_ws with a workspace of lba_grad_workspace_bytes_fast bytes (split sums combined there)")
     ap.add_argument("--maps", action="store_true", help="with --bwd: time lba_gemm_bwd_ws (also leaves the brick maps) instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-threads", type=int, default=0, help="threads of the oracle leg (default: min(16, cores))")
@@ -216,15 +218,17 @@ def run(args):
             if ste == 2:
                 l["last"] = lb.last_overflow(l["of"], l["K"])
                 l["of"] = None
-        wsbuf = torch.empty(max(256, max(lb.lba_grad_workspace_bytes(l["M"], l["N"], l["K"]) for l in layers)), dtype=torch.uint8, device=dev)
+        wsbuf = torch.empty(max(256, max(lb.lba_grad_workspace_bytes_fast(l["M"], l["N"], l["K"]) for l in layers)), dtype=torch.uint8, device=dev)
         torch.cuda.synchronize()
 
         def launch(l):
             if premapped:
                 rc = lb.lba_grad_premapped(Gbuf.data_ptr(), l["A"].data_ptr(), l["B"].data_ptr(), l["of"].data_ptr(),
                                            dXbuf.data_ptr(), dWbuf.data_ptr(), l["M"], l["N"], l["K"], l["ws"].data_ptr(), l["ws"].numel(), stream)
-            elif ste == 1:
-                rc = lb.lba_grad_ws(Gbuf.data_ptr(), l["A"].data_ptr(), l["B"].data_ptr(), l["of"].data_ptr(), None,
+            elif ste == 1 or args.ws:
+                rc = lb.lba_grad_ws(Gbuf.data_ptr(), l["A"].data_ptr(), l["B"].data_ptr(),
+                                    l["of"].data_ptr() if l["of"] is not None else None,
+                                    l["last"].data_ptr() if l["last"] is not None else None,
                                     dXbuf.data_ptr(), dWbuf.data_ptr(), l["M"], l["N"], l["K"], ste, wsbuf.data_ptr(), wsbuf.numel(), stream)
             else:
                 rc = lb.lba_grad(Gbuf.data_ptr(), l["A"].data_ptr(), l["B"].data_ptr(),
@@ -365,7 +369,7 @@ def run(args):
     workload_key = "%s:%s:%s:%s:acc=%d,%d" % (
         args.workload, ("grad-" + args.grad) if args.grad else ("diff" if args.diff is not None else ("bwd-of" if args.of_only else "bwd")) if args.bwd else "fwd",
         args.round, args.order, acc_fmt[0], acc_fmt[1]) + (":in=%d,%d" % in_fmt if in_fmt else "") + (":implicit" if args.implicit else "") + (
-        ":paper-biases" if args.paper_biases else "") + (":maps" if args.maps else "")
+        ":paper-biases" if args.paper_biases else "") + (":maps" if args.maps else "") + (":ws" if args.ws else "")
     rec = counter_record(workload_key, dom_name)
     probe_rate = None
     if rec and rec.get("probe_mix"):
@@ -448,7 +452,7 @@ def run(args):
                                 "config1": "single GEMM M=N=64, K=256, operands scaled to max|x|=448"}.get(
                                     args.workload, "single GEMM %s, ReLU activations, He weights" % args.workload),
                    "macs_per_step": total_macs, "qprod": "M%dE%d b=%d" % (prod_fmt[1], prod_fmt[0], prod_fmt[2]), "qacc": "M%dE%d b=%d" % (acc_fmt[1], acc_fmt[0], acc_fmt[2]) + (" (12-bit)" if acc_fmt == ACC_FMT else ""),
-                   "call": ("%s, %s estimator: dX and dW (2 masked MACs per forward MAC)" % ({"immediate": "lba_grad_ws", "premapped": "lba_grad_premapped"}.get(args.grad, "lba_grad"), "immediate" if args.grad == "premapped" else args.grad)) if args.grad else ("lba_gemm_bwd_diff (C + DIFF plane, eps2 = %g)" % args.diff) if args.diff is not None else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else (("lba_gemm_bwd_ws" if args.maps else ("lba_conv2d_bwd" if args.implicit else "lba_gemm_bwd")) + (" (C + OF plane)" if args.of_only else " (C + OF and UF planes)"))) if args.bwd else ("lba_conv2d" if args.implicit else "lba_gemm"), "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
+                   "call": ("%s, %s estimator: dX and dW (2 masked MACs per forward MAC)" % ({"immediate": "lba_grad_ws", "premapped": "lba_grad_premapped"}.get(args.grad, "lba_grad_ws" if args.ws else "lba_grad"), "immediate" if args.grad == "premapped" else args.grad)) if args.grad else ("lba_gemm_bwd_diff (C + DIFF plane, eps2 = %g)" % args.diff) if args.diff is not None else ("lba_gemm_bwd_chunked (C + four planes)" if order == 1 else (("lba_gemm_bwd_ws" if args.maps else ("lba_conv2d_bwd" if args.implicit else "lba_gemm_bwd")) + (" (C + OF plane)" if args.of_only else " (C + OF and UF planes)"))) if args.bwd else ("lba_conv2d" if args.implicit else "lba_gemm"), "round": args.round, "order": "sequential" if order == 0 else "chunks of 16", "scale": "per-tensor power of two, folded into b",
                    "conv": "implicit im2col from NHWC activations (lba_conv2d)" if args.implicit else "operand A is the written-out im2col matrix",
                    "operands": ("E%dM%d codes with per-tensor flex bias (lba_gemm_in)" % in_fmt) if in_fmt else "E4M3"},
         "roofline": roofline,
@@ -507,6 +511,8 @@ SUITE = [
     ("wide", "lba_conv2d_bwd (Y + 2 planes) from NHWC activations, ResNet-50 sweep", "--implicit --bwd --steps 3 --warmup 1"),
     ("grad", "lba_grad, identity estimator, ResNet-50 sweep (dX and dW)", "--grad identity --steps 3 --warmup 1"),
     ("grad", "lba_grad, recursive estimator", "--grad recursive --steps 3 --warmup 1"),
+    ("grad", "lba_grad_ws, identity estimator (split sums combined in the workspace)", "--grad identity --ws --steps 3 --warmup 1"),
+    ("grad", "lba_grad_ws, recursive estimator", "--grad recursive --ws --steps 3 --warmup 1"),
     ("grad", "lba_grad_ws, immediate estimator (pass over the plane + matrix cores + vector kernel)", "--grad immediate --steps 3 --warmup 1"),
     ("grad", "lba_grad, identity estimator, 4096^3", "--workload gemm4096 --grad identity --steps 3 --warmup 1"),
     ("grad", "lba_grad, recursive estimator, 4096^3", "--workload gemm4096 --grad recursive --steps 3 --warmup 1"),

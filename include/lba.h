@@ -265,10 +265,16 @@ int lba_grad(const float* G, const uint8_t* A, const uint8_t* B,
  * 128 rows x 32 summed indices x 256 k: one pass over the plane marks, in the workspace, the bricks that hold a
  * blocked coefficient; all other bricks are dense products and run on the matrix cores, the marked ones in the
  * kernel that applies the plane bit by bit.  Where the accumulator format fits the data (few or no overflows)
- * this is close to the cost of the identity estimator plus one read of the plane.  Other estimators ignore the
- * workspace.  workspace: device memory owned by the caller, 256-byte aligned (else LBA_ERR_ALIGN), at least
+ * this is close to the cost of the identity estimator plus one read of the plane.
+ * workspace: device memory owned by the caller, 256-byte aligned (else LBA_ERR_ALIGN), at least
  * lba_grad_workspace_bytes(M, N, K) bytes (else LBA_ERR_SHAPE), NULL is LBA_ERR_NULL; its contents on return are
- * unspecified, and calls that share a workspace must not overlap. */
+ * unspecified, and calls that share a workspace must not overlap.  What a workspace holds beyond that size is
+ * scratch memory for every estimator that runs on the matrix cores (identity, recursive, the clean bricks of the
+ * immediate one): where a sum over m or n is cut across workgroups, its slices are stored there and added up in a
+ * fixed order instead of meeting in atomic adds (faster; with the identity estimator no atomic add is left and every
+ * run gives the same bits); from
+ * lba_grad_workspace_bytes_fast(M, N, K) bytes on every such sum of the call fits.  A smaller workspace is not an
+ * error: sums whose slices do not fit take the atomic adds. */
 int lba_grad_ws(const float* G, const uint8_t* A, const uint8_t* B,
                 const uint32_t* of_mask, const int32_t* last_of,
                 float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste,
@@ -285,21 +291,23 @@ int lba_grad_ws(const float* G, const uint8_t* A, const uint8_t* B,
  * lba_grad_premapped is lba_grad_ws with ste = LBA_STE_IMMEDIATE_OF for exactly that plane and that workspace,
  * both unchanged since lba_gemm_bwd_ws wrote them (same shape; any stream order that makes the recompute call
  * complete first): it skips the pass over the plane.  A workspace that does not describe the plane gives wrong
- * gradients without an error.  Results (FP32 sums, order unspecified) and errors as lba_grad_ws. */
+ * gradients without an error.  The maps are read only; what the workspace holds beyond them is used as lba_grad_ws
+ * uses it (slices of split sums).  Results (FP32 sums, order unspecified) and errors as lba_grad_ws. */
 int lba_gemm_bwd_ws(const uint8_t* A, const uint8_t* B, float* C,
                     uint32_t* of_mask, uint32_t* uf_mask,
                     int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qfmt qacc,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 int lba_grad_premapped(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask,
                        float* dX, float* dW, int64_t M, int64_t N, int64_t K,
-                       const void* workspace, size_t workspace_bytes, void* hip_stream);
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* lba_grad_ws for callers that cannot allocate device memory (code under HIP graph capture, serving loops,
  * harnesses that forbid hipMalloc): the brick maps live in 1 MiB of device memory that belongs to the library
  * itself (one copy per GPU, held until the process ends), so the call takes no workspace and allocates nothing.
  * Shapes whose maps would not fit, lba_grad_workspace_bytes(M, N, K) > 2^20 (about M * N * K > 5 * 10^11), are
  * refused with LBA_ERR_SHAPE: use lba_grad_ws.  Results and every other error as lba_grad_ws.  All calls on one GPU
- * share that memory (it is cleared by each call that uses it): calls of lba_grad_static that overlap on one GPU,
+ * share that memory (its maps are cleared by each call that uses them; what they leave of the 1 MiB serves as
+ * lba_grad_ws's scratch memory for split sums that fit): calls of lba_grad_static that overlap on one GPU,
  * from several streams or threads, race; calls on one stream, or otherwise ordered, are fine.  The first call on
  * a device looks the memory's address up (no allocation, but a runtime query): make it before a stream capture
  * starts. */
@@ -310,6 +318,12 @@ int lba_grad_static(const float* G, const uint8_t* A, const uint8_t* B,
 /* Bytes of workspace lba_grad_ws needs for a shape (two brick maps: about M * N * K / 2^19 bytes; 0 for an empty
  * or invalid shape). */
 size_t lba_grad_workspace_bytes(int64_t M, int64_t N, int64_t K);
+
+/* Bytes of workspace from which lba_grad_ws / lba_grad_premapped combine every split sum of a call through the
+ * workspace instead of atomic adds (see lba_grad_ws): lba_grad_workspace_bytes plus the slices of the larger of the
+ * two products, a multiple of 256; equal to lba_grad_workspace_bytes where no sum is split; 0 for an empty or
+ * invalid shape.  (ResNet-50 at batch 64: at most 60 MB for a layer.) */
+size_t lba_grad_workspace_bytes_fast(int64_t M, int64_t N, int64_t K);
 
 /* Static, human-readable text for a status code (never NULL). */
 const char* lba_strerror(int code);

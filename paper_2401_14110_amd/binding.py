@@ -104,6 +104,8 @@ def lib(path=None):
         L.lba_grad_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, i64, i64, i64, i32, vp]
         L.lba_grad_workspace_bytes.restype = ctypes.c_size_t
         L.lba_grad_workspace_bytes.argtypes = [i64, i64, i64]
+        L.lba_grad_workspace_bytes_fast.restype = ctypes.c_size_t
+        L.lba_grad_workspace_bytes_fast.argtypes = [i64, i64, i64]
         L.lba_mask_words.restype = ctypes.c_size_t
         L.lba_mask_words.argtypes = [i64, i64, i64]
         L.lba_strerror.restype = ctypes.c_char_p
@@ -246,6 +248,10 @@ def lba_grad_workspace_bytes(M, N, K):
     return int(lib().lba_grad_workspace_bytes(M, N, K))
 
 
+def lba_grad_workspace_bytes_fast(M, N, K):
+    return int(lib().lba_grad_workspace_bytes_fast(M, N, K))
+
+
 def lba_mask_words(M, N, K):
     return int(lib().lba_mask_words(M, N, K))
 
@@ -338,14 +344,15 @@ def _workspace(workspace):
 
 def gemm_bwd_ws(A, B, qprod, qacc, workspace=None, want_c=True, stream=None, want_uf=True):
     """lba_gemm_bwd_ws: as gemm_bwd (sequential order), and `workspace` (allocated here if None: a uint8 device tensor
-    of lba_grad_workspace_bytes(M, N, K) bytes) receives the brick maps of the OF plane for grad_premapped.
+    of lba_grad_workspace_bytes_fast(M, N, K) bytes: the maps, and behind them the scratch memory in which
+    grad_premapped combines its split sums) receives the brick maps of the OF plane for grad_premapped.
     Returns (C or None, OF plane, UF plane or None, workspace)."""
     A, B = _ops(A, B)
     M, K = A.shape
     N = B.shape[0]
     W = (K + 31) // 32
     if workspace is None:
-        workspace = torch.empty(max(256, lba_grad_workspace_bytes(M, N, K)), dtype=torch.uint8, device=A.device)
+        workspace = torch.empty(max(256, lba_grad_workspace_bytes_fast(M, N, K)), dtype=torch.uint8, device=A.device)
     workspace = _workspace(workspace)
     C = torch.empty((M, N), dtype=torch.float32, device=A.device) if want_c else None
     of = torch.empty((W, M, N), dtype=torch.int32, device=A.device)

@@ -34,7 +34,9 @@ namespace lba {
 // lba_grad_mfma.hip: the identity estimator as a dense contraction on the matrix cores
 bool grad_dense_ok(const float* G, const uint8_t* V, const int32_t* last_of, int64_t M, int64_t N, int64_t K);
 int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* last_of, float* out,
-                   int64_t M, int64_t N, int64_t K, hipStream_t st, const uint8_t* bricks = nullptr);
+                   int64_t M, int64_t N, int64_t K, hipStream_t st, const uint8_t* bricks = nullptr,
+                   float* partials = nullptr, size_t partial_bytes = 0);
+size_t grad_dense_partial_bytes(int64_t M, int64_t N, int64_t K);
 
 // Sizes of one launch; the pointers are separate kernel arguments so that they can be declared
 // non-aliasing, which is what lets the compiler fetch the wave-uniform values with scalar loads.
@@ -611,17 +613,19 @@ static hipError_t launch_grad(int ste, const float* G, const uint8_t* V, const u
 
 // One of the two products.  Splits s over grid z when the (r, k) grid alone would leave the chip idle.
 // bricks: this side's brick map (immediate estimator / coefficient plane with a workspace), or NULL
+// partials / partial_bytes: scratch memory in which the matrix-core path keeps the slices of a split sum, or NULL / 0
 static int run_grad_side(bool dx, const float* G, const uint8_t* V, const uint32_t* plane, const int32_t* last_of,
-                         float* out, int64_t M, int64_t N, int64_t K, int ste, hipStream_t st, const uint8_t* bricks = nullptr) {
+                         float* out, int64_t M, int64_t N, int64_t K, int ste, hipStream_t st, const uint8_t* bricks = nullptr,
+                         float* partials = nullptr, size_t partial_bytes = 0) {
     // coefficients that are constant inside a k tile: the matrix-core path (identity; recursive, with a sliver pass)
     if (ste == LBA_STE_IDENTITY && grad_dense_ok(G, V, nullptr, M, N, K))
-        return run_grad_dense(dx, G, V, nullptr, out, M, N, K, st);
+        return run_grad_dense(dx, G, V, nullptr, out, M, N, K, st, nullptr, partials, partial_bytes);
     if (ste == LBA_STE_RECURSIVE_OF && grad_dense_ok(G, V, last_of, M, N, K))
-        return run_grad_dense(dx, G, V, last_of, out, M, N, K, st);
+        return run_grad_dense(dx, G, V, last_of, out, M, N, K, st, nullptr, partials, partial_bytes);
     if (bricks) {
         // the bricks whose coefficients are all 1 on the matrix cores (the output is overwritten, or zeroed and
         // added to); the vector kernel below then adds the other bricks
-        const int rc = run_grad_dense(dx, G, V, nullptr, out, M, N, K, st, bricks);
+        const int rc = run_grad_dense(dx, G, V, nullptr, out, M, N, K, st, bricks, partials, partial_bytes);
         if (rc != LBA_OK) return rc;
     }
     GradDims gp;
@@ -746,13 +750,19 @@ size_t lba_grad_workspace_bytes(int64_t M, int64_t N, int64_t K) {
     return a + b;
 }
 
+size_t lba_grad_workspace_bytes_fast(int64_t M, int64_t N, int64_t K) {
+    const size_t maps = lba_grad_workspace_bytes(M, N, K);
+    if (maps == 0) return 0;
+    return maps + (lba::grad_dense_partial_bytes(M, N, K) + 255) / 256 * 256;
+}
+
 static int grad_impl(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
-                     float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* workspace, void* hip_stream,
-                     bool maps_ready = false);
+                     float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* workspace, size_t workspace_bytes,
+                     void* hip_stream, bool maps_ready = false);
 
 int lba_grad(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
              float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* hip_stream) {
-    return grad_impl(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, nullptr, hip_stream);
+    return grad_impl(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, nullptr, 0, hip_stream);
 }
 
 int lba_grad_ws(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
@@ -765,7 +775,7 @@ int lba_grad_ws(const float* G, const uint8_t* A, const uint8_t* B, const uint32
         if (((uintptr_t)workspace % 256) != 0) return LBA_ERR_ALIGN;
         if (workspace_bytes < lba_grad_workspace_bytes(M, N, K)) return LBA_ERR_SHAPE;
     }
-    return grad_impl(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, workspace, hip_stream);
+    return grad_impl(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, workspace, workspace_bytes, hip_stream);
 }
 
 // The brick maps of lba_grad_static: device memory that belongs to the library (every GPU the library runs on holds
@@ -791,7 +801,7 @@ static int static_scratch(void** out) {
 
 int lba_grad_premapped(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask,
                        float* dX, float* dW, int64_t M, int64_t N, int64_t K,
-                       const void* workspace, size_t workspace_bytes, void* hip_stream) {
+                       void* workspace, size_t workspace_bytes, void* hip_stream) {
     const int rc = lba::validate_shapes(M, N, K);
     if (rc != LBA_OK) return rc;
     if (M > 0 && N > 0 && K > 0 && M * N <= ((int64_t)1 << 30)) {
@@ -799,7 +809,7 @@ int lba_grad_premapped(const float* G, const uint8_t* A, const uint8_t* B, const
         if (((uintptr_t)workspace % 256) != 0) return LBA_ERR_ALIGN;
         if (workspace_bytes < lba_grad_workspace_bytes(M, N, K)) return LBA_ERR_SHAPE;
     }
-    return grad_impl(G, A, B, of_mask, nullptr, dX, dW, M, N, K, LBA_STE_IMMEDIATE_OF, const_cast<void*>(workspace), hip_stream, true);
+    return grad_impl(G, A, B, of_mask, nullptr, dX, dW, M, N, K, LBA_STE_IMMEDIATE_OF, workspace, workspace_bytes, hip_stream, true);
 }
 
 int lba_grad_static(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
@@ -811,12 +821,12 @@ int lba_grad_static(const float* G, const uint8_t* A, const uint8_t* B, const ui
     void* ws = nullptr;
     const int rs = static_scratch(&ws);
     if (rs != LBA_OK) return rs;
-    return grad_impl(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, ws, hip_stream);
+    return grad_impl(G, A, B, of_mask, last_of, dX, dW, M, N, K, ste, ws, (size_t)LBA_GRAD_STATIC_BYTES, hip_stream);
 }
 
 static int grad_impl(const float* G, const uint8_t* A, const uint8_t* B, const uint32_t* of_mask, const int32_t* last_of,
-                     float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* workspace, void* hip_stream,
-                     bool maps_ready) {
+                     float* dX, float* dW, int64_t M, int64_t N, int64_t K, int32_t ste, void* workspace, size_t workspace_bytes,
+                     void* hip_stream, bool maps_ready) {
     int rc = lba::validate_shapes(M, N, K);
     if (rc != LBA_OK) return rc;
     if (ste != LBA_STE_IDENTITY && ste != LBA_STE_IMMEDIATE_OF && ste != LBA_STE_RECURSIVE_OF &&
@@ -858,12 +868,21 @@ static int grad_impl(const float* G, const uint8_t* A, const uint8_t* B, const u
         bricks_dx = map_dx;
         bricks_dw = map_dw;
     }
+    // What lies behind the maps in the workspace holds the slices of a sum over s that the matrix-core kernel cuts
+    // across workgroups (first of dX, then, after dX's slices have been added up, of dW).
+    float* partials = nullptr;
+    size_t partial_bytes = 0;
+    const size_t maps_bytes = lba_grad_workspace_bytes(M, N, K);
+    if (workspace && workspace_bytes > maps_bytes) {
+        partials = (float*)((uint8_t*)workspace + maps_bytes);  // 256-byte aligned: the maps are padded
+        partial_bytes = workspace_bytes - maps_bytes;
+    }
     if (dX) {
-        rc = lba::run_grad_side(true, G, B, of_mask, last_of, dX, M, N, K, ste, st, bricks_dx);
+        rc = lba::run_grad_side(true, G, B, of_mask, last_of, dX, M, N, K, ste, st, bricks_dx, partials, partial_bytes);
         if (rc != LBA_OK) return rc;
     }
     if (dW) {
-        rc = lba::run_grad_side(false, G, A, of_mask, last_of, dW, M, N, K, ste, st, bricks_dw);
+        rc = lba::run_grad_side(false, G, A, of_mask, last_of, dW, M, N, K, ste, st, bricks_dw, partials, partial_bytes);
         if (rc != LBA_OK) return rc;
     }
     return LBA_OK;

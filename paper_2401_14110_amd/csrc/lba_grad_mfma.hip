@@ -40,7 +40,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 struct DenseDims {
     int32_t R, S, K;
     int32_t s_chunk;           // s values per grid z (a multiple of 32)
-    int32_t atomic;            // 1: gridDim.z > 1, combine with atomic adds into a zeroed output
+    int32_t atomic;            // 1: gridDim.z > 1, combine with atomic adds into a zeroed output; 2: gridDim.z > 1, slice z
+                               // is stored whole at out + z * R * K (a workspace; lba_grad_combine_kernel adds the slices)
     int32_t ld_g;              // N: G[m * N + n]
     int32_t b_chunk;           // sliver pass: s values per grid y (a multiple of 256)
     int32_t k_shift;           // log2 of the k tile of the dense pass (the sliver pass cuts k into the same blocks)
@@ -100,6 +101,7 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
     const int r0 = blockIdx.x * DTR, k0 = blockIdx.y * DTK;
     const int s_begin = blockIdx.z * d.s_chunk;
     const int s_end = min(d.S, s_begin + d.s_chunk);
+    if (d.atomic == 2) out += (int64_t)blockIdx.z * d.R * d.K;     // this slice's own copy of the output (a workspace)
 
     // this lane's 4 x 4 patch of the G tile and of the V tile
     // Consecutive lanes take consecutive s: the eight lanes of a row write 64 contiguous bytes of LDS and the next
@@ -252,8 +254,8 @@ __global__ void __launch_bounds__(256, 2) lba_grad_dense_kernel(const float* __r
                 const int row = r0 + wy * 64 + bi * 32 + 8 * (t >> 2) + 4 * (lane >> 5) + (t & 3);
                 if (row < d.R && col < d.K) {
                     float* dst = out + (int64_t)row * d.K + col;
-                    if (d.atomic) unsafeAtomicAdd(dst, acc[bi][bj][t]);
-                    else          *dst = acc[bi][bj][t];
+                    if (d.atomic == 1) unsafeAtomicAdd(dst, acc[bi][bj][t]);
+                    else               *dst = acc[bi][bj][t];
                 }
             }
         }
@@ -332,6 +334,39 @@ __global__ void __launch_bounds__(256) lba_grad_boundary_kernel(const float* __r
     }
 }
 
+// out[i] = sum over the slices z of part[z * n + i], added in the order of z (the slices of a sum over s that was
+// cut across workgroups, stored whole in a workspace: no atomic adds).  VEC: n % 4 == 0 and out 16-byte aligned
+// (the slices are: the workspace is 256-byte aligned): four outputs per lane with 16-byte accesses.
+template <bool VEC>
+__global__ void __launch_bounds__(256) lba_grad_combine_kernel(const float* __restrict__ part, float* __restrict__ out, int64_t n, int slices) {
+    const int64_t step = (int64_t)gridDim.x * blockDim.x;
+    if (VEC) {
+        const int64_t n4 = n >> 2;
+        const float4* __restrict__ p4 = reinterpret_cast<const float4*>(part);
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += step) {
+            float4 a = p4[i];
+            for (int z0 = 1; z0 < slices; z0 += 8) {           // eight loads in flight, then the additions in the order of z
+                float4 v[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const int z = z0 + j < slices ? z0 + j : slices - 1;   // (beyond the last slice: read it again, unused)
+                    v[j] = p4[(int64_t)z * n4 + i];
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (z0 + j < slices) { a.x += v[j].x; a.y += v[j].y; a.z += v[j].z; a.w += v[j].w; }
+            }
+            reinterpret_cast<float4*>(out)[i] = a;
+        }
+    } else {
+        for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += step) {
+            float acc = part[i];
+            for (int z = 1; z < slices; ++z) acc += part[(int64_t)z * n + i];
+            out[i] = acc;
+        }
+    }
+}
+
 __global__ void lba_grad_dense_zero_kernel(float* x, int64_t n) {
     const int64_t step = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += step) x[i] = 0.0f;
@@ -348,47 +383,87 @@ bool grad_dense_ok(const float* G, const uint8_t* V, const int32_t* last_of, int
     return true;
 }
 
+// Tile width, grid and slices of s of one of the two products (v_vec: rows of codes are 4-byte aligned).
+struct DenseShape { int64_t gx, gy, split; bool wide; };
+static DenseShape dense_shape(bool dx, int64_t M, int64_t N, int64_t K, bool v_vec, DenseDims* d) {
+    DenseShape h;
+    d->R = (int32_t)(dx ? M : N); d->S = (int32_t)(dx ? N : M); d->K = (int32_t)K; d->ld_g = (int32_t)N;
+    h.gx = (d->R + DTR - 1) / DTR;
+    // 128 x 256 tiles where they still give two workgroups per CU (K <= 128 would leave half of such a tile empty;
+    // rows of codes that are not 4-byte aligned are read by the narrow kernel only)
+    h.wide = K > 128 && v_vec && h.gx * ((K + 255) / 256) >= 512;
+    const int dtk = h.wide ? 256 : 128;
+    d->k_shift = h.wide ? 8 : 7;
+    h.gy = (K + dtk - 1) / dtk;
+    // enough workgroups for two per CU: cut s into slices of a multiple of 32
+    int64_t split = 1;
+    const int64_t steps = (d->S + DBS - 1) / DBS;
+    while (h.gx * h.gy * split < 512 && split * 2 <= steps && split < 512) split *= 2;
+    const int64_t per = (steps + split - 1) / split;
+    d->s_chunk = (int32_t)(per * DBS);
+    h.split = (d->S + d->s_chunk - 1) / d->s_chunk;
+    return h;
+}
+
+// Bytes of workspace with which both products of a call combine their slices without atomic adds (the larger of the
+// two needs, whatever the alignment of the code matrices); 0 if neither product is cut into slices.
+size_t grad_dense_partial_bytes(int64_t M, int64_t N, int64_t K) {
+    size_t need = 0;
+    for (int dx = 0; dx < 2; ++dx)
+        for (int vec = 0; vec < 2; ++vec) {
+            DenseDims d;
+            const DenseShape h = dense_shape(dx != 0, M, N, K, vec != 0, &d);
+            if (h.split > 1) {
+                const size_t b = (size_t)h.split * (size_t)d.R * (size_t)K * sizeof(float);
+                if (b > need) need = b;
+            }
+        }
+    return need;
+}
+
 // One of the two products with the identity coefficients (last_of == NULL) or the recursive ones.
+// partials / partial_bytes: 256-byte aligned scratch memory for the slices of a split sum, or NULL / 0 (atomic adds).
 // LBA_OK or LBA_ERR_LAUNCH.
 int run_grad_dense(bool dx, const float* G, const uint8_t* V, const int32_t* last_of, float* out,
-                   int64_t M, int64_t N, int64_t K, hipStream_t st, const uint8_t* bricks) {
+                   int64_t M, int64_t N, int64_t K, hipStream_t st, const uint8_t* bricks,
+                   float* partials, size_t partial_bytes) {
     DenseDims d;
     d.brick_rb = (int32_t)(((dx ? M : N) + 127) / 128);
     d.brick_sb = (int32_t)(((dx ? N : M) + 31) / 32);
-    d.R = (int32_t)(dx ? M : N); d.S = (int32_t)(dx ? N : M); d.K = (int32_t)K; d.ld_g = (int32_t)N;
-    d.b_chunk = d.S;
     d.v_vec = (((uintptr_t)V % 4) == 0 && (K % 4) == 0) ? 1 : 0;
-    const int64_t gx = (d.R + DTR - 1) / DTR;
-    // 128 x 256 tiles where they still give two workgroups per CU (K <= 128 would leave half of such a tile empty;
-    // rows of codes that are not 4-byte aligned are read by the narrow kernel only)
-    const bool wide = K > 128 && d.v_vec && gx * ((K + 255) / 256) >= 512;
-    const int dtk = wide ? 256 : 128;
-    d.k_shift = wide ? 8 : 7;
-    const int64_t gy = (K + dtk - 1) / dtk;
-    // enough workgroups for two per CU: cut s into slices of a multiple of 32
-    int64_t split = 1;
-    const int64_t steps = (d.S + DBS - 1) / DBS;
-    while (gx * gy * split < 512 && split * 2 <= steps && split < 512) split *= 2;
-    const int64_t per = (steps + split - 1) / split;
-    d.s_chunk = (int32_t)(per * DBS);
-    split = (d.S + d.s_chunk - 1) / d.s_chunk;
+    const DenseShape h = dense_shape(dx, M, N, K, d.v_vec != 0, &d);
+    d.b_chunk = d.S;
+    const int64_t gx = h.gx, gy = h.gy, split = h.split;
+    const bool wide = h.wide;
+    const int64_t n_out = (int64_t)d.R * K;
     d.atomic = split > 1 ? 1 : 0;
-    if (d.atomic) {
-        const int64_t n = (int64_t)d.R * K;
+    float* target = out;
+    if (d.atomic && partials && (size_t)split * (size_t)n_out * sizeof(float) <= partial_bytes) {
+        d.atomic = 2;
+        target = partials;
+    }
+    if (d.atomic == 1) {
+        const int64_t n = n_out;
         hipLaunchKernelGGL(lba_grad_dense_zero_kernel, dim3((unsigned)((n + 255) / 256 < (1 << 20) ? (n + 255) / 256 : (1 << 20))), dim3(256), 0, st, out, n);
         if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
     }
     const dim3 grid((unsigned)gx, (unsigned)gy, (unsigned)split);
-#define LBA_DENSE(SC, MK) do { if (wide)          hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 256>), grid, dim3(256), 0, st, G, V, last_of, out, d, bricks); \
-                               else if (d.v_vec) hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 128>), grid, dim3(256), 0, st, G, V, last_of, out, d, bricks); \
-                               else              hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 128, true>), grid, dim3(256), 0, st, G, V, last_of, out, d, bricks); } while (0)
-    if (!last_of) {
-        if (dx) LBA_DENSE(true, false); else LBA_DENSE(false, false);
-        return hipGetLastError() == hipSuccess ? LBA_OK : LBA_ERR_LAUNCH;
-    }
-    if (dx) LBA_DENSE(true, true); else LBA_DENSE(false, true);
+#define LBA_DENSE(SC, MK) do { if (wide)          hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 256>), grid, dim3(256), 0, st, G, V, last_of, target, d, bricks); \
+                               else if (d.v_vec) hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 128>), grid, dim3(256), 0, st, G, V, last_of, target, d, bricks); \
+                               else              hipLaunchKernelGGL((lba_grad_dense_kernel<SC, MK, 128, true>), grid, dim3(256), 0, st, G, V, last_of, target, d, bricks); } while (0)
+    if (!last_of) { if (dx) LBA_DENSE(true, false); else LBA_DENSE(false, false); }
+    else          { if (dx) LBA_DENSE(true, true);  else LBA_DENSE(false, true); }
 #undef LBA_DENSE
     if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
+    if (d.atomic == 2) {                                       // the slices, added in order, become the output
+        const bool vec = (n_out % 4) == 0 && ((uintptr_t)out % 16) == 0;
+        const int64_t blocks = ((vec ? n_out / 4 : n_out) + 255) / 256;
+        const dim3 cgrid((unsigned)(blocks < (1 << 20) ? blocks : (1 << 20)));
+        if (vec) hipLaunchKernelGGL(lba_grad_combine_kernel<true>, cgrid, dim3(256), 0, st, partials, out, n_out, (int)split);
+        else     hipLaunchKernelGGL(lba_grad_combine_kernel<false>, cgrid, dim3(256), 0, st, partials, out, n_out, (int)split);
+        if (hipGetLastError() != hipSuccess) return LBA_ERR_LAUNCH;
+    }
+    if (!last_of) return LBA_OK;
     // the sliver pass: one workgroup per group of rows, and with few groups also slices of s, to have about 2048
     // workgroups
     const size_t lds = (size_t)K * sizeof(float);

@@ -256,3 +256,21 @@ def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     assert q(64, 64, 64, (4, 12, 7, 1), (4, 9, 7, 1))["valu_per_mac_x100"] == base + 400   # 13 + 9 bits: an inexact sum could reach one
     with pytest.raises(lb.LbaError):
         q(64, 64, 64, (5, 7, 15, 0), (4, 7, 7, 0), order=2)
+
+
+def test_workspace_sizes_of_the_gradient_calls():
+    # host arithmetic only: the size from which split sums are combined in the workspace is the maps plus whole
+    # slices, a multiple of 256, never below the minimum, equal to it where no sum is split, 0 where the minimum is 0
+    for M, N, K in [(300, 200, 600), (3000, 24, 300), (40, 2100, 72), (1500, 64, 147), (50176, 512, 128), (802816, 64, 147),
+                    (64, 1000, 2048), (130, 68, 260), (32, 28, 260), (4096, 4096, 4096), (1, 4, 1)]:
+        small, fast = lb.lba_grad_workspace_bytes(M, N, K), lb.lba_grad_workspace_bytes_fast(M, N, K)
+        assert small > 0 and fast >= small and fast % 256 == 0, (M, N, K, small, fast)
+        extra = fast - small
+        # slices of one product: a whole number (2 or more) of outputs-sized blocks of floats, rounded up to 256 bytes
+        blocks = [extra // (4 * r * K) for r in (M, N) if extra >= 8 * r * K and (extra - 255 <= (extra // (4 * r * K)) * 4 * r * K <= extra)]
+        assert extra == 0 or blocks, (M, N, K, extra)
+    assert lb.lba_grad_workspace_bytes_fast(4096, 4096, 4096) == lb.lba_grad_workspace_bytes(4096, 4096, 4096)
+    assert lb.lba_grad_workspace_bytes_fast(32, 28, 260) == lb.lba_grad_workspace_bytes(32, 28, 260)     # one step of s either way
+    assert lb.lba_grad_workspace_bytes_fast(50176, 512, 128) - lb.lba_grad_workspace_bytes(50176, 512, 128) == 2 * 50176 * 128 * 4
+    for bad in [(0, 8, 8), (8, 0, 8), (8, 8, 0), (-1, 8, 8), (1 << 31, 8, 8), (1 << 20, 1 << 11, 64)]:
+        assert lb.lba_grad_workspace_bytes_fast(*bad) == 0 and lb.lba_grad_workspace_bytes(*bad) == 0

@@ -453,3 +453,47 @@ def test_recompute_call_leaves_the_brick_maps(ref, gref):
             assert (np.abs(dX - wX) <= 2 * (N + 1) * 2.0 ** -24 * aX + 1e-30).all(), (M, N, K, loud, "dX")
             assert (np.abs(dW - wW) <= 2 * (M + 1) * 2.0 ** -24 * aW + 1e-30).all(), (M, N, K, loud, "dW")
     assert {"fused", "fused+mixed", "general", "all-marked", "clean", "dirty", "partly"} <= seen, seen
+
+
+def test_split_sums_combined_in_the_workspace(ref, gref):
+    # lba_grad_ws with lba_grad_workspace_bytes_fast bytes: where the matrix-core kernel cuts a sum over m or n across
+    # workgroups, the slices are stored behind the maps and added in a fixed order instead of meeting in atomic adds.
+    # All three estimators, both products split (few output tiles, long sums), rows of codes aligned and not; bit-exact
+    # against the oracle on exactly representable sums; on general data the FP32 bound, for the identity estimator (no
+    # atomic add left anywhere) the same bits on every call, and a workspace between the two sizes (some slices fit, or none) still gives correct sums.
+    rng = np.random.default_rng(778)
+    QPb, QAb = (4, 7, 12, 0), (4, 7, 10, 0)
+    ptr = lambda t: t.data_ptr() if t is not None else None
+    for (M, N, K) in [(300, 200, 600), (3000, 24, 300), (40, 2100, 72), (1500, 64, 147), (2600, 132, 128), (32, 28, 260)]:
+        small, fast = lb.lba_grad_workspace_bytes(M, N, K), lb.lba_grad_workspace_bytes_fast(M, N, K)
+        assert fast % 256 == 0 and fast >= small
+        assert (fast > small) == ((M, N, K) != (32, 28, 260)), (M, N, K, small, fast)   # the last shape splits nothing
+        A = codes(rng, (M, K), 2, 5); B = codes(rng, (N, K), 2, 5)
+        A[:, K - K // 3:] = codes(rng, (M, K // 3), 6, 10); B[:, K - K // 3:] = codes(rng, (N, K // 3), 6, 10)   # overflows in the last third
+        tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+        _, of, _ = lb.gemm_bwd(tA, tB, QPb, QAb, want_c=False)
+        last = lb.last_overflow(of, K)
+        assert bool((of != 0).any())
+        qp, qa = ref.QFmt(*QPb), ref.QFmt(*QAb)
+        ws = torch.full((fast,), 0x5A, dtype=torch.uint8, device=DEV)
+        for exact in (True, False):
+            G = (rng.integers(-8, 9, (M, N)) / 4.0).astype(np.float32) if exact else rng.standard_normal((M, N)).astype(np.float32)
+            tG = torch.from_numpy(G).to(DEV)
+            for ste, kw in ((lb.STE_IDENTITY, {}), (lb.STE_RECURSIVE_OF, dict(last_of=last)), (lb.STE_IMMEDIATE_OF, dict(of_plane=of))):
+                wX, wW = gref.grad(G, A, B, qp, qa, ste)
+                outs = []
+                for w in (ws, ws[:small + 256 * ((fast - small) // 512)], ws):      # all slices fit; the smaller product's or none; again
+                    dX, dW = lb.grad(tG, tA, tB, ste, workspace=w, **kw)
+                    torch.cuda.synchronize()
+                    outs.append((dX.cpu().numpy(), dW.cpu().numpy()))
+                if ste == lb.STE_IDENTITY:                                  # no atomic add anywhere: the same bits on every call
+                    assert np.array_equal(outs[0][0], outs[2][0]) and np.array_equal(outs[0][1], outs[2][1]), (M, N, K, ste)
+                for dX, dW in outs[:2]:
+                    if exact:
+                        assert np.array_equal(dX, wX.astype(np.float32)) and np.array_equal(dW, wW.astype(np.float32)), (M, N, K, ste)
+                    else:
+                        aX, aW = gref.grad_abs(G, A, B, qp, qa, ste)
+                        assert (np.abs(dX - wX) <= 2 * (N + 1) * 2.0 ** -24 * aX + 1e-30).all(), (M, N, K, ste, "dX")
+                        assert (np.abs(dW - wW) <= 2 * (M + 1) * 2.0 ** -24 * aW + 1e-30).all(), (M, N, K, ste, "dW")
+    assert lb.lba_grad_workspace_bytes_fast(0, 8, 8) == 0 and lb.lba_grad_workspace_bytes_fast(1 << 31, 8, 8) == 0
+    assert lb.lba_grad_workspace_bytes_fast(4096, 4096, 4096) == lb.lba_grad_workspace_bytes(4096, 4096, 4096)
