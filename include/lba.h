@@ -322,7 +322,7 @@ size_t lba_grad_workspace_bytes(int64_t M, int64_t N, int64_t K);
 /* Bytes of workspace from which lba_grad_ws / lba_grad_premapped combine every split sum of a call through the
  * workspace instead of atomic adds (see lba_grad_ws): lba_grad_workspace_bytes plus the slices of the larger of the
  * two products, a multiple of 256; equal to lba_grad_workspace_bytes where no sum is split; 0 for an empty or
- * invalid shape.  (ResNet-50 at batch 64: at most 60 MB for a layer.) */
+ * invalid shape.  (ResNet-50 at batch 64: at most 38 MB for a layer.) */
 size_t lba_grad_workspace_bytes_fast(int64_t M, int64_t N, int64_t K);
 
 /* Static, human-readable text for a status code (never NULL). */
