@@ -1072,7 +1072,10 @@ __global__ void __launch_bounds__(256, (CPW == 4 && TM == 4) ? 3 : 4) lba_kpar_k
 // product's domain, i.e. 2^(c_a - c_p - 126) here (the planner admits c_p - c_a <= 23).
 //   OF_k  <=>  |t| >= R_OF.  Floor: the clamped, truncated sum has magnitude exactly R_OF.  Nearest-even: decided
 //         on a second sum rounded toward zero (a sum just below R_OF may round up to it without being an overflow).
-//   product underflow  <=>  the product reads as zero although both operands are non-zero
+//   product underflow  <=>  the product reads as zero although both operands are non-zero (UF = 1), or, where the
+//         smallest non-zero product is at least 2^-149 here (the planner's test; UF = 2), the product is a denormal
+//         number: it underflowed, was kept by the multiply, and reads as zero from then on.  One class test per step
+//         instead of a compare, two scalar ands and the operands' own tests: the sweep's recompute 57.7 -> 45 ms.
 //   accumulator underflow  <=>  the sum is a denormal number
 // Nearest-even: the sum is rounded once to 24 bits and then to M+1 bits by bit manipulation (the planner admits
 // the formats for which that equals one rounding); a denormal sum is flushed by one multiply by 1 first.
@@ -1107,7 +1110,7 @@ __device__ __forceinline__ float bwd_round(float td, const BwdConst& c, int RND,
 }
 
 // One k-tile with event bits.  QUIET: no sum of the tile can reach R_OF (no clamp, no overflow test).
-template <int TM, int TN, int PM, int RND, int ORDER, bool UF, bool QUIET, int BM, int BN>
+template <int TM, int TN, int PM, int RND, int ORDER, int UF, bool QUIET, int BM, int BN>
 __device__ __forceinline__ void bwd_tile(float (&acc)[TM][TN], float (&top)[TM][TN], uint32_t (&wof)[TM][TN], uint32_t (&wuf)[TM][TN],
                                          uint32_t (&wof2)[TM][TN], uint32_t (&wuf2)[TM][TN], const float* As, const float* Bs,
                                          int tx, int ty, const BwdConst& c) {
@@ -1118,7 +1121,7 @@ __device__ __forceinline__ void bwd_tile(float (&acc)[TM][TN], float (&top)[TM][
         read_operands<TM, TN, BM, BN>(As, Bs, k, tx, ty, a, b);
         // all tests produce 64-bit lane masks; the event logic runs on the scalar unit
         uint64_t nza[TM], nzb[TN];
-        if (UF) {
+        if (UF == 1) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) nza[i] = __builtin_amdgcn_ballot_w64(a[i] != 0.0f);
 #pragma unroll
@@ -1134,6 +1137,13 @@ __device__ __forceinline__ void bwd_tile(float (&acc)[TM][TN], float (&top)[TM][
             for (int i = 0; i < NI; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) q[i][j] = a[i0 + i] * b[j];   // below Q_prod's R_UF: a denormal, read as zero from here on
+            uint64_t qden[NI][TN];                                         // UF == 2: the product itself says that it underflowed
+            if (UF == 2) {
+#pragma unroll
+                for (int i = 0; i < NI; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) qden[i][j] = ballot_denormal(q[i][j], c.cls);
+            }
             if (PM == PM_TRUNC || PM == PM_TRUNC_CLAMP) {                  // Q_prod's mantissa, by truncation
 #pragma unroll
                 for (int i = 0; i < NI; ++i)
@@ -1169,7 +1179,9 @@ __device__ __forceinline__ void bwd_tile(float (&acc)[TM][TN], float (&top)[TM][
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     uint64_t uf = 0;
-                    if (UF) {
+                    if (UF == 2) {
+                        uf = qden[i][j] | ballot_denormal(td[i][j], c.cls);
+                    } else if (UF) {
                         const uint64_t zq = __builtin_amdgcn_ballot_w64(q[i][j] == 0.0f);
                         uf = (zq & nza[i0 + i] & nzb[j]) | ballot_denormal(td[i][j], c.cls);
                     }
@@ -1258,7 +1270,7 @@ __device__ __forceinline__ void mark_bricks(const uint32_t (&wof)[TM][TN], int m
     }
 }
 
-template <int TM, int TN, int PM, int RND, int ORDER, bool UF, int AMODE>
+template <int TM, int TN, int PM, int RND, int ORDER, int UF, int AMODE>
 __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, const int m0, const int n0) {
     constexpr int BK = 32, BM = 16 * TM, BN = 16 * TN;
     constexpr int STAGE = BK * (BM + BN);
@@ -1398,7 +1410,7 @@ __device__ __forceinline__ void fast_bwd_body(const KParams& p, float* smem, con
     }
 }
 
-template <int PM, int RND, int ORDER, bool UF, int AMODE = 0>
+template <int PM, int RND, int ORDER, int UF, int AMODE = 0>
 __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_fast_bwd_kernel(const KParams p) {
     __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
     fast_bwd_body<4, 4, PM, RND, ORDER, UF, AMODE>(p, smem, blockIdx.x * 64, blockIdx.y * 64);
@@ -1406,7 +1418,7 @@ __global__ void __launch_bounds__(256, ORDER == LBA_ORDER_CHUNK16 ? 2 : 4) lba_f
 
 // The sequential order on E4M3 matrices on the mixed grid of lba_fast_mixed_kernel: 64 x 64 workgroups for the
 // full rounds, 32 x 32 ones on the last rows.
-template <int PM, int RND, bool UF, int AMODE>
+template <int PM, int RND, int UF, int AMODE>
 __device__ __forceinline__ void fast_bwd_mixed_body(const KParams& p, float* smem, const int b) {
     if (b < p.mix_main) {                                      // uniform
         const int by = b / p.mix_gx_main, bx = b - by * p.mix_gx_main;
@@ -1418,14 +1430,14 @@ __device__ __forceinline__ void fast_bwd_mixed_body(const KParams& p, float* sme
     }
 }
 
-template <int PM, int RND, bool UF>
+template <int PM, int RND, int UF>
 __global__ void __launch_bounds__(256, 4) lba_fast_bwd_mixed_kernel(const KParams p) {
     __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
     fast_bwd_mixed_body<PM, RND, UF, 0>(p, smem, blockIdx.x);
 }
 
 // The same with A read as im2col rows of an NHWC tensor (AMODE 2).
-template <int PM, int RND, bool UF>
+template <int PM, int RND, int UF>
 __global__ void __launch_bounds__(256, 4) lba_fast_bwd_conv_mixed_kernel(const KParams p) {
     __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
     fast_bwd_mixed_body<PM, RND, UF, 2>(p, smem, blockIdx.x);

@@ -76,6 +76,7 @@ struct Plan {
     int valu_per_mac_x100;
     int mix_tail;            // > 0: mixed grid with that many 32 x 32 workgroups after kp.mix_main 64 x 64 ones
     int of_only;             // 1 (events == 1): only the overflow plane is asked for (no underflow tests)
+    int uf_class;            // 1 (events == 1, underflow plane): an underflowed product is a denormal number (never zero): one class test
     int rne_odd;             // 1: nearest-even through two directed sums and round-to-odd (RND_RNE_ODD; 4 x 4 only)
     int kpar;                // > 0 (chunked order, forward): lba_kpar_kernel; 1: 32 x 32 outputs per workgroup and 4 chunks in flight,
                              // 3: 8 x 16 outputs and 16 chunks

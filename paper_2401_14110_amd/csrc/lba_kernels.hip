@@ -36,7 +36,7 @@ static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
 // that actually ran.  uf: the call asks for an underflow plane.  Mirrors launch_plan and the launchers.
 static void plan_kernel_name(const Plan& pl, bool uf, char* buf, size_t n) {
     const int pm = pl.prod_mode, ord = pl.order;
-    const char* b = uf ? "true" : "false";
+    const char* b = uf ? (pl.uf_class ? "2" : "1") : "0";      // the UF argument of the recompute kernels
     if (pl.kernel == KERNEL_GEN) {
         snprintf(buf, n, "lba_gen_kernel<%d, %s, %d, %s>", pl.round, pl.events == 1 ? "true" : "false", ord,
                  pl.events == 2 ? "true" : "false");

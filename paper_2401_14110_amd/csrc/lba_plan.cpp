@@ -330,6 +330,10 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
         kp.exp_b = c_p - kp.exp_a;
         kp.kc = (float)std::ldexp(1.0, c_a - c_p);
         kp.out_exp = -c_a;
+        // recompute call with an underflow plane: where the smallest non-zero product, 2^(min_lsb + c_p) here, is an FP32
+        // denormal number at worst (not below 2^-149, where the multiply would return zero), a product that underflows
+        // Q_prod is one, and one class test finds it
+        p.uf_class = (p.events == 1 && !p.of_only && flush && in.min_lsb + c_p >= -149) ? 1 : 0;
         fill_quant(qa, c_a, &kp.mask_a, &kp.half_a, &kp.sh_a, &kp.rof_a, &kp.ruf_a);
         fill_quant(qp, c_p, &kp.mask_p, &kp.half_p, &kp.sh_p, &kp.rof_p, &kp.ruf_p);
         // Issue slots per MAC of the clamp-free inner loop, in units of one full-rate VALU op
@@ -346,6 +350,8 @@ int make_plan(int64_t M, int64_t N, int64_t K, const lba_qfmt& qp_in, const lba_
             // test of the sum, carry-in add at half rate; the operand tests (8 per 16 chains); nearest-even adds the
             // flushing multiply, bfe, add3.  (A tile that can overflow adds med3, a compare and a carry-in add: 6.)
             p.valu_per_mac_x100 = 1000 + (qa.round == LBA_ROUND_RNE ? 500 : 0);
+            // an underflowed product found by its class (one half-rate test) instead of its zero test and the operands' tests
+            if (p.uf_class) p.valu_per_mac_x100 -= 100;
             if (p.prod_mode == PM_FLUSH_CLAMP || p.prod_mode == PM_TRUNC_CLAMP) p.valu_per_mac_x100 += 200;
             if (p.prod_mode == PM_TRUNC || p.prod_mode == PM_TRUNC_CLAMP) p.valu_per_mac_x100 += 100;
         }
