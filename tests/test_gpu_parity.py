@@ -495,6 +495,39 @@ def test_event_planes_of_the_chunked_order(ref):
                            (5, 7, 15, 0), (4, 7, 7, 0), order=1) == lb.ERR_UNSUPPORTED
 
 
+def test_product_underflow_at_the_boundary_of_the_class_test(ref):
+    # Where the smallest non-zero product (2^-18: two smallest subnormal codes) is still an FP32 denormal number in the
+    # kernel's product domain, an underflowed product is found by its class; one bias further down it would round to
+    # zero and the kernel tests the operands and the product for zero instead.  Q_prod biases on both sides of that
+    # line (-5 | -6), operands full of subnormal codes and zeros, both orders: C and all planes against the oracle.
+    rng = np.random.default_rng(4243)
+    M, N, K = 70, 40, 150
+    A = rand_codes(rng, (M, K), 0, 3); B = rand_codes(rng, (N, K), 0, 3)
+    A[rng.random((M, K)) < 0.1] = 0x01; B[rng.random((N, K)) < 0.1] = 0x81            # the smallest magnitudes
+    A[rng.random((M, K)) < 0.05] = 0x00; B[rng.random((N, K)) < 0.05] = 0x80           # zeros of both signs
+    A[:, 128:] = rand_codes(rng, (M, K - 128), 6, 12)
+    tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+    slots = set()
+    for bp in (-3, -4, -5, -6, -7, -9):
+        for (Ea, Ma, ba), order in itertools.product([(4, 7, 7), (5, 10, bp - 2)], (0, 1)):
+            qpf, qaf = (5, 7, bp, 0), (Ea, Ma, ba, 0)
+            plan = lb.lba_plan_query(M, N, K, qpf, qaf, order, 1)
+            if plan["kernel"] == 0:
+                slots.add((bp >= -5, (plan["valu_per_mac_x100"] // 100) % 2 == 1))       # 9 slots per MAC with the class test, 10 without
+            if order == 1:
+                got = lb.gemm_bwd_chunked(tA, tB, qpf, qaf)
+                want = ref.gemm_bwd(A, B, fm(ref, qpf), fm(ref, qaf), order=ref.ORDER_CHUNK16, level2=True)
+            else:
+                got = lb.gemm_bwd(tA, tB, qpf, qaf)
+                want = ref.gemm_bwd(A, B, fm(ref, qpf), fm(ref, qaf))
+            torch.cuda.synchronize()
+            assert np.array_equal(bits(got[0].cpu().numpy()), bits(want[0])), (qpf, qaf, order, "C")
+            for i in range(1, len(want)):
+                assert np.array_equal(got[i].cpu().numpy().view(np.uint32), want[i]), (qpf, qaf, order, "plane %d" % i)
+            assert want[2].any()                                                     # products do underflow
+    assert (True, True) in slots and (False, False) in slots and len(slots) == 2, slots   # the planner's line is where the test says
+
+
 def test_random_formats_event_planes(ref):
     # a seeded sweep of the recompute call over formats (both roundings, both orders, with and without the
     # underflow plane) whose ranges lie near the operands' own, so that overflows, product underflows and
