@@ -901,6 +901,13 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_conv_mixed_k
     fast_mixed_body<BK, PM, RND, ORDER, 2>(p, smem, blockIdx.x);
 }
 
+// The same for other operand formats and / or im2col rows whose products Q_prod rounds (AMODE 1).
+template <int BK, int PM, int RND, int ORDER>
+__global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_in_mixed_kernel(const KParams p) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * BK * 16 * 8];
+    fast_mixed_body<BK, PM, RND, ORDER, 1>(p, smem, blockIdx.x);
+}
+
 // ---------------------------------------------------------------------------------------------
 // K-parallel kernel for the chunked order (forward call, launches with too few outputs to fill the chip)
 // ---------------------------------------------------------------------------------------------

@@ -21,7 +21,9 @@ static hipError_t launch_plan(const Plan& pl, hipStream_t st) {
     if (pl.kernel == KERNEL_FAST && pl.events) return launch_fast_bwd(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.rne_odd) return launch_fast_odd(pl, st);
     if (pl.kernel == KERNEL_FAST && pl.amode == 2) return launch_fast_conv(pl, st);
-    if (pl.kernel == KERNEL_FAST && pl.amode) return launch_fast_amode(pl, st);   // the planner keeps these on 4 x 4
+    if (pl.kernel == KERNEL_FAST && pl.amode == 1 && pl.mix_tail > 0)
+        return pl.order == LBA_ORDER_CHUNK16 ? launch_fast_in_mixed_chunk(pl, st) : launch_fast_in_mixed_seq(pl, st);
+    if (pl.kernel == KERNEL_FAST && pl.amode) return launch_fast_amode(pl, st);   // 4 x 4 workgroups on a plain grid
     if (pl.kernel == KERNEL_FAST && pl.mix_tail > 0) return launch_fast_mixed(pl, st);
     if (pl.kernel == KERNEL_FAST) {
         if (pl.tm == 2 && pl.tn == 2) return launch_fast_22(pl, st);
@@ -60,6 +62,7 @@ static void plan_kernel_name(const Plan& pl, bool uf, char* buf, size_t n) {
         const int rnd = pl.round == LBA_ROUND_FLOOR ? 0 : ((pl.kp.sh_a == 16 && pl.amode != 1) ? 2 : 1);
         if (pl.amode == 2 && pl.mix_tail > 0) snprintf(buf, n, "lba_fast_conv_mixed_kernel<%d, %d, %d, %d>", pl.bk, pm, rnd, ord);
         else if (pl.amode == 2)   snprintf(buf, n, "lba_fast_kernel<%d, %d, %d, %d, %d, %d, 2>", pl.tm, pl.tn, pl.bk, pm, rnd, ord);
+        else if (pl.amode && pl.mix_tail > 0) snprintf(buf, n, "lba_fast_in_mixed_kernel<%d, %d, %d, %d>", pl.bk, pm, rnd, ord);
         else if (pl.amode)        snprintf(buf, n, "lba_fast_kernel<4, 4, %d, %d, %d, %d, 1>", pl.bk, pm, rnd, ord);
         else if (pl.mix_tail > 0) snprintf(buf, n, "lba_fast_mixed_kernel<%d, %d, %d, %d>", pl.bk, pm, rnd, ord);
         else                      snprintf(buf, n, "lba_fast_kernel<%d, %d, %d, %d, %d, %d, 0>", pl.tm, pl.tn, pl.bk, pm, rnd, ord);

@@ -17,6 +17,8 @@ hipError_t launch_fast_22(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_amode(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_mixed(const Plan& pl, hipStream_t st);   // plans with mix_tail > 0
 hipError_t launch_fast_conv(const Plan& pl, hipStream_t st);    // plans with amode == 2 (any lane block, mixed or not)
+hipError_t launch_fast_in_mixed_seq(const Plan& pl, hipStream_t st);    // plans with amode == 1 and mix_tail > 0, by order
+hipError_t launch_fast_in_mixed_chunk(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_odd(const Plan& pl, hipStream_t st);     // plans with rne_odd
 // forward, chunked order, several chunks of an output side by side (plans with kpar > 0)
 hipError_t launch_kpar(const Plan& pl, hipStream_t st);

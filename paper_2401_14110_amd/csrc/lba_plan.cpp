@@ -205,11 +205,16 @@ static bool set_mixed_grid(int64_t M, int64_t N, int64_t gx_main, int64_t gx_hal
 
 static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
     p->mix_tail = 0;
-    if (p->kernel != KERNEL_FAST || p->amode == 1 || p->rne_odd || batch != 1) return;
+    if (p->kernel != KERNEL_FAST || p->rne_odd || batch != 1) return;
+    // other operand formats, rounded products: the forward call only (lba_fast_in_mixed_kernel)
+    if (p->amode == 1 && p->events) return;
     // the recompute call has the mixed grid under the sequential order, and for the DIFF plane under both
     if (p->events == 1 && p->order != LBA_ORDER_SEQ) return;
-    if (p->prod_mode != PM_IDENT && p->prod_mode != PM_FLUSH && p->prod_mode != PM_FLUSH_CLAMP) return;
+    if (p->amode != 1 && p->prod_mode != PM_IDENT && p->prod_mode != PM_FLUSH && p->prod_mode != PM_FLUSH_CLAMP) return;
     const int64_t gx = (M + 63) / 64, gy = (N + 63) / 64, blocks = gx * gy;
+    // those kernels have the 4 x 4 lane block alone outside the mixed grid: a grid too small for it (a single wave per
+    // SIMD issues at half rate) becomes 32 x 32 workgroups throughout
+    if (p->amode == 1 && blocks <= 256 && set_mixed_grid(M, N, 0, 0, p)) return;
     if (blocks > 256 * 16) return;
     // Rounds of 48 x 64 workgroups (forward call only; measured on M sweeps at N = 256 and 512, whose rates depend on
     // blocks / 256 alone): a CU that holds three 64 x 64 workgroups, or one, issues well below one that holds four or

@@ -704,6 +704,33 @@ def test_operand_code_formats(ref):
     torch.cuda.synchronize()
 
 
+def test_operand_code_formats_on_mixed_grids(ref):
+    # lba_gemm_in on the grids of the E4M3 product: 64 x 64 workgroups with a 32 x 32 tail, whole rounds of 48 x 64, full
+    # rounds followed by one of 48 x 64, and small grids as 32 x 32 workgroups throughout; the product modes that only
+    # these kernels have (truncated and nearest-even products), both orders, both roundings
+    rng = np.random.default_rng(111)
+    combos = [((3, 4, 3), (3, 4, 3), (5, 7, 15), (4, 7, 7)),        # 10-bit products into an 8-bit Q_prod mantissa
+              ((3, 4, 6), (4, 3, 9), (4, 7, 12), (4, 7, 10)),       # flex bias, mixed with E4M3
+              ((3, 4, 3), (3, 4, 3), (6, 9, 20), (4, 7, 7))]        # Q_prod wide enough: no product rounding
+    kinds = set()
+    for (M, N, K) in [(64 * 420 + 17, 60, 40), (12544, 256, 40), (64 * 947 + 17, 64, 40), (70, 50, 96), (34560, 60, 27)]:
+        A = rng.integers(0, 256, (M, K)).astype(np.uint8); B = rng.integers(0, 256, (N, K)).astype(np.uint8)
+        tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
+        for (fa, fb, qp, qa), rnd, order in itertools.product(combos, (0, 1), (0, 1)):
+            qpf, qaf = qp + (rnd,), qa + (rnd,)
+            plan = lb.lba_plan_query_in(M, N, K, fa, fb, qpf, qaf, order)
+            if plan["kernel"] == 0:
+                main = plan["grid_x"] - plan["mid_blocks"] - plan["tail_blocks"]
+                assert plan["mid_blocks"] + plan["tail_blocks"] > 0, ((M, N, K), plan)
+                kinds.add((main > 0, plan["mid_blocks"] > 0, plan["tail_blocks"] > 0))
+            got = lb.gemm_in(tA, tB, fa, fb, qpf, qaf, order=order)
+            torch.cuda.synchronize()
+            want = ref.gemm_in(A, B, ref.InFmt(*fa), ref.InFmt(*fb), fm(ref, qpf), fm(ref, qaf), order=order)
+            bad = bits(got.cpu().numpy()) != bits(want)
+            assert not bad.any(), ((M, N, K), fa, fb, qpf, qaf, order, int(bad.sum()))
+    assert {(True, False, True), (False, True, True), (True, True, True), (False, False, True)} <= kinds, kinds
+
+
 def test_mixed_grid(ref):
     # launches whose last round of 64 x 64 workgroups would be mostly empty finish their last rows with
     # 32 x 32 workgroups: both regions, their seam and the ragged edges against the oracle
