@@ -838,20 +838,24 @@ __device__ __forceinline__ void store_event_words(uint32_t* of_plane, uint32_t* 
                 o[j] = __builtin_bitreverse32(wof[i][j] << up) & vmask;
                 u[j] = __builtin_bitreverse32(wuf[i][j] << up) & vmask;
             }
+            // written once and not read again by this call: non-temporal stores, so that the plane (one word per 32
+            // MACs, more bytes than A, B and C together) does not push the operand tiles out of L2
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
             if (p.c_vec && n + TN - 1 < p.N) {                 // N % 4 == 0 and aligned planes: 16- or 8-byte stores
                 if (TN == 4) {
-                    if (of_plane) *reinterpret_cast<uint4*>(of_plane + off) = make_uint4(o[0], o[1], o[TN - 2], o[TN - 1]);
-                    if (uf_plane) *reinterpret_cast<uint4*>(uf_plane + off) = make_uint4(u[0], u[1], u[TN - 2], u[TN - 1]);
+                    if (of_plane) __builtin_nontemporal_store(u32x4{o[0], o[1], o[TN - 2], o[TN - 1]}, reinterpret_cast<u32x4*>(of_plane + off));
+                    if (uf_plane) __builtin_nontemporal_store(u32x4{u[0], u[1], u[TN - 2], u[TN - 1]}, reinterpret_cast<u32x4*>(uf_plane + off));
                 } else {
-                    if (of_plane) *reinterpret_cast<uint2*>(of_plane + off) = make_uint2(o[0], o[1]);
-                    if (uf_plane) *reinterpret_cast<uint2*>(uf_plane + off) = make_uint2(u[0], u[1]);
+                    if (of_plane) __builtin_nontemporal_store(u32x2{o[0], o[1]}, reinterpret_cast<u32x2*>(of_plane + off));
+                    if (uf_plane) __builtin_nontemporal_store(u32x2{u[0], u[1]}, reinterpret_cast<u32x2*>(uf_plane + off));
                 }
             } else {
 #pragma unroll
                 for (int j = 0; j < TN; ++j)
                     if (n + j < p.N) {
-                        if (of_plane) of_plane[off + j] = o[j];
-                        if (uf_plane) uf_plane[off + j] = u[j];
+                        if (of_plane) __builtin_nontemporal_store(o[j], of_plane + off + j);
+                        if (uf_plane) __builtin_nontemporal_store(u[j], uf_plane + off + j);
                     }
             }
         }
