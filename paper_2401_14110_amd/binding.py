@@ -484,8 +484,9 @@ def ste_plane(of_plane, K, ste, order=ORDER_SEQ, of_plane2=None, stream=None):
     return out
 
 
-def gemm_in(A, B, fmt_a, fmt_b, qprod, qacc, order=ORDER_SEQ, planes=False, stream=None):
-    """lba_gemm_in (or, with planes, lba_gemm_bwd_in: returns (C, OF, UF)) on uint8 device tensors."""
+def gemm_in(A, B, fmt_a, fmt_b, qprod, qacc, order=ORDER_SEQ, planes=False, stream=None, uf_plane=True):
+    """lba_gemm_in (or, with planes, lba_gemm_bwd_in: returns (C, OF, UF); UF is None without uf_plane) on uint8
+    device tensors."""
     A, B = _ops(A, B)
     M, K = A.shape
     N = B.shape[0]
@@ -496,9 +497,9 @@ def gemm_in(A, B, fmt_a, fmt_b, qprod, qacc, order=ORDER_SEQ, planes=False, stre
         return C
     W = (K + 31) // 32
     of = torch.empty((W, M, N), dtype=torch.int32, device=A.device)
-    uf = torch.empty((W, M, N), dtype=torch.int32, device=A.device)
+    uf = torch.empty((W, M, N), dtype=torch.int32, device=A.device) if uf_plane else None
     _check(lib().lba_gemm_bwd_in(A.data_ptr() or None, B.data_ptr() or None, C.data_ptr() or None,
-                                 of.data_ptr() or None, uf.data_ptr() or None, M, N, K,
+                                 of.data_ptr() or None, (uf.data_ptr() or None) if uf_plane else None, M, N, K,
                                  infmt(fmt_a), infmt(fmt_b), qfmt(qprod), qfmt(qacc), order, _stream(stream)))
     return C, of, uf
 

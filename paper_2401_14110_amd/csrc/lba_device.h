@@ -1454,6 +1454,13 @@ __global__ void __launch_bounds__(256, 4) lba_fast_bwd_conv_mixed_kernel(const K
     fast_bwd_mixed_body<PM, RND, UF, 2>(p, smem, blockIdx.x);
 }
 
+// The same for other operand formats and truncated products (AMODE 1: the operands decoded with their run-time formats).
+template <int PM, int RND, int UF>
+__global__ void __launch_bounds__(256, 4) lba_fast_bwd_in_mixed_kernel(const KParams p) {
+    __shared__ __attribute__((aligned(16))) float smem[2 * 32 * 128];
+    fast_bwd_mixed_body<PM, RND, UF, 1>(p, smem, blockIdx.x);
+}
+
 // Recompute call for the DIFF plane (Sec. 4 "Immediate / DIFF", App. D, eps1 -> 0+) in the scaled domain:
 // floor or (where rounding twice is exact) nearest-even rounding, E4M3 operands, Q_prod without mantissa rounding, flush kept.  Per step:
 //   DIFF = [ |S' - S| <= eps2 * |x w| ],  both sides formed 2^60 above the accumulator's domain, where

@@ -52,6 +52,7 @@ static void plan_kernel_name(const Plan& pl, bool uf, char* buf, size_t n) {
     } else if (pl.events) {
         if (pl.amode == 2 && pl.mix_tail > 0) snprintf(buf, n, "lba_fast_bwd_conv_mixed_kernel<%d, 0, %s>", pm, b);
         else if (pl.amode == 2)   snprintf(buf, n, "lba_fast_bwd_kernel<%d, 0, 0, %s, 2>", pm, b);
+        else if (pl.amode && pl.mix_tail > 0) snprintf(buf, n, "lba_fast_bwd_in_mixed_kernel<%d, 0, %s>", pm, b);
         else if (pl.amode)        snprintf(buf, n, "lba_fast_bwd_kernel<%d, 0, 0, %s, 1>", pm, b);
         else if (pl.mix_tail > 0) snprintf(buf, n, "lba_fast_bwd_mixed_kernel<%d, %d, %s>", pm, pl.round, b);
         else                      snprintf(buf, n, "lba_fast_bwd_kernel<%d, %d, %d, %s, 0>", pm, pl.round, ord, b);

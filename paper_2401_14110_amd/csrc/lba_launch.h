@@ -26,6 +26,7 @@ hipError_t launch_kpar(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_bwd(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_bwd_rne(const Plan& pl, hipStream_t st);
 hipError_t launch_fast_bwd_conv(const Plan& pl, hipStream_t st);   // plans with amode == 2
+hipError_t launch_fast_bwd_in_mixed(const Plan& pl, hipStream_t st);   // plans with amode == 1 on a mixed grid
 // the DIFF plane, scaled-domain kernel (plans with events == 2)
 hipError_t launch_fast_diff(const Plan& pl, hipStream_t st);
 // general kernel (forward and recompute)

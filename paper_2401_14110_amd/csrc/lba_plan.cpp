@@ -206,8 +206,11 @@ static bool set_mixed_grid(int64_t M, int64_t N, int64_t gx_main, int64_t gx_hal
 static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
     p->mix_tail = 0;
     if (p->kernel != KERNEL_FAST || p->rne_odd || batch != 1) return;
-    // other operand formats, rounded products: the forward call only (lba_fast_in_mixed_kernel)
-    if (p->amode == 1 && p->events) return;
+    // other operand formats, rounded products: the forward call (lba_fast_in_mixed_kernel) and the recompute call's OF / UF
+    // planes (lba_fast_bwd_in_mixed_kernel: floor, the product modes that have a scaled recompute kernel)
+    if (p->amode == 1 && (p->events == 2 || (p->events == 1 && p->round != LBA_ROUND_FLOOR))) return;
+    if (p->amode == 1 && p->events == 1 && p->prod_mode != PM_FLUSH && p->prod_mode != PM_FLUSH_CLAMP &&
+        p->prod_mode != PM_TRUNC && p->prod_mode != PM_TRUNC_CLAMP) return;
     // the recompute call has the mixed grid under the sequential order, and for the DIFF plane under both
     if (p->events == 1 && p->order != LBA_ORDER_SEQ) return;
     if (p->amode != 1 && p->prod_mode != PM_IDENT && p->prod_mode != PM_FLUSH && p->prod_mode != PM_FLUSH_CLAMP) return;

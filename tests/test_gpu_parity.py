@@ -707,12 +707,13 @@ def test_operand_code_formats(ref):
 def test_operand_code_formats_on_mixed_grids(ref):
     # lba_gemm_in on the grids of the E4M3 product: 64 x 64 workgroups with a 32 x 32 tail, whole rounds of 48 x 64, full
     # rounds followed by one of 48 x 64, and small grids as 32 x 32 workgroups throughout; the product modes that only
-    # these kernels have (truncated and nearest-even products), both orders, both roundings
+    # these kernels have (truncated and nearest-even products), both orders, both roundings; and lba_gemm_bwd_in on its
+    # mixed grids (floor, sequential order)
     rng = np.random.default_rng(111)
     combos = [((3, 4, 3), (3, 4, 3), (5, 7, 15), (4, 7, 7)),        # 10-bit products into an 8-bit Q_prod mantissa
               ((3, 4, 6), (4, 3, 9), (4, 7, 12), (4, 7, 10)),       # flex bias, mixed with E4M3
               ((3, 4, 3), (3, 4, 3), (6, 9, 20), (4, 7, 7))]        # Q_prod wide enough: no product rounding
-    kinds = set()
+    kinds, bwd_kinds = set(), set()
     for (M, N, K) in [(64 * 420 + 17, 60, 40), (12544, 256, 40), (64 * 947 + 17, 64, 40), (70, 50, 96), (34560, 60, 27)]:
         A = rng.integers(0, 256, (M, K)).astype(np.uint8); B = rng.integers(0, 256, (N, K)).astype(np.uint8)
         tA, tB = torch.from_numpy(A).to(DEV), torch.from_numpy(B).to(DEV)
@@ -728,7 +729,20 @@ def test_operand_code_formats_on_mixed_grids(ref):
             want = ref.gemm_in(A, B, ref.InFmt(*fa), ref.InFmt(*fb), fm(ref, qpf), fm(ref, qaf), order=order)
             bad = bits(got.cpu().numpy()) != bits(want)
             assert not bad.any(), ((M, N, K), fa, fb, qpf, qaf, order, int(bad.sum()))
+            if rnd == 0 and order == 0:                        # the recompute call: 64 x 64 workgroups and the 32 x 32 tail
+                wc, wof, wuf = ref.gemm_in(A, B, ref.InFmt(*fa), ref.InFmt(*fb), fm(ref, qpf), fm(ref, qaf), planes=True)
+                for with_masks in (1, 3):                      # both planes; the OF plane alone (truncated products: this one only)
+                    plan = lb.lba_plan_query_in(M, N, K, fa, fb, qpf, qaf, order, with_masks=with_masks)
+                    if plan["kernel"] == 0 and plan["tail_blocks"] > 0:    # (three full rounds and most of a fourth: plain grid)
+                        assert plan["mid_blocks"] == 0, ((M, N, K), plan)
+                        bwd_kinds.add((with_masks, plan["grid_x"] > plan["tail_blocks"]))
+                    C, of, uf = lb.gemm_in(tA, tB, fa, fb, qpf, qaf, planes=True, uf_plane=with_masks == 1)
+                    torch.cuda.synchronize()
+                    assert np.array_equal(bits(C.cpu().numpy()), bits(wc)), ((M, N, K), fa, fb, qpf, qaf)
+                    assert np.array_equal(of.cpu().numpy().view(np.uint32), wof), ((M, N, K), fa, fb, qpf, qaf)
+                    assert uf is None or np.array_equal(uf.cpu().numpy().view(np.uint32), wuf), ((M, N, K), fa, fb, qpf, qaf)
     assert {(True, False, True), (False, True, True), (True, True, True), (False, False, True)} <= kinds, kinds
+    assert bwd_kinds == {(1, True), (1, False), (3, True), (3, False)}, bwd_kinds
 
 
 def test_mixed_grid(ref):
