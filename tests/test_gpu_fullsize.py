@@ -89,6 +89,49 @@ def test_resnet50_layers_chunked_order(ref, resnet50):
         del C
 
 
+def test_resnet50_layers_m4e3_operands(ref):
+    # lba_gemm_in / lba_gemm_bwd_in as bench.py --in-fmt 3,4 runs them: the paper's M4E3 codes with per-tensor flex
+    # biases, the quantizers' biases in real units; every distinct shape of the sweep (plain and mixed grids, 48 x 64
+    # rounds, truncated and nearest-even products), and the OF plane of the recompute call on three of them
+    layers = inputs.make_workload("resnet50", DEV, in_fmt=(3, 4))
+    seen, mixed, planes_checked = set(), 0, 0
+    for l in layers:
+        key = (l["M"], l["N"], l["K"])
+        if key in seen:
+            continue
+        seen.add(key)
+        fa, fb = (3, 4, l["ta"]), (3, 4, l["tb"])
+        rows = sample_rows(l["M"], 12)
+        idx = torch.from_numpy(rows).to(DEV)
+        A = l["A"].index_select(0, idx).cpu().numpy()
+        B = l["B"].cpu().numpy()
+        for rnd, order in ((0, 0), (1, 0), (0, 1)):
+            qp, qa = PROD + (rnd,), ACC + (rnd,)
+            plan = lb.lba_plan_query_in(l["M"], l["N"], l["K"], fa, fb, qp, qa, order)
+            mixed += plan["kernel"] == 0 and plan["tail_blocks"] + plan["mid_blocks"] > 0
+            C = lb.gemm_in(l["A"], l["B"], fa, fb, qp, qa, order=order)
+            torch.cuda.synchronize()
+            want = ref.gemm_in(A, B, ref.InFmt(*fa), ref.InFmt(*fb), ref.QFmt(*qp), ref.QFmt(*qa), order=order)
+            got = C.index_select(0, idx).cpu().numpy()
+            bad = got.view(np.uint32) != want.view(np.uint32)
+            assert not bad.any(), (key, rnd, order, int(bad.sum()), np.argwhere(bad)[0])
+            if rnd == 0:
+                check_grid_property(C, qa)
+            del C
+        if key in ((12544, 1024, 256), (50176, 128, 512), (3136, 512, 2048)):
+            qp, qa = PROD + (0,), ACC + (0,)
+            plan = lb.lba_plan_query_in(l["M"], l["N"], l["K"], fa, fb, qp, qa, 0, with_masks=3)
+            assert plan["kernel"] == 0, plan
+            C, of, _ = lb.gemm_in(l["A"], l["B"], fa, fb, qp, qa, planes=True, uf_plane=False)
+            torch.cuda.synchronize()
+            wc, wof, _ = ref.gemm_in(A, B, ref.InFmt(*fa), ref.InFmt(*fb), ref.QFmt(*qp), ref.QFmt(*qa), planes=True)
+            assert np.array_equal(C.index_select(0, idx).cpu().numpy().view(np.uint32), wc.view(np.uint32)), key
+            assert np.array_equal(of.index_select(1, idx).cpu().numpy().view(np.uint32), wof), key
+            planes_checked += 1
+            del C, of
+    assert len(seen) == 21 and planes_checked == 3 and mixed >= 30, (len(seen), planes_checked, mixed)
+
+
 def test_resnet18_conv_config(ref):
     (l,) = inputs.make_workload("conv", DEV)
     assert (l["M"], l["N"], l["K"]) == (100352, 64, 576)
