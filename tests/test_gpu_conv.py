@@ -75,7 +75,7 @@ def test_conv2d_on_every_lane_block_and_on_mixed_grids(ref):
     # tiles and grids: 2 x 4 and 4 x 4 lane blocks, whole rounds of 48 x 64 workgroups with a 32 x 32 tail, and full
     # rounds of 64 x 64 followed by a round of 48 x 64 and the tail (the small cases above run the 2 x 2 block)
     rng = np.random.default_rng(126)
-    seen = set()
+    seen, rounded = set(), set()
     for (n, h, w, c, cout, kh, kw, stride, pad), want_plan in [
             ((3, 76, 76, 16, 64, 3, 3, 1, 1), "2x4"), ((8, 64, 64, 16, 64, 1, 1, 1, 0), "4x4"),
             ((5, 23, 167, 16, 64, 3, 3, 1, 1), "mid"), ((4, 112, 112, 16, 256, 3, 3, 2, 1), "mid"),
@@ -96,6 +96,17 @@ def test_conv2d_on_every_lane_block_and_on_mixed_grids(ref):
             torch.cuda.synchronize()
             want = ref.gemm(A, B, ref.QFmt(*qpf), ref.QFmt(*qaf), order=order)
             assert np.array_equal(bits(Y.cpu().numpy().reshape(want.shape)), bits(want)), ((n, h, w, c, cout, kh, kw, stride, pad), rnd, order)
+        # a Q_prod that rounds the products (5 mantissa bits): the kernels for other operand formats, which gather
+        # by themselves, on their mixed grids
+        for rnd in (0, 1):
+            qpf, qaf = (5, 4, 15, rnd), (4, 7, 7, rnd)
+            plan = lb.lba_plan_query(A.shape[0], cout, A.shape[1], qpf, qaf, 0)
+            assert plan["kernel"] == 0
+            rounded.add((plan["grid_x"] - plan["mid_blocks"] - plan["tail_blocks"] > 0, plan["mid_blocks"] > 0, plan["tail_blocks"] > 0))
+            Y = lb.conv2d(tX, tW, qpf, qaf, stride=stride, pad=pad)
+            torch.cuda.synchronize()
+            want = ref.gemm(A, B, ref.QFmt(*qpf), ref.QFmt(*qaf))
+            assert np.array_equal(bits(Y.cpu().numpy().reshape(want.shape)), bits(want)), ((n, h, w, c, cout, kh, kw, stride, pad), qpf)
         # the recompute call: 4 x 4 workgroups, with the 32 x 32 tail where the forward call's grid has one
         qpf, qaf = (5, 7, 15, 0), (4, 7, 7, 0)
         plan = lb.lba_plan_query(A.shape[0], cout, A.shape[1], qpf, qaf, 0, 1)
@@ -108,6 +119,7 @@ def test_conv2d_on_every_lane_block_and_on_mixed_grids(ref):
         assert np.array_equal(of.cpu().numpy().view(np.uint32), wof) and np.array_equal(uf.cpu().numpy().view(np.uint32), wuf)
         assert wof.any() and wuf.any()
     assert seen == {"2x4", "4x4", "mid", "main+mid", "tail", "planes", "planes, tail"}
+    assert {(False, True, True), (True, True, True), (True, False, True)} <= rounded, rounded
 
 
 def test_conv2d_unaligned_tensor_and_status_codes(ref):
