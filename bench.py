@@ -172,7 +172,8 @@ def run(args):
         if in_fmt:                                          # biases stay in real units: the library folds the flex biases
             l["qp"], l["qa"] = prod_fmt + (rnd,), acc_fmt + (rnd,)
             l["fa"], l["fb"] = in_fmt + (l["ta"],), in_fmt + (l["tb"],)
-            l["plan"] = lb.lba_plan_query_in(l["M"], l["N"], l["K"], l["fa"], l["fb"], l["qp"], l["qa"], order, 1 if args.bwd else 0)
+            l["plan"] = lb.lba_plan_query_in(l["M"], l["N"], l["K"], l["fa"], l["fb"], l["qp"], l["qa"], order, with_masks)
+            l["kname"] = lb.lba_plan_kernel_name_in(l["M"], l["N"], l["K"], l["fa"], l["fb"], l["qp"], l["qa"], order, with_masks)
             if args.bwd and args.of_only:
                 fwd = lb.lba_plan_query_in(l["M"], l["N"], l["K"], l["fa"], l["fb"], l["qp"], l["qa"], order, 0)
                 l["plan"] = dict(l["plan"], valu_per_mac_x100=fwd["valu_per_mac_x100"])

@@ -367,6 +367,10 @@ int lba_plan_kernel_name(int64_t M, int64_t N, int64_t K, lba_qfmt qprod, lba_qf
 int lba_plan_query_in(int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,
                       lba_qfmt qprod, lba_qfmt qacc, int32_t order, int32_t with_masks, lba_plan_info* out);
 
+/* lba_plan_kernel_name for the operand formats of lba_gemm_in / lba_gemm_bwd_in. */
+int lba_plan_kernel_name_in(int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,
+                            lba_qfmt qprod, lba_qfmt qacc, int32_t order, int32_t with_masks, char* buf, size_t buf_len);
+
 #ifdef __cplusplus
 }
 #endif

@@ -110,6 +110,9 @@ def lib(path=None):
         L.lba_mask_words.argtypes = [i64, i64, i64]
         L.lba_strerror.restype = ctypes.c_char_p
         L.lba_strerror.argtypes = [ctypes.c_int]
+        L.lba_plan_kernel_name_in.restype = ctypes.c_int
+        L.lba_plan_kernel_name_in.argtypes = [i64, i64, i64, lba_infmt, lba_infmt, lba_qfmt, lba_qfmt, i32, i32, ctypes.c_char_p,
+                                              ctypes.c_size_t]
         L.lba_plan_kernel_name.restype = ctypes.c_int
         L.lba_plan_kernel_name.argtypes = [i64, i64, i64, lba_qfmt, lba_qfmt, i32, i32, ctypes.c_char_p, ctypes.c_size_t]
         L.lba_plan_query.restype = ctypes.c_int
@@ -276,6 +279,13 @@ def lba_plan_query(M, N, K, qprod, qacc, order=ORDER_SEQ, with_masks=0):
 def lba_plan_kernel_name(M, N, K, qprod, qacc, order=ORDER_SEQ, with_masks=0):
     buf = ctypes.create_string_buffer(128)
     _check(lib().lba_plan_kernel_name(M, N, K, qfmt(qprod), qfmt(qacc), order, with_masks, buf, len(buf)))
+    return buf.value.decode()
+
+
+def lba_plan_kernel_name_in(M, N, K, fmt_a, fmt_b, qprod, qacc, order=ORDER_SEQ, with_masks=0):
+    buf = ctypes.create_string_buffer(128)
+    _check(lib().lba_plan_kernel_name_in(M, N, K, infmt(fmt_a), infmt(fmt_b), qfmt(qprod), qfmt(qacc), order, with_masks, buf,
+                                         len(buf)))
     return buf.value.decode()
 
 

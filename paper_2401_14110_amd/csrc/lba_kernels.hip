@@ -373,4 +373,19 @@ int lba_plan_query_in(int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infm
     return plan_query(M, N, K, qprod, qacc, order, with_masks, &in, out);
 }
 
+int lba_plan_kernel_name_in(int64_t M, int64_t N, int64_t K, lba_infmt fmt_a, lba_infmt fmt_b,
+                            lba_qfmt qprod, lba_qfmt qacc, int32_t order, int32_t with_masks, char* buf, size_t buf_len) {
+    if (!buf || buf_len == 0) return LBA_ERR_NULL;
+    lba::InSpec in;
+    int rc = lba::make_in_spec(fmt_a, fmt_b, &in);
+    if (rc != LBA_OK) return rc;
+    if ((rc = lba::validate_fmt(qprod)) != LBA_OK || (rc = lba::validate_fmt(qacc)) != LBA_OK) return rc;
+    qprod.bias -= in.delta;
+    qacc.bias -= in.delta;
+    lba::Plan pl;
+    if ((rc = lba::make_plan(M, N, K, qprod, qacc, order, with_masks, &pl, 1, &in)) != LBA_OK) return rc;
+    lba::plan_kernel_name(pl, with_masks == 1, buf, buf_len);
+    return LBA_OK;
+}
+
 }  // extern "C"

@@ -197,6 +197,22 @@ def test_plan_picks_the_scaled_kernel_for_the_paper_formats():
     assert lb.lba_plan_query(64, 64, 64, (5, 7, -1, 0), (4, 7, -9, 0))["prod_mode"] == 1  # can only flush
 
 
+def test_kernel_names_for_other_operand_formats():
+    # lba_plan_kernel_name_in mirrors the launchers: the mixed-grid kernels of the forward and the recompute call, the
+    # 4 x 4 kernel on a plain grid, and lba_plan_kernel_name itself for E4M3
+    fa, fb, qp, qa = (3, 4, 6), (4, 3, 9), (4, 7, 12, 0), (4, 7, 10, 0)
+    assert lb.lba_plan_kernel_name_in(26897, 60, 40, fa, fb, qp, qa) == "lba_fast_in_mixed_kernel<32, 4, 0, 0>"
+    assert lb.lba_plan_kernel_name_in(70, 50, 96, fa, fb, qp, qa, with_masks=1) == "lba_fast_bwd_in_mixed_kernel<4, 0, 2>"
+    assert lb.lba_plan_kernel_name_in(26897, 60, 40, fa, fb, qp, qa, with_masks=3) == "lba_fast_bwd_in_mixed_kernel<4, 0, 0>"
+    assert lb.lba_plan_kernel_name_in(60625, 64, 40, fa, fb, qp, qa, with_masks=1) == "lba_fast_bwd_kernel<4, 0, 0, 2, 1>"
+    assert lb.lba_plan_kernel_name_in(4096, 768, 768, (3, 4, 3), (3, 4, 3), (5, 7, 15, 0), (4, 7, 7, 0)) == "lba_fast_kernel<4, 4, 32, 3, 0, 0, 1>"
+    e4m3 = (4, 3, 7)
+    assert lb.lba_plan_kernel_name_in(26897, 60, 40, e4m3, e4m3, (5, 7, 15, 0), (4, 7, 7, 0)) == \
+        lb.lba_plan_kernel_name(26897, 60, 40, (5, 7, 15, 0), (4, 7, 7, 0))
+    with pytest.raises(Exception):
+        lb.lba_plan_kernel_name_in(64, 64, 64, (3, 3, 3), (3, 4, 3), (5, 7, 15, 0), (4, 7, 7, 0))
+
+
 def test_plan_falls_back_to_the_general_kernel_when_the_fast_one_is_not_exact():
     q = lb.lba_plan_query
     # nearest-even where one FP32 rounding first would not be exact (M_acc < 7 with inexact sums below R_OF,
