@@ -665,23 +665,45 @@ __device__ __forceinline__ void fast_kstep(float (&acc)[TM][TN], const float (&a
     fast_group<PM, RND, CLAMP, 0, TM, TM, TN>(acc, a, b, c);
 }
 
-// One k-tile from LDS, fully unrolled; operands are read one k ahead of their use.  With the
+// One k-tile from LDS, fully unrolled; operands are read one k ahead of their use (four with the 2 x 2 block).  With the
 // chunked order every 16th step is followed by the second-level step (tiles start at multiples
 // of 16, so chunk boundaries are compile-time positions).
 template <int PM, int RND, int ORDER, bool CLAMP, int TM, int TN, int BK, int BM, int BN>
 __device__ __forceinline__ void fast_tile(float (&acc)[TM][TN], float (&top)[TM][TN], const float* As, const float* Bs,
                                           int tx, int ty, const FastConst& c) {
-    float a0[TM], b0[TN], a1[TM], b1[TN];
-    read_operands<TM, TN, BM, BN>(As, Bs, 0, tx, ty, a0, b0);
+    if constexpr (TM * TN <= 4) {
+        // The 2 x 2 block runs where a CU holds one workgroup (see fast_stage_depth): its 12 instructions per step do
+        // not cover an LDS round trip, so it reads four steps ahead.
+        constexpr int AHEAD = 4, SLOTS = AHEAD + 1;
+        float a[SLOTS][TM], b[SLOTS][TN];
 #pragma unroll
-    for (int k = 0; k < BK; k += 2) {
-        read_operands<TM, TN, BM, BN>(As, Bs, k + 1, tx, ty, a1, b1);
-        fast_kstep<PM, RND, CLAMP, TM, TN>(acc, a0, b0, c);
-        if (k + 2 < BK) read_operands<TM, TN, BM, BN>(As, Bs, k + 2, tx, ty, a0, b0);
-        fast_kstep<PM, RND, CLAMP, TM, TN>(acc, a1, b1, c);
-        if (ORDER == LBA_ORDER_CHUNK16 && ((k + 2) & 15) == 0) fast_level2<RND, CLAMP, TM, TN>(top, acc, c);
+        for (int k = 0; k < AHEAD; ++k) read_operands<TM, TN, BM, BN>(As, Bs, k, tx, ty, a[k], b[k]);
+#pragma unroll
+        for (int k = 0; k < BK; ++k) {
+            if (k + AHEAD < BK) read_operands<TM, TN, BM, BN>(As, Bs, k + AHEAD, tx, ty, a[(k + AHEAD) % SLOTS], b[(k + AHEAD) % SLOTS]);
+            fast_kstep<PM, RND, CLAMP, TM, TN>(acc, a[k % SLOTS], b[k % SLOTS], c);
+            if (ORDER == LBA_ORDER_CHUNK16 && ((k + 1) & 15) == 0) fast_level2<RND, CLAMP, TM, TN>(top, acc, c);
+        }
+    } else {
+        float a0[TM], b0[TN], a1[TM], b1[TN];
+        read_operands<TM, TN, BM, BN>(As, Bs, 0, tx, ty, a0, b0);
+#pragma unroll
+        for (int k = 0; k < BK; k += 2) {
+            read_operands<TM, TN, BM, BN>(As, Bs, k + 1, tx, ty, a1, b1);
+            fast_kstep<PM, RND, CLAMP, TM, TN>(acc, a0, b0, c);
+            if (k + 2 < BK) read_operands<TM, TN, BM, BN>(As, Bs, k + 2, tx, ty, a0, b0);
+            fast_kstep<PM, RND, CLAMP, TM, TN>(acc, a1, b1, c);
+            if (ORDER == LBA_ORDER_CHUNK16 && ((k + 2) & 15) == 0) fast_level2<RND, CLAMP, TM, TN>(top, acc, c);
+        }
     }
 }
+
+// k-steps that a workgroup fetches and stages at a time.  The 2 x 2 lane block runs where a CU holds one workgroup
+// (small grids; the 32 x 32 tail of a mixed grid once the larger workgroups have finished): 32 steps of its 12
+// instructions take 0.7 us, the next tile's global loads 1.5 us, and nothing else on the CU covers the difference,
+// so it fetches 64 steps at a time (the same 32 KB of LDS as the two 64 x 64 stages of the larger blocks).  The
+// tile logic (clamp-free tiles, their bounds) stays per BK steps.
+__host__ __device__ constexpr int fast_stage_depth(int TM, int TN, int BK) { return TM * TN <= 4 ? 2 * BK : BK; }
 
 #ifndef LBA_FAST_MIN_WAVES
 #define LBA_FAST_MIN_WAVES 4        // waves per SIMD the register allocation must allow
@@ -696,12 +718,13 @@ template <int TM, int TN, int BK, int PM, int RND, int ORDER, int AMODE>
 __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ smem, int m0, int n0) {
     static_assert(BK % 16 == 0, "chunk boundaries must fall on fixed positions of a k-tile");
     constexpr int BM = 16 * TM, BN = 16 * TN;
-    constexpr int BMP = Stage<BM, BK>::kPitch;                // floats per k of the A tile in LDS
-    constexpr int STAGE = BK * (BMP + BN);
+    constexpr int BKS = fast_stage_depth(TM, TN, BK);          // k-steps fetched and staged at a time
+    constexpr int BMP = Stage<BM, BKS>::kPitch;               // floats per k of the A tile in LDS
+    constexpr int STAGE = BKS * (BMP + BN);
 
     const int tid = threadIdx.x;
     const int tx = tid & 15, ty = tid >> 4;
-    const int tidb = tid - Stage<BN, BK>::kTailShift;       // B's pieces go to the last lanes
+    const int tidb = tid - Stage<BN, BKS>::kTailShift;      // B's pieces go to the last lanes
     // batch member blockIdx.z (strides are 0 for a single GEMM)
     const uint8_t* pA = p.A + (int64_t)blockIdx.z * p.stride_a;
     const uint8_t* pB = p.B + (int64_t)blockIdx.z * p.stride_b;
@@ -724,8 +747,8 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
 #pragma unroll
         for (int j = 0; j < TN; ++j) { acc[i][j] = 0.0f; top[i][j] = 0.0f; }
 
-    uint4 ra[Stage<BM, BK>::kPerLane], rb[Stage<BN, BK>::kPerLane];
-    const int ntiles = (p.K + BK - 1) / BK;                    // K > 0 here; division by a constant
+    uint4 ra[Stage<BM, BKS>::kPerLane], rb[Stage<BN, BKS>::kPerLane];
+    const int ntiles = (p.K + BKS - 1) / BKS;                  // K > 0 here; division by a constant
 
     // Formats whose R_OF is within a few maximal products of zero (the planner's flag: the fixed bounds below fail
     // for four tiles at once) also get a bound per tile from the operands actually staged.
@@ -734,34 +757,37 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
     auto stage_tiles = [&](float* Ad, int st) {
         if (dyn) {
             float lm = 0.0f;
-            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, 4, 3, 0, &lm);
-            store_tile_cvt<BN, BK>(Ad + BK * BMP, sc_b, tidb, rb, 4, 3, 0, &lm);
+            store_tile_cvt<BM, BKS>(Ad, sc_a, tid, ra, 4, 3, 0, &lm);
+            store_tile_cvt<BN, BKS>(Ad + BKS * BMP, sc_b, tidb, rb, 4, 3, 0, &lm);
             publish_tile_max(tile_max[st], lm, tid);
         } else {
-            store_tile_cvt<BM, BK>(Ad, sc_a, tid, ra, AMODE == 1 ? p.in_ea : 4, p.in_ma, p.exp_a);
-            store_tile_cvt<BN, BK>(Ad + BK * BMP, sc_b, tidb, rb, AMODE == 1 ? p.in_eb : 4, p.in_mb, p.exp_b);
+            store_tile_cvt<BM, BKS>(Ad, sc_a, tid, ra, AMODE == 1 ? p.in_ea : 4, p.in_ma, p.exp_a);
+            store_tile_cvt<BN, BKS>(Ad + BKS * BMP, sc_b, tidb, rb, AMODE == 1 ? p.in_eb : 4, p.in_mb, p.exp_b);
         }
     };
     ConvLane cl;
-    if (AMODE == 2) cl = conv_lane<BM, BK>(pA, p, m0, tid);
+    if (AMODE == 2) cl = conv_lane<BM, BKS>(pA, p, m0, tid);
     auto fetch_a = [&](int k0) {
-        if (AMODE == 2)      fetch_tile_conv_lane<BM, BK>(cl, p, k0, ra);
-        else if (AMODE == 1) fetch_tile_a<BM, BK>(pA, p, m0, k0, tid, ra);
-        else                 fetch_tile<BM, BK>(pA, p.M, p.K, m0, k0, p.ld_align, tid, ra);
+        if (AMODE == 2)      fetch_tile_conv_lane<BM, BKS>(cl, p, k0, ra);
+        else if (AMODE == 1) fetch_tile_a<BM, BKS>(pA, p, m0, k0, tid, ra);
+        else                 fetch_tile<BM, BKS>(pA, p.M, p.K, m0, k0, p.ld_align, tid, ra);
     };
     fetch_a(0);
-    fetch_tile<BN, BK>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
+    fetch_tile<BN, BKS>(pB, p.N, p.K, n0, 0, p.ld_align, tidb, rb);
     stage_tiles(smem, 0);
     __syncthreads();
 
     for (int t = 0; t < ntiles; ++t) {
-        const float* As = smem + (t & 1) * STAGE;
-        const float* Bs = As + BK * BMP;
+        const float* As0 = smem + (t & 1) * STAGE;
+        const float* Bs0 = As0 + BKS * BMP;
         const bool more = (t + 1) < ntiles;
         if (more) {
-            fetch_a((t + 1) * BK);
-            fetch_tile<BN, BK>(pB, p.N, p.K, n0, (t + 1) * BK, p.ld_align, tidb, rb);
+            fetch_a((t + 1) * BKS);
+            fetch_tile<BN, BKS>(pB, p.N, p.K, n0, (t + 1) * BKS, p.ld_align, tidb, rb);
         }
+        for (int part = 0; part < BKS / BK; ++part) {              // the planner's bounds are per BK steps
+        const float* As = As0 + part * BK * BMP;
+        const float* Bs = Bs0 + part * BK * BN;
         // (Chunked order: the test is on the second-level sums; a first-level sum starts from 0 and
         // is covered by the same bound.)
         // If every chain of the wave starts a tile below R_OF - n * BK * max|p| (scaled down further
@@ -785,6 +811,7 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
             fast_tile<PM, RND, ORDER, false, TM, TN, BK, BMP, BN>(acc, top, As, Bs, tx, ty, c);
         } else {
             fast_tile<PM, RND, ORDER, true, TM, TN, BK, BMP, BN>(acc, top, As, Bs, tx, ty, c);
+        }
         }
         if (more) stage_tiles(smem + ((t + 1) & 1) * STAGE, (t + 1) & 1);
         __syncthreads();
@@ -866,7 +893,7 @@ __device__ __forceinline__ void store_event_words(uint32_t* of_plane, uint32_t* 
 
 template <int TM, int TN, int BK, int PM, int RND, int ORDER, int AMODE = 0>
 __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const KParams p) {
-    __shared__ __attribute__((aligned(16))) float smem[2 * BK * 16 * (TM + TN)];
+    __shared__ __attribute__((aligned(16))) float smem[2 * fast_stage_depth(TM, TN, BK) * 16 * (TM + TN)];
     fast_body<TM, TN, BK, PM, RND, ORDER, AMODE>(p, smem, blockIdx.x * 16 * TM, blockIdx.y * 16 * TN);
 }
 
