@@ -347,7 +347,8 @@ typedef struct {
                                          grid_x - mid_blocks - tail_blocks workgroups of tile_m x tile_n,
                                          mid_blocks workgroups of 48 x 64 (3 x 4 outputs per lane) on the rows
                                          after them and tail_blocks workgroups of 32 x 32 (2 x 2 per lane) on
-                                         the last rows; grid_y is 1                                          */
+                                         the last rows (of 32 x 16, 2 x 1 per lane, where the forward call's tail
+                                         would otherwise leave most CUs idle); grid_y is 1                    */
     int32_t mid_blocks;
 } lba_plan_info;
 

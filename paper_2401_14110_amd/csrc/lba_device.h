@@ -567,13 +567,13 @@ __device__ __forceinline__ float tile_threshold(const float* slot, float rof_gro
     return rof_grow1 - 32.0f * 1.001f * (amax * bmax) * kc;
 }
 
-// Reads the TM + TN operand values of one k from an LDS stage (TM in {2, 3, 4}, TN in {2, 4}): the lane's
+// Reads the TM + TN operand values of one k from an LDS stage (TM in {2, 3, 4}, TN in {1, 2, 4}): the lane's
 // rows ty*TM .. and columns tx*TN .. are contiguous in the k-major tiles (BM, BN: floats per k; three rows
 // per lane sit in slots of four, see Stage).
 template <int TM, int TN, int BM, int BN>
 __device__ __forceinline__ void read_operands(const float* As, const float* Bs, int k, int tx, int ty,
                                               float (&a)[TM], float (&b)[TN]) {
-    static_assert((TM == 2 || TM == 3 || TM == 4) && (TN == 2 || TN == 4), "lane block");
+    static_assert((TM == 2 || TM == 3 || TM == 4) && (TN == 1 || TN == 2 || TN == 4), "lane block");
     if (TM == 4) {
         const float4 v = *reinterpret_cast<const float4*>(As + k * BM + ty * 4);
         a[0] = v.x; a[1] = v.y; a[TM - 2] = v.z; a[TM - 1] = v.w;
@@ -587,9 +587,11 @@ __device__ __forceinline__ void read_operands(const float* As, const float* Bs, 
     if (TN == 4) {
         const float4 w = *reinterpret_cast<const float4*>(Bs + k * BN + tx * 4);
         b[0] = w.x; b[1] = w.y; b[TN - 2] = w.z; b[TN - 1] = w.w;
-    } else {
+    } else if (TN == 2) {
         const float2 w = *reinterpret_cast<const float2*>(Bs + k * BN + tx * 2);
-        b[0] = w.x; b[1] = w.y;
+        b[0] = w.x; b[TN - 1] = w.y;
+    } else {
+        b[0] = Bs[k * BN + tx];
     }
 }
 
@@ -799,10 +801,12 @@ __device__ __forceinline__ void fast_body(const KParams& p, float* __restrict__ 
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; j += 2)
+                for (int j = 0; j < TN; j += 2) {
+                    constexpr int J1 = TN > 1 ? 1 : 0;             // the pair's second column (the same one when TN = 1)
                     mx = (ORDER == LBA_ORDER_CHUNK16)
-                             ? __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(top[i][j]), __builtin_fabsf(top[i][j + 1])))
-                             : __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(acc[i][j]), __builtin_fabsf(acc[i][j + 1])));
+                             ? __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(top[i][j]), __builtin_fabsf(top[i][j + J1])))
+                             : __builtin_fmaxf(mx, __builtin_fmaxf(__builtin_fabsf(acc[i][j]), __builtin_fabsf(acc[i][j + J1])));
+                }
             safe_tiles = __all(mx < thresh4) ? 4 : (__all(mx < thresh) ? 1 : 0);
             if (dyn && safe_tiles == 0 && __all(mx < tile_threshold(tile_max[t & 1], p.rof_grow1, c.kc))) safe_tiles = 1;
         }
@@ -902,6 +906,11 @@ __global__ void __launch_bounds__(256, LBA_FAST_MIN_WAVES) lba_fast_kernel(const
 // per lane, the next mix_half (rows below mix_m_half) 48 x 64 tiles with 3 x 4 per lane, three quarters of the work
 // each, and the rest covers the remaining rows with 32 x 32 tiles (2 x 2 per lane), a quarter of the work each, so
 // that the tail of the launch is cut four times finer.  Workgroups are numbered rows-first in every region.
+// mix_tail16: the tail takes 32 x 16 tiles (2 x 1 per lane) instead.  The planner sets it where the tail starts on
+// an empty chip (the workgroups before it fill every slot a whole number of times) and its workgroups, doubled,
+// are still at most one per CU: a lone 2 x 2 wave issues its 15 instructions per step (12 arithmetic, two LDS
+// reads, a wait) at 4 to 5 cycles each, twice as many waves issue 9.  Elsewhere the narrower tile would only read
+// more from LDS per MAC.
 // b: the workgroup's number in the launch.
 template <int BK, int PM, int RND, int ORDER, int AMODE>
 __device__ __forceinline__ void fast_mixed_body(const KParams& p, float* smem, const int b) {
@@ -915,7 +924,8 @@ __device__ __forceinline__ void fast_mixed_body(const KParams& p, float* smem, c
     } else {
         const int t = b - p.mix_main - p.mix_half;
         const int by = t / p.mix_gx_tail, bx = t - by * p.mix_gx_tail;
-        fast_body<2, 2, BK, PM, RND, ORDER, AMODE>(p, smem, p.mix_m_half + bx * 32, by * 32);
+        if (p.mix_tail16) fast_body<2, 1, BK, PM, RND, ORDER, AMODE>(p, smem, p.mix_m_half + bx * 32, by * 16);   // uniform
+        else              fast_body<2, 2, BK, PM, RND, ORDER, AMODE>(p, smem, p.mix_m_half + bx * 32, by * 32);
     }
 }
 

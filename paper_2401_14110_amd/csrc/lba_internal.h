@@ -54,6 +54,7 @@ struct KParams {
     // mix_m_half (mix_gx_half per tile column; the forward kernel only), the rest 32 x 32 tiles of the remaining rows
     int32_t mix_main, mix_gx_main, mix_gx_tail, mix_m_main;
     int32_t mix_half, mix_gx_half, mix_m_half;
+    int32_t mix_tail16;      // the tail's tiles are 32 x 16 (forward kernels; set where the tail runs alone on the chip)
     // brick maps of the overflow plane as a by-product of the recompute call (lba_gemm_bwd_ws), else null: byte
     // ((k / 256) * map_rbx + m / 128) * map_sbx + n / 32 of map_dx and ((k / 256) * map_rbw + n / 128) * map_sbw + m / 32
     // of map_dw are set when a step of that brick overflows (the maps arrive zeroed)

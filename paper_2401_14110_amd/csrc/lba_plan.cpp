@@ -183,10 +183,18 @@ static void pick_tile(int64_t M, int64_t N, int64_t batch, int kernel, int event
 // Fills in a mixed grid: gx_main tile rows of 64 x 64 workgroups, then gx_half tile rows of 48 x 64 ones, then
 // 32 x 32 workgroups on whatever rows are left.  False when the counts do not fit a launch.
 static bool set_mixed_grid(int64_t M, int64_t N, int64_t gx_main, int64_t gx_half, Plan* p) {
-    const int64_t gy = (N + 63) / 64, gy_tail = (N + 31) / 32;
+    const int64_t gy = (N + 63) / 64;
     const int64_t m_main = gx_main * 64, m_half = m_main + gx_half * 48;
     if (gx_main < 0 || gx_half < 0 || m_half > M) return false;
-    const int64_t gx_tail = m_half < M ? (M - m_half + 31) / 32 : 0, tail = gx_tail * gy_tail;
+    const int64_t gx_tail = m_half < M ? (M - m_half + 31) / 32 : 0;
+    // The forward call's tail as 32 x 16 tiles: where the workgroups before it fill the chip's 1024 slots (four per CU)
+    // a whole number of times, so that the tail starts on an empty chip, and it has at most 128 workgroups of 32 x 32
+    // (a lone wave per SIMD issues at half rate; twice the workgroups of half the size, still at most one per CU, take
+    // less time: the 12544 x 256 x 2304 layer 451 -> 437 us; with two per CU, 200704 x 64 x 576, nothing is gained).
+    const int64_t before = (gx_main + gx_half) * gy;
+    const bool tail16 = p->events == 0 && before > 0 && before % 1024 == 0 && gx_tail > 0 && gx_tail * ((N + 31) / 32) <= 128;
+    const int64_t gy_tail = tail16 ? (N + 15) / 16 : (N + 31) / 32, tail = gx_tail * gy_tail;
+    p->kp.mix_tail16 = tail16 ? 1 : 0;
     const int64_t total = (gx_main + gx_half) * gy + tail;
     if (total > 2147483647LL || gx_half * gy + tail < 1) return false;
     p->mix_tail = (int)(gx_half * gy + tail);

@@ -197,6 +197,19 @@ def test_plan_picks_the_scaled_kernel_for_the_paper_formats():
     assert lb.lba_plan_query(64, 64, 64, (5, 7, -1, 0), (4, 7, -9, 0))["prod_mode"] == 1  # can only flush
 
 
+def test_tail_of_a_mixed_grid_is_cut_finer_where_it_runs_alone():
+    # four rounds of 48 x 64 workgroups fill every slot of the chip, the 256 remaining rows follow on an empty chip:
+    # 8 x 16 workgroups of 32 x 16 instead of 8 x 8 of 32 x 32 (forward call only)
+    qp, qa = (5, 7, 15, 0), (4, 7, 7, 0)
+    p = lb.lba_plan_query(12544, 256, 2304, qp, qa)
+    assert (p["mid_blocks"], p["tail_blocks"], p["grid_x"]) == (1024, 128, 1152)
+    assert lb.lba_plan_query(12544, 256, 2304, qp, qa, 0, 1)["tail_blocks"] == 64
+    # twelve rounds of 64 x 64 and 256 tail workgroups: too many to double within one per CU
+    assert lb.lba_plan_query(200704, 64, 576, qp, qa)["tail_blocks"] == 256
+    # two rounds of 48 x 64 leave slots free: the tail runs beside them
+    assert lb.lba_plan_query(3136, 512, 4608, qp, qa)["tail_blocks"] == 32
+
+
 def test_kernel_names_for_other_operand_formats():
     # lba_plan_kernel_name_in mirrors the launchers: the mixed-grid kernels of the forward and the recompute call, the
     # 4 x 4 kernel on a plain grid, and lba_plan_kernel_name itself for E4M3
