@@ -188,11 +188,11 @@ static bool set_mixed_grid(int64_t M, int64_t N, int64_t gx_main, int64_t gx_hal
     if (gx_main < 0 || gx_half < 0 || m_half > M) return false;
     const int64_t gx_tail = m_half < M ? (M - m_half + 31) / 32 : 0;
     // The forward call's tail as 32 x 16 tiles: where the workgroups before it fill the chip's 1024 slots (four per CU)
-    // a whole number of times, so that the tail starts on an empty chip, and it has at most 128 workgroups of 32 x 32
+    // a whole number of times (or there are none), so that the tail starts on an empty chip, and it has at most 128 workgroups of 32 x 32
     // (a lone wave per SIMD issues at half rate; twice the workgroups of half the size, still at most one per CU, take
     // less time: the 12544 x 256 x 2304 layer 451 -> 437 us; with two per CU, 200704 x 64 x 576, nothing is gained).
     const int64_t before = (gx_main + gx_half) * gy;
-    const bool tail16 = p->events == 0 && before > 0 && before % 1024 == 0 && gx_tail > 0 && gx_tail * ((N + 31) / 32) <= 128;
+    const bool tail16 = p->events == 0 && before % 1024 == 0 && gx_tail > 0 && gx_tail * ((N + 31) / 32) <= 128;
     const int64_t gy_tail = tail16 ? (N + 15) / 16 : (N + 31) / 32, tail = gx_tail * gy_tail;
     p->kp.mix_tail16 = tail16 ? 1 : 0;
     const int64_t total = (gx_main + gx_half) * gy + tail;
@@ -226,6 +226,9 @@ static void plan_mixed_grid(int64_t M, int64_t N, int64_t batch, Plan* p) {
     // those kernels have the 4 x 4 lane block alone outside the mixed grid: a grid too small for it (a single wave per
     // SIMD issues at half rate) becomes 32 x 32 workgroups throughout
     if (p->amode == 1 && blocks <= 256 && set_mixed_grid(M, N, 0, 0, p)) return;
+    // the smallest grids of the forward call (at most 128 workgroups of 32 x 32, e.g. a 64 x 1000 classifier layer): the
+    // tail's 32 x 16 tiles throughout, twice the workgroups of the 2 x 2 lane block
+    if (p->events == 0 && ((M + 31) / 32) * ((N + 31) / 32) <= 128 && set_mixed_grid(M, N, 0, 0, p)) return;
     if (blocks > 256 * 16) return;
     // Rounds of 48 x 64 workgroups (forward call only; measured on M sweeps at N = 256 and 512, whose rates depend on
     // blocks / 256 alone): a CU that holds three 64 x 64 workgroups, or one, issues well below one that holds four or

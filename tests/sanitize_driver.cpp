@@ -207,7 +207,9 @@ static void sweep_planner() {
                                             const int64_t quarters = pl.mix_tail - kp.mix_half;
                                             CHECK(quarters >= 0 && (quarters == 0) == (kp.mix_m_half >= M), "32-row region present iff rows are left");
                                             CHECK(quarters == 0 || ((int64_t)kp.mix_gx_tail * 32 >= M - kp.mix_m_half && (int64_t)(kp.mix_gx_tail - 1) * 32 < M - kp.mix_m_half), "tail rows cover M");
-                                            CHECK(quarters == 0 || quarters == kp.mix_gx_tail * gy32, "tail count");
+                                            CHECK(quarters == 0 || quarters == kp.mix_gx_tail * (kp.mix_tail16 ? (N + 15) / 16 : gy32), "tail count");
+                                            CHECK(kp.mix_tail16 == 0 || (events == 0 && kp.mix_gx_tail * gy32 <= 128 && kp.mix_main + kp.mix_half >= 0 &&
+                                                                         (kp.mix_main + kp.mix_half) % 1024 == 0), "32 x 16 tail only where it runs alone");
                                             CHECK(kp.mix_gx_main >= 1 && kp.mix_gx_half >= 1 && kp.mix_gx_tail >= 1, "divisors");
                                             CHECK(pl.grid_x == kp.mix_main + pl.mix_tail && pl.grid_y == 1, "mixed grid");
                                         } else if (pl.kpar > 0) {
